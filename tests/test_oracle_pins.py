@@ -1,0 +1,404 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the HIP library.  Each is chosen so that a
+plausible mistake in the oracle (a dropped term, a wrong bound, a transposed
+operand, a wrong tier order) fails at least one of them.
+"""
+
+import itertools
+import os
+from fractions import Fraction
+from functools import lru_cache
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import tc_oracle as o
+from tests.invariants import check_state
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _tiers(r, base=1):
+    """(gpu, cpu, nvme) sets of paper-numbered tensor ids."""
+    g = {t + base for t in range(r.p.n_tensors) if r.cur[t] == o.GPU}
+    c = {t + base for t in range(r.p.n_tensors) if r.cur[t] == o.CPU}
+    n = {t + base for t in range(r.p.n_tensors) if r.cur[t] == o.NVME}
+    return g, c, n
+
+
+def _build(wl, payload=None):
+    st, te, rw, _ = wl.events()
+    return o.build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
+                   wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload)
+
+
+# ----------------------------------------------------------------------------
+# Alg. 1
+# ----------------------------------------------------------------------------
+
+def test_alg1_distribution_sums_to_one_and_matches_hand_values():
+    tc = [(512, 4), (1024, 2), (4096, 1)]            # bytes per size: 2048, 2048, 4096
+    d = o.tsd(tc)
+    assert d == [Fraction(1, 4), Fraction(1, 4), Fraction(1, 2)]
+    assert sum(d) == 1
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        tc = [(int(s), int(c)) for s, c in zip(rng.integers(1, 1 << 20, 7), rng.integers(1, 100, 7))]
+        d = o.tsd(tc)
+        assert sum(d) == 1
+        total = sum(s * c for s, c in tc)
+        for (s, c), x in zip(tc, d):
+            assert x * total == s * c
+
+
+# ----------------------------------------------------------------------------
+# Alg. 2
+# ----------------------------------------------------------------------------
+
+def test_alg2_closed_form_every_class_gets_the_same_fraction():
+    # TSD[s]*avail/s = c_s*avail/total: the size cancels
+    rng = np.random.default_rng(2)
+    for _ in range(100):
+        sizes = rng.choice(np.arange(1, 4000) * 256, size=6, replace=False)
+        tc = [(int(s), int(c)) for s, c in zip(sizes, rng.integers(1, 200, 6))]
+        total = sum(s * c for s, c in tc)
+        avail = int(rng.integers(0, 2 * total))
+        got = o.buffer_count(tc, avail, [c for _s, c in tc])
+        assert got == [min(c, c * avail // total) for _s, c in tc]
+        assert sum(n * s for n, (s, _c) in zip(got, tc)) <= max(avail, 0) or avail >= total
+        if avail >= total:
+            assert got == [c for _s, c in tc]
+
+
+def test_alg2_hand_example():
+    # 3 sizes; 10 KiB of GPU memory over 20 KiB of tensors -> half of every class, rounded down
+    tc = [(512, 8), (1024, 7), (3072, 3)]            # 4096 + 7168 + 9216 = 20480
+    assert o.buffer_count(tc, 10240, [8, 7, 3]) == [4, 3, 1]
+    # the CPU line is capped by what the GPU did not take
+    assert o.buffer_count(tc, 1 << 30, [8 - 4, 7 - 3, 3 - 1]) == [4, 4, 2]
+
+
+def _profile_of(wl):
+    st, te, rw, _ = wl.events()
+    return o.profile(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw)
+
+
+def test_plan_literal_vs_floor_and_budget():
+    for seed in range(20):
+        wl = W.random_workload(seed, n_tensors=30, literal=False)
+        p = _profile_of(wl)
+        plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, literal=False)
+        lit = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, literal=True)
+        n_c = len(p.count)
+        for pl in (plan, lit):
+            assert sum(pl.gpu_count[s] * pl.stride[s] for s in range(n_c)) <= wl.hbm_bytes
+            for s in range(n_c):
+                assert pl.gpu_count[s] <= p.used[s]
+                assert pl.gpu_count[s] + pl.cpu_count[s] <= p.count[s]
+            for g in (0, 1):
+                assert sum(pl.cpu_count[s] * pl.stride[s] for s in range(n_c)
+                           if p.class_group[s] == g) <= wl.host_bytes[g]
+        for s in range(n_c):
+            assert plan.gpu_count[s] >= min(p.step_max[s], p.used[s])
+        total = sum(lit.stride[s] * p.used[s] for s in range(n_c))
+        assert lit.gpu_count == [min(p.used[s], p.used[s] * wl.hbm_bytes // total) for s in range(n_c)]
+
+
+def test_plan_floor_equals_literal_when_no_step_uses_anything():
+    # a profile with tensors but a trace that touches a class at most 0 times -> floor is 0 there
+    wl = W.single_class_fwd_bwd(6, 3, 3)
+    p = _profile_of(wl)
+    p.step_max = [0] * len(p.step_max)
+    a = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, literal=False)
+    b = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, literal=True)
+    assert a == b
+
+
+def test_plan_capacity_error_when_working_set_does_not_fit():
+    wl = W.random_workload(3, literal=False)
+    p = _profile_of(wl)
+    with pytest.raises(o.CapacityError):
+        o.plan_pools(p, 255, wl.host_bytes, literal=False)
+
+
+def test_everything_fits_means_no_migration_and_all_hits():
+    wl = W.random_workload(5, literal=True)
+    wl.hbm_bytes = int(((wl.tensor_bytes + 255) // 256 * 256).sum())
+    r = o.replay_workload(wl, check=check_state)
+    assert r.misses == 0 and r.log == [] and r.hits == sum(len(dict.fromkeys(s)) for it in wl.iterations for s in it)
+
+
+# ----------------------------------------------------------------------------
+# Step 3 layout
+# ----------------------------------------------------------------------------
+
+def test_layout_buffer0_is_first_chunk_of_smallest_size_and_chunks_do_not_overlap():
+    wl = W.random_workload(7, n_tensors=40, sizes=(512, 1024, 2048, 100), literal=False)
+    p = _profile_of(wl)
+    plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align)
+    assert p.class_bytes == sorted(p.class_bytes)
+    for off, cnt, total in ((plan.gpu_off, plan.gpu_count, plan.gpu_total),
+                            (plan.cpu_off, plan.cpu_count, plan.cpu_total)):
+        first = next(s for s in range(len(cnt)) if cnt[s])
+        assert off[first] == 0                       # "buffer0"
+        chunks = [(off[s] + k * plan.stride[s], off[s] + (k + 1) * plan.stride[s])
+                  for s in range(len(cnt)) for k in range(cnt[s])]
+        chunks.sort()
+        assert all(a[1] <= b[0] for a, b in zip(chunks, chunks[1:]))
+        assert (chunks[-1][1] if chunks else 0) == total
+    # a 512-byte tensor sits in a 512-byte buffer: no internal fragmentation (Sec. 3.3.1)
+    for s, b in enumerate(p.class_bytes):
+        if b % wl.align == 0:
+            assert plan.stride[s] == b
+
+
+def test_free_list_hands_out_lowest_buffer_first():
+    wl = W.example_cpu_gpu()
+    r = _build(wl)
+    assert [r.gslot[t] for t in (0, 1, 2)] == [0, 1, 2]
+    assert [r.cslot[t] for t in (3, 4, 5)] == [0, 1, 2]
+
+
+# ----------------------------------------------------------------------------
+# placement
+# ----------------------------------------------------------------------------
+
+def test_placement_is_monotone_in_execution_order_within_a_class():
+    for seed in range(10):
+        wl = W.random_workload(seed, n_tensors=40)
+        p = _profile_of(wl)
+        plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align)
+        pl = o.place(p, plan)
+        for s in range(len(p.count)):
+            tiers = [pl.final[t] for t in pl.order if p.class_of[t] == s and p.first_use[t] != o.INF]
+            assert tiers == sorted(tiers)             # GPU(0) then CPU(1) then NVMe(2)
+        for t in range(p.n_tensors):
+            if p.first_use[t] == o.INF:
+                assert pl.final[t] != o.GPU
+        offs = [(pl.file_off[t], pl.file_off[t] + int(wl.tensor_bytes[t])) for t in range(p.n_tensors)]
+        assert all(a[1] <= b[0] for a, b in zip(offs, offs[1:])) and all(a[0] % 4096 == 0 for a in offs)
+
+
+# ----------------------------------------------------------------------------
+# worked examples (golden fixtures hold what the paper's text states)
+# ----------------------------------------------------------------------------
+
+def _parse_golden(name):
+    events = []
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        events.append(line)
+    return events
+
+
+def _ids(txt):
+    txt = txt.split("=", 1)[1].strip()
+    return txt
+
+
+def _run_example(wl, golden):
+    r = _build(wl)
+    n = wl.n_tensors
+    lines = _parse_golden(golden)
+    states = {"initial": _tiers(r)}
+    logs = {}
+    slots = {}
+    for k, access in enumerate(wl.profile):
+        before = len(r.log)
+        r.pre(k, access)
+        r.post(k, [t for t, _ in access])
+        check_state(r, k, access, o.POST)
+        name = ("forward_done %d" % (access[0][0] + 1)) if k < n else ("backward_done %d" % (access[0][0] + 1))
+        states[name] = _tiers(r)
+        logs[name] = r.log[before:]
+        slots[name] = list(r.gslot)
+    return r, lines, states, logs, slots
+
+
+def test_example_cpu_gpu_matches_the_papers_state_sequence():
+    r, lines, states, logs, _ = _run_example(W.example_cpu_gpu(), "example_cpu_gpu.txt")
+    for line in lines:
+        if line.startswith("halt"):
+            assert logs[line[5:].strip()] == [], line
+            continue
+        ev, g, c, n = [x.strip() for x in line.split(";")]
+        want = tuple({int(i) for i in _ids(x).split(",") if i} for x in (g, c, n))
+        assert states[ev] == want, (ev, states[ev], want)
+    # the backward pass walks the window back; the iteration ends where it began
+    assert states["backward_done 6"][0] == {3, 4, 5}
+    assert states["backward_done 5"][0] == {2, 3, 4}
+    assert states["backward_done 4"][0] == {1, 2, 3}
+    assert r.misses == 0 and r.hits == 12
+    n_before = len(r.log)
+    r.end_iteration()
+    assert len(r.log) == n_before                    # restore is a no-op
+
+
+def test_example_cpu_gpu_nvme_matches_what_the_text_fixes():
+    r, lines, states, logs, slots = _run_example(W.example_cpu_gpu_nvme(), "example_cpu_gpu_nvme.txt")
+    spilled = None
+    for line in lines:
+        if line.startswith("halt"):
+            assert logs[line[5:].strip()] == [], line
+            continue
+        if line.startswith("reuse"):
+            # tensor 4 lands in the GPU buffer tensor 7 just left
+            assert slots["backward_done 7"][3] == slots["forward_done 7"][6]
+            continue
+        ev, g, c, n = [x.strip() for x in line.split(";")]
+        got_g, got_c, got_n = states[ev]
+        assert got_g == {int(i) for i in _ids(g).split(",")}, ev
+        ctxt, ntxt = _ids(c), _ids(n)
+        if "x" not in ntxt:
+            assert got_c == {int(i) for i in ctxt.split(",")} and got_n == {int(i) for i in ntxt.split(",")}
+            continue
+        x = got_n - {7}
+        assert len(x) == 1 and x <= {1, 2, 3}
+        spilled = spilled or x
+        assert x == spilled                           # the same tensor stays spilled
+        fixed = {int(i) for i in ctxt.replace("{1,2,3}-x", "").split(",") if i.strip()}
+        assert got_c == fixed | ({1, 2, 3} - x), ev
+    ops = [(o.OP_NAMES[e[3]], e[4] + 1) for e in logs["forward_done 4"]]
+    assert [a for a, _ in ops] == ["SPILL", "EVICT", "PREFETCH"] and ops[1][1] == 4 and ops[2][1] == 7
+    assert logs["forward_done 4"][2][5] == o.NVME     # tensor 7 comes from the file tier
+    ops = [(o.OP_NAMES[e[3]], e[4] + 1) for e in logs["backward_done 7"]]
+    assert ops == [("RELEASE", 7), ("PREFETCH", 4)]   # the NVMe copy exists: only the buffer is freed
+
+
+# ----------------------------------------------------------------------------
+# closed form: one class, N tensors, K GPU buffers, trace 0..N-1, N-1..0
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,k", [(6, 3), (8, 3), (8, 1), (8, 7), (5, 5), (7, 2), (2, 1)])
+def test_single_class_closed_form(n, k):
+    size = 512
+    wl = W.single_class_fwd_bwd(n, k, n - k, size=size, n_iterations=2)
+    r = o.replay_workload(wl, check=check_state)
+    per_it = {}
+    for e in r.log:
+        per_it.setdefault(e[0], []).append(e)
+    assert r.hits == 2 * 2 * n and r.misses == 0 and r.fails == 0
+    for it in (0, 1):
+        ops = per_it.get(it, [])
+        assert sum(1 for e in ops if e[3] == o.PREFETCH) == 2 * (n - k)
+        assert sum(1 for e in ops if e[3] == o.EVICT) == 2 * (n - k)
+        assert all(e[3] in (o.PREFETCH, o.EVICT) for e in ops)
+        steps_with_action = {e[1] for e in ops}
+        assert len(steps_with_action) == 2 * (n - k)          # the other 2K steps do nothing
+    assert r.bytes_h2d == r.bytes_d2h == 2 * 2 * (n - k) * size
+    assert r.bytes_file_read == r.bytes_file_write == 0
+
+
+# ----------------------------------------------------------------------------
+# brute force: fewest fetches over every possible eviction choice
+# ----------------------------------------------------------------------------
+
+def _min_fetches(seq, k, initial):
+    """Exhaustive search: smallest number of fetches with a k-buffer cache that
+    starts with `initial`, when every access must be resident."""
+    seq = tuple(seq)
+
+    @lru_cache(maxsize=None)
+    def go(i, cache):
+        if i == len(seq):
+            return 0
+        t = seq[i]
+        if t in cache:
+            return go(i + 1, cache)
+        if len(cache) < k:
+            return 1 + go(i + 1, cache | frozenset([t]))
+        return 1 + min(go(i + 1, (cache - frozenset([x])) | frozenset([t])) for x in cache)
+
+    return go(0, frozenset(initial))
+
+
+@pytest.mark.parametrize("n", [3, 5, 7, 8])
+def test_fetch_count_is_the_exhaustive_minimum_on_forward_backward_traces(n):
+    for k in range(1, n + 1):
+        wl = W.single_class_fwd_bwd(n, k, n - k)
+        r = o.replay_workload(wl)
+        seq = [st[0][0] for st in wl.profile]
+        fetched = sum(1 for e in r.log if e[3] in (o.PREFETCH, o.DEMAND) and e[2] != o.END)
+        assert fetched == _min_fetches(seq, k, range(k)), (n, k)
+
+
+def test_fetch_count_never_beats_the_exhaustive_minimum_on_random_single_class_traces():
+    rng = np.random.default_rng(11)
+    for trial in range(60):
+        n = int(rng.integers(3, 8))
+        k = int(rng.integers(1, n + 1))
+        seq = [int(x) for x in rng.integers(0, n, size=int(rng.integers(4, 14)))]
+        sizes = [512] * n
+        steps = [[(t, W.R)] for t in seq]
+        wl = W.traces._simple("bf", sizes, [0] * n, steps, k * 512, ((n - k) * 512, 0))
+        r = o.replay_workload(wl, check=check_state)
+        used_in_order = list(dict.fromkeys(seq))
+        initial = used_in_order[:k]
+        fetched = sum(1 for e in r.log if e[3] in (o.PREFETCH, o.DEMAND) and e[2] != o.END)
+        assert fetched >= _min_fetches(seq, k, initial)
+        assert r.fails == 0
+        assert r.hits + r.misses == len(seq)
+
+
+# ----------------------------------------------------------------------------
+# bytes conserved, full-bytes mode, multi-class random traces (incl. odd sizes,
+# the file tier, write accesses, order drift and several iterations)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(12))
+def test_bytes_conserved_and_invariants_on_random_traces(seed):
+    wl = W.random_workload(seed, n_tensors=36, n_steps=60, perturb_one_in=(0 if seed % 2 else 7),
+                           host_frac=(0.3 if seed % 3 else 1.2), literal=(seed % 4 == 3))
+    pay = lambda t: W.workload_payload(wl, t)
+    r = o.replay_workload(wl, payload=pay, check=check_state)
+    for t in range(wl.n_tensors):
+        assert np.array_equal(r.read_tensor(t), r.expected_bytes(t, pay)), t
+    # byte counters equal the op log's bytes, each byte crossing each link once
+    h2d = sum(e[9] for e in r.log if e[3] in (o.PREFETCH, o.DEMAND))
+    d2h = sum(e[9] for e in r.log if e[3] == o.EVICT)
+    fw = sum(e[9] for e in r.log if e[3] in (o.SPILL, o.WRITEBACK))
+    fr = sum(e[9] for e in r.log if e[3] == o.RESTORE or (e[3] in (o.PREFETCH, o.DEMAND) and e[5] == o.NVME))
+    assert (h2d, d2h, fw, fr) == (r.bytes_h2d, r.bytes_d2h, r.bytes_file_write, r.bytes_file_read)
+    meta = o.replay_workload(wl)                      # metadata mode decides identically
+    assert meta.log == r.log and meta.cur == r.cur and meta.gslot == r.gslot
+
+
+def test_metadata_and_full_bytes_agree_on_a_small_transformer_trace():
+    wl = W.config(0, layers=8)
+    pay = lambda t: W.workload_payload(wl, t)
+    r = o.replay_workload(wl, payload=pay, check=check_state)
+    assert r.misses == 0 and r.fails == 0
+    for t in range(wl.n_tensors):
+        assert np.array_equal(r.read_tensor(t), r.expected_bytes(t, pay))
+    assert o.replay_workload(wl).log == r.log
+
+
+def test_stamp_is_an_involution_on_head_and_tail():
+    buf = W.payload_bytes(3, 100)
+    ref = buf.copy()
+    s = o.stamp16(1, 2, 3)
+    o.apply_stamp(buf, s)
+    assert not np.array_equal(buf[:16], ref[:16]) and np.array_equal(buf[16:84], ref[16:84])
+    o.apply_stamp(buf, s)
+    assert np.array_equal(buf, ref)
+
+
+# ----------------------------------------------------------------------------
+# planted mistakes: each pin above must notice a plausible error
+# ----------------------------------------------------------------------------
+
+def test_a_wrong_halt_rule_is_caught_by_the_worked_example(monkeypatch):
+    # plant: always let the finished tensor go (drop the halt rule's comparison)
+    real = o.Profile.next_use
+    monkeypatch.setattr(o.Profile, "next_use", lambda self, t, row: o.INF)
+    wl = W.example_cpu_gpu()
+    r = _build(wl)
+    for k in range(4):
+        r.pre(k, wl.profile[k])
+        r.post(k, [wl.profile[k][0][0]])
+    monkeypatch.setattr(o.Profile, "next_use", real)
+    assert _tiers(r)[0] != {4, 5, 6}                  # tensor 4 was wrongly sent away
