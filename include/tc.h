@@ -1,0 +1,307 @@
+/*
+ * tc.h - C ABI of the MI355X tensor-cache migration library (libtc.so).
+ *
+ * The library implements the migration hot path of 10Cache (arXiv 2511.14124):
+ * a profiled tensor-access order (Sec. 3.2) drives size-class buffer pools in
+ * HBM and pinned host memory (Sec. 3.3.1, Alg. 1-2), an execution-order tensor
+ * placement over GPU / CPU / NVMe (Sec. 3.3.2), and a hook-driven
+ * prefetch-eviction scheduler (Sec. 3.4, Alg. 3-4) whose decisions run in a
+ * GPU kernel and whose copies run in a batched GPU migration kernel.
+ *
+ * Conventions
+ *   - Every call returns TC_OK (0) or a negative TC_E_* code.  Nothing throws
+ *     or aborts across this boundary.  tc_strerror() names a code;
+ *     tc_last_error() gives the detail text of the context's last failure.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device memory; "pinned" pointers are page-locked host memory mapped into
+ *     the GPU (hipHostMalloc, or a pin_memory tensor).
+ *   - Inputs are caller-owned and copied during the call.  Outputs are
+ *     caller-allocated plain structs.  The HBM region, the pinned region, the
+ *     staging region, the file descriptor and the streams are caller-owned and
+ *     must outlive the context.
+ *   - A context serves one GPU and is not thread-safe; calls on one context
+ *     must not overlap.
+ *   - Call order: tc_create, tc_profile_order, tc_plan_pools,
+ *     tc_plan_schedule, tc_bind_memory, then tc_load_tensor / tc_fill_payload,
+ *     then per step tc_migrate_step(PRE), (the module's kernels),
+ *     tc_migrate_step(POST), and tc_end_iteration after the last step.  A call
+ *     made out of order returns TC_E_STATE.
+ */
+#ifndef TC_H
+#define TC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- return codes ---- */
+#define TC_OK          0
+#define TC_E_ARG      (-1)   /* bad argument (null pointer, id out of range, unordered events, ...) */
+#define TC_E_STATE    (-2)   /* call made out of order */
+#define TC_E_CAPACITY (-3)   /* a budget, region or limit is too small */
+#define TC_E_IO       (-4)   /* file-tier read/write failed or was short */
+#define TC_E_HIP      (-5)   /* a HIP runtime call failed */
+
+/* ---- tiers, phases, op codes (values are part of the ABI) ---- */
+#define TC_GPU  0
+#define TC_CPU  1
+#define TC_NVME 2
+
+#define TC_PRE      0   /* pre-hook: residency check + demand fetch */
+#define TC_POST     1   /* post-hook: Alg. 3 over the tensors that finished */
+#define TC_END      2   /* end of iteration, first call: GPU-final tensors return */
+#define TC_END_CPU  3   /* end of iteration, second call: CPU-final tensors return from the file tier */
+
+#define TC_OP_DEMAND    0   /* miss: tensor fetched into a GPU buffer by the pre-hook */
+#define TC_OP_PREFETCH  1   /* tensor fetched ahead of use (Alg. 3), or returned home at iteration end */
+#define TC_OP_EVICT     2   /* GPU buffer -> CPU buffer (Alg. 4) */
+#define TC_OP_RELEASE   3   /* NVMe-final tensor, clean: GPU buffer freed, no bytes move */
+#define TC_OP_WRITEBACK 4   /* GPU buffer -> file extent */
+#define TC_OP_SPILL     5   /* CPU buffer -> file extent, to make room (Alg. 4) */
+#define TC_OP_RESTORE   6   /* file extent -> CPU buffer at iteration end */
+#define TC_OP_FAIL      7   /* access that could not be given a GPU buffer */
+
+#define TC_R 1
+#define TC_W 2
+
+#define TC_NONE 0xFFFFFFFFu          /* "no slot" / "never" */
+#define TC_MAX_STEP_TENSORS 16       /* most tensors one hook call may name */
+
+/* tc_budget.flags */
+#define TC_LITERAL_ALG2 1u           /* Alg. 2 exactly as printed: no per-step working-set floor */
+
+/* tc_bind_memory flags */
+#define TC_BIND_NULL_MOVER 1u        /* decide and log only; no region needed, no byte moves */
+
+typedef struct tc_ctx tc_ctx;        /* opaque, library-owned */
+
+/* One tensor.  group: 0 = 16-bit (parameter, gradient, checkpoint), 1 = fp32
+ * optimizer state; it selects the host budget and separates size classes
+ * (Sec. 3.3.1 Step 2 sizes the two kinds in separate runs).  kind is carried
+ * through untouched. */
+typedef struct {
+    uint64_t bytes;                  /* >= 16 */
+    uint8_t  group;
+    uint8_t  kind;
+    uint8_t  pad_[6];
+} tc_tensor_desc;
+
+/* One access of the profiled iteration (Sec. 3.2.1: execution order and
+ * activation time recorded by the module hooks). */
+typedef struct {
+    uint32_t step;                   /* non-decreasing over the array */
+    uint32_t tensor;
+    uint64_t compute_ns;             /* modelled compute time of the step (kept, not used by decisions) */
+    uint8_t  rw;                     /* TC_R, TC_W or both */
+    uint8_t  pad_[7];
+} tc_event;
+
+typedef struct {
+    uint64_t hbm_bytes;              /* GPU cache budget ("gpu_avl_mem" of Alg. 2) */
+    uint64_t host_bytes[2];          /* pinned-host budget per group ("cpu_avl_mem") */
+    uint32_t align;                  /* buffer stride granularity, power of two, >= 16 (default 256 if 0) */
+    uint32_t flags;
+} tc_budget;
+
+/* One size class of the pool plan (Alg. 2 + Step 3 of Sec. 3.3.1). */
+typedef struct {
+    uint64_t bytes;                  /* tensor size of the class */
+    uint64_t stride;                 /* buffer size: bytes rounded up to align */
+    uint64_t hbm_off;                /* offset of buffer 0 in the HBM region */
+    uint64_t host_off;               /* offset of buffer 0 in the pinned region */
+    uint32_t group;
+    uint32_t count;                  /* tensors of the class (c_s) */
+    uint32_t used;                   /* tensors of the class seen by the profiled iteration */
+    uint32_t step_max;               /* most tensors of the class one step uses */
+    uint32_t gpu_count;              /* GPU_BUFFER_COUNT */
+    uint32_t cpu_count;              /* CPU_BUFFER_COUNT */
+} tc_pool_class;
+
+typedef struct {
+    uint32_t n_classes;
+    uint32_t n_rows;                 /* rows of the prefetch table */
+    uint32_t n_steps;
+    uint32_t pad_;
+    uint64_t hbm_total;              /* bytes of the HBM region the plan needs */
+    uint64_t host_total;             /* bytes of the pinned region the plan needs */
+    uint64_t file_total;             /* bytes of the file tier (every tensor owns an extent) */
+} tc_pool_plan;
+
+typedef struct {
+    uint64_t file_off;               /* tensor's extent in the file tier, 4 KiB aligned */
+    uint32_t cls;                    /* size class index (classes ascending by bytes, then group) */
+    uint32_t slot;                   /* buffer index within the class on its final tier, TC_NONE for NVMe */
+    uint32_t first_use;              /* first row using the tensor, TC_NONE if never used */
+    uint8_t  final_tier;             /* TC_GPU / TC_CPU / TC_NVME: the "final location" of Sec. 3.2.1 */
+    uint8_t  pad_[3];
+} tc_placement;
+
+/* One record of the op log: the schedule, in decision order. */
+typedef struct {
+    uint32_t iteration;
+    uint32_t step;                   /* n_steps for the end-of-iteration calls */
+    uint32_t tensor;
+    uint32_t src_slot;               /* buffer index within the class, TC_NONE for the file tier */
+    uint32_t dst_slot;
+    uint8_t  phase;                  /* TC_PRE .. TC_END_CPU */
+    uint8_t  op;                     /* TC_OP_* */
+    uint8_t  src_tier;
+    uint8_t  dst_tier;
+    uint64_t bytes;                  /* bytes moved (0 for RELEASE and FAIL) */
+} tc_op;
+
+typedef struct {
+    uint64_t hits, misses, fails;    /* GPU cache hit / miss counts of pre-hook accesses (Sec. 4.3) */
+    uint64_t n_ops[8];               /* per TC_OP_* */
+    uint64_t bytes_h2d;              /* bytes copied into HBM (from pinned buffers or file staging) */
+    uint64_t bytes_d2h;              /* bytes copied HBM -> pinned buffers */
+    uint64_t bytes_file_read, bytes_file_write;
+    uint64_t mover_launches;         /* migration-kernel launches */
+    uint64_t mover_units;            /* exchange units those launches carried */
+    uint64_t decide_launches;        /* decision-kernel launches */
+    uint64_t stall_ns;               /* time the compute stream was held back by migration (tc_emulate_compute) */
+    uint64_t waits_under_30us, waits_total;   /* share of steps waiting < 0.03 ms (Sec. 4.2.2) */
+    uint32_t cursor;                 /* prefetch-table cursor */
+    uint32_t iteration;
+} tc_stats;
+
+const char *tc_strerror(int code);
+const char *tc_last_error(const tc_ctx *ctx);
+
+int tc_create(tc_ctx **out);
+int tc_destroy(tc_ctx *ctx);
+
+/* Sec. 3.2 (tensor characteristic analyzer).  Builds the prefetch table from
+ * one profiled iteration: rows in execution order (a tensor named twice by one
+ * step is one row), per-tensor use lists, the size->count dictionary TC and the
+ * per-class per-step maximum.  t, ev: host arrays. */
+int tc_profile_order(tc_ctx *ctx, const tc_tensor_desc *t, uint32_t n_tensors,
+                     const tc_event *ev, uint64_t n_events);
+
+/* Sec. 3.3.1 (cache allocator): Alg. 1 (size distribution), Alg. 2 (buffer
+ * counts, exact integer arithmetic, rounded down) and Step 3 (one contiguous
+ * region per tier cut into per-class chunks, classes ascending).  Unless
+ * TC_LITERAL_ALG2 is set every class first gets step_max buffers and Alg. 2
+ * divides the rest.  TC_E_CAPACITY if that floor exceeds hbm_bytes.
+ * classes_out: host array of at least the number of distinct (bytes, group)
+ * pairs (n_classes_cap entries; TC_E_CAPACITY if too few), may be NULL. */
+int tc_plan_pools(tc_ctx *ctx, const tc_budget *b, tc_pool_plan *plan_out,
+                  tc_pool_class *classes_out, uint32_t n_classes_cap);
+
+/* Sec. 3.3.2 (tensor allocator): in execution order every tensor takes the
+ * fastest tier with a free buffer of its class, GPU then CPU then NVMe, lowest
+ * buffer first.  out: host array of n_tensors entries, may be NULL. */
+int tc_plan_schedule(tc_ctx *ctx, tc_placement *out);
+
+/* Hands the library its memory and builds the device-side tables.
+ *   hbm_region     device, >= plan.hbm_total bytes, 256-byte aligned
+ *   pinned_region  pinned, >= plan.host_total bytes, 256-byte aligned
+ *   staging        pinned bounce buffer for the file tier (may be NULL with
+ *                  staging_bytes 0 if no tensor ever touches the file tier;
+ *                  otherwise at least twice the largest tensor)
+ *   file_fd        open read/write file of >= plan.file_total bytes, or -1
+ *   migrate_stream hipStream_t the copies are issued on (default priority)
+ * With TC_BIND_NULL_MOVER no bytes move and the regions may be NULL: the
+ * decision kernel still runs and the op log, stats and state are exact. */
+int tc_bind_memory(tc_ctx *ctx, void *hbm_region, uint64_t hbm_bytes,
+                   void *pinned_region, uint64_t pinned_bytes,
+                   void *staging, uint64_t staging_bytes,
+                   int file_fd, void *migrate_stream, uint32_t flags);
+
+/* Copies a tensor's initial bytes (host pointer, tensor's size) into its
+ * final location.  Synchronous. */
+int tc_load_tensor(tc_ctx *ctx, uint32_t tensor, const void *src);
+
+/* Fills every tensor, where it lives, with the counter pattern
+ * word(i) = h(i*0x9E3779B1 + tensor*0x85EBCA77 + seed*0xC2B2AE3D mod 2^32),
+ * h = x^=x>>16; x*=0x7FEB352D; x^=x>>15; x*=0x846CA68B; x^=x>>16 (32-bit
+ * words, little endian), using a fill kernel.  Synchronous. */
+int tc_fill_payload(tc_ctx *ctx, uint32_t seed);
+
+/* Copies a tensor's current bytes, from whichever tier holds it, to dst
+ * (host pointer).  Waits for outstanding copies first. */
+int tc_read_tensor(tc_ctx *ctx, uint32_t tensor, void *dst);
+
+/* One hook call (Sec. 3.2.1, Sec. 3.4).
+ *   TC_PRE : every listed tensor must be in a GPU buffer before the module
+ *            runs.  Resident -> hit.  Otherwise a miss: demand fetch.
+ *            dev_ptrs_out (host array of n pointers, may be NULL) receives the
+ *            device address of each tensor's GPU buffer (NULL for a failed
+ *            access), valid until the same step's POST.  compute_stream is
+ *            made to wait for the copies that fill those buffers.
+ *   TC_POST: Alg. 3 over the listed (finished) tensors: per tensor at most one
+ *            eviction (Alg. 4) paired with one prefetch of the next row of the
+ *            prefetch table that is not resident.  The copies wait for the
+ *            work already enqueued on compute_stream.
+ * ids, rw: host arrays of n <= TC_MAX_STEP_TENSORS entries (rw may be NULL
+ * for POST).  step indexes the profiled iteration.  Decisions are made by a
+ * GPU kernel; the call returns once they are known and the copies are
+ * enqueued, not when the copies finish. */
+int tc_migrate_step(tc_ctx *ctx, uint32_t step, int phase,
+                    const uint32_t *ids, const uint8_t *rw, uint32_t n,
+                    void *compute_stream, void **dev_ptrs_out);
+
+/* End of an iteration (Sec. 3.2.1): tensors return to their final locations,
+ * the cursor returns to row 0. */
+int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
+
+/* Stand-in for the module's kernels in a replay: on compute_stream, XORs the
+ * 16-byte stamp (words 0x10CAC4E5, iteration, step, tensor; little endian)
+ * into the first and the last 16 bytes of every tensor the last PRE call
+ * listed with TC_W, then spins for busy_ns nanoseconds.  Accumulates
+ * stall_ns / waits_* when measure_stall is non-zero (synchronises). */
+int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns, int measure_stall);
+
+/* Waits for every copy issued so far. */
+int tc_synchronize(tc_ctx *ctx);
+
+int tc_cache_stats(const tc_ctx *ctx, tc_stats *out);
+
+/* Copies the op log from record `first` on: at most cap records into buf;
+ * *n_total receives the log's length.  The log is kept on the host. */
+int tc_dump_oplog(const tc_ctx *ctx, uint64_t first, tc_op *buf, uint64_t cap, uint64_t *n_total);
+
+/* Current tier and buffer of every tensor (host arrays of n_tensors entries;
+ * any may be NULL).  Reads the device tables; synchronises the decision stream. */
+int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_slot);
+
+/* Migration-kernel tuning: workgroups per launch (0 = default) and bytes per
+ * work chunk (0 = default; a multiple of 4096). */
+int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
+
+/* Average duration in ns of the migration-kernel launches since the last
+ * call, measured with HIP events on the migration stream; *n = launches
+ * measured.  Only launches made while timing is enabled are counted. */
+int tc_mover_timing(tc_ctx *ctx, int enable, double *avg_ns, uint64_t *n);
+
+/* ---- stand-alone kernels ---- */
+
+/* One segment of a pack / unpack / copy batch. */
+typedef struct {
+    const void *src;
+    void       *dst;
+    uint64_t    bytes;
+} tc_segment;
+
+/* Batched copy: one launch moves every segment (device or pinned pointers,
+ * any alignment, any size).  segs: host array, copied.  Asynchronous on
+ * stream. */
+int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream,
+                  uint32_t workgroups, uint32_t chunk_bytes);
+
+/* Pack: gathers n small tensors (device pointers, any alignment) into one
+ * contiguous device slab, segment i at slab_off[i]; unpack is the reverse.
+ * LDS-staged so both the reads and the writes are 128-bit and coalesced even
+ * when source and destination are misaligned against each other.
+ * ptrs, bytes, slab_off: device arrays of n entries.  Asynchronous. */
+int tc_pack(void *slab, const void *const *ptrs, const uint64_t *bytes,
+            const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, void *stream);
+int tc_unpack(const void *slab, void *const *ptrs, const uint64_t *bytes,
+              const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TC_H */

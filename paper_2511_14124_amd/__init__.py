@@ -1,0 +1,14 @@
+"""MI355X tensor-cache migration library: thin Python binding over libtc.so.
+
+The binding marshals arguments only; every step of the hot path (decisions,
+copies, pack/unpack) runs in the HIP kernels of the C-ABI library declared in
+include/tc.h.
+"""
+
+from .binding import (  # noqa: F401
+    TensorCache, TcError, lib, load_library, LIB_PATH,
+    TENSOR_DESC, EVENT, POOL_CLASS, PLACEMENT, OP, STATS_FIELDS,
+    copy_batch, pack, unpack,
+    GPU, CPU, NVME, PRE, POST, END, END_CPU,
+    OP_NAMES, LITERAL_ALG2, BIND_NULL_MOVER,
+)

@@ -1,0 +1,316 @@
+"""ctypes binding of libtc.so.  Names follow include/tc.h one to one."""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtc.so")
+
+GPU, CPU, NVME = 0, 1, 2
+PRE, POST, END, END_CPU = 0, 1, 2, 3
+OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL"]
+LITERAL_ALG2 = 1
+BIND_NULL_MOVER = 1
+NONE = 0xFFFFFFFF
+MAX_STEP_TENSORS = 16
+
+TENSOR_DESC = np.dtype([("bytes", "<u8"), ("group", "u1"), ("kind", "u1"), ("pad_", "u1", (6,))])
+EVENT = np.dtype([("step", "<u4"), ("tensor", "<u4"), ("compute_ns", "<u8"), ("rw", "u1"), ("pad_", "u1", (7,))])
+POOL_CLASS = np.dtype([("bytes", "<u8"), ("stride", "<u8"), ("hbm_off", "<u8"), ("host_off", "<u8"),
+                       ("group", "<u4"), ("count", "<u4"), ("used", "<u4"), ("step_max", "<u4"),
+                       ("gpu_count", "<u4"), ("cpu_count", "<u4")])
+PLACEMENT = np.dtype([("file_off", "<u8"), ("cls", "<u4"), ("slot", "<u4"), ("first_use", "<u4"),
+                      ("final_tier", "u1"), ("pad_", "u1", (3,))])
+OP = np.dtype([("iteration", "<u4"), ("step", "<u4"), ("tensor", "<u4"), ("src_slot", "<u4"),
+               ("dst_slot", "<u4"), ("phase", "u1"), ("op", "u1"), ("src_tier", "u1"), ("dst_tier", "u1"),
+               ("bytes", "<u8")])
+SEGMENT = np.dtype([("src", "<u8"), ("dst", "<u8"), ("bytes", "<u8")])
+
+assert TENSOR_DESC.itemsize == 16 and EVENT.itemsize == 24 and POOL_CLASS.itemsize == 56
+assert PLACEMENT.itemsize == 24 and OP.itemsize == 32 and SEGMENT.itemsize == 24
+
+
+class Budget(C.Structure):
+    _fields_ = [("hbm_bytes", C.c_uint64), ("host_bytes", C.c_uint64 * 2), ("align", C.c_uint32), ("flags", C.c_uint32)]
+
+
+class PoolPlan(C.Structure):
+    _fields_ = [("n_classes", C.c_uint32), ("n_rows", C.c_uint32), ("n_steps", C.c_uint32), ("pad_", C.c_uint32),
+                ("hbm_total", C.c_uint64), ("host_total", C.c_uint64), ("file_total", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("hits", C.c_uint64), ("misses", C.c_uint64), ("fails", C.c_uint64), ("n_ops", C.c_uint64 * 8),
+                ("bytes_h2d", C.c_uint64), ("bytes_d2h", C.c_uint64),
+                ("bytes_file_read", C.c_uint64), ("bytes_file_write", C.c_uint64),
+                ("mover_launches", C.c_uint64), ("mover_units", C.c_uint64), ("decide_launches", C.c_uint64),
+                ("stall_ns", C.c_uint64), ("waits_under_30us", C.c_uint64), ("waits_total", C.c_uint64),
+                ("cursor", C.c_uint32), ("iteration", C.c_uint32)]
+
+
+STATS_FIELDS = [f[0] for f in Stats._fields_]
+
+_lib = None
+
+
+class TcError(RuntimeError):
+    def __init__(self, code: int, detail: str = ""):
+        self.code = code
+        name = lib().tc_strerror(code).decode() if _lib is not None else str(code)
+        super().__init__(f"tc error {code} ({name}): {detail}")
+
+
+def load_library(path: str = LIB_PATH):
+    """Loads libtc.so.  There is no fallback: without the built library the
+    product path does not exist."""
+    global _lib
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: run `python -m paper_2511_14124_amd.build` first")
+    L = C.CDLL(path)
+    vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
+    sig = {
+        "tc_strerror": (C.c_char_p, [i32]),
+        "tc_last_error": (C.c_char_p, [vp]),
+        "tc_create": (i32, [C.POINTER(vp)]),
+        "tc_destroy": (i32, [vp]),
+        "tc_profile_order": (i32, [vp, vp, u32, vp, u64]),
+        "tc_plan_pools": (i32, [vp, C.POINTER(Budget), C.POINTER(PoolPlan), vp, u32]),
+        "tc_plan_schedule": (i32, [vp, vp]),
+        "tc_bind_memory": (i32, [vp, vp, u64, vp, u64, vp, u64, i32, vp, u32]),
+        "tc_load_tensor": (i32, [vp, u32, vp]),
+        "tc_fill_payload": (i32, [vp, u32]),
+        "tc_read_tensor": (i32, [vp, u32, vp]),
+        "tc_migrate_step": (i32, [vp, u32, i32, vp, vp, u32, vp, vp]),
+        "tc_end_iteration": (i32, [vp, vp]),
+        "tc_emulate_compute": (i32, [vp, vp, u64, i32]),
+        "tc_synchronize": (i32, [vp]),
+        "tc_cache_stats": (i32, [vp, C.POINTER(Stats)]),
+        "tc_dump_oplog": (i32, [vp, u64, vp, u64, C.POINTER(u64)]),
+        "tc_dump_state": (i32, [vp, vp, vp, vp]),
+        "tc_set_mover": (i32, [vp, u32, u32]),
+        "tc_mover_timing": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(u64)]),
+        "tc_copy_batch": (i32, [vp, u32, vp, u32, u32]),
+        "tc_pack": (i32, [vp, vp, vp, vp, u32, u64, vp]),
+        "tc_unpack": (i32, [vp, vp, vp, vp, u32, u64, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def lib():
+    return _lib if _lib is not None else load_library()
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class TensorCache:
+    """One context of the library (one GPU).  Methods mirror the C calls."""
+
+    def __init__(self):
+        self._h = C.c_void_p()
+        rc = lib().tc_create(C.byref(self._h))
+        if rc:
+            raise TcError(rc)
+        self.n_tensors = 0
+        self.n_steps = 0
+        self._keep = []          # torch tensors / buffers that must outlive the context
+
+    def close(self):
+        if self._h:
+            lib().tc_destroy(self._h)
+            self._h = C.c_void_p()
+        self._keep = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc:
+            raise TcError(rc, lib().tc_last_error(self._h).decode())
+
+    # -- planning --------------------------------------------------------------
+    def profile_order(self, tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw, ev_ns=None, tensor_kind=None):
+        n_t = len(tensor_bytes)
+        t = np.zeros(n_t, dtype=TENSOR_DESC)
+        t["bytes"] = tensor_bytes
+        t["group"] = tensor_group
+        if tensor_kind is not None:
+            t["kind"] = tensor_kind
+        ev = np.zeros(len(ev_step), dtype=EVENT)
+        ev["step"] = ev_step
+        ev["tensor"] = ev_tensor
+        ev["rw"] = ev_rw
+        if ev_ns is not None:
+            ev["compute_ns"] = ev_ns
+        self._check(lib().tc_profile_order(self._h, _ptr(t), n_t, _ptr(ev), len(ev)))
+        self.n_tensors = n_t
+        self.tensor_bytes = np.asarray(tensor_bytes, dtype=np.uint64)
+
+    def plan_pools(self, hbm_bytes: int, host_bytes: Sequence[int], align: int = 256, flags: int = 0):
+        b = Budget(int(hbm_bytes), (C.c_uint64 * 2)(int(host_bytes[0]), int(host_bytes[1])), int(align), int(flags))
+        plan = PoolPlan()
+        classes = np.zeros(max(1, 2 * self.n_tensors), dtype=POOL_CLASS)
+        self._check(lib().tc_plan_pools(self._h, C.byref(b), C.byref(plan), _ptr(classes), len(classes)))
+        self.plan = plan
+        self.classes = classes[: plan.n_classes].copy()
+        self.n_steps = plan.n_steps
+        return plan, self.classes
+
+    def plan_schedule(self):
+        out = np.zeros(self.n_tensors, dtype=PLACEMENT)
+        self._check(lib().tc_plan_schedule(self._h, _ptr(out)))
+        self.placement = out
+        return out
+
+    # -- memory ----------------------------------------------------------------
+    def bind_memory(self, hbm_ptr: int, hbm_bytes: int, pinned_ptr: int, pinned_bytes: int,
+                    staging_ptr: int = 0, staging_bytes: int = 0, file_fd: int = -1,
+                    migrate_stream: int = 0, flags: int = 0):
+        self._check(lib().tc_bind_memory(self._h, hbm_ptr or None, hbm_bytes, pinned_ptr or None, pinned_bytes,
+                                         staging_ptr or None, staging_bytes, file_fd, migrate_stream or None, flags))
+
+    def bind_torch(self, *, staging_bytes: int = 0, file_path: Optional[str] = None, null_mover: bool = False,
+                   stream=None):
+        """Allocates the regions with PyTorch (device memory and pinned host
+        memory are PyTorch's job here) and binds them."""
+        import torch
+        if null_mover:
+            self.bind_memory(0, 0, 0, 0, 0, 0, -1, 0, BIND_NULL_MOVER)
+            return
+        dev = torch.device("cuda:0")
+        hbm = torch.empty(max(256, int(self.plan.hbm_total)), dtype=torch.uint8, device=dev)
+        pinned = torch.empty(max(256, int(self.plan.host_total)), dtype=torch.uint8, pin_memory=True)
+        staging = torch.empty(max(256, int(staging_bytes)), dtype=torch.uint8, pin_memory=True)
+        self.mstream = stream if stream is not None else torch.cuda.Stream(device=dev)
+        fd = -1
+        if file_path is not None:
+            fd = os.open(file_path, os.O_RDWR | os.O_CREAT, 0o600)
+            os.ftruncate(fd, int(self.plan.file_total))
+        self._fd = fd
+        self._keep = [hbm, pinned, staging, self.mstream]
+        self.hbm, self.pinned, self.staging = hbm, pinned, staging
+        self.bind_memory(hbm.data_ptr(), hbm.numel(), pinned.data_ptr(), pinned.numel(),
+                         staging.data_ptr(), int(staging_bytes), fd, self.mstream.cuda_stream, 0)
+
+    def load_tensor(self, tensor: int, data: np.ndarray):
+        data = np.ascontiguousarray(data, dtype=np.uint8)
+        assert data.size == int(self.tensor_bytes[tensor])
+        self._check(lib().tc_load_tensor(self._h, tensor, _ptr(data)))
+
+    def fill_payload(self, seed: int = 0):
+        self._check(lib().tc_fill_payload(self._h, seed))
+
+    def read_tensor(self, tensor: int) -> np.ndarray:
+        out = np.empty(int(self.tensor_bytes[tensor]), dtype=np.uint8)
+        self._check(lib().tc_read_tensor(self._h, tensor, _ptr(out)))
+        return out
+
+    # -- hot path ---------------------------------------------------------------
+    def migrate_step(self, step: int, phase: int, ids, rw=None, compute_stream: int = 0, want_ptrs: bool = False):
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        rwa = None if rw is None else np.ascontiguousarray(rw, dtype=np.uint8)
+        ptrs = (C.c_void_p * max(1, len(ids)))() if want_ptrs else None
+        self._check(lib().tc_migrate_step(self._h, step, phase, _ptr(ids), _ptr(rwa), len(ids),
+                                          compute_stream or None, ptrs))
+        if want_ptrs:
+            return [p or 0 for p in ptrs[: len(ids)]]
+        return None
+
+    def end_iteration(self, compute_stream: int = 0):
+        self._check(lib().tc_end_iteration(self._h, compute_stream or None))
+
+    def emulate_compute(self, compute_stream: int = 0, busy_ns: int = 0, measure_stall: bool = False):
+        self._check(lib().tc_emulate_compute(self._h, compute_stream or None, int(busy_ns), int(measure_stall)))
+
+    def synchronize(self):
+        self._check(lib().tc_synchronize(self._h))
+
+    def replay_iteration(self, steps, compute_stream: int = 0, busy_ns=None, measure_stall: bool = False):
+        """PRE, stand-in compute, POST for every step, then the end-of-iteration call."""
+        for k, access in enumerate(steps):
+            ids = [t for (t, _a) in access]
+            rw = [a for (_t, a) in access]
+            self.migrate_step(k, PRE, ids, rw, compute_stream)
+            self.emulate_compute(compute_stream, 0 if busy_ns is None else int(busy_ns[k]), measure_stall)
+            self.migrate_step(k, POST, ids, rw, compute_stream)
+        self.end_iteration(compute_stream)
+
+    # -- introspection -----------------------------------------------------------
+    def cache_stats(self) -> dict:
+        s = Stats()
+        self._check(lib().tc_cache_stats(self._h, C.byref(s)))
+        out = {}
+        for name in STATS_FIELDS:
+            v = getattr(s, name)
+            out[name] = list(v) if name == "n_ops" else int(v)
+        return out
+
+    def dump_oplog(self) -> np.ndarray:
+        n = C.c_uint64()
+        self._check(lib().tc_dump_oplog(self._h, 0, None, 0, C.byref(n)))
+        buf = np.zeros(n.value, dtype=OP)
+        if n.value:
+            self._check(lib().tc_dump_oplog(self._h, 0, _ptr(buf), n.value, C.byref(n)))
+        return buf
+
+    def dump_state(self):
+        tier = np.zeros(self.n_tensors, dtype=np.uint8)
+        gs = np.zeros(self.n_tensors, dtype=np.uint32)
+        cs = np.zeros(self.n_tensors, dtype=np.uint32)
+        self._check(lib().tc_dump_state(self._h, _ptr(tier), _ptr(gs), _ptr(cs)))
+        return tier, gs, cs
+
+    def set_mover(self, workgroups: int = 0, chunk_bytes: int = 0):
+        self._check(lib().tc_set_mover(self._h, workgroups, chunk_bytes))
+
+    def mover_timing(self, enable: bool):
+        avg = C.c_double()
+        n = C.c_uint64()
+        self._check(lib().tc_mover_timing(self._h, int(enable), C.byref(avg), C.byref(n)))
+        return avg.value, n.value
+
+    # -- convenience: a workload object from the workloads package ----------------
+    @classmethod
+    def from_workload(cls, wl) -> "TensorCache":
+        tc = cls()
+        st, te, rw, ns = wl.events()
+        tc.profile_order(wl.tensor_bytes, wl.tensor_group, st, te, rw, ns, wl.tensor_kind)
+        tc.plan_pools(wl.hbm_bytes, wl.host_bytes, wl.align, LITERAL_ALG2 if wl.literal_alg2 else 0)
+        tc.plan_schedule()
+        return tc
+
+
+def copy_batch(src_ptrs, dst_ptrs, nbytes, stream: int = 0, workgroups: int = 0, chunk_bytes: int = 0):
+    segs = np.zeros(len(src_ptrs), dtype=SEGMENT)
+    segs["src"] = src_ptrs
+    segs["dst"] = dst_ptrs
+    segs["bytes"] = nbytes
+    rc = lib().tc_copy_batch(_ptr(segs), len(segs), stream or None, workgroups, chunk_bytes)
+    if rc:
+        raise TcError(rc)
+
+
+def pack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, stream: int = 0):
+    rc = lib().tc_pack(slab_ptr, ptrs_dev, bytes_dev, off_dev, n, total, stream or None)
+    if rc:
+        raise TcError(rc)
+
+
+def unpack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, stream: int = 0):
+    rc = lib().tc_unpack(slab_ptr, ptrs_dev, bytes_dev, off_dev, n, total, stream or None)
+    if rc:
+        raise TcError(rc)

@@ -1,0 +1,677 @@
+// HIP kernels for gfx950 (MI355X): the scheduler's decision kernel, the batched
+// migration kernel, the stamp/spin stand-in for module compute, the payload
+// fill kernel and the LDS-staged pack/unpack kernel.
+#include "tc_internal.h"
+
+#define NONE 0xFFFFFFFFu
+#define WAVE 64
+
+// ===========================================================================
+// Decision kernel: the prefetch-eviction scheduler of Sec. 3.4 (Alg. 3 and
+// Alg. 4) as ONE wavefront.
+//
+// The scheduler is a sequential state machine (each decision moves the
+// cursor and the owner tables the next one reads), so the sequence of
+// decisions stays in one wave.  What the wave parallelises is each decision's
+// table search: residency of the rows ahead of the cursor and lowest free
+// buffer by ballot + find-first-set, farthest-next-use victim by a 64-lane
+// max-reduction.  All control flow is wave-uniform.  Every lane performs every
+// state store itself (same address, same value), so a lane's later loads see
+// the table as updated without any cross-lane memory ordering.
+// ===========================================================================
+
+struct DecideCtx {
+    TcDevTables T;
+    TcDecideOut *out;
+    TcOpRec *ops;
+    uint32_t cap, n_ops;
+    uint32_t call, bound, step, phase;
+    uint32_t lane;
+};
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        uint32_t lo = __shfl_xor((uint32_t)v, off, WAVE);
+        uint32_t hi = __shfl_xor((uint32_t)(v >> 32), off, WAVE);
+        uint64_t o = ((uint64_t)hi << 32) | lo;
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// first row >= bound that uses tensor t, NONE if there is none
+__device__ __forceinline__ uint32_t next_use(const TcDevTables &T, uint32_t t, uint32_t bound)
+{
+    uint32_t b = T.occ_ptr[t], e = T.occ_ptr[t + 1];
+    const uint32_t end = e;
+    while (b < e) {
+        uint32_t m = (b + e) >> 1;
+        if (T.occ_rows[m] < bound) b = m + 1; else e = m;
+    }
+    return b < end ? T.occ_rows[b] : NONE;
+}
+
+__device__ __forceinline__ void emit(DecideCtx &c, uint32_t op, uint32_t t, uint32_t st, uint32_t ss,
+                                     uint32_t dt, uint32_t ds)
+{
+    if (c.n_ops < c.cap) {
+        if (c.lane == 0) {
+            TcOpRec r;
+            r.tensor = t; r.src_slot = ss; r.dst_slot = ds;
+            r.op = (uint8_t)op; r.phase = (uint8_t)c.phase; r.src_tier = (uint8_t)st; r.dst_tier = (uint8_t)dt;
+            c.ops[c.n_ops] = r;
+        }
+    }
+    c.n_ops++;
+}
+
+// lowest free buffer of a class that was not freed by this hook call
+__device__ __forceinline__ uint32_t lowest_free(const DecideCtx &c, const uint32_t *owner,
+                                                const uint32_t *freed, uint32_t count)
+{
+    for (uint32_t base = 0; base < count; base += WAVE) {
+        uint32_t k = base + c.lane;
+        bool ok = k < count && owner[k] == NONE && freed[k] != c.call;
+        uint64_t m = __ballot(ok);
+        if (m) return base + (uint32_t)__ffsll((long long)m) - 1;
+    }
+    return NONE;
+}
+
+// key of "used farthest in the future, ties -> lowest id"; larger is better
+__device__ __forceinline__ uint64_t far_key(uint32_t nu, uint32_t id)
+{
+    return ((uint64_t)nu << 32) | (uint64_t)(NONE - id);
+}
+
+// Alg. 4's spill victim: an occupied host buffer of the class, GPU-designated
+// ones first, whose tensor was not moved by this call and is used farthest in
+// the future.
+__device__ uint32_t spill_victim(const DecideCtx &c, uint32_t s)
+{
+    const TcDevTables &T = c.T;
+    const uint32_t cb = T.cpu_base[s], cc = T.cpu_count[s];
+    uint64_t best_d = 0, best_a = 0;
+    for (uint32_t k = c.lane; k < cc; k += WAVE) {
+        uint32_t o = T.cpu_owner[cb + k];
+        if (o == NONE || T.moved[o] == c.call) continue;
+        uint64_t key = far_key(next_use(T, o, c.bound), o);
+        if (T.designated[cb + k]) best_d = key > best_d ? key : best_d;
+        best_a = key > best_a ? key : best_a;
+    }
+    best_d = wave_max_u64(best_d);
+    best_a = wave_max_u64(best_a);
+    uint64_t best = best_d ? best_d : best_a;
+    return best ? NONE - (uint32_t)best : NONE;
+}
+
+// EvictTensor (Alg. 4).  partner = host buffer of the tensor about to take
+// v's GPU buffer (the two swap places), or NONE.
+__device__ void evict(DecideCtx &c, uint32_t v, uint32_t partner)
+{
+    const TcDevTables &T = c.T;
+    const uint32_t s = T.class_of[v], y = T.gslot[v];
+    const uint32_t gb = T.gpu_base[s], cb = T.cpu_base[s];
+    if (T.final_tier[v] == TC_NVME) {
+        if (T.dirty[v]) {
+            emit(c, TC_OP_WRITEBACK, v, TC_GPU, y, TC_NVME, NONE);
+            T.dirty[v] = 0;
+        } else {
+            emit(c, TC_OP_RELEASE, v, TC_GPU, y, TC_NVME, NONE);
+        }
+        T.cur[v] = TC_NVME;
+    } else {
+        uint32_t x = partner;
+        if (x == NONE) x = lowest_free(c, T.cpu_owner + cb, T.cpu_freed + cb, T.cpu_count[s]);
+        if (x == NONE) {
+            uint32_t w = spill_victim(c, s);
+            if (w != NONE) {
+                x = T.cslot[w];
+                emit(c, TC_OP_SPILL, w, TC_CPU, x, TC_NVME, NONE);
+                T.cur[w] = TC_NVME;
+                T.cslot[w] = NONE;
+                T.moved[w] = c.call;
+                T.cpu_owner[cb + x] = NONE;
+                T.designated[cb + x] = 0;
+            }
+        }
+        if (x == NONE) {            // the class has no host buffer to give: straight to the file tier
+            emit(c, TC_OP_WRITEBACK, v, TC_GPU, y, TC_NVME, NONE);
+            T.cur[v] = TC_NVME;
+        } else {
+            T.designated[cb + x] = (T.final_tier[v] == TC_GPU) ? 1u : 0u;
+            T.cpu_owner[cb + x] = v;
+            T.cslot[v] = x;
+            emit(c, TC_OP_EVICT, v, TC_GPU, y, TC_CPU, x);
+            T.cur[v] = TC_CPU;
+        }
+    }
+    T.gslot[v] = NONE;
+    T.gpu_owner[gb + y] = NONE;
+    T.gpu_freed[gb + y] = c.call;
+    T.moved[v] = c.call;
+}
+
+// evict v (if any) and bring u into GPU buffer y of their common class
+__device__ void exchange(DecideCtx &c, uint32_t v, uint32_t u, uint32_t y, uint32_t op_in)
+{
+    const TcDevTables &T = c.T;
+    const uint32_t s = T.class_of[u];
+    const uint32_t gb = T.gpu_base[s], cb = T.cpu_base[s];
+    const uint32_t src_tier = T.cur[u], src_slot = T.cslot[u];
+    if (v != NONE) {
+        uint32_t swap = (src_tier == TC_CPU && T.final_tier[v] != TC_NVME) ? src_slot : NONE;
+        if (swap != NONE) {
+            T.cpu_owner[cb + swap] = NONE;
+            T.designated[cb + swap] = 0;
+        }
+        evict(c, v, swap);
+    }
+    if (src_tier == TC_CPU && T.cpu_owner[cb + src_slot] == u) {
+        T.cpu_owner[cb + src_slot] = NONE;
+        T.designated[cb + src_slot] = 0;
+        T.cpu_freed[cb + src_slot] = c.call;
+    }
+    emit(c, op_in, u, src_tier, src_tier == TC_CPU ? src_slot : NONE, TC_GPU, y);
+    T.cur[u] = TC_GPU;
+    T.gslot[u] = y;
+    T.cslot[u] = NONE;
+    T.gpu_owner[gb + y] = u;
+    T.moved[u] = c.call;
+}
+
+__device__ __forceinline__ bool in_list(const TcStepArgs &a, uint32_t x)
+{
+    bool hit = false;
+    for (uint32_t i = 0; i < a.n; ++i) hit |= (a.ids[i] == x);
+    return hit;
+}
+
+// pre-hook: residency of the step's tensors, demand fetch of the missing ones
+__device__ void decide_pre(DecideCtx &c, const TcStepArgs &a)
+{
+    const TcDevTables &T = c.T;
+    c.bound = a.step < T.n_steps ? T.row_begin[a.step] : T.n_rows;
+    // residency of the whole list in one ballot: an all-hit step (the common
+    // case when prefetching keeps up) is resolved without the serial loop
+    {
+        const bool mine = c.lane < a.n;
+        const uint32_t t = a.ids[mine ? c.lane : 0];
+        const bool res = mine && T.cur[t] == TC_GPU;
+        const uint64_t mk = __ballot(res);
+        if ((uint32_t)__popcll(mk) == a.n) {
+            if (mine) {
+                if (a.rw[c.lane] & TC_W) T.dirty[t] = 1;
+                c.out->slots[c.lane] = T.gslot[t];
+            }
+            if (c.lane == 0) { c.out->hits = a.n; c.out->misses = 0; c.out->fails = 0; }
+            return;
+        }
+    }
+    uint32_t h = 0, m = 0, f = 0;
+    for (uint32_t i = 0; i < a.n; ++i) {
+        const uint32_t t = a.ids[i];
+        const uint32_t s = T.class_of[t];
+        const uint32_t gb = T.gpu_base[s], gc = T.gpu_count[s];
+        if (T.cur[t] == TC_GPU) {
+            h++;
+        } else {
+            m++;
+            uint32_t y = lowest_free(c, T.gpu_owner + gb, T.gpu_freed + gb, gc);
+            uint32_t v = NONE;
+            if (y == NONE) {
+                uint64_t best = 0;
+                for (uint32_t k = c.lane; k < gc; k += WAVE) {
+                    uint32_t x = T.gpu_owner[gb + k];
+                    if (x == NONE || T.moved[x] == c.call || in_list(a, x)) continue;
+                    uint64_t key = far_key(next_use(T, x, c.bound), x);
+                    best = key > best ? key : best;
+                }
+                best = wave_max_u64(best);
+                if (best) { v = NONE - (uint32_t)best; y = T.gslot[v]; }
+            }
+            if (y == NONE) {
+                f++;
+                emit(c, TC_OP_FAIL, t, T.cur[t], NONE, TC_GPU, NONE);
+                if (c.lane == 0) c.out->slots[i] = NONE;
+                continue;
+            }
+            exchange(c, v, t, y, TC_OP_DEMAND);
+        }
+        if (a.rw[i] & TC_W) T.dirty[t] = 1;
+        if (c.lane == 0) c.out->slots[i] = T.gslot[t];
+    }
+    if (c.lane == 0) { c.out->hits = h; c.out->misses = m; c.out->fails = f; }
+}
+
+// post-hook: PrefetchTensor (Alg. 3) over the tensors that finished
+__device__ void decide_post(DecideCtx &c, const TcStepArgs &a)
+{
+    const TcDevTables &T = c.T;
+    const uint32_t n_rows = T.n_rows;
+    c.bound = a.step < T.n_steps ? T.row_begin[a.step + 1] : n_rows;
+    uint32_t cursor = T.scalars[0];
+    cursor = cursor > c.bound ? cursor : c.bound;
+    for (uint32_t i = 0; i < a.n; ++i) {
+        const uint32_t t = a.ids[i];
+        if (cursor >= n_rows) break;
+        // skip rows already in the active tensor window, 64 rows per ballot
+        while (cursor < n_rows) {
+            uint32_t r = cursor + c.lane;
+            bool stop = false;
+            if (r < n_rows) {
+                uint32_t x = T.rows_tensor[r];
+                stop = !(T.cur[x] == TC_GPU || T.gpu_count[T.class_of[x]] == 0);
+            }
+            uint64_t mk = __ballot(stop);
+            if (mk) { cursor += (uint32_t)__ffsll((long long)mk) - 1; break; }
+            cursor = cursor + WAVE < n_rows ? cursor + WAVE : n_rows;
+        }
+        if (cursor >= n_rows) break;
+        const uint32_t u = T.rows_tensor[cursor];
+        if (T.moved[u] == c.call) break;                  // in flight
+        const uint32_t s = T.class_of[u];
+        const uint32_t gb = T.gpu_base[s], gc = T.gpu_count[s];
+        uint32_t v = NONE, y = NONE;
+        if (T.class_of[t] == s && T.cur[t] == TC_GPU && T.moved[t] != c.call &&
+            next_use(T, t, c.bound) > cursor) {
+            v = t;                                        // the finished tensor gives up its buffer
+            y = T.gslot[t];
+        } else {
+            y = lowest_free(c, T.gpu_owner + gb, T.gpu_freed + gb, gc);
+            if (y == NONE) {
+                uint64_t best = 0;
+                for (uint32_t k = c.lane; k < gc; k += WAVE) {
+                    uint32_t x = T.gpu_owner[gb + k];
+                    if (x == NONE || T.moved[x] == c.call) continue;
+                    uint32_t nu = next_use(T, x, c.bound);
+                    if (nu <= cursor) continue;           // needed before u: stays
+                    uint64_t key = far_key(nu, x);
+                    best = key > best ? key : best;
+                }
+                best = wave_max_u64(best);
+                if (best) { v = NONE - (uint32_t)best; y = T.gslot[v]; }
+            }
+        }
+        if (y == NONE) continue;                          // halt for this tensor
+        exchange(c, v, u, y, TC_OP_PREFETCH);
+        cursor++;
+    }
+    T.scalars[0] = cursor;
+}
+
+// end of iteration: tensors return to their final locations (Sec. 3.2.1)
+__device__ void decide_end(DecideCtx &c)
+{
+    const TcDevTables &T = c.T;
+    c.bound = T.n_rows;
+    // first call: GPU-final tensors come home, class by class, placement order
+    for (uint32_t s = 0; s < T.n_classes; ++s) {
+        const uint32_t gb = T.gpu_base[s], gc = T.gpu_count[s];
+        const uint32_t mb = T.member_ptr[s], me = T.member_ptr[s + 1];
+        uint32_t i = mb;
+        while (i < me) {
+            // next member that is GPU-final and elsewhere, 64 members per ballot
+            uint32_t j = i + c.lane;
+            bool want = false;
+            if (j < me) {
+                uint32_t u = T.members[j];
+                want = T.final_tier[u] == TC_GPU && T.cur[u] != TC_GPU;
+            }
+            uint64_t mk = __ballot(want);
+            if (!mk) { i += WAVE; continue; }
+            i += (uint32_t)__ffsll((long long)mk) - 1;
+            const uint32_t u = T.members[i];
+            i++;
+            uint32_t y = lowest_free(c, T.gpu_owner + gb, T.gpu_freed + gb, gc);
+            uint32_t v = NONE;
+            if (y == NONE) {
+                uint32_t best = NONE;                      // lowest-id guest
+                for (uint32_t k = c.lane; k < gc; k += WAVE) {
+                    uint32_t x = T.gpu_owner[gb + k];
+                    if (x == NONE || T.final_tier[x] == TC_GPU || T.moved[x] == c.call) continue;
+                    best = x < best ? x : best;
+                }
+                uint64_t r = wave_max_u64((uint64_t)(NONE - best));
+                best = NONE - (uint32_t)r;
+                if (best == NONE) continue;
+                v = best;
+                y = T.gslot[v];
+            }
+            exchange(c, v, u, y, TC_OP_PREFETCH);
+        }
+    }
+    // second call: CPU-final tensors on the file tier return to host buffers
+    c.call++;
+    c.phase = TC_END_CPU;
+    for (uint32_t s = 0; s < T.n_classes; ++s) {
+        const uint32_t cb = T.cpu_base[s], cc = T.cpu_count[s];
+        const uint32_t mb = T.member_ptr[s], me = T.member_ptr[s + 1];
+        uint32_t i = mb;
+        while (i < me) {
+            uint32_t j = i + c.lane;
+            bool want = false;
+            if (j < me) {
+                uint32_t u = T.members[j];
+                want = T.final_tier[u] == TC_CPU && T.cur[u] == TC_NVME;
+            }
+            uint64_t mk = __ballot(want);
+            if (!mk) { i += WAVE; continue; }
+            i += (uint32_t)__ffsll((long long)mk) - 1;
+            const uint32_t u = T.members[i];
+            i++;
+            uint32_t x = lowest_free(c, T.cpu_owner + cb, T.cpu_freed + cb, cc);
+            if (x == NONE) continue;
+            emit(c, TC_OP_RESTORE, u, TC_NVME, NONE, TC_CPU, x);
+            T.cur[u] = TC_CPU;
+            T.cslot[u] = x;
+            T.cpu_owner[cb + x] = u;
+            T.moved[u] = c.call;
+        }
+        for (uint32_t k = c.lane; k < cc; k += WAVE) T.designated[cb + k] = 0;
+    }
+    T.scalars[0] = 0;
+    T.scalars[2] = T.scalars[2] + 1;
+}
+
+__global__ __launch_bounds__(WAVE) void tc_decide_kernel(TcDevTables T, TcStepArgs a, TcDecideOut *out)
+{
+    DecideCtx c;
+    c.T = T;
+    c.out = out;
+    c.ops = (TcOpRec *)(out + 1);
+    c.cap = a.cap;
+    c.n_ops = 0;
+    c.lane = threadIdx.x;
+    c.step = a.step;
+    c.phase = a.phase;
+    c.call = T.scalars[1] + 1;
+    c.bound = 0;
+    if (c.lane == 0) { out->hits = 0; out->misses = 0; out->fails = 0; }
+    if (a.phase == TC_PRE) decide_pre(c, a);
+    else if (a.phase == TC_POST) decide_post(c, a);
+    else decide_end(c);
+    T.scalars[1] = c.call;
+    if (c.lane == 0) {
+        out->cursor = T.scalars[0];
+        out->iteration = T.scalars[2];
+        out->overflow = c.n_ops > c.cap ? 1u : 0u;
+        out->n_ops = c.n_ops < c.cap ? c.n_ops : c.cap;
+    }
+}
+
+hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(tc_decide_kernel, dim3(1), dim3(WAVE), 0, s, T, a, out);
+    return hipGetLastError();
+}
+
+// ===========================================================================
+// Migration kernel: one launch moves every exchange unit of a hook call.
+//
+// The link to host memory, not HBM and not the ALUs, bounds this kernel, so the
+// design goal is enough 128-bit requests in flight per wave to cover the host
+// link's latency, on both directions at once.  Work is cut into chunks of
+// chunk_bytes; workgroup b takes chunks b, b+grid, ... (static assignment: no
+// queue, no waiting, every wave exits after its last chunk).  Within a chunk
+// each lane moves 16 bytes per request; a wave's 64 lanes cover 1 KiB of
+// consecutive addresses, and four requests per direction are issued before
+// the first store.  For a unit with both directions each lane holds the
+// outgoing and the incoming 16 bytes of the same index before storing either,
+// which is what lets a tensor leave a GPU buffer while another arrives in it.
+// ===========================================================================
+
+#define MOVER_THREADS 256
+#define MOVER_UNROLL 4
+
+__device__ __forceinline__ uint4 ld16(const uint8_t *p) { return *(const uint4 *)p; }
+__device__ __forceinline__ void st16(uint8_t *p, uint4 v) { *(uint4 *)p = v; }
+
+__global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
+{
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
+        // unit of this chunk: the last one whose first chunk is <= c
+        uint32_t ui = 0;
+        for (uint32_t i = 1; i < a.n_units; ++i) ui = (a.u[i].chunk0 <= c) ? i : ui;
+        const TcUnit &U = a.u[ui];
+        const uint64_t off = (c - U.chunk0) * (uint64_t)a.chunk_bytes;
+        const uint64_t left = U.bytes - off;
+        const uint32_t len = left < a.chunk_bytes ? (uint32_t)left : a.chunk_bytes;
+        const uint32_t n16 = len >> 4;
+        const uint8_t *os = U.out_src ? U.out_src + off : nullptr;
+        uint8_t *od = U.out_dst ? U.out_dst + off : nullptr;
+        const uint8_t *is = U.in_src ? U.in_src + off : nullptr;
+        uint8_t *id = U.in_dst ? U.in_dst + off : nullptr;
+        uint32_t i = tid;
+        if (os && is) {
+            for (; i + (MOVER_UNROLL - 1) * MOVER_THREADS < n16; i += MOVER_UNROLL * MOVER_THREADS) {
+                uint4 vo[MOVER_UNROLL], vi[MOVER_UNROLL];
+#pragma unroll
+                for (int k = 0; k < MOVER_UNROLL; ++k) vi[k] = ld16(is + (uint64_t)(i + k * MOVER_THREADS) * 16);
+#pragma unroll
+                for (int k = 0; k < MOVER_UNROLL; ++k) vo[k] = ld16(os + (uint64_t)(i + k * MOVER_THREADS) * 16);
+#pragma unroll
+                for (int k = 0; k < MOVER_UNROLL; ++k) st16(od + (uint64_t)(i + k * MOVER_THREADS) * 16, vo[k]);
+#pragma unroll
+                for (int k = 0; k < MOVER_UNROLL; ++k) st16(id + (uint64_t)(i + k * MOVER_THREADS) * 16, vi[k]);
+            }
+            for (; i < n16; i += MOVER_THREADS) {
+                uint4 vi = ld16(is + (uint64_t)i * 16);
+                uint4 vo = ld16(os + (uint64_t)i * 16);
+                st16(od + (uint64_t)i * 16, vo);
+                st16(id + (uint64_t)i * 16, vi);
+            }
+            const uint32_t tail = len & 15u;               // only the unit's last chunk has one
+            if (tid < tail) {
+                uint8_t bo = os[(uint64_t)n16 * 16 + tid], bi = is[(uint64_t)n16 * 16 + tid];
+                od[(uint64_t)n16 * 16 + tid] = bo;
+                id[(uint64_t)n16 * 16 + tid] = bi;
+            }
+        } else {
+            const uint8_t *s = os ? os : is;
+            uint8_t *d = os ? od : id;
+            if (!s) continue;
+            for (; i + (MOVER_UNROLL - 1) * MOVER_THREADS < n16; i += MOVER_UNROLL * MOVER_THREADS) {
+                uint4 v[MOVER_UNROLL];
+#pragma unroll
+                for (int k = 0; k < MOVER_UNROLL; ++k) v[k] = ld16(s + (uint64_t)(i + k * MOVER_THREADS) * 16);
+#pragma unroll
+                for (int k = 0; k < MOVER_UNROLL; ++k) st16(d + (uint64_t)(i + k * MOVER_THREADS) * 16, v[k]);
+            }
+            for (; i < n16; i += MOVER_THREADS) st16(d + (uint64_t)i * 16, ld16(s + (uint64_t)i * 16));
+            const uint32_t tail = len & 15u;
+            if (tid < tail) d[(uint64_t)n16 * 16 + tid] = s[(uint64_t)n16 * 16 + tid];
+        }
+    }
+}
+
+hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_t s)
+{
+    if (a.n_units == 0 || a.n_chunks == 0) return hipSuccess;
+    // the kernel trusts these counts: check them against the units before it runs
+    if (a.n_units > TC_MOVER_MAX_UNITS || a.chunk_bytes == 0 || (a.chunk_bytes & 15)) return hipErrorInvalidValue;
+    uint64_t chunks = 0;
+    for (uint32_t i = 0; i < a.n_units; ++i) {
+        const TcUnit &u = a.u[i];
+        if (u.chunk0 != chunks || u.bytes == 0) return hipErrorInvalidValue;
+        if ((u.out_src == nullptr) != (u.out_dst == nullptr)) return hipErrorInvalidValue;
+        if ((u.in_src == nullptr) != (u.in_dst == nullptr)) return hipErrorInvalidValue;
+        if (!u.out_src && !u.in_src) return hipErrorInvalidValue;
+        chunks += (u.bytes + a.chunk_bytes - 1) / a.chunk_bytes;
+    }
+    if (chunks != a.n_chunks) return hipErrorInvalidValue;
+    uint64_t g = a.n_chunks < workgroups ? a.n_chunks : workgroups;
+    hipLaunchKernelGGL(tc_mover_kernel, dim3((uint32_t)g), dim3(MOVER_THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+// ===========================================================================
+// Stand-in for a module's kernels in a replay: stamp written tensors, then spin.
+// ===========================================================================
+__global__ __launch_bounds__(WAVE) void tc_stamp_kernel(TcStampArgs a)
+{
+    const uint32_t i = threadIdx.x;
+    // a list may name a tensor more than once; its stamps are identical and XOR
+    // cancels in pairs, so the first occurrence applies it iff the count is odd
+    bool apply = false;
+    if (i < a.n && a.ptr[i]) {
+        uint32_t same = 0, earlier = 0;
+        for (uint32_t j = 0; j < a.n; ++j) {
+            same += (a.ptr[j] == a.ptr[i]);
+            earlier += (j < i && a.ptr[j] == a.ptr[i]);
+        }
+        apply = earlier == 0 && (same & 1);
+    }
+    if (apply) {
+        const uint32_t w[4] = {0x10CAC4E5u, a.iteration, a.step, a.tensor[i]};
+        uint8_t *p = a.ptr[i];
+        const uint64_t n = a.bytes[i];
+        // head then tail, byte by byte: the two ranges may overlap for tiny tensors
+        for (uint32_t b = 0; b < 16; ++b) p[b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+        for (uint32_t b = 0; b < 16; ++b) p[n - 16 + b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+    }
+    if (a.busy_ns && i == 0) {
+        // wall_clock64 counts at 100 MHz; the loop ends once busy_ns have passed
+        const uint64_t t0 = wall_clock64();
+        const uint64_t ticks = a.busy_ns / 10;
+        while (wall_clock64() - t0 < ticks) { __builtin_amdgcn_s_sleep(8); }
+    }
+}
+
+hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(tc_stamp_kernel, dim3(1), dim3(WAVE), 0, s, a);
+    return hipGetLastError();
+}
+
+// ===========================================================================
+// Payload fill: word i of tensor t = h(i*0x9E3779B1 + t*0x85EBCA77 + seed*0xC2B2AE3D)
+// ===========================================================================
+__device__ __forceinline__ uint32_t hash32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+
+__global__ __launch_bounds__(256) void tc_fill_kernel(uint8_t *dst, uint64_t bytes, uint32_t base)
+{
+    const uint64_t n16 = bytes >> 4;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        uint32_t w0 = (uint32_t)(i * 4);
+        uint4 v;
+        v.x = hash32((w0 + 0) * 0x9E3779B1u + base);
+        v.y = hash32((w0 + 1) * 0x9E3779B1u + base);
+        v.z = hash32((w0 + 2) * 0x9E3779B1u + base);
+        v.w = hash32((w0 + 3) * 0x9E3779B1u + base);
+        *(uint4 *)(dst + i * 16) = v;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (bytes & 15)) {
+        uint64_t b = n16 * 16 + threadIdx.x;
+        uint32_t w = hash32((uint32_t)(b >> 2) * 0x9E3779B1u + base);
+        dst[b] = (uint8_t)(w >> (8 * (b & 3)));
+    }
+}
+
+hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t seed, hipStream_t s)
+{
+    uint32_t base = tensor * 0x85EBCA77u + seed * 0xC2B2AE3Du;
+    uint64_t n16 = bytes >> 4;
+    uint32_t blocks = (uint32_t)((n16 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(tc_fill_kernel, dim3(blocks), dim3(256), 0, s, (uint8_t *)dst, bytes, base);
+    return hipGetLastError();
+}
+
+// ===========================================================================
+// Pack / unpack of small tensors: HBM buffers <-> one contiguous HBM slab.
+//
+// Bound by HBM bandwidth: every payload byte is read once and written once.
+// A workgroup owns one 16 KiB tile of the slab.  The tile's bytes come from
+// (pack) or go to (unpack) one or more tensors whose addresses are aligned
+// differently from the slab's, so the tile is staged in LDS: the global side
+// that is 16-byte aligned for its own pointer moves as 128-bit requests into
+// LDS, and the other side leaves LDS as 128-bit requests aligned for *its*
+// pointer; only the few bytes at segment edges move bytewise.
+// ===========================================================================
+#define PACK_TILE 16384
+#define PACK_THREADS 256
+
+__global__ __launch_bounds__(PACK_THREADS) void tc_pack_kernel(
+    uint8_t *slab, uint8_t *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
+    uint32_t n, uint64_t total, int unpack)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t tile[PACK_TILE];
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t t0 = (uint64_t)blockIdx.x * PACK_TILE; t0 < total; t0 += (uint64_t)gridDim.x * PACK_TILE) {
+        const uint64_t t1 = t0 + PACK_TILE < total ? t0 + PACK_TILE : total;
+        const uint32_t tlen = (uint32_t)(t1 - t0);
+        // first segment that reaches into the tile: last i with slab_off[i] <= t0
+        uint32_t lo = 0, hi = n;
+        while (hi - lo > 1) {
+            uint32_t m = (lo + hi) >> 1;
+            if (slab_off[m] <= t0) lo = m; else hi = m;
+        }
+        if (unpack) {
+            // slab -> LDS, 128-bit and aligned (slab and tile start are 16-byte aligned)
+            for (uint32_t i = tid * 16; i < (tlen & ~15u); i += PACK_THREADS * 16)
+                *(uint4 *)(tile + i) = *(const uint4 *)(slab + t0 + i);
+            for (uint32_t i = (tlen & ~15u) + tid; i < tlen; i += PACK_THREADS) tile[i] = slab[t0 + i];
+            __syncthreads();
+        }
+        for (uint32_t sg = lo; sg < n && slab_off[sg] < t1; ++sg) {
+            const uint64_t so = slab_off[sg], sb = bytes[sg];
+            const uint64_t b = so > t0 ? so : t0;               // overlap of segment and tile, slab coords
+            const uint64_t e = so + sb < t1 ? so + sb : t1;
+            if (e <= b) continue;
+            uint8_t *g = ptrs[sg] + (b - so);                   // global address of the first byte
+            uint8_t *l = tile + (b - t0);
+            const uint32_t len = (uint32_t)(e - b);
+            // head bytes until the GLOBAL pointer is 16-byte aligned
+            uint32_t head = (uint32_t)((16 - ((uintptr_t)g & 15)) & 15);
+            if (head > len) head = len;
+            const uint32_t body = (len - head) & ~15u;
+            const uint32_t lmis = (uint32_t)((uintptr_t)(l + head) & 15);
+            if (unpack) {
+                if (tid < head) g[tid] = l[tid];
+                for (uint32_t i = tid * 16; i < body; i += PACK_THREADS * 16) {
+                    uint4 v;
+                    if (lmis == 0) v = *(const uint4 *)(l + head + i);
+                    else __builtin_memcpy(&v, l + head + i, 16);  // LDS side may be misaligned
+                    *(uint4 *)(g + head + i) = v;
+                }
+                for (uint32_t i = head + body + tid; i < len; i += PACK_THREADS) g[i] = l[i];
+            } else {
+                if (tid < head) l[tid] = g[tid];
+                for (uint32_t i = tid * 16; i < body; i += PACK_THREADS * 16) {
+                    uint4 v = *(const uint4 *)(g + head + i);
+                    if (lmis == 0) *(uint4 *)(l + head + i) = v;
+                    else __builtin_memcpy(l + head + i, &v, 16);
+                }
+                for (uint32_t i = head + body + tid; i < len; i += PACK_THREADS) l[i] = g[i];
+            }
+        }
+        if (!unpack) {
+            __syncthreads();
+            for (uint32_t i = tid * 16; i < (tlen & ~15u); i += PACK_THREADS * 16)
+                *(uint4 *)(slab + t0 + i) = *(const uint4 *)(tile + i);
+            for (uint32_t i = (tlen & ~15u) + tid; i < tlen; i += PACK_THREADS) slab[t0 + i] = tile[i];
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t tc_launch_pack(void *slab, const void *const *ptrs, const uint64_t *bytes,
+                          const uint64_t *slab_off, uint32_t n, uint64_t total, int unpack, hipStream_t s)
+{
+    if (n == 0 || total == 0) return hipSuccess;
+    uint64_t tiles = (total + PACK_TILE - 1) / PACK_TILE;
+    uint32_t blocks = (uint32_t)(tiles < 8192 ? tiles : 8192);
+    hipLaunchKernelGGL(tc_pack_kernel, dim3(blocks), dim3(PACK_THREADS), 0, s, (uint8_t *)slab,
+                       (uint8_t *const *)ptrs, bytes, slab_off, n, total, unpack);
+    return hipGetLastError();
+}

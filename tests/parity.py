@@ -1,0 +1,63 @@
+"""Helpers that compare a replay through the C-ABI library with the oracle."""
+
+import numpy as np
+
+import paper_2511_14124_amd as T
+import workloads as W
+from oracle import tc_oracle as o
+
+
+def oracle_log_array(r):
+    a = np.zeros(len(r.log), dtype=T.OP)
+    if len(r.log):
+        cols = list(zip(*r.log))
+        for name, col in zip(("iteration", "step", "phase", "op", "tensor", "src_tier", "src_slot",
+                              "dst_tier", "dst_slot", "bytes"), cols):
+            a[name] = col
+    return a
+
+
+def compare_logs(got, want):
+    assert len(got) == len(want), (len(got), len(want))
+    for name in T.OP.names:
+        if not np.array_equal(got[name], want[name]):
+            i = int(np.nonzero(got[name] != want[name])[0][0])
+            raise AssertionError(f"op log differs at record {i} field {name}: got {got[i]} want {want[i]}")
+
+
+def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
+                busy=False):
+    """Replays every iteration of wl through the library; returns the context."""
+    import torch
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes)
+    if mover:
+        tc.set_mover(*mover)
+    if payload and not null_mover:
+        for t in range(wl.n_tensors):
+            tc.load_tensor(t, W.workload_payload(wl, t))
+    cs = torch.cuda.Stream()
+    for steps in wl.iterations:
+        tc.replay_iteration(steps, cs.cuda_stream, busy_ns=(wl.compute_ns if busy else None))
+    tc.synchronize()
+    torch.cuda.synchronize()
+    return tc
+
+
+def check_against_oracle(wl, tc, *, check_bytes=True, tensors=None):
+    r = o.replay_workload(wl)
+    compare_logs(tc.dump_oplog(), oracle_log_array(r))
+    st = tc.cache_stats()
+    assert (st["hits"], st["misses"], st["fails"]) == (r.hits, r.misses, r.fails)
+    assert (st["bytes_h2d"], st["bytes_d2h"], st["bytes_file_read"], st["bytes_file_write"]) == \
+        (r.bytes_h2d, r.bytes_d2h, r.bytes_file_read, r.bytes_file_write)
+    tier, gs, cs = tc.dump_state()
+    assert tier.tolist() == r.cur and gs.tolist() == r.gslot and cs.tolist() == r.cslot
+    assert st["cursor"] == r.cursor and st["iteration"] == r.iteration
+    if check_bytes:
+        pay = lambda t: W.workload_payload(wl, t)
+        for t in (range(wl.n_tensors) if tensors is None else tensors):
+            got = tc.read_tensor(t)
+            want = r.expected_bytes(t, pay)
+            assert np.array_equal(got, want), f"tensor {t} bytes differ"
+    return r

@@ -1,0 +1,103 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/tc.h
+declares, and its host planner (profile, Alg. 1-2, layout, placement) agrees
+with the oracle bit for bit.  No kernel is launched here."""
+
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_14124_amd as T
+import workloads as W
+from oracle import tc_oracle as o
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tc.h")).read()
+    names = set(re.findall(r"\b(tc_[a-z_]+)\s*\(", hdr))
+    assert {"tc_profile_order", "tc_plan_pools", "tc_plan_schedule", "tc_migrate_step", "tc_cache_stats"} <= names
+    L = T.load_library()
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+def _oracle_plan(wl):
+    st, te, rw, _ = wl.events()
+    p = o.profile(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw)
+    plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2)
+    return p, plan, o.place(p, plan)
+
+
+def _check_plan(wl):
+    tc = T.TensorCache.from_workload(wl)
+    p, plan, pl = _oracle_plan(wl)
+    c = tc.classes
+    assert c["bytes"].tolist() == p.class_bytes and c["group"].tolist() == p.class_group
+    assert c["count"].tolist() == p.count and c["used"].tolist() == p.used
+    assert c["step_max"].tolist() == p.step_max
+    assert c["stride"].tolist() == plan.stride
+    assert c["gpu_count"].tolist() == plan.gpu_count and c["cpu_count"].tolist() == plan.cpu_count
+    assert c["hbm_off"].tolist() == plan.gpu_off and c["host_off"].tolist() == plan.cpu_off
+    assert (tc.plan.hbm_total, tc.plan.host_total, tc.plan.file_total) == (plan.gpu_total, plan.cpu_total, pl.file_total)
+    assert (tc.plan.n_rows, tc.plan.n_steps) == (p.n_rows, p.n_steps)
+    q = tc.placement
+    assert q["final_tier"].tolist() == pl.final and q["slot"].tolist() == pl.slot
+    assert q["file_off"].tolist() == pl.file_off and q["cls"].tolist() == p.class_of
+    assert q["first_use"].tolist() == p.first_use
+    tc.close()
+
+
+@pytest.mark.parametrize("index", range(5))
+def test_plan_and_placement_match_the_oracle_on_the_five_configs(index):
+    _check_plan(W.config(index))
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_plan_and_placement_match_the_oracle_on_random_traces(seed):
+    wl = W.random_workload(seed, n_tensors=40, n_steps=50, literal=(seed % 3 == 0),
+                           host_frac=(0.3 if seed % 2 else 1.5))
+    if seed % 5 == 0:                       # a step that names a tensor twice is one row
+        wl.profile[3] = wl.profile[3] + [wl.profile[3][0]]
+    _check_plan(wl)
+
+
+def test_worked_example_placements():
+    for wl, gpu, cpu, nvme in ((W.example_cpu_gpu(), [0, 1, 2], [3, 4, 5], []),
+                               (W.example_cpu_gpu_nvme(), [0, 1, 2], [3, 4, 5], [6])):
+        tc = T.TensorCache.from_workload(wl)
+        f = tc.placement["final_tier"]
+        assert [t for t in range(wl.n_tensors) if f[t] == T.GPU] == gpu
+        assert [t for t in range(wl.n_tensors) if f[t] == T.CPU] == cpu
+        assert [t for t in range(wl.n_tensors) if f[t] == T.NVME] == nvme
+
+
+def test_error_codes_and_call_order():
+    tc = T.TensorCache()
+    with pytest.raises(T.TcError) as e:
+        tc.plan_schedule()
+    assert e.value.code == -2                                  # TC_E_STATE
+    with pytest.raises(T.TcError) as e:
+        tc.profile_order([512, 512], [0, 0], [1, 0], [0, 1], [1, 1])      # steps out of order
+    assert e.value.code == -1
+    with pytest.raises(T.TcError) as e:
+        tc.profile_order([512, 512], [0, 0], [0, 1], [0, 7], [1, 1])      # unknown tensor
+    assert e.value.code == -1
+    with pytest.raises(T.TcError) as e:
+        tc.profile_order([8, 512], [0, 0], [0, 1], [0, 1], [1, 1])        # tensor too small
+    assert e.value.code == -1
+    tc.profile_order([512, 512], [0, 0], [0, 1], [0, 1], [1, 1])
+    tc.n_tensors = 2
+    with pytest.raises(T.TcError) as e:
+        tc.plan_pools(100, (0, 0))                               # working set does not fit
+    assert e.value.code == -3                                   # TC_E_CAPACITY
+    with pytest.raises(T.TcError) as e:
+        tc.plan_pools(4096, (4096, 0), align=100)
+    assert e.value.code == -1
+    tc.plan_pools(4096, (4096, 0))
+    with pytest.raises(T.TcError) as e:
+        tc.migrate_step(0, T.PRE, [0], [1])                      # not bound yet
+    assert e.value.code == -2
+    tc.close()
