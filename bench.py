@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the tensor-cache migration hot path on one MI355X.
+
+A "step" is one replayed training iteration of the workload: every module's
+pre-hook (residency + demand fetch), stand-in compute (stamps of written
+tensors), post-hook (Alg. 3/4 decisions + one migration launch) and the
+end-of-iteration restore.  The workload is configuration 2 of the five
+(1.3B GPT-shaped trace with activation checkpoints, 19.95 GiB of tensors,
+2.99 GiB HBM cache), resident in its tiers (HBM region + pinned host region)
+before the timed region starts.
+
+Prints ONE JSON line: host->HBM migration GB/s (whole replay, zero modelled
+compute), with hit rate, stall per step (second, modelled-compute replay),
+the migration kernel's roofline against the measured host-link peak, the
+pack/unpack kernel's roofline against HBM peak, and the CPU oracle timed on
+this machine's host cores.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def measure_link_peak(torch, nbytes=1 << 30, reps=5):
+    """Best-of-N pinned hipMemcpyAsync H2D, D2H, and both at once (GB/s)."""
+    dev = torch.device("cuda:0")
+    h1 = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    h2 = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    d1 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    d2 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    h1.fill_(1)
+    h2.fill_(2)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def run(fn):
+        best = 0.0
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            best = max(best, nbytes / (time.perf_counter() - t0) / 1e9)
+        return best
+
+    def h2d():
+        with torch.cuda.stream(s1):
+            d1.copy_(h1, non_blocking=True)
+
+    def d2h():
+        with torch.cuda.stream(s2):
+            h2.copy_(d2, non_blocking=True)
+
+    def both():
+        h2d()
+        d2h()
+
+    out = {"h2d": run(h2d), "d2h": run(d2h)}
+    out["duplex_each"] = run(both)            # bytes per direction / time with both running
+    del h1, h2, d1, d2
+    return out
+
+
+def bench_pack(torch, T, total_bytes=4 << 30, reps=5):
+    """Pack kernel on a stress shape: the workload's small-tensor size histogram
+    repeated until ~4 GiB; returns (GB/s algorithmic = 2 x payload / time, ms)."""
+    dev = torch.device("cuda:0")
+    sizes = np.asarray([4096, 4096, 8192, 12288, 16384, 4096, 4096, 32768, 8192, 4096], dtype=np.uint64)
+    n = int(total_bytes // int(sizes.sum())) * len(sizes)
+    nb = np.tile(sizes, n // len(sizes))
+    off = np.zeros(n, dtype=np.uint64)
+    off[1:] = np.cumsum(nb)[:-1]
+    total = int(nb.sum())
+    src = torch.empty(total + 4096, dtype=torch.uint8, device=dev)
+    slab = torch.empty(total, dtype=torch.uint8, device=dev)
+    src.random_(0, 255)
+    # source buffers: the same sizes, in reverse order, so source and slab offsets differ
+    src_off = (total - off - nb).astype(np.uint64)
+    ptrs = torch.from_numpy((src_off + np.uint64(src.data_ptr())).astype(np.int64)).to(dev)
+    nbt = torch.from_numpy(nb.astype(np.int64)).to(dev)
+    offt = torch.from_numpy(off.astype(np.int64)).to(dev)
+    st = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = 1e30
+    for _ in range(reps + 1):
+        e0.record()
+        T.pack(slab.data_ptr(), ptrs.data_ptr(), nbt.data_ptr(), offt.data_ptr(), n, total, st)
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    return 2.0 * total / (best * 1e-3) / 1e9, best, total, n
+
+
+def cpu_baseline(W, seconds_target=15.0):
+    """The oracle, as it stands, in full-bytes mode on a bounded sample of the
+    same workload (fewer layers, same shapes); GB/s of bytes copied into its
+    HBM array over the replay's wall time."""
+    from oracle import tc_oracle as o
+    layers = 6
+    wl = W.config(1, layers=layers)
+    st, te, rw, _ = wl.events()
+    zeros = {}
+
+    def payload(t):                       # contents do not matter for the timing
+        n = int(wl.tensor_bytes[t])
+        if n not in zeros:
+            zeros[n] = np.zeros(n, dtype=np.uint8)
+        return zeros[n]
+
+    r = o.build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
+                wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload)
+    t0 = time.perf_counter()
+    its = 0
+    while True:
+        for steps in wl.iterations:
+            r.run_iteration(steps)
+        its += 1
+        if time.perf_counter() - t0 > seconds_target or its >= 20:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": r.bytes_h2d / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"config 2 shapes at {layers} layers ({wl.total_bytes() / 2**30:.2f} GiB of tensors), "
+                      f"{its} iterations, full-bytes mode, {dt:.1f} s",
+            "us_per_hook_step": dt / (its * wl.n_steps) * 1e6}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--layers", type=int, default=None, help="shallower model of the same shapes (debug)")
+    ap.add_argument("--workgroups", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-stall", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the migration path has no multi-GPU exchange step; run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_14124_amd as T
+    import workloads as W
+
+    T.load_library()                       # fails loudly if the HIP library is not built
+    wl = W.config(1, layers=args.layers)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch()
+    if args.workgroups or args.chunk:
+        tc.set_mover(args.workgroups, args.chunk)
+    tc.fill_payload(0)
+    cs = torch.cuda.Stream()
+    steps = wl.iterations[0]
+
+    for _ in range(args.warmup):
+        tc.replay_iteration_c(steps, cs.cuda_stream)
+    tc.synchronize()
+    torch.cuda.synchronize()
+    s0 = tc.cache_stats()
+    tc.mover_timing(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tc.replay_iteration_c(steps, cs.cuda_stream)
+    tc.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    avg_launch_ns, n_launch = tc.mover_timing(False)
+    s1 = tc.cache_stats()
+    h2d = s1["bytes_h2d"] - s0["bytes_h2d"]
+    d2h = s1["bytes_d2h"] - s0["bytes_d2h"]
+    hits = s1["hits"] - s0["hits"]
+    misses = s1["misses"] - s0["misses"]
+
+    # stall per step with modelled compute (not part of the timed throughput run)
+    stall_ms = None
+    wait_share = None
+    if not args.no_stall:
+        b0 = tc.cache_stats()
+        tc.replay_iteration_c(steps, cs.cuda_stream, busy_ns=wl.compute_ns, measure_stall=True)
+        tc.synchronize()
+        b1 = tc.cache_stats()
+        stall_ms = (b1["stall_ns"] - b0["stall_ns"]) / 1e6 / len(steps)
+        wait_share = (b1["waits_under_30us"] - b0["waits_under_30us"]) / max(1, b1["waits_total"] - b0["waits_total"])
+    tc.close()
+    del tc
+    torch.cuda.empty_cache()
+
+    link = measure_link_peak(torch)
+    pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)
+
+    value = h2d / dt / 1e9
+    launch_s = avg_launch_ns * 1e-9 * n_launch           # time inside migration launches
+    link_bytes_per_launch = (h2d + d2h) / max(1, n_launch)
+    achieved = (h2d + d2h) / launch_s / 1e9 if launch_s else 0.0
+    peak = 2.0 * link["duplex_each"]                      # both directions, measured with pinned hipMemcpyAsync
+    out = {
+        "metric": "host->HBM migration GB/s (% of PCIe peak); GPU cache hit rate; stall ms/step",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": wl.name + ("" if args.layers is None else f"@{args.layers}layers"),
+                   "tensors": wl.n_tensors, "total_GiB": wl.total_bytes() / 2**30,
+                   "hbm_cache_GiB": wl.hbm_bytes / 2**30, "hook_steps_per_iteration": wl.n_steps,
+                   "mode": "zero modelled compute, H2D and D2H concurrent"},
+        "pct_of_pcie_peak_h2d": 100.0 * value / link["h2d"],
+        "pcie_peak_measured_GBps": link,
+        "d2h_GBps": d2h / dt / 1e9,
+        "hit_rate": hits / max(1, hits + misses),
+        "stall_ms_per_step": stall_ms, "share_of_steps_waiting_under_0.03ms": wait_share,
+        "roofline": {"bound": "pcie", "achieved": achieved, "peak": peak, "unit": "GB/s",
+                     "frac": achieved / peak if peak else None, "traffic": None,
+                     "kernel": "tc_mover_kernel", "launches": n_launch, "avg_launch_us": avg_launch_ns / 1e3,
+                     "algorithmic_bytes_per_launch": link_bytes_per_launch,
+                     "note": "host link, both directions; peak = 2 x per-direction rate of concurrent pinned hipMemcpyAsync H2D+D2H"},
+        "roofline_pack": {"bound": "hbm", "achieved": pack_gbs, "peak": 8000.0, "unit": "GB/s",
+                          "frac": pack_gbs / 8000.0, "traffic": None, "kernel": "tc_pack_kernel",
+                          "payload_bytes": pack_bytes, "segments": pack_n, "ms": pack_ms},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(W)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

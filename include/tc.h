@@ -254,6 +254,13 @@ int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
  * stall_ns / waits_* when measure_stall is non-zero (synchronises). */
 int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns, int measure_stall);
 
+/* Replays one whole iteration from C: for every step PRE, tc_emulate_compute,
+ * POST, then tc_end_iteration.  step_ptr: n_steps+1 offsets into ids/rw (host
+ * arrays); busy_ns: per-step modelled compute or NULL.  A convenience for
+ * replays and benchmarks: the same calls, without per-call binding overhead. */
+int tc_replay_iteration(tc_ctx *ctx, const uint32_t *step_ptr, const uint32_t *ids, const uint8_t *rw,
+                        uint32_t n_steps, void *compute_stream, const uint64_t *busy_ns, int measure_stall);
+
 /* Waits for every copy issued so far. */
 int tc_synchronize(tc_ctx *ctx);
 

@@ -88,6 +88,7 @@ def load_library(path: str = LIB_PATH):
         "tc_migrate_step": (i32, [vp, u32, i32, vp, vp, u32, vp, vp]),
         "tc_end_iteration": (i32, [vp, vp]),
         "tc_emulate_compute": (i32, [vp, vp, u64, i32]),
+        "tc_replay_iteration": (i32, [vp, vp, vp, vp, u32, vp, vp, i32]),
         "tc_synchronize": (i32, [vp]),
         "tc_cache_stats": (i32, [vp, C.POINTER(Stats)]),
         "tc_dump_oplog": (i32, [vp, u64, vp, u64, C.POINTER(u64)]),
@@ -238,6 +239,16 @@ class TensorCache:
 
     def synchronize(self):
         self._check(lib().tc_synchronize(self._h))
+
+    def replay_iteration_c(self, steps, compute_stream: int = 0, busy_ns=None, measure_stall: bool = False):
+        """The same sequence as replay_iteration, driven by tc_replay_iteration."""
+        ptr = np.zeros(len(steps) + 1, dtype=np.uint32)
+        ptr[1:] = np.cumsum([len(s) for s in steps])
+        ids = np.asarray([t for s in steps for (t, _a) in s], dtype=np.uint32)
+        rw = np.asarray([a for s in steps for (_t, a) in s], dtype=np.uint8)
+        ns = None if busy_ns is None else np.ascontiguousarray(busy_ns, dtype=np.uint64)
+        self._check(lib().tc_replay_iteration(self._h, _ptr(ptr), _ptr(ids), _ptr(rw), len(steps),
+                                              compute_stream or None, _ptr(ns), int(measure_stall)))
 
     def replay_iteration(self, steps, compute_stream: int = 0, busy_ns=None, measure_stall: bool = False):
         """PRE, stand-in compute, POST for every step, then the end-of-iteration call."""

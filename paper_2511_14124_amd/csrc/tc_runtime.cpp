@@ -680,6 +680,27 @@ extern "C" int tc_emulate_compute(tc_ctx *c, void *compute_stream, uint64_t busy
     return TC_OK;
 }
 
+extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *ids, const uint8_t *rw,
+                                   uint32_t n_steps, void *compute_stream, const uint64_t *busy_ns, int measure_stall)
+{
+    if (!c || !step_ptr || !ids || !rw) return fail(c, TC_E_ARG, "null argument");
+    if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
+    if (n_steps > c->prof.n_steps) return fail(c, TC_E_ARG, "more steps than the profiled iteration");
+    for (uint32_t k = 0; k < n_steps; ++k) {
+        if (step_ptr[k + 1] < step_ptr[k]) return fail(c, TC_E_ARG, "step_ptr must not decrease");
+        const uint32_t n = step_ptr[k + 1] - step_ptr[k];
+        const uint32_t *id = ids + step_ptr[k];
+        const uint8_t *a = rw + step_ptr[k];
+        int rc = tc_migrate_step(c, k, TC_PRE, id, a, n, compute_stream, nullptr);
+        if (rc != TC_OK) return rc;
+        rc = tc_emulate_compute(c, compute_stream, busy_ns ? busy_ns[k] : 0, measure_stall);
+        if (rc != TC_OK) return rc;
+        rc = tc_migrate_step(c, k, TC_POST, id, a, n, compute_stream, nullptr);
+        if (rc != TC_OK) return rc;
+    }
+    return tc_end_iteration(c, compute_stream);
+}
+
 extern "C" int tc_synchronize(tc_ctx *c)
 {
     if (!c) return TC_E_ARG;
