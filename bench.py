@@ -29,7 +29,17 @@ sys.path.insert(0, ROOT)
 
 
 def measure_link_peak(torch, nbytes=1 << 30, reps=5):
-    """Best-of-N pinned hipMemcpyAsync H2D, D2H, and both at once (GB/s)."""
+    """Best-of-N pinned hipMemcpyAsync H2D, D2H, and both at once on two
+    streams (GB/s per direction).  The copies are issued straight through the
+    HIP runtime on streams created here, so each direction has a queue of its
+    own whatever streams the rest of the process holds."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipMemcpyAsync.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+    hip.hipStreamCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+    hip.hipStreamSynchronize.argtypes = [C.c_void_p]
+    hip.hipStreamDestroy.argtypes = [C.c_void_p]
+    H2D, D2H, NONBLOCKING = 1, 2, 1
     dev = torch.device("cuda:0")
     h1 = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
     h2 = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
@@ -37,32 +47,32 @@ def measure_link_peak(torch, nbytes=1 << 30, reps=5):
     d2 = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     h1.fill_(1)
     h2.fill_(2)
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    d2.fill_(3)
+    s1, s2 = C.c_void_p(), C.c_void_p()
+    assert hip.hipStreamCreateWithFlags(C.byref(s1), NONBLOCKING) == 0
+    assert hip.hipStreamCreateWithFlags(C.byref(s2), NONBLOCKING) == 0
 
-    def run(fn):
+    def h2d():
+        assert hip.hipMemcpyAsync(d1.data_ptr(), h1.data_ptr(), nbytes, H2D, s1) == 0
+
+    def d2h():
+        assert hip.hipMemcpyAsync(h2.data_ptr(), d2.data_ptr(), nbytes, D2H, s2) == 0
+
+    def run(*fns):
         best = 0.0
         for _ in range(reps):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            fn()
-            torch.cuda.synchronize()
+            for fn in fns:
+                fn()
+            assert hip.hipStreamSynchronize(s1) == 0 and hip.hipStreamSynchronize(s2) == 0
             best = max(best, nbytes / (time.perf_counter() - t0) / 1e9)
         return best
 
-    def h2d():
-        with torch.cuda.stream(s1):
-            d1.copy_(h1, non_blocking=True)
-
-    def d2h():
-        with torch.cuda.stream(s2):
-            h2.copy_(d2, non_blocking=True)
-
-    def both():
-        h2d()
-        d2h()
-
     out = {"h2d": run(h2d), "d2h": run(d2h)}
-    out["duplex_each"] = run(both)            # bytes per direction / time with both running
+    out["duplex_each"] = run(h2d, d2h)        # bytes per direction / time with both running
+    hip.hipStreamDestroy(s1)
+    hip.hipStreamDestroy(s2)
     del h1, h2, d1, d2
     return out
 
@@ -138,6 +148,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="shallower model of the same shapes (debug)")
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--merge-mib", type=int, default=None, help="bytes merged into one migration launch")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-stall", action="store_true")
     args = ap.parse_args()
@@ -151,11 +162,14 @@ def main():
     import workloads as W
 
     T.load_library()                       # fails loudly if the HIP library is not built
+    link = measure_link_peak(torch)        # first: before this process holds any other stream
     wl = W.config(1, layers=args.layers)
     tc = T.TensorCache.from_workload(wl)
     tc.bind_torch()
     if args.workgroups or args.chunk:
         tc.set_mover(args.workgroups, args.chunk)
+    if args.merge_mib is not None:
+        tc.set_merge_bytes(args.merge_mib << 20)
     tc.fill_payload(0)
     cs = torch.cuda.Stream()
     steps = wl.iterations[0]
@@ -172,7 +186,7 @@ def main():
     tc.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    avg_launch_ns, n_launch = tc.mover_timing(False)
+    tm = tc.mover_timing(False)
     s1 = tc.cache_stats()
     h2d = s1["bytes_h2d"] - s0["bytes_h2d"]
     d2h = s1["bytes_d2h"] - s0["bytes_d2h"]
@@ -193,14 +207,13 @@ def main():
     del tc
     torch.cuda.empty_cache()
 
-    link = measure_link_peak(torch)
     pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)
 
     value = h2d / dt / 1e9
-    launch_s = avg_launch_ns * 1e-9 * n_launch           # time inside migration launches
-    link_bytes_per_launch = (h2d + d2h) / max(1, n_launch)
-    achieved = (h2d + d2h) / launch_s / 1e9 if launch_s else 0.0
-    peak = 2.0 * link["duplex_each"]                      # both directions, measured with pinned hipMemcpyAsync
+    n_launch = tm["kernel_launches"]
+    launch_s = tm["kernel_ns"] * 1e-9                     # time inside migration launches (HIP events)
+    achieved = tm["kernel_bytes"] / launch_s / 1e9 if launch_s else 0.0
+    peak = 2.0 * link["duplex_each"]                      # both directions at once, pinned hipMemcpyAsync
     out = {
         "metric": "host->HBM migration GB/s (% of PCIe peak); GPU cache hit rate; stall ms/step",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -209,17 +222,22 @@ def main():
         "config": {"workload": wl.name + ("" if args.layers is None else f"@{args.layers}layers"),
                    "tensors": wl.n_tensors, "total_GiB": wl.total_bytes() / 2**30,
                    "hbm_cache_GiB": wl.hbm_bytes / 2**30, "hook_steps_per_iteration": wl.n_steps,
-                   "mode": "zero modelled compute, H2D and D2H concurrent"},
+                   "mode": "zero modelled compute; every prefetch is paired with an eviction, so H2D and D2H run concurrently"},
         "pct_of_pcie_peak_h2d": 100.0 * value / link["h2d"],
+        "pct_of_pcie_duplex_peak_h2d": 100.0 * value / link["duplex_each"],
         "pcie_peak_measured_GBps": link,
         "d2h_GBps": d2h / dt / 1e9,
         "hit_rate": hits / max(1, hits + misses),
         "stall_ms_per_step": stall_ms, "share_of_steps_waiting_under_0.03ms": wait_share,
         "roofline": {"bound": "pcie", "achieved": achieved, "peak": peak, "unit": "GB/s",
                      "frac": achieved / peak if peak else None, "traffic": None,
-                     "kernel": "tc_mover_kernel", "launches": n_launch, "avg_launch_us": avg_launch_ns / 1e3,
-                     "algorithmic_bytes_per_launch": link_bytes_per_launch,
-                     "note": "host link, both directions; peak = 2 x per-direction rate of concurrent pinned hipMemcpyAsync H2D+D2H"},
+                     "kernel": "tc_mover_kernel", "launches": n_launch,
+                     "avg_launch_us": tm["kernel_ns"] / 1e3 / max(1, n_launch),
+                     "algorithmic_bytes_per_launch": tm["kernel_bytes"] / max(1, n_launch),
+                     "peak_published": 128.0,
+                     "note": "bound by the host link, both directions in use; achieved = bytes crossing the link "
+                             "(H2D + D2H) / time inside launches; peak = 2 x per-direction rate of concurrent "
+                             "pinned hipMemcpyAsync H2D + D2H measured in this run; peak_published = PCIe 5.0 x16 raw"},
         "roofline_pack": {"bound": "hbm", "achieved": pack_gbs, "peak": 8000.0, "unit": "GB/s",
                           "frac": pack_gbs / 8000.0, "traffic": None, "kernel": "tc_pack_kernel",
                           "payload_bytes": pack_bytes, "segments": pack_n, "ms": pack_ms},

@@ -160,6 +160,7 @@ typedef struct {
     uint64_t bytes_file_read, bytes_file_write;
     uint64_t mover_launches;         /* migration-kernel launches */
     uint64_t mover_units;            /* exchange units those launches carried */
+    uint64_t dma_copies;             /* DMA-engine copies (large tensors) */
     uint64_t decide_launches;        /* decision-kernel launches */
     uint64_t stall_ns;               /* time the compute stream was held back by migration (tc_emulate_compute) */
     uint64_t waits_under_30us, waits_total;   /* share of steps waiting < 0.03 ms (Sec. 4.2.2) */
@@ -254,10 +255,17 @@ int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
  * stall_ns / waits_* when measure_stall is non-zero (synchronises). */
 int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns, int measure_stall);
 
-/* Replays one whole iteration from C: for every step PRE, tc_emulate_compute,
- * POST, then tc_end_iteration.  step_ptr: n_steps+1 offsets into ids/rw (host
- * arrays); busy_ns: per-step modelled compute or NULL.  A convenience for
- * replays and benchmarks: the same calls, without per-call binding overhead. */
+/* Replays one whole iteration whose accesses are known up front: for every
+ * step the pre-hook call, tc_emulate_compute, the post-hook call, then
+ * tc_end_iteration.  step_ptr: n_steps+1 offsets into ids/rw, starting at 0
+ * (host arrays); busy_ns: per-step modelled compute or NULL.  Decisions, op
+ * log, statistics and bytes are those of the same sequence of
+ * tc_migrate_step calls; the difference is that the decision kernel takes a
+ * window of steps per launch (tc_set_replay_window) instead of one hook call,
+ * which the scheduler allows because its decisions depend on the access
+ * order and the tables only, never on when a copy finishes.  After an error
+ * the context must be destroyed (the device tables may be ahead of the
+ * copies issued). */
 int tc_replay_iteration(tc_ctx *ctx, const uint32_t *step_ptr, const uint32_t *ids, const uint8_t *rw,
                         uint32_t n_steps, void *compute_stream, const uint64_t *busy_ns, int measure_stall);
 
@@ -278,10 +286,36 @@ int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_
  * work chunk (0 = default; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
 
-/* Average duration in ns of the migration-kernel launches since the last
- * call, measured with HIP events on the migration stream; *n = launches
- * measured.  Only launches made while timing is enabled are counted. */
-int tc_mover_timing(tc_ctx *ctx, int enable, double *avg_ns, uint64_t *n);
+/* Hook calls are merged into one migration launch until `bytes` bytes are
+ * prepared (or a prepared buffer is needed, or the file tier is involved).
+ * 0 = one launch per hook call.  Default 256 MiB. */
+int tc_set_merge_bytes(tc_ctx *ctx, uint64_t bytes);
+
+/* Steps decided per decision-kernel launch by tc_replay_iteration, 1 .. 256
+ * (default 64).  Each launch the host waits for interrupts a running
+ * migration launch for some microseconds. */
+int tc_set_replay_window(tc_ctx *ctx, uint32_t steps);
+
+/* Tensors of at least `bytes` bytes move as DMA-engine copies (hipMemcpyAsync
+ * on two side streams, one per direction), smaller ones in the migration
+ * kernel's batched launch.  0 (default) = everything in the kernel. */
+int tc_set_dma_threshold(tc_ctx *ctx, uint64_t bytes);
+
+/* Time spent inside migration work since the last call, measured with HIP
+ * events on the stream each piece ran on.  Only work issued while timing is
+ * enabled is counted. */
+typedef struct {
+    double   kernel_ns;              /* sum of migration-kernel launch durations */
+    uint64_t kernel_launches;
+    uint64_t kernel_bytes;           /* bytes those launches moved (both directions, incl. HBM staging copies) */
+    double   h2d_ns;                 /* sum of host->HBM DMA copy durations */
+    uint64_t h2d_copies;
+    uint64_t h2d_bytes;
+    double   d2h_ns;                 /* sum of HBM->host DMA copy durations */
+    uint64_t d2h_copies;
+    uint64_t d2h_bytes;
+} tc_timing;
+int tc_mover_timing(tc_ctx *ctx, int enable, tc_timing *out);
 
 /* ---- stand-alone kernels ---- */
 
@@ -297,6 +331,15 @@ typedef struct {
  * stream. */
 int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream,
                   uint32_t workgroups, uint32_t chunk_bytes);
+
+/* Batched exchange: unit i copies out[i] and in[i] (same byte count, either
+ * may have bytes == 0 to leave that half out) with the ordering guarantee of
+ * the migration kernel: every 16-byte piece of both sources is read before
+ * either destination piece is written, so out[i].src may equal in[i].dst (a
+ * tensor leaves a buffer while another arrives) and out[i].dst may equal
+ * in[i].src (a swap).  Pointers 16-byte aligned.  Asynchronous on stream. */
+int tc_exchange_batch(const tc_segment *out, const tc_segment *in, uint32_t n, void *stream,
+                      uint32_t workgroups, uint32_t chunk_bytes);
 
 /* Pack: gathers n small tensors (device pointers, any alignment) into one
  * contiguous device slab, segment i at slab_off[i]; unpack is the reverse.

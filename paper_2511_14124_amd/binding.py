@@ -48,9 +48,16 @@ class Stats(C.Structure):
     _fields_ = [("hits", C.c_uint64), ("misses", C.c_uint64), ("fails", C.c_uint64), ("n_ops", C.c_uint64 * 8),
                 ("bytes_h2d", C.c_uint64), ("bytes_d2h", C.c_uint64),
                 ("bytes_file_read", C.c_uint64), ("bytes_file_write", C.c_uint64),
-                ("mover_launches", C.c_uint64), ("mover_units", C.c_uint64), ("decide_launches", C.c_uint64),
+                ("mover_launches", C.c_uint64), ("mover_units", C.c_uint64), ("dma_copies", C.c_uint64),
+                ("decide_launches", C.c_uint64),
                 ("stall_ns", C.c_uint64), ("waits_under_30us", C.c_uint64), ("waits_total", C.c_uint64),
                 ("cursor", C.c_uint32), ("iteration", C.c_uint32)]
+
+
+class Timing(C.Structure):
+    _fields_ = [("kernel_ns", C.c_double), ("kernel_launches", C.c_uint64), ("kernel_bytes", C.c_uint64),
+                ("h2d_ns", C.c_double), ("h2d_copies", C.c_uint64), ("h2d_bytes", C.c_uint64),
+                ("d2h_ns", C.c_double), ("d2h_copies", C.c_uint64), ("d2h_bytes", C.c_uint64)]
 
 
 STATS_FIELDS = [f[0] for f in Stats._fields_]
@@ -94,8 +101,12 @@ def load_library(path: str = LIB_PATH):
         "tc_dump_oplog": (i32, [vp, u64, vp, u64, C.POINTER(u64)]),
         "tc_dump_state": (i32, [vp, vp, vp, vp]),
         "tc_set_mover": (i32, [vp, u32, u32]),
-        "tc_mover_timing": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(u64)]),
+        "tc_mover_timing": (i32, [vp, i32, C.POINTER(Timing)]),
+        "tc_set_dma_threshold": (i32, [vp, u64]),
+        "tc_set_merge_bytes": (i32, [vp, u64]),
+        "tc_set_replay_window": (i32, [vp, u32]),
         "tc_copy_batch": (i32, [vp, u32, vp, u32, u32]),
+        "tc_exchange_batch": (i32, [vp, vp, u32, vp, u32, u32]),
         "tc_pack": (i32, [vp, vp, vp, vp, u32, u64, vp]),
         "tc_unpack": (i32, [vp, vp, vp, vp, u32, u64, vp]),
     }
@@ -288,11 +299,19 @@ class TensorCache:
     def set_mover(self, workgroups: int = 0, chunk_bytes: int = 0):
         self._check(lib().tc_set_mover(self._h, workgroups, chunk_bytes))
 
-    def mover_timing(self, enable: bool):
-        avg = C.c_double()
-        n = C.c_uint64()
-        self._check(lib().tc_mover_timing(self._h, int(enable), C.byref(avg), C.byref(n)))
-        return avg.value, n.value
+    def mover_timing(self, enable: bool) -> dict:
+        t = Timing()
+        self._check(lib().tc_mover_timing(self._h, int(enable), C.byref(t)))
+        return {f[0]: getattr(t, f[0]) for f in Timing._fields_}
+
+    def set_merge_bytes(self, nbytes: int):
+        self._check(lib().tc_set_merge_bytes(self._h, int(nbytes)))
+
+    def set_replay_window(self, steps: int):
+        self._check(lib().tc_set_replay_window(self._h, int(steps)))
+
+    def set_dma_threshold(self, nbytes: int):
+        self._check(lib().tc_set_dma_threshold(self._h, int(nbytes)))
 
     # -- convenience: a workload object from the workloads package ----------------
     @classmethod
@@ -311,6 +330,19 @@ def copy_batch(src_ptrs, dst_ptrs, nbytes, stream: int = 0, workgroups: int = 0,
     segs["dst"] = dst_ptrs
     segs["bytes"] = nbytes
     rc = lib().tc_copy_batch(_ptr(segs), len(segs), stream or None, workgroups, chunk_bytes)
+    if rc:
+        raise TcError(rc)
+
+
+def exchange_batch(out_src, out_dst, in_src, in_dst, nbytes, stream: int = 0, workgroups: int = 0,
+                   chunk_bytes: int = 0):
+    o = np.zeros(len(nbytes), dtype=SEGMENT)
+    i = np.zeros(len(nbytes), dtype=SEGMENT)
+    o["src"], o["dst"], o["bytes"] = out_src, out_dst, nbytes
+    i["src"], i["dst"], i["bytes"] = in_src, in_dst, nbytes
+    o["bytes"][np.asarray(out_src) == 0] = 0
+    i["bytes"][np.asarray(in_src) == 0] = 0
+    rc = lib().tc_exchange_batch(_ptr(o), _ptr(i), len(o), stream or None, workgroups, chunk_bytes)
     if rc:
         raise TcError(rc)
 

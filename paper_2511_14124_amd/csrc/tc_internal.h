@@ -79,18 +79,28 @@ struct TcOpRec {
     uint8_t op, phase, src_tier, dst_tier;
 };
 
-// header of the block the decision kernel writes (pinned host memory)
+// what the decision kernel reports for one hook call (pinned host memory);
+// the call's op records are written to a separate array
 struct TcDecideOut {
     uint32_t n_ops, hits, misses, fails;
     uint32_t cursor, iteration, overflow, pad_;
     uint32_t slots[TC_MAX_STEP_TENSORS];
-    // TcOpRec ops[cap] follow
 };
 
 struct TcStepArgs {
     uint32_t ids[TC_MAX_STEP_TENSORS];
     uint8_t rw[TC_MAX_STEP_TENSORS];
     uint32_t n, step, phase, cap;
+};
+
+// a window of steps decided by one launch (lists in device memory)
+#define TC_WINDOW_MAX 256
+struct TcWindowArgs {
+    const uint32_t *step_ptr;                   // n_steps + 1 offsets into ids / rw
+    const uint32_t *ids;
+    const uint8_t *rw;
+    uint32_t first, count;                      // steps first .. first+count-1
+    uint32_t cap;                               // op records the window may write
 };
 
 // ---------------------------------------------------------------------------
@@ -109,7 +119,7 @@ struct TcUnit {
     uint64_t chunk0;                            // first work chunk of this unit in the launch
 };
 
-#define TC_MOVER_MAX_UNITS 24
+#define TC_MOVER_MAX_UNITS 48
 struct TcMoverArgs {
     TcUnit u[TC_MOVER_MAX_UNITS];
     uint64_t n_chunks;
@@ -126,7 +136,9 @@ struct TcStampArgs {
 };
 
 // launchers (tc_kernels.hip)
-hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, hipStream_t s);
+hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, TcOpRec *ops, hipStream_t s);
+hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, TcDecideOut *out, TcOpRec *ops,
+                                   hipStream_t s);
 hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_t s);
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s);
 hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t seed, hipStream_t s);

@@ -376,15 +376,14 @@ __device__ void decide_end(DecideCtx &c)
     T.scalars[2] = T.scalars[2] + 1;
 }
 
-__global__ __launch_bounds__(WAVE) void tc_decide_kernel(TcDevTables T, TcStepArgs a, TcDecideOut *out)
+// one hook call: the call id advances, the phase's routine runs, the record is filled
+__device__ void decide_call(DecideCtx &c, const TcStepArgs &a, TcDecideOut *out, TcOpRec *ops, uint32_t cap)
 {
-    DecideCtx c;
-    c.T = T;
+    const TcDevTables &T = c.T;
     c.out = out;
-    c.ops = (TcOpRec *)(out + 1);
-    c.cap = a.cap;
+    c.ops = ops;
+    c.cap = cap;
     c.n_ops = 0;
-    c.lane = threadIdx.x;
     c.step = a.step;
     c.phase = a.phase;
     c.call = T.scalars[1] + 1;
@@ -397,14 +396,63 @@ __global__ __launch_bounds__(WAVE) void tc_decide_kernel(TcDevTables T, TcStepAr
     if (c.lane == 0) {
         out->cursor = T.scalars[0];
         out->iteration = T.scalars[2];
-        out->overflow = c.n_ops > c.cap ? 1u : 0u;
-        out->n_ops = c.n_ops < c.cap ? c.n_ops : c.cap;
+        out->overflow = c.n_ops > cap ? 1u : 0u;
+        out->n_ops = c.n_ops < cap ? c.n_ops : cap;
     }
 }
 
-hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, hipStream_t s)
+__global__ __launch_bounds__(WAVE) void tc_decide_kernel(TcDevTables T, TcStepArgs a, TcDecideOut *out, TcOpRec *ops)
 {
-    hipLaunchKernelGGL(tc_decide_kernel, dim3(1), dim3(WAVE), 0, s, T, a, out);
+    DecideCtx c;
+    c.T = T;
+    c.lane = threadIdx.x;
+    decide_call(c, a, out, ops, a.cap);
+}
+
+// A window of steps in one launch: for each step the pre-hook call, then the
+// post-hook call, exactly the sequence the per-hook kernel would run.  The
+// decisions depend on the trace and the tables only, never on when a copy
+// finishes, so deciding a window ahead of the copies changes nothing but the
+// number of launches.  Record 2*i is step first+i's pre-hook call, record
+// 2*i+1 its post-hook call; their op records follow each other in `ops`.
+__global__ __launch_bounds__(WAVE) void tc_decide_window_kernel(TcDevTables T, TcWindowArgs w, TcDecideOut *out,
+                                                                TcOpRec *ops)
+{
+    DecideCtx c;
+    c.T = T;
+    c.lane = threadIdx.x;
+    uint32_t used = 0;
+    for (uint32_t k = 0; k < w.count; ++k) {
+        TcStepArgs a;
+        const uint32_t b = w.step_ptr[w.first + k];
+        uint32_t n = w.step_ptr[w.first + k + 1] - b;
+        n = n < TC_MAX_STEP_TENSORS ? n : TC_MAX_STEP_TENSORS;
+        for (uint32_t i = 0; i < TC_MAX_STEP_TENSORS; ++i) {
+            a.ids[i] = i < n ? w.ids[b + i] : 0;
+            a.rw[i] = i < n ? w.rw[b + i] : 0;
+        }
+        a.n = n;
+        a.step = w.first + k;
+        for (uint32_t ph = TC_PRE; ph <= TC_POST; ++ph) {
+            a.phase = ph;
+            TcDecideOut *rec = out + 2 * k + ph;
+            decide_call(c, a, rec, ops + used, w.cap - used);
+            used += c.n_ops < w.cap - used ? c.n_ops : w.cap - used;
+        }
+    }
+}
+
+hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, TcOpRec *ops, hipStream_t s)
+{
+    hipLaunchKernelGGL(tc_decide_kernel, dim3(1), dim3(WAVE), 0, s, T, a, out, ops);
+    return hipGetLastError();
+}
+
+hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, TcDecideOut *out, TcOpRec *ops,
+                                   hipStream_t s)
+{
+    if (w.count == 0 || w.count > TC_WINDOW_MAX) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tc_decide_window_kernel, dim3(1), dim3(WAVE), 0, s, T, w, out, ops);
     return hipGetLastError();
 }
 
@@ -510,18 +558,21 @@ hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_
 
 // ===========================================================================
 // Stand-in for a module's kernels in a replay: stamp written tensors, then spin.
+// One 32-lane group per list entry: lanes 0-15 XOR the head bytes, lanes 16-31
+// the tail bytes.  When head and tail overlap (tensors under 32 bytes) lane 0
+// applies both in order.
 // ===========================================================================
-__global__ __launch_bounds__(WAVE) void tc_stamp_kernel(TcStampArgs a)
+__global__ __launch_bounds__(32 * TC_MAX_STEP_TENSORS) void tc_stamp_kernel(TcStampArgs a)
 {
-    const uint32_t i = threadIdx.x;
+    const uint32_t i = threadIdx.x >> 5, j = threadIdx.x & 31;
     // a list may name a tensor more than once; its stamps are identical and XOR
     // cancels in pairs, so the first occurrence applies it iff the count is odd
     bool apply = false;
     if (i < a.n && a.ptr[i]) {
         uint32_t same = 0, earlier = 0;
-        for (uint32_t j = 0; j < a.n; ++j) {
-            same += (a.ptr[j] == a.ptr[i]);
-            earlier += (j < i && a.ptr[j] == a.ptr[i]);
+        for (uint32_t k = 0; k < a.n; ++k) {
+            same += (a.ptr[k] == a.ptr[i]);
+            earlier += (k < i && a.ptr[k] == a.ptr[i]);
         }
         apply = earlier == 0 && (same & 1);
     }
@@ -529,11 +580,16 @@ __global__ __launch_bounds__(WAVE) void tc_stamp_kernel(TcStampArgs a)
         const uint32_t w[4] = {0x10CAC4E5u, a.iteration, a.step, a.tensor[i]};
         uint8_t *p = a.ptr[i];
         const uint64_t n = a.bytes[i];
-        // head then tail, byte by byte: the two ranges may overlap for tiny tensors
-        for (uint32_t b = 0; b < 16; ++b) p[b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
-        for (uint32_t b = 0; b < 16; ++b) p[n - 16 + b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+        if (n >= 32) {
+            const uint32_t b = j & 15;
+            uint8_t *q = j < 16 ? p + b : p + n - 16 + b;
+            *q ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+        } else if (j == 0) {
+            for (uint32_t b = 0; b < 16; ++b) p[b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+            for (uint32_t b = 0; b < 16; ++b) p[n - 16 + b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+        }
     }
-    if (a.busy_ns && i == 0) {
+    if (a.busy_ns && threadIdx.x == 0) {
         // wall_clock64 counts at 100 MHz; the loop ends once busy_ns have passed
         const uint64_t t0 = wall_clock64();
         const uint64_t ticks = a.busy_ns / 10;
@@ -543,7 +599,7 @@ __global__ __launch_bounds__(WAVE) void tc_stamp_kernel(TcStampArgs a)
 
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(tc_stamp_kernel, dim3(1), dim3(WAVE), 0, s, a);
+    hipLaunchKernelGGL(tc_stamp_kernel, dim3(1), dim3(32 * TC_MAX_STEP_TENSORS), 0, s, a);
     return hipGetLastError();
 }
 
@@ -591,77 +647,133 @@ hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t s
 // Pack / unpack of small tensors: HBM buffers <-> one contiguous HBM slab.
 //
 // Bound by HBM bandwidth: every payload byte is read once and written once.
-// A workgroup owns one 16 KiB tile of the slab.  The tile's bytes come from
-// (pack) or go to (unpack) one or more tensors whose addresses are aligned
-// differently from the slab's, so the tile is staged in LDS: the global side
-// that is 16-byte aligned for its own pointer moves as 128-bit requests into
-// LDS, and the other side leaves LDS as 128-bit requests aligned for *its*
-// pointer; only the few bytes at segment edges move bytewise.
+// The slab is cut into 16 KiB tiles; a workgroup owns a run of consecutive
+// tiles, finds the first segment of its run by bisection once and from then on
+// walks the segment table forwards, so the table costs one dependent chain per
+// workgroup and not one per tile.  A piece of a segment inside a tile moves in
+// one of two ways:
+//   - its tensor address and its slab address agree modulo 16: both sides are
+//     128-bit aligned at the same indices, and the piece goes register to
+//     register, four requests per lane in flight;
+//   - they disagree: the piece is staged in LDS, which holds the tile as the
+//     slab sees it.  The global side that is aligned for its own pointer moves
+//     as 128-bit requests, the LDS side absorbs the shift, and the other global
+//     side leaves as 128-bit requests aligned for *its* pointer; only the few
+//     bytes at piece edges move bytewise.
+// Bytes of the slab (pack) or of a tensor (unpack) that no piece covers are
+// never written.  Segments must be sorted by slab offset and must not overlap.
 // ===========================================================================
 #define PACK_TILE 16384
 #define PACK_THREADS 256
 
+// dst and src agree modulo 16; any address space mix (global/LDS)
+__device__ __forceinline__ void pack_copy_aligned(uint8_t *dst, const uint8_t *src, uint32_t len, uint32_t tid)
+{
+    uint32_t head = (uint32_t)((16 - ((uintptr_t)dst & 15)) & 15);
+    head = head < len ? head : len;
+    if (tid < head) dst[tid] = src[tid];
+    const uint32_t body = (len - head) & ~15u;
+    const uint8_t *s = src + head;
+    uint8_t *d = dst + head;
+    uint32_t i = tid * 16;
+    for (; i + 3 * PACK_THREADS * 16 < body; i += 4 * PACK_THREADS * 16) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = *(const uint4 *)(s + i + k * PACK_THREADS * 16);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) *(uint4 *)(d + i + k * PACK_THREADS * 16) = v[k];
+    }
+    for (; i < body; i += PACK_THREADS * 16) *(uint4 *)(d + i) = *(const uint4 *)(s + i);
+    for (uint32_t j = head + body + tid; j < len; j += PACK_THREADS) dst[j] = src[j];
+}
+
+// src is 128-bit aligned after `head` bytes; dst (LDS) may sit at any shift
+__device__ __forceinline__ void pack_global_to_lds(uint8_t *l, const uint8_t *g, uint32_t len, uint32_t tid)
+{
+    uint32_t head = (uint32_t)((16 - ((uintptr_t)g & 15)) & 15);
+    head = head < len ? head : len;
+    if (tid < head) l[tid] = g[tid];
+    const uint32_t body = (len - head) & ~15u;
+    for (uint32_t i = tid * 16; i < body; i += PACK_THREADS * 16) {
+        const uint4 v = *(const uint4 *)(g + head + i);
+        __builtin_memcpy(l + head + i, &v, 16);
+    }
+    for (uint32_t j = head + body + tid; j < len; j += PACK_THREADS) l[j] = g[j];
+}
+
+// dst is 128-bit aligned after `head` bytes; src (LDS) may sit at any shift
+__device__ __forceinline__ void pack_lds_to_global(uint8_t *g, const uint8_t *l, uint32_t len, uint32_t tid)
+{
+    uint32_t head = (uint32_t)((16 - ((uintptr_t)g & 15)) & 15);
+    head = head < len ? head : len;
+    if (tid < head) g[tid] = l[tid];
+    const uint32_t body = (len - head) & ~15u;
+    for (uint32_t i = tid * 16; i < body; i += PACK_THREADS * 16) {
+        uint4 v;
+        __builtin_memcpy(&v, l + head + i, 16);
+        *(uint4 *)(g + head + i) = v;
+    }
+    for (uint32_t j = head + body + tid; j < len; j += PACK_THREADS) g[j] = l[j];
+}
+
 __global__ __launch_bounds__(PACK_THREADS) void tc_pack_kernel(
     uint8_t *slab, uint8_t *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
-    uint32_t n, uint64_t total, int unpack)
+    uint32_t n, uint64_t total, int unpack, uint32_t tiles_per_wg)
 {
     __shared__ __attribute__((aligned(16))) uint8_t tile[PACK_TILE];
     const uint32_t tid = threadIdx.x;
-    for (uint64_t t0 = (uint64_t)blockIdx.x * PACK_TILE; t0 < total; t0 += (uint64_t)gridDim.x * PACK_TILE) {
-        const uint64_t t1 = t0 + PACK_TILE < total ? t0 + PACK_TILE : total;
-        const uint32_t tlen = (uint32_t)(t1 - t0);
-        // first segment that reaches into the tile: last i with slab_off[i] <= t0
+    const uint64_t n_tiles = (total + PACK_TILE - 1) / PACK_TILE;
+    const uint64_t tb = (uint64_t)blockIdx.x * tiles_per_wg;
+    const uint64_t te = tb + tiles_per_wg < n_tiles ? tb + tiles_per_wg : n_tiles;
+    if (tb >= te) return;
+    // first segment that can reach into tile tb: the last i with slab_off[i] <= tb*TILE
+    uint32_t seg = 0;
+    {
+        const uint64_t t0 = tb * PACK_TILE;
         uint32_t lo = 0, hi = n;
         while (hi - lo > 1) {
-            uint32_t m = (lo + hi) >> 1;
+            const uint32_t m = (lo + hi) >> 1;
             if (slab_off[m] <= t0) lo = m; else hi = m;
         }
-        if (unpack) {
-            // slab -> LDS, 128-bit and aligned (slab and tile start are 16-byte aligned)
-            for (uint32_t i = tid * 16; i < (tlen & ~15u); i += PACK_THREADS * 16)
-                *(uint4 *)(tile + i) = *(const uint4 *)(slab + t0 + i);
-            for (uint32_t i = (tlen & ~15u) + tid; i < tlen; i += PACK_THREADS) tile[i] = slab[t0 + i];
-            __syncthreads();
-        }
-        for (uint32_t sg = lo; sg < n && slab_off[sg] < t1; ++sg) {
+        seg = lo;
+    }
+    for (uint64_t ti = tb; ti < te; ++ti) {
+        const uint64_t t0 = ti * PACK_TILE;
+        const uint64_t t1 = t0 + PACK_TILE < total ? t0 + PACK_TILE : total;
+        while (seg < n && slab_off[seg] + bytes[seg] <= t0) ++seg;
+        bool staged = false;
+        for (uint32_t sg = seg; sg < n && slab_off[sg] < t1; ++sg) {
             const uint64_t so = slab_off[sg], sb = bytes[sg];
-            const uint64_t b = so > t0 ? so : t0;               // overlap of segment and tile, slab coords
+            const uint64_t b = so > t0 ? so : t0;               // overlap of segment and tile, slab coordinates
             const uint64_t e = so + sb < t1 ? so + sb : t1;
             if (e <= b) continue;
-            uint8_t *g = ptrs[sg] + (b - so);                   // global address of the first byte
-            uint8_t *l = tile + (b - t0);
+            uint8_t *g = ptrs[sg] + (b - so);
+            uint8_t *s = slab + b;
             const uint32_t len = (uint32_t)(e - b);
-            // head bytes until the GLOBAL pointer is 16-byte aligned
-            uint32_t head = (uint32_t)((16 - ((uintptr_t)g & 15)) & 15);
-            if (head > len) head = len;
-            const uint32_t body = (len - head) & ~15u;
-            const uint32_t lmis = (uint32_t)((uintptr_t)(l + head) & 15);
-            if (unpack) {
-                if (tid < head) g[tid] = l[tid];
-                for (uint32_t i = tid * 16; i < body; i += PACK_THREADS * 16) {
-                    uint4 v;
-                    if (lmis == 0) v = *(const uint4 *)(l + head + i);
-                    else __builtin_memcpy(&v, l + head + i, 16);  // LDS side may be misaligned
-                    *(uint4 *)(g + head + i) = v;
-                }
-                for (uint32_t i = head + body + tid; i < len; i += PACK_THREADS) g[i] = l[i];
+            if ((((uintptr_t)g ^ (uintptr_t)s) & 15) == 0) {
+                if (unpack) pack_copy_aligned(g, s, len, tid); else pack_copy_aligned(s, g, len, tid);
             } else {
-                if (tid < head) l[tid] = g[tid];
-                for (uint32_t i = tid * 16; i < body; i += PACK_THREADS * 16) {
-                    uint4 v = *(const uint4 *)(g + head + i);
-                    if (lmis == 0) *(uint4 *)(l + head + i) = v;
-                    else __builtin_memcpy(l + head + i, &v, 16);
-                }
-                for (uint32_t i = head + body + tid; i < len; i += PACK_THREADS) l[i] = g[i];
+                staged = true;
+                uint8_t *l = tile + (b - t0);                   // s and l agree modulo 16
+                if (unpack) pack_copy_aligned(l, s, len, tid); else pack_global_to_lds(l, g, len, tid);
             }
         }
-        if (!unpack) {
+        if (staged) {                                           // the same for every lane of the workgroup
             __syncthreads();
-            for (uint32_t i = tid * 16; i < (tlen & ~15u); i += PACK_THREADS * 16)
-                *(uint4 *)(slab + t0 + i) = *(const uint4 *)(tile + i);
-            for (uint32_t i = (tlen & ~15u) + tid; i < tlen; i += PACK_THREADS) slab[t0 + i] = tile[i];
+            for (uint32_t sg = seg; sg < n && slab_off[sg] < t1; ++sg) {
+                const uint64_t so = slab_off[sg], sb = bytes[sg];
+                const uint64_t b = so > t0 ? so : t0;
+                const uint64_t e = so + sb < t1 ? so + sb : t1;
+                if (e <= b) continue;
+                uint8_t *g = ptrs[sg] + (b - so);
+                uint8_t *s = slab + b;
+                if ((((uintptr_t)g ^ (uintptr_t)s) & 15) == 0) continue;
+                const uint32_t len = (uint32_t)(e - b);
+                const uint8_t *l = tile + (b - t0);
+                if (unpack) pack_lds_to_global(g, l, len, tid); else pack_copy_aligned(s, l, len, tid);
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
@@ -669,9 +781,11 @@ hipError_t tc_launch_pack(void *slab, const void *const *ptrs, const uint64_t *b
                           const uint64_t *slab_off, uint32_t n, uint64_t total, int unpack, hipStream_t s)
 {
     if (n == 0 || total == 0) return hipSuccess;
-    uint64_t tiles = (total + PACK_TILE - 1) / PACK_TILE;
-    uint32_t blocks = (uint32_t)(tiles < 8192 ? tiles : 8192);
+    const uint64_t tiles = (total + PACK_TILE - 1) / PACK_TILE;
+    const uint64_t want = 4096;                                 // workgroups: 16 per compute unit
+    const uint32_t per = (uint32_t)((tiles + want - 1) / want);
+    const uint32_t blocks = (uint32_t)((tiles + per - 1) / per);
     hipLaunchKernelGGL(tc_pack_kernel, dim3(blocks), dim3(PACK_THREADS), 0, s, (uint8_t *)slab,
-                       (uint8_t *const *)ptrs, bytes, slab_off, n, total, unpack);
+                       (uint8_t *const *)ptrs, bytes, slab_off, n, total, unpack, per);
     return hipGetLastError();
 }

@@ -4,20 +4,49 @@
 #include "tc_internal.h"
 
 #include <errno.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 #include <unistd.h>
 
 #include <algorithm>
 #include <chrono>
 
+#include <deque>
+
 namespace {
 
-const uint32_t EVENT_RING = 256;
+// Streams the copies run on.  K: the caller's migration stream, used by the
+// migration kernel (small tensors, staging copies inside HBM).  H and D: two
+// streams of the library's own, one per direction, that carry the large
+// tensors as DMA-engine copies (hipMemcpyAsync).
+enum { S_K = 0, S_H = 1, S_D = 2, N_STREAMS = 3 };
 
-struct Pending {            // file write that must wait for a migration launch
-    uint64_t launch;
+const uint32_t OP_RING = 1024;          // events kept for the most recent copy operations
+
+struct Pending {            // file write that must wait for a copy operation
+    uint64_t op;
     const uint8_t *src;
     uint64_t bytes, file_off;
+};
+
+struct BounceBlock {        // live piece of the HBM bounce ring
+    uint64_t off, size, op; // op: the copy that reads it last (0 = not issued yet)
+};
+
+struct PUnit {              // one exchange unit being prepared
+    TcUnit u{};
+    int64_t gpu_y = -1;     // flat index of the GPU buffer
+    int64_t cpu_out = -1;   // flat index of the host buffer the outgoing tensor goes to
+    int64_t cpu_in = -1;    // flat index of the host buffer the incoming tensor comes from
+    bool out_staging = false, in_staging = false;
+    uint32_t out_tensor = 0;
+};
+
+struct Timed {              // event pair around one timed operation
+    hipEvent_t t0, t1;
+    int kind;               // S_K kernel launch, S_H / S_D copy
+    uint64_t bytes;
 };
 
 } // namespace
@@ -34,34 +63,52 @@ struct tc_ctx {
     uint8_t *hbm = nullptr, *pinned = nullptr, *staging = nullptr;
     uint64_t hbm_bytes = 0, pinned_bytes = 0, staging_bytes = 0;
     int fd = -1;
-    hipStream_t mstream = nullptr;      // migration stream (caller's)
+    hipStream_t streams[N_STREAMS]{};   // [S_K] is the caller's migration stream
     hipStream_t dstream = nullptr;      // decision stream (ours)
     bool null_mover = false;
 
     // device tables
     uint32_t *dev_block = nullptr;      // one allocation holding every table
     TcDevTables T{};
-    TcDecideOut *dout = nullptr;        // pinned result block of the decision kernel
-    uint32_t dout_cap = 0;
+    TcDecideOut *dout = nullptr;        // pinned: one record per hook call of a window, then the op records
+    TcOpRec *dops = nullptr;            // (inside the same pinned block)
+    uint32_t dout_cap = 0;              // op records the block holds
+    uint32_t *d_step_ptr = nullptr;     // device copy of a replayed iteration's lists (tc_replay_iteration)
+    uint32_t *d_ids = nullptr;
+    uint8_t *d_rw = nullptr;
+    uint32_t replay_window = 64;        // steps decided per launch by tc_replay_iteration
 
     // dispatch state
-    uint32_t mover_wgs = 512, chunk_bytes = 65536;
-    uint64_t launch_id = 0;             // migration launches issued
-    uint64_t launch_done = 0;           // launches known complete
-    hipEvent_t ring[EVENT_RING]{};
+    uint32_t mover_wgs = 64, chunk_bytes = 65536;
+    uint64_t sdma_threshold = 0;            // tensors at least this large go through the DMA engines (0: none)
+    uint64_t op_id = 0;                 // copy operations issued (kernel launches and DMA copies)
+    uint64_t op_done[N_STREAMS]{};      // per stream: operations known complete
+    hipEvent_t op_ev[OP_RING]{};
+    uint8_t op_stream[OP_RING]{};
     hipEvent_t ev_compute = nullptr;
-    std::vector<uint64_t> gpu_ticket, cpu_ticket;   // last launch that touched the buffer
-    uint64_t staging_ticket = 0;
+    bool compute_recorded = false;      // this hook call: ev_compute recorded
+    bool stream_waited[N_STREAMS]{};    // this hook call: stream already waits for ev_compute
+    std::vector<uint64_t> gpu_ticket, cpu_ticket;   // last operation that touched the buffer
+    uint64_t staging_ticket[N_STREAMS]{};
     uint64_t staging_used = 0;
+    uint8_t *bounce = nullptr;          // HBM ring: outgoing large tensors wait here for their DMA copy
+    uint64_t bounce_bytes = 0, bounce_head = 0;
+    std::deque<BounceBlock> bounce_q;
     std::vector<Pending> pending;
+    // units prepared but not issued yet: hook calls are merged into larger launches
+    std::vector<PUnit> deferred;
+    uint64_t deferred_bytes = 0;
+    uint64_t merge_bytes = 256ull << 20;
+    std::vector<uint8_t> gpu_pending, cpu_pending;  // buffer is touched by a deferred unit
+    hipStream_t last_compute = nullptr;
     // last PRE call, for tc_emulate_compute
     TcStampArgs last_pre{};
-    uint64_t last_pre_ticket = 0;
+    std::vector<uint64_t> last_pre_tickets;
     uint32_t iteration = 0;
 
-    // mover timing
+    // timing of migration launches and DMA copies
     bool timing = false;
-    std::vector<std::pair<hipEvent_t, hipEvent_t>> timed;
+    std::vector<Timed> timed;
 
     std::vector<tc_op> log;
     tc_stats stats{};
@@ -105,14 +152,21 @@ extern "C" int tc_create(tc_ctx **out)
 static void release_device(tc_ctx *c)
 {
     if (c->dstream) { (void)hipStreamSynchronize(c->dstream); }
-    if (c->mstream || c->stage >= 4) { (void)hipStreamSynchronize(c->mstream); }
-    for (auto &p : c->timed) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+    for (int i = 0; i < N_STREAMS; ++i)
+        if (c->streams[i] || (i == S_K && c->stage >= 4)) { (void)hipStreamSynchronize(c->streams[i]); }
+    for (auto &p : c->timed) { (void)hipEventDestroy(p.t0); (void)hipEventDestroy(p.t1); }
     c->timed.clear();
-    for (uint32_t i = 0; i < EVENT_RING; ++i)
-        if (c->ring[i]) { (void)hipEventDestroy(c->ring[i]); c->ring[i] = nullptr; }
+    for (uint32_t i = 0; i < OP_RING; ++i)
+        if (c->op_ev[i]) { (void)hipEventDestroy(c->op_ev[i]); c->op_ev[i] = nullptr; }
     if (c->ev_compute) { (void)hipEventDestroy(c->ev_compute); c->ev_compute = nullptr; }
     if (c->dstream) { (void)hipStreamDestroy(c->dstream); c->dstream = nullptr; }
+    for (int i = S_H; i < N_STREAMS; ++i)
+        if (c->streams[i]) { (void)hipStreamDestroy(c->streams[i]); c->streams[i] = nullptr; }
     if (c->dev_block) { (void)hipFree(c->dev_block); c->dev_block = nullptr; }
+    if (c->d_step_ptr) { (void)hipFree(c->d_step_ptr); c->d_step_ptr = nullptr; }
+    if (c->d_ids) { (void)hipFree(c->d_ids); c->d_ids = nullptr; }
+    if (c->d_rw) { (void)hipFree(c->d_rw); c->d_rw = nullptr; }
+    if (c->bounce) { (void)hipFree(c->bounce); c->bounce = nullptr; }
     if (c->dout) { (void)hipHostFree(c->dout); c->dout = nullptr; }
 }
 
@@ -261,27 +315,50 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     T.gpu_owner = d + o_go; T.gpu_freed = d + o_gf; T.cpu_owner = d + o_co; T.cpu_freed = d + o_cf;
     T.designated = d + o_des; T.scalars = d + o_sc;
 
-    c->dout_cap = 3 * n_t + 64;
-    e = hipHostMalloc((void **)&c->dout, sizeof(TcDecideOut) + (size_t)c->dout_cap * sizeof(TcOpRec), hipHostMallocDefault);
+    // result block: room for the end-of-iteration call (every tensor may move, with
+    // a spill and an eviction each) and for a full window of hook calls (per listed
+    // tensor at most a spill, an eviction and a fetch)
+    c->dout_cap = std::max<uint32_t>(3 * n_t + 64, TC_WINDOW_MAX * 2 * 3 * TC_MAX_STEP_TENSORS);
+    const size_t rec_bytes = (size_t)2 * TC_WINDOW_MAX * sizeof(TcDecideOut);
+    e = hipHostMalloc((void **)&c->dout, rec_bytes + (size_t)c->dout_cap * sizeof(TcOpRec), hipHostMallocDefault);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
-    memset(c->dout, 0, sizeof(TcDecideOut));
+    memset(c->dout, 0, rec_bytes);
+    c->dops = (TcOpRec *)((uint8_t *)c->dout + rec_bytes);
+    e = hipMalloc((void **)&c->d_step_ptr, ((size_t)p.n_steps + 1) * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_ids, std::max<size_t>(1, (size_t)p.n_steps * TC_MAX_STEP_TENSORS) * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_rw, std::max<size_t>(1, (size_t)p.n_steps * TC_MAX_STEP_TENSORS));
+    if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     e = hipStreamCreateWithFlags(&c->dstream, hipStreamNonBlocking);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
-    for (uint32_t i = 0; i < EVENT_RING; ++i) {
-        e = hipEventCreateWithFlags(&c->ring[i], hipEventDisableTiming);
+    for (uint32_t i = 0; i < OP_RING; ++i) {
+        e = hipEventCreateWithFlags(&c->op_ev[i], hipEventDisableTiming);
         if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     }
     e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    if (!null_mover) {
+        for (int i = S_H; i < N_STREAMS; ++i) {
+            e = hipStreamCreateWithFlags(&c->streams[i], hipStreamNonBlocking);
+            if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+        }
+        // bounce ring in HBM: room for four of the largest tensors, 64 MiB .. 2 GiB
+        uint64_t largest = 0;
+        for (uint32_t k = 0; k < n_c; ++k) largest = std::max(largest, pl.stride[k]);
+        c->bounce_bytes = std::min<uint64_t>(std::max<uint64_t>(4 * largest, 64ull << 20), 2048ull << 20);
+        e = hipMalloc((void **)&c->bounce, c->bounce_bytes);
+        if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    }
 
     c->hbm = (uint8_t *)hbm; c->hbm_bytes = hbm_bytes;
     c->pinned = (uint8_t *)pinned; c->pinned_bytes = pinned_bytes;
     c->staging = (uint8_t *)staging; c->staging_bytes = staging_bytes;
     c->fd = fd;
-    c->mstream = (hipStream_t)mstream;
+    c->streams[S_K] = (hipStream_t)mstream;
     c->null_mover = null_mover;
     c->gpu_ticket.assign(pl.gpu_slots, 0);
     c->cpu_ticket.assign(pl.cpu_slots, 0);
+    c->gpu_pending.assign(pl.gpu_slots, 0);
+    c->cpu_pending.assign(pl.cpu_slots, 0);
     c->stage = 4;
     return TC_OK;
 }
@@ -298,17 +375,80 @@ static inline uint8_t *cpu_addr(const tc_ctx *c, uint32_t s, uint32_t k)
     return c->pinned + c->pools.host_off[s] + (uint64_t)k * c->pools.stride[s];
 }
 
-// block the host until migration launch `id` has completed
-static int wait_launch(tc_ctx *c, uint64_t id)
+// ---- copy operations: ids, events, dependencies -----------------------------
+// Every kernel launch and every DMA copy is one operation with an id and an
+// event in a ring.  A stream is in order, so per stream it is enough to know the
+// newest operation seen complete.  An id older than the ring has completed by
+// construction: begin_op waits for the operation whose event it recycles.
+static inline bool op_complete(const tc_ctx *c, uint64_t id)
 {
-    if (id <= c->launch_done) return TC_OK;
-    if (c->launch_id - id >= EVENT_RING) {           // its event was recycled: the stream is in order
-        HIP_TRY(c, hipStreamSynchronize(c->mstream));
-        c->launch_done = c->launch_id;
-        return TC_OK;
+    if (id == 0 || c->op_id - id >= OP_RING) return true;
+    return id <= c->op_done[c->op_stream[id % OP_RING]];
+}
+
+// block the host until operation `id` has completed
+static int wait_op(tc_ctx *c, uint64_t id)
+{
+    if (op_complete(c, id)) return TC_OK;
+    const uint32_t st = c->op_stream[id % OP_RING];
+    HIP_TRY(c, hipEventSynchronize(c->op_ev[id % OP_RING]));
+    c->op_done[st] = std::max(c->op_done[st], id);
+    return TC_OK;
+}
+
+// make stream S wait for operation `id` (nothing to do if it ran on S or is done)
+static int dep(tc_ctx *c, int S, uint64_t id)
+{
+    if (op_complete(c, id) || c->op_stream[id % OP_RING] == S) return TC_OK;
+    HIP_TRY(c, hipStreamWaitEvent(c->streams[S], c->op_ev[id % OP_RING], 0));
+    return TC_OK;
+}
+
+// start an operation on stream S: the first one of a hook call on that stream
+// makes the stream wait for the work already queued on the compute stream
+static int begin_op(tc_ctx *c, int S, hipStream_t compute, uint64_t *id)
+{
+    const uint64_t n = c->op_id + 1;
+    if (n > OP_RING) {
+        int rc = wait_op(c, n - OP_RING);              // the event about to be reused
+        if (rc != TC_OK) return rc;
     }
-    HIP_TRY(c, hipEventSynchronize(c->ring[id % EVENT_RING]));
-    c->launch_done = std::max(c->launch_done, id);
+    if (!c->stream_waited[S]) {
+        if (!c->compute_recorded) {
+            HIP_TRY(c, hipEventRecord(c->ev_compute, compute));
+            c->compute_recorded = true;
+        }
+        HIP_TRY(c, hipStreamWaitEvent(c->streams[S], c->ev_compute, 0));
+        c->stream_waited[S] = true;
+    }
+    *id = n;
+    return TC_OK;
+}
+
+static int end_op(tc_ctx *c, int S, uint64_t id)
+{
+    c->op_stream[id % OP_RING] = (uint8_t)S;
+    c->op_id = id;
+    HIP_TRY(c, hipEventRecord(c->op_ev[id % OP_RING], c->streams[S]));
+    return TC_OK;
+}
+
+static int timed_begin(tc_ctx *c, int S, hipEvent_t *t0)
+{
+    *t0 = nullptr;
+    if (!c->timing) return TC_OK;
+    HIP_TRY(c, hipEventCreate(t0));
+    HIP_TRY(c, hipEventRecord(*t0, c->streams[S]));
+    return TC_OK;
+}
+
+static int timed_end(tc_ctx *c, int S, hipEvent_t t0, uint64_t bytes)
+{
+    if (!t0) return TC_OK;
+    hipEvent_t t1;
+    HIP_TRY(c, hipEventCreate(&t1));
+    HIP_TRY(c, hipEventRecord(t1, c->streams[S]));
+    c->timed.push_back(Timed{t0, t1, S, bytes});
     return TC_OK;
 }
 
@@ -337,57 +477,26 @@ static int file_read(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t off)
 }
 
 // ---------------------------------------------------------------------------
-// dispatch: op records -> migration launches + file I/O
+// dispatch: op records -> migration-kernel launches, DMA copies and file I/O
+//
+// A hook call's records are grouped into exchange units (an optional outgoing
+// copy that leaves a GPU buffer and the incoming copy that fills it).  Small
+// units all go into one migration-kernel launch on stream K: per-copy overhead
+// would dominate them, and the kernel's load-load-store-store order lets a
+// unit swap two buffers in place.  Large units go through the DMA engines,
+// which sustain the link in both directions better than a kernel does when a
+// replay is a stream of modest launches: the outgoing tensor is first copied
+// inside HBM to a bounce block (by the same kernel launch, at HBM speed), then
+// the incoming tensor is copied into the GPU buffer on stream H and the
+// outgoing one leaves the bounce block on stream D.  Ordering between streams
+// comes from per-buffer tickets: each buffer remembers the last operation that
+// touched it, and an operation waits for the tickets of the buffers it touches.
 // ---------------------------------------------------------------------------
-namespace {
-struct Batch {
-    TcMoverArgs args{};                                      // zeroed: counts start at 0
-    std::vector<std::pair<uint32_t, uint32_t>> gpu_touched;  // flat buffer indices
-    std::vector<uint32_t> cpu_touched;
-    bool uses_staging = false;
-};
-}
-
-static int flush_batch(tc_ctx *c, Batch &b, bool wait_compute, hipStream_t compute)
-{
-    if (b.args.n_units == 0) return TC_OK;
-    const uint64_t id = c->launch_id + 1;
-    hipEvent_t ev = c->ring[id % EVENT_RING];
-    if (id > EVENT_RING) {                            // the event's previous user must be done
-        int rc = wait_launch(c, id - EVENT_RING);
-        if (rc != TC_OK) return rc;
-    }
-    if (wait_compute) {
-        HIP_TRY(c, hipEventRecord(c->ev_compute, compute));
-        HIP_TRY(c, hipStreamWaitEvent(c->mstream, c->ev_compute, 0));
-    }
-    hipEvent_t t0 = nullptr, t1 = nullptr;
-    if (c->timing) {
-        HIP_TRY(c, hipEventCreate(&t0));
-        HIP_TRY(c, hipEventCreate(&t1));
-        HIP_TRY(c, hipEventRecord(t0, c->mstream));
-    }
-    HIP_TRY(c, tc_launch_mover(b.args, c->mover_wgs, c->mstream));
-    if (c->timing) {
-        HIP_TRY(c, hipEventRecord(t1, c->mstream));
-        c->timed.push_back({t0, t1});
-    }
-    HIP_TRY(c, hipEventRecord(ev, c->mstream));
-    c->launch_id = id;
-    for (auto &g : b.gpu_touched) c->gpu_ticket[g.first] = id;
-    for (uint32_t x : b.cpu_touched) c->cpu_ticket[x] = id;
-    if (b.uses_staging) c->staging_ticket = id;
-    c->stats.mover_launches++;
-    c->stats.mover_units += b.args.n_units;
-    b = Batch();
-    return TC_OK;
-}
-
-// writes that waited for a launch (GPU buffer -> staging -> file)
+// writes that waited for a copy (GPU buffer -> staging -> file)
 static int drain_pending(tc_ctx *c)
 {
     for (const Pending &p : c->pending) {
-        int rc = wait_launch(c, p.launch);
+        int rc = wait_op(c, p.op);
         if (rc != TC_OK) return rc;
         rc = file_write(c, p.src, p.bytes, p.file_off);
         if (rc != TC_OK) return rc;
@@ -396,60 +505,229 @@ static int drain_pending(tc_ctx *c)
     return TC_OK;
 }
 
-static int staging_alloc(tc_ctx *c, Batch &b, uint64_t bytes, bool wait_compute, hipStream_t compute, uint8_t **out)
+// a block of the HBM bounce ring, or nullptr if none can be had without
+// waiting for a copy of the batch being prepared
+static int bounce_alloc(tc_ctx *c, uint64_t bytes, uint8_t **out)
+{
+    *out = nullptr;
+    const uint64_t need = (bytes + 255) & ~255ull;
+    if (!c->bounce || need > c->bounce_bytes) return TC_OK;
+    for (;;) {
+        while (!c->bounce_q.empty() && c->bounce_q.front().op && op_complete(c, c->bounce_q.front().op))
+            c->bounce_q.pop_front();
+        if (c->bounce_q.empty()) c->bounce_head = 0;
+        const uint64_t tail = c->bounce_q.empty() ? 0 : c->bounce_q.front().off;
+        uint64_t at = UINT64_MAX;
+        if (c->bounce_q.empty() || c->bounce_head > tail) {        // free: [head, end) and [0, tail)
+            if (c->bounce_head + need <= c->bounce_bytes) at = c->bounce_head;
+            else if (need <= tail && !c->bounce_q.empty()) at = 0;
+        } else if (c->bounce_head < tail) {                        // free: [head, tail)
+            if (c->bounce_head + need <= tail) at = c->bounce_head;
+        }
+        if (at != UINT64_MAX) {
+            c->bounce_q.push_back(BounceBlock{at, need, 0});
+            c->bounce_head = at + need;
+            *out = c->bounce + at;
+            return TC_OK;
+        }
+        if (c->bounce_q.front().op == 0) return TC_OK;             // held by this very batch: give up
+        int rc = wait_op(c, c->bounce_q.front().op);               // oldest reader must finish first
+        if (rc != TC_OK) return rc;
+    }
+}
+
+// issue the prepared units of a hook call
+static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute)
+{
+    if (units.empty()) return TC_OK;
+    struct Large { size_t unit; uint8_t *bounce; uint64_t kop; };
+    std::vector<Large> large;
+    std::vector<size_t> small;
+    for (size_t i = 0; i < units.size(); ++i) {
+        PUnit &p = units[i];
+        bool dma = c->sdma_threshold && p.u.bytes >= c->sdma_threshold && p.u.in_src;
+        Large L{i, nullptr, 0};
+        if (dma && p.u.out_src) {
+            int rc = bounce_alloc(c, p.u.bytes, &L.bounce);
+            if (rc != TC_OK) return rc;
+            if (!L.bounce) dma = false;                            // no room: the kernel swaps it in place
+        }
+        if (dma) large.push_back(L); else small.push_back(i);
+    }
+    // ---- stream K: small units and the staging copies of large ones, <= 24 units per launch
+    std::vector<std::pair<TcUnit, int64_t>> kunits;                // unit, index into `large` or -1-small
+    for (size_t i : small) kunits.push_back({units[i].u, -1 - (int64_t)i});
+    for (size_t j = 0; j < large.size(); ++j)
+        if (large[j].bounce) {
+            TcUnit t{};
+            t.in_src = units[large[j].unit].u.out_src;
+            t.in_dst = large[j].bounce;
+            t.bytes = units[large[j].unit].u.bytes;
+            kunits.push_back({t, (int64_t)j});
+        }
+    for (size_t at = 0; at < kunits.size(); at += TC_MOVER_MAX_UNITS) {
+        const size_t end = std::min(kunits.size(), at + (size_t)TC_MOVER_MAX_UNITS);
+        TcMoverArgs args{};
+        args.chunk_bytes = c->chunk_bytes;
+        uint64_t id, bytes = 0;
+        int rc = begin_op(c, S_K, compute, &id);
+        if (rc != TC_OK) return rc;
+        for (size_t k = at; k < end; ++k) {
+            TcUnit u = kunits[k].first;
+            u.chunk0 = args.n_chunks;
+            args.n_chunks += (u.bytes + c->chunk_bytes - 1) / c->chunk_bytes;
+            args.u[args.n_units++] = u;
+            bytes += u.bytes * ((u.out_src ? 1 : 0) + (u.in_src ? 1 : 0));
+            const PUnit &p = kunits[k].second < 0 ? units[(size_t)(-1 - kunits[k].second)] : units[large[(size_t)kunits[k].second].unit];
+            if ((rc = dep(c, S_K, c->gpu_ticket[(size_t)p.gpu_y])) != TC_OK) return rc;
+            if (kunits[k].second < 0) {
+                if (p.cpu_out >= 0 && (rc = dep(c, S_K, c->cpu_ticket[(size_t)p.cpu_out])) != TC_OK) return rc;
+                if (p.cpu_in >= 0 && (rc = dep(c, S_K, c->cpu_ticket[(size_t)p.cpu_in])) != TC_OK) return rc;
+            }
+        }
+        hipEvent_t t0;
+        if ((rc = timed_begin(c, S_K, &t0)) != TC_OK) return rc;
+        HIP_TRY(c, tc_launch_mover(args, c->mover_wgs, c->streams[S_K]));
+        if ((rc = timed_end(c, S_K, t0, bytes)) != TC_OK) return rc;
+        if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
+        c->stats.mover_launches++;
+        c->stats.mover_units += args.n_units;
+        for (size_t k = at; k < end; ++k) {
+            if (kunits[k].second < 0) {
+                const PUnit &p = units[(size_t)(-1 - kunits[k].second)];
+                c->gpu_ticket[(size_t)p.gpu_y] = id;
+                if (p.cpu_out >= 0) c->cpu_ticket[(size_t)p.cpu_out] = id;
+                if (p.cpu_in >= 0) c->cpu_ticket[(size_t)p.cpu_in] = id;
+                if (p.out_staging || p.in_staging) c->staging_ticket[S_K] = id;
+                if (p.out_staging)
+                    c->pending.push_back(Pending{id, p.u.out_dst, c->prof.bytes[p.out_tensor], c->place.file_off[p.out_tensor]});
+            } else {
+                Large &L = large[(size_t)kunits[k].second];
+                L.kop = id;
+                c->gpu_ticket[(size_t)units[L.unit].gpu_y] = id;
+            }
+        }
+    }
+    // ---- streams H and D: the large units, one DMA copy per direction
+    for (Large &L : large) {
+        const PUnit &p = units[L.unit];
+        uint64_t idh, idd;
+        int rc = begin_op(c, S_H, compute, &idh);
+        if (rc != TC_OK) return rc;
+        if ((rc = dep(c, S_H, c->gpu_ticket[(size_t)p.gpu_y])) != TC_OK) return rc;   // staging copy, earlier users
+        if (p.cpu_in >= 0 && (rc = dep(c, S_H, c->cpu_ticket[(size_t)p.cpu_in])) != TC_OK) return rc;
+        hipEvent_t t0;
+        if ((rc = timed_begin(c, S_H, &t0)) != TC_OK) return rc;
+        HIP_TRY(c, hipMemcpyAsync(p.u.in_dst, p.u.in_src, p.u.bytes, hipMemcpyHostToDevice, c->streams[S_H]));
+        if ((rc = timed_end(c, S_H, t0, p.u.bytes)) != TC_OK) return rc;
+        if ((rc = end_op(c, S_H, idh)) != TC_OK) return rc;
+        c->gpu_ticket[(size_t)p.gpu_y] = idh;
+        if (p.cpu_in >= 0) c->cpu_ticket[(size_t)p.cpu_in] = idh;
+        if (p.in_staging) c->staging_ticket[S_H] = idh;
+        c->stats.dma_copies++;
+        if (!L.bounce) continue;
+        if ((rc = begin_op(c, S_D, compute, &idd)) != TC_OK) return rc;
+        // the outgoing bytes sit in the bounce block once the staging launch is done;
+        // in a swap the host buffer they go to must first have been read by the copy above
+        if ((rc = dep(c, S_D, L.kop)) != TC_OK) return rc;
+        if (p.cpu_out >= 0 && p.cpu_out == p.cpu_in && (rc = dep(c, S_D, idh)) != TC_OK) return rc;
+        if (p.cpu_out >= 0 && (rc = dep(c, S_D, c->cpu_ticket[(size_t)p.cpu_out])) != TC_OK) return rc;
+        if ((rc = timed_begin(c, S_D, &t0)) != TC_OK) return rc;
+        HIP_TRY(c, hipMemcpyAsync(p.u.out_dst, L.bounce, p.u.bytes, hipMemcpyDeviceToHost, c->streams[S_D]));
+        if ((rc = timed_end(c, S_D, t0, p.u.bytes)) != TC_OK) return rc;
+        if ((rc = end_op(c, S_D, idd)) != TC_OK) return rc;
+        if (p.cpu_out >= 0) c->cpu_ticket[(size_t)p.cpu_out] = idd;
+        for (BounceBlock &blk : c->bounce_q)
+            if (c->bounce + blk.off == L.bounce) blk.op = idd;
+        c->stats.dma_copies++;
+        if (p.out_staging) {
+            c->staging_ticket[S_D] = idd;
+            c->pending.push_back(Pending{idd, p.u.out_dst, c->prof.bytes[p.out_tensor], c->place.file_off[p.out_tensor]});
+        }
+    }
+    for (const PUnit &p : units) {
+        c->gpu_pending[(size_t)p.gpu_y] = 0;
+        if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 0;
+        if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 0;
+    }
+    units.clear();
+    c->deferred_bytes = 0;
+    return TC_OK;
+}
+
+// issue whatever earlier hook calls left prepared
+static int flush_deferred(tc_ctx *c, hipStream_t compute)
+{
+    if (c->deferred.empty()) return TC_OK;
+    c->compute_recorded = false;
+    for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
+    int rc = issue_units(c, c->deferred, compute);
+    if (rc != TC_OK) return rc;
+    return drain_pending(c);
+}
+
+static int staging_wait_all(tc_ctx *c)
+{
+    for (int i = 0; i < N_STREAMS; ++i) {
+        int rc = wait_op(c, c->staging_ticket[i]);
+        if (rc != TC_OK) return rc;
+    }
+    return TC_OK;
+}
+
+static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, hipStream_t compute, uint8_t **out)
 {
     const uint64_t need = (bytes + 255) & ~255ull;
     if (need > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a tensor that needs the file tier");
     if (c->staging_used + need > c->staging_bytes) {
-        // out of bounce space: issue what is batched, let it finish, start over
-        int rc = flush_batch(c, b, wait_compute, compute);
+        // out of bounce space: issue what is prepared, let it finish, start over
+        int rc = issue_units(c, units, compute);
         if (rc != TC_OK) return rc;
         rc = drain_pending(c);
-        if (rc != TC_OK) return rc;
-        rc = wait_launch(c, c->staging_ticket);
         if (rc != TC_OK) return rc;
         c->staging_used = 0;
     }
     if (c->staging_used == 0) {
-        int rc = wait_launch(c, c->staging_ticket);   // earlier calls' reads of the bounce space
+        int rc = staging_wait_all(c);                 // earlier copies that still read the space
         if (rc != TC_OK) return rc;
     }
     *out = c->staging + c->staging_used;
     c->staging_used += need;
-    b.uses_staging = true;
     return TC_OK;
 }
 
-static int dispatch(tc_ctx *c, uint32_t step, hipStream_t compute)
+static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step, int phase,
+                    hipStream_t compute)
 {
-    const TcDecideOut *o = c->dout;
-    const TcOpRec *ops = (const TcOpRec *)(o + 1);
     if (o->overflow) return fail(c, TC_E_CAPACITY, "decision log overflow");
-    Batch b{};
-    TcUnit pend{};                  // outgoing half waiting for its incoming partner
+    // Units are not issued per hook call: a launch that moves tens of MiB spends a
+    // visible share of its time ramping the link up in both directions, so calls
+    // are merged until merge_bytes are prepared, a prepared buffer is needed
+    // (by a module, by a later unit or by the host), or the file tier is involved.
+    std::vector<PUnit> &units = c->deferred;
+    bool must_issue = false;
+    c->last_compute = compute;
+    PUnit pend{};                   // outgoing half waiting for its incoming partner
     bool have_out = false;
-    std::pair<uint32_t, uint32_t> out_gpu{0, 0};
-    int64_t out_cpu = -1;
-    bool out_staging = false;
-    uint32_t out_tensor = 0;
-    uint8_t *reserved_in = nullptr;  // bounce space kept for the partner of a write-back
+    uint8_t *reserved_in = nullptr; // bounce space kept for the partner of a write-back
     c->staging_used = 0;
+    c->compute_recorded = false;
+    for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
     for (uint32_t i = 0; i < o->n_ops; ++i) {
         const TcOpRec &r = ops[i];
         const uint32_t t = r.tensor;
         // never turn a record into an address before it is known to be in range
         if (t >= c->prof.n_tensors || r.op > TC_OP_FAIL)
             return fail(c, TC_E_HIP, "decision record out of range (tensor/op)");
+        const uint32_t s = c->prof.class_of[t];
         {
-            const uint32_t sc = c->prof.class_of[t];
-            const bool src_ok = r.src_tier == TC_GPU ? r.src_slot < c->pools.gpu_count[sc]
-                              : r.src_tier == TC_CPU ? r.src_slot < c->pools.cpu_count[sc] : r.src_slot == TC_NONE;
-            const bool dst_ok = r.dst_tier == TC_GPU ? r.dst_slot < c->pools.gpu_count[sc]
-                              : r.dst_tier == TC_CPU ? r.dst_slot < c->pools.cpu_count[sc] : r.dst_slot == TC_NONE;
+            const bool src_ok = r.src_tier == TC_GPU ? r.src_slot < c->pools.gpu_count[s]
+                              : r.src_tier == TC_CPU ? r.src_slot < c->pools.cpu_count[s] : r.src_slot == TC_NONE;
+            const bool dst_ok = r.dst_tier == TC_GPU ? r.dst_slot < c->pools.gpu_count[s]
+                              : r.dst_tier == TC_CPU ? r.dst_slot < c->pools.cpu_count[s] : r.dst_slot == TC_NONE;
             if (r.op != TC_OP_FAIL && !(src_ok && dst_ok))
                 return fail(c, TC_E_HIP, "decision record out of range (slot)");
         }
-        const uint32_t s = c->prof.class_of[t];
         const uint64_t n = c->prof.bytes[t];
         tc_op rec;
         rec.iteration = c->iteration; rec.step = step; rec.tensor = t;
@@ -469,26 +747,27 @@ static int dispatch(tc_ctx *c, uint32_t step, hipStream_t compute)
         default: break;
         }
         if (c->null_mover) continue;
-        const bool wait_compute = true;
         switch (r.op) {
         case TC_OP_SPILL: {
             // host buffer -> file extent, now: the buffer is about to be reused
             const uint32_t flat = c->pools.cpu_base[s] + r.src_slot;
-            int rc = wait_launch(c, c->cpu_ticket[flat]);
+            int rc = c->cpu_pending[flat] ? issue_units(c, units, compute) : TC_OK;
             if (rc != TC_OK) return rc;
+            rc = wait_op(c, c->cpu_ticket[flat]);
+            if (rc != TC_OK) return rc;
+            must_issue = true;
             rc = file_write(c, cpu_addr(c, s, r.src_slot), n, c->place.file_off[t]);
             if (rc != TC_OK) return rc;
             break;
         }
         case TC_OP_EVICT: {
-            pend = TcUnit{};
-            pend.out_src = gpu_addr(c, s, r.src_slot);
-            pend.out_dst = cpu_addr(c, s, r.dst_slot);
-            pend.bytes = n;
+            pend = PUnit{};
+            pend.u.out_src = gpu_addr(c, s, r.src_slot);
+            pend.u.out_dst = cpu_addr(c, s, r.dst_slot);
+            pend.u.bytes = n;
+            pend.gpu_y = c->pools.gpu_base[s] + r.src_slot;
+            pend.cpu_out = c->pools.cpu_base[s] + r.dst_slot;
             have_out = true;
-            out_gpu = {c->pools.gpu_base[s] + r.src_slot, 0};
-            out_cpu = c->pools.cpu_base[s] + r.dst_slot;
-            out_staging = false;
             break;
         }
         case TC_OP_WRITEBACK: {
@@ -496,70 +775,61 @@ static int dispatch(tc_ctx *c, uint32_t step, hipStream_t compute)
             // incoming tensor of the same class should it come from the file tier
             uint8_t *st = nullptr;
             const uint64_t half = (n + 255) & ~255ull;
-            int rc = staging_alloc(c, b, 2 * half, wait_compute, compute, &st);
+            int rc = staging_alloc(c, units, 2 * half, compute, &st);
             if (rc != TC_OK) return rc;
             reserved_in = st + half;
-            pend = TcUnit{};
-            pend.out_src = gpu_addr(c, s, r.src_slot);
-            pend.out_dst = st;
-            pend.bytes = n;
+            pend = PUnit{};
+            pend.u.out_src = gpu_addr(c, s, r.src_slot);
+            pend.u.out_dst = st;
+            pend.u.bytes = n;
+            pend.gpu_y = c->pools.gpu_base[s] + r.src_slot;
+            pend.out_staging = true;
+            pend.out_tensor = t;
             have_out = true;
-            out_gpu = {c->pools.gpu_base[s] + r.src_slot, 0};
-            out_cpu = -1;
-            out_staging = true;
-            out_tensor = t;
             break;
         }
         case TC_OP_DEMAND:
         case TC_OP_PREFETCH: {
-            TcUnit u = have_out ? pend : TcUnit{};
-            u.bytes = n;
-            u.in_dst = gpu_addr(c, s, r.dst_slot);
-            int64_t in_cpu = -1;
+            PUnit p = have_out ? pend : PUnit{};
+            p.u.bytes = n;
+            p.u.in_dst = gpu_addr(c, s, r.dst_slot);
+            p.gpu_y = c->pools.gpu_base[s] + r.dst_slot;
             if (r.src_tier == TC_CPU) {
-                u.in_src = cpu_addr(c, s, r.src_slot);
-                in_cpu = c->pools.cpu_base[s] + r.src_slot;
+                p.u.in_src = cpu_addr(c, s, r.src_slot);
+                p.cpu_in = c->pools.cpu_base[s] + r.src_slot;
             } else {
                 uint8_t *st = nullptr;
                 int rc = TC_OK;
-                if (have_out && out_staging) st = reserved_in;
-                else rc = staging_alloc(c, b, n, wait_compute, compute, &st);
+                if (have_out && p.out_staging) st = reserved_in;
+                else rc = staging_alloc(c, units, n, compute, &st);
                 if (rc != TC_OK) return rc;
                 rc = file_read(c, st, n, c->place.file_off[t]);
                 if (rc != TC_OK) return rc;
-                u.in_src = st;
+                p.u.in_src = st;
+                p.in_staging = true;
             }
-            if (b.args.n_units == TC_MOVER_MAX_UNITS) {
-                int rc = flush_batch(c, b, wait_compute, compute);
+            // a buffer that a prepared unit already touches: issue those first
+            if (c->gpu_pending[(size_t)p.gpu_y] || (p.cpu_out >= 0 && c->cpu_pending[(size_t)p.cpu_out]) ||
+                (p.cpu_in >= 0 && c->cpu_pending[(size_t)p.cpu_in])) {
+                int rc = issue_units(c, units, compute);
                 if (rc != TC_OK) return rc;
             }
-            u.chunk0 = b.args.n_chunks;
-            b.args.n_chunks += (n + c->chunk_bytes - 1) / c->chunk_bytes;
-            b.args.chunk_bytes = c->chunk_bytes;
-            b.args.u[b.args.n_units++] = u;
-            b.gpu_touched.push_back({c->pools.gpu_base[s] + r.dst_slot, 0});
-            if (have_out) b.gpu_touched.push_back(out_gpu);
-            if (in_cpu >= 0) b.cpu_touched.push_back((uint32_t)in_cpu);
-            if (have_out && out_cpu >= 0) b.cpu_touched.push_back((uint32_t)out_cpu);
-            if (r.src_tier != TC_CPU || (have_out && out_staging)) b.uses_staging = true;
-            if (have_out && out_staging) {
-                Pending p;
-                p.launch = c->launch_id + 1;          // the launch this batch becomes
-                p.src = u.out_dst;
-                p.bytes = c->prof.bytes[out_tensor];
-                p.file_off = c->place.file_off[out_tensor];
-                c->pending.push_back(p);
-            }
+            c->gpu_pending[(size_t)p.gpu_y] = 1;
+            if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 1;
+            if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 1;
+            if (p.out_staging || p.in_staging) must_issue = true;
+            c->deferred_bytes += n * ((p.u.out_src ? 1 : 0) + 1);
+            units.push_back(p);
             have_out = false;
             break;
         }
         case TC_OP_RESTORE: {
             // file extent -> host buffer, by the host; earlier copies that read
             // or wrote the buffer must have finished
-            int rc = flush_batch(c, b, wait_compute, compute);
+            int rc = issue_units(c, units, compute);
             if (rc != TC_OK) return rc;
             const uint32_t flat = c->pools.cpu_base[s] + r.dst_slot;
-            rc = wait_launch(c, c->cpu_ticket[flat]);
+            rc = wait_op(c, c->cpu_ticket[flat]);
             if (rc != TC_OK) return rc;
             rc = file_read(c, cpu_addr(c, s, r.dst_slot), n, c->place.file_off[t]);
             if (rc != TC_OK) return rc;
@@ -569,17 +839,65 @@ static int dispatch(tc_ctx *c, uint32_t step, hipStream_t compute)
         }
     }
     if (c->null_mover) return TC_OK;
-    int rc = flush_batch(c, b, true, compute);
+    if (!must_issue && phase < TC_END && c->deferred_bytes < c->merge_bytes &&
+        units.size() < 4 * TC_MOVER_MAX_UNITS)
+        return TC_OK;                                  // keep them for a larger launch
+    int rc = issue_units(c, units, compute);
     if (rc != TC_OK) return rc;
     return drain_pending(c);
 }
 
 static int run_decide(tc_ctx *c, const TcStepArgs &a)
 {
-    HIP_TRY(c, tc_launch_decide(c->T, a, c->dout, c->dstream));
+    HIP_TRY(c, tc_launch_decide(c->T, a, c->dout, c->dops, c->dstream));
     HIP_TRY(c, hipStreamSynchronize(c->dstream));
     c->stats.decide_launches++;
     c->stats.cursor = c->dout->cursor;
+    return TC_OK;
+}
+
+// what a pre-hook call does once its decisions are dispatched: counters, the
+// buffers' addresses, the waits of the compute stream, the stamp list
+static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint32_t *ids, const uint8_t *rw,
+                      uint32_t n, hipStream_t compute, void **dev_ptrs_out)
+{
+    c->stats.hits += o->hits;
+    c->stats.misses += o->misses;
+    c->stats.fails += o->fails;
+    TcStampArgs &sa = c->last_pre;
+    sa = TcStampArgs{};
+    sa.iteration = c->iteration;
+    sa.step = step;
+    c->last_pre_tickets.clear();
+    for (uint32_t i = 0; i < n && !c->null_mover; ++i)
+        if (o->slots[i] != TC_NONE && c->gpu_pending[c->pools.gpu_base[c->prof.class_of[ids[i]]] + o->slots[i]]) {
+            int rc = flush_deferred(c, compute);          // its copy has to be on its way before the module runs
+            if (rc != TC_OK) return rc;
+            break;
+        }
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t t = ids[i], s = c->prof.class_of[t];
+        uint8_t *ptr = nullptr;
+        if (o->slots[i] != TC_NONE) {
+            if (o->slots[i] >= c->pools.gpu_count[s]) return fail(c, TC_E_HIP, "decision record out of range (buffer)");
+            if (!c->null_mover) {
+                ptr = gpu_addr(c, s, o->slots[i]);
+                // the module's kernels wait only for the copies that fill ITS buffers
+                const uint64_t ticket = c->gpu_ticket[c->pools.gpu_base[s] + o->slots[i]];
+                if (!op_complete(c, ticket)) {
+                    c->last_pre_tickets.push_back(ticket);
+                    HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
+                }
+            }
+        }
+        if (dev_ptrs_out) dev_ptrs_out[i] = ptr;
+        if ((rw[i] & TC_W) && ptr) {
+            sa.ptr[sa.n] = ptr;
+            sa.bytes[sa.n] = c->prof.bytes[t];
+            sa.tensor[sa.n] = t;
+            sa.n++;
+        }
+    }
     return TC_OK;
 }
 
@@ -602,42 +920,9 @@ extern "C" int tc_migrate_step(tc_ctx *c, uint32_t step, int phase, const uint32
     int rc = run_decide(c, a);
     if (rc != TC_OK) return rc;
     hipStream_t compute = (hipStream_t)compute_stream;
-    rc = dispatch(c, step, compute);
+    rc = dispatch(c, c->dout, c->dops, step, phase, compute);
     if (rc != TC_OK) return rc;
-    if (phase == TC_PRE) {
-        const TcDecideOut *o = c->dout;
-        c->stats.hits += o->hits;
-        c->stats.misses += o->misses;
-        c->stats.fails += o->fails;
-        TcStampArgs &sa = c->last_pre;
-        sa = TcStampArgs{};
-        sa.iteration = c->iteration;
-        sa.step = step;
-        uint64_t ticket = 0;
-        for (uint32_t i = 0; i < n; ++i) {
-            const uint32_t t = ids[i], s = c->prof.class_of[t];
-            uint8_t *ptr = nullptr;
-            if (o->slots[i] != TC_NONE) {
-                if (!c->null_mover) ptr = gpu_addr(c, s, o->slots[i]);
-                ticket = std::max(ticket, c->gpu_ticket[c->pools.gpu_base[s] + o->slots[i]]);
-            }
-            if (dev_ptrs_out) dev_ptrs_out[i] = ptr;
-            if ((a.rw[i] & TC_W) && ptr) {
-                sa.ptr[sa.n] = ptr;
-                sa.bytes[sa.n] = c->prof.bytes[t];
-                sa.tensor[sa.n] = t;
-                sa.n++;
-            }
-        }
-        c->last_pre_ticket = ticket;
-        // the module's kernels wait only for the copies that fill ITS buffers
-        if (!c->null_mover && ticket > c->launch_done && c->launch_id - ticket < EVENT_RING)
-            HIP_TRY(c, hipStreamWaitEvent(compute, c->ring[ticket % EVENT_RING], 0));
-        else if (!c->null_mover && ticket > c->launch_done) {
-            rc = wait_launch(c, ticket);
-            if (rc != TC_OK) return rc;
-        }
-    }
+    if (phase == TC_PRE) return finish_pre(c, c->dout, step, ids, a.rw, n, compute, dev_ptrs_out);
     return TC_OK;
 }
 
@@ -649,7 +934,7 @@ extern "C" int tc_end_iteration(tc_ctx *c, void *compute_stream)
     a.n = 0; a.step = c->prof.n_steps; a.phase = TC_END; a.cap = c->dout_cap;
     int rc = run_decide(c, a);
     if (rc != TC_OK) return rc;
-    rc = dispatch(c, c->prof.n_steps, (hipStream_t)compute_stream);
+    rc = dispatch(c, c->dout, c->dops, c->prof.n_steps, TC_END, (hipStream_t)compute_stream);
     if (rc != TC_OK) return rc;
     c->iteration = c->dout->iteration;
     c->stats.iteration = c->iteration;
@@ -668,8 +953,10 @@ extern "C" int tc_emulate_compute(tc_ctx *c, void *compute_stream, uint64_t busy
         // already queued: drain compute, then time the wait for the ticket
         HIP_TRY(c, hipStreamSynchronize(compute));
         auto t0 = std::chrono::steady_clock::now();
-        int rc = wait_launch(c, c->last_pre_ticket);
-        if (rc != TC_OK) return rc;
+        for (uint64_t ticket : c->last_pre_tickets) {
+            int rc = wait_op(c, ticket);
+            if (rc != TC_OK) return rc;
+        }
         uint64_t ns = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
                           std::chrono::steady_clock::now() - t0).count();
         c->stats.stall_ns += ns;
@@ -686,17 +973,53 @@ extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const ui
     if (!c || !step_ptr || !ids || !rw) return fail(c, TC_E_ARG, "null argument");
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     if (n_steps > c->prof.n_steps) return fail(c, TC_E_ARG, "more steps than the profiled iteration");
+    if (step_ptr[0] != 0) return fail(c, TC_E_ARG, "step_ptr must start at 0");
     for (uint32_t k = 0; k < n_steps; ++k) {
         if (step_ptr[k + 1] < step_ptr[k]) return fail(c, TC_E_ARG, "step_ptr must not decrease");
-        const uint32_t n = step_ptr[k + 1] - step_ptr[k];
-        const uint32_t *id = ids + step_ptr[k];
-        const uint8_t *a = rw + step_ptr[k];
-        int rc = tc_migrate_step(c, k, TC_PRE, id, a, n, compute_stream, nullptr);
-        if (rc != TC_OK) return rc;
-        rc = tc_emulate_compute(c, compute_stream, busy_ns ? busy_ns[k] : 0, measure_stall);
-        if (rc != TC_OK) return rc;
-        rc = tc_migrate_step(c, k, TC_POST, id, a, n, compute_stream, nullptr);
-        if (rc != TC_OK) return rc;
+        if (step_ptr[k + 1] - step_ptr[k] > TC_MAX_STEP_TENSORS) return fail(c, TC_E_ARG, "too many tensors in a step");
+    }
+    const uint32_t n_ids = step_ptr[n_steps];
+    for (uint32_t i = 0; i < n_ids; ++i) {
+        if (ids[i] >= c->prof.n_tensors) return fail(c, TC_E_ARG, "unknown tensor id");
+        if (rw[i] < 1 || rw[i] > 3) return fail(c, TC_E_ARG, "rw must be TC_R, TC_W or both");
+    }
+    hipStream_t compute = (hipStream_t)compute_stream;
+    // The lists go to the device once; the decision kernel then takes a window of
+    // steps per launch.  Every launch the host waits for costs a running migration
+    // launch some link time, so a replay that knows its trace decides in windows.
+    HIP_TRY(c, hipStreamSynchronize(c->dstream));
+    HIP_TRY(c, hipMemcpy(c->d_step_ptr, step_ptr, ((size_t)n_steps + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+    if (n_ids) {
+        HIP_TRY(c, hipMemcpy(c->d_ids, ids, (size_t)n_ids * sizeof(uint32_t), hipMemcpyHostToDevice));
+        HIP_TRY(c, hipMemcpy(c->d_rw, rw, (size_t)n_ids, hipMemcpyHostToDevice));
+    }
+    for (uint32_t k0 = 0; k0 < n_steps; k0 += c->replay_window) {
+        TcWindowArgs w{};
+        w.step_ptr = c->d_step_ptr; w.ids = c->d_ids; w.rw = c->d_rw;
+        w.first = k0;
+        w.count = std::min(c->replay_window, n_steps - k0);
+        w.cap = c->dout_cap;
+        HIP_TRY(c, tc_launch_decide_window(c->T, w, c->dout, c->dops, c->dstream));
+        HIP_TRY(c, hipStreamSynchronize(c->dstream));
+        c->stats.decide_launches++;
+        const TcOpRec *ops = c->dops;
+        for (uint32_t k = k0; k < k0 + w.count; ++k) {
+            const uint32_t n = step_ptr[k + 1] - step_ptr[k];
+            const uint32_t *id = ids + step_ptr[k];
+            const uint8_t *a = rw + step_ptr[k];
+            const TcDecideOut *pre = c->dout + 2 * (k - k0), *post = pre + 1;
+            int rc = dispatch(c, pre, ops, k, TC_PRE, compute);
+            if (rc != TC_OK) return rc;
+            ops += pre->n_ops;
+            rc = finish_pre(c, pre, k, id, a, n, compute, nullptr);
+            if (rc != TC_OK) return rc;
+            rc = tc_emulate_compute(c, compute_stream, busy_ns ? busy_ns[k] : 0, measure_stall);
+            if (rc != TC_OK) return rc;
+            rc = dispatch(c, post, ops, k, TC_POST, compute);
+            if (rc != TC_OK) return rc;
+            ops += post->n_ops;
+            c->stats.cursor = post->cursor;
+        }
     }
     return tc_end_iteration(c, compute_stream);
 }
@@ -707,8 +1030,12 @@ extern "C" int tc_synchronize(tc_ctx *c)
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     HIP_TRY(c, hipStreamSynchronize(c->dstream));
     if (!c->null_mover) {
-        HIP_TRY(c, hipStreamSynchronize(c->mstream));
-        c->launch_done = c->launch_id;
+        int rc = flush_deferred(c, c->last_compute);
+        if (rc != TC_OK) return rc;
+        for (int i = 0; i < N_STREAMS; ++i) {
+            HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
+            c->op_done[i] = c->op_id;
+        }
     }
     return TC_OK;
 }
@@ -806,17 +1133,17 @@ extern "C" int tc_fill_payload(tc_ctx *c, uint32_t seed)
     for (uint32_t t = 0; t < n_t; ++t) {
         const uint32_t s = c->prof.class_of[t];
         const uint64_t n = c->prof.bytes[t];
-        if (tier[t] == TC_GPU) HIP_TRY(c, tc_launch_fill(gpu_addr(c, s, gs[t]), n, t, seed, c->mstream));
-        else if (tier[t] == TC_CPU) HIP_TRY(c, tc_launch_fill(cpu_addr(c, s, cs[t]), n, t, seed, c->mstream));
+        if (tier[t] == TC_GPU) HIP_TRY(c, tc_launch_fill(gpu_addr(c, s, gs[t]), n, t, seed, c->streams[S_K]));
+        else if (tier[t] == TC_CPU) HIP_TRY(c, tc_launch_fill(cpu_addr(c, s, cs[t]), n, t, seed, c->streams[S_K]));
         else {
             if (n > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a file-tier tensor");
-            HIP_TRY(c, tc_launch_fill(c->staging, n, t, seed, c->mstream));
-            HIP_TRY(c, hipStreamSynchronize(c->mstream));
+            HIP_TRY(c, tc_launch_fill(c->staging, n, t, seed, c->streams[S_K]));
+            HIP_TRY(c, hipStreamSynchronize(c->streams[S_K]));
             rc = file_write(c, c->staging, n, c->place.file_off[t]);
             if (rc != TC_OK) return rc;
         }
     }
-    HIP_TRY(c, hipStreamSynchronize(c->mstream));
+    HIP_TRY(c, hipStreamSynchronize(c->streams[S_K]));
     return TC_OK;
 }
 
@@ -825,30 +1152,68 @@ extern "C" int tc_set_mover(tc_ctx *c, uint32_t workgroups, uint32_t chunk_bytes
     if (!c) return TC_E_ARG;
     if (chunk_bytes && (chunk_bytes % 4096)) return fail(c, TC_E_ARG, "chunk_bytes must be a multiple of 4096");
     if (workgroups > 65536) return fail(c, TC_E_ARG, "too many workgroups");
-    c->mover_wgs = workgroups ? workgroups : 512;
+    c->mover_wgs = workgroups ? workgroups : 64;
     c->chunk_bytes = chunk_bytes ? chunk_bytes : 65536;
     return TC_OK;
 }
 
-extern "C" int tc_mover_timing(tc_ctx *c, int enable, double *avg_ns, uint64_t *n)
+static int collect_timing(tc_ctx *c, double busy_ns[N_STREAMS], uint64_t count[N_STREAMS], uint64_t bytes[N_STREAMS])
+{
+    for (int i = 0; i < N_STREAMS; ++i) { busy_ns[i] = 0; count[i] = 0; bytes[i] = 0; }
+    int rcf = flush_deferred(c, c->last_compute);
+    if (rcf != TC_OK) return rcf;
+    if (c->timed.empty()) return TC_OK;
+    for (int i = 0; i < N_STREAMS; ++i) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
+    for (auto &p : c->timed) {
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, p.t0, p.t1) == hipSuccess) {
+            busy_ns[p.kind] += (double)ms * 1e6;
+            count[p.kind]++;
+            bytes[p.kind] += p.bytes;
+        }
+        (void)hipEventDestroy(p.t0);
+        (void)hipEventDestroy(p.t1);
+    }
+    c->timed.clear();
+    return TC_OK;
+}
+
+extern "C" int tc_mover_timing(tc_ctx *c, int enable, tc_timing *out)
 {
     if (!c) return TC_E_ARG;
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
-    double total = 0;
-    uint64_t cnt = 0;
-    if (!c->timed.empty()) {
-        HIP_TRY(c, hipStreamSynchronize(c->mstream));
-        for (auto &p : c->timed) {
-            float ms = 0;
-            if (hipEventElapsedTime(&ms, p.first, p.second) == hipSuccess) { total += (double)ms * 1e6; cnt++; }
-            (void)hipEventDestroy(p.first);
-            (void)hipEventDestroy(p.second);
-        }
-        c->timed.clear();
+    double busy[N_STREAMS];
+    uint64_t cnt[N_STREAMS], bytes[N_STREAMS];
+    int rc = collect_timing(c, busy, cnt, bytes);
+    if (rc != TC_OK) return rc;
+    if (out) {
+        out->kernel_ns = busy[S_K]; out->kernel_launches = cnt[S_K]; out->kernel_bytes = bytes[S_K];
+        out->h2d_ns = busy[S_H]; out->h2d_copies = cnt[S_H]; out->h2d_bytes = bytes[S_H];
+        out->d2h_ns = busy[S_D]; out->d2h_copies = cnt[S_D]; out->d2h_bytes = bytes[S_D];
     }
-    if (avg_ns) *avg_ns = cnt ? total / (double)cnt : 0.0;
-    if (n) *n = cnt;
     c->timing = enable != 0;
+    return TC_OK;
+}
+
+extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)
+{
+    if (!c) return TC_E_ARG;
+    c->merge_bytes = bytes;
+    return TC_OK;
+}
+
+extern "C" int tc_set_replay_window(tc_ctx *c, uint32_t steps)
+{
+    if (!c) return TC_E_ARG;
+    if (steps == 0 || steps > TC_WINDOW_MAX) return fail(c, TC_E_ARG, "window must be 1 .. 256 steps");
+    c->replay_window = steps;
+    return TC_OK;
+}
+
+extern "C" int tc_set_dma_threshold(tc_ctx *c, uint64_t bytes)
+{
+    if (!c) return TC_E_ARG;
+    c->sdma_threshold = bytes;
     return TC_OK;
 }
 
@@ -859,7 +1224,7 @@ extern "C" int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream, u
                              uint32_t chunk_bytes)
 {
     if (!segs && n) return TC_E_ARG;
-    if (!workgroups) workgroups = 512;
+    if (!workgroups) workgroups = 64;
     if (!chunk_bytes) chunk_bytes = 65536;
     if (chunk_bytes % 4096) return TC_E_ARG;
     uint32_t i = 0;
@@ -876,6 +1241,42 @@ extern "C" int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream, u
             u.bytes = segs[i].bytes;
             u.chunk0 = a.n_chunks;
             a.n_chunks += (segs[i].bytes + chunk_bytes - 1) / chunk_bytes;
+        }
+        if (tc_launch_mover(a, workgroups, (hipStream_t)stream) != hipSuccess) return TC_E_HIP;
+    }
+    return TC_OK;
+}
+
+extern "C" int tc_exchange_batch(const tc_segment *out, const tc_segment *in, uint32_t n, void *stream,
+                                 uint32_t workgroups, uint32_t chunk_bytes)
+{
+    if ((!out || !in) && n) return TC_E_ARG;
+    if (!workgroups) workgroups = 64;
+    if (!chunk_bytes) chunk_bytes = 65536;
+    if (chunk_bytes % 4096) return TC_E_ARG;
+    uint32_t i = 0;
+    while (i < n) {
+        TcMoverArgs a{};
+        a.chunk_bytes = chunk_bytes;
+        for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
+            const uint64_t bytes = out[i].bytes ? out[i].bytes : in[i].bytes;
+            if (!bytes) continue;
+            if (out[i].bytes && in[i].bytes && out[i].bytes != in[i].bytes) return TC_E_ARG;
+            TcUnit &u = a.u[a.n_units];
+            if (out[i].bytes) {
+                if (!out[i].src || !out[i].dst || ((((uintptr_t)out[i].src) | ((uintptr_t)out[i].dst)) & 15)) return TC_E_ARG;
+                u.out_src = (const uint8_t *)out[i].src;
+                u.out_dst = (uint8_t *)out[i].dst;
+            }
+            if (in[i].bytes) {
+                if (!in[i].src || !in[i].dst || ((((uintptr_t)in[i].src) | ((uintptr_t)in[i].dst)) & 15)) return TC_E_ARG;
+                u.in_src = (const uint8_t *)in[i].src;
+                u.in_dst = (uint8_t *)in[i].dst;
+            }
+            u.bytes = bytes;
+            u.chunk0 = a.n_chunks;
+            a.n_chunks += (bytes + chunk_bytes - 1) / chunk_bytes;
+            a.n_units++;
         }
         if (tc_launch_mover(a, workgroups, (hipStream_t)stream) != hipSuccess) return TC_E_HIP;
     }

@@ -26,19 +26,36 @@ def compare_logs(got, want):
 
 
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
-                busy=False):
-    """Replays every iteration of wl through the library; returns the context."""
+                busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False):
+    """Replays every iteration of wl through the library; returns the context.
+
+    window None: one tc_migrate_step call per hook (the hook-driven interface);
+    otherwise tc_replay_iteration with that many steps per decision launch.
+    fill: the library's fill kernel writes the payload pattern instead of
+    tc_load_tensor (for footprints too large to generate on the host)."""
     import torch
     tc = T.TensorCache.from_workload(wl)
     tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes)
     if mover:
         tc.set_mover(*mover)
-    if payload and not null_mover:
+    if merge_bytes is not None:
+        tc.set_merge_bytes(merge_bytes)
+    if dma_threshold is not None:
+        tc.set_dma_threshold(dma_threshold)
+    if window is not None:
+        tc.set_replay_window(window)
+    if fill and not null_mover:
+        tc.fill_payload(W.PAYLOAD_SEED)
+    elif payload and not null_mover:
         for t in range(wl.n_tensors):
             tc.load_tensor(t, W.workload_payload(wl, t))
     cs = torch.cuda.Stream()
     for steps in wl.iterations:
-        tc.replay_iteration(steps, cs.cuda_stream, busy_ns=(wl.compute_ns if busy else None))
+        ns = wl.compute_ns if busy else None
+        if window is None:
+            tc.replay_iteration(steps, cs.cuda_stream, busy_ns=ns)
+        else:
+            tc.replay_iteration_c(steps, cs.cuda_stream, busy_ns=ns)
     tc.synchronize()
     torch.cuda.synchronize()
     return tc

@@ -1,0 +1,146 @@
+"""The stand-alone movers of the library on a real MI355X, byte for byte
+against the plain definitions in oracle/pack_oracle.py: LDS-staged pack and
+unpack, the batched copy and the batched exchange of the migration kernel."""
+
+import numpy as np
+import pytest
+
+import paper_2511_14124_amd as T
+from oracle import pack_oracle as po
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _layout(rng, sizes, gap_choices):
+    off, at = [], 0
+    for n in sizes:
+        at += int(rng.choice(gap_choices))
+        off.append(at)
+        at += int(n)
+    return np.asarray(off, dtype=np.uint64), at
+
+
+PACK_CASES = [
+    # (name, segment sizes, source gaps, slab gaps): sizes off 16 bytes, misaligned on both sides,
+    # segments smaller than a vector, segments spanning several 16 KiB tiles, a ragged last tile
+    ("aligned", [4096] * 37, [0], [0]),
+    ("tiny", [1, 2, 3, 15, 16, 17, 31, 33, 1, 1, 64, 5], [0, 1, 3, 7], [0]),
+    ("misaligned_both", [100, 33000, 4096, 17, 70001, 12288, 8192, 555], [1, 5, 9, 13], [0, 3, 16, 21]),
+    ("multi_tile", [16384 * 3 + 48, 16384, 16383, 16385, 200000], [2], [0]),
+    ("one_big", [5 << 20], [4], [0]),
+]
+
+
+@pytest.mark.parametrize("name,sizes,src_gaps,slab_gaps", PACK_CASES, ids=[c[0] for c in PACK_CASES])
+def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps):
+    rng = np.random.default_rng(len(sizes))
+    nb = np.asarray(sizes, dtype=np.uint64)
+    src_off, src_total = _layout(rng, sizes, src_gaps)
+    slab_off, slab_total = _layout(rng, sizes, slab_gaps)
+    slab_total += 11                                   # ragged tail no segment covers
+    src = rng.integers(0, 256, size=src_total + 16, dtype=np.uint8)
+    tensors = [src[int(o):int(o) + int(n)] for o, n in zip(src_off, nb)]
+    want = po.pack(tensors, slab_off, np.full(slab_total, 0xEE, dtype=np.uint8))
+
+    d_src = _dev(src)
+    d_slab = torch.full((slab_total,), 0xEE, dtype=torch.uint8, device="cuda:0")
+    ptrs = _dev((src_off + np.uint64(d_src.data_ptr())).astype(np.int64))
+    d_nb, d_off = _dev(nb.astype(np.int64)), _dev(slab_off.astype(np.int64))
+    st = torch.cuda.current_stream().cuda_stream
+    T.pack(d_slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_slab.cpu().numpy(), want), name
+
+    # unpack into a fresh, differently filled source image
+    d_back = torch.full((src_total + 16,), 0x55, dtype=torch.uint8, device="cuda:0")
+    ptrs2 = _dev((src_off + np.uint64(d_back.data_ptr())).astype(np.int64))
+    T.unpack(d_slab.data_ptr(), ptrs2.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st)
+    torch.cuda.synchronize()
+    got = d_back.cpu().numpy()
+    want_back = np.full(src_total + 16, 0x55, dtype=np.uint8)
+    for t, o in zip(po.unpack(want, nb, slab_off), src_off):
+        want_back[int(o):int(o) + t.size] = t
+    assert np.array_equal(got, want_back), name
+
+
+def test_pack_of_nothing_is_a_no_op():
+    d = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    T.pack(d.data_ptr(), 0, 0, 0, 0, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert int(d.sum()) == 0
+
+
+@pytest.mark.parametrize("wg,chunk", [(1, 4096), (7, 8192), (64, 65536), (512, 1 << 20)])
+def test_copy_batch_moves_every_segment(wg, chunk):
+    # sizes off the chunk and off 16 bytes; device->device, pinned->device and device->pinned
+    rng = np.random.default_rng(wg)
+    sizes = [16, 17, 4096, 70001, 262144 + 48, (1 << 20) + 3, 31] * 9      # 63 segments: two launches
+    off, at = [], 0
+    for n in sizes:
+        off.append(at)
+        at += (n + 15) // 16 * 16
+    off = np.asarray(off, dtype=np.uint64)
+    img = rng.integers(0, 256, size=at, dtype=np.uint8)
+    pinned_src = torch.from_numpy(img.copy()).pin_memory()
+    d_mid = torch.zeros(at, dtype=torch.uint8, device="cuda:0")
+    d_mid2 = torch.zeros(at, dtype=torch.uint8, device="cuda:0")
+    pinned_dst = torch.zeros(at, dtype=torch.uint8).pin_memory()
+    st = torch.cuda.current_stream().cuda_stream
+    nb = np.asarray(sizes, dtype=np.uint64)
+    for a, b in ((pinned_src, d_mid), (d_mid, d_mid2), (d_mid2, pinned_dst)):
+        T.copy_batch(off + np.uint64(a.data_ptr()), off + np.uint64(b.data_ptr()), nb, st, wg, chunk)
+    torch.cuda.synchronize()
+    want = np.zeros(at, dtype=np.uint8)
+    for o, n in zip(off, sizes):
+        want[int(o):int(o) + n] = img[int(o):int(o) + n]
+    assert np.array_equal(pinned_dst.numpy(), want)
+
+
+@pytest.mark.parametrize("wg,chunk", [(3, 4096), (64, 65536)])
+def test_exchange_batch_swaps_in_place(wg, chunk):
+    # unit i: a tensor leaves GPU buffer y_i for host buffer x_i while the tensor in x_i arrives in y_i
+    rng = np.random.default_rng(5)
+    sizes = [16, 48, 4096 + 16, 70000, 262144 + 48, 1 << 20]
+    off, at = [], 0
+    for n in sizes:
+        off.append(at)
+        at += n
+    host = rng.integers(0, 256, size=at, dtype=np.uint8)
+    gpu = rng.integers(0, 256, size=at, dtype=np.uint8)
+    # the oracle works on one flat array: [gpu image | host image]
+    mem = np.concatenate([gpu, host])
+    units = [(o, at + o, at + o, o, n) for o, n in zip(off, sizes)]
+    units[1] = (-1, 0, at + off[1], off[1], sizes[1])          # incoming half only
+    units[2] = (off[2], at + off[2], -1, 0, sizes[2])          # outgoing half only
+    want = po.exchange(mem.copy(), units)
+    d = _dev(gpu)
+    h = torch.from_numpy(host.copy()).pin_memory()
+    D, H = d.data_ptr(), h.data_ptr()
+    o64 = np.asarray(off, dtype=np.uint64)
+    out_src, out_dst = o64 + np.uint64(D), o64 + np.uint64(H)
+    in_src, in_dst = o64 + np.uint64(H), o64 + np.uint64(D)
+    out_src[1] = 0
+    in_src[2] = 0
+    T.exchange_batch(out_src, out_dst, in_src, in_dst, np.asarray(sizes, dtype=np.uint64),
+                     torch.cuda.current_stream().cuda_stream, wg, chunk)
+    torch.cuda.synchronize()
+    assert np.array_equal(d.cpu().numpy(), want[:at]) and np.array_equal(h.numpy(), want[at:])
+
+
+def test_movers_reject_bad_arguments():
+    with pytest.raises(T.TcError):
+        T.copy_batch(np.asarray([8], dtype=np.uint64), np.asarray([16], dtype=np.uint64),
+                     np.asarray([16], dtype=np.uint64))                     # misaligned pointer
+    with pytest.raises(T.TcError):
+        T.copy_batch(np.asarray([0], dtype=np.uint64), np.asarray([16], dtype=np.uint64),
+                     np.asarray([16], dtype=np.uint64))                     # null source
+    d = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(T.TcError):
+        T.copy_batch(np.asarray([d.data_ptr()], dtype=np.uint64), np.asarray([d.data_ptr() + 32], dtype=np.uint64),
+                     np.asarray([16], dtype=np.uint64), 0, 64, 1000)        # chunk not a multiple of 4096

@@ -100,3 +100,69 @@ def test_modelled_compute_does_not_change_the_schedule():
     tc = run_library(wl, busy=True)
     check_against_oracle(wl, tc)
     tc.close()
+
+
+# ---- the same schedule whatever the launch shape -----------------------------
+
+@pytest.mark.parametrize("window", [1, 3, 64, 256])
+def test_windowed_replay_equals_hook_by_hook(window, tmp_path):
+    # tc_replay_iteration decides a window of steps per launch; log, state, counters
+    # and bytes must be those of one tc_migrate_step call per hook
+    for seed in (2, 3, 8):
+        wl = W.random_workload(seed, n_tensors=36, n_steps=60, max_per_step=4,
+                               perturb_one_in=(0 if seed % 2 else 7),
+                               host_frac=(0.3 if seed % 3 else 1.2), literal=(seed % 4 == 3))
+        tc = run_library(wl, file_path=_tmpfile(tmp_path, f"w{seed}.bin"), staging_bytes=1 << 20, window=window)
+        check_against_oracle(wl, tc)
+        tc.close()
+    wl = W.config(0, layers=8)
+    tc = run_library(wl, window=window)
+    check_against_oracle(wl, tc)
+    tc.close()
+
+
+@pytest.mark.parametrize("merge_bytes", [0, 1 << 20, 1 << 30])
+def test_merging_hook_calls_into_launches_keeps_every_byte(merge_bytes, tmp_path):
+    wl = W.random_workload(11, n_tensors=120, n_steps=90, max_per_step=3, sizes=(70001, 262144 + 48, 1 << 20, 17, 4096),
+                           hbm_frac=0.1, host_frac=0.5, perturb_one_in=9)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=4 << 20, merge_bytes=merge_bytes, window=16)
+    check_against_oracle(wl, tc)
+    tc.close()
+    wl = W.config(0, layers=6)
+    tc = run_library(wl, merge_bytes=merge_bytes)
+    check_against_oracle(wl, tc)
+    tc.close()
+
+
+@pytest.mark.parametrize("threshold", [1 << 16, 1 << 20])
+def test_dma_engine_path_keeps_every_byte(threshold, tmp_path):
+    # tensors at or above the threshold leave through an HBM bounce block and two
+    # hipMemcpyAsync side streams; smaller ones stay in the migration kernel
+    wl = W.random_workload(13, n_tensors=120, n_steps=90, max_per_step=2, sizes=(70001, 262144 + 48, 1 << 20, 17, 4096),
+                           hbm_frac=0.1, host_frac=0.6, perturb_one_in=8)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=4 << 20, dma_threshold=threshold)
+    check_against_oracle(wl, tc)
+    assert tc.cache_stats()["dma_copies"] > 0
+    tc.close()
+    wl = W.config(0, layers=6)
+    tc = run_library(wl, dma_threshold=threshold, window=32)
+    check_against_oracle(wl, tc)
+    tc.close()
+
+
+def test_gpt_1p3b_config_full_size_sampled_bytes():
+    # configuration 2 at full size in the launch configuration bench.py times: 1544
+    # tensors, 19.95 GiB (17 GiB pinned, 3 GiB HBM), windowed replay, default merging.
+    # Schedule, counters and final maps are compared in full; bytes on a sample of
+    # tensors the oracle rebuilds one by one (smallest, largest, every kind, stamped ones).
+    wl = W.config(1)
+    tc = run_library(wl, fill=True, window=64)
+    kinds = wl.tensor_kind
+    order = np.argsort(wl.tensor_bytes, kind="stable")
+    sample = set(order[:6].tolist()) | set(order[-6:].tolist())
+    for k in range(6):
+        ids = np.nonzero(kinds == k)[0]
+        sample |= set(ids[:: max(1, len(ids) // 5)].tolist())
+    r = check_against_oracle(wl, tc, tensors=sorted(sample))
+    assert r.misses == 0 and any(r.stamps[t] for t in sample)
+    tc.close()
