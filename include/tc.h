@@ -162,8 +162,8 @@ typedef struct {
     uint64_t mover_units;            /* exchange units those launches carried */
     uint64_t dma_copies;             /* DMA-engine copies (large tensors) */
     uint64_t decide_launches;        /* decision-kernel launches */
-    uint64_t stall_ns;               /* time the compute stream was held back by migration (tc_emulate_compute) */
-    uint64_t waits_under_30us, waits_total;   /* share of steps waiting < 0.03 ms (Sec. 4.2.2) */
+    uint64_t stall_ns;               /* time modules waited for their tensors (tc_set_stall_measurement) */
+    uint64_t waits_under_30us, waits_total;   /* tensors that waited < 0.03 ms / tensors measured (Sec. 4.2.2) */
     uint32_t cursor;                 /* prefetch-table cursor */
     uint32_t iteration;
 } tc_stats;
@@ -251,14 +251,22 @@ int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
 /* Stand-in for the module's kernels in a replay: on compute_stream, XORs the
  * 16-byte stamp (words 0x10CAC4E5, iteration, step, tensor; little endian)
  * into the first and the last 16 bytes of every tensor the last PRE call
- * listed with TC_W, then spins for busy_ns nanoseconds.  Accumulates
- * stall_ns / waits_* when measure_stall is non-zero (synchronises). */
-int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns, int measure_stall);
+ * listed with TC_W, then spins for busy_ns nanoseconds. */
+int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns);
+
+/* Wait-time measurement (Sec. 4.2.2).  While enabled, a PRE call drains
+ * compute_stream, then waits on the host for the copy that fills each listed
+ * tensor's buffer and records how long that took: stall_ns grows by the
+ * longest wait of the call, waits_total by one per tensor, waits_under_30us
+ * by one per tensor that waited less than 0.03 ms.  Decisions are unchanged;
+ * the calls no longer overlap with the compute stream. */
+int tc_set_stall_measurement(tc_ctx *ctx, int enable);
 
 /* Replays one whole iteration whose accesses are known up front: for every
  * step the pre-hook call, tc_emulate_compute, the post-hook call, then
  * tc_end_iteration.  step_ptr: n_steps+1 offsets into ids/rw, starting at 0
- * (host arrays); busy_ns: per-step modelled compute or NULL.  Decisions, op
+ * (host arrays); busy_ns: per-step modelled compute or NULL; measure_stall: enable
+ * tc_set_stall_measurement for the duration of the call.  Decisions, op
  * log, statistics and bytes are those of the same sequence of
  * tc_migrate_step calls; the difference is that the decision kernel takes a
  * window of steps per launch (tc_set_replay_window) instead of one hook call,
@@ -286,9 +294,11 @@ int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_
  * work chunk (0 = default; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
 
-/* Hook calls are merged into one migration launch until `bytes` bytes are
- * prepared (or a prepared buffer is needed, or the file tier is involved).
- * 0 = one launch per hook call.  Default 256 MiB. */
+/* While a migration launch is still running, the copies of further hook calls
+ * are held back and merged into one launch, until `bytes` bytes are prepared,
+ * a prepared buffer is needed, or the file tier is involved; when the
+ * migration stream is idle they are issued at once.  0 = one launch per hook
+ * call.  Default 256 MiB. */
 int tc_set_merge_bytes(tc_ctx *ctx, uint64_t bytes);
 
 /* Steps decided per decision-kernel launch by tc_replay_iteration, 1 .. 256

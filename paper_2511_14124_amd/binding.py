@@ -94,7 +94,8 @@ def load_library(path: str = LIB_PATH):
         "tc_read_tensor": (i32, [vp, u32, vp]),
         "tc_migrate_step": (i32, [vp, u32, i32, vp, vp, u32, vp, vp]),
         "tc_end_iteration": (i32, [vp, vp]),
-        "tc_emulate_compute": (i32, [vp, vp, u64, i32]),
+        "tc_emulate_compute": (i32, [vp, vp, u64]),
+        "tc_set_stall_measurement": (i32, [vp, i32]),
         "tc_replay_iteration": (i32, [vp, vp, vp, vp, u32, vp, vp, i32]),
         "tc_synchronize": (i32, [vp]),
         "tc_cache_stats": (i32, [vp, C.POINTER(Stats)]),
@@ -245,8 +246,11 @@ class TensorCache:
     def end_iteration(self, compute_stream: int = 0):
         self._check(lib().tc_end_iteration(self._h, compute_stream or None))
 
-    def emulate_compute(self, compute_stream: int = 0, busy_ns: int = 0, measure_stall: bool = False):
-        self._check(lib().tc_emulate_compute(self._h, compute_stream or None, int(busy_ns), int(measure_stall)))
+    def emulate_compute(self, compute_stream: int = 0, busy_ns: int = 0):
+        self._check(lib().tc_emulate_compute(self._h, compute_stream or None, int(busy_ns)))
+
+    def set_stall_measurement(self, enable: bool):
+        self._check(lib().tc_set_stall_measurement(self._h, int(enable)))
 
     def synchronize(self):
         self._check(lib().tc_synchronize(self._h))
@@ -263,13 +267,15 @@ class TensorCache:
 
     def replay_iteration(self, steps, compute_stream: int = 0, busy_ns=None, measure_stall: bool = False):
         """PRE, stand-in compute, POST for every step, then the end-of-iteration call."""
+        self.set_stall_measurement(measure_stall)
         for k, access in enumerate(steps):
             ids = [t for (t, _a) in access]
             rw = [a for (_t, a) in access]
             self.migrate_step(k, PRE, ids, rw, compute_stream)
-            self.emulate_compute(compute_stream, 0 if busy_ns is None else int(busy_ns[k]), measure_stall)
+            self.emulate_compute(compute_stream, 0 if busy_ns is None else int(busy_ns[k]))
             self.migrate_step(k, POST, ids, rw, compute_stream)
         self.end_iteration(compute_stream)
+        self.set_stall_measurement(False)
 
     # -- introspection -----------------------------------------------------------
     def cache_stats(self) -> dict:

@@ -72,7 +72,9 @@ struct tc_ctx {
     TcDevTables T{};
     TcDecideOut *dout = nullptr;        // pinned: one record per hook call of a window, then the op records
     TcOpRec *dops = nullptr;            // (inside the same pinned block)
-    uint32_t dout_cap = 0;              // op records the block holds
+    TcDecideOut *dout2 = nullptr;       // second block: a window is decided while the one before is dispatched
+    TcOpRec *dops2 = nullptr;
+    uint32_t dout_cap = 0;              // op records a block holds
     uint32_t *d_step_ptr = nullptr;     // device copy of a replayed iteration's lists (tc_replay_iteration)
     uint32_t *d_ids = nullptr;
     uint8_t *d_rw = nullptr;
@@ -101,9 +103,10 @@ struct tc_ctx {
     uint64_t merge_bytes = 256ull << 20;
     std::vector<uint8_t> gpu_pending, cpu_pending;  // buffer is touched by a deferred unit
     hipStream_t last_compute = nullptr;
+    uint64_t last_k_op = 0;             // newest operation issued on the migration stream
+    bool measure_stall = false;         // pre-hook calls time the wait for their copies on the host
     // last PRE call, for tc_emulate_compute
     TcStampArgs last_pre{};
-    std::vector<uint64_t> last_pre_tickets;
     uint32_t iteration = 0;
 
     // timing of migration launches and DMA copies
@@ -320,10 +323,13 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     // tensor at most a spill, an eviction and a fetch)
     c->dout_cap = std::max<uint32_t>(3 * n_t + 64, TC_WINDOW_MAX * 2 * 3 * TC_MAX_STEP_TENSORS);
     const size_t rec_bytes = (size_t)2 * TC_WINDOW_MAX * sizeof(TcDecideOut);
-    e = hipHostMalloc((void **)&c->dout, rec_bytes + (size_t)c->dout_cap * sizeof(TcOpRec), hipHostMallocDefault);
+    const size_t blk_bytes = (rec_bytes + (size_t)c->dout_cap * sizeof(TcOpRec) + 255) & ~(size_t)255;
+    e = hipHostMalloc((void **)&c->dout, 2 * blk_bytes, hipHostMallocDefault);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
-    memset(c->dout, 0, rec_bytes);
+    memset(c->dout, 0, 2 * blk_bytes);
     c->dops = (TcOpRec *)((uint8_t *)c->dout + rec_bytes);
+    c->dout2 = (TcDecideOut *)((uint8_t *)c->dout + blk_bytes);
+    c->dops2 = (TcOpRec *)((uint8_t *)c->dout2 + rec_bytes);
     e = hipMalloc((void **)&c->d_step_ptr, ((size_t)p.n_steps + 1) * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_ids, std::max<size_t>(1, (size_t)p.n_steps * TC_MAX_STEP_TENSORS) * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_rw, std::max<size_t>(1, (size_t)p.n_steps * TC_MAX_STEP_TENSORS));
@@ -336,19 +342,6 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     }
     e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
-    if (!null_mover) {
-        for (int i = S_H; i < N_STREAMS; ++i) {
-            e = hipStreamCreateWithFlags(&c->streams[i], hipStreamNonBlocking);
-            if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
-        }
-        // bounce ring in HBM: room for four of the largest tensors, 64 MiB .. 2 GiB
-        uint64_t largest = 0;
-        for (uint32_t k = 0; k < n_c; ++k) largest = std::max(largest, pl.stride[k]);
-        c->bounce_bytes = std::min<uint64_t>(std::max<uint64_t>(4 * largest, 64ull << 20), 2048ull << 20);
-        e = hipMalloc((void **)&c->bounce, c->bounce_bytes);
-        if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
-    }
-
     c->hbm = (uint8_t *)hbm; c->hbm_bytes = hbm_bytes;
     c->pinned = (uint8_t *)pinned; c->pinned_bytes = pinned_bytes;
     c->staging = (uint8_t *)staging; c->staging_bytes = staging_bytes;
@@ -394,6 +387,16 @@ static int wait_op(tc_ctx *c, uint64_t id)
     HIP_TRY(c, hipEventSynchronize(c->op_ev[id % OP_RING]));
     c->op_done[st] = std::max(c->op_done[st], id);
     return TC_OK;
+}
+
+// has operation `id` completed?  (asks the runtime, without blocking)
+static bool poll_op(tc_ctx *c, uint64_t id)
+{
+    if (op_complete(c, id)) return true;
+    if (hipEventQuery(c->op_ev[id % OP_RING]) != hipSuccess) return false;
+    const uint32_t st = c->op_stream[id % OP_RING];
+    c->op_done[st] = std::max(c->op_done[st], id);
+    return true;
 }
 
 // make stream S wait for operation `id` (nothing to do if it ran on S or is done)
@@ -590,6 +593,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         HIP_TRY(c, tc_launch_mover(args, c->mover_wgs, c->streams[S_K]));
         if ((rc = timed_end(c, S_K, t0, bytes)) != TC_OK) return rc;
         if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
+        c->last_k_op = id;
         c->stats.mover_launches++;
         c->stats.mover_units += args.n_units;
         for (size_t k = at; k < end; ++k) {
@@ -840,8 +844,8 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
     }
     if (c->null_mover) return TC_OK;
     if (!must_issue && phase < TC_END && c->deferred_bytes < c->merge_bytes &&
-        units.size() < 4 * TC_MOVER_MAX_UNITS)
-        return TC_OK;                                  // keep them for a larger launch
+        units.size() < 4 * TC_MOVER_MAX_UNITS && !poll_op(c, c->last_k_op))
+        return TC_OK;                                  // the link is busy: keep them for a larger launch
     int rc = issue_units(c, units, compute);
     if (rc != TC_OK) return rc;
     return drain_pending(c);
@@ -868,13 +872,20 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
     sa = TcStampArgs{};
     sa.iteration = c->iteration;
     sa.step = step;
-    c->last_pre_tickets.clear();
     for (uint32_t i = 0; i < n && !c->null_mover; ++i)
         if (o->slots[i] != TC_NONE && c->gpu_pending[c->pools.gpu_base[c->prof.class_of[ids[i]]] + o->slots[i]]) {
             int rc = flush_deferred(c, compute);          // its copy has to be on its way before the module runs
             if (rc != TC_OK) return rc;
             break;
         }
+    std::chrono::steady_clock::time_point t0;
+    uint64_t waited_ns = 0;
+    if (c->measure_stall && !c->null_mover) {
+        // wait time as the paper measures it (Sec. 4.2.2): once the modules queued so
+        // far have finished, how long until each tensor of this one is in its buffer
+        HIP_TRY(c, hipStreamSynchronize(compute));
+        t0 = std::chrono::steady_clock::now();
+    }
     for (uint32_t i = 0; i < n; ++i) {
         const uint32_t t = ids[i], s = c->prof.class_of[t];
         uint8_t *ptr = nullptr;
@@ -884,8 +895,15 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
                 ptr = gpu_addr(c, s, o->slots[i]);
                 // the module's kernels wait only for the copies that fill ITS buffers
                 const uint64_t ticket = c->gpu_ticket[c->pools.gpu_base[s] + o->slots[i]];
-                if (!op_complete(c, ticket)) {
-                    c->last_pre_tickets.push_back(ticket);
+                if (c->measure_stall) {
+                    int rc = wait_op(c, ticket);
+                    if (rc != TC_OK) return rc;
+                    const uint64_t ns = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                                            std::chrono::steady_clock::now() - t0).count();
+                    waited_ns = std::max(waited_ns, ns);
+                    c->stats.waits_total++;
+                    if (ns < 30000) c->stats.waits_under_30us++;
+                } else if (!op_complete(c, ticket)) {
                     HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
                 }
             }
@@ -898,6 +916,7 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
             sa.n++;
         }
     }
+    c->stats.stall_ns += waited_ns;
     return TC_OK;
 }
 
@@ -941,31 +960,25 @@ extern "C" int tc_end_iteration(tc_ctx *c, void *compute_stream)
     return TC_OK;
 }
 
-extern "C" int tc_emulate_compute(tc_ctx *c, void *compute_stream, uint64_t busy_ns, int measure_stall)
+extern "C" int tc_emulate_compute(tc_ctx *c, void *compute_stream, uint64_t busy_ns)
 {
     if (!c) return TC_E_ARG;
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
-    hipStream_t compute = (hipStream_t)compute_stream;
     TcStampArgs sa = c->last_pre;
     sa.busy_ns = busy_ns;
-    if (measure_stall) {
-        // stall = how long the copies this step depends on outlast the compute
-        // already queued: drain compute, then time the wait for the ticket
-        HIP_TRY(c, hipStreamSynchronize(compute));
-        auto t0 = std::chrono::steady_clock::now();
-        for (uint64_t ticket : c->last_pre_tickets) {
-            int rc = wait_op(c, ticket);
-            if (rc != TC_OK) return rc;
-        }
-        uint64_t ns = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
-                          std::chrono::steady_clock::now() - t0).count();
-        c->stats.stall_ns += ns;
-        c->stats.waits_total++;
-        if (ns < 30000) c->stats.waits_under_30us++;
-    }
-    if (sa.n || busy_ns) HIP_TRY(c, tc_launch_stamp(sa, compute));
+    if (sa.n || busy_ns) HIP_TRY(c, tc_launch_stamp(sa, (hipStream_t)compute_stream));
     return TC_OK;
 }
+
+extern "C" int tc_set_stall_measurement(tc_ctx *c, int enable)
+{
+    if (!c) return TC_E_ARG;
+    c->measure_stall = enable != 0;
+    return TC_OK;
+}
+
+static int replay_windows(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *ids, const uint8_t *rw,
+                          uint32_t n_steps, void *compute_stream, const uint64_t *busy_ns);
 
 extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *ids, const uint8_t *rw,
                                    uint32_t n_steps, void *compute_stream, const uint64_t *busy_ns, int measure_stall)
@@ -983,37 +996,65 @@ extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const ui
         if (ids[i] >= c->prof.n_tensors) return fail(c, TC_E_ARG, "unknown tensor id");
         if (rw[i] < 1 || rw[i] > 3) return fail(c, TC_E_ARG, "rw must be TC_R, TC_W or both");
     }
+    const bool saved = c->measure_stall;
+    c->measure_stall = saved || measure_stall != 0;
+    int rc = replay_windows(c, step_ptr, ids, rw, n_steps, compute_stream, busy_ns);
+    c->measure_stall = saved;
+    if (rc != TC_OK) return rc;
+    return tc_end_iteration(c, compute_stream);
+}
+
+static int replay_windows(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *ids, const uint8_t *rw,
+                          uint32_t n_steps, void *compute_stream, const uint64_t *busy_ns)
+{
     hipStream_t compute = (hipStream_t)compute_stream;
+    const uint32_t n_ids = step_ptr[n_steps];
     // The lists go to the device once; the decision kernel then takes a window of
     // steps per launch.  Every launch the host waits for costs a running migration
-    // launch some link time, so a replay that knows its trace decides in windows.
+    // launch some link time, so a replay that knows its trace decides in windows,
+    // and window i+1 is decided (into the second result block) while window i is
+    // dispatched.
     HIP_TRY(c, hipStreamSynchronize(c->dstream));
     HIP_TRY(c, hipMemcpy(c->d_step_ptr, step_ptr, ((size_t)n_steps + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
     if (n_ids) {
         HIP_TRY(c, hipMemcpy(c->d_ids, ids, (size_t)n_ids * sizeof(uint32_t), hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(c->d_rw, rw, (size_t)n_ids, hipMemcpyHostToDevice));
     }
-    for (uint32_t k0 = 0; k0 < n_steps; k0 += c->replay_window) {
+    auto launch = [&](uint32_t k0, uint32_t blk) -> int {
         TcWindowArgs w{};
         w.step_ptr = c->d_step_ptr; w.ids = c->d_ids; w.rw = c->d_rw;
         w.first = k0;
         w.count = std::min(c->replay_window, n_steps - k0);
         w.cap = c->dout_cap;
-        HIP_TRY(c, tc_launch_decide_window(c->T, w, c->dout, c->dops, c->dstream));
-        HIP_TRY(c, hipStreamSynchronize(c->dstream));
+        HIP_TRY(c, tc_launch_decide_window(c->T, w, blk ? c->dout2 : c->dout, blk ? c->dops2 : c->dops, c->dstream));
         c->stats.decide_launches++;
-        const TcOpRec *ops = c->dops;
-        for (uint32_t k = k0; k < k0 + w.count; ++k) {
+        return TC_OK;
+    };
+    uint32_t blk = 0;
+    if (n_steps) {
+        int rc = launch(0, 0);
+        if (rc != TC_OK) return rc;
+    }
+    for (uint32_t k0 = 0; k0 < n_steps; k0 += c->replay_window, blk ^= 1) {
+        const uint32_t count = std::min(c->replay_window, n_steps - k0);
+        HIP_TRY(c, hipStreamSynchronize(c->dstream));
+        if (k0 + count < n_steps) {
+            int rc = launch(k0 + count, blk ^ 1);
+            if (rc != TC_OK) return rc;
+        }
+        const TcDecideOut *recs = blk ? c->dout2 : c->dout;
+        const TcOpRec *ops = blk ? c->dops2 : c->dops;
+        for (uint32_t k = k0; k < k0 + count; ++k) {
             const uint32_t n = step_ptr[k + 1] - step_ptr[k];
             const uint32_t *id = ids + step_ptr[k];
             const uint8_t *a = rw + step_ptr[k];
-            const TcDecideOut *pre = c->dout + 2 * (k - k0), *post = pre + 1;
+            const TcDecideOut *pre = recs + 2 * (k - k0), *post = pre + 1;
             int rc = dispatch(c, pre, ops, k, TC_PRE, compute);
             if (rc != TC_OK) return rc;
             ops += pre->n_ops;
             rc = finish_pre(c, pre, k, id, a, n, compute, nullptr);
             if (rc != TC_OK) return rc;
-            rc = tc_emulate_compute(c, compute_stream, busy_ns ? busy_ns[k] : 0, measure_stall);
+            rc = tc_emulate_compute(c, compute_stream, busy_ns ? busy_ns[k] : 0);
             if (rc != TC_OK) return rc;
             rc = dispatch(c, post, ops, k, TC_POST, compute);
             if (rc != TC_OK) return rc;
@@ -1021,7 +1062,7 @@ extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const ui
             c->stats.cursor = post->cursor;
         }
     }
-    return tc_end_iteration(c, compute_stream);
+    return TC_OK;
 }
 
 extern "C" int tc_synchronize(tc_ctx *c)
@@ -1033,7 +1074,7 @@ extern "C" int tc_synchronize(tc_ctx *c)
         int rc = flush_deferred(c, c->last_compute);
         if (rc != TC_OK) return rc;
         for (int i = 0; i < N_STREAMS; ++i) {
-            HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
+            if (i == S_K || c->streams[i]) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
             c->op_done[i] = c->op_id;
         }
     }
@@ -1163,7 +1204,8 @@ static int collect_timing(tc_ctx *c, double busy_ns[N_STREAMS], uint64_t count[N
     int rcf = flush_deferred(c, c->last_compute);
     if (rcf != TC_OK) return rcf;
     if (c->timed.empty()) return TC_OK;
-    for (int i = 0; i < N_STREAMS; ++i) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
+    for (int i = 0; i < N_STREAMS; ++i)
+        if (i == S_K || c->streams[i]) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
     for (auto &p : c->timed) {
         float ms = 0;
         if (hipEventElapsedTime(&ms, p.t0, p.t1) == hipSuccess) {
@@ -1213,6 +1255,21 @@ extern "C" int tc_set_replay_window(tc_ctx *c, uint32_t steps)
 extern "C" int tc_set_dma_threshold(tc_ctx *c, uint64_t bytes)
 {
     if (!c) return TC_E_ARG;
+    if (bytes && c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
+    if (bytes && c->null_mover) return fail(c, TC_E_STATE, "no copies are made in this context");
+    if (bytes && !c->bounce) {
+        // The side streams and the bounce ring exist only once this path is asked
+        // for: every stream a process holds is mapped onto a few hardware queues,
+        // and an idle stream of ours could push the caller's compute stream onto
+        // the queue the migration launches run on.
+        for (int i = S_H; i < N_STREAMS; ++i)
+            if (!c->streams[i]) HIP_TRY(c, hipStreamCreateWithFlags(&c->streams[i], hipStreamNonBlocking));
+        // bounce ring in HBM: room for four of the largest tensors, 64 MiB .. 2 GiB
+        uint64_t largest = 0;
+        for (uint64_t st : c->pools.stride) largest = std::max(largest, st);
+        c->bounce_bytes = std::min<uint64_t>(std::max<uint64_t>(4 * largest, 64ull << 20), 2048ull << 20);
+        HIP_TRY(c, hipMalloc((void **)&c->bounce, c->bounce_bytes));
+    }
     c->sdma_threshold = bytes;
     return TC_OK;
 }
