@@ -351,15 +351,30 @@ int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream,
 int tc_exchange_batch(const tc_segment *out, const tc_segment *in, uint32_t n, void *stream,
                       uint32_t workgroups, uint32_t chunk_bytes);
 
-/* Pack: gathers n small tensors (device pointers, any alignment) into one
- * contiguous device slab, segment i at slab_off[i]; unpack is the reverse.
- * LDS-staged so both the reads and the writes are 128-bit and coalesced even
- * when source and destination are misaligned against each other.
- * ptrs, bytes, slab_off: device arrays of n entries.  Asynchronous. */
+/* Pack: gathers n small tensors (device pointers, any alignment, any size)
+ * into one contiguous device slab, segment i at slab_off[i]; unpack is the
+ * reverse.  Segments must be sorted by slab_off and must not overlap; bytes of
+ * the slab (pack) or of a tensor (unpack) that no segment covers are not
+ * written.  The slab is processed in 16 KiB tiles, one workgroup each.  When a
+ * tile's pieces begin and end on 16-byte boundaries of the slab and each
+ * tensor address agrees with its slab address modulo 16 (pool buffers are
+ * 256-byte aligned), the tile moves register to register with all its loads
+ * in flight at once; otherwise it is staged in LDS so that both the reads and
+ * the writes are still 128-bit and coalesced although source and destination
+ * are misaligned against each other.
+ *   slab        device, 16-byte aligned, total_bytes long
+ *   ptrs, bytes, slab_off   device arrays of n entries
+ *   tile_first  device array of tc_pack_tiles(total_bytes) entries written by
+ *               tc_pack_index for this slab_off / total_bytes, or NULL (each
+ *               workgroup then bisects slab_off itself: correct but slower).
+ *               A layout that repeats every iteration is indexed once.
+ * All three calls are asynchronous on stream and allocate nothing. */
+uint64_t tc_pack_tiles(uint64_t total_bytes);
+int tc_pack_index(const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, uint32_t *tile_first, void *stream);
 int tc_pack(void *slab, const void *const *ptrs, const uint64_t *bytes,
-            const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, void *stream);
+            const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, const uint32_t *tile_first, void *stream);
 int tc_unpack(const void *slab, void *const *ptrs, const uint64_t *bytes,
-              const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, void *stream);
+              const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, const uint32_t *tile_first, void *stream);
 
 #ifdef __cplusplus
 }

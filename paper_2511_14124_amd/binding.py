@@ -108,8 +108,10 @@ def load_library(path: str = LIB_PATH):
         "tc_set_replay_window": (i32, [vp, u32]),
         "tc_copy_batch": (i32, [vp, u32, vp, u32, u32]),
         "tc_exchange_batch": (i32, [vp, vp, u32, vp, u32, u32]),
-        "tc_pack": (i32, [vp, vp, vp, vp, u32, u64, vp]),
-        "tc_unpack": (i32, [vp, vp, vp, vp, u32, u64, vp]),
+        "tc_pack_tiles": (u64, [u64]),
+        "tc_pack_index": (i32, [vp, u32, u64, vp, vp]),
+        "tc_pack": (i32, [vp, vp, vp, vp, u32, u64, vp, vp]),
+        "tc_unpack": (i32, [vp, vp, vp, vp, u32, u64, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -353,13 +355,27 @@ def exchange_batch(out_src, out_dst, in_src, in_dst, nbytes, stream: int = 0, wo
         raise TcError(rc)
 
 
-def pack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, stream: int = 0):
-    rc = lib().tc_pack(slab_ptr, ptrs_dev, bytes_dev, off_dev, n, total, stream or None)
+def pack_tiles(total: int) -> int:
+    return int(lib().tc_pack_tiles(int(total)))
+
+
+def pack_index(off_dev: int, n: int, total: int, tile_first_dev: int, stream: int = 0):
+    rc = lib().tc_pack_index(off_dev or None, n, total, tile_first_dev or None, stream or None)
     if rc:
         raise TcError(rc)
 
 
-def unpack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, stream: int = 0):
-    rc = lib().tc_unpack(slab_ptr, ptrs_dev, bytes_dev, off_dev, n, total, stream or None)
+def pack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, stream: int = 0,
+         tile_first_dev: int = 0):
+    rc = lib().tc_pack(slab_ptr or None, ptrs_dev or None, bytes_dev or None, off_dev or None, n, total,
+                       tile_first_dev or None, stream or None)
+    if rc:
+        raise TcError(rc)
+
+
+def unpack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, stream: int = 0,
+           tile_first_dev: int = 0):
+    rc = lib().tc_unpack(slab_ptr or None, ptrs_dev or None, bytes_dev or None, off_dev or None, n, total,
+                         tile_first_dev or None, stream or None)
     if rc:
         raise TcError(rc)

@@ -142,5 +142,7 @@ hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, 
 hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_t s);
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s);
 hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t seed, hipStream_t s);
-hipError_t tc_launch_pack(void *slab, const void *const *ptrs, const uint64_t *bytes,
-                          const uint64_t *slab_off, uint32_t n, uint64_t total, int unpack, hipStream_t s);
+uint64_t tc_pack_tile_count(uint64_t total);
+hipError_t tc_launch_pack_index(const uint64_t *slab_off, uint32_t n, uint64_t total, uint32_t *tile_first, hipStream_t s);
+hipError_t tc_launch_pack(void *slab, const void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
+                          uint32_t n, uint64_t total, int unpack, const uint32_t *tile_first, hipStream_t s);

@@ -1340,19 +1340,28 @@ extern "C" int tc_exchange_batch(const tc_segment *out, const tc_segment *in, ui
     return TC_OK;
 }
 
+extern "C" uint64_t tc_pack_tiles(uint64_t total_bytes) { return tc_pack_tile_count(total_bytes); }
+
+extern "C" int tc_pack_index(const uint64_t *slab_off, uint32_t n, uint64_t total, uint32_t *tile_first, void *stream)
+{
+    if ((!slab_off || !tile_first) && n && total) return TC_E_ARG;
+    return tc_launch_pack_index(slab_off, n, total, tile_first, (hipStream_t)stream) == hipSuccess ? TC_OK : TC_E_HIP;
+}
+
 extern "C" int tc_pack(void *slab, const void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
-                       uint32_t n, uint64_t total, void *stream)
+                       uint32_t n, uint64_t total, const uint32_t *tile_first, void *stream)
 {
     if ((!slab || !ptrs || !bytes || !slab_off) && n) return TC_E_ARG;
     if ((uintptr_t)slab & 15) return TC_E_ARG;
-    return tc_launch_pack(slab, ptrs, bytes, slab_off, n, total, 0, (hipStream_t)stream) == hipSuccess ? TC_OK : TC_E_HIP;
+    return tc_launch_pack(slab, ptrs, bytes, slab_off, n, total, 0, tile_first, (hipStream_t)stream) == hipSuccess
+               ? TC_OK : TC_E_HIP;
 }
 
 extern "C" int tc_unpack(const void *slab, void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
-                         uint32_t n, uint64_t total, void *stream)
+                         uint32_t n, uint64_t total, const uint32_t *tile_first, void *stream)
 {
     if ((!slab || !ptrs || !bytes || !slab_off) && n) return TC_E_ARG;
     if ((uintptr_t)slab & 15) return TC_E_ARG;
-    return tc_launch_pack((void *)slab, (const void *const *)ptrs, bytes, slab_off, n, total, 1,
+    return tc_launch_pack((void *)slab, (const void *const *)ptrs, bytes, slab_off, n, total, 1, tile_first,
                           (hipStream_t)stream) == hipSuccess ? TC_OK : TC_E_HIP;
 }

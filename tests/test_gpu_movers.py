@@ -34,11 +34,18 @@ PACK_CASES = [
     ("misaligned_both", [100, 33000, 4096, 17, 70001, 12288, 8192, 555], [1, 5, 9, 13], [0, 3, 16, 21]),
     ("multi_tile", [16384 * 3 + 48, 16384, 16383, 16385, 200000], [2], [0]),
     ("one_big", [5 << 20], [4], [0]),
+    # 256-byte aligned buffers with padding between them (pool strides): the register path, gaps kept
+    ("pool_strides", [1536, 4096, 12288, 3072, 24576, 512, 16384 * 2, 768] * 6, [0, 256, 1024], [0, 256]),
+    # more than 32 pieces in a tile: falls back to the piece-by-piece path
+    ("many_small_aligned", [256] * 200 + [4096] * 5, [0], [0]),
+    # aligned and misaligned pieces mixed, tile by tile
+    ("mixed", [4096] * 9 + [100] + [4096] * 7 + [8192, 33, 16384, 16384], [0], [0]),
 ]
 
 
+@pytest.mark.parametrize("indexed", [False, True], ids=["bisect", "indexed"])
 @pytest.mark.parametrize("name,sizes,src_gaps,slab_gaps", PACK_CASES, ids=[c[0] for c in PACK_CASES])
-def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps):
+def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps, indexed):
     rng = np.random.default_rng(len(sizes))
     nb = np.asarray(sizes, dtype=np.uint64)
     src_off, src_total = _layout(rng, sizes, src_gaps)
@@ -53,14 +60,19 @@ def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps):
     ptrs = _dev((src_off + np.uint64(d_src.data_ptr())).astype(np.int64))
     d_nb, d_off = _dev(nb.astype(np.int64)), _dev(slab_off.astype(np.int64))
     st = torch.cuda.current_stream().cuda_stream
-    T.pack(d_slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st)
+    index = 0
+    if indexed:
+        d_index = torch.full((T.pack_tiles(slab_total),), -1, dtype=torch.int32, device="cuda:0")
+        T.pack_index(d_off.data_ptr(), len(sizes), slab_total, d_index.data_ptr(), st)
+        index = d_index.data_ptr()
+    T.pack(d_slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st, index)
     torch.cuda.synchronize()
     assert np.array_equal(d_slab.cpu().numpy(), want), name
 
     # unpack into a fresh, differently filled source image
     d_back = torch.full((src_total + 16,), 0x55, dtype=torch.uint8, device="cuda:0")
     ptrs2 = _dev((src_off + np.uint64(d_back.data_ptr())).astype(np.int64))
-    T.unpack(d_slab.data_ptr(), ptrs2.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st)
+    T.unpack(d_slab.data_ptr(), ptrs2.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st, index)
     torch.cuda.synchronize()
     got = d_back.cpu().numpy()
     want_back = np.full(src_total + 16, 0x55, dtype=np.uint8)
@@ -71,6 +83,7 @@ def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps):
 
 def test_pack_of_nothing_is_a_no_op():
     d = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    assert T.pack_tiles(0) == 0 and T.pack_tiles(1) == 1 and T.pack_tiles(16384) == 1 and T.pack_tiles(16385) == 2
     T.pack(d.data_ptr(), 0, 0, 0, 0, 0, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert int(d.sum()) == 0
