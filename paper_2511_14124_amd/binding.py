@@ -145,7 +145,18 @@ class TensorCache:
         if self._h:
             lib().tc_destroy(self._h)
             self._h = C.c_void_p()
-        self._keep = []
+        if getattr(self, "_fd", -1) >= 0:
+            os.close(self._fd)
+            self._fd = -1
+        if self._keep:
+            # regions bind_torch allocated: hand them back to the system, not to
+            # PyTorch's caches (a pinned region can be tens of GiB)
+            self._keep = []
+            self.hbm = self.pinned = self.staging = self.mstream = None
+            import torch
+            torch.cuda.empty_cache()
+            if hasattr(torch._C, "_host_emptyCache"):
+                torch._C._host_emptyCache()
 
     def __del__(self):
         try:

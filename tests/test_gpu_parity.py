@@ -166,3 +166,52 @@ def test_gpt_1p3b_config_full_size_sampled_bytes():
     r = check_against_oracle(wl, tc, tensors=sorted(sample))
     assert r.misses == 0 and any(r.stamps[t] for t in sample)
     tc.close()
+
+
+def _sample(wl, r, per_kind=4, extremes=4):
+    kinds = wl.tensor_kind
+    order = np.argsort(wl.tensor_bytes, kind="stable")
+    sample = set(order[:extremes].tolist()) | set(order[-extremes:].tolist())
+    for k in range(6):
+        ids = np.nonzero(kinds == k)[0]
+        if len(ids):
+            sample |= set(ids[:: max(1, len(ids) // per_kind)].tolist())
+    # tensors that ended on every tier, and some that were written
+    for tier in (0, 1, 2):
+        on = [t for t in range(wl.n_tensors) if r.cur[t] == tier]
+        sample |= set(on[:: max(1, len(on) // per_kind)])
+    return sorted(sample)
+
+
+def test_llama_7b_config_full_size_sampled_bytes():
+    # configuration 3 at full size: 1525 tensors, 100.4 GiB (40 GiB HBM cache, 60.6 GiB pinned),
+    # three iterations replayed from the profile of the first, 363 GiB moved each way
+    wl = W.config(2)
+    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30)
+    from oracle import tc_oracle as o
+    r0 = o.replay_workload(wl)
+    r = check_against_oracle(wl, tc, tensors=_sample(wl, r0, per_kind=3, extremes=3))
+    assert r.misses == 0 and r.iteration == 3
+    tc.close()
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_file_tier_configs_at_two_layers_full_bytes(index, tmp_path):
+    # configurations 4 and 5 at their real tensor sizes (10 KiB norms to 270 / 455 MiB fp32
+    # matrices) but two layers deep, so that pinned pools and the file tier fit the box:
+    # optimizer states on the file tier (4), scarce host pools with spills and 1 % of the
+    # accesses perturbed (5).  Schedule, counters and maps in full; bytes of every tensor
+    # under 1 MiB and of a sample of the large ones over all kinds and final tiers.
+    wl = W.config(index, layers=2)
+    big = int(wl.tensor_bytes.max())
+    tc = run_library(wl, fill=True, window=64, file_path=_tmpfile(tmp_path),
+                     staging_bytes=4 * ((big + 4095) // 4096 * 4096))
+    from oracle import tc_oracle as o
+    r0 = o.replay_workload(wl)
+    small = [t for t in range(wl.n_tensors) if wl.tensor_bytes[t] < (1 << 20)]
+    r = check_against_oracle(wl, tc, tensors=sorted(set(small) | set(_sample(wl, r0, per_kind=3, extremes=2))))
+    st = tc.cache_stats()
+    assert st["bytes_file_read"] > 0 and st["bytes_file_write"] > 0
+    if index == 4:
+        assert r.misses > 0
+    tc.close()
