@@ -215,3 +215,53 @@ def test_file_tier_configs_at_two_layers_full_bytes(index, tmp_path):
     if index == 4:
         assert r.misses > 0
     tc.close()
+
+
+def test_pre_hook_returns_the_buffers_the_oracle_names():
+    # dev_ptrs_out of every PRE call = HBM region + class offset + buffer * stride of the
+    # oracle's (class, buffer) for that access; and the bytes found there are the tensor's
+    from oracle import tc_oracle as o
+    wl = W.random_workload(21, n_tensors=60, n_steps=50, max_per_step=3, hbm_frac=0.15, host_frac=1.5,
+                           two_groups=True, perturb_one_in=6, n_iterations=1)
+    st, te, rw, _ = wl.events()
+    r = o.build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw, wl.hbm_bytes, wl.host_bytes,
+                wl.align, wl.literal_alg2)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch()
+    for t in range(wl.n_tensors):
+        tc.load_tensor(t, W.workload_payload(wl, t))
+    cs = torch.cuda.Stream()
+    base = tc.hbm.data_ptr()
+    for k, access in enumerate(wl.iterations[0]):
+        ids = [t for (t, _a) in access]
+        flags = [a for (_t, a) in access]
+        ptrs = tc.migrate_step(k, T.PRE, ids, flags, cs.cuda_stream, want_ptrs=True)
+        want = r.pre(k, access)
+        for (t, _a), p, w in zip(access, ptrs, want):
+            if w is None:
+                assert p == 0
+                continue
+            s, slot = w
+            assert p == base + int(tc.classes["hbm_off"][s]) + slot * int(tc.classes["stride"][s])
+        # what a module would read through the pointer (after the stream wait the call queued)
+        cs.synchronize()
+        tc.synchronize()
+        t0, p0 = ids[0], ptrs[0]
+        if p0:
+            n = int(wl.tensor_bytes[t0])
+            off = p0 - base
+            got = tc.hbm[off:off + n].cpu().numpy()
+            stamps = [x for x in r.stamps[t0] if x != (r.iteration, k)]     # this step's stamp comes after PRE
+            want_bytes = np.array(W.workload_payload(wl, t0), dtype=np.uint8, copy=True)
+            for (it, step) in stamps:
+                o.apply_stamp(want_bytes, o.stamp16(it, step, t0))
+            assert np.array_equal(got, want_bytes), (k, t0)
+        tc.emulate_compute(cs.cuda_stream)
+        tc.migrate_step(k, T.POST, ids, flags, cs.cuda_stream)
+        r.post(k, ids)
+    tc.end_iteration(cs.cuda_stream)
+    r.end_iteration()
+    tc.synchronize()
+    tier, gs, cslot = tc.dump_state()
+    assert tier.tolist() == r.cur and gs.tolist() == r.gslot and cslot.tolist() == r.cslot
+    tc.close()
