@@ -74,6 +74,7 @@ extern "C" {
 
 /* tc_bind_memory flags */
 #define TC_BIND_NULL_MOVER 1u        /* decide and log only; no region needed, no byte moves */
+#define TC_BIND_FILE_DIRECT 2u       /* file_fd was opened with O_DIRECT: all file I/O is 4 KiB aligned */
 
 typedef struct tc_ctx tc_ctx;        /* opaque, library-owned */
 
@@ -158,6 +159,7 @@ typedef struct {
     uint64_t bytes_h2d;              /* bytes copied into HBM (from pinned buffers or file staging) */
     uint64_t bytes_d2h;              /* bytes copied HBM -> pinned buffers */
     uint64_t bytes_file_read, bytes_file_write;
+    uint64_t file_read_ns, file_write_ns;     /* host time inside file-tier reads / writes */
     uint64_t mover_launches;         /* migration-kernel launches */
     uint64_t mover_units;            /* exchange units those launches carried */
     uint64_t dma_copies;             /* DMA-engine copies (large tensors) */
@@ -202,7 +204,14 @@ int tc_plan_schedule(tc_ctx *ctx, tc_placement *out);
  *   staging        pinned bounce buffer for the file tier (may be NULL with
  *                  staging_bytes 0 if no tensor ever touches the file tier;
  *                  otherwise at least twice the largest tensor)
- *   file_fd        open read/write file of >= plan.file_total bytes, or -1
+ *   file_fd        open read/write file of >= plan.file_total bytes, or -1.
+ *                  With TC_BIND_FILE_DIRECT (a file opened with O_DIRECT, to
+ *                  bypass the page cache) every request is 4 KiB aligned in
+ *                  memory, offset and length and goes through a page-aligned
+ *                  bounce block of the library's own (direct I/O cannot
+ *                  target GPU-mapped pinned memory); staging must then be
+ *                  4 KiB aligned and sized.  File I/O is synchronous in the
+ *                  calling thread.
  *   migrate_stream hipStream_t the copies are issued on (default priority)
  * With TC_BIND_NULL_MOVER no bytes move and the regions may be NULL: the
  * decision kernel still runs and the op log, stats and state are exact. */

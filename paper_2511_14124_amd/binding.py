@@ -16,6 +16,7 @@ PRE, POST, END, END_CPU = 0, 1, 2, 3
 OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL"]
 LITERAL_ALG2 = 1
 BIND_NULL_MOVER = 1
+BIND_FILE_DIRECT = 2
 NONE = 0xFFFFFFFF
 MAX_STEP_TENSORS = 16
 
@@ -48,6 +49,7 @@ class Stats(C.Structure):
     _fields_ = [("hits", C.c_uint64), ("misses", C.c_uint64), ("fails", C.c_uint64), ("n_ops", C.c_uint64 * 8),
                 ("bytes_h2d", C.c_uint64), ("bytes_d2h", C.c_uint64),
                 ("bytes_file_read", C.c_uint64), ("bytes_file_write", C.c_uint64),
+                ("file_read_ns", C.c_uint64), ("file_write_ns", C.c_uint64),
                 ("mover_launches", C.c_uint64), ("mover_units", C.c_uint64), ("dma_copies", C.c_uint64),
                 ("decide_launches", C.c_uint64),
                 ("stall_ns", C.c_uint64), ("waits_under_30us", C.c_uint64), ("waits_total", C.c_uint64),
@@ -129,6 +131,38 @@ def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
 
+class _PinnedRegion:
+    """Page-locked host memory from hipHostMalloc, freed explicitly."""
+
+    _hip = None
+
+    def __init__(self, nbytes: int):
+        if _PinnedRegion._hip is None:
+            hip = C.CDLL("libamdhip64.so")
+            hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+            hip.hipHostFree.argtypes = [C.c_void_p]
+            _PinnedRegion._hip = hip
+        p = C.c_void_p()
+        rc = _PinnedRegion._hip.hipHostMalloc(C.byref(p), int(nbytes), 0)
+        if rc != 0 or not p.value:
+            raise MemoryError(f"hipHostMalloc of {nbytes} bytes failed (HIP error {rc})")
+        self.ptr, self.nbytes = int(p.value), int(nbytes)
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def free(self):
+        if self.ptr:
+            _PinnedRegion._hip.hipHostFree(C.c_void_p(self.ptr))
+            self.ptr = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
 class TensorCache:
     """One context of the library (one GPU).  Methods mirror the C calls."""
 
@@ -151,12 +185,13 @@ class TensorCache:
         if self._keep:
             # regions bind_torch allocated: hand them back to the system, not to
             # PyTorch's caches (a pinned region can be tens of GiB)
+            for r in self._keep:
+                if isinstance(r, _PinnedRegion):
+                    r.free()
             self._keep = []
             self.hbm = self.pinned = self.staging = self.mstream = None
             import torch
             torch.cuda.empty_cache()
-            if hasattr(torch._C, "_host_emptyCache"):
-                torch._C._host_emptyCache()
 
     def __del__(self):
         try:
@@ -210,27 +245,32 @@ class TensorCache:
                                          staging_ptr or None, staging_bytes, file_fd, migrate_stream or None, flags))
 
     def bind_torch(self, *, staging_bytes: int = 0, file_path: Optional[str] = None, null_mover: bool = False,
-                   stream=None):
-        """Allocates the regions with PyTorch (device memory and pinned host
-        memory are PyTorch's job here) and binds them."""
+                   stream=None, direct: bool = False):
+        """Allocates the regions and binds them: device memory and the streams
+        come from PyTorch, the pinned regions straight from hipHostMalloc
+        (PyTorch's pinned allocator rounds every request up to a power of two,
+        which for a 60 GiB pool locks 64 GiB)."""
         import torch
         if null_mover:
             self.bind_memory(0, 0, 0, 0, 0, 0, -1, 0, BIND_NULL_MOVER)
             return
         dev = torch.device("cuda:0")
         hbm = torch.empty(max(256, int(self.plan.hbm_total)), dtype=torch.uint8, device=dev)
-        pinned = torch.empty(max(256, int(self.plan.host_total)), dtype=torch.uint8, pin_memory=True)
-        staging = torch.empty(max(256, int(staging_bytes)), dtype=torch.uint8, pin_memory=True)
+        pinned = _PinnedRegion(max(4096, int(self.plan.host_total)))
+        if direct:
+            staging_bytes = (int(staging_bytes) + 4095) // 4096 * 4096
+        staging = _PinnedRegion(max(4096, int(staging_bytes)))
         self.mstream = stream if stream is not None else torch.cuda.Stream(device=dev)
         fd = -1
         if file_path is not None:
-            fd = os.open(file_path, os.O_RDWR | os.O_CREAT, 0o600)
+            fd = os.open(file_path, os.O_RDWR | os.O_CREAT | (os.O_DIRECT if direct else 0), 0o600)
             os.ftruncate(fd, int(self.plan.file_total))
         self._fd = fd
         self._keep = [hbm, pinned, staging, self.mstream]
         self.hbm, self.pinned, self.staging = hbm, pinned, staging
-        self.bind_memory(hbm.data_ptr(), hbm.numel(), pinned.data_ptr(), pinned.numel(),
-                         staging.data_ptr(), int(staging_bytes), fd, self.mstream.cuda_stream, 0)
+        self.bind_memory(hbm.data_ptr(), hbm.numel(), pinned.data_ptr(), pinned.nbytes,
+                         staging.data_ptr(), int(staging_bytes), fd, self.mstream.cuda_stream,
+                         BIND_FILE_DIRECT if (direct and fd >= 0) else 0)
 
     def load_tensor(self, tensor: int, data: np.ndarray):
         data = np.ascontiguousarray(data, dtype=np.uint8)

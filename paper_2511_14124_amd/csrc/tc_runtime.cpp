@@ -63,6 +63,9 @@ struct tc_ctx {
     uint8_t *hbm = nullptr, *pinned = nullptr, *staging = nullptr;
     uint64_t hbm_bytes = 0, pinned_bytes = 0, staging_bytes = 0;
     int fd = -1;
+    bool file_direct = false;           // the file was opened with O_DIRECT: 4 KiB aligned memory, offsets and lengths
+    uint8_t *io_bounce = nullptr;       // 4 KiB aligned host block for file I/O of pool buffers in that mode
+    uint64_t io_bounce_bytes = 0;
     hipStream_t streams[N_STREAMS]{};   // [S_K] is the caller's migration stream
     hipStream_t dstream = nullptr;      // decision stream (ours)
     bool null_mover = false;
@@ -171,6 +174,7 @@ static void release_device(tc_ctx *c)
     if (c->d_rw) { (void)hipFree(c->d_rw); c->d_rw = nullptr; }
     if (c->bounce) { (void)hipFree(c->bounce); c->bounce = nullptr; }
     if (c->dout) { (void)hipHostFree(c->dout); c->dout = nullptr; }
+    if (c->io_bounce) { free(c->io_bounce); c->io_bounce = nullptr; }
 }
 
 extern "C" int tc_destroy(tc_ctx *c)
@@ -265,6 +269,9 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (!c) return TC_E_ARG;
     if (c->stage != 3) return fail(c, TC_E_STATE, "tc_plan_schedule must come first (and bind only once)");
     const bool null_mover = (flags & TC_BIND_NULL_MOVER) != 0;
+    const bool direct = (flags & TC_BIND_FILE_DIRECT) != 0 && fd >= 0 && !null_mover;
+    if (direct && ((((uintptr_t)staging) & 4095) || (staging_bytes & 4095)))
+        return fail(c, TC_E_ARG, "with TC_BIND_FILE_DIRECT the staging region must be 4 KiB aligned and sized");
     if (!null_mover) {
         if (c->pools.hbm_total && (!hbm || hbm_bytes < c->pools.hbm_total))
             return fail(c, TC_E_CAPACITY, "HBM region smaller than the plan");
@@ -346,6 +353,15 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->pinned = (uint8_t *)pinned; c->pinned_bytes = pinned_bytes;
     c->staging = (uint8_t *)staging; c->staging_bytes = staging_bytes;
     c->fd = fd;
+    c->file_direct = direct;
+    if (direct) {
+        uint64_t largest = 0;
+        for (uint32_t t = 0; t < n_t; ++t) largest = std::max(largest, p.bytes[t]);
+        c->io_bounce_bytes = (largest + 4095) & ~4095ull;
+        void *blk = nullptr;
+        if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) { release_device(c); return fail(c, TC_E_CAPACITY, "no memory for the I/O bounce block"); }
+        c->io_bounce = (uint8_t *)blk;
+    }
     c->streams[S_K] = (hipStream_t)mstream;
     c->null_mover = null_mover;
     c->gpu_ticket.assign(pl.gpu_slots, 0);
@@ -455,27 +471,67 @@ static int timed_end(tc_ctx *c, int S, hipEvent_t t0, uint64_t bytes)
     return TC_OK;
 }
 
-static int file_write(tc_ctx *c, const uint8_t *src, uint64_t bytes, uint64_t off)
+// File-tier I/O.  With an O_DIRECT file every request must be 4 KiB aligned in
+// memory, offset and length: extents are 4 KiB aligned and sized, so a length
+// rounded up stays inside the tensor's own extent, and the memory side is the
+// bounce block.
+static inline uint64_t io_align(const tc_ctx *c) { return c->file_direct ? 4096 : 256; }
+static inline uint64_t io_len(const tc_ctx *c, uint64_t n) { return c->file_direct ? (n + 4095) & ~4095ull : n; }
+
+static int file_write_raw(tc_ctx *c, const uint8_t *src, uint64_t bytes, uint64_t off)
 {
     if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
+    const auto t0 = std::chrono::steady_clock::now();
     while (bytes) {
         ssize_t w = pwrite(c->fd, src, bytes, (off_t)off);
         if (w < 0 && errno == EINTR) continue;
         if (w <= 0) return fail(c, TC_E_IO, std::string("pwrite: ") + strerror(errno));
         src += w; off += (uint64_t)w; bytes -= (uint64_t)w;
     }
+    c->stats.file_write_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                                  std::chrono::steady_clock::now() - t0).count();
     return TC_OK;
+}
+
+static int file_read_raw(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t want, uint64_t off)
+{
+    // `bytes` are requested (rounded for O_DIRECT); at least `want` must arrive: a file
+    // whose last extent ends at the tensor's last byte is not a short read
+    if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
+    const auto t0 = std::chrono::steady_clock::now();
+    uint64_t got = 0;
+    while (got < bytes) {
+        ssize_t r = pread(c->fd, dst + got, bytes - got, (off_t)(off + got));
+        if (r < 0 && errno == EINTR) continue;
+        if (r < 0) return fail(c, TC_E_IO, std::string("pread: ") + strerror(errno));
+        if (r == 0) break;
+        got += (uint64_t)r;
+    }
+    if (got < want) return fail(c, TC_E_IO, "pread: short file");
+    c->stats.file_read_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                                 std::chrono::steady_clock::now() - t0).count();
+    return TC_OK;
+}
+
+// O_DIRECT cannot target memory the GPU driver has mapped (pread into a pinned
+// region fails with EFAULT on this kernel), so in that mode every request goes
+// through the bounce block, ordinary page-aligned memory of the library's own.
+static int file_write(tc_ctx *c, const uint8_t *src, uint64_t bytes, uint64_t off)
+{
+    if (!c->file_direct) return file_write_raw(c, src, bytes, off);
+    if (io_len(c, bytes) > c->io_bounce_bytes) return fail(c, TC_E_CAPACITY, "tensor larger than the I/O bounce block");
+    memcpy(c->io_bounce, src, bytes);
+    memset(c->io_bounce + bytes, 0, io_len(c, bytes) - bytes);
+    return file_write_raw(c, c->io_bounce, io_len(c, bytes), off);
 }
 
 static int file_read(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t off)
 {
-    if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
-    while (bytes) {
-        ssize_t r = pread(c->fd, dst, bytes, (off_t)off);
-        if (r < 0 && errno == EINTR) continue;
-        if (r <= 0) return fail(c, TC_E_IO, r == 0 ? std::string("pread: short file") : std::string("pread: ") + strerror(errno));
-        dst += r; off += (uint64_t)r; bytes -= (uint64_t)r;
-    }
+    if (!c->file_direct) return file_read_raw(c, dst, bytes, bytes, off);
+    if (io_len(c, bytes) > c->io_bounce_bytes) return fail(c, TC_E_CAPACITY, "tensor larger than the I/O bounce block");
+    int rc = file_read_raw(c, c->io_bounce, io_len(c, bytes), bytes, off);
+    if (rc != TC_OK) return rc;
+    memcpy(dst, c->io_bounce, bytes);
     return TC_OK;
 }
 
@@ -681,7 +737,7 @@ static int staging_wait_all(tc_ctx *c)
 
 static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, hipStream_t compute, uint8_t **out)
 {
-    const uint64_t need = (bytes + 255) & ~255ull;
+    const uint64_t need = (bytes + io_align(c) - 1) & ~(io_align(c) - 1);
     if (need > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a tensor that needs the file tier");
     if (c->staging_used + need > c->staging_bytes) {
         // out of bounce space: issue what is prepared, let it finish, start over
@@ -778,7 +834,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             // room for the outgoing bytes and, right behind them, for an
             // incoming tensor of the same class should it come from the file tier
             uint8_t *st = nullptr;
-            const uint64_t half = (n + 255) & ~255ull;
+            const uint64_t half = (n + io_align(c) - 1) & ~(io_align(c) - 1);
             int rc = staging_alloc(c, units, 2 * half, compute, &st);
             if (rc != TC_OK) return rc;
             reserved_in = st + half;
@@ -831,6 +887,10 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             // file extent -> host buffer, by the host; earlier copies that read
             // or wrote the buffer must have finished
             int rc = issue_units(c, units, compute);
+            if (rc != TC_OK) return rc;
+            // the same end-of-iteration call may have written this very tensor back to
+            // its extent a moment ago: that write has to reach the file first
+            rc = drain_pending(c);
             if (rc != TC_OK) return rc;
             const uint32_t flat = c->pools.cpu_base[s] + r.dst_slot;
             rc = wait_op(c, c->cpu_ticket[flat]);
@@ -1177,7 +1237,7 @@ extern "C" int tc_fill_payload(tc_ctx *c, uint32_t seed)
         if (tier[t] == TC_GPU) HIP_TRY(c, tc_launch_fill(gpu_addr(c, s, gs[t]), n, t, seed, c->streams[S_K]));
         else if (tier[t] == TC_CPU) HIP_TRY(c, tc_launch_fill(cpu_addr(c, s, cs[t]), n, t, seed, c->streams[S_K]));
         else {
-            if (n > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a file-tier tensor");
+            if (io_len(c, n) > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a file-tier tensor");
             HIP_TRY(c, tc_launch_fill(c->staging, n, t, seed, c->streams[S_K]));
             HIP_TRY(c, hipStreamSynchronize(c->streams[S_K]));
             rc = file_write(c, c->staging, n, c->place.file_off[t]);

@@ -26,7 +26,7 @@ def compare_logs(got, want):
 
 
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
-                busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False):
+                busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False, direct=False):
     """Replays every iteration of wl through the library; returns the context.
 
     window None: one tc_migrate_step call per hook (the hook-driven interface);
@@ -35,7 +35,7 @@ def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_b
     tc_load_tensor (for footprints too large to generate on the host)."""
     import torch
     tc = T.TensorCache.from_workload(wl)
-    tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes)
+    tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes, direct=direct)
     if mover:
         tc.set_mover(*mover)
     if merge_bytes is not None:
