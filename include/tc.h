@@ -333,6 +333,9 @@ typedef struct {
     double   d2h_ns;                 /* sum of HBM->host DMA copy durations */
     uint64_t d2h_copies;
     uint64_t d2h_bytes;
+    double   decide_ns;              /* sum of decision-kernel launch durations */
+    uint64_t decide_launches;
+    uint64_t decide_calls;           /* hook calls those launches decided */
 } tc_timing;
 int tc_mover_timing(tc_ctx *ctx, int enable, tc_timing *out);
 

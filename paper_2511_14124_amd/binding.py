@@ -59,7 +59,8 @@ class Stats(C.Structure):
 class Timing(C.Structure):
     _fields_ = [("kernel_ns", C.c_double), ("kernel_launches", C.c_uint64), ("kernel_bytes", C.c_uint64),
                 ("h2d_ns", C.c_double), ("h2d_copies", C.c_uint64), ("h2d_bytes", C.c_uint64),
-                ("d2h_ns", C.c_double), ("d2h_copies", C.c_uint64), ("d2h_bytes", C.c_uint64)]
+                ("d2h_ns", C.c_double), ("d2h_copies", C.c_uint64), ("d2h_bytes", C.c_uint64),
+                ("decide_ns", C.c_double), ("decide_launches", C.c_uint64), ("decide_calls", C.c_uint64)]
 
 
 STATS_FIELDS = [f[0] for f in Stats._fields_]

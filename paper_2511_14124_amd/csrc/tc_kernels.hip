@@ -813,6 +813,162 @@ __device__ void pack_tile_general(uint8_t *tile, uint8_t *slab, uint8_t *const *
     }
 }
 
+// Lanes of one wave exchange data through LDS without a workgroup barrier: the
+// hardware executes a wave's LDS instructions in order, but to the compiler every
+// lane is a thread of its own, and without this it may place one lane's load ahead
+// of another lane's store (it did: a value written under `if (lane == 63)` was read
+// by the other lanes first).  The fences are compiler-only at wavefront scope.
+__device__ __forceinline__ void pack_wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// 16 bytes to / from LDS at any alignment: the widest access the address allows
+__device__ __forceinline__ void pack_lds_store16(uint8_t *q, pack_v4 v)
+{
+    const uint32_t a = (uint32_t)(uintptr_t)q;
+    if ((a & 15) == 0) {
+        *(pack_v4 *)q = v;
+    } else if ((a & 3) == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ((uint32_t *)q)[k] = v[k];
+    } else if ((a & 1) == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ((uint16_t *)q)[k] = (uint16_t)(v[k >> 1] >> (16 * (k & 1)));
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) q[k] = (uint8_t)(v[k >> 2] >> (8 * (k & 3)));
+    }
+}
+
+__device__ __forceinline__ pack_v4 pack_lds_load16(const uint8_t *q)
+{
+    const uint32_t a = (uint32_t)(uintptr_t)q;
+    pack_v4 v = {0, 0, 0, 0};
+    if ((a & 15) == 0) {
+        v = *(const pack_v4 *)q;
+    } else if ((a & 3) == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = ((const uint32_t *)q)[k];
+    } else if ((a & 1) == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k >> 1] |= (uint32_t)((const uint16_t *)q)[k] << (16 * (k & 1));
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k >> 2] |= (uint32_t)q[k] << (8 * (k & 3));
+    }
+    return v;
+}
+
+// One tile with at most PACK_CAND pieces, some of them misaligned: staged in LDS, all
+// pieces at once.  The piece table (this wave's rows) gives for piece p its slab range
+// [tb[p], te[p]), its tensor address minus tb[p] in tg[p], and in tv[p] the number of
+// 128-bit body vectors of the pieces before it (tv[n_p] = all of them).  A piece's
+// body is what lies between its tensor address rounded up to 16 and its end rounded
+// down; the up to 15 bytes before and after move bytewise.  `stage` holds the tile as
+// the slab sees it.
+__device__ __forceinline__ void pack_tile_staged(uint8_t *stage, const uint64_t *tb, const uint64_t *te,
+                                                 uint8_t *const *tg, const uint32_t *tv, uint32_t n_p,
+                                                 uint8_t *slab, uint64_t t0, uint64_t t1, int unpack, uint32_t tid)
+{
+    constexpr int VEC = PACK_TILE / (PACK_THREADS * 16);
+    const uint32_t n_body = tv[n_p];
+    // tensor side of every body vector this lane handles: address and place in the tile
+    uint8_t *ga[VEC];
+    uint32_t lo[VEC];
+    uint32_t p = 0;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const uint32_t j = tid + k * PACK_THREADS;
+        ga[k] = nullptr;
+        lo[k] = 0;
+        if (j < n_body) {
+            while (tv[p + 1] <= j) ++p;
+            uint8_t *g0 = tg[p] + tb[p];
+            const uint32_t h = (uint32_t)((16 - ((uintptr_t)g0 & 15)) & 15);
+            const uint32_t o = h + (j - tv[p]) * 16;
+            ga[k] = g0 + o;
+            lo[k] = (uint32_t)(tb[p] - t0) + o;
+        }
+    }
+    if (!unpack) {
+        // tensors -> LDS: every body vector in flight, then the shifted LDS stores
+        pack_v4 v[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            v[k] = pack_v4{0, 0, 0, 0};
+            if (ga[k]) v[k] = __builtin_nontemporal_load((const pack_v4 *)ga[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k)
+            if (ga[k]) pack_lds_store16(stage + lo[k], v[k]);
+    } else {
+        // slab -> LDS: the whole tile, aligned on both sides
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+            if (x + 16 <= t1) *(pack_v4 *)(stage + (x - t0)) = __builtin_nontemporal_load((const pack_v4 *)(slab + x));
+            else for (uint64_t y = x; y < t1; ++y) stage[y - t0] = slab[y];
+        }
+    }
+    // bytes before and after each piece's body (tensor side): 32 byte-tasks per piece
+    if (!unpack) {
+        for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
+            const uint32_t q = task >> 5, idx = task & 31;
+            const uint8_t *g0 = tg[q] + tb[q];
+            const uint32_t len = (uint32_t)(te[q] - tb[q]);
+            uint32_t h = (uint32_t)((16 - ((uintptr_t)g0 & 15)) & 15);
+            h = h < len ? h : len;
+            const uint32_t nb = (len - h) >> 4, tail = len - h - nb * 16;
+            const uint32_t base = (uint32_t)(tb[q] - t0);
+            if (idx < 16) { if (idx < h) stage[base + idx] = g0[idx]; }
+            else if (idx - 16 < tail) { const uint32_t o = h + nb * 16 + idx - 16; stage[base + o] = g0[o]; }
+        }
+    }
+    __syncthreads();
+    if (!unpack) {
+        // LDS -> slab: whole vectors inside a piece, then the bytes at piece edges
+        uint32_t q = 0;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+            while (q < n_p && te[q] <= x) ++q;
+            if (q < n_p && tb[q] <= x && x + 16 <= te[q])
+                __builtin_nontemporal_store(*(const pack_v4 *)(stage + (x - t0)), (pack_v4 *)(slab + x));
+        }
+        for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
+            const uint32_t r = task >> 5, idx = task & 31;
+            const uint64_t b = tb[r], e = te[r];
+            const uint64_t up = (b + 15) & ~15ull, dn = e & ~15ull;
+            if (idx < 16) {
+                const uint64_t y = b + idx;
+                if (y < (e < up ? e : up)) slab[y] = stage[y - t0];
+            } else {
+                const uint64_t y = (up > dn ? up : dn) + (idx - 16);
+                if (y < e) slab[y] = stage[y - t0];
+            }
+        }
+    } else {
+        // LDS -> tensors: shifted LDS loads, aligned 128-bit stores, then the edge bytes
+#pragma unroll
+        for (int k = 0; k < VEC; ++k)
+            if (ga[k]) __builtin_nontemporal_store(pack_lds_load16(stage + lo[k]), (pack_v4 *)ga[k]);
+        for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
+            const uint32_t r = task >> 5, idx = task & 31;
+            uint8_t *g0 = tg[r] + tb[r];
+            const uint32_t len = (uint32_t)(te[r] - tb[r]);
+            uint32_t h = (uint32_t)((16 - ((uintptr_t)g0 & 15)) & 15);
+            h = h < len ? h : len;
+            const uint32_t nb = (len - h) >> 4, tail = len - h - nb * 16;
+            const uint32_t base = (uint32_t)(tb[r] - t0);
+            if (idx < 16) { if (idx < h) g0[idx] = stage[base + idx]; }
+            else if (idx - 16 < tail) { const uint32_t o = h + nb * 16 + idx - 16; g0[o] = stage[base + o]; }
+        }
+    }
+}
+
 // 64 registers per lane keep eight waves per SIMD resident: measured 5.5 -> 6.1 TB/s together
 // with the streaming (non-temporal) accesses of the fast path
 __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void tc_pack_kernel(
@@ -824,6 +980,7 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
     __shared__ __attribute__((aligned(16))) uint8_t stage[PACK_TILE];
     __shared__ uint64_t tab_b[PACK_THREADS / WAVE][PACK_CAND], tab_e[PACK_THREADS / WAVE][PACK_CAND];
     __shared__ uint8_t *tab_g[PACK_THREADS / WAVE][PACK_CAND];
+    __shared__ uint32_t tab_v[PACK_THREADS / WAVE][PACK_CAND + 1];
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const uint64_t t0 = (uint64_t)blockIdx.x * TILE;
     const uint64_t t1 = t0 + TILE < total ? t0 + TILE : total;
@@ -849,11 +1006,12 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
         }
     }
     const uint64_t vmask = __ballot(valid);
-    const bool general = __ballot(beyond || (valid && !ok)) != 0;
-    if (general) {                                          // the same in every wave: all read the same entries
+    // the same in every wave (all read the same entries): which way this tile goes
+    if (__ballot(beyond) != 0) {
         pack_tile_general(stage, slab, ptrs, bytes, slab_off, n, seg, t0, t1, unpack, tid);
         return;
     }
+    const bool staged = __ballot(valid && !ok) != 0;
     const uint32_t n_p = (uint32_t)__popcll(vmask);
     if (valid) {
         const uint32_t p = (uint32_t)__popcll(vmask & ((1ull << lane) - 1));
@@ -861,7 +1019,29 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
         tab_e[wave][p] = e;
         tab_g[wave][p] = g - b;                             // tensor address of slab offset x is tab_g + x
     }
-    // each wave reads only what its own lanes wrote: no barrier, the wave's LDS traffic is ordered
+    // each wave reads only what its own lanes wrote: no workgroup barrier, a wave-level one
+    pack_wave_lds_sync();
+    if (staged) {
+        // body vectors per piece and their running sum over the pieces before (lane order = piece order)
+        uint32_t nb = 0;
+        if (valid) {
+            const uint32_t len = (uint32_t)(e - b);
+            uint32_t h = (uint32_t)((16 - ((uintptr_t)g & 15)) & 15);
+            h = h < len ? h : len;
+            nb = (len - h) >> 4;
+        }
+        uint32_t incl = nb;
+#pragma unroll
+        for (int d = 1; d < WAVE; d <<= 1) {
+            const uint32_t up = __shfl_up(incl, d, WAVE);
+            if (lane >= (uint32_t)d) incl += up;
+        }
+        if (valid) tab_v[wave][(uint32_t)__popcll(vmask & ((1ull << lane) - 1))] = incl - nb;
+        if (lane == WAVE - 1) tab_v[wave][n_p] = incl;
+        pack_wave_lds_sync();
+        pack_tile_staged(stage, tab_b[wave], tab_e[wave], tab_g[wave], tab_v[wave], n_p, slab, t0, t1, unpack, tid);
+        return;
+    }
     // address pairs first (table look-ups), then every load, then every store
     const uint8_t *src[VEC];
     uint8_t *dst[VEC];

@@ -45,9 +45,10 @@ struct PUnit {              // one exchange unit being prepared
 
 struct Timed {              // event pair around one timed operation
     hipEvent_t t0, t1;
-    int kind;               // S_K kernel launch, S_H / S_D copy
-    uint64_t bytes;
+    int kind;               // S_K kernel launch, S_H / S_D copy, K_DECIDE decision launch
+    uint64_t bytes;         // bytes moved; hook calls decided for K_DECIDE
 };
+enum { K_DECIDE = 3, N_KINDS = 4 };
 
 } // namespace
 
@@ -452,22 +453,24 @@ static int end_op(tc_ctx *c, int S, uint64_t id)
     return TC_OK;
 }
 
-static int timed_begin(tc_ctx *c, int S, hipEvent_t *t0)
+static inline hipStream_t kind_stream(tc_ctx *c, int kind) { return kind == K_DECIDE ? c->dstream : c->streams[kind]; }
+
+static int timed_begin(tc_ctx *c, int kind, hipEvent_t *t0)
 {
     *t0 = nullptr;
     if (!c->timing) return TC_OK;
     HIP_TRY(c, hipEventCreate(t0));
-    HIP_TRY(c, hipEventRecord(*t0, c->streams[S]));
+    HIP_TRY(c, hipEventRecord(*t0, kind_stream(c, kind)));
     return TC_OK;
 }
 
-static int timed_end(tc_ctx *c, int S, hipEvent_t t0, uint64_t bytes)
+static int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes)
 {
     if (!t0) return TC_OK;
     hipEvent_t t1;
     HIP_TRY(c, hipEventCreate(&t1));
-    HIP_TRY(c, hipEventRecord(t1, c->streams[S]));
-    c->timed.push_back(Timed{t0, t1, S, bytes});
+    HIP_TRY(c, hipEventRecord(t1, kind_stream(c, kind)));
+    c->timed.push_back(Timed{t0, t1, kind, bytes});
     return TC_OK;
 }
 
@@ -913,7 +916,11 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
 
 static int run_decide(tc_ctx *c, const TcStepArgs &a)
 {
+    hipEvent_t t0;
+    int rc = timed_begin(c, K_DECIDE, &t0);
+    if (rc != TC_OK) return rc;
     HIP_TRY(c, tc_launch_decide(c->T, a, c->dout, c->dops, c->dstream));
+    if ((rc = timed_end(c, K_DECIDE, t0, 1)) != TC_OK) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->dstream));
     c->stats.decide_launches++;
     c->stats.cursor = c->dout->cursor;
@@ -1086,7 +1093,11 @@ static int replay_windows(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *i
         w.first = k0;
         w.count = std::min(c->replay_window, n_steps - k0);
         w.cap = c->dout_cap;
+        hipEvent_t t0;
+        int rc = timed_begin(c, K_DECIDE, &t0);
+        if (rc != TC_OK) return rc;
         HIP_TRY(c, tc_launch_decide_window(c->T, w, blk ? c->dout2 : c->dout, blk ? c->dops2 : c->dops, c->dstream));
+        if ((rc = timed_end(c, K_DECIDE, t0, 2ull * w.count)) != TC_OK) return rc;
         c->stats.decide_launches++;
         return TC_OK;
     };
@@ -1258,14 +1269,15 @@ extern "C" int tc_set_mover(tc_ctx *c, uint32_t workgroups, uint32_t chunk_bytes
     return TC_OK;
 }
 
-static int collect_timing(tc_ctx *c, double busy_ns[N_STREAMS], uint64_t count[N_STREAMS], uint64_t bytes[N_STREAMS])
+static int collect_timing(tc_ctx *c, double busy_ns[N_KINDS], uint64_t count[N_KINDS], uint64_t bytes[N_KINDS])
 {
-    for (int i = 0; i < N_STREAMS; ++i) { busy_ns[i] = 0; count[i] = 0; bytes[i] = 0; }
+    for (int i = 0; i < N_KINDS; ++i) { busy_ns[i] = 0; count[i] = 0; bytes[i] = 0; }
     int rcf = flush_deferred(c, c->last_compute);
     if (rcf != TC_OK) return rcf;
     if (c->timed.empty()) return TC_OK;
     for (int i = 0; i < N_STREAMS; ++i)
         if (i == S_K || c->streams[i]) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
+    HIP_TRY(c, hipStreamSynchronize(c->dstream));
     for (auto &p : c->timed) {
         float ms = 0;
         if (hipEventElapsedTime(&ms, p.t0, p.t1) == hipSuccess) {
@@ -1284,14 +1296,15 @@ extern "C" int tc_mover_timing(tc_ctx *c, int enable, tc_timing *out)
 {
     if (!c) return TC_E_ARG;
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
-    double busy[N_STREAMS];
-    uint64_t cnt[N_STREAMS], bytes[N_STREAMS];
+    double busy[N_KINDS];
+    uint64_t cnt[N_KINDS], bytes[N_KINDS];
     int rc = collect_timing(c, busy, cnt, bytes);
     if (rc != TC_OK) return rc;
     if (out) {
         out->kernel_ns = busy[S_K]; out->kernel_launches = cnt[S_K]; out->kernel_bytes = bytes[S_K];
         out->h2d_ns = busy[S_H]; out->h2d_copies = cnt[S_H]; out->h2d_bytes = bytes[S_H];
         out->d2h_ns = busy[S_D]; out->d2h_copies = cnt[S_D]; out->d2h_bytes = bytes[S_D];
+        out->decide_ns = busy[K_DECIDE]; out->decide_launches = cnt[K_DECIDE]; out->decide_calls = bytes[K_DECIDE];
     }
     c->timing = enable != 0;
     return TC_OK;

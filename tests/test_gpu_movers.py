@@ -81,6 +81,49 @@ def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps, 
     assert np.array_equal(got, want_back), name
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_pack_and_unpack_on_random_layouts(seed):
+    # random sizes (1 B .. 40 KiB, skewed to small ones), random gaps and phases on both
+    # sides, several hundred segments over dozens of tiles: register path, LDS-staged path
+    # and the piece-by-piece path (more than 32 pieces in a tile) all occur, tile by tile
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(150, 700))
+    kinds = rng.integers(0, 4, size=n)
+    sizes = np.where(kinds == 0, rng.integers(1, 64, size=n),
+             np.where(kinds == 1, 16 * rng.integers(1, 256, size=n),
+              np.where(kinds == 2, 256 * rng.integers(1, 160, size=n), rng.integers(1, 40000, size=n)))).tolist()
+    aligned = seed % 2 == 0
+    src_gaps = [0, 16, 256] if aligned else [0, 1, 2, 4, 7, 16, 100]
+    slab_gaps = [0, 16] if aligned else [0, 0, 3, 16, 40]
+    if aligned:
+        sizes = [(x + 15) // 16 * 16 if i % 7 else x for i, x in enumerate(sizes)]   # mostly regular, some odd
+    nb = np.asarray(sizes, dtype=np.uint64)
+    src_off, src_total = _layout(rng, sizes, src_gaps)
+    slab_off, slab_total = _layout(rng, sizes, slab_gaps)
+    slab_total += int(rng.integers(0, 40))
+    src = rng.integers(0, 256, size=src_total + 16, dtype=np.uint8)
+    tensors = [src[int(o):int(o) + int(k)] for o, k in zip(src_off, nb)]
+    want = po.pack(tensors, slab_off, np.full(slab_total, 0xEE, dtype=np.uint8))
+    d_src = _dev(src)
+    d_slab = torch.full((slab_total,), 0xEE, dtype=torch.uint8, device="cuda:0")
+    ptrs = _dev((src_off + np.uint64(d_src.data_ptr())).astype(np.int64))
+    d_nb, d_off = _dev(nb.astype(np.int64)), _dev(slab_off.astype(np.int64))
+    st = torch.cuda.current_stream().cuda_stream
+    d_index = torch.empty(T.pack_tiles(slab_total), dtype=torch.int32, device="cuda:0")
+    T.pack_index(d_off.data_ptr(), n, slab_total, d_index.data_ptr(), st)
+    T.pack(d_slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), n, slab_total, st, d_index.data_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(d_slab.cpu().numpy(), want)
+    d_back = torch.full((src_total + 16,), 0x55, dtype=torch.uint8, device="cuda:0")
+    ptrs2 = _dev((src_off + np.uint64(d_back.data_ptr())).astype(np.int64))
+    T.unpack(d_slab.data_ptr(), ptrs2.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), n, slab_total, st, d_index.data_ptr())
+    torch.cuda.synchronize()
+    want_back = np.full(src_total + 16, 0x55, dtype=np.uint8)
+    for t, o in zip(po.unpack(want, nb, slab_off), src_off):
+        want_back[int(o):int(o) + t.size] = t
+    assert np.array_equal(d_back.cpu().numpy(), want_back)
+
+
 def test_pack_of_nothing_is_a_no_op():
     d = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
     assert T.pack_tiles(0) == 0 and T.pack_tiles(1) == 1 and T.pack_tiles(16384) == 1 and T.pack_tiles(16385) == 2
