@@ -81,6 +81,13 @@ def load_library(path: str = LIB_PATH):
     global _lib
     if not os.path.exists(path):
         raise FileNotFoundError(f"{path} is missing: run `python -m paper_2511_14124_amd.build` first")
+    try:
+        # PyTorch ships its own HIP runtime under the same library name.  Whichever copy is
+        # loaded first serves the whole process, and the device memory and streams handed to
+        # the library come from PyTorch: let PyTorch's copy be that one.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(path)
     vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
     sig = {
