@@ -108,6 +108,25 @@ def test_modelled_compute_does_not_change_the_schedule():
     tc.close()
 
 
+def test_wait_time_measurement_does_not_change_the_schedule():
+    # with the host timing every pre-hook's waits (and no stream-side waits) the log, the
+    # state and the bytes stay those of the oracle; every listed tensor is measured once
+    import torch as _torch
+    wl = W.config(0, layers=4)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch()
+    for t in range(wl.n_tensors):
+        tc.load_tensor(t, W.workload_payload(wl, t))
+    cs = _torch.cuda.Stream()
+    tc.replay_iteration_c(wl.iterations[0], cs.cuda_stream, busy_ns=wl.compute_ns, measure_stall=True)
+    tc.synchronize()
+    r = check_against_oracle(wl, tc)
+    st = tc.cache_stats()
+    assert st["waits_total"] == r.hits + r.misses - r.fails
+    assert st["waits_under_30us"] <= st["waits_total"]
+    tc.close()
+
+
 # ---- the same schedule whatever the launch shape -----------------------------
 
 @pytest.mark.parametrize("window", [1, 3, 64, 256])

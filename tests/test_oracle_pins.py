@@ -258,6 +258,9 @@ def test_example_cpu_gpu_nvme_matches_what_the_text_fixes():
             continue
         x = got_n - {7}
         assert len(x) == 1 and x <= {1, 2, 3}
+        # the text spills a tensor "inactive for a longer period": whichever of 1 and 2 it is,
+        # it is not tensor 3, the one the backward pass needs soonest
+        assert x != {3}
         spilled = spilled or x
         assert x == spilled                           # the same tensor stays spilled
         fixed = {int(i) for i in ctxt.replace("{1,2,3}-x", "").split(",") if i.strip()}
@@ -402,3 +405,90 @@ def test_a_wrong_halt_rule_is_caught_by_the_worked_example(monkeypatch):
         r.post(k, [wl.profile[k][0][0]])
     monkeypatch.setattr(o.Profile, "next_use", real)
     assert _tiers(r)[0] != {4, 5, 6}                  # tensor 4 was wrongly sent away
+
+
+def _some_pin_fails(pins):
+    """True if at least one of the given pin tests raises under the current (mutated) oracle."""
+    for pin in pins:
+        try:
+            pin()
+        except Exception:
+            return True
+    return False
+
+
+def test_rounding_up_in_alg2_is_caught(monkeypatch):
+    # plant: buffers rounded up instead of down
+    real = o.buffer_count
+
+    def wrong(tc, avail, cap):
+        dist = o.tsd(tc)
+        return [max(0, min(int(-((-d * avail / s).__floor__())) if s else 0, int(k)))
+                for (s, _c), d, k in zip(tc, dist, cap)]
+    monkeypatch.setattr(o, "buffer_count", wrong)
+    assert _some_pin_fails([test_alg2_hand_example, test_alg2_closed_form_every_class_gets_the_same_fraction])
+    monkeypatch.setattr(o, "buffer_count", real)
+    test_alg2_hand_example()
+
+
+def test_placing_later_tensors_first_is_caught(monkeypatch):
+    # plant: the tensor allocator walks the execution order backwards
+    real = o.place
+
+    def wrong(p, plan):
+        q = o.Profile(p.n_tensors, p.rows_tensor, p.rows_rw, p.row_begin, p.row_end, p.occ,
+                      [(-f if f != o.INF else o.INF) for f in p.first_use], p.class_of, p.class_bytes,
+                      p.class_group, p.count, p.used, p.step_max)
+        return real(q, plan)
+    monkeypatch.setattr(o, "place", wrong)
+    assert _some_pin_fails([test_example_cpu_gpu_matches_the_papers_state_sequence,
+                            test_placement_is_monotone_in_execution_order_within_a_class])
+
+
+def test_evicting_the_soonest_needed_tensor_is_caught(monkeypatch):
+    # plant: the victim is the tensor needed soonest instead of farthest in the future
+    def wrong(self, cands, bound):
+        best, best_key = o.NONE, None
+        for x in cands:
+            key = (self.p.next_use(x, bound), x)
+            if best_key is None or key < best_key:
+                best, best_key = x, key
+        return best
+    monkeypatch.setattr(o.Replay, "_farthest", wrong)
+    assert _some_pin_fails([test_fetch_count_never_beats_the_exhaustive_minimum_on_random_single_class_traces,
+                            lambda: test_fetch_count_is_the_exhaustive_minimum_on_forward_backward_traces(7),
+                            test_example_cpu_gpu_nvme_matches_what_the_text_fixes])
+
+
+def test_dropping_the_swap_of_host_buffers_is_caught(monkeypatch):
+    # plant: Alg. 3 read literally - EvictTensor runs before the prefetch has freed the incoming
+    # tensor's host buffer.  With exactly c - G host buffers the CPU-GPU example then has to
+    # spill to NVMe, which the text rules out (its NVMe column stays empty).
+    def literal(self, v, u, y, step, phase, op_in, bound):
+        s, n = self.p.class_of[u], self.bytes_of[u]
+        src_tier, src_slot = self.cur[u], self.cslot[u]
+        if v != o.NONE:
+            self._evict(v, step, phase, bound, o.NONE)
+        if src_tier == o.CPU and self.cpu_owner[s][src_slot] == u:
+            self.cpu_owner[s][src_slot] = o.NONE
+            self.designated[s][src_slot] = False
+            self.cpu_freed[s][src_slot] = self.call
+        self._emit(step, phase, op_in, u, src_tier, src_slot if src_tier == o.CPU else o.NONE, o.GPU, y, n)
+        self.bytes_h2d += n
+        self.cur[u], self.gslot[u], self.cslot[u] = o.GPU, y, o.NONE
+        self.gpu_owner[s][y] = u
+        self.moved[u] = self.call
+    monkeypatch.setattr(o.Replay, "_exchange", literal)
+    assert _some_pin_fails([test_example_cpu_gpu_matches_the_papers_state_sequence])
+
+
+def test_forgetting_the_dirty_write_back_is_caught(monkeypatch):
+    # plant: an NVMe-final tensor is never written back, written or not
+    real = o.Replay._evict
+
+    def wrong(self, v, step, phase, bound, partner_cpu_slot):
+        if self.pl.final[v] == o.NVME:
+            self.dirty[v] = False
+        return real(self, v, step, phase, bound, partner_cpu_slot)
+    monkeypatch.setattr(o.Replay, "_evict", wrong)
+    assert _some_pin_fails([lambda: test_bytes_conserved_and_invariants_on_random_traces(s) for s in range(12)])
