@@ -121,6 +121,8 @@ def main():
                          "the one the metric is quoted on); 3 and 4 need the file tier and --layers")
     ap.add_argument("--layers", type=int, default=None, help="shallower model of the same shapes")
     ap.add_argument("--no-pack", action="store_true")
+    ap.add_argument("--no-prefetch", action="store_true",
+                    help="the paper's base variant: demand fetch only (an ablation, not the benchmark)")
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--merge-mib", type=int, default=1024, help="bytes merged into one migration launch")
@@ -140,6 +142,7 @@ def main():
     from paper_2511_14124_amd.link_probe import measure_link_peak
     link = measure_link_peak(torch)        # first: before this process holds any other stream
     wl = W.config(args.config, layers=args.layers)
+    wl.no_prefetch = args.no_prefetch
     tc = T.TensorCache.from_workload(wl)
     tmpdir = None
     if int((tc.placement["final_tier"] == T.NVME).sum()) or args.config >= 3:
@@ -179,13 +182,18 @@ def main():
     # stall per step with modelled compute (not part of the timed throughput run)
     stall_ms = None
     wait_share = None
+    wait_hist = None
     if not args.no_stall:
         b0 = tc.cache_stats()
         tc.replay_iteration_c(steps, cs.cuda_stream, busy_ns=wl.compute_ns, measure_stall=True)
         tc.synchronize()
         b1 = tc.cache_stats()
         stall_ms = (b1["stall_ns"] - b0["stall_ns"]) / 1e6 / len(steps)
-        wait_share = (b1["waits_under_30us"] - b0["waits_under_30us"]) / max(1, b1["waits_total"] - b0["waits_total"])
+        n_waits = max(1, b1["waits_total"] - b0["waits_total"])
+        wait_share = (b1["waits_under_30us"] - b0["waits_under_30us"]) / n_waits
+        wait_hist = {"under_0.01ms": (b1["waits_under_10us"] - b0["waits_under_10us"]) / n_waits,
+                     "under_0.03ms": wait_share,
+                     "under_0.1ms": (b1["waits_under_100us"] - b0["waits_under_100us"]) / n_waits}
     tc.close()
     del tc
     torch.cuda.empty_cache()
@@ -207,12 +215,15 @@ def main():
         "config": {"workload": wl.name + ("" if args.layers is None else f"@{args.layers}layers"),
                    "tensors": wl.n_tensors, "total_GiB": wl.total_bytes() / 2**30,
                    "hbm_cache_GiB": wl.hbm_bytes / 2**30, "hook_steps_per_iteration": wl.n_steps,
+                   "variant": "base (no prefetching)" if args.no_prefetch else "prefetching (Alg. 3)",
                    "mode": "zero modelled compute; every prefetch is paired with an eviction, so H2D and D2H run concurrently"},
         "pct_of_pcie_peak_h2d": 100.0 * value / link["h2d"],
         "pcie_peak_measured_GBps": link,
         "d2h_GBps": d2h / dt / 1e9,
         "hit_rate": hits / max(1, hits + misses),
+        "hbm_utilisation": s1["hbm_pool_bytes"] / max(1, s1["hbm_budget"]),
         "stall_ms_per_step": stall_ms, "share_of_tensors_waiting_under_0.03ms": wait_share,
+        "share_of_tensors_waiting": wait_hist,
         "modelled_compute_ms_per_iteration": float(wl.compute_ns.sum()) / 1e6,
         "decision_kernel": {"us_per_hook_call": tm["decide_ns"] / 1e3 / max(1, tm["decide_calls"]),
                             "launches": tm["decide_launches"], "hook_calls": tm["decide_calls"],

@@ -71,6 +71,8 @@ extern "C" {
 
 /* tc_budget.flags */
 #define TC_LITERAL_ALG2 1u           /* Alg. 2 exactly as printed: no per-step working-set floor */
+#define TC_NO_PREFETCH  2u           /* the paper's base variant (Sec. 4.1.4, "without prefetching"): post-hook
+                                        calls move nothing, tensors arrive by the pre-hook's demand fetch alone */
 
 /* tc_bind_memory flags */
 #define TC_BIND_NULL_MOVER 1u        /* decide and log only; no region needed, no byte moves */
@@ -164,8 +166,11 @@ typedef struct {
     uint64_t mover_units;            /* exchange units those launches carried */
     uint64_t dma_copies;             /* DMA-engine copies (large tensors) */
     uint64_t decide_launches;        /* decision-kernel launches */
+    uint64_t hbm_budget, hbm_pool_bytes;      /* GPU memory offered to / taken by the buffer pools (utilisation, Sec. 4.5) */
+    uint64_t host_budget, host_pool_bytes;    /* the same for pinned host memory, both groups together */
     uint64_t stall_ns;               /* time modules waited for their tensors (tc_set_stall_measurement) */
     uint64_t waits_under_30us, waits_total;   /* tensors that waited < 0.03 ms / tensors measured (Sec. 4.2.2) */
+    uint64_t waits_under_10us, waits_under_100us;   /* the other two thresholds of Sec. 4.2.2 (0.01 ms, 0.1 ms) */
     uint32_t cursor;                 /* prefetch-table cursor */
     uint32_t iteration;
 } tc_stats;

@@ -324,8 +324,9 @@ class Replay:
     its initial payload and the stamps it received ("metadata mode").
     """
 
-    def __init__(self, p: Profile, plan: PoolPlan, pl: Placement, payload=None):
+    def __init__(self, p: Profile, plan: PoolPlan, pl: Placement, payload=None, prefetch: bool = True):
         self.p, self.plan, self.pl = p, plan, pl
+        self.prefetch = prefetch          # False: the "base" variant of Sec. 4.1.4, demand fetch only
         n_t, n_c = p.n_tensors, len(p.count)
         self.bytes_of = [p.class_bytes[p.class_of[t]] for t in range(n_t)]
         self.cur = list(pl.final)
@@ -611,6 +612,11 @@ class Replay:
         """
         p = self.p
         self.call += 1
+        if not self.prefetch:
+            # the variant the paper calls the base version (Sec. 4.1.4: "without
+            # prefetching"): the post-hook moves nothing, tensors arrive by the
+            # pre-hook's demand fetch alone
+            return
         n_rows = p.n_rows
         bound = p.row_end[step] if step < p.n_steps else n_rows
         self.cursor = max(self.cursor, bound)
@@ -715,19 +721,20 @@ class Replay:
 
 
 def build(tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw, hbm_bytes, host_bytes,
-          align=256, literal=False, payload=None):
+          align=256, literal=False, payload=None, prefetch=True):
     """Profile, plan, place and return a Replay ready at iteration 0."""
     p = profile(tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw)
     plan = plan_pools(p, hbm_bytes, host_bytes, align, literal)
     pl = place(p, plan)
-    return Replay(p, plan, pl, payload)
+    return Replay(p, plan, pl, payload, prefetch)
 
 
 def replay_workload(wl, payload=None, check=None) -> Replay:
     """Run every iteration of a workload object (see the workloads package)."""
     st, te, rw, _ns = wl.events()
     r = build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
-              wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload)
+              wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload,
+              prefetch=not getattr(wl, "no_prefetch", False))
     for steps in wl.iterations:
         r.run_iteration(steps, check)
     return r

@@ -15,6 +15,7 @@ GPU, CPU, NVME = 0, 1, 2
 PRE, POST, END, END_CPU = 0, 1, 2, 3
 OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL"]
 LITERAL_ALG2 = 1
+NO_PREFETCH = 2
 BIND_NULL_MOVER = 1
 BIND_FILE_DIRECT = 2
 NONE = 0xFFFFFFFF
@@ -52,7 +53,10 @@ class Stats(C.Structure):
                 ("file_read_ns", C.c_uint64), ("file_write_ns", C.c_uint64),
                 ("mover_launches", C.c_uint64), ("mover_units", C.c_uint64), ("dma_copies", C.c_uint64),
                 ("decide_launches", C.c_uint64),
+                ("hbm_budget", C.c_uint64), ("hbm_pool_bytes", C.c_uint64),
+                ("host_budget", C.c_uint64), ("host_pool_bytes", C.c_uint64),
                 ("stall_ns", C.c_uint64), ("waits_under_30us", C.c_uint64), ("waits_total", C.c_uint64),
+                ("waits_under_10us", C.c_uint64), ("waits_under_100us", C.c_uint64),
                 ("cursor", C.c_uint32), ("iteration", C.c_uint32)]
 
 
@@ -386,7 +390,8 @@ class TensorCache:
         tc = cls()
         st, te, rw, ns = wl.events()
         tc.profile_order(wl.tensor_bytes, wl.tensor_group, st, te, rw, ns, wl.tensor_kind)
-        tc.plan_pools(wl.hbm_bytes, wl.host_bytes, wl.align, LITERAL_ALG2 if wl.literal_alg2 else 0)
+        tc.plan_pools(wl.hbm_bytes, wl.host_bytes, wl.align,
+                      (LITERAL_ALG2 if wl.literal_alg2 else 0) | (NO_PREFETCH if getattr(wl, "no_prefetch", False) else 0))
         tc.plan_schedule()
         return tc
 

@@ -67,6 +67,7 @@ struct TcDevTables {
     const uint32_t *gpu_count, *cpu_count, *gpu_base, *cpu_base;
     const uint32_t *member_ptr, *members;
     uint32_t n_rows, n_steps, n_tensors, n_classes;
+    uint32_t flags;                             // tc_budget.flags
     // mutable scheduler state
     uint32_t *cur, *gslot, *cslot, *dirty, *moved;
     uint32_t *gpu_owner, *gpu_freed, *cpu_owner, *cpu_freed, *designated;

@@ -250,6 +250,7 @@ __device__ void decide_pre(DecideCtx &c, const TcStepArgs &a)
 __device__ void decide_post(DecideCtx &c, const TcStepArgs &a)
 {
     const TcDevTables &T = c.T;
+    if (T.flags & TC_NO_PREFETCH) return;                 // base variant: nothing moves after a module
     const uint32_t n_rows = T.n_rows;
     c.bound = a.step < T.n_steps ? T.row_begin[a.step + 1] : n_rows;
     uint32_t cursor = T.scalars[0];

@@ -322,6 +322,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     T.gpu_count = d + o_gc; T.cpu_count = d + o_cc; T.gpu_base = d + o_gb; T.cpu_base = d + o_cb;
     T.member_ptr = d + o_mp; T.members = d + o_mem;
     T.n_rows = n_rows; T.n_steps = p.n_steps; T.n_tensors = n_t; T.n_classes = n_c;
+    T.flags = c->budget.flags;
     T.cur = d + o_cur; T.gslot = d + o_gs; T.cslot = d + o_cs; T.dirty = d + o_dirty; T.moved = d + o_moved;
     T.gpu_owner = d + o_go; T.gpu_freed = d + o_gf; T.cpu_owner = d + o_co; T.cpu_freed = d + o_cf;
     T.designated = d + o_des; T.scalars = d + o_sc;
@@ -365,6 +366,10 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     }
     c->streams[S_K] = (hipStream_t)mstream;
     c->null_mover = null_mover;
+    c->stats.hbm_budget = c->budget.hbm_bytes;
+    c->stats.hbm_pool_bytes = pl.hbm_total;
+    c->stats.host_budget = c->budget.host_bytes[0] + c->budget.host_bytes[1];
+    c->stats.host_pool_bytes = pl.host_total;
     c->gpu_ticket.assign(pl.gpu_slots, 0);
     c->cpu_ticket.assign(pl.cpu_slots, 0);
     c->gpu_pending.assign(pl.gpu_slots, 0);
@@ -969,7 +974,9 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
                                             std::chrono::steady_clock::now() - t0).count();
                     waited_ns = std::max(waited_ns, ns);
                     c->stats.waits_total++;
+                    if (ns < 10000) c->stats.waits_under_10us++;
                     if (ns < 30000) c->stats.waits_under_30us++;
+                    if (ns < 100000) c->stats.waits_under_100us++;
                 } else if (!op_complete(c, ticket)) {
                     HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
                 }

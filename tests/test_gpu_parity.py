@@ -112,7 +112,7 @@ def test_wait_time_measurement_does_not_change_the_schedule():
     # with the host timing every pre-hook's waits (and no stream-side waits) the log, the
     # state and the bytes stay those of the oracle; every listed tensor is measured once
     import torch as _torch
-    wl = W.config(0, layers=4)
+    wl = W.config(0, layers=8)
     tc = T.TensorCache.from_workload(wl)
     tc.bind_torch()
     for t in range(wl.n_tensors):
@@ -311,4 +311,23 @@ def test_file_tier_through_o_direct(seed, tmp_path):
     st = tc.cache_stats()
     assert st["bytes_file_read"] + st["bytes_file_write"] > 0
     assert (st["file_read_ns"] > 0) == (st["bytes_file_read"] > 0)
+    tc.close()
+
+
+@pytest.mark.parametrize("seed", [1, 2, 11])
+def test_base_variant_without_prefetching(seed, tmp_path):
+    # TC_NO_PREFETCH: post-hook calls move nothing, every non-resident access is a demand miss
+    wl = _random(seed)
+    wl.no_prefetch = True
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=1 << 20, window=(None if seed == 1 else 16))
+    r = check_against_oracle(wl, tc)
+    assert r.misses > 0 and not any(e[2] == 1 for e in r.log)
+    tc.close()
+    wl = W.config(0, layers=6)
+    wl.no_prefetch = True
+    tc = run_library(wl, window=64)
+    r = check_against_oracle(wl, tc)
+    assert r.misses > 0
+    st = tc.cache_stats()
+    assert st["hbm_pool_bytes"] <= st["hbm_budget"] and st["host_pool_bytes"] <= st["host_budget"]
     tc.close()

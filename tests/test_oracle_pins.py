@@ -347,6 +347,38 @@ def test_fetch_count_never_beats_the_exhaustive_minimum_on_random_single_class_t
         assert r.hits + r.misses == len(seq)
 
 
+def test_without_prefetching_the_demand_path_is_beladys_min_on_single_class_traces():
+    # the base variant (demand fetch only, Sec. 4.1.4): the victim rule "used farthest in
+    # the future" is Belady's MIN, a textbook optimum, so the number of fetches must EQUAL
+    # the exhaustive minimum on every single-class trace
+    rng = np.random.default_rng(12)
+    for trial in range(80):
+        n = int(rng.integers(3, 8))
+        k = int(rng.integers(1, n + 1))
+        seq = [int(x) for x in rng.integers(0, n, size=int(rng.integers(4, 14)))]
+        steps = [[(t, W.R)] for t in seq]
+        wl = W.traces._simple("bf", [512] * n, [0] * n, steps, k * 512, ((n - k) * 512, 0))
+        wl.no_prefetch = True
+        r = o.replay_workload(wl, check=check_state)
+        initial = list(dict.fromkeys(seq))[:k]
+        fetched = sum(1 for e in r.log if e[3] == o.DEMAND)
+        assert all(e[3] != o.PREFETCH or e[2] == o.END for e in r.log)
+        assert fetched == r.misses == _min_fetches(seq, k, initial), (seq, k)
+        assert r.hits + r.misses == len(seq) and r.fails == 0
+
+
+def test_without_prefetching_hits_drop_and_invariants_hold():
+    wl = W.config(0, layers=8)
+    with_p = o.replay_workload(wl, check=check_state)
+    wl.no_prefetch = True
+    pay = lambda t: W.workload_payload(wl, t)
+    base = o.replay_workload(wl, payload=pay, check=check_state)
+    assert with_p.misses == 0 and base.misses > 0 and base.hits + base.misses == with_p.hits
+    assert all(e[2] != o.POST for e in base.log)          # the post-hook moves nothing
+    for t in range(wl.n_tensors):
+        assert np.array_equal(base.read_tensor(t), base.expected_bytes(t, pay))
+
+
 # ----------------------------------------------------------------------------
 # bytes conserved, full-bytes mode, multi-class random traces (incl. odd sizes,
 # the file tier, write accesses, order drift and several iterations)
@@ -354,10 +386,13 @@ def test_fetch_count_never_beats_the_exhaustive_minimum_on_random_single_class_t
 
 @pytest.mark.parametrize("seed", range(12))
 def test_bytes_conserved_and_invariants_on_random_traces(seed):
-    wl = W.random_workload(seed, n_tensors=36, n_steps=60, perturb_one_in=(0 if seed % 2 else 7),
+    wl = W.random_workload(seed, n_tensors=120, n_steps=80, max_per_step=3, hbm_frac=(0.08 if seed % 2 else 0.2),
+                           perturb_one_in=(0 if seed % 2 else 7),
                            host_frac=(0.3 if seed % 3 else 1.2), literal=(seed % 4 == 3))
+    wl.no_prefetch = (seed == 5)
     pay = lambda t: W.workload_payload(wl, t)
     r = o.replay_workload(wl, payload=pay, check=check_state)
+    assert len(r.log) > 100
     for t in range(wl.n_tensors):
         assert np.array_equal(r.read_tensor(t), r.expected_bytes(t, pay)), t
     # byte counters equal the op log's bytes, each byte crossing each link once
@@ -368,6 +403,7 @@ def test_bytes_conserved_and_invariants_on_random_traces(seed):
     assert (h2d, d2h, fw, fr) == (r.bytes_h2d, r.bytes_d2h, r.bytes_file_write, r.bytes_file_read)
     meta = o.replay_workload(wl)                      # metadata mode decides identically
     assert meta.log == r.log and meta.cur == r.cur and meta.gslot == r.gslot
+    assert wl.no_prefetch == (not any(e[2] == o.POST for e in r.log))
 
 
 def test_metadata_and_full_bytes_agree_on_a_small_transformer_trace():

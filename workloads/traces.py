@@ -49,6 +49,7 @@ class Workload:
     iterations: List[List[Step]] = field(default_factory=list)   # replayed iterations
     align: int = 256
     literal_alg2: bool = False                # Alg. 2 without the working-set floor
+    no_prefetch: bool = False                 # replay the paper's base variant: demand fetch only
     gaussian_p16: bool = False                # 16-bit params are fp16(N(0, 0.02))
     notes: str = ""
 
