@@ -30,7 +30,24 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    build_c_example(verbose)
     return LIB
+
+
+def build_c_example(verbose: bool = True) -> str:
+    """The plain-C99 user of the ABI under tests/c (run by the GPU tests): built with gcc
+    against include/tc.h and the HIP runtime API, found at run time next to libtc.so."""
+    src = os.path.join(ROOT, "tests", "c", "tc_example.c")
+    out = os.path.join(ROOT, "tests", "c", "tc_example.bin")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), src, "-o", out,
+           "-L", HERE, "-l:libtc.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2511_14124_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return out
 
 
 if __name__ == "__main__":
