@@ -300,6 +300,11 @@ int tc_cache_stats(const tc_ctx *ctx, tc_stats *out);
  * *n_total receives the log's length.  The log is kept on the host. */
 int tc_dump_oplog(const tc_ctx *ctx, uint64_t first, tc_op *buf, uint64_t cap, uint64_t *n_total);
 
+/* The op log grows by one 32-byte record per decision for as long as it is
+ * enabled (it is at creation): a long run switches it off or clears it between
+ * iterations.  enable: keep recording or not; clear: drop what is recorded. */
+int tc_set_oplog(tc_ctx *ctx, int enable, int clear);
+
 /* Current tier and buffer of every tensor (host arrays of n_tensors entries;
  * any may be NULL).  Reads the device tables; synchronises the decision stream. */
 int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_slot);

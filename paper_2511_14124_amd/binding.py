@@ -115,6 +115,7 @@ def load_library(path: str = LIB_PATH):
         "tc_cache_stats": (i32, [vp, C.POINTER(Stats)]),
         "tc_dump_oplog": (i32, [vp, u64, vp, u64, C.POINTER(u64)]),
         "tc_dump_state": (i32, [vp, vp, vp, vp]),
+        "tc_set_oplog": (i32, [vp, i32, i32]),
         "tc_set_mover": (i32, [vp, u32, u32]),
         "tc_mover_timing": (i32, [vp, i32, C.POINTER(Timing)]),
         "tc_set_dma_threshold": (i32, [vp, u64]),
@@ -359,6 +360,9 @@ class TensorCache:
         if n.value:
             self._check(lib().tc_dump_oplog(self._h, 0, _ptr(buf), n.value, C.byref(n)))
         return buf
+
+    def set_oplog(self, enable: bool = True, clear: bool = False):
+        self._check(lib().tc_set_oplog(self._h, int(enable), int(clear)))
 
     def dump_state(self):
         tier = np.zeros(self.n_tensors, dtype=np.uint8)

@@ -118,6 +118,7 @@ struct tc_ctx {
     std::vector<Timed> timed;
 
     std::vector<tc_op> log;
+    bool logging = true;
     tc_stats stats{};
 };
 
@@ -802,7 +803,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
         rec.src_slot = r.src_slot; rec.dst_slot = r.dst_slot;
         rec.phase = r.phase; rec.op = r.op; rec.src_tier = r.src_tier; rec.dst_tier = r.dst_tier;
         rec.bytes = (r.op == TC_OP_RELEASE || r.op == TC_OP_FAIL) ? 0 : n;
-        c->log.push_back(rec);
+        if (c->logging) c->log.push_back(rec);
         c->stats.n_ops[r.op]++;
         switch (r.op) {
         case TC_OP_EVICT: c->stats.bytes_d2h += n; break;
@@ -1172,6 +1173,14 @@ extern "C" int tc_dump_oplog(const tc_ctx *c, uint64_t first, tc_op *buf, uint64
     if (n_total) *n_total = c->log.size();
     if (buf)
         for (uint64_t i = first, k = 0; i < c->log.size() && k < cap; ++i, ++k) buf[k] = c->log[i];
+    return TC_OK;
+}
+
+extern "C" int tc_set_oplog(tc_ctx *c, int enable, int clear)
+{
+    if (!c) return TC_E_ARG;
+    c->logging = enable != 0;
+    if (clear) { c->log.clear(); c->log.shrink_to_fit(); }
     return TC_OK;
 }
 

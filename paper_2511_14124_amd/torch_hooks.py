@@ -1,0 +1,219 @@
+"""Live profiling and hook-driven migration for a PyTorch module.
+
+The paper's tensor characteristic analyzer (Sec. 3.2.1) registers a pre-hook
+and a post-hook on every module, records execution order and tensor sizes in
+one dry-run iteration, and the scheduler (Sec. 3.4) is then driven by the same
+hooks.  `ParamCache` does that for the parameters of an `nn.Module` on top of
+the C-ABI library:
+
+    pc = ParamCache(model, hbm_bytes=...)
+    pc.profile(lambda: loss_fn(model(x), y).backward())   # dry run: order + sizes
+    pc.install()                                          # plan, place, move the parameters out
+    for batch in data:
+        loss_fn(model(x), y).backward()                   # hooks fetch / evict around every module
+        pc.sgd_step(lr)                                   # parameters pass through the cache once more
+        pc.end_iteration()
+
+Between its pre-hook and its post-hook a module's parameters are views into
+the HBM cache buffers the library returned; outside that window they point
+nowhere useful and must not be touched.  Gradients stay ordinary PyTorch
+tensors: this helper manages parameters only (the FP16-parameter policy of
+Sec. 3.4.2), it is a way to drive the library from real modules, not a
+training framework.
+
+Only argument marshalling and hook bookkeeping happen here; decisions and
+copies are the library's kernels.
+"""
+
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional, Tuple
+
+import numpy as np
+
+from . import binding as T
+
+R, W, RW = 1, 2, 3
+
+
+class ParamCache:
+    def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256):
+        import torch
+        self.torch = torch
+        self.model = model
+        self.hbm_bytes = int(hbm_bytes)
+        self.host_bytes = host_bytes
+        self.align = align
+        # leaf modules: those that own parameters directly
+        self.mods = [m for m in model.modules() if any(True for _ in m.parameters(recurse=False))]
+        self.params: List = []
+        self.pid: Dict[int, int] = {}
+        for m in self.mods:
+            for p in m.parameters(recurse=False):
+                if id(p) not in self.pid:
+                    self.pid[id(p)] = len(self.params)
+                    self.params.append(p)
+        if any(len(list(m.parameters(recurse=False))) > T.MAX_STEP_TENSORS for m in self.mods):
+            raise ValueError("a module owns more parameters than one hook call may name")
+        self.mod_ids = {id(m): [self.pid[id(p)] for p in m.parameters(recurse=False)] for m in self.mods}
+        self.steps: List[List[Tuple[int, int]]] = []      # the profiled iteration
+        self.tc: Optional[T.TensorCache] = None
+        self._handles: list = []
+        self._k = 0                                       # next step of the running iteration
+        self._recording = False
+        self._pending_bwd: Dict[int, int] = {}            # module -> parameters whose gradient is still due
+        self._bwd_step: Dict[int, int] = {}               # module -> step index of its running backward
+        self._fwd_step: Dict[int, int] = {}               # module -> step index of its running forward
+        if any(not p.requires_grad for p in self.params):
+            raise ValueError("every managed parameter must require a gradient (its post-hook waits for it)")
+
+    # ------------------------------------------------------------------ hooks
+    def _register(self):
+        for m in self.mods:
+            self._handles.append(m.register_forward_pre_hook(self._fwd_pre))
+            self._handles.append(m.register_forward_hook(self._fwd_post))
+            for p in m.parameters(recurse=False):
+                self._handles.append(p.register_post_accumulate_grad_hook(self._make_grad_done(m)))
+
+    def _remove(self):
+        for h in self._handles:
+            h.remove()
+        self._handles = []
+
+    def _begin(self, m, rw: int) -> int:
+        """Opens the next step for module m (steps are numbered in the order they open)."""
+        ids = self.mod_ids[id(m)]
+        k = self._k
+        self._k += 1
+        if self._recording:
+            self.steps.append([(t, rw) for t in ids])
+        else:
+            self._fetch(k, ids, [rw] * len(ids))
+        return k
+
+    def _end(self, m, k: int, rw: int):
+        ids = self.mod_ids[id(m)]
+        if not self._recording:
+            stream = self.torch.cuda.current_stream().cuda_stream
+            self.tc.migrate_step(k, T.POST, ids, [rw] * len(ids), stream)
+
+    def _fetch(self, k: int, ids, rw):
+        stream = self.torch.cuda.current_stream().cuda_stream
+        ptrs = self.tc.migrate_step(k, T.PRE, ids, rw, stream, want_ptrs=True)
+        base = self.tc.hbm.data_ptr()
+        for t, ptr in zip(ids, ptrs):
+            if not ptr:
+                raise RuntimeError(f"parameter {t} could not be given a GPU buffer (cache too small for this module)")
+            p = self.params[t]
+            n = self._nbytes[t]
+            p.data = self.tc.hbm[ptr - base: ptr - base + n].view(self._dtype[t]).view(self._shape[t])
+
+    def _fwd_pre(self, m, args):
+        self._fwd_step[id(m)] = self._begin(m, R)
+
+    def _fwd_post(self, m, args, out):
+        self._end(m, self._fwd_step.pop(id(m)), R)
+        # the module's backward starts when the gradient of its output arrives
+        outs = out if isinstance(out, (tuple, list)) else (out,)
+        for o in outs:
+            if self.torch.is_tensor(o) and o.requires_grad:
+                o.register_hook(self._make_bwd_start(m))
+                break
+
+    def _make_bwd_start(self, m):
+        def hook(grad):
+            if id(m) not in self._bwd_step:               # several outputs: the first gradient opens the step
+                self._bwd_step[id(m)] = self._begin(m, R)
+                self._pending_bwd[id(m)] = len(self.mod_ids[id(m)])
+            return grad
+        return hook
+
+    def _make_grad_done(self, m):
+        def hook(param):
+            if id(m) not in self._bwd_step:
+                return
+            self._pending_bwd[id(m)] -= 1
+            if self._pending_bwd[id(m)] == 0:
+                self._end(m, self._bwd_step.pop(id(m)), R)
+        return hook
+
+    # ---------------------------------------------------------------- profile
+    def profile(self, run_iteration: Callable[[], None]):
+        """Dry run (Sec. 3.2.1): one forward + backward under recording hooks."""
+        self.steps = []
+        self._k = 0
+        self._recording = True
+        self._register()
+        try:
+            run_iteration()
+        finally:
+            self._remove()
+            self._recording = False
+        if self._bwd_step:
+            raise RuntimeError("a module's backward did not finish during the dry run")
+        self._n_model_steps = len(self.steps)
+        # the optimizer sweep: every parameter once, read and written
+        for t in range(len(self.params)):
+            self.steps.append([(t, RW)])
+        for p in self.params:
+            p.grad = None
+
+    # ---------------------------------------------------------------- install
+    def install(self):
+        torch = self.torch
+        self._nbytes = [p.numel() * p.element_size() for p in self.params]
+        self._dtype = [p.dtype for p in self.params]
+        self._shape = [tuple(p.shape) for p in self.params]
+        if min(self._nbytes) < 16:
+            raise ValueError("parameters smaller than 16 bytes are not supported")
+        st, te, rw = [], [], []
+        for k, step in enumerate(self.steps):
+            for (t, a) in step:
+                st.append(k)
+                te.append(t)
+                rw.append(a)
+        tc = T.TensorCache()
+        tc.profile_order(self._nbytes, [0] * len(self.params), st, te, rw)
+        host = self.host_bytes if self.host_bytes is not None else sum((n + 255) // 256 * 256 for n in self._nbytes) + 4096
+        tc.plan_pools(self.hbm_bytes, (host, 0), self.align)
+        tc.plan_schedule()
+        tc.bind_torch()
+        for t, p in enumerate(self.params):
+            tc.load_tensor(t, p.detach().cpu().contiguous().view(torch.uint8).numpy().reshape(-1))
+            p.data = torch.empty(0, dtype=self._dtype[t], device=p.device)
+        self.tc = tc
+        self._k = 0
+        self._register()
+
+    # ------------------------------------------------------------- iteration
+    def sgd_step(self, lr: float):
+        """Plain SGD through the cache: each parameter is fetched (read + write),
+        updated in its cache buffer and left to the scheduler."""
+        torch = self.torch
+        stream = torch.cuda.current_stream().cuda_stream
+        k = self._n_model_steps
+        with torch.no_grad():
+            for t, p in enumerate(self.params):
+                self._fetch(k, [t], [RW])
+                if p.grad is not None:
+                    p.data.add_(p.grad, alpha=-lr)
+                self.tc.migrate_step(k, T.POST, [t], [RW], stream)
+                k += 1
+
+    def end_iteration(self):
+        self.tc.end_iteration(self.torch.cuda.current_stream().cuda_stream)
+        self._k = 0
+        for p in self.params:
+            p.grad = None
+
+    def gather(self) -> list:
+        """Current value of every parameter, wherever it lives (CPU tensors)."""
+        torch = self.torch
+        return [torch.from_numpy(self.tc.read_tensor(t)).view(self._dtype[t]).view(self._shape[t])
+                for t in range(len(self.params))]
+
+    def close(self):
+        self._remove()
+        if self.tc is not None:
+            self.tc.close()
+            self.tc = None

@@ -331,3 +331,21 @@ def test_base_variant_without_prefetching(seed, tmp_path):
     st = tc.cache_stats()
     assert st["hbm_pool_bytes"] <= st["hbm_budget"] and st["host_pool_bytes"] <= st["host_budget"]
     tc.close()
+
+
+def test_op_log_can_be_cleared_and_switched_off():
+    wl = W.single_class_fwd_bwd(8, 3, 5, n_iterations=3)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch()
+    cs = torch.cuda.Stream()
+    tc.replay_iteration(wl.iterations[0], cs.cuda_stream)
+    n1 = len(tc.dump_oplog())
+    assert n1 == 20
+    tc.set_oplog(enable=True, clear=True)
+    tc.replay_iteration(wl.iterations[1], cs.cuda_stream)
+    log = tc.dump_oplog()
+    assert len(log) == n1 and set(log["iteration"].tolist()) == {1}
+    tc.set_oplog(enable=False, clear=True)
+    tc.replay_iteration_c(wl.iterations[2], cs.cuda_stream)
+    assert len(tc.dump_oplog()) == 0 and sum(tc.cache_stats()["n_ops"]) == 3 * n1
+    tc.close()
