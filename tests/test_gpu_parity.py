@@ -349,3 +349,24 @@ def test_op_log_can_be_cleared_and_switched_off():
     tc.replay_iteration_c(wl.iterations[2], cs.cuda_stream)
     assert len(tc.dump_oplog()) == 0 and sum(tc.cache_stats()["n_ops"]) == 3 * n1
     tc.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_settings_keep_the_schedule_and_every_byte(seed, tmp_path):
+    # the launch shape must never matter: random combinations of window, merge size, DMA
+    # threshold, mover grid and chunk, modelled compute, buffered or direct file I/O
+    rng = np.random.default_rng(500 + seed)
+    wl = W.random_workload(40 + seed, n_tensors=140, n_steps=90, max_per_step=3,
+                           sizes=(512, 4096, 100, 33000, 70001, 262144 + 48), hbm_frac=0.1,
+                           host_frac=float(rng.choice([0.3, 0.6, 1.3])), perturb_one_in=int(rng.choice([0, 6, 11])),
+                           n_iterations=3)
+    window = [None, 1, 5, 64, 256][int(rng.integers(0, 5))]
+    direct = bool(rng.integers(0, 2)) and _direct_ok(tmp_path)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=2 << 20, window=window,
+                     merge_bytes=int(rng.choice([0, 1 << 16, 1 << 22, 1 << 30])),
+                     dma_threshold=int(rng.choice([0, 0, 1 << 16, 1 << 18])) or None,
+                     mover=(int(rng.choice([1, 8, 64, 300])), int(rng.choice([4096, 16384, 65536, 1 << 20]))),
+                     busy=bool(rng.integers(0, 2)), direct=direct)
+    r = check_against_oracle(wl, tc)
+    assert len(r.log) > 100
+    tc.close()
