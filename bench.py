@@ -149,7 +149,7 @@ def main():
         import tempfile
         tmpdir = tempfile.TemporaryDirectory(dir="/tmp")
         big = (int(wl.tensor_bytes.max()) + 4095) // 4096 * 4096
-        tc.bind_torch(file_path=os.path.join(tmpdir.name, "tier.bin"), staging_bytes=4 * big)
+        tc.bind_torch(file_path=os.path.join(tmpdir.name, "tier.bin"), staging_bytes=8 * big)
     else:
         tc.bind_torch()
     if args.workgroups or args.chunk:
@@ -248,7 +248,8 @@ def main():
             "write_GBps": file_stats["bytes_file_write"] / max(1, file_stats["file_write_ns"]),
             "read_GiB_per_step": file_stats["bytes_file_read"] / args.steps / 2**30,
             "write_GiB_per_step": file_stats["bytes_file_write"] / args.steps / 2**30,
-            "note": "buffered pread/pwrite on the box's disk, host time inside the calls; not part of the PCIe figure"}
+            "note": "buffered pread (hook thread) / pwrite (writer thread, behind the hook thread) on the box's "
+                    "disk, time inside the calls; not part of the PCIe figure"}
     if not args.no_pack:
         pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)
         unpack_gbs, unpack_ms, _, _ = bench_pack(torch, T, unpack=True)

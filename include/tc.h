@@ -208,15 +208,22 @@ int tc_plan_schedule(tc_ctx *ctx, tc_placement *out);
  *   pinned_region  pinned, >= plan.host_total bytes, 256-byte aligned
  *   staging        pinned bounce buffer for the file tier (may be NULL with
  *                  staging_bytes 0 if no tensor ever touches the file tier;
- *                  otherwise at least twice the largest tensor)
+ *                  otherwise at least twice the largest tensor).  It is used
+ *                  as a ring: the deeper it is, the more file reads, copies
+ *                  and file writes of successive hook calls overlap (eight
+ *                  times the largest tensor is a good size).
  *   file_fd        open read/write file of >= plan.file_total bytes, or -1.
  *                  With TC_BIND_FILE_DIRECT (a file opened with O_DIRECT, to
  *                  bypass the page cache) every request is 4 KiB aligned in
  *                  memory, offset and length and goes through a page-aligned
  *                  bounce block of the library's own (direct I/O cannot
  *                  target GPU-mapped pinned memory); staging must then be
- *                  4 KiB aligned and sized.  File I/O is synchronous in the
- *                  calling thread.
+ *                  4 KiB aligned and sized.  File reads run in the calling
+ *                  thread; file writes are queued to writer threads of the
+ *                  library's own (tc_set_io_writers) and have reached the
+ *                  file when tc_synchronize returns.  A failed write is
+ *                  reported (TC_E_IO) by the next call that queues or waits
+ *                  for one.
  *   migrate_stream hipStream_t the copies are issued on (default priority)
  * With TC_BIND_NULL_MOVER no bytes move and the regions may be NULL: the
  * decision kernel still runs and the op log, stats and state are exact. */
@@ -312,6 +319,14 @@ int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_
 /* Migration-kernel tuning: workgroups per launch (0 = default) and bytes per
  * work chunk (0 = default; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
+
+/* File-tier writes (Sec. 3.4.2: dirty tensors leaving for NVMe; Alg. 4: a host
+ * buffer spilled to make room) run behind the calling thread on `writers`
+ * threads (0..16; default 1).  A tensor's extent always belongs to the same
+ * writer, so its writes keep their order, and a read of an extent first waits
+ * for the write queued for it.  0 = every write runs in the calling thread.
+ * On a bound context the call first waits for everything in flight. */
+int tc_set_io_writers(tc_ctx *ctx, uint32_t writers);
 
 /* While a migration launch is still running, the copies of further hook calls
  * are held back and merged into one launch, until `bytes` bytes are prepared,

@@ -120,6 +120,7 @@ def load_library(path: str = LIB_PATH):
         "tc_mover_timing": (i32, [vp, i32, C.POINTER(Timing)]),
         "tc_set_dma_threshold": (i32, [vp, u64]),
         "tc_set_merge_bytes": (i32, [vp, u64]),
+        "tc_set_io_writers": (i32, [vp, u32]),
         "tc_set_replay_window": (i32, [vp, u32]),
         "tc_copy_batch": (i32, [vp, u32, vp, u32, u32]),
         "tc_exchange_batch": (i32, [vp, vp, u32, vp, u32, u32]),
@@ -258,7 +259,7 @@ class TensorCache:
                                          staging_ptr or None, staging_bytes, file_fd, migrate_stream or None, flags))
 
     def bind_torch(self, *, staging_bytes: int = 0, file_path: Optional[str] = None, null_mover: bool = False,
-                   stream=None, direct: bool = False):
+                   stream=None, direct: bool = False, file_fd: Optional[int] = None):
         """Allocates the regions and binds them: device memory and the streams
         come from PyTorch, the pinned regions straight from hipHostMalloc
         (PyTorch's pinned allocator rounds every request up to a power of two,
@@ -275,7 +276,9 @@ class TensorCache:
         staging = _PinnedRegion(max(4096, int(staging_bytes)))
         self.mstream = stream if stream is not None else torch.cuda.Stream(device=dev)
         fd = -1
-        if file_path is not None:
+        if file_fd is not None:                 # an open descriptor of the caller's (closed with the context)
+            fd = int(file_fd)
+        elif file_path is not None:
             fd = os.open(file_path, os.O_RDWR | os.O_CREAT | (os.O_DIRECT if direct else 0), 0o600)
             os.ftruncate(fd, int(self.plan.file_total))
         self._fd = fd
@@ -381,6 +384,9 @@ class TensorCache:
 
     def set_merge_bytes(self, nbytes: int):
         self._check(lib().tc_set_merge_bytes(self._h, int(nbytes)))
+
+    def set_io_writers(self, writers: int):
+        self._check(lib().tc_set_io_writers(self._h, int(writers)))
 
     def set_replay_window(self, steps: int):
         self._check(lib().tc_set_replay_window(self._h, int(steps)))

@@ -10,9 +10,13 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
-
+#include <condition_variable>
 #include <deque>
+#include <memory>
+#include <mutex>
+#include <thread>
 
 namespace {
 
@@ -24,10 +28,39 @@ enum { S_K = 0, S_H = 1, S_D = 2, N_STREAMS = 3 };
 
 const uint32_t OP_RING = 1024;          // events kept for the most recent copy operations
 
-struct Pending {            // file write that must wait for a copy operation
-    uint64_t op;
+// File writes run behind the hook thread: a job names the bytes, the extent and
+// (for bytes a copy is still producing) an event to wait for.  A tensor always
+// goes to the same writer, and a writer works in order, so two writes of one
+// extent land in the order they were issued.
+struct IoJob {
+    uint64_t seq;
+    hipEvent_t ev;          // nullptr: the bytes are ready
     const uint8_t *src;
-    uint64_t bytes, file_off;
+    uint64_t bytes, off;
+};
+
+struct IoWriter {
+    std::thread th;
+    std::mutex mu;
+    std::condition_variable cv_job, cv_done;
+    std::deque<IoJob> q;
+    uint64_t issued = 0;    // hook thread only
+    uint64_t done = 0;      // under mu
+    bool quit = false;      // under mu
+    uint8_t *bounce = nullptr;                              // O_DIRECT: page-aligned block of its own
+    std::deque<std::pair<uint64_t, hipEvent_t>> ev_busy;    // hook thread only: events of queued jobs
+};
+
+struct JobRef {             // a queued write; seq 0: none
+    uint32_t w = 0;
+    uint64_t seq = 0;
+};
+
+struct StBlock {            // live piece of the staging ring
+    uint64_t id, off, size;
+    uint64_t ops[2];        // copies that read or write it
+    JobRef job;             // write that reads it
+    bool issued;            // its unit has been launched (ops and job are final)
 };
 
 struct BounceBlock {        // live piece of the HBM bounce ring
@@ -41,6 +74,7 @@ struct PUnit {              // one exchange unit being prepared
     int64_t cpu_in = -1;    // flat index of the host buffer the incoming tensor comes from
     bool out_staging = false, in_staging = false;
     uint32_t out_tensor = 0;
+    uint64_t st_id = 0;     // its block of the staging ring (0: none)
 };
 
 struct Timed {              // event pair around one timed operation
@@ -95,12 +129,22 @@ struct tc_ctx {
     bool compute_recorded = false;      // this hook call: ev_compute recorded
     bool stream_waited[N_STREAMS]{};    // this hook call: stream already waits for ev_compute
     std::vector<uint64_t> gpu_ticket, cpu_ticket;   // last operation that touched the buffer
-    uint64_t staging_ticket[N_STREAMS]{};
-    uint64_t staging_used = 0;
+    std::deque<StBlock> st_q;           // staging ring, oldest block first
+    uint64_t st_head = 0, st_next_id = 1;
     uint8_t *bounce = nullptr;          // HBM ring: outgoing large tensors wait here for their DMA copy
     uint64_t bounce_bytes = 0, bounce_head = 0;
     std::deque<BounceBlock> bounce_q;
-    std::vector<Pending> pending;
+    // write-behind file tier
+    int device = 0;
+    uint32_t n_writers = 1;             // 0: writes run in the calling thread
+    std::vector<std::unique_ptr<IoWriter>> writers;
+    std::vector<hipEvent_t> ev_free;
+    std::vector<JobRef> tensor_job;     // per tensor: newest queued write of its extent
+    std::vector<JobRef> cpu_job;        // per host buffer: queued write that reads it
+    std::atomic<uint64_t> wr_ns{0};     // time the writers spent in pwrite
+    std::mutex io_mu;
+    std::string io_err;                 // first failure of a writer (under io_mu)
+    std::atomic<bool> io_failed{false};
     // units prepared but not issued yet: hook calls are merged into larger launches
     std::vector<PUnit> deferred;
     uint64_t deferred_bytes = 0;
@@ -157,8 +201,15 @@ extern "C" int tc_create(tc_ctx **out)
     return *out ? TC_OK : TC_E_CAPACITY;
 }
 
+static void io_stop(tc_ctx *c);
+static int io_start(tc_ctx *c, uint32_t n);
+static int io_wait_all(tc_ctx *c);
+
 static void release_device(tc_ctx *c)
 {
+    io_stop(c);
+    for (hipEvent_t e : c->ev_free) (void)hipEventDestroy(e);
+    c->ev_free.clear();
     if (c->dstream) { (void)hipStreamSynchronize(c->dstream); }
     for (int i = 0; i < N_STREAMS; ++i)
         if (c->streams[i] || (i == S_K && c->stage >= 4)) { (void)hipStreamSynchronize(c->streams[i]); }
@@ -375,6 +426,14 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->cpu_ticket.assign(pl.cpu_slots, 0);
     c->gpu_pending.assign(pl.gpu_slots, 0);
     c->cpu_pending.assign(pl.cpu_slots, 0);
+    c->tensor_job.assign(n_t, JobRef{});
+    c->cpu_job.assign(pl.cpu_slots, JobRef{});
+    e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    if (fd >= 0 && !null_mover) {
+        int rc = io_start(c, c->n_writers);
+        if (rc != TC_OK) { release_device(c); return rc; }
+    }
     c->stage = 4;
     return TC_OK;
 }
@@ -487,16 +546,24 @@ static int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes)
 static inline uint64_t io_align(const tc_ctx *c) { return c->file_direct ? 4096 : 256; }
 static inline uint64_t io_len(const tc_ctx *c, uint64_t n) { return c->file_direct ? (n + 4095) & ~4095ull : n; }
 
+// pwrite until everything is out; no context state is touched (writer threads use it)
+static bool pwrite_all(int fd, const uint8_t *src, uint64_t bytes, uint64_t off, std::string &err)
+{
+    while (bytes) {
+        ssize_t w = pwrite(fd, src, bytes, (off_t)off);
+        if (w < 0 && errno == EINTR) continue;
+        if (w <= 0) { err = std::string("pwrite: ") + strerror(errno); return false; }
+        src += w; off += (uint64_t)w; bytes -= (uint64_t)w;
+    }
+    return true;
+}
+
 static int file_write_raw(tc_ctx *c, const uint8_t *src, uint64_t bytes, uint64_t off)
 {
     if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
     const auto t0 = std::chrono::steady_clock::now();
-    while (bytes) {
-        ssize_t w = pwrite(c->fd, src, bytes, (off_t)off);
-        if (w < 0 && errno == EINTR) continue;
-        if (w <= 0) return fail(c, TC_E_IO, std::string("pwrite: ") + strerror(errno));
-        src += w; off += (uint64_t)w; bytes -= (uint64_t)w;
-    }
+    std::string err;
+    if (!pwrite_all(c->fd, src, bytes, off, err)) return fail(c, TC_E_IO, err);
     c->stats.file_write_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
                                   std::chrono::steady_clock::now() - t0).count();
     return TC_OK;
@@ -560,16 +627,184 @@ static int file_read(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t off)
 // comes from per-buffer tickets: each buffer remembers the last operation that
 // touched it, and an operation waits for the tickets of the buffers it touches.
 // ---------------------------------------------------------------------------
-// writes that waited for a copy (GPU buffer -> staging -> file)
-static int drain_pending(tc_ctx *c)
+// ---- write-behind ------------------------------------------------------------
+// one write, by a writer thread (w) or by the calling thread (w == nullptr)
+static void io_run_job(tc_ctx *c, IoWriter *w, const IoJob &j)
 {
-    for (const Pending &p : c->pending) {
-        int rc = wait_op(c, p.op);
-        if (rc != TC_OK) return rc;
-        rc = file_write(c, p.src, p.bytes, p.file_off);
-        if (rc != TC_OK) return rc;
+    std::string err;
+    if (j.ev) {
+        hipError_t e = hipEventSynchronize(j.ev);
+        if (e != hipSuccess) err = std::string("hipEventSynchronize (file write): ") + hipGetErrorString(e);
     }
-    c->pending.clear();
+    if (err.empty()) {
+        const auto t0 = std::chrono::steady_clock::now();
+        const uint8_t *src = j.src;
+        uint64_t len = j.bytes;
+        if (c->file_direct) {
+            uint8_t *blk = w ? w->bounce : c->io_bounce;
+            len = io_len(c, j.bytes);
+            memcpy(blk, j.src, j.bytes);
+            memset(blk + j.bytes, 0, len - j.bytes);
+            src = blk;
+        }
+        pwrite_all(c->fd, src, len, j.off, err);
+        c->wr_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                        std::chrono::steady_clock::now() - t0).count();
+    }
+    if (!err.empty()) {
+        std::lock_guard<std::mutex> g(c->io_mu);
+        if (!c->io_failed.load()) { c->io_err = err; c->io_failed.store(true); }
+    }
+}
+
+static void io_writer_main(tc_ctx *c, IoWriter *w)
+{
+    (void)hipSetDevice(c->device);
+    for (;;) {
+        IoJob j;
+        {
+            std::unique_lock<std::mutex> lk(w->mu);
+            w->cv_job.wait(lk, [&] { return w->quit || !w->q.empty(); });
+            if (w->q.empty()) return;                  // quit, and nothing left to write
+            j = w->q.front();
+            w->q.pop_front();
+        }
+        io_run_job(c, w, j);
+        {
+            std::lock_guard<std::mutex> g(w->mu);
+            w->done = j.seq;
+        }
+        w->cv_done.notify_all();
+    }
+}
+
+// a writer's failure surfaces at the next call that waits for or queues a write
+static int io_check(tc_ctx *c)
+{
+    if (!c->io_failed.load()) return TC_OK;
+    std::lock_guard<std::mutex> g(c->io_mu);
+    return fail(c, TC_E_IO, c->io_err);
+}
+
+static bool io_done(tc_ctx *c, const JobRef &r)
+{
+    if (!r.seq || r.w >= c->writers.size()) return true;
+    IoWriter &w = *c->writers[r.w];
+    std::lock_guard<std::mutex> g(w.mu);
+    return w.done >= r.seq;
+}
+
+static int io_wait(tc_ctx *c, JobRef &r)
+{
+    if (r.seq && r.w < c->writers.size()) {
+        IoWriter &w = *c->writers[r.w];
+        std::unique_lock<std::mutex> lk(w.mu);
+        w.cv_done.wait(lk, [&] { return w.done >= r.seq; });
+    }
+    r.seq = 0;
+    return io_check(c);
+}
+
+static int io_wait_all(tc_ctx *c)
+{
+    for (auto &pw : c->writers) {
+        IoWriter &w = *pw;
+        {
+            std::unique_lock<std::mutex> lk(w.mu);
+            w.cv_done.wait(lk, [&] { return w.done >= w.issued; });
+        }
+        for (auto &e : w.ev_busy) c->ev_free.push_back(e.second);
+        w.ev_busy.clear();
+    }
+    return io_check(c);
+}
+
+static void io_stop(tc_ctx *c)
+{
+    (void)io_wait_all(c);
+    for (auto &pw : c->writers) {
+        {
+            std::lock_guard<std::mutex> g(pw->mu);
+            pw->quit = true;
+        }
+        pw->cv_job.notify_all();
+        if (pw->th.joinable()) pw->th.join();
+        if (pw->bounce) free(pw->bounce);
+    }
+    c->writers.clear();
+    for (JobRef &r : c->tensor_job) r = JobRef{};
+    for (JobRef &r : c->cpu_job) r = JobRef{};
+    for (StBlock &b : c->st_q) b.job = JobRef{};
+}
+
+static int io_start(tc_ctx *c, uint32_t n)
+{
+    for (uint32_t i = 0; i < n; ++i) {
+        std::unique_ptr<IoWriter> w(new (std::nothrow) IoWriter());
+        if (!w) return fail(c, TC_E_CAPACITY, "no memory for a writer");
+        if (c->file_direct) {
+            void *blk = nullptr;
+            if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) return fail(c, TC_E_CAPACITY, "no memory for a writer's bounce block");
+            w->bounce = (uint8_t *)blk;
+        }
+        try {
+            w->th = std::thread(io_writer_main, c, w.get());
+        } catch (...) {
+            if (w->bounce) free(w->bounce);
+            return fail(c, TC_E_CAPACITY, "could not start a writer thread");
+        }
+        c->writers.push_back(std::move(w));
+    }
+    return TC_OK;
+}
+
+// Queue the write of tensor t's extent from `src`.  op != 0: the bytes are
+// being produced by copy operation `op`, issued on stream S a moment ago.
+static int io_enqueue(tc_ctx *c, uint32_t t, uint64_t op, int S, const uint8_t *src, JobRef *ref)
+{
+    *ref = JobRef{};
+    if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
+    int rc = io_check(c);
+    if (rc != TC_OK) return rc;
+    IoJob j{0, nullptr, src, c->prof.bytes[t], c->place.file_off[t]};
+    if (c->file_direct && io_len(c, j.bytes) > c->io_bounce_bytes)
+        return fail(c, TC_E_CAPACITY, "tensor larger than the I/O bounce block");
+    if (c->writers.empty()) {
+        if ((rc = wait_op(c, op)) != TC_OK) return rc;
+        io_run_job(c, nullptr, j);
+        return io_check(c);
+    }
+    const uint32_t wi = t % (uint32_t)c->writers.size();
+    IoWriter &w = *c->writers[wi];
+    if (op) {
+        if (c->ev_free.empty()) {
+            HIP_TRY(c, hipEventCreateWithFlags(&j.ev, hipEventDisableTiming | hipEventBlockingSync));
+        } else {
+            j.ev = c->ev_free.back();
+            c->ev_free.pop_back();
+        }
+        hipError_t e = hipEventRecord(j.ev, c->streams[S]);
+        if (e != hipSuccess) {
+            c->ev_free.push_back(j.ev);
+            return fail(c, TC_E_HIP, std::string("hipEventRecord (file write): ") + hipGetErrorString(e));
+        }
+    }
+    j.seq = ++w.issued;
+    uint64_t done;
+    {
+        std::lock_guard<std::mutex> g(w.mu);
+        done = w.done;
+        w.q.push_back(j);
+    }
+    w.cv_job.notify_one();
+    if (j.ev) w.ev_busy.push_back({j.seq, j.ev});
+    while (!w.ev_busy.empty() && w.ev_busy.front().first <= done) {
+        c->ev_free.push_back(w.ev_busy.front().second);
+        w.ev_busy.pop_front();
+    }
+    ref->w = wi;
+    ref->seq = j.seq;
+    c->tensor_job[t] = *ref;
     return TC_OK;
 }
 
@@ -604,10 +839,23 @@ static int bounce_alloc(tc_ctx *c, uint64_t bytes, uint8_t **out)
     }
 }
 
+static StBlock *st_find(tc_ctx *c, uint64_t id)
+{
+    for (StBlock &b : c->st_q)
+        if (b.id == id) return &b;
+    return nullptr;
+}
+
 // issue the prepared units of a hook call
 static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute)
 {
     if (units.empty()) return TC_OK;
+    // a host buffer some unit is about to overwrite may still be the source of a queued spill
+    for (const PUnit &p : units)
+        if (p.cpu_out >= 0) {
+            int rc = io_wait(c, c->cpu_job[(size_t)p.cpu_out]);
+            if (rc != TC_OK) return rc;
+        }
     struct Large { size_t unit; uint8_t *bounce; uint64_t kop; };
     std::vector<Large> large;
     std::vector<size_t> small;
@@ -667,9 +915,11 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
                 c->gpu_ticket[(size_t)p.gpu_y] = id;
                 if (p.cpu_out >= 0) c->cpu_ticket[(size_t)p.cpu_out] = id;
                 if (p.cpu_in >= 0) c->cpu_ticket[(size_t)p.cpu_in] = id;
-                if (p.out_staging || p.in_staging) c->staging_ticket[S_K] = id;
-                if (p.out_staging)
-                    c->pending.push_back(Pending{id, p.u.out_dst, c->prof.bytes[p.out_tensor], c->place.file_off[p.out_tensor]});
+                if (StBlock *b = p.st_id ? st_find(c, p.st_id) : nullptr) {
+                    b->issued = true;
+                    b->ops[0] = id;
+                    if (p.out_staging && (rc = io_enqueue(c, p.out_tensor, id, S_K, p.u.out_dst, &b->job)) != TC_OK) return rc;
+                }
             } else {
                 Large &L = large[(size_t)kunits[k].second];
                 L.kop = id;
@@ -692,7 +942,11 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         if ((rc = end_op(c, S_H, idh)) != TC_OK) return rc;
         c->gpu_ticket[(size_t)p.gpu_y] = idh;
         if (p.cpu_in >= 0) c->cpu_ticket[(size_t)p.cpu_in] = idh;
-        if (p.in_staging) c->staging_ticket[S_H] = idh;
+        StBlock *blk = p.st_id ? st_find(c, p.st_id) : nullptr;
+        if (blk) {
+            blk->issued = true;
+            if (p.in_staging) blk->ops[0] = idh;
+        }
         c->stats.dma_copies++;
         if (!L.bounce) continue;
         if ((rc = begin_op(c, S_D, compute, &idd)) != TC_OK) return rc;
@@ -709,9 +963,9 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         for (BounceBlock &blk : c->bounce_q)
             if (c->bounce + blk.off == L.bounce) blk.op = idd;
         c->stats.dma_copies++;
-        if (p.out_staging) {
-            c->staging_ticket[S_D] = idd;
-            c->pending.push_back(Pending{idd, p.u.out_dst, c->prof.bytes[p.out_tensor], c->place.file_off[p.out_tensor]});
+        if (p.out_staging && blk) {
+            blk->ops[1] = idd;
+            if ((rc = io_enqueue(c, p.out_tensor, idd, S_D, p.u.out_dst, &blk->job)) != TC_OK) return rc;
         }
     }
     for (const PUnit &p : units) {
@@ -730,39 +984,58 @@ static int flush_deferred(tc_ctx *c, hipStream_t compute)
     if (c->deferred.empty()) return TC_OK;
     c->compute_recorded = false;
     for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
-    int rc = issue_units(c, c->deferred, compute);
-    if (rc != TC_OK) return rc;
-    return drain_pending(c);
+    return issue_units(c, c->deferred, compute);
 }
 
-static int staging_wait_all(tc_ctx *c)
-{
-    for (int i = 0; i < N_STREAMS; ++i) {
-        int rc = wait_op(c, c->staging_ticket[i]);
-        if (rc != TC_OK) return rc;
-    }
-    return TC_OK;
-}
-
-static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, hipStream_t compute, uint8_t **out)
+// The staging region is a ring: a block is taken when a record needs bounce
+// space for the file tier and is free again once the copies that touch it have
+// completed and, for an outgoing tensor, its write has reached the file.  Blocks
+// free in the order they were taken, so file reads, copies and writes of
+// successive hook calls overlap as far as the ring is deep.
+static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, hipStream_t compute, uint8_t **out,
+                         uint64_t *id)
 {
     const uint64_t need = (bytes + io_align(c) - 1) & ~(io_align(c) - 1);
     if (need > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a tensor that needs the file tier");
-    if (c->staging_used + need > c->staging_bytes) {
-        // out of bounce space: issue what is prepared, let it finish, start over
-        int rc = issue_units(c, units, compute);
+    for (;;) {
+        while (!c->st_q.empty()) {
+            const StBlock &f = c->st_q.front();
+            if (!(f.issued && poll_op(c, f.ops[0]) && poll_op(c, f.ops[1]) && io_done(c, f.job))) break;
+            c->st_q.pop_front();
+        }
+        if (c->st_q.empty()) c->st_head = 0;
+        const uint64_t tail = c->st_q.empty() ? 0 : c->st_q.front().off;
+        uint64_t at = UINT64_MAX;
+        if (c->st_q.empty() || c->st_head > tail) {                // free: [head, end) and [0, tail)
+            if (c->st_head + need <= c->staging_bytes) at = c->st_head;
+            else if (!c->st_q.empty() && need <= tail) at = 0;
+        } else if (c->st_head < tail) {                            // free: [head, tail)
+            if (c->st_head + need <= tail) at = c->st_head;
+        }
+        if (at != UINT64_MAX) {
+            StBlock b{};
+            b.id = c->st_next_id++;
+            b.off = at;
+            b.size = need;
+            c->st_q.push_back(b);
+            c->st_head = at + need;
+            *out = c->staging + at;
+            *id = b.id;
+            return TC_OK;
+        }
+        // no room: the oldest block has to go first
+        if (!c->st_q.front().issued) {
+            int rc = issue_units(c, units, compute);
+            if (rc != TC_OK) return rc;
+            if (!c->st_q.front().issued) return fail(c, TC_E_STATE, "staging ring holds a block no prepared unit owns");
+        }
+        StBlock &f = c->st_q.front();
+        int rc = wait_op(c, f.ops[0]);
+        if (rc == TC_OK) rc = wait_op(c, f.ops[1]);
+        if (rc == TC_OK) rc = io_wait(c, f.job);
         if (rc != TC_OK) return rc;
-        rc = drain_pending(c);
-        if (rc != TC_OK) return rc;
-        c->staging_used = 0;
+        c->st_q.pop_front();
     }
-    if (c->staging_used == 0) {
-        int rc = staging_wait_all(c);                 // earlier copies that still read the space
-        if (rc != TC_OK) return rc;
-    }
-    *out = c->staging + c->staging_used;
-    c->staging_used += need;
-    return TC_OK;
 }
 
 static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step, int phase,
@@ -779,7 +1052,6 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
     PUnit pend{};                   // outgoing half waiting for its incoming partner
     bool have_out = false;
     uint8_t *reserved_in = nullptr; // bounce space kept for the partner of a write-back
-    c->staging_used = 0;
     c->compute_recorded = false;
     for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
     for (uint32_t i = 0; i < o->n_ops; ++i) {
@@ -825,7 +1097,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             rc = wait_op(c, c->cpu_ticket[flat]);
             if (rc != TC_OK) return rc;
             must_issue = true;
-            rc = file_write(c, cpu_addr(c, s, r.src_slot), n, c->place.file_off[t]);
+            rc = io_enqueue(c, t, 0, 0, cpu_addr(c, s, r.src_slot), &c->cpu_job[flat]);
             if (rc != TC_OK) return rc;
             break;
         }
@@ -844,10 +1116,12 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             // incoming tensor of the same class should it come from the file tier
             uint8_t *st = nullptr;
             const uint64_t half = (n + io_align(c) - 1) & ~(io_align(c) - 1);
-            int rc = staging_alloc(c, units, 2 * half, compute, &st);
+            uint64_t st_id = 0;
+            int rc = staging_alloc(c, units, 2 * half, compute, &st, &st_id);
             if (rc != TC_OK) return rc;
             reserved_in = st + half;
             pend = PUnit{};
+            pend.st_id = st_id;
             pend.u.out_src = gpu_addr(c, s, r.src_slot);
             pend.u.out_dst = st;
             pend.u.bytes = n;
@@ -870,8 +1144,9 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
                 uint8_t *st = nullptr;
                 int rc = TC_OK;
                 if (have_out && p.out_staging) st = reserved_in;
-                else rc = staging_alloc(c, units, n, compute, &st);
+                else rc = staging_alloc(c, units, n, compute, &st, &p.st_id);
                 if (rc != TC_OK) return rc;
+                if ((rc = io_wait(c, c->tensor_job[t])) != TC_OK) return rc;   // a queued write of this very extent
                 rc = file_read(c, st, n, c->place.file_off[t]);
                 if (rc != TC_OK) return rc;
                 p.u.in_src = st;
@@ -899,11 +1174,12 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             if (rc != TC_OK) return rc;
             // the same end-of-iteration call may have written this very tensor back to
             // its extent a moment ago: that write has to reach the file first
-            rc = drain_pending(c);
+            rc = io_wait(c, c->tensor_job[t]);
             if (rc != TC_OK) return rc;
             const uint32_t flat = c->pools.cpu_base[s] + r.dst_slot;
             rc = wait_op(c, c->cpu_ticket[flat]);
             if (rc != TC_OK) return rc;
+            if ((rc = io_wait(c, c->cpu_job[flat])) != TC_OK) return rc;
             rc = file_read(c, cpu_addr(c, s, r.dst_slot), n, c->place.file_off[t]);
             if (rc != TC_OK) return rc;
             break;
@@ -912,12 +1188,11 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
         }
     }
     if (c->null_mover) return TC_OK;
+    if (have_out) return fail(c, TC_E_HIP, "decision records end with an eviction that has no incoming tensor");
     if (!must_issue && phase < TC_END && c->deferred_bytes < c->merge_bytes &&
         units.size() < 4 * TC_MOVER_MAX_UNITS && !poll_op(c, c->last_k_op))
         return TC_OK;                                  // the link is busy: keep them for a larger launch
-    int rc = issue_units(c, units, compute);
-    if (rc != TC_OK) return rc;
-    return drain_pending(c);
+    return issue_units(c, units, compute);
 }
 
 static int run_decide(tc_ctx *c, const TcStepArgs &a)
@@ -1156,6 +1431,9 @@ extern "C" int tc_synchronize(tc_ctx *c)
             if (i == S_K || c->streams[i]) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
             c->op_done[i] = c->op_id;
         }
+        rc = io_wait_all(c);                           // queued file writes
+        if (rc != TC_OK) return rc;
+        c->st_q.clear();
     }
     return TC_OK;
 }
@@ -1164,6 +1442,7 @@ extern "C" int tc_cache_stats(const tc_ctx *c, tc_stats *out)
 {
     if (!c || !out) return TC_E_ARG;
     *out = c->stats;
+    out->file_write_ns += c->wr_ns.load();
     return TC_OK;
 }
 
@@ -1324,6 +1603,18 @@ extern "C" int tc_mover_timing(tc_ctx *c, int enable, tc_timing *out)
     }
     c->timing = enable != 0;
     return TC_OK;
+}
+
+extern "C" int tc_set_io_writers(tc_ctx *c, uint32_t writers)
+{
+    if (!c) return TC_E_ARG;
+    if (writers > 16) return fail(c, TC_E_ARG, "at most 16 writer threads");
+    c->n_writers = writers;
+    if (c->stage != 4 || c->fd < 0 || c->null_mover) return TC_OK;
+    int rc = tc_synchronize(c);
+    if (rc != TC_OK) return rc;
+    io_stop(c);
+    return io_start(c, writers);
 }
 
 extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)

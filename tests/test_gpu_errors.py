@@ -105,6 +105,23 @@ def test_file_tier_errors_are_return_codes(tmp_path):
     tc.close()
 
 
+def test_failed_background_write_is_reported(tmp_path):
+    # /dev/full takes no byte: every queued write fails in its writer thread, and the next
+    # call that queues or waits for a write (at the latest tc_synchronize) returns TC_E_IO
+    wl = W.random_workload(3, n_tensors=60, n_steps=40, max_per_step=2, sizes=(4096, 33000), hbm_frac=0.1,
+                           host_frac=0.3, n_iterations=1)
+    for writers in (2, 0):
+        tc = _planned(wl)
+        tc.bind_torch(file_fd=os.open("/dev/full", os.O_RDWR), staging_bytes=1 << 20)
+        tc.set_io_writers(writers)
+        cs = torch.cuda.Stream()
+        with pytest.raises(T.TcError) as e:
+            tc.replay_iteration_c(wl.iterations[0], cs.cuda_stream)
+            tc.synchronize()
+        assert e.value.code == E_IO and "pwrite" in str(e.value)
+        tc.close()
+
+
 def test_null_mover_context_refuses_payload_calls():
     wl = W.example_cpu_gpu()
     tc = _planned(wl)

@@ -351,6 +351,36 @@ def test_op_log_can_be_cleared_and_switched_off():
     tc.close()
 
 
+@pytest.mark.parametrize("writers", [0, 1, 2, 5])
+@pytest.mark.parametrize("staging", ["tight", "deep"])
+def test_write_behind_keeps_every_byte(writers, staging, tmp_path):
+    # file writes run behind the hook thread: whatever the number of writer threads and
+    # however shallow the staging ring (twice the largest tensor = one block at a time),
+    # the schedule and every byte are those of the oracle
+    for seed in (4, 7):
+        wl = _random(seed)
+        big = int(wl.tensor_bytes.max())
+        half = (big + 255) // 256 * 256
+        tc = run_library(wl, file_path=_tmpfile(tmp_path, f"wb{seed}.bin"),
+                         staging_bytes=2 * half if staging == "tight" else 16 * half,
+                         window=(None if seed == 4 else 32), io_writers=writers)
+        r = check_against_oracle(wl, tc)
+        assert r.bytes_file_write > 0 and r.bytes_file_read > 0
+        tc.close()
+
+
+def test_write_behind_with_dma_copies_and_o_direct(tmp_path):
+    wl = _random(5)
+    direct = _direct_ok(tmp_path)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=4 << 20, dma_threshold=1 << 15, direct=direct,
+                     window=16, io_writers=3)
+    r = check_against_oracle(wl, tc)
+    assert r.bytes_file_write > 0
+    st = tc.cache_stats()
+    assert st["dma_copies"] > 0 and st["file_write_ns"] > 0
+    tc.close()
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_settings_keep_the_schedule_and_every_byte(seed, tmp_path):
     # the launch shape must never matter: random combinations of window, merge size, DMA
@@ -366,7 +396,7 @@ def test_random_settings_keep_the_schedule_and_every_byte(seed, tmp_path):
                      merge_bytes=int(rng.choice([0, 1 << 16, 1 << 22, 1 << 30])),
                      dma_threshold=int(rng.choice([0, 0, 1 << 16, 1 << 18])) or None,
                      mover=(int(rng.choice([1, 8, 64, 300])), int(rng.choice([4096, 16384, 65536, 1 << 20]))),
-                     busy=bool(rng.integers(0, 2)), direct=direct)
+                     busy=bool(rng.integers(0, 2)), direct=direct, io_writers=int(rng.integers(0, 4)))
     r = check_against_oracle(wl, tc)
     assert len(r.log) > 100
     tc.close()
