@@ -218,12 +218,11 @@ int tc_plan_schedule(tc_ctx *ctx, tc_placement *out);
  *                  memory, offset and length and goes through a page-aligned
  *                  bounce block of the library's own (direct I/O cannot
  *                  target GPU-mapped pinned memory); staging must then be
- *                  4 KiB aligned and sized.  File reads run in the calling
- *                  thread; file writes are queued to writer threads of the
- *                  library's own (tc_set_io_writers) and have reached the
- *                  file when tc_synchronize returns.  A failed write is
- *                  reported (TC_E_IO) by the next call that queues or waits
- *                  for one.
+ *                  4 KiB aligned and sized.  File reads and writes are
+ *                  queued to worker threads of the library's own
+ *                  (tc_set_io_threads); writes have reached the file when
+ *                  tc_synchronize returns.  A failed request is reported
+ *                  (TC_E_IO) by the next call that queues or waits for one.
  *   migrate_stream hipStream_t the copies are issued on (default priority)
  * With TC_BIND_NULL_MOVER no bytes move and the regions may be NULL: the
  * decision kernel still runs and the op log, stats and state are exact. */
@@ -320,13 +319,35 @@ int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_
  * work chunk (0 = default; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
 
-/* File-tier writes (Sec. 3.4.2: dirty tensors leaving for NVMe; Alg. 4: a host
- * buffer spilled to make room) run behind the calling thread on `writers`
- * threads (0..16; default 1).  A tensor's extent always belongs to the same
- * writer, so its writes keep their order, and a read of an extent first waits
- * for the write queued for it.  0 = every write runs in the calling thread.
- * On a bound context the call first waits for everything in flight. */
-int tc_set_io_writers(tc_ctx *ctx, uint32_t writers);
+/* File-tier I/O runs behind the calling thread.  Writes (Sec. 3.4.2: dirty
+ * tensors leaving for NVMe; Alg. 4: a host buffer spilled to make room) go to
+ * `writers` threads, reads into staging (a fetch from the file tier) to
+ * `readers` threads (0..8 each; default 4 and 4).  An extent is cut into
+ * chunks (tc_set_io_chunk); chunk i of tensor t belongs to lane t + i, and the lane picks the
+ * worker, so one large request spreads over the threads while a given chunk
+ * always goes to the same writer: writes of one extent keep their order.  A
+ * read of an extent is queued only after the write queued for it has finished.
+ * A copy whose bytes are still on their way from the file is launched by the
+ * first later call that finds the read finished, at the latest by the call
+ * that needs one of its buffers (which then waits).  0 = that kind of I/O runs
+ * in the calling thread.  On a bound context the call first waits for
+ * everything in flight. */
+int tc_set_io_threads(tc_ctx *ctx, uint32_t writers, uint32_t readers);
+
+/* Bytes per chunk of an extent (a multiple of 4096, at least 64 KiB; default
+ * 8 MiB): the size of one request to the file system and the unit of striping.
+ * Only before the first request to the file tier (TC_E_STATE afterwards). */
+int tc_set_io_chunk(tc_ctx *ctx, uint64_t bytes);
+
+/* Stripes the file tier over one more file (at most 8 in all, the first being
+ * tc_bind_memory's file_fd): with n files the chunk of lane l lives in file
+ * l mod n, at the offset it would have in a single file, so every file must
+ * allow offsets up to plan.file_total (files may be sparse) and be opened the
+ * way file_fd was (O_DIRECT or not).  Several files let buffered writes, which
+ * a file system serialises per file, and several devices work in parallel.
+ * Only before the first request to the file tier (TC_E_STATE afterwards); the
+ * descriptor stays the caller's. */
+int tc_add_stripe(tc_ctx *ctx, int fd);
 
 /* While a migration launch is still running, the copies of further hook calls
  * are held back and merged into one launch, until `bytes` bytes are prepared,

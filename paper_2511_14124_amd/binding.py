@@ -120,7 +120,9 @@ def load_library(path: str = LIB_PATH):
         "tc_mover_timing": (i32, [vp, i32, C.POINTER(Timing)]),
         "tc_set_dma_threshold": (i32, [vp, u64]),
         "tc_set_merge_bytes": (i32, [vp, u64]),
-        "tc_set_io_writers": (i32, [vp, u32]),
+        "tc_set_io_threads": (i32, [vp, u32, u32]),
+        "tc_add_stripe": (i32, [vp, i32]),
+        "tc_set_io_chunk": (i32, [vp, u64]),
         "tc_set_replay_window": (i32, [vp, u32]),
         "tc_copy_batch": (i32, [vp, u32, vp, u32, u32]),
         "tc_exchange_batch": (i32, [vp, vp, u32, vp, u32, u32]),
@@ -196,6 +198,9 @@ class TensorCache:
         if getattr(self, "_fd", -1) >= 0:
             os.close(self._fd)
             self._fd = -1
+        for sfd in getattr(self, "_stripe_fds", []):
+            os.close(sfd)
+        self._stripe_fds = []
         if self._keep:
             # regions bind_torch allocated: hand them back to the system, not to
             # PyTorch's caches (a pinned region can be tens of GiB)
@@ -259,7 +264,7 @@ class TensorCache:
                                          staging_ptr or None, staging_bytes, file_fd, migrate_stream or None, flags))
 
     def bind_torch(self, *, staging_bytes: int = 0, file_path: Optional[str] = None, null_mover: bool = False,
-                   stream=None, direct: bool = False, file_fd: Optional[int] = None):
+                   stream=None, direct: bool = False, file_fd: Optional[int] = None, stripes: int = 1):
         """Allocates the regions and binds them: device memory and the streams
         come from PyTorch, the pinned regions straight from hipHostMalloc
         (PyTorch's pinned allocator rounds every request up to a power of two,
@@ -287,6 +292,13 @@ class TensorCache:
         self.bind_memory(hbm.data_ptr(), hbm.numel(), pinned.data_ptr(), pinned.nbytes,
                          staging.data_ptr(), int(staging_bytes), fd, self.mstream.cuda_stream,
                          BIND_FILE_DIRECT if (direct and fd >= 0) else 0)
+        # further files the tier is striped over: file_path.1, file_path.2, ...
+        self._stripe_fds = []
+        for k in range(1, int(stripes) if file_path is not None and file_fd is None else 1):
+            sfd = os.open(f"{file_path}.{k}", os.O_RDWR | os.O_CREAT | (os.O_DIRECT if direct else 0), 0o600)
+            self._stripe_fds.append(sfd)
+            os.ftruncate(sfd, int(self.plan.file_total))
+            self.add_stripe(sfd)
 
     def load_tensor(self, tensor: int, data: np.ndarray):
         data = np.ascontiguousarray(data, dtype=np.uint8)
@@ -385,8 +397,14 @@ class TensorCache:
     def set_merge_bytes(self, nbytes: int):
         self._check(lib().tc_set_merge_bytes(self._h, int(nbytes)))
 
-    def set_io_writers(self, writers: int):
-        self._check(lib().tc_set_io_writers(self._h, int(writers)))
+    def set_io_chunk(self, nbytes: int):
+        self._check(lib().tc_set_io_chunk(self._h, int(nbytes)))
+
+    def add_stripe(self, fd: int):
+        self._check(lib().tc_add_stripe(self._h, int(fd)))
+
+    def set_io_threads(self, writers: int, readers: int):
+        self._check(lib().tc_set_io_threads(self._h, int(writers), int(readers)))
 
     def set_replay_window(self, steps: int):
         self._check(lib().tc_set_replay_window(self._h, int(steps)))

@@ -28,38 +28,48 @@ enum { S_K = 0, S_H = 1, S_D = 2, N_STREAMS = 3 };
 
 const uint32_t OP_RING = 1024;          // events kept for the most recent copy operations
 
-// File writes run behind the hook thread: a job names the bytes, the extent and
-// (for bytes a copy is still producing) an event to wait for.  A tensor always
-// goes to the same writer, and a writer works in order, so two writes of one
-// extent land in the order they were issued.
+// File I/O runs behind the hook thread on worker threads.  A tensor's extent
+// is cut into chunks of IO_CHUNK bytes; chunk i of tensor t belongs to lane
+// t + i, and the lane picks the file (if the tier is striped over several), the
+// writer and the reader.  One request therefore spreads over the workers, while
+// every chunk always goes to the same writer, and a worker works in order: two
+// writes of one extent land in the order they were issued.  A read of an extent
+// is queued only once the write queued for it has finished.  A write job may
+// carry an event to wait for (bytes a copy is still producing).
+const uint32_t IO_MAX_THREADS = 8, IO_MAX_FILES = 8;
+
 struct IoJob {
     uint64_t seq;
-    hipEvent_t ev;          // nullptr: the bytes are ready
-    const uint8_t *src;
+    hipEvent_t ev;          // write: nullptr = the bytes are ready
+    uint8_t *mem;           // write: source, read: destination
     uint64_t bytes, off;
+    int fd;
+    bool read;
 };
 
-struct IoWriter {
+struct IoWorker {
     std::thread th;
     std::mutex mu;
     std::condition_variable cv_job, cv_done;
     std::deque<IoJob> q;
-    uint64_t issued = 0;    // hook thread only
-    uint64_t done = 0;      // under mu
-    bool quit = false;      // under mu
-    uint8_t *bounce = nullptr;                              // O_DIRECT: page-aligned block of its own
-    std::deque<std::pair<uint64_t, hipEvent_t>> ev_busy;    // hook thread only: events of queued jobs
+    uint64_t issued = 0;                // hook thread only
+    std::atomic<uint64_t> done{0};      // stored under mu, polled without
+    bool quit = false;                  // under mu
+    uint8_t *bounce = nullptr;          // O_DIRECT: page-aligned block of its own
 };
 
-struct JobRef {             // a queued write; seq 0: none
-    uint32_t w = 0;
-    uint64_t seq = 0;
+enum { IO_WRITERS = 0, IO_READERS = 1 };
+
+struct JobSet {             // the jobs of one request: per worker the newest of them (0: none)
+    uint8_t pool = IO_WRITERS;
+    bool any = false;
+    uint64_t seq[IO_MAX_THREADS] = {};
 };
 
 struct StBlock {            // live piece of the staging ring
     uint64_t id, off, size;
     uint64_t ops[2];        // copies that read or write it
-    JobRef job;             // write that reads it
+    JobSet job;             // write that reads it
     bool issued;            // its unit has been launched (ops and job are final)
 };
 
@@ -75,6 +85,7 @@ struct PUnit {              // one exchange unit being prepared
     bool out_staging = false, in_staging = false;
     uint32_t out_tensor = 0;
     uint64_t st_id = 0;     // its block of the staging ring (0: none)
+    JobSet read_job;        // file read that fills in_src (in_staging)
 };
 
 struct Timed {              // event pair around one timed operation
@@ -97,9 +108,12 @@ struct tc_ctx {
     // bound memory
     uint8_t *hbm = nullptr, *pinned = nullptr, *staging = nullptr;
     uint64_t hbm_bytes = 0, pinned_bytes = 0, staging_bytes = 0;
-    int fd = -1;
+    int fds[IO_MAX_FILES];              // the file tier: one file, or several that stripe it by lane
+    uint32_t n_files = 0;
+    bool io_begun = false;              // a file request has been made: files and chunk size are final
+    uint64_t io_chunk = 8ull << 20;     // bytes per chunk of an extent
     bool file_direct = false;           // the file was opened with O_DIRECT: 4 KiB aligned memory, offsets and lengths
-    uint8_t *io_bounce = nullptr;       // 4 KiB aligned host block for file I/O of pool buffers in that mode
+    uint8_t *io_bounce = nullptr;       // 4 KiB aligned host block (one chunk) for file I/O done by the calling thread in that mode
     uint64_t io_bounce_bytes = 0;
     hipStream_t streams[N_STREAMS]{};   // [S_K] is the caller's migration stream
     hipStream_t dstream = nullptr;      // decision stream (ours)
@@ -134,14 +148,15 @@ struct tc_ctx {
     uint8_t *bounce = nullptr;          // HBM ring: outgoing large tensors wait here for their DMA copy
     uint64_t bounce_bytes = 0, bounce_head = 0;
     std::deque<BounceBlock> bounce_q;
-    // write-behind file tier
+    // file tier behind the hook thread
     int device = 0;
-    uint32_t n_writers = 1;             // 0: writes run in the calling thread
-    std::vector<std::unique_ptr<IoWriter>> writers;
+    uint32_t n_io[2] = {4, 4};          // writer and reader threads; 0: that kind of I/O runs in the calling thread
+    std::vector<std::unique_ptr<IoWorker>> io[2];
     std::vector<hipEvent_t> ev_free;
-    std::vector<JobRef> tensor_job;     // per tensor: newest queued write of its extent
-    std::vector<JobRef> cpu_job;        // per host buffer: queued write that reads it
-    std::atomic<uint64_t> wr_ns{0};     // time the writers spent in pwrite
+    std::deque<std::pair<hipEvent_t, JobSet>> ev_busy;  // events the queued jobs of a request wait for
+    std::vector<JobSet> tensor_job;     // per tensor: newest queued write of its extent
+    std::vector<JobSet> cpu_job;        // per host buffer: queued write that reads it
+    std::atomic<uint64_t> wr_ns{0}, rd_ns{0};   // time the workers spent in pwrite / pread
     std::mutex io_mu;
     std::string io_err;                 // first failure of a writer (under io_mu)
     std::atomic<bool> io_failed{false};
@@ -202,7 +217,7 @@ extern "C" int tc_create(tc_ctx **out)
 }
 
 static void io_stop(tc_ctx *c);
-static int io_start(tc_ctx *c, uint32_t n);
+static int io_start(tc_ctx *c);
 static int io_wait_all(tc_ctx *c);
 
 static void release_device(tc_ctx *c)
@@ -406,12 +421,14 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->hbm = (uint8_t *)hbm; c->hbm_bytes = hbm_bytes;
     c->pinned = (uint8_t *)pinned; c->pinned_bytes = pinned_bytes;
     c->staging = (uint8_t *)staging; c->staging_bytes = staging_bytes;
-    c->fd = fd;
+    c->n_files = 0;
+    if (fd >= 0) c->fds[c->n_files++] = fd;
+    c->io_begun = false;
     c->file_direct = direct;
     if (direct) {
         uint64_t largest = 0;
         for (uint32_t t = 0; t < n_t; ++t) largest = std::max(largest, p.bytes[t]);
-        c->io_bounce_bytes = (largest + 4095) & ~4095ull;
+        c->io_bounce_bytes = std::min<uint64_t>(c->io_chunk, (largest + 4095) & ~4095ull);
         void *blk = nullptr;
         if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) { release_device(c); return fail(c, TC_E_CAPACITY, "no memory for the I/O bounce block"); }
         c->io_bounce = (uint8_t *)blk;
@@ -426,12 +443,12 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->cpu_ticket.assign(pl.cpu_slots, 0);
     c->gpu_pending.assign(pl.gpu_slots, 0);
     c->cpu_pending.assign(pl.cpu_slots, 0);
-    c->tensor_job.assign(n_t, JobRef{});
-    c->cpu_job.assign(pl.cpu_slots, JobRef{});
+    c->tensor_job.assign(n_t, JobSet{});
+    c->cpu_job.assign(pl.cpu_slots, JobSet{});
     e = hipGetDevice(&c->device);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     if (fd >= 0 && !null_mover) {
-        int rc = io_start(c, c->n_writers);
+        int rc = io_start(c);
         if (rc != TC_OK) { release_device(c); return rc; }
     }
     c->stage = 4;
@@ -558,59 +575,6 @@ static bool pwrite_all(int fd, const uint8_t *src, uint64_t bytes, uint64_t off,
     return true;
 }
 
-static int file_write_raw(tc_ctx *c, const uint8_t *src, uint64_t bytes, uint64_t off)
-{
-    if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
-    const auto t0 = std::chrono::steady_clock::now();
-    std::string err;
-    if (!pwrite_all(c->fd, src, bytes, off, err)) return fail(c, TC_E_IO, err);
-    c->stats.file_write_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
-                                  std::chrono::steady_clock::now() - t0).count();
-    return TC_OK;
-}
-
-static int file_read_raw(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t want, uint64_t off)
-{
-    // `bytes` are requested (rounded for O_DIRECT); at least `want` must arrive: a file
-    // whose last extent ends at the tensor's last byte is not a short read
-    if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
-    const auto t0 = std::chrono::steady_clock::now();
-    uint64_t got = 0;
-    while (got < bytes) {
-        ssize_t r = pread(c->fd, dst + got, bytes - got, (off_t)(off + got));
-        if (r < 0 && errno == EINTR) continue;
-        if (r < 0) return fail(c, TC_E_IO, std::string("pread: ") + strerror(errno));
-        if (r == 0) break;
-        got += (uint64_t)r;
-    }
-    if (got < want) return fail(c, TC_E_IO, "pread: short file");
-    c->stats.file_read_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
-                                 std::chrono::steady_clock::now() - t0).count();
-    return TC_OK;
-}
-
-// O_DIRECT cannot target memory the GPU driver has mapped (pread into a pinned
-// region fails with EFAULT on this kernel), so in that mode every request goes
-// through the bounce block, ordinary page-aligned memory of the library's own.
-static int file_write(tc_ctx *c, const uint8_t *src, uint64_t bytes, uint64_t off)
-{
-    if (!c->file_direct) return file_write_raw(c, src, bytes, off);
-    if (io_len(c, bytes) > c->io_bounce_bytes) return fail(c, TC_E_CAPACITY, "tensor larger than the I/O bounce block");
-    memcpy(c->io_bounce, src, bytes);
-    memset(c->io_bounce + bytes, 0, io_len(c, bytes) - bytes);
-    return file_write_raw(c, c->io_bounce, io_len(c, bytes), off);
-}
-
-static int file_read(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t off)
-{
-    if (!c->file_direct) return file_read_raw(c, dst, bytes, bytes, off);
-    if (io_len(c, bytes) > c->io_bounce_bytes) return fail(c, TC_E_CAPACITY, "tensor larger than the I/O bounce block");
-    int rc = file_read_raw(c, c->io_bounce, io_len(c, bytes), bytes, off);
-    if (rc != TC_OK) return rc;
-    memcpy(dst, c->io_bounce, bytes);
-    return TC_OK;
-}
-
 // ---------------------------------------------------------------------------
 // dispatch: op records -> migration-kernel launches, DMA copies and file I/O
 //
@@ -627,9 +591,28 @@ static int file_read(tc_ctx *c, uint8_t *dst, uint64_t bytes, uint64_t off)
 // comes from per-buffer tickets: each buffer remembers the last operation that
 // touched it, and an operation waits for the tickets of the buffers it touches.
 // ---------------------------------------------------------------------------
-// ---- write-behind ------------------------------------------------------------
-// one write, by a writer thread (w) or by the calling thread (w == nullptr)
-static void io_run_job(tc_ctx *c, IoWriter *w, const IoJob &j)
+// ---- file I/O behind the hook thread -------------------------------------------
+static bool pread_all(int fd, uint8_t *dst, uint64_t bytes, uint64_t want, uint64_t off, std::string &err)
+{
+    // `bytes` are requested (rounded for O_DIRECT); at least `want` must arrive: a file
+    // whose last extent ends at the tensor's last byte is not a short read
+    uint64_t got = 0;
+    while (got < bytes) {
+        ssize_t r = pread(fd, dst + got, bytes - got, (off_t)(off + got));
+        if (r < 0 && errno == EINTR) continue;
+        if (r < 0) { err = std::string("pread: ") + strerror(errno); return false; }
+        if (r == 0) break;
+        got += (uint64_t)r;
+    }
+    if (got < want) { err = "pread: short file"; return false; }
+    return true;
+}
+
+// one job, by a worker thread (w) or by the calling thread (w == nullptr).
+// O_DIRECT cannot target memory the GPU driver has mapped (pread into a pinned
+// region fails with EFAULT on this kernel), so in that mode every request goes
+// through a bounce block, ordinary page-aligned memory of the library's own.
+static void io_run_job(tc_ctx *c, IoWorker *w, const IoJob &j)
 {
     std::string err;
     if (j.ev) {
@@ -638,18 +621,23 @@ static void io_run_job(tc_ctx *c, IoWriter *w, const IoJob &j)
     }
     if (err.empty()) {
         const auto t0 = std::chrono::steady_clock::now();
-        const uint8_t *src = j.src;
-        uint64_t len = j.bytes;
-        if (c->file_direct) {
-            uint8_t *blk = w ? w->bounce : c->io_bounce;
-            len = io_len(c, j.bytes);
-            memcpy(blk, j.src, j.bytes);
+        uint8_t *blk = w ? w->bounce : c->io_bounce;
+        const uint64_t len = io_len(c, j.bytes);
+        if (j.read) {
+            if (c->file_direct) {
+                if (pread_all(j.fd, blk, len, j.bytes, j.off, err)) memcpy(j.mem, blk, j.bytes);
+            } else {
+                pread_all(j.fd, j.mem, j.bytes, j.bytes, j.off, err);
+            }
+        } else if (c->file_direct) {
+            memcpy(blk, j.mem, j.bytes);
             memset(blk + j.bytes, 0, len - j.bytes);
-            src = blk;
+            pwrite_all(j.fd, blk, len, j.off, err);
+        } else {
+            pwrite_all(j.fd, j.mem, j.bytes, j.off, err);
         }
-        pwrite_all(c->fd, src, len, j.off, err);
-        c->wr_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
-                        std::chrono::steady_clock::now() - t0).count();
+        (j.read ? c->rd_ns : c->wr_ns) += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                                              std::chrono::steady_clock::now() - t0).count();
     }
     if (!err.empty()) {
         std::lock_guard<std::mutex> g(c->io_mu);
@@ -657,7 +645,7 @@ static void io_run_job(tc_ctx *c, IoWriter *w, const IoJob &j)
     }
 }
 
-static void io_writer_main(tc_ctx *c, IoWriter *w)
+static void io_worker_main(tc_ctx *c, IoWorker *w)
 {
     (void)hipSetDevice(c->device);
     for (;;) {
@@ -665,20 +653,20 @@ static void io_writer_main(tc_ctx *c, IoWriter *w)
         {
             std::unique_lock<std::mutex> lk(w->mu);
             w->cv_job.wait(lk, [&] { return w->quit || !w->q.empty(); });
-            if (w->q.empty()) return;                  // quit, and nothing left to write
+            if (w->q.empty()) return;                  // quit, and nothing left to do
             j = w->q.front();
             w->q.pop_front();
         }
         io_run_job(c, w, j);
         {
             std::lock_guard<std::mutex> g(w->mu);
-            w->done = j.seq;
+            w->done.store(j.seq);
         }
         w->cv_done.notify_all();
     }
 }
 
-// a writer's failure surfaces at the next call that waits for or queues a write
+// a worker's failure surfaces at the next call that waits for or queues a job
 static int io_check(tc_ctx *c)
 {
     if (!c->io_failed.load()) return TC_OK;
@@ -686,126 +674,155 @@ static int io_check(tc_ctx *c)
     return fail(c, TC_E_IO, c->io_err);
 }
 
-static bool io_done(tc_ctx *c, const JobRef &r)
+static bool io_done(tc_ctx *c, const JobSet &r)
 {
-    if (!r.seq || r.w >= c->writers.size()) return true;
-    IoWriter &w = *c->writers[r.w];
-    std::lock_guard<std::mutex> g(w.mu);
-    return w.done >= r.seq;
+    if (!r.any) return true;
+    const auto &pool = c->io[r.pool];
+    for (size_t w = 0; w < pool.size(); ++w)
+        if (r.seq[w] && pool[w]->done.load() < r.seq[w]) return false;
+    return true;
 }
 
-static int io_wait(tc_ctx *c, JobRef &r)
+static int io_wait(tc_ctx *c, JobSet &r)
 {
-    if (r.seq && r.w < c->writers.size()) {
-        IoWriter &w = *c->writers[r.w];
-        std::unique_lock<std::mutex> lk(w.mu);
-        w.cv_done.wait(lk, [&] { return w.done >= r.seq; });
+    if (r.any) {
+        const auto &pool = c->io[r.pool];
+        for (size_t wi = 0; wi < pool.size(); ++wi) {
+            if (!r.seq[wi] || pool[wi]->done.load() >= r.seq[wi]) continue;
+            IoWorker &w = *pool[wi];
+            std::unique_lock<std::mutex> lk(w.mu);
+            w.cv_done.wait(lk, [&] { return w.done.load() >= r.seq[wi]; });
+        }
+        r = JobSet{};
     }
-    r.seq = 0;
     return io_check(c);
 }
 
 static int io_wait_all(tc_ctx *c)
 {
-    for (auto &pw : c->writers) {
-        IoWriter &w = *pw;
-        {
-            std::unique_lock<std::mutex> lk(w.mu);
-            w.cv_done.wait(lk, [&] { return w.done >= w.issued; });
+    for (int pool = 0; pool < 2; ++pool)
+        for (auto &pw : c->io[pool]) {
+            IoWorker &w = *pw;
+            {
+                std::unique_lock<std::mutex> lk(w.mu);
+                w.cv_done.wait(lk, [&] { return w.done.load() >= w.issued; });
+            }
         }
-        for (auto &e : w.ev_busy) c->ev_free.push_back(e.second);
-        w.ev_busy.clear();
-    }
+    for (auto &e : c->ev_busy) c->ev_free.push_back(e.first);
+    c->ev_busy.clear();
     return io_check(c);
 }
 
 static void io_stop(tc_ctx *c)
 {
     (void)io_wait_all(c);
-    for (auto &pw : c->writers) {
-        {
-            std::lock_guard<std::mutex> g(pw->mu);
-            pw->quit = true;
+    for (int pool = 0; pool < 2; ++pool) {
+        for (auto &pw : c->io[pool]) {
+            {
+                std::lock_guard<std::mutex> g(pw->mu);
+                pw->quit = true;
+            }
+            pw->cv_job.notify_all();
+            if (pw->th.joinable()) pw->th.join();
+            if (pw->bounce) free(pw->bounce);
         }
-        pw->cv_job.notify_all();
-        if (pw->th.joinable()) pw->th.join();
-        if (pw->bounce) free(pw->bounce);
+        c->io[pool].clear();
     }
-    c->writers.clear();
-    for (JobRef &r : c->tensor_job) r = JobRef{};
-    for (JobRef &r : c->cpu_job) r = JobRef{};
-    for (StBlock &b : c->st_q) b.job = JobRef{};
+    for (JobSet &r : c->tensor_job) r = JobSet{};
+    for (JobSet &r : c->cpu_job) r = JobSet{};
+    for (StBlock &b : c->st_q) b.job = JobSet{};
+    for (PUnit &p : c->deferred) p.read_job = JobSet{};
 }
 
-static int io_start(tc_ctx *c, uint32_t n)
+static int io_start(tc_ctx *c)
 {
-    for (uint32_t i = 0; i < n; ++i) {
-        std::unique_ptr<IoWriter> w(new (std::nothrow) IoWriter());
-        if (!w) return fail(c, TC_E_CAPACITY, "no memory for a writer");
-        if (c->file_direct) {
-            void *blk = nullptr;
-            if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) return fail(c, TC_E_CAPACITY, "no memory for a writer's bounce block");
-            w->bounce = (uint8_t *)blk;
+    for (int pool = 0; pool < 2; ++pool)
+        for (uint32_t i = 0; i < c->n_io[pool]; ++i) {
+            std::unique_ptr<IoWorker> w(new (std::nothrow) IoWorker());
+            if (!w) return fail(c, TC_E_CAPACITY, "no memory for an I/O worker");
+            if (c->file_direct) {
+                void *blk = nullptr;
+                if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0)
+                    return fail(c, TC_E_CAPACITY, "no memory for an I/O worker's bounce block");
+                w->bounce = (uint8_t *)blk;
+            }
+            try {
+                w->th = std::thread(io_worker_main, c, w.get());
+            } catch (...) {
+                if (w->bounce) free(w->bounce);
+                return fail(c, TC_E_CAPACITY, "could not start an I/O worker thread");
+            }
+            c->io[pool].push_back(std::move(w));
         }
-        try {
-            w->th = std::thread(io_writer_main, c, w.get());
-        } catch (...) {
-            if (w->bounce) free(w->bounce);
-            return fail(c, TC_E_CAPACITY, "could not start a writer thread");
-        }
-        c->writers.push_back(std::move(w));
-    }
     return TC_OK;
 }
 
-// Queue the write of tensor t's extent from `src`.  op != 0: the bytes are
-// being produced by copy operation `op`, issued on stream S a moment ago.
-static int io_enqueue(tc_ctx *c, uint32_t t, uint64_t op, int S, const uint8_t *src, JobRef *ref)
+// Queue (or, without worker threads of that kind, perform) the transfer of
+// tensor t's extent: a write from `mem` or a read into it.  op != 0: the bytes
+// to write are being produced by copy operation `op`, issued on stream S a
+// moment ago.  `set` names the queued jobs.
+static int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set)
 {
-    *ref = JobRef{};
-    if (c->fd < 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
+    *set = JobSet{};
+    set->pool = read ? IO_READERS : IO_WRITERS;
+    if (c->n_files == 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
     int rc = io_check(c);
+    if (rc == TC_OK && read) rc = io_wait(c, c->tensor_job[t]);    // a queued write of this very extent goes first
     if (rc != TC_OK) return rc;
-    IoJob j{0, nullptr, src, c->prof.bytes[t], c->place.file_off[t]};
-    if (c->file_direct && io_len(c, j.bytes) > c->io_bounce_bytes)
-        return fail(c, TC_E_CAPACITY, "tensor larger than the I/O bounce block");
-    if (c->writers.empty()) {
-        if ((rc = wait_op(c, op)) != TC_OK) return rc;
-        io_run_job(c, nullptr, j);
-        return io_check(c);
-    }
-    const uint32_t wi = t % (uint32_t)c->writers.size();
-    IoWriter &w = *c->writers[wi];
-    if (op) {
+    c->io_begun = true;
+    auto &pool = c->io[set->pool];
+    if (pool.empty() && (rc = wait_op(c, op)) != TC_OK) return rc;
+    const uint64_t n = c->prof.bytes[t], base = c->place.file_off[t];
+    hipEvent_t ev = nullptr;
+    if (op && !pool.empty()) {
+        // one event for the whole request, recorded right behind the copy
+        while (!c->ev_busy.empty() && io_done(c, c->ev_busy.front().second)) {
+            c->ev_free.push_back(c->ev_busy.front().first);
+            c->ev_busy.pop_front();
+        }
         if (c->ev_free.empty()) {
-            HIP_TRY(c, hipEventCreateWithFlags(&j.ev, hipEventDisableTiming | hipEventBlockingSync));
+            HIP_TRY(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming | hipEventBlockingSync));
         } else {
-            j.ev = c->ev_free.back();
+            ev = c->ev_free.back();
             c->ev_free.pop_back();
         }
-        hipError_t e = hipEventRecord(j.ev, c->streams[S]);
+        hipError_t e = hipEventRecord(ev, c->streams[S]);
         if (e != hipSuccess) {
-            c->ev_free.push_back(j.ev);
+            c->ev_free.push_back(ev);
             return fail(c, TC_E_HIP, std::string("hipEventRecord (file write): ") + hipGetErrorString(e));
         }
     }
-    j.seq = ++w.issued;
-    uint64_t done;
-    {
-        std::lock_guard<std::mutex> g(w.mu);
-        done = w.done;
-        w.q.push_back(j);
+    uint64_t lane = t;
+    for (uint64_t o = 0; o < n; o += c->io_chunk, ++lane) {
+        IoJob j{0, ev, mem + o, std::min(c->io_chunk, n - o), base + o, c->fds[lane % c->n_files], read};
+        if (pool.empty()) {
+            io_run_job(c, nullptr, j);
+            continue;
+        }
+        const size_t wi = lane % pool.size();
+        IoWorker &w = *pool[wi];
+        j.seq = ++w.issued;
+        {
+            std::lock_guard<std::mutex> g(w.mu);
+            w.q.push_back(j);
+        }
+        w.cv_job.notify_one();
+        set->any = true;
+        set->seq[wi] = j.seq;
     }
-    w.cv_job.notify_one();
-    if (j.ev) w.ev_busy.push_back({j.seq, j.ev});
-    while (!w.ev_busy.empty() && w.ev_busy.front().first <= done) {
-        c->ev_free.push_back(w.ev_busy.front().second);
-        w.ev_busy.pop_front();
-    }
-    ref->w = wi;
-    ref->seq = j.seq;
-    c->tensor_job[t] = *ref;
+    if (ev) c->ev_busy.push_back({ev, *set});
+    if (pool.empty()) return io_check(c);
+    if (!read) c->tensor_job[t] = *set;
     return TC_OK;
+}
+
+// the same, finished before it returns (loads, read-backs, restores)
+static int io_transfer(tc_ctx *c, uint32_t t, uint8_t *mem, bool read)
+{
+    JobSet set;
+    int rc = io_submit(c, t, mem, read, 0, 0, &set);
+    if (rc != TC_OK) return rc;
+    return io_wait(c, set);
 }
 
 // a block of the HBM bounce ring, or nullptr if none can be had without
@@ -850,12 +867,13 @@ static StBlock *st_find(tc_ctx *c, uint64_t id)
 static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute)
 {
     if (units.empty()) return TC_OK;
-    // a host buffer some unit is about to overwrite may still be the source of a queued spill
-    for (const PUnit &p : units)
-        if (p.cpu_out >= 0) {
-            int rc = io_wait(c, c->cpu_job[(size_t)p.cpu_out]);
-            if (rc != TC_OK) return rc;
-        }
+    // a host buffer some unit is about to overwrite may still be the source of a queued
+    // spill, and bytes coming from the file tier may still be on their way into staging
+    for (PUnit &p : units) {
+        int rc = p.cpu_out >= 0 ? io_wait(c, c->cpu_job[(size_t)p.cpu_out]) : TC_OK;
+        if (rc == TC_OK) rc = io_wait(c, p.read_job);
+        if (rc != TC_OK) return rc;
+    }
     struct Large { size_t unit; uint8_t *bounce; uint64_t kop; };
     std::vector<Large> large;
     std::vector<size_t> small;
@@ -918,7 +936,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
                 if (StBlock *b = p.st_id ? st_find(c, p.st_id) : nullptr) {
                     b->issued = true;
                     b->ops[0] = id;
-                    if (p.out_staging && (rc = io_enqueue(c, p.out_tensor, id, S_K, p.u.out_dst, &b->job)) != TC_OK) return rc;
+                    if (p.out_staging && (rc = io_submit(c, p.out_tensor, p.u.out_dst, false, id, S_K, &b->job)) != TC_OK) return rc;
                 }
             } else {
                 Large &L = large[(size_t)kunits[k].second];
@@ -965,7 +983,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         c->stats.dma_copies++;
         if (p.out_staging && blk) {
             blk->ops[1] = idd;
-            if ((rc = io_enqueue(c, p.out_tensor, idd, S_D, p.u.out_dst, &blk->job)) != TC_OK) return rc;
+            if ((rc = io_submit(c, p.out_tensor, p.u.out_dst, false, idd, S_D, &blk->job)) != TC_OK) return rc;
         }
     }
     for (const PUnit &p : units) {
@@ -1047,7 +1065,6 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
     // are merged until merge_bytes are prepared, a prepared buffer is needed
     // (by a module, by a later unit or by the host), or the file tier is involved.
     std::vector<PUnit> &units = c->deferred;
-    bool must_issue = false;
     c->last_compute = compute;
     PUnit pend{};                   // outgoing half waiting for its incoming partner
     bool have_out = false;
@@ -1096,8 +1113,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             if (rc != TC_OK) return rc;
             rc = wait_op(c, c->cpu_ticket[flat]);
             if (rc != TC_OK) return rc;
-            must_issue = true;
-            rc = io_enqueue(c, t, 0, 0, cpu_addr(c, s, r.src_slot), &c->cpu_job[flat]);
+            rc = io_submit(c, t, cpu_addr(c, s, r.src_slot), false, 0, 0, &c->cpu_job[flat]);
             if (rc != TC_OK) return rc;
             break;
         }
@@ -1146,8 +1162,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
                 if (have_out && p.out_staging) st = reserved_in;
                 else rc = staging_alloc(c, units, n, compute, &st, &p.st_id);
                 if (rc != TC_OK) return rc;
-                if ((rc = io_wait(c, c->tensor_job[t])) != TC_OK) return rc;   // a queued write of this very extent
-                rc = file_read(c, st, n, c->place.file_off[t]);
+                rc = io_submit(c, t, st, true, 0, 0, &p.read_job);
                 if (rc != TC_OK) return rc;
                 p.u.in_src = st;
                 p.in_staging = true;
@@ -1161,7 +1176,6 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             c->gpu_pending[(size_t)p.gpu_y] = 1;
             if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 1;
             if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 1;
-            if (p.out_staging || p.in_staging) must_issue = true;
             c->deferred_bytes += n * ((p.u.out_src ? 1 : 0) + 1);
             units.push_back(p);
             have_out = false;
@@ -1180,7 +1194,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             rc = wait_op(c, c->cpu_ticket[flat]);
             if (rc != TC_OK) return rc;
             if ((rc = io_wait(c, c->cpu_job[flat])) != TC_OK) return rc;
-            rc = file_read(c, cpu_addr(c, s, r.dst_slot), n, c->place.file_off[t]);
+            rc = io_transfer(c, t, cpu_addr(c, s, r.dst_slot), true);
             if (rc != TC_OK) return rc;
             break;
         }
@@ -1189,9 +1203,22 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
     }
     if (c->null_mover) return TC_OK;
     if (have_out) return fail(c, TC_E_HIP, "decision records end with an eviction that has no incoming tensor");
-    if (!must_issue && phase < TC_END && c->deferred_bytes < c->merge_bytes &&
-        units.size() < 4 * TC_MOVER_MAX_UNITS && !poll_op(c, c->last_k_op))
-        return TC_OK;                                  // the link is busy: keep them for a larger launch
+    if (phase < TC_END) {
+        // Units whose bytes are still being read from the file, or whose host buffer a
+        // queued spill still reads, stay prepared: a later hook call issues them, at the
+        // latest the one that needs a buffer they touch.
+        bool staged = false;
+        for (const PUnit &p : units) {
+            if (!io_done(c, p.read_job) || (p.cpu_out >= 0 && !io_done(c, c->cpu_job[(size_t)p.cpu_out])))
+                return TC_OK;
+            staged = staged || p.st_id != 0;
+        }
+        // the link is busy: keep them for a larger launch (file-tier units go at once,
+        // their staging blocks and their writes should not wait)
+        if (!staged && c->deferred_bytes < c->merge_bytes && units.size() < 4 * TC_MOVER_MAX_UNITS &&
+            !poll_op(c, c->last_k_op))
+            return TC_OK;
+    }
     return issue_units(c, units, compute);
 }
 
@@ -1431,7 +1458,7 @@ extern "C" int tc_synchronize(tc_ctx *c)
             if (i == S_K || c->streams[i]) HIP_TRY(c, hipStreamSynchronize(c->streams[i]));
             c->op_done[i] = c->op_id;
         }
-        rc = io_wait_all(c);                           // queued file writes
+        rc = io_wait_all(c);                           // queued file I/O
         if (rc != TC_OK) return rc;
         c->st_q.clear();
     }
@@ -1443,6 +1470,7 @@ extern "C" int tc_cache_stats(const tc_ctx *c, tc_stats *out)
     if (!c || !out) return TC_E_ARG;
     *out = c->stats;
     out->file_write_ns += c->wr_ns.load();
+    out->file_read_ns += c->rd_ns.load();
     return TC_OK;
 }
 
@@ -1503,7 +1531,7 @@ extern "C" int tc_load_tensor(tc_ctx *c, uint32_t t, const void *src)
     const uint64_t n = c->prof.bytes[t];
     if (tier == TC_GPU) HIP_TRY(c, hipMemcpy(gpu_addr(c, s, gs), src, n, hipMemcpyHostToDevice));
     else if (tier == TC_CPU) memcpy(cpu_addr(c, s, cs), src, n);
-    else return file_write(c, (const uint8_t *)src, n, c->place.file_off[t]);
+    else return io_transfer(c, t, const_cast<uint8_t *>((const uint8_t *)src), false);
     return TC_OK;
 }
 
@@ -1522,7 +1550,7 @@ extern "C" int tc_read_tensor(tc_ctx *c, uint32_t t, void *dst)
     const uint64_t n = c->prof.bytes[t];
     if (tier == TC_GPU) HIP_TRY(c, hipMemcpy(dst, gpu_addr(c, s, gs), n, hipMemcpyDeviceToHost));
     else if (tier == TC_CPU) memcpy(dst, cpu_addr(c, s, cs), n);
-    else return file_read(c, (uint8_t *)dst, n, c->place.file_off[t]);
+    else return io_transfer(c, t, (uint8_t *)dst, true);
     return TC_OK;
 }
 
@@ -1546,7 +1574,7 @@ extern "C" int tc_fill_payload(tc_ctx *c, uint32_t seed)
             if (io_len(c, n) > c->staging_bytes) return fail(c, TC_E_CAPACITY, "staging region smaller than a file-tier tensor");
             HIP_TRY(c, tc_launch_fill(c->staging, n, t, seed, c->streams[S_K]));
             HIP_TRY(c, hipStreamSynchronize(c->streams[S_K]));
-            rc = file_write(c, c->staging, n, c->place.file_off[t]);
+            rc = io_transfer(c, t, c->staging, false);
             if (rc != TC_OK) return rc;
         }
     }
@@ -1605,16 +1633,48 @@ extern "C" int tc_mover_timing(tc_ctx *c, int enable, tc_timing *out)
     return TC_OK;
 }
 
-extern "C" int tc_set_io_writers(tc_ctx *c, uint32_t writers)
+extern "C" int tc_set_io_threads(tc_ctx *c, uint32_t writers, uint32_t readers)
 {
     if (!c) return TC_E_ARG;
-    if (writers > 16) return fail(c, TC_E_ARG, "at most 16 writer threads");
-    c->n_writers = writers;
-    if (c->stage != 4 || c->fd < 0 || c->null_mover) return TC_OK;
+    if (writers > IO_MAX_THREADS || readers > IO_MAX_THREADS) return fail(c, TC_E_ARG, "at most 8 writer and 8 reader threads");
+    c->n_io[IO_WRITERS] = writers;
+    c->n_io[IO_READERS] = readers;
+    if (c->stage != 4 || c->n_files == 0 || c->null_mover) return TC_OK;
     int rc = tc_synchronize(c);
     if (rc != TC_OK) return rc;
     io_stop(c);
-    return io_start(c, writers);
+    return io_start(c);
+}
+
+extern "C" int tc_set_io_chunk(tc_ctx *c, uint64_t bytes)
+{
+    if (!c) return TC_E_ARG;
+    if (bytes < 65536 || bytes % 4096) return fail(c, TC_E_ARG, "chunk must be a multiple of 4096, at least 64 KiB");
+    if (c->stage == 4 && c->io_begun) return fail(c, TC_E_STATE, "the file tier is already in use");
+    c->io_chunk = bytes;
+    if (c->stage != 4 || c->n_files == 0 || c->null_mover || !c->file_direct) return TC_OK;
+    // O_DIRECT bounce blocks are one chunk each: make them anew
+    io_stop(c);
+    uint64_t largest = 0;
+    for (uint32_t t = 0; t < c->prof.n_tensors; ++t) largest = std::max(largest, c->prof.bytes[t]);
+    c->io_bounce_bytes = std::min<uint64_t>(c->io_chunk, (largest + 4095) & ~4095ull);
+    free(c->io_bounce);
+    void *blk = nullptr;
+    if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) { c->io_bounce = nullptr; return fail(c, TC_E_CAPACITY, "no memory for the I/O bounce block"); }
+    c->io_bounce = (uint8_t *)blk;
+    return io_start(c);
+}
+
+extern "C" int tc_add_stripe(tc_ctx *c, int fd)
+{
+    if (!c) return TC_E_ARG;
+    if (c->stage != 4 || c->null_mover) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
+    if (fd < 0) return fail(c, TC_E_ARG, "not a file descriptor");
+    if (c->n_files == 0) return fail(c, TC_E_STATE, "tc_bind_memory was given no file to add stripes to");
+    if (c->io_begun) return fail(c, TC_E_STATE, "the file tier is already in use");
+    if (c->n_files >= IO_MAX_FILES) return fail(c, TC_E_CAPACITY, "at most 8 files");
+    c->fds[c->n_files++] = fd;
+    return TC_OK;
 }
 
 extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)

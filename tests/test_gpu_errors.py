@@ -110,10 +110,10 @@ def test_failed_background_write_is_reported(tmp_path):
     # call that queues or waits for a write (at the latest tc_synchronize) returns TC_E_IO
     wl = W.random_workload(3, n_tensors=60, n_steps=40, max_per_step=2, sizes=(4096, 33000), hbm_frac=0.1,
                            host_frac=0.3, n_iterations=1)
-    for writers in (2, 0):
+    for writers in ((2, 1), (0, 0)):
         tc = _planned(wl)
         tc.bind_torch(file_fd=os.open("/dev/full", os.O_RDWR), staging_bytes=1 << 20)
-        tc.set_io_writers(writers)
+        tc.set_io_threads(*writers)
         cs = torch.cuda.Stream()
         with pytest.raises(T.TcError) as e:
             tc.replay_iteration_c(wl.iterations[0], cs.cuda_stream)

@@ -351,12 +351,12 @@ def test_op_log_can_be_cleared_and_switched_off():
     tc.close()
 
 
-@pytest.mark.parametrize("writers", [0, 1, 2, 5])
+@pytest.mark.parametrize("writers", [(0, 0), (1, 0), (0, 1), (1, 1), (2, 3), (5, 2)])
 @pytest.mark.parametrize("staging", ["tight", "deep"])
 def test_write_behind_keeps_every_byte(writers, staging, tmp_path):
-    # file writes run behind the hook thread: whatever the number of writer threads and
-    # however shallow the staging ring (twice the largest tensor = one block at a time),
-    # the schedule and every byte are those of the oracle
+    # file reads and writes run behind the hook thread: whatever the number of writer and
+    # reader threads and however shallow the staging ring (twice the largest tensor = one
+    # block at a time), the schedule and every byte are those of the oracle
     for seed in (4, 7):
         wl = _random(seed)
         big = int(wl.tensor_bytes.max())
@@ -369,11 +369,48 @@ def test_write_behind_keeps_every_byte(writers, staging, tmp_path):
         tc.close()
 
 
+@pytest.mark.parametrize("stripes,threads,direct,chunk", [(1, (2, 4), False, None), (3, (3, 2), False, 1 << 16),
+                                                          (4, (1, 5), True, None), (2, (0, 0), True, 1 << 20),
+                                                          (8, (8, 8), False, 12 << 20), (2, (4, 4), True, 1 << 30)])
+def test_multi_chunk_extents_over_stripes(stripes, threads, direct, chunk, tmp_path):
+    # tensors of several 8 MiB chunks (odd tails), so that one request spreads over the
+    # workers and, with stripes, over the files; the bytes must come back whole from
+    # whatever file, in whatever order the workers finished
+    if direct and not _direct_ok(tmp_path):
+        pytest.skip("the temporary directory's file system does not take O_DIRECT")
+    wl = W.random_workload(21, n_tensors=36, n_steps=50, max_per_step=2,
+                           sizes=((8 << 20) + 100, (20 << 20) + 4096 + 48, 1 << 19, 33000), hbm_frac=0.1,
+                           host_frac=0.25, n_iterations=2)
+    big = (int(wl.tensor_bytes.max()) + 4095) // 4096 * 4096
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=6 * big, window=16, io_writers=threads,
+                     stripes=stripes, direct=direct, io_chunk=chunk)
+    r = check_against_oracle(wl, tc)
+    assert r.bytes_file_write > (64 << 20) and r.bytes_file_read > (64 << 20)
+    tc.close()
+
+
+def test_stripes_are_fixed_once_the_file_tier_is_in_use(tmp_path):
+    wl = _random(4)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch(file_path=_tmpfile(tmp_path), staging_bytes=1 << 20, stripes=2)
+    for t in range(wl.n_tensors):
+        tc.load_tensor(t, W.workload_payload(wl, t))
+    fd = os.open(_tmpfile(tmp_path, "late.bin"), os.O_RDWR | os.O_CREAT, 0o600)
+    with pytest.raises(T.TcError) as e:
+        tc.add_stripe(fd)
+    assert e.value.code == -2                       # TC_E_STATE
+    with pytest.raises(T.TcError) as e:
+        tc.set_io_chunk(1 << 20)
+    assert e.value.code == -2
+    os.close(fd)
+    tc.close()
+
+
 def test_write_behind_with_dma_copies_and_o_direct(tmp_path):
     wl = _random(5)
     direct = _direct_ok(tmp_path)
     tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=4 << 20, dma_threshold=1 << 15, direct=direct,
-                     window=16, io_writers=3)
+                     window=16, io_writers=(3, 2))
     r = check_against_oracle(wl, tc)
     assert r.bytes_file_write > 0
     st = tc.cache_stats()
@@ -396,7 +433,8 @@ def test_random_settings_keep_the_schedule_and_every_byte(seed, tmp_path):
                      merge_bytes=int(rng.choice([0, 1 << 16, 1 << 22, 1 << 30])),
                      dma_threshold=int(rng.choice([0, 0, 1 << 16, 1 << 18])) or None,
                      mover=(int(rng.choice([1, 8, 64, 300])), int(rng.choice([4096, 16384, 65536, 1 << 20]))),
-                     busy=bool(rng.integers(0, 2)), direct=direct, io_writers=int(rng.integers(0, 4)))
+                     busy=bool(rng.integers(0, 2)), direct=direct,
+                     io_writers=(int(rng.integers(0, 4)), int(rng.integers(0, 4))))
     r = check_against_oracle(wl, tc)
     assert len(r.log) > 100
     tc.close()
