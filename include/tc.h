@@ -315,8 +315,11 @@ int tc_set_oplog(tc_ctx *ctx, int enable, int clear);
  * any may be NULL).  Reads the device tables; synchronises the decision stream. */
 int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_slot);
 
-/* Migration-kernel tuning: workgroups per launch (0 = default) and bytes per
- * work chunk (0 = default; a multiple of 4096). */
+/* Migration-kernel tuning.  workgroups: how many workgroups of 256 lanes move
+ * data (0 = default 12, at most 8192); they all run on one XCD, the launch
+ * itself has eight times as many and those dealt to other XCDs exit at once.
+ * chunk_bytes: the piece of work a workgroup takes from the launch's ticket
+ * counter at a time (0 = default 16 KiB; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
 
 /* File-tier I/O runs behind the calling thread.  Writes (Sec. 3.4.2: dirty
@@ -394,9 +397,11 @@ typedef struct {
     uint64_t    bytes;
 } tc_segment;
 
-/* Batched copy: one launch moves every segment (device or pinned pointers,
- * any alignment, any size).  segs: host array, copied.  Asynchronous on
- * stream. */
+/* Batched copy: one launch per 48 segments moves them all (device or pinned
+ * pointers, 16-byte aligned, any size).  segs: host array, copied.
+ * Asynchronous on stream; the kernel's ticket counters come from and go back
+ * to the stream-ordered allocator (hipMallocAsync / hipFreeAsync).
+ * workgroups, chunk_bytes: as for tc_set_mover. */
 int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream,
                   uint32_t workgroups, uint32_t chunk_bytes);
 

@@ -126,6 +126,9 @@ struct TcMoverArgs {
     uint64_t n_chunks;
     uint32_t n_units;
     uint32_t chunk_bytes;
+    uint32_t *tickets;                          // device: two words, both zero before the stream's first launch
+    uint32_t slot;                              // 0 or 1: set by the launcher, alternates between launches
+    uint32_t xcc;                               // the XCD whose workgroups do the work
 };
 
 struct TcStampArgs {
@@ -140,7 +143,9 @@ struct TcStampArgs {
 hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, TcOpRec *ops, hipStream_t s);
 hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, TcDecideOut *out, TcOpRec *ops,
                                    hipStream_t s);
-hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_t s);
+// workgroups: how many should work (the launch has eight times as many, those on other XCDs exit)
+// launches: how many launches have used a.tickets so far (all on one stream, in order); counted up here
+hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, uint64_t *launches);
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s);
 hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t seed, hipStream_t s);
 uint64_t tc_pack_tile_count(uint64_t total);

@@ -461,30 +461,55 @@ hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, 
 // Migration kernel: one launch moves every exchange unit of a hook call.
 //
 // The link to host memory, not HBM and not the ALUs, bounds this kernel, so the
-// design goal is enough 128-bit requests in flight per wave to cover the host
-// link's latency, on both directions at once.  Work is cut into chunks of
-// chunk_bytes; workgroup b takes chunks b, b+grid, ... (static assignment: no
-// queue, no waiting, every wave exits after its last chunk).  Within a chunk
-// each lane moves 16 bytes per request; a wave's 64 lanes cover 1 KiB of
-// consecutive addresses, and four requests per direction are issued before
-// the first store.  For a unit with both directions each lane holds the
-// outgoing and the incoming 16 bytes of the same index before storing either,
-// which is what lets a tensor leave a GPU buffer while another arrives in it.
+// design goal is enough 128-bit requests in flight to cover the host link's
+// latency, on both directions at once, and not more.  Work is cut into chunks
+// of chunk_bytes; a workgroup takes the next chunk from a ticket counter, moves
+// it in blocks of 16 KiB (each lane 16 bytes per request, a wave's 64 lanes
+// cover 1 KiB of consecutive addresses, four requests per lane and direction
+// before the first store) and comes back for another.  For a unit with both
+// directions each lane holds the outgoing and the incoming 16 bytes of the same
+// index before storing either, which is what lets a tensor leave a GPU buffer
+// while another arrives in it.
+//
+// All working workgroups sit on ONE XCD.  With both directions loaded, requests
+// from different XCDs are served very unevenly (measured per 16 KiB block under
+// load: 10 us on two XCDs, 19 us on three, 40-120 us on the other three), every
+// launch ends waiting ~100 us for the workgroups on the starved XCDs, and a
+// 16 MiB exchange runs at 39 GB/s per direction instead of 48.  Workgroups are
+// dealt to the XCDs in turn, so the grid is eight times the number wanted and a
+// workgroup that finds itself on another XCD exits at once (workgroup 0 always
+// stays, so that every chunk is moved wherever the dispatcher puts things).  A
+// dozen workgroups (192 KiB in flight per direction) are the optimum: fewer
+// leave the link idle, more crowd each other out.
+//
+// The ticket counter is one of two words: a launch uses word `slot` and clears
+// the other for the launch that follows it on the same stream.
 // ===========================================================================
 
 #define MOVER_THREADS 256
 #define MOVER_UNROLL 4
+#define MOVER_XCDS 8
 
 __device__ __forceinline__ uint4 ld16(const uint8_t *p) { return *(const uint4 *)p; }
 __device__ __forceinline__ void st16(uint8_t *p, uint4 v) { *(uint4 *)p = v; }
 
 __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
 {
+    uint32_t xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    if ((xcc & 15u) != a.xcc && blockIdx.x != 0) return;
+    __shared__ uint32_t ticket;
     const uint32_t tid = threadIdx.x;
-    for (uint64_t c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
+    if (blockIdx.x == 0 && tid == 0) a.tickets[a.slot ^ 1u] = 0;
+    uint32_t ui = 0;                                       // tickets only grow: the unit search resumes where it stopped
+    for (;;) {
+        __syncthreads();                                   // everyone has read the ticket before
+        if (tid == 0) ticket = atomicAdd(&a.tickets[a.slot], 1u);
+        __syncthreads();
+        const uint64_t c = ticket;
+        if (c >= a.n_chunks) break;
         // unit of this chunk: the last one whose first chunk is <= c
-        uint32_t ui = 0;
-        for (uint32_t i = 1; i < a.n_units; ++i) ui = (a.u[i].chunk0 <= c) ? i : ui;
+        while (ui + 1 < a.n_units && a.u[ui + 1].chunk0 <= c) ++ui;
         const TcUnit &U = a.u[ui];
         const uint64_t off = (c - U.chunk0) * (uint64_t)a.chunk_bytes;
         const uint64_t left = U.bytes - off;
@@ -537,11 +562,12 @@ __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
     }
 }
 
-hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_t s)
+hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, uint64_t *launches)
 {
     if (a.n_units == 0 || a.n_chunks == 0) return hipSuccess;
     // the kernel trusts these counts: check them against the units before it runs
     if (a.n_units > TC_MOVER_MAX_UNITS || a.chunk_bytes == 0 || (a.chunk_bytes & 15)) return hipErrorInvalidValue;
+    if (!a.tickets || !launches || workgroups == 0 || workgroups > 8192) return hipErrorInvalidValue;
     uint64_t chunks = 0;
     for (uint32_t i = 0; i < a.n_units; ++i) {
         const TcUnit &u = a.u[i];
@@ -551,10 +577,14 @@ hipError_t tc_launch_mover(const TcMoverArgs &a, uint32_t workgroups, hipStream_
         if (!u.out_src && !u.in_src) return hipErrorInvalidValue;
         chunks += (u.bytes + a.chunk_bytes - 1) / a.chunk_bytes;
     }
-    if (chunks != a.n_chunks) return hipErrorInvalidValue;
-    uint64_t g = a.n_chunks < workgroups ? a.n_chunks : workgroups;
+    if (chunks != a.n_chunks || chunks >= 0xFFFF0000ull) return hipErrorInvalidValue;   // tickets are 32-bit
+    // the counters alternate between the launches that really happen: each clears the other's
+    a.slot = (uint32_t)(*launches & 1);
+    const uint64_t g = (a.n_chunks < workgroups ? a.n_chunks : workgroups) * MOVER_XCDS;
     hipLaunchKernelGGL(tc_mover_kernel, dim3((uint32_t)g), dim3(MOVER_THREADS), 0, s, a);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) ++*launches;
+    return e;
 }
 
 // ===========================================================================

@@ -133,7 +133,9 @@ struct tc_ctx {
     uint32_t replay_window = 64;        // steps decided per launch by tc_replay_iteration
 
     // dispatch state
-    uint32_t mover_wgs = 64, chunk_bytes = 65536;
+    uint32_t mover_wgs = 12, chunk_bytes = 16384;
+    uint32_t *tickets = nullptr;            // device: the migration kernel's two ticket counters
+    uint64_t k_launches = 0;                // migration-kernel launches so far (their parity picks the counter)
     uint64_t sdma_threshold = 0;            // tensors at least this large go through the DMA engines (0: none)
     uint64_t op_id = 0;                 // copy operations issued (kernel launches and DMA copies)
     uint64_t op_done[N_STREAMS]{};      // per stream: operations known complete
@@ -241,6 +243,7 @@ static void release_device(tc_ctx *c)
     if (c->d_ids) { (void)hipFree(c->d_ids); c->d_ids = nullptr; }
     if (c->d_rw) { (void)hipFree(c->d_rw); c->d_rw = nullptr; }
     if (c->bounce) { (void)hipFree(c->bounce); c->bounce = nullptr; }
+    if (c->tickets) { (void)hipFree(c->tickets); c->tickets = nullptr; }
     if (c->dout) { (void)hipHostFree(c->dout); c->dout = nullptr; }
     if (c->io_bounce) { free(c->io_bounce); c->io_bounce = nullptr; }
 }
@@ -412,6 +415,10 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     e = hipStreamCreateWithFlags(&c->dstream, hipStreamNonBlocking);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    e = hipMalloc((void **)&c->tickets, 256);
+    if (e == hipSuccess) e = hipMemset(c->tickets, 0, 256);
+    if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    c->k_launches = 0;
     for (uint32_t i = 0; i < OP_RING; ++i) {
         e = hipEventCreateWithFlags(&c->op_ev[i], hipEventDisableTiming);
         if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
@@ -903,6 +910,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         const size_t end = std::min(kunits.size(), at + (size_t)TC_MOVER_MAX_UNITS);
         TcMoverArgs args{};
         args.chunk_bytes = c->chunk_bytes;
+        args.tickets = c->tickets;                          // (every launch of this context is on stream K, in order)
         uint64_t id, bytes = 0;
         int rc = begin_op(c, S_K, compute, &id);
         if (rc != TC_OK) return rc;
@@ -921,7 +929,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         }
         hipEvent_t t0;
         if ((rc = timed_begin(c, S_K, &t0)) != TC_OK) return rc;
-        HIP_TRY(c, tc_launch_mover(args, c->mover_wgs, c->streams[S_K]));
+        HIP_TRY(c, tc_launch_mover(args, c->mover_wgs, c->streams[S_K], &c->k_launches));
         if ((rc = timed_end(c, S_K, t0, bytes)) != TC_OK) return rc;
         if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
         c->last_k_op = id;
@@ -1586,9 +1594,9 @@ extern "C" int tc_set_mover(tc_ctx *c, uint32_t workgroups, uint32_t chunk_bytes
 {
     if (!c) return TC_E_ARG;
     if (chunk_bytes && (chunk_bytes % 4096)) return fail(c, TC_E_ARG, "chunk_bytes must be a multiple of 4096");
-    if (workgroups > 65536) return fail(c, TC_E_ARG, "too many workgroups");
-    c->mover_wgs = workgroups ? workgroups : 64;
-    c->chunk_bytes = chunk_bytes ? chunk_bytes : 65536;
+    if (workgroups > 8192) return fail(c, TC_E_ARG, "too many workgroups");
+    c->mover_wgs = workgroups ? workgroups : 12;
+    c->chunk_bytes = chunk_bytes ? chunk_bytes : 16384;
     return TC_OK;
 }
 
@@ -1717,17 +1725,39 @@ extern "C" int tc_set_dma_threshold(tc_ctx *c, uint64_t bytes)
 // ---------------------------------------------------------------------------
 // stand-alone kernels
 // ---------------------------------------------------------------------------
+// Ticket counters for the stand-alone movers: two words from the stream-ordered
+// allocator, cleared on the stream, freed on the stream behind the launches.
+namespace {
+struct StreamTickets {
+    uint32_t *p = nullptr;
+    hipStream_t s;
+    uint64_t launches = 0;
+    explicit StreamTickets(hipStream_t stream) : s(stream)
+    {
+        if (hipMallocAsync((void **)&p, 256, s) != hipSuccess) { p = nullptr; return; }
+        if (hipMemsetAsync(p, 0, 256, s) != hipSuccess) { (void)hipFreeAsync(p, s); p = nullptr; }
+    }
+    ~StreamTickets() { if (p) (void)hipFreeAsync(p, s); }
+};
+} // namespace
+
 extern "C" int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream, uint32_t workgroups,
                              uint32_t chunk_bytes)
 {
     if (!segs && n) return TC_E_ARG;
-    if (!workgroups) workgroups = 64;
-    if (!chunk_bytes) chunk_bytes = 65536;
-    if (chunk_bytes % 4096) return TC_E_ARG;
+    if (!workgroups) workgroups = 12;
+    if (!chunk_bytes) chunk_bytes = 16384;
+    if (chunk_bytes % 4096 || workgroups > 8192) return TC_E_ARG;
+    for (uint32_t k = 0; k < n; ++k)
+        if (segs[k].bytes && (!segs[k].src || !segs[k].dst || ((((uintptr_t)segs[k].src) | ((uintptr_t)segs[k].dst)) & 15)))
+            return TC_E_ARG;
+    StreamTickets tk((hipStream_t)stream);
+    if (!tk.p) return TC_E_HIP;
     uint32_t i = 0;
     while (i < n) {
         TcMoverArgs a{};
         a.chunk_bytes = chunk_bytes;
+        a.tickets = tk.p;
         for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
             if (!segs[i].bytes) continue;
             if (!segs[i].src || !segs[i].dst) return TC_E_ARG;
@@ -1739,7 +1769,7 @@ extern "C" int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream, u
             u.chunk0 = a.n_chunks;
             a.n_chunks += (segs[i].bytes + chunk_bytes - 1) / chunk_bytes;
         }
-        if (tc_launch_mover(a, workgroups, (hipStream_t)stream) != hipSuccess) return TC_E_HIP;
+        if (tc_launch_mover(a, workgroups, (hipStream_t)stream, &tk.launches) != hipSuccess) return TC_E_HIP;
     }
     return TC_OK;
 }
@@ -1748,13 +1778,21 @@ extern "C" int tc_exchange_batch(const tc_segment *out, const tc_segment *in, ui
                                  uint32_t workgroups, uint32_t chunk_bytes)
 {
     if ((!out || !in) && n) return TC_E_ARG;
-    if (!workgroups) workgroups = 64;
-    if (!chunk_bytes) chunk_bytes = 65536;
-    if (chunk_bytes % 4096) return TC_E_ARG;
+    if (!workgroups) workgroups = 12;
+    if (!chunk_bytes) chunk_bytes = 16384;
+    if (chunk_bytes % 4096 || workgroups > 8192) return TC_E_ARG;
+    for (uint32_t k = 0; k < n; ++k) {
+        if (out[k].bytes && in[k].bytes && out[k].bytes != in[k].bytes) return TC_E_ARG;
+        if (out[k].bytes && (!out[k].src || !out[k].dst || ((((uintptr_t)out[k].src) | ((uintptr_t)out[k].dst)) & 15))) return TC_E_ARG;
+        if (in[k].bytes && (!in[k].src || !in[k].dst || ((((uintptr_t)in[k].src) | ((uintptr_t)in[k].dst)) & 15))) return TC_E_ARG;
+    }
+    StreamTickets tk((hipStream_t)stream);
+    if (!tk.p) return TC_E_HIP;
     uint32_t i = 0;
     while (i < n) {
         TcMoverArgs a{};
         a.chunk_bytes = chunk_bytes;
+        a.tickets = tk.p;
         for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
             const uint64_t bytes = out[i].bytes ? out[i].bytes : in[i].bytes;
             if (!bytes) continue;
@@ -1775,7 +1813,7 @@ extern "C" int tc_exchange_batch(const tc_segment *out, const tc_segment *in, ui
             a.n_chunks += (bytes + chunk_bytes - 1) / chunk_bytes;
             a.n_units++;
         }
-        if (tc_launch_mover(a, workgroups, (hipStream_t)stream) != hipSuccess) return TC_E_HIP;
+        if (tc_launch_mover(a, workgroups, (hipStream_t)stream, &tk.launches) != hipSuccess) return TC_E_HIP;
     }
     return TC_OK;
 }
