@@ -59,7 +59,8 @@ def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
     st = torch.cuda.current_stream().cuda_stream
     if shift == 0 and not unpack:
         # reference for hardware-counter runs: a plain device-to-device copy of exactly 1 GiB by
-        # the batched copy kernel with 1024 workgroups (grid 262144 x 1 names it in a kernel trace)
+        # the batched copy kernel with 1024 working workgroups (its grid of 8 x 1024 workgroups,
+        # 2097152 lanes, names it in a kernel trace)
         T.copy_batch(np.asarray([src.data_ptr()], dtype=np.uint64), np.asarray([slab.data_ptr()], dtype=np.uint64),
                      np.asarray([1 << 30], dtype=np.uint64), st, 1024, 65536)
         torch.cuda.synchronize()

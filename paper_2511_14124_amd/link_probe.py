@@ -7,13 +7,16 @@ Run as `python -m paper_2511_14124_amd.link_probe`.  Prints, in GB/s:
 2. the library's batched copy / exchange kernel over the same link, one launch
    per line: host->HBM only, HBM->host only, and exchange units (a tensor
    leaves a GPU buffer for a pinned buffer while another arrives), by unit size;
-3. the exchange kernel by workgroup count;
-4. the exchange kernel while another stream runs small kernels the host waits
+3. the exchange kernel by launch size (what a launch of a few MiB loses);
+4. the exchange kernel by the number of working workgroups (all on one XCD)
+   and by chunk size;
+5. the exchange kernel while another stream runs small kernels the host waits
    for one by one (what a decision launch per hook call does to a running
    migration launch).
 
-The numbers justify the defaults of the library (64 workgroups, 64 KiB chunks,
-zero-copy kernel instead of DMA-engine copies, decisions in windows).
+The numbers justify the defaults of the library (12 workgroups on one XCD,
+16 KiB chunks, zero-copy kernel instead of DMA-engine copies, decisions in
+windows).
 """
 
 from __future__ import annotations
@@ -103,14 +106,14 @@ def main():
         off = np.arange(n, dtype=np.uint64) * np.uint64(size)
         return off, np.full(n, size, dtype=np.uint64)
 
-    def exchange(size, wg=64, chunk=65536):
-        off, nb = units(size)
+    def exchange(size, wg=0, chunk=0, total=G):
+        off, nb = units(size, total)
         # out: HBM half 0 -> pinned half 0 (swap in place with in: pinned half 0 -> HBM half 0)
         dt = timed(lambda: T.exchange_batch(off + np.uint64(H), off + np.uint64(P), off + np.uint64(P),
                                             off + np.uint64(H), nb, st.cuda_stream, wg, chunk))
         return float(nb.sum()) / dt / 1e9
 
-    def oneway(size, h2d, wg=64, chunk=65536):
+    def oneway(size, h2d, wg=0, chunk=0):
         off, nb = units(size)
         src, dst = (P, H) if h2d else (H, P)
         dt = timed(lambda: T.copy_batch(off + np.uint64(src), off + np.uint64(dst), nb, st.cuda_stream, wg, chunk))
@@ -123,12 +126,16 @@ def main():
         print(f"{size >> 10:>8}Ki {n:>6} {oneway(size, True):>10.2f} {oneway(size, False):>10.2f} {exchange(size):>10.2f}",
               flush=True)
 
-    print("\nexchange of 16 x 64 MiB by workgroups per launch (GB/s per direction):")
-    for wg in (16, 32, 48, 64, 96, 128, 256, 1024):
+    print("\nexchange, one launch of 4 units, by bytes per direction (GB/s per direction; the call's own"
+          "\nstream-ordered allocation of the ticket counters is inside the time):")
+    for total in (1 * M, 2 * M, 4 * M, 8 * M, 16 * M, 32 * M, 64 * M, 256 * M):
+        print(f"  {total >> 20:>5} MiB {exchange(total // 4, total=total):8.2f}", flush=True)
+    print("\nexchange of 16 x 64 MiB by working workgroups (GB/s per direction):")
+    for wg in (4, 8, 12, 16, 24, 32, 64, 256):
         print(f"  {wg:>5} workgroups {exchange(64 * M, wg):8.2f}", flush=True)
-    print("\nexchange of 16 x 64 MiB by chunk size (64 workgroups):")
+    print("\nexchange of 16 x 64 MiB by chunk size (12 workgroups):")
     for chunk in (4096, 16384, 65536, 262144, 1 << 20):
-        print(f"  {chunk >> 10:>5} KiB chunks {exchange(64 * M, 64, chunk):8.2f}", flush=True)
+        print(f"  {chunk >> 10:>5} KiB chunks {exchange(64 * M, 12, chunk):8.2f}", flush=True)
 
     # a stream of small kernels the host waits for, while eight 1 GiB exchange launches run
     side = torch.cuda.Stream()
@@ -138,7 +145,7 @@ def main():
     def eight():
         for _ in range(8):
             T.exchange_batch(off + np.uint64(H), off + np.uint64(P), off + np.uint64(P), off + np.uint64(H), nb,
-                             st.cuda_stream, 64, 65536)
+                             st.cuda_stream)
 
     def with_side(n_small, sync_each):
         def fn():
