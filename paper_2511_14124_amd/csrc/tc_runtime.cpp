@@ -1,200 +1,13 @@
 // Runtime of libtc.so: the context, memory binding, the per-hook dispatch that
 // turns the decision kernel's op records into migration-kernel launches and
 // file-tier I/O, statistics, and the C ABI of include/tc.h.
-#include "tc_internal.h"
+#include "tc_ctx.h"
 
-#include <errno.h>
-#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
-#include <unistd.h>
 
 #include <algorithm>
-#include <atomic>
 #include <chrono>
-#include <condition_variable>
-#include <deque>
-#include <memory>
-#include <mutex>
-#include <thread>
-
-namespace {
-
-// Streams the copies run on.  K: the caller's migration stream, used by the
-// migration kernel (small tensors, staging copies inside HBM).  H and D: two
-// streams of the library's own, one per direction, that carry the large
-// tensors as DMA-engine copies (hipMemcpyAsync).
-enum { S_K = 0, S_H = 1, S_D = 2, N_STREAMS = 3 };
-
-const uint32_t OP_RING = 1024;          // events kept for the most recent copy operations
-
-// File I/O runs behind the hook thread on worker threads.  A tensor's extent
-// is cut into chunks of IO_CHUNK bytes; chunk i of tensor t belongs to lane
-// t + i, and the lane picks the file (if the tier is striped over several), the
-// writer and the reader.  One request therefore spreads over the workers, while
-// every chunk always goes to the same writer, and a worker works in order: two
-// writes of one extent land in the order they were issued.  A read of an extent
-// is queued only once the write queued for it has finished.  A write job may
-// carry an event to wait for (bytes a copy is still producing).
-const uint32_t IO_MAX_THREADS = 8, IO_MAX_FILES = 8;
-
-struct IoJob {
-    uint64_t seq;
-    hipEvent_t ev;          // write: nullptr = the bytes are ready
-    uint8_t *mem;           // write: source, read: destination
-    uint64_t bytes, off;
-    int fd;
-    bool read;
-};
-
-struct IoWorker {
-    std::thread th;
-    std::mutex mu;
-    std::condition_variable cv_job, cv_done;
-    std::deque<IoJob> q;
-    uint64_t issued = 0;                // hook thread only
-    std::atomic<uint64_t> done{0};      // stored under mu, polled without
-    bool quit = false;                  // under mu
-    uint8_t *bounce = nullptr;          // O_DIRECT: page-aligned block of its own
-};
-
-enum { IO_WRITERS = 0, IO_READERS = 1 };
-
-struct JobSet {             // the jobs of one request: per worker the newest of them (0: none)
-    uint8_t pool = IO_WRITERS;
-    bool any = false;
-    uint64_t seq[IO_MAX_THREADS] = {};
-};
-
-struct StBlock {            // live piece of the staging ring
-    uint64_t id, off, size;
-    uint64_t ops[2];        // copies that read or write it
-    JobSet job;             // write that reads it
-    bool issued;            // its unit has been launched (ops and job are final)
-};
-
-struct BounceBlock {        // live piece of the HBM bounce ring
-    uint64_t off, size, op; // op: the copy that reads it last (0 = not issued yet)
-};
-
-struct PUnit {              // one exchange unit being prepared
-    TcUnit u{};
-    int64_t gpu_y = -1;     // flat index of the GPU buffer
-    int64_t cpu_out = -1;   // flat index of the host buffer the outgoing tensor goes to
-    int64_t cpu_in = -1;    // flat index of the host buffer the incoming tensor comes from
-    bool out_staging = false, in_staging = false;
-    uint32_t out_tensor = 0;
-    uint64_t st_id = 0;     // its block of the staging ring (0: none)
-    JobSet read_job;        // file read that fills in_src (in_staging)
-};
-
-struct Timed {              // event pair around one timed operation
-    hipEvent_t t0, t1;
-    int kind;               // S_K kernel launch, S_H / S_D copy, K_DECIDE decision launch
-    uint64_t bytes;         // bytes moved; hook calls decided for K_DECIDE
-};
-enum { K_DECIDE = 3, N_KINDS = 4 };
-
-} // namespace
-
-struct tc_ctx {
-    int stage = 0;          // 0 created, 1 profiled, 2 pools, 3 placed, 4 bound
-    std::string err;
-    TcProfile prof;
-    tc_budget budget{};
-    TcPools pools;
-    TcPlacement place;
-
-    // bound memory
-    uint8_t *hbm = nullptr, *pinned = nullptr, *staging = nullptr;
-    uint64_t hbm_bytes = 0, pinned_bytes = 0, staging_bytes = 0;
-    int fds[IO_MAX_FILES];              // the file tier: one file, or several that stripe it by lane
-    uint32_t n_files = 0;
-    bool io_begun = false;              // a file request has been made: files and chunk size are final
-    uint64_t io_chunk = 8ull << 20;     // bytes per chunk of an extent
-    bool file_direct = false;           // the file was opened with O_DIRECT: 4 KiB aligned memory, offsets and lengths
-    uint8_t *io_bounce = nullptr;       // 4 KiB aligned host block (one chunk) for file I/O done by the calling thread in that mode
-    uint64_t io_bounce_bytes = 0;
-    hipStream_t streams[N_STREAMS]{};   // [S_K] is the caller's migration stream
-    hipStream_t dstream = nullptr;      // decision stream (ours)
-    bool null_mover = false;
-
-    // device tables
-    uint32_t *dev_block = nullptr;      // one allocation holding every table
-    TcDevTables T{};
-    TcDecideOut *dout = nullptr;        // pinned: one record per hook call of a window, then the op records
-    TcOpRec *dops = nullptr;            // (inside the same pinned block)
-    TcDecideOut *dout2 = nullptr;       // second block: a window is decided while the one before is dispatched
-    TcOpRec *dops2 = nullptr;
-    uint32_t dout_cap = 0;              // op records a block holds
-    uint32_t *d_step_ptr = nullptr;     // device copy of a replayed iteration's lists (tc_replay_iteration)
-    uint32_t *d_ids = nullptr;
-    uint8_t *d_rw = nullptr;
-    uint32_t replay_window = 64;        // steps decided per launch by tc_replay_iteration
-
-    // dispatch state
-    uint32_t mover_wgs = 12, chunk_bytes = 16384;
-    uint32_t *tickets = nullptr;            // device: the migration kernel's two ticket counters
-    uint64_t k_launches = 0;                // migration-kernel launches so far (their parity picks the counter)
-    uint64_t sdma_threshold = 0;            // tensors at least this large go through the DMA engines (0: none)
-    uint64_t op_id = 0;                 // copy operations issued (kernel launches and DMA copies)
-    uint64_t op_done[N_STREAMS]{};      // per stream: operations known complete
-    hipEvent_t op_ev[OP_RING]{};
-    uint8_t op_stream[OP_RING]{};
-    hipEvent_t ev_compute = nullptr;
-    bool compute_recorded = false;      // this hook call: ev_compute recorded
-    bool stream_waited[N_STREAMS]{};    // this hook call: stream already waits for ev_compute
-    std::vector<uint64_t> gpu_ticket, cpu_ticket;   // last operation that touched the buffer
-    std::deque<StBlock> st_q;           // staging ring, oldest block first
-    uint64_t st_head = 0, st_next_id = 1;
-    uint8_t *bounce = nullptr;          // HBM ring: outgoing large tensors wait here for their DMA copy
-    uint64_t bounce_bytes = 0, bounce_head = 0;
-    std::deque<BounceBlock> bounce_q;
-    // file tier behind the hook thread
-    int device = 0;
-    uint32_t n_io[2] = {4, 4};          // writer and reader threads; 0: that kind of I/O runs in the calling thread
-    std::vector<std::unique_ptr<IoWorker>> io[2];
-    std::vector<hipEvent_t> ev_free;
-    std::deque<std::pair<hipEvent_t, JobSet>> ev_busy;  // events the queued jobs of a request wait for
-    std::vector<JobSet> tensor_job;     // per tensor: newest queued write of its extent
-    std::vector<JobSet> cpu_job;        // per host buffer: queued write that reads it
-    std::atomic<uint64_t> wr_ns{0}, rd_ns{0};   // time the workers spent in pwrite / pread
-    std::mutex io_mu;
-    std::string io_err;                 // first failure of a writer (under io_mu)
-    std::atomic<bool> io_failed{false};
-    // units prepared but not issued yet: hook calls are merged into larger launches
-    std::vector<PUnit> deferred;
-    uint64_t deferred_bytes = 0;
-    uint64_t merge_bytes = 256ull << 20;
-    std::vector<uint8_t> gpu_pending, cpu_pending;  // buffer is touched by a deferred unit
-    hipStream_t last_compute = nullptr;
-    uint64_t last_k_op = 0;             // newest operation issued on the migration stream
-    bool measure_stall = false;         // pre-hook calls time the wait for their copies on the host
-    // last PRE call, for tc_emulate_compute
-    TcStampArgs last_pre{};
-    uint32_t iteration = 0;
-
-    // timing of migration launches and DMA copies
-    bool timing = false;
-    std::vector<Timed> timed;
-
-    std::vector<tc_op> log;
-    bool logging = true;
-    tc_stats stats{};
-};
-
-static int fail(tc_ctx *c, int code, const std::string &msg)
-{
-    if (c) c->err = msg;
-    return code;
-}
-
-#define HIP_TRY(c, expr)                                                                          \
-    do {                                                                                          \
-        hipError_t e_ = (expr);                                                                   \
-        if (e_ != hipSuccess)                                                                     \
-            return fail((c), TC_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));        \
-    } while (0)
 
 extern "C" const char *tc_strerror(int code)
 {
@@ -217,10 +30,6 @@ extern "C" int tc_create(tc_ctx **out)
     *out = new (std::nothrow) tc_ctx();
     return *out ? TC_OK : TC_E_CAPACITY;
 }
-
-static void io_stop(tc_ctx *c);
-static int io_start(tc_ctx *c);
-static int io_wait_all(tc_ctx *c);
 
 static void release_device(tc_ctx *c)
 {
@@ -495,6 +304,8 @@ static int wait_op(tc_ctx *c, uint64_t id)
     return TC_OK;
 }
 
+int tc_wait_op(tc_ctx *c, uint64_t id) { return wait_op(c, id); }
+
 // has operation `id` completed?  (asks the runtime, without blocking)
 static bool poll_op(tc_ctx *c, uint64_t id)
 {
@@ -567,20 +378,7 @@ static int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes)
 // memory, offset and length: extents are 4 KiB aligned and sized, so a length
 // rounded up stays inside the tensor's own extent, and the memory side is the
 // bounce block.
-static inline uint64_t io_align(const tc_ctx *c) { return c->file_direct ? 4096 : 256; }
-static inline uint64_t io_len(const tc_ctx *c, uint64_t n) { return c->file_direct ? (n + 4095) & ~4095ull : n; }
 
-// pwrite until everything is out; no context state is touched (writer threads use it)
-static bool pwrite_all(int fd, const uint8_t *src, uint64_t bytes, uint64_t off, std::string &err)
-{
-    while (bytes) {
-        ssize_t w = pwrite(fd, src, bytes, (off_t)off);
-        if (w < 0 && errno == EINTR) continue;
-        if (w <= 0) { err = std::string("pwrite: ") + strerror(errno); return false; }
-        src += w; off += (uint64_t)w; bytes -= (uint64_t)w;
-    }
-    return true;
-}
 
 // ---------------------------------------------------------------------------
 // dispatch: op records -> migration-kernel launches, DMA copies and file I/O
@@ -598,240 +396,6 @@ static bool pwrite_all(int fd, const uint8_t *src, uint64_t bytes, uint64_t off,
 // comes from per-buffer tickets: each buffer remembers the last operation that
 // touched it, and an operation waits for the tickets of the buffers it touches.
 // ---------------------------------------------------------------------------
-// ---- file I/O behind the hook thread -------------------------------------------
-static bool pread_all(int fd, uint8_t *dst, uint64_t bytes, uint64_t want, uint64_t off, std::string &err)
-{
-    // `bytes` are requested (rounded for O_DIRECT); at least `want` must arrive: a file
-    // whose last extent ends at the tensor's last byte is not a short read
-    uint64_t got = 0;
-    while (got < bytes) {
-        ssize_t r = pread(fd, dst + got, bytes - got, (off_t)(off + got));
-        if (r < 0 && errno == EINTR) continue;
-        if (r < 0) { err = std::string("pread: ") + strerror(errno); return false; }
-        if (r == 0) break;
-        got += (uint64_t)r;
-    }
-    if (got < want) { err = "pread: short file"; return false; }
-    return true;
-}
-
-// one job, by a worker thread (w) or by the calling thread (w == nullptr).
-// O_DIRECT cannot target memory the GPU driver has mapped (pread into a pinned
-// region fails with EFAULT on this kernel), so in that mode every request goes
-// through a bounce block, ordinary page-aligned memory of the library's own.
-static void io_run_job(tc_ctx *c, IoWorker *w, const IoJob &j)
-{
-    std::string err;
-    if (j.ev) {
-        hipError_t e = hipEventSynchronize(j.ev);
-        if (e != hipSuccess) err = std::string("hipEventSynchronize (file write): ") + hipGetErrorString(e);
-    }
-    if (err.empty()) {
-        const auto t0 = std::chrono::steady_clock::now();
-        uint8_t *blk = w ? w->bounce : c->io_bounce;
-        const uint64_t len = io_len(c, j.bytes);
-        if (j.read) {
-            if (c->file_direct) {
-                if (pread_all(j.fd, blk, len, j.bytes, j.off, err)) memcpy(j.mem, blk, j.bytes);
-            } else {
-                pread_all(j.fd, j.mem, j.bytes, j.bytes, j.off, err);
-            }
-        } else if (c->file_direct) {
-            memcpy(blk, j.mem, j.bytes);
-            memset(blk + j.bytes, 0, len - j.bytes);
-            pwrite_all(j.fd, blk, len, j.off, err);
-        } else {
-            pwrite_all(j.fd, j.mem, j.bytes, j.off, err);
-        }
-        (j.read ? c->rd_ns : c->wr_ns) += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
-                                              std::chrono::steady_clock::now() - t0).count();
-    }
-    if (!err.empty()) {
-        std::lock_guard<std::mutex> g(c->io_mu);
-        if (!c->io_failed.load()) { c->io_err = err; c->io_failed.store(true); }
-    }
-}
-
-static void io_worker_main(tc_ctx *c, IoWorker *w)
-{
-    (void)hipSetDevice(c->device);
-    for (;;) {
-        IoJob j;
-        {
-            std::unique_lock<std::mutex> lk(w->mu);
-            w->cv_job.wait(lk, [&] { return w->quit || !w->q.empty(); });
-            if (w->q.empty()) return;                  // quit, and nothing left to do
-            j = w->q.front();
-            w->q.pop_front();
-        }
-        io_run_job(c, w, j);
-        {
-            std::lock_guard<std::mutex> g(w->mu);
-            w->done.store(j.seq);
-        }
-        w->cv_done.notify_all();
-    }
-}
-
-// a worker's failure surfaces at the next call that waits for or queues a job
-static int io_check(tc_ctx *c)
-{
-    if (!c->io_failed.load()) return TC_OK;
-    std::lock_guard<std::mutex> g(c->io_mu);
-    return fail(c, TC_E_IO, c->io_err);
-}
-
-static bool io_done(tc_ctx *c, const JobSet &r)
-{
-    if (!r.any) return true;
-    const auto &pool = c->io[r.pool];
-    for (size_t w = 0; w < pool.size(); ++w)
-        if (r.seq[w] && pool[w]->done.load() < r.seq[w]) return false;
-    return true;
-}
-
-static int io_wait(tc_ctx *c, JobSet &r)
-{
-    if (r.any) {
-        const auto &pool = c->io[r.pool];
-        for (size_t wi = 0; wi < pool.size(); ++wi) {
-            if (!r.seq[wi] || pool[wi]->done.load() >= r.seq[wi]) continue;
-            IoWorker &w = *pool[wi];
-            std::unique_lock<std::mutex> lk(w.mu);
-            w.cv_done.wait(lk, [&] { return w.done.load() >= r.seq[wi]; });
-        }
-        r = JobSet{};
-    }
-    return io_check(c);
-}
-
-static int io_wait_all(tc_ctx *c)
-{
-    for (int pool = 0; pool < 2; ++pool)
-        for (auto &pw : c->io[pool]) {
-            IoWorker &w = *pw;
-            {
-                std::unique_lock<std::mutex> lk(w.mu);
-                w.cv_done.wait(lk, [&] { return w.done.load() >= w.issued; });
-            }
-        }
-    for (auto &e : c->ev_busy) c->ev_free.push_back(e.first);
-    c->ev_busy.clear();
-    return io_check(c);
-}
-
-static void io_stop(tc_ctx *c)
-{
-    (void)io_wait_all(c);
-    for (int pool = 0; pool < 2; ++pool) {
-        for (auto &pw : c->io[pool]) {
-            {
-                std::lock_guard<std::mutex> g(pw->mu);
-                pw->quit = true;
-            }
-            pw->cv_job.notify_all();
-            if (pw->th.joinable()) pw->th.join();
-            if (pw->bounce) free(pw->bounce);
-        }
-        c->io[pool].clear();
-    }
-    for (JobSet &r : c->tensor_job) r = JobSet{};
-    for (JobSet &r : c->cpu_job) r = JobSet{};
-    for (StBlock &b : c->st_q) b.job = JobSet{};
-    for (PUnit &p : c->deferred) p.read_job = JobSet{};
-}
-
-static int io_start(tc_ctx *c)
-{
-    for (int pool = 0; pool < 2; ++pool)
-        for (uint32_t i = 0; i < c->n_io[pool]; ++i) {
-            std::unique_ptr<IoWorker> w(new (std::nothrow) IoWorker());
-            if (!w) return fail(c, TC_E_CAPACITY, "no memory for an I/O worker");
-            if (c->file_direct) {
-                void *blk = nullptr;
-                if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0)
-                    return fail(c, TC_E_CAPACITY, "no memory for an I/O worker's bounce block");
-                w->bounce = (uint8_t *)blk;
-            }
-            try {
-                w->th = std::thread(io_worker_main, c, w.get());
-            } catch (...) {
-                if (w->bounce) free(w->bounce);
-                return fail(c, TC_E_CAPACITY, "could not start an I/O worker thread");
-            }
-            c->io[pool].push_back(std::move(w));
-        }
-    return TC_OK;
-}
-
-// Queue (or, without worker threads of that kind, perform) the transfer of
-// tensor t's extent: a write from `mem` or a read into it.  op != 0: the bytes
-// to write are being produced by copy operation `op`, issued on stream S a
-// moment ago.  `set` names the queued jobs.
-static int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set)
-{
-    *set = JobSet{};
-    set->pool = read ? IO_READERS : IO_WRITERS;
-    if (c->n_files == 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
-    int rc = io_check(c);
-    if (rc == TC_OK && read) rc = io_wait(c, c->tensor_job[t]);    // a queued write of this very extent goes first
-    if (rc != TC_OK) return rc;
-    c->io_begun = true;
-    auto &pool = c->io[set->pool];
-    if (pool.empty() && (rc = wait_op(c, op)) != TC_OK) return rc;
-    const uint64_t n = c->prof.bytes[t], base = c->place.file_off[t];
-    hipEvent_t ev = nullptr;
-    if (op && !pool.empty()) {
-        // one event for the whole request, recorded right behind the copy
-        while (!c->ev_busy.empty() && io_done(c, c->ev_busy.front().second)) {
-            c->ev_free.push_back(c->ev_busy.front().first);
-            c->ev_busy.pop_front();
-        }
-        if (c->ev_free.empty()) {
-            HIP_TRY(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming | hipEventBlockingSync));
-        } else {
-            ev = c->ev_free.back();
-            c->ev_free.pop_back();
-        }
-        hipError_t e = hipEventRecord(ev, c->streams[S]);
-        if (e != hipSuccess) {
-            c->ev_free.push_back(ev);
-            return fail(c, TC_E_HIP, std::string("hipEventRecord (file write): ") + hipGetErrorString(e));
-        }
-    }
-    uint64_t lane = t;
-    for (uint64_t o = 0; o < n; o += c->io_chunk, ++lane) {
-        IoJob j{0, ev, mem + o, std::min(c->io_chunk, n - o), base + o, c->fds[lane % c->n_files], read};
-        if (pool.empty()) {
-            io_run_job(c, nullptr, j);
-            continue;
-        }
-        const size_t wi = lane % pool.size();
-        IoWorker &w = *pool[wi];
-        j.seq = ++w.issued;
-        {
-            std::lock_guard<std::mutex> g(w.mu);
-            w.q.push_back(j);
-        }
-        w.cv_job.notify_one();
-        set->any = true;
-        set->seq[wi] = j.seq;
-    }
-    if (ev) c->ev_busy.push_back({ev, *set});
-    if (pool.empty()) return io_check(c);
-    if (!read) c->tensor_job[t] = *set;
-    return TC_OK;
-}
-
-// the same, finished before it returns (loads, read-backs, restores)
-static int io_transfer(tc_ctx *c, uint32_t t, uint8_t *mem, bool read)
-{
-    JobSet set;
-    int rc = io_submit(c, t, mem, read, 0, 0, &set);
-    if (rc != TC_OK) return rc;
-    return io_wait(c, set);
-}
-
 // a block of the HBM bounce ring, or nullptr if none can be had without
 // waiting for a copy of the batch being prepared
 static int bounce_alloc(tc_ctx *c, uint64_t bytes, uint8_t **out)
@@ -1641,50 +1205,6 @@ extern "C" int tc_mover_timing(tc_ctx *c, int enable, tc_timing *out)
     return TC_OK;
 }
 
-extern "C" int tc_set_io_threads(tc_ctx *c, uint32_t writers, uint32_t readers)
-{
-    if (!c) return TC_E_ARG;
-    if (writers > IO_MAX_THREADS || readers > IO_MAX_THREADS) return fail(c, TC_E_ARG, "at most 8 writer and 8 reader threads");
-    c->n_io[IO_WRITERS] = writers;
-    c->n_io[IO_READERS] = readers;
-    if (c->stage != 4 || c->n_files == 0 || c->null_mover) return TC_OK;
-    int rc = tc_synchronize(c);
-    if (rc != TC_OK) return rc;
-    io_stop(c);
-    return io_start(c);
-}
-
-extern "C" int tc_set_io_chunk(tc_ctx *c, uint64_t bytes)
-{
-    if (!c) return TC_E_ARG;
-    if (bytes < 65536 || bytes % 4096) return fail(c, TC_E_ARG, "chunk must be a multiple of 4096, at least 64 KiB");
-    if (c->stage == 4 && c->io_begun) return fail(c, TC_E_STATE, "the file tier is already in use");
-    c->io_chunk = bytes;
-    if (c->stage != 4 || c->n_files == 0 || c->null_mover || !c->file_direct) return TC_OK;
-    // O_DIRECT bounce blocks are one chunk each: make them anew
-    io_stop(c);
-    uint64_t largest = 0;
-    for (uint32_t t = 0; t < c->prof.n_tensors; ++t) largest = std::max(largest, c->prof.bytes[t]);
-    c->io_bounce_bytes = std::min<uint64_t>(c->io_chunk, (largest + 4095) & ~4095ull);
-    free(c->io_bounce);
-    void *blk = nullptr;
-    if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) { c->io_bounce = nullptr; return fail(c, TC_E_CAPACITY, "no memory for the I/O bounce block"); }
-    c->io_bounce = (uint8_t *)blk;
-    return io_start(c);
-}
-
-extern "C" int tc_add_stripe(tc_ctx *c, int fd)
-{
-    if (!c) return TC_E_ARG;
-    if (c->stage != 4 || c->null_mover) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
-    if (fd < 0) return fail(c, TC_E_ARG, "not a file descriptor");
-    if (c->n_files == 0) return fail(c, TC_E_STATE, "tc_bind_memory was given no file to add stripes to");
-    if (c->io_begun) return fail(c, TC_E_STATE, "the file tier is already in use");
-    if (c->n_files >= IO_MAX_FILES) return fail(c, TC_E_CAPACITY, "at most 8 files");
-    c->fds[c->n_files++] = fd;
-    return TC_OK;
-}
-
 extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)
 {
     if (!c) return TC_E_ARG;
@@ -1720,126 +1240,4 @@ extern "C" int tc_set_dma_threshold(tc_ctx *c, uint64_t bytes)
     }
     c->sdma_threshold = bytes;
     return TC_OK;
-}
-
-// ---------------------------------------------------------------------------
-// stand-alone kernels
-// ---------------------------------------------------------------------------
-// Ticket counters for the stand-alone movers: two words from the stream-ordered
-// allocator, cleared on the stream, freed on the stream behind the launches.
-namespace {
-struct StreamTickets {
-    uint32_t *p = nullptr;
-    hipStream_t s;
-    uint64_t launches = 0;
-    explicit StreamTickets(hipStream_t stream) : s(stream)
-    {
-        if (hipMallocAsync((void **)&p, 256, s) != hipSuccess) { p = nullptr; return; }
-        if (hipMemsetAsync(p, 0, 256, s) != hipSuccess) { (void)hipFreeAsync(p, s); p = nullptr; }
-    }
-    ~StreamTickets() { if (p) (void)hipFreeAsync(p, s); }
-};
-} // namespace
-
-extern "C" int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream, uint32_t workgroups,
-                             uint32_t chunk_bytes)
-{
-    if (!segs && n) return TC_E_ARG;
-    if (!workgroups) workgroups = 12;
-    if (!chunk_bytes) chunk_bytes = 16384;
-    if (chunk_bytes % 4096 || workgroups > 8192) return TC_E_ARG;
-    for (uint32_t k = 0; k < n; ++k)
-        if (segs[k].bytes && (!segs[k].src || !segs[k].dst || ((((uintptr_t)segs[k].src) | ((uintptr_t)segs[k].dst)) & 15)))
-            return TC_E_ARG;
-    StreamTickets tk((hipStream_t)stream);
-    if (!tk.p) return TC_E_HIP;
-    uint32_t i = 0;
-    while (i < n) {
-        TcMoverArgs a{};
-        a.chunk_bytes = chunk_bytes;
-        a.tickets = tk.p;
-        for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
-            if (!segs[i].bytes) continue;
-            if (!segs[i].src || !segs[i].dst) return TC_E_ARG;
-            if ((((uintptr_t)segs[i].src) | ((uintptr_t)segs[i].dst)) & 15) return TC_E_ARG;
-            TcUnit &u = a.u[a.n_units++];
-            u.in_src = (const uint8_t *)segs[i].src;
-            u.in_dst = (uint8_t *)segs[i].dst;
-            u.bytes = segs[i].bytes;
-            u.chunk0 = a.n_chunks;
-            a.n_chunks += (segs[i].bytes + chunk_bytes - 1) / chunk_bytes;
-        }
-        if (tc_launch_mover(a, workgroups, (hipStream_t)stream, &tk.launches) != hipSuccess) return TC_E_HIP;
-    }
-    return TC_OK;
-}
-
-extern "C" int tc_exchange_batch(const tc_segment *out, const tc_segment *in, uint32_t n, void *stream,
-                                 uint32_t workgroups, uint32_t chunk_bytes)
-{
-    if ((!out || !in) && n) return TC_E_ARG;
-    if (!workgroups) workgroups = 12;
-    if (!chunk_bytes) chunk_bytes = 16384;
-    if (chunk_bytes % 4096 || workgroups > 8192) return TC_E_ARG;
-    for (uint32_t k = 0; k < n; ++k) {
-        if (out[k].bytes && in[k].bytes && out[k].bytes != in[k].bytes) return TC_E_ARG;
-        if (out[k].bytes && (!out[k].src || !out[k].dst || ((((uintptr_t)out[k].src) | ((uintptr_t)out[k].dst)) & 15))) return TC_E_ARG;
-        if (in[k].bytes && (!in[k].src || !in[k].dst || ((((uintptr_t)in[k].src) | ((uintptr_t)in[k].dst)) & 15))) return TC_E_ARG;
-    }
-    StreamTickets tk((hipStream_t)stream);
-    if (!tk.p) return TC_E_HIP;
-    uint32_t i = 0;
-    while (i < n) {
-        TcMoverArgs a{};
-        a.chunk_bytes = chunk_bytes;
-        a.tickets = tk.p;
-        for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
-            const uint64_t bytes = out[i].bytes ? out[i].bytes : in[i].bytes;
-            if (!bytes) continue;
-            if (out[i].bytes && in[i].bytes && out[i].bytes != in[i].bytes) return TC_E_ARG;
-            TcUnit &u = a.u[a.n_units];
-            if (out[i].bytes) {
-                if (!out[i].src || !out[i].dst || ((((uintptr_t)out[i].src) | ((uintptr_t)out[i].dst)) & 15)) return TC_E_ARG;
-                u.out_src = (const uint8_t *)out[i].src;
-                u.out_dst = (uint8_t *)out[i].dst;
-            }
-            if (in[i].bytes) {
-                if (!in[i].src || !in[i].dst || ((((uintptr_t)in[i].src) | ((uintptr_t)in[i].dst)) & 15)) return TC_E_ARG;
-                u.in_src = (const uint8_t *)in[i].src;
-                u.in_dst = (uint8_t *)in[i].dst;
-            }
-            u.bytes = bytes;
-            u.chunk0 = a.n_chunks;
-            a.n_chunks += (bytes + chunk_bytes - 1) / chunk_bytes;
-            a.n_units++;
-        }
-        if (tc_launch_mover(a, workgroups, (hipStream_t)stream, &tk.launches) != hipSuccess) return TC_E_HIP;
-    }
-    return TC_OK;
-}
-
-extern "C" uint64_t tc_pack_tiles(uint64_t total_bytes) { return tc_pack_tile_count(total_bytes); }
-
-extern "C" int tc_pack_index(const uint64_t *slab_off, uint32_t n, uint64_t total, uint32_t *tile_first, void *stream)
-{
-    if ((!slab_off || !tile_first) && n && total) return TC_E_ARG;
-    return tc_launch_pack_index(slab_off, n, total, tile_first, (hipStream_t)stream) == hipSuccess ? TC_OK : TC_E_HIP;
-}
-
-extern "C" int tc_pack(void *slab, const void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
-                       uint32_t n, uint64_t total, const uint32_t *tile_first, void *stream)
-{
-    if ((!slab || !ptrs || !bytes || !slab_off) && n) return TC_E_ARG;
-    if ((uintptr_t)slab & 15) return TC_E_ARG;
-    return tc_launch_pack(slab, ptrs, bytes, slab_off, n, total, 0, tile_first, (hipStream_t)stream) == hipSuccess
-               ? TC_OK : TC_E_HIP;
-}
-
-extern "C" int tc_unpack(const void *slab, void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
-                         uint32_t n, uint64_t total, const uint32_t *tile_first, void *stream)
-{
-    if ((!slab || !ptrs || !bytes || !slab_off) && n) return TC_E_ARG;
-    if ((uintptr_t)slab & 15) return TC_E_ARG;
-    return tc_launch_pack((void *)slab, (const void *const *)ptrs, bytes, slab_off, n, total, 1, tile_first,
-                          (hipStream_t)stream) == hipSuccess ? TC_OK : TC_E_HIP;
 }
