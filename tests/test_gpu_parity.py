@@ -175,11 +175,12 @@ def test_dma_engine_path_keeps_every_byte(threshold, tmp_path):
 
 def test_gpt_1p3b_config_full_size_sampled_bytes():
     # configuration 2 at full size in the launch configuration bench.py times: 1544
-    # tensors, 19.95 GiB (17 GiB pinned, 3 GiB HBM), windowed replay, default merging.
+    # tensors, 19.95 GiB (17 GiB pinned, 3 GiB HBM), windows of 64 steps, launches merged up
+    # to 1 GiB, twelve workgroups on one XCD taking 16 KiB chunks (the defaults).
     # Schedule, counters and final maps are compared in full; bytes on a sample of
     # tensors the oracle rebuilds one by one (smallest, largest, every kind, stamped ones).
     wl = W.config(1)
-    tc = run_library(wl, fill=True, window=64)
+    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30)
     kinds = wl.tensor_kind
     order = np.argsort(wl.tensor_bytes, kind="stable")
     sample = set(order[:6].tolist()) | set(order[-6:].tolist())
@@ -224,11 +225,13 @@ def test_file_tier_configs_at_two_layers_full_bytes(index, tmp_path):
     # matrices) but two layers deep, so that pinned pools and the file tier fit the box:
     # optimizer states on the file tier (4), scarce host pools with spills and 1 % of the
     # accesses perturbed (5).  Schedule, counters and maps in full; bytes of every tensor
-    # under 1 MiB and of a sample of the large ones over all kinds and final tiers.
+    # under 1 MiB and of a sample of the large ones over all kinds and final tiers.  Launch
+    # configuration as bench.py times it: file tier striped over four files, staging ring
+    # sixteen largest tensors deep, 4 + 4 I/O threads, launches merged up to 1 GiB.
     wl = W.config(index, layers=2)
     big = int(wl.tensor_bytes.max())
-    tc = run_library(wl, fill=True, window=64, file_path=_tmpfile(tmp_path),
-                     staging_bytes=4 * ((big + 4095) // 4096 * 4096))
+    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30, file_path=_tmpfile(tmp_path),
+                     staging_bytes=16 * ((big + 4095) // 4096 * 4096), stripes=4)
     from oracle import tc_oracle as o
     r0 = o.replay_workload(wl)
     small = [t for t in range(wl.n_tensors) if wl.tensor_bytes[t] < (1 << 20)]
