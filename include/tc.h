@@ -317,7 +317,8 @@ int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_
 
 /* Migration-kernel tuning.  workgroups: how many workgroups of 256 lanes move
  * data (0 = default 12, at most 8192); they all run on one XCD, the launch
- * itself has eight times as many and those dealt to other XCDs exit at once.
+ * itself has as many times more as the GPU has XCDs (probed once per device)
+ * and those dealt to other XCDs exit at once.
  * chunk_bytes: the piece of work a workgroup takes from the launch's ticket
  * counter at a time (0 = default 16 KiB; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);

@@ -130,6 +130,7 @@ struct tc_ctx {
     uint32_t mover_wgs = 12, chunk_bytes = 16384;
     uint32_t *tickets = nullptr;            // device: the migration kernel's two ticket counters
     uint64_t k_launches = 0;                // migration-kernel launches so far (their parity picks the counter)
+    uint32_t mover_xcc = 0, mover_xcds = 1; // where the migration kernel's workgroups work (tc_mover_topology)
     uint64_t sdma_threshold = 0;            // tensors at least this large go through the DMA engines (0: none)
     uint64_t op_id = 0;                 // copy operations issued (kernel launches and DMA copies)
     uint64_t op_done[N_STREAMS]{};      // per stream: operations known complete

@@ -129,6 +129,7 @@ struct TcMoverArgs {
     uint32_t *tickets;                          // device: two words, both zero before the stream's first launch
     uint32_t slot;                              // 0 or 1: set by the launcher, alternates between launches
     uint32_t xcc;                               // the XCD whose workgroups do the work
+    uint32_t n_xcd;                             // XCDs the dispatcher deals workgroups to (grid = workgroups x n_xcd)
 };
 
 struct TcStampArgs {
@@ -143,7 +144,9 @@ struct TcStampArgs {
 hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideOut *out, TcOpRec *ops, hipStream_t s);
 hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, TcDecideOut *out, TcOpRec *ops,
                                    hipStream_t s);
-// workgroups: how many should work (the launch has eight times as many, those on other XCDs exit)
+// workgroups: how many should work (the launch has n_xcd times as many, those on other XCDs exit)
+// where the dispatcher puts workgroups on the current device (probed once): XCD of workgroup 0, number of XCDs
+hipError_t tc_mover_topology(uint32_t *xcc, uint32_t *n_xcd);
 // launches: how many launches have used a.tickets so far (all on one stream, in order); counted up here
 hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, uint64_t *launches);
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s);

@@ -3,6 +3,8 @@
 // fill kernel and the LDS-staged pack/unpack kernel.
 #include "tc_internal.h"
 
+#include <mutex>
+
 #define NONE 0xFFFFFFFFu
 #define WAVE 64
 
@@ -476,9 +478,10 @@ hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, 
 // load: 10 us on two XCDs, 19 us on three, 40-120 us on the other three), every
 // launch ends waiting ~100 us for the workgroups on the starved XCDs, and a
 // 16 MiB exchange runs at 39 GB/s per direction instead of 48.  Workgroups are
-// dealt to the XCDs in turn, so the grid is eight times the number wanted and a
-// workgroup that finds itself on another XCD exits at once (workgroup 0 always
-// stays, so that every chunk is moved wherever the dispatcher puts things).  A
+// dealt to the XCDs in turn, so the grid is n_xcd times the number wanted and a
+// workgroup that finds itself on another XCD than `xcc` exits at once (workgroup
+// 0 always stays, so that every chunk is moved wherever the dispatcher puts
+// things).  A
 // dozen workgroups (192 KiB in flight per direction) are the optimum: fewer
 // leave the link idle, more crowd each other out.
 //
@@ -488,7 +491,6 @@ hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, 
 
 #define MOVER_THREADS 256
 #define MOVER_UNROLL 4
-#define MOVER_XCDS 8
 
 __device__ __forceinline__ uint4 ld16(const uint8_t *p) { return *(const uint4 *)p; }
 __device__ __forceinline__ void st16(uint8_t *p, uint4 v) { *(uint4 *)p = v; }
@@ -562,12 +564,55 @@ __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
     }
 }
 
+// Which XCDs does the dispatcher deal workgroups to?  A probe launch of 64
+// workgroups writes down where each one ran: the number of distinct XCDs is the
+// factor between the grid and the workgroups that work, and the XCD of workgroup
+// 0 is the one they work on (with a single XCD visible, as in a partitioned
+// GPU, nothing is filtered).  Once per device and process.
+#define XCC_PROBE_WGS 64
+
+__global__ void tc_xcc_probe_kernel(uint32_t *out)
+{
+    uint32_t xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    if (threadIdx.x == 0) out[blockIdx.x] = xcc & 15u;
+}
+
+hipError_t tc_mover_topology(uint32_t *xcc, uint32_t *n_xcd)
+{
+    static std::mutex mu;
+    static struct { bool known; uint32_t xcc, n; } cache[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> g(mu);
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!cache[dev].known) {
+        uint32_t *d = nullptr, h[XCC_PROBE_WGS];
+        if ((e = hipMalloc((void **)&d, sizeof(h))) != hipSuccess) return e;
+        hipLaunchKernelGGL(tc_xcc_probe_kernel, dim3(XCC_PROBE_WGS), dim3(64), 0, nullptr, d);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipMemcpy(h, d, sizeof(h), hipMemcpyDeviceToHost);
+        (void)hipFree(d);
+        if (e != hipSuccess) return e;
+        uint32_t seen = 0;
+        for (uint32_t i = 0; i < XCC_PROBE_WGS; ++i) seen |= 1u << h[i];
+        cache[dev].xcc = h[0];
+        cache[dev].n = (uint32_t)__builtin_popcount(seen);
+        cache[dev].known = true;
+    }
+    *xcc = cache[dev].xcc;
+    *n_xcd = cache[dev].n;
+    return hipSuccess;
+}
+
 hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, uint64_t *launches)
 {
     if (a.n_units == 0 || a.n_chunks == 0) return hipSuccess;
     // the kernel trusts these counts: check them against the units before it runs
     if (a.n_units > TC_MOVER_MAX_UNITS || a.chunk_bytes == 0 || (a.chunk_bytes & 15)) return hipErrorInvalidValue;
-    if (!a.tickets || !launches || workgroups == 0 || workgroups > 8192) return hipErrorInvalidValue;
+    if (!a.tickets || !launches || workgroups == 0 || workgroups > 8192 || a.n_xcd == 0 || a.n_xcd > 16)
+        return hipErrorInvalidValue;
     uint64_t chunks = 0;
     for (uint32_t i = 0; i < a.n_units; ++i) {
         const TcUnit &u = a.u[i];
@@ -580,7 +625,7 @@ hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, u
     if (chunks != a.n_chunks || chunks >= 0xFFFF0000ull) return hipErrorInvalidValue;   // tickets are 32-bit
     // the counters alternate between the launches that really happen: each clears the other's
     a.slot = (uint32_t)(*launches & 1);
-    const uint64_t g = (a.n_chunks < workgroups ? a.n_chunks : workgroups) * MOVER_XCDS;
+    const uint64_t g = (a.n_chunks < workgroups ? a.n_chunks : workgroups) * a.n_xcd;
     hipLaunchKernelGGL(tc_mover_kernel, dim3((uint32_t)g), dim3(MOVER_THREADS), 0, s, a);
     const hipError_t e = hipGetLastError();
     if (e == hipSuccess) ++*launches;

@@ -11,8 +11,10 @@ struct StreamTickets {
     uint32_t *p = nullptr;
     hipStream_t s;
     uint64_t launches = 0;
+    uint32_t xcc = 0, n_xcd = 1;
     explicit StreamTickets(hipStream_t stream) : s(stream)
     {
+        if (tc_mover_topology(&xcc, &n_xcd) != hipSuccess) return;
         if (hipMallocAsync((void **)&p, 256, s) != hipSuccess) { p = nullptr; return; }
         if (hipMemsetAsync(p, 0, 256, s) != hipSuccess) { (void)hipFreeAsync(p, s); p = nullptr; }
     }
@@ -37,6 +39,8 @@ extern "C" int tc_copy_batch(const tc_segment *segs, uint32_t n, void *stream, u
         TcMoverArgs a{};
         a.chunk_bytes = chunk_bytes;
         a.tickets = tk.p;
+        a.xcc = tk.xcc;
+        a.n_xcd = tk.n_xcd;
         for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
             if (!segs[i].bytes) continue;
             if (!segs[i].src || !segs[i].dst) return TC_E_ARG;
@@ -72,6 +76,8 @@ extern "C" int tc_exchange_batch(const tc_segment *out, const tc_segment *in, ui
         TcMoverArgs a{};
         a.chunk_bytes = chunk_bytes;
         a.tickets = tk.p;
+        a.xcc = tk.xcc;
+        a.n_xcd = tk.n_xcd;
         for (; i < n && a.n_units < TC_MOVER_MAX_UNITS; ++i) {
             const uint64_t bytes = out[i].bytes ? out[i].bytes : in[i].bytes;
             if (!bytes) continue;

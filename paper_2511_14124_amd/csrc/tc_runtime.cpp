@@ -228,6 +228,8 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (e == hipSuccess) e = hipMemset(c->tickets, 0, 256);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     c->k_launches = 0;
+    e = tc_mover_topology(&c->mover_xcc, &c->mover_xcds);
+    if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     for (uint32_t i = 0; i < OP_RING; ++i) {
         e = hipEventCreateWithFlags(&c->op_ev[i], hipEventDisableTiming);
         if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
@@ -475,6 +477,8 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         TcMoverArgs args{};
         args.chunk_bytes = c->chunk_bytes;
         args.tickets = c->tickets;                          // (every launch of this context is on stream K, in order)
+        args.xcc = c->mover_xcc;
+        args.n_xcd = c->mover_xcds;
         uint64_t id, bytes = 0;
         int rc = begin_op(c, S_K, compute, &id);
         if (rc != TC_OK) return rc;
