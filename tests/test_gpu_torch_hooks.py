@@ -83,3 +83,18 @@ def test_training_through_the_cache_equals_resident_training():
     assert [(int(x["step"]), int(x["op"]), int(x["tensor"]), int(x["dst_slot"])) for x in log] == \
         [(e[1], e[3], e[4], e[8]) for e in r.log]
     assert (st["hits"], st["misses"]) == (r.hits, r.misses)
+
+
+def test_training_demo_runs_a_gpt_shaped_model_through_the_cache(capsys, monkeypatch):
+    # the demonstration script, at a size that takes a second: attention blocks, embedding,
+    # untied head, bf16; every parameter passes through the cache and nothing misses
+    import json
+    import sys
+    from paper_2511_14124_amd import train_demo
+    monkeypatch.setattr(sys, "argv", ["train_demo", "--layers", "2", "--d-model", "128", "--heads", "4", "--vocab", "512",
+                                      "--batch", "2", "--seq", "64", "--steps", "2", "--cache", "0.4"])
+    train_demo.main()
+    out = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    assert out["through_cache"]["hit_rate"] == 1.0
+    assert out["through_cache"]["h2d_GiB_per_step"] > 0 and out["cache_fraction"] < 0.8
+    assert out["model"]["modules_with_hooks"] == 2 * 6 + 3
