@@ -353,6 +353,17 @@ int tc_set_io_chunk(tc_ctx *ctx, uint64_t bytes);
  * descriptor stays the caller's. */
 int tc_add_stripe(tc_ctx *ctx, int fd);
 
+/* tc_migrate_step decides ahead: a training loop repeats the profiled iteration
+ * (Sec. 3.2.1), so instead of one decision launch and one wait per hook call the
+ * library decides windows of `steps` profiled steps per launch (the next window
+ * while the current one is handed out) and a call that is the profile's next one
+ * just takes its result.  A call that is not (another step, other tensors, other
+ * R/W flags) is still decided exactly: the tables return to their state before
+ * the window, the calls already handed out are decided again, and the call gets
+ * a launch of its own; results never depend on this setting.  0 = one launch per
+ * call; default 16; at most 256. */
+int tc_set_decide_ahead(tc_ctx *ctx, uint32_t steps);
+
 /* While a migration launch is still running, the copies of further hook calls
  * are held back and merged into one launch, until `bytes` bytes are prepared,
  * a prepared buffer is needed, or the file tier is involved; when the

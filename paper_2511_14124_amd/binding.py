@@ -124,6 +124,7 @@ def load_library(path: str = LIB_PATH):
         "tc_add_stripe": (i32, [vp, i32]),
         "tc_set_io_chunk": (i32, [vp, u64]),
         "tc_set_replay_window": (i32, [vp, u32]),
+        "tc_set_decide_ahead": (i32, [vp, u32]),
         "tc_copy_batch": (i32, [vp, u32, vp, u32, u32]),
         "tc_exchange_batch": (i32, [vp, vp, u32, vp, u32, u32]),
         "tc_pack_tiles": (u64, [u64]),
@@ -405,6 +406,9 @@ class TensorCache:
 
     def set_io_threads(self, writers: int, readers: int):
         self._check(lib().tc_set_io_threads(self._h, int(writers), int(readers)))
+
+    def set_decide_ahead(self, steps: int):
+        self._check(lib().tc_set_decide_ahead(self._h, int(steps)))
 
     def set_replay_window(self, steps: int):
         self._check(lib().tc_set_replay_window(self._h, int(steps)))

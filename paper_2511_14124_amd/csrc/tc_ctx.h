@@ -83,6 +83,16 @@ struct PUnit {              // one exchange unit being prepared
     JobSet read_job;        // file read that fills in_src (in_staging)
 };
 
+// Decisions made ahead for hook calls that follow the profile (tc_migrate_step):
+// a window of the profiled steps decided by one launch, consumed call by call.
+struct SpecWin {
+    bool valid = false, ready = false;  // ready: the host has seen its launch finish
+    uint32_t first = 0;                 // first step
+    uint32_t n_calls = 0, used = 0;     // hook calls decided / handed out
+    uint32_t ops_used = 0;              // op records handed out
+    int blk = 0;                        // result block and snapshot it uses
+};
+
 struct Timed {              // event pair around one timed operation
     hipEvent_t t0, t1;
     int kind;               // S_K kernel launch, S_H / S_D copy, K_DECIDE decision launch
@@ -125,6 +135,15 @@ struct tc_ctx {
     uint32_t *d_ids = nullptr;
     uint8_t *d_rw = nullptr;
     uint32_t replay_window = 64;        // steps decided per launch by tc_replay_iteration
+    // tc_migrate_step decides ahead along the profile: win[0] is being handed out, win[1]
+    // was launched behind it; snap[b] holds the mutable tables from before the window in block b
+    uint32_t ahead_steps = 16;          // steps per window (0: every call has its own launch)
+    SpecWin win[2];
+    uint32_t *snap[2] = {nullptr, nullptr};
+    hipEvent_t win_ev[2] = {nullptr, nullptr};
+    uint8_t *d_prof_rw = nullptr;       // device: R/W flags of the profiled rows
+    size_t mut_off = 0, mut_words = 0;  // the mutable tables inside dev_block
+    uint32_t ahead_pause = 0;           // calls to sit out after a call left the profile
 
     // dispatch state
     uint32_t mover_wgs = 12, chunk_bytes = 16384;

@@ -102,6 +102,7 @@ struct TcWindowArgs {
     const uint8_t *rw;
     uint32_t first, count;                      // steps first .. first+count-1
     uint32_t cap;                               // op records the window may write
+    uint32_t n_calls;                           // hook calls to decide: 2 * count, or fewer to stop inside the window
 };
 
 // ---------------------------------------------------------------------------

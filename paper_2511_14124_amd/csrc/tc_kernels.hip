@@ -437,6 +437,7 @@ __global__ __launch_bounds__(WAVE) void tc_decide_window_kernel(TcDevTables T, T
         a.n = n;
         a.step = w.first + k;
         for (uint32_t ph = TC_PRE; ph <= TC_POST; ++ph) {
+            if (2 * k + ph >= w.n_calls) return;
             a.phase = ph;
             TcDecideOut *rec = out + 2 * k + ph;
             decide_call(c, a, rec, ops + used, w.cap - used);
@@ -454,7 +455,7 @@ hipError_t tc_launch_decide(const TcDevTables &T, const TcStepArgs &a, TcDecideO
 hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, TcDecideOut *out, TcOpRec *ops,
                                    hipStream_t s)
 {
-    if (w.count == 0 || w.count > TC_WINDOW_MAX) return hipErrorInvalidValue;
+    if (w.count == 0 || w.count > TC_WINDOW_MAX || w.n_calls == 0 || w.n_calls > 2 * w.count) return hipErrorInvalidValue;
     hipLaunchKernelGGL(tc_decide_window_kernel, dim3(1), dim3(WAVE), 0, s, T, w, out, ops);
     return hipGetLastError();
 }

@@ -53,6 +53,12 @@ static void release_device(tc_ctx *c)
     if (c->d_rw) { (void)hipFree(c->d_rw); c->d_rw = nullptr; }
     if (c->bounce) { (void)hipFree(c->bounce); c->bounce = nullptr; }
     if (c->tickets) { (void)hipFree(c->tickets); c->tickets = nullptr; }
+    for (int b = 0; b < 2; ++b) {
+        if (c->snap[b]) { (void)hipFree(c->snap[b]); c->snap[b] = nullptr; }
+        if (c->win_ev[b]) { (void)hipEventDestroy(c->win_ev[b]); c->win_ev[b] = nullptr; }
+        c->win[b] = SpecWin{};
+    }
+    if (c->d_prof_rw) { (void)hipFree(c->d_prof_rw); c->d_prof_rw = nullptr; }
     if (c->dout) { (void)hipHostFree(c->dout); c->dout = nullptr; }
     if (c->io_bounce) { free(c->io_bounce); c->io_bounce = nullptr; }
 }
@@ -224,6 +230,18 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     e = hipStreamCreateWithFlags(&c->dstream, hipStreamNonBlocking);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    c->mut_off = o_cur;
+    c->mut_words = img.size() - o_cur;
+    for (int b = 0; b < 2 && e == hipSuccess; ++b) {
+        e = hipMalloc((void **)&c->snap[b], c->mut_words * sizeof(uint32_t));
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->win_ev[b], hipEventDisableTiming);
+        c->win[b] = SpecWin{};
+    }
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_prof_rw, std::max<size_t>(1, p.rows_rw.size()));
+    if (e == hipSuccess && !p.rows_rw.empty())
+        e = hipMemcpy(c->d_prof_rw, p.rows_rw.data(), p.rows_rw.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    c->ahead_pause = 0;
     e = hipMalloc((void **)&c->tickets, 256);
     if (e == hipSuccess) e = hipMemset(c->tickets, 0, 256);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
@@ -811,6 +829,126 @@ static int run_decide(tc_ctx *c, const TcStepArgs &a)
     return TC_OK;
 }
 
+// ---- deciding ahead along the profile ---------------------------------------
+// A training loop repeats the profiled iteration, so tc_migrate_step need not pay a
+// launch and a wait per hook call: it decides a window of the profiled steps in one
+// launch (and the window after it behind that one) and hands the results out as the
+// calls arrive.  A call that is not the profile's next one (another step, other
+// tensors, other R/W flags) ends this: the tables go back to what they were before
+// the window being handed out, the calls already handed out are decided again, and
+// the odd call gets a launch of its own.  Decisions depend on the tables and the
+// calls only, never on when a copy finishes, so deciding early changes no result.
+static bool call_follows_profile(const tc_ctx *c, uint32_t step, int phase, const uint32_t *ids, const uint8_t *rw,
+                                 uint32_t n)
+{
+    const TcProfile &p = c->prof;
+    const uint32_t b = p.row_begin[step];
+    if (p.row_begin[step + 1] - b != n) return false;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (p.rows_tensor[b + i] != ids[i]) return false;
+        if (phase == TC_PRE && p.rows_rw[b + i] != rw[i]) return false;   // (the post-hook decisions ignore the flags)
+    }
+    return true;
+}
+
+static int launch_window_ahead(tc_ctx *c, SpecWin &w, uint32_t first, int blk, uint32_t n_calls)
+{
+    TcWindowArgs a{};
+    a.step_ptr = c->T.row_begin; a.ids = c->T.rows_tensor; a.rw = c->d_prof_rw;
+    a.first = first;
+    a.count = std::min(c->ahead_steps, c->prof.n_steps - first);
+    a.cap = c->dout_cap;
+    a.n_calls = n_calls ? n_calls : 2 * a.count;
+    a.count = (a.n_calls + 1) / 2;
+    hipEvent_t t0;
+    int rc = timed_begin(c, K_DECIDE, &t0);
+    if (rc != TC_OK) return rc;
+    HIP_TRY(c, tc_launch_decide_window(c->T, a, blk ? c->dout2 : c->dout, blk ? c->dops2 : c->dops, c->dstream));
+    if ((rc = timed_end(c, K_DECIDE, t0, a.n_calls)) != TC_OK) return rc;
+    HIP_TRY(c, hipEventRecord(c->win_ev[blk], c->dstream));
+    c->stats.decide_launches++;
+    w = SpecWin{};
+    w.valid = true; w.first = first; w.n_calls = a.n_calls; w.blk = blk;
+    return TC_OK;
+}
+
+// start a window at `first`: the tables as they are now go into the block's snapshot
+static int start_window_ahead(tc_ctx *c, SpecWin &w, uint32_t first, int blk)
+{
+    HIP_TRY(c, hipMemcpyAsync(c->snap[blk], c->dev_block + c->mut_off, c->mut_words * sizeof(uint32_t),
+                              hipMemcpyDeviceToDevice, c->dstream));
+    return launch_window_ahead(c, w, first, blk, 0);
+}
+
+// Bring the tables back in step with the calls made so far: needed before anything
+// else decides or reads them (a call off the profile, the end of the iteration, a
+// replay, a state dump).
+static int settle_ahead(tc_ctx *c)
+{
+    if (!c->win[0].valid) return TC_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->dstream));
+    const SpecWin w = c->win[0];
+    c->win[0] = SpecWin{};
+    c->win[1] = SpecWin{};
+    HIP_TRY(c, hipMemcpyAsync(c->dev_block + c->mut_off, c->snap[w.blk], c->mut_words * sizeof(uint32_t),
+                              hipMemcpyDeviceToDevice, c->dstream));
+    if (w.used) {
+        SpecWin again;
+        int rc = launch_window_ahead(c, again, w.first, w.blk, w.used);
+        if (rc != TC_OK) return rc;
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->dstream));
+    return TC_OK;
+}
+
+// the decision of this call if it is the profile's next one (*o == nullptr otherwise)
+static int take_ahead(tc_ctx *c, uint32_t step, int phase, const uint32_t *ids, const uint8_t *rw, uint32_t n,
+                      const TcDecideOut **o, const TcOpRec **ops)
+{
+    *o = nullptr;
+    if (!c->ahead_steps) return TC_OK;
+    const bool follows = call_follows_profile(c, step, phase, ids, rw, n);
+    SpecWin &w = c->win[0];
+    if (w.valid && !(follows && step == w.first + w.used / 2 && (uint32_t)phase == (w.used & 1u))) {
+        c->ahead_pause = 8;                               // the loop has left the profile: sit a few calls out
+        return settle_ahead(c);
+    }
+    if (!w.valid) {
+        if (c->ahead_pause) { c->ahead_pause--; return TC_OK; }
+        if (!follows || phase != TC_PRE) return TC_OK;
+        int rc = start_window_ahead(c, c->win[0], step, 0);
+        if (rc != TC_OK) return rc;
+        const uint32_t next = step + c->win[0].n_calls / 2;
+        if (next < c->prof.n_steps && (rc = start_window_ahead(c, c->win[1], next, 1)) != TC_OK) return rc;
+    }
+    if (!w.ready) {
+        HIP_TRY(c, hipEventSynchronize(c->win_ev[w.blk]));
+        w.ready = true;
+    }
+    *o = (w.blk ? c->dout2 : c->dout) + w.used;
+    *ops = (w.blk ? c->dops2 : c->dops) + w.ops_used;
+    return TC_OK;
+}
+
+// the call's decision has been dispatched and its results are no longer needed
+static int advance_ahead(tc_ctx *c, const TcDecideOut *o)
+{
+    SpecWin &w = c->win[0];
+    w.ops_used += o->n_ops;
+    w.used++;
+    c->stats.cursor = o->cursor;
+    if (w.used < w.n_calls) return TC_OK;
+    // the window is used up: the one decided behind it takes its place, and its block
+    // and snapshot serve the window after that
+    const int freed = w.blk;
+    c->win[0] = c->win[1];
+    c->win[1] = SpecWin{};
+    if (!c->win[0].valid) return TC_OK;
+    const uint32_t next = c->win[0].first + c->win[0].n_calls / 2;
+    if (next < c->prof.n_steps) return start_window_ahead(c, c->win[1], next, freed);
+    return TC_OK;
+}
+
 // what a pre-hook call does once its decisions are dispatched: counters, the
 // buffers' addresses, the waits of the compute stream, the stamp list
 static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint32_t *ids, const uint8_t *rw,
@@ -889,13 +1027,21 @@ extern "C" int tc_migrate_step(tc_ctx *c, uint32_t step, int phase, const uint32
         a.rw[i] = rw ? rw[i] : (uint8_t)TC_R;
     }
     a.n = n; a.step = step; a.phase = (uint32_t)phase; a.cap = c->dout_cap;
-    int rc = run_decide(c, a);
-    if (rc != TC_OK) return rc;
     hipStream_t compute = (hipStream_t)compute_stream;
-    rc = dispatch(c, c->dout, c->dops, step, phase, compute);
+    const TcDecideOut *o = nullptr;
+    const TcOpRec *ops = nullptr;
+    int rc = take_ahead(c, step, phase, a.ids, a.rw, n, &o, &ops);
     if (rc != TC_OK) return rc;
-    if (phase == TC_PRE) return finish_pre(c, c->dout, step, ids, a.rw, n, compute, dev_ptrs_out);
-    return TC_OK;
+    const bool ahead = o != nullptr;
+    if (!ahead) {
+        if ((rc = run_decide(c, a)) != TC_OK) return rc;
+        o = c->dout;
+        ops = c->dops;
+    }
+    rc = dispatch(c, o, ops, step, phase, compute);
+    if (rc == TC_OK && phase == TC_PRE) rc = finish_pre(c, o, step, ids, a.rw, n, compute, dev_ptrs_out);
+    if (rc != TC_OK) return rc;
+    return ahead ? advance_ahead(c, o) : TC_OK;
 }
 
 extern "C" int tc_end_iteration(tc_ctx *c, void *compute_stream)
@@ -904,7 +1050,9 @@ extern "C" int tc_end_iteration(tc_ctx *c, void *compute_stream)
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     TcStepArgs a{};
     a.n = 0; a.step = c->prof.n_steps; a.phase = TC_END; a.cap = c->dout_cap;
-    int rc = run_decide(c, a);
+    int rc = settle_ahead(c);
+    if (rc != TC_OK) return rc;
+    rc = run_decide(c, a);
     if (rc != TC_OK) return rc;
     rc = dispatch(c, c->dout, c->dops, c->prof.n_steps, TC_END, (hipStream_t)compute_stream);
     if (rc != TC_OK) return rc;
@@ -951,7 +1099,8 @@ extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const ui
     }
     const bool saved = c->measure_stall;
     c->measure_stall = saved || measure_stall != 0;
-    int rc = replay_windows(c, step_ptr, ids, rw, n_steps, compute_stream, busy_ns);
+    int rc = settle_ahead(c);
+    if (rc == TC_OK) rc = replay_windows(c, step_ptr, ids, rw, n_steps, compute_stream, busy_ns);
     c->measure_stall = saved;
     if (rc != TC_OK) return rc;
     return tc_end_iteration(c, compute_stream);
@@ -979,6 +1128,7 @@ static int replay_windows(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *i
         w.first = k0;
         w.count = std::min(c->replay_window, n_steps - k0);
         w.cap = c->dout_cap;
+        w.n_calls = 2 * w.count;
         hipEvent_t t0;
         int rc = timed_begin(c, K_DECIDE, &t0);
         if (rc != TC_OK) return rc;
@@ -1072,6 +1222,8 @@ extern "C" int tc_dump_state(tc_ctx *c, uint8_t *tier, uint32_t *gpu_slot, uint3
     if (!c) return TC_E_ARG;
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     const uint32_t n_t = c->prof.n_tensors;
+    int rcs = settle_ahead(c);
+    if (rcs != TC_OK) return rcs;
     HIP_TRY(c, hipStreamSynchronize(c->dstream));
     std::vector<uint32_t> tmp(n_t);
     if (tier) {
@@ -1086,6 +1238,8 @@ extern "C" int tc_dump_state(tc_ctx *c, uint8_t *tier, uint32_t *gpu_slot, uint3
 // where tensor t lives right now (reads three words of the device tables)
 static int locate(tc_ctx *c, uint32_t t, uint32_t *tier, uint32_t *gs, uint32_t *cs)
 {
+    int rc = settle_ahead(c);
+    if (rc != TC_OK) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->dstream));
     HIP_TRY(c, hipMemcpy(tier, c->T.cur + t, 4, hipMemcpyDeviceToHost));
     HIP_TRY(c, hipMemcpy(gs, c->T.gslot + t, 4, hipMemcpyDeviceToHost));
@@ -1213,6 +1367,18 @@ extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)
 {
     if (!c) return TC_E_ARG;
     c->merge_bytes = bytes;
+    return TC_OK;
+}
+
+extern "C" int tc_set_decide_ahead(tc_ctx *c, uint32_t steps)
+{
+    if (!c) return TC_E_ARG;
+    if (steps > TC_WINDOW_MAX) return fail(c, TC_E_ARG, "window out of range");
+    if (c->stage == 4) {
+        int rc = settle_ahead(c);
+        if (rc != TC_OK) return rc;
+    }
+    c->ahead_steps = steps;
     return TC_OK;
 }
 

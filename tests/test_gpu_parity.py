@@ -9,7 +9,7 @@ import pytest
 
 import paper_2511_14124_amd as T
 import workloads as W
-from tests.parity import run_library, check_against_oracle
+from tests.parity import run_library, check_against_oracle, compare_logs, oracle_log_array
 
 pytestmark = pytest.mark.gpu
 
@@ -290,6 +290,57 @@ def test_pre_hook_returns_the_buffers_the_oracle_names():
     tc.synchronize()
     tier, gs, cslot = tc.dump_state()
     assert tier.tolist() == r.cur and gs.tolist() == r.gslot and cslot.tolist() == r.cslot
+    tc.close()
+
+
+@pytest.mark.parametrize("ahead", [0, 1, 3, 16, 256])
+def test_deciding_ahead_of_the_hooks_changes_nothing(ahead, tmp_path):
+    # tc_migrate_step decides windows of profiled steps ahead of the calls.  Calls that leave
+    # the profile (one access in six perturbed), state dumps in the middle of an iteration
+    # (after an odd number of calls, inside a window) and an iteration cut short all have to
+    # put the tables back in step: state after every few calls, op log, counters and bytes
+    # are the oracle's whatever the window.
+    from oracle import tc_oracle as o
+    wl = W.random_workload(33, n_tensors=90, n_steps=70, max_per_step=3, hbm_frac=0.12, host_frac=0.5,
+                           perturb_one_in=6, n_iterations=3)
+    st, te, rw, _ = wl.events()
+    r = o.build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw, wl.hbm_bytes, wl.host_bytes,
+                wl.align, wl.literal_alg2, payload=lambda t: W.workload_payload(wl, t))
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch(file_path=_tmpfile(tmp_path), staging_bytes=1 << 20)
+    tc.set_decide_ahead(ahead)
+    for t in range(wl.n_tensors):
+        tc.load_tensor(t, W.workload_payload(wl, t))
+    cs = torch.cuda.Stream()
+
+    def same_state():
+        tier, gs, cslot = tc.dump_state()
+        assert tier.tolist() == r.cur and gs.tolist() == r.gslot and cslot.tolist() == r.cslot
+
+    for it, steps in enumerate(wl.iterations):
+        last = len(steps) if it != 1 else len(steps) // 2          # the second iteration stops half way
+        for k, access in enumerate(steps[:last]):
+            ids = [t for (t, _a) in access]
+            flags = [a for (_t, a) in access]
+            tc.migrate_step(k, T.PRE, ids, flags, cs.cuda_stream)
+            r.pre(k, access)
+            if k % 7 == 3:
+                same_state()                                       # between a step's two calls
+            tc.emulate_compute(cs.cuda_stream)
+            tc.migrate_step(k, T.POST, ids, flags, cs.cuda_stream)
+            r.post(k, ids)
+            if k % 11 == 5:
+                same_state()
+        tc.end_iteration(cs.cuda_stream)
+        r.end_iteration()
+        same_state()
+    tc.synchronize()
+    compare_logs(tc.dump_oplog(), oracle_log_array(r))
+    stt = tc.cache_stats()
+    assert (stt["hits"], stt["misses"], stt["fails"]) == (r.hits, r.misses, r.fails)
+    assert r.misses > 0
+    for t in range(wl.n_tensors):
+        assert np.array_equal(tc.read_tensor(t), r.read_tensor(t)), t
     tc.close()
 
 
