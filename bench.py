@@ -38,8 +38,8 @@ TRAFFIC_RATIO = {"tc_mover_kernel": (1.0000 + 1.0000) / 2.0,          # (fetch +
 def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
     """Pack kernel on a stress shape: the workloads' small-tensor size histogram
     repeated until ~4 GiB, one launch.  shift = 0: tensor and slab addresses agree
-    modulo 16 (pool buffers are 256-byte aligned), the register path; shift != 0:
-    every tensor sits `shift` bytes off, the LDS-staged path.  Returns
+    modulo 16 (pool buffers are 256-byte aligned); shift != 0: every tensor sits
+    `shift` bytes off, so every tensor-side 128-bit access is misaligned.  Returns
     (GB/s algorithmic = 2 x payload / time, ms, payload bytes, segments)."""
     dev = torch.device("cuda:0")
     sizes = np.asarray([4096, 4096, 8192, 12288, 16384, 4096, 4096, 32768, 8192, 4096], dtype=np.uint64)
@@ -279,13 +279,18 @@ def main():
         pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)
         unpack_gbs, unpack_ms, _, _ = bench_pack(torch, T, unpack=True)
         staged_gbs, staged_ms, _, _ = bench_pack(torch, T, shift=4)
+        odd_gbs, odd_ms, _, _ = bench_pack(torch, T, shift=1)
+        odd_un_gbs, odd_un_ms, _, _ = bench_pack(torch, T, shift=1, unpack=True)
         out["roofline_pack"] = {
             "bound": "hbm", "achieved": pack_gbs, "peak": 8000.0, "unit": "GB/s",
             "frac": pack_gbs / 8000.0, "traffic": TRAFFIC_RATIO["tc_pack_kernel"] * 2.0 * pack_bytes,
             "kernel": "tc_pack_kernel", "payload_bytes": pack_bytes, "segments": pack_n, "ms": pack_ms,
             "unpack": {"achieved": unpack_gbs, "frac": unpack_gbs / 8000.0, "ms": unpack_ms},
-            "lds_staged_variant": {"achieved": staged_gbs, "frac": staged_gbs / 8000.0, "ms": staged_ms,
-                                   "note": "every tensor 4 bytes off the slab's 16-byte phase"}}
+            "misaligned_variant": {"achieved": staged_gbs, "frac": staged_gbs / 8000.0, "ms": staged_ms,
+                                   "note": "pack, every tensor 4 bytes off the slab's 16-byte phase"},
+            "odd_shift_variant": {"achieved": odd_gbs, "frac": odd_gbs / 8000.0, "ms": odd_ms,
+                                  "unpack": {"achieved": odd_un_gbs, "frac": odd_un_gbs / 8000.0, "ms": odd_un_ms},
+                                  "note": "every tensor 1 byte off"}}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(W)
     print(json.dumps(out))

@@ -430,13 +430,13 @@ int tc_exchange_batch(const tc_segment *out, const tc_segment *in, uint32_t n, v
  * into one contiguous device slab, segment i at slab_off[i]; unpack is the
  * reverse.  Segments must be sorted by slab_off and must not overlap; bytes of
  * the slab (pack) or of a tensor (unpack) that no segment covers are not
- * written.  The slab is processed in 16 KiB tiles, one workgroup each.  When a
- * tile's pieces begin and end on 16-byte boundaries of the slab and each
- * tensor address agrees with its slab address modulo 16 (pool buffers are
- * 256-byte aligned), the tile moves register to register with all its loads
- * in flight at once; otherwise it is staged in LDS so that both the reads and
- * the writes are still 128-bit and coalesced although source and destination
- * are misaligned against each other.
+ * written.  The slab is processed in 16 KiB tiles, one workgroup each.  A tile
+ * that at most 32 segments reach into moves register to register, 128 bits
+ * per request with all its loads in flight at once: aligned on the slab side,
+ * at whatever address the tensor has on the other (bytes at segment edges that
+ * fill no whole 16-byte vector of the slab move bytewise).  A tile of more,
+ * tinier segments is staged in LDS so that the slab side still moves 128 bits
+ * per request.
  *   slab        device, 16-byte aligned, total_bytes long
  *   ptrs, bytes, slab_off   device arrays of n entries
  *   tile_first  device array of tc_pack_tiles(total_bytes) entries written by

@@ -733,21 +733,26 @@ hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t s
 // an index the workgroup bisects for itself and pays that latency on every
 // launch.
 //
-// Fast path (every piece of the tile starts and ends on a 16-byte boundary of
-// the slab, and its tensor address agrees with the slab address modulo 16;
-// pool buffers are 256-byte aligned, so this is the normal case): the first 32
-// lanes of each wave fetch 32 consecutive table entries in one round trip, the
-// pieces go into a small per-wave table in LDS, and each lane then moves four
-// 128-bit vectors, looking up the piece of each vector in that table: all
-// loads of the tile are in flight before the first store.
+// Register path (a tile that at most 32 pieces reach into): the first 33 lanes
+// of each wave fetch consecutive table entries in one round trip, the pieces go
+// into a small per-wave table in LDS, and each lane then moves four 128-bit
+// vectors, looking up the piece of each vector in that table: all loads of the
+// tile are in flight before the first store.  The slab side of a vector is
+// always 16-byte aligned.  The tensor side is aligned too in the normal case
+// (pool buffers are 256-byte aligned; slab offsets that are multiples of 16);
+// where it is not, the access simply goes to the odd address: 128-bit global
+// loads at any byte address run at 95-97 % of the aligned rate and stores at
+// 91-92 % (measured on a plain tile copy), which beats realigning the tile
+// through LDS (the earlier table-driven LDS path reached 63 % of the HBM peak
+// for a 4-byte shift and 50 % for an odd one).  Vectors that a piece covers only
+// partly (a piece that does not begin or end on a 16-byte boundary of the slab)
+// move bytewise afterwards, 32 byte-tasks per piece.
 //
-// General path (anything else): pieces are taken one after the other.  A piece
-// whose two addresses agree modulo 16 goes register to register; one whose
-// addresses disagree is staged in LDS, which holds the tile as the slab sees
-// it: the global side that is aligned for its own pointer moves as 128-bit
-// requests, the LDS side absorbs the shift, and the other global side leaves as
-// 128-bit requests aligned for *its* pointer; only the few bytes at piece edges
-// move bytewise.
+// Many-piece path (more than 32 pieces in one 16 KiB tile, i.e. pieces of a few
+// hundred bytes): pieces are taken one after the other and the tile is staged in
+// LDS as the slab sees it, so that however small the pieces, the slab side moves
+// as 128-bit requests; a piece whose two addresses agree modulo 16 goes register
+// to register.
 //
 // Bytes of the slab (pack) or of a tensor (unpack) that no piece covers are
 // never written.  Segments must be sorted by slab offset and must not overlap.
@@ -756,6 +761,7 @@ hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t s
 #define PACK_THREADS 256
 #define PACK_CAND 32
 typedef uint32_t pack_v4 __attribute__((ext_vector_type(4)));
+struct __attribute__((packed, aligned(1))) pack_u16 { pack_v4 v; };   // 16 bytes at any address
 
 // dst and src agree modulo 16; any address space mix (global/LDS); len <= PACK_TILE,
 // so a lane has at most four vectors and all of them are loaded before the first store
@@ -902,152 +908,6 @@ __device__ __forceinline__ void pack_wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// 16 bytes to / from LDS at any alignment: the widest access the address allows
-__device__ __forceinline__ void pack_lds_store16(uint8_t *q, pack_v4 v)
-{
-    const uint32_t a = (uint32_t)(uintptr_t)q;
-    if ((a & 15) == 0) {
-        *(pack_v4 *)q = v;
-    } else if ((a & 3) == 0) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) ((uint32_t *)q)[k] = v[k];
-    } else if ((a & 1) == 0) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) ((uint16_t *)q)[k] = (uint16_t)(v[k >> 1] >> (16 * (k & 1)));
-    } else {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) q[k] = (uint8_t)(v[k >> 2] >> (8 * (k & 3)));
-    }
-}
-
-__device__ __forceinline__ pack_v4 pack_lds_load16(const uint8_t *q)
-{
-    const uint32_t a = (uint32_t)(uintptr_t)q;
-    pack_v4 v = {0, 0, 0, 0};
-    if ((a & 15) == 0) {
-        v = *(const pack_v4 *)q;
-    } else if ((a & 3) == 0) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = ((const uint32_t *)q)[k];
-    } else if ((a & 1) == 0) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k >> 1] |= (uint32_t)((const uint16_t *)q)[k] << (16 * (k & 1));
-    } else {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) v[k >> 2] |= (uint32_t)q[k] << (8 * (k & 3));
-    }
-    return v;
-}
-
-// One tile with at most PACK_CAND pieces, some of them misaligned: staged in LDS, all
-// pieces at once.  The piece table (this wave's rows) gives for piece p its slab range
-// [tb[p], te[p]), its tensor address minus tb[p] in tg[p], and in tv[p] the number of
-// 128-bit body vectors of the pieces before it (tv[n_p] = all of them).  A piece's
-// body is what lies between its tensor address rounded up to 16 and its end rounded
-// down; the up to 15 bytes before and after move bytewise.  `stage` holds the tile as
-// the slab sees it.
-__device__ __forceinline__ void pack_tile_staged(uint8_t *stage, const uint64_t *tb, const uint64_t *te,
-                                                 uint8_t *const *tg, const uint32_t *tv, uint32_t n_p,
-                                                 uint8_t *slab, uint64_t t0, uint64_t t1, int unpack, uint32_t tid)
-{
-    constexpr int VEC = PACK_TILE / (PACK_THREADS * 16);
-    const uint32_t n_body = tv[n_p];
-    // tensor side of every body vector this lane handles: address and place in the tile
-    uint8_t *ga[VEC];
-    uint32_t lo[VEC];
-    uint32_t p = 0;
-#pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-        const uint32_t j = tid + k * PACK_THREADS;
-        ga[k] = nullptr;
-        lo[k] = 0;
-        if (j < n_body) {
-            while (tv[p + 1] <= j) ++p;
-            uint8_t *g0 = tg[p] + tb[p];
-            const uint32_t h = (uint32_t)((16 - ((uintptr_t)g0 & 15)) & 15);
-            const uint32_t o = h + (j - tv[p]) * 16;
-            ga[k] = g0 + o;
-            lo[k] = (uint32_t)(tb[p] - t0) + o;
-        }
-    }
-    if (!unpack) {
-        // tensors -> LDS: every body vector in flight, then the shifted LDS stores
-        pack_v4 v[VEC];
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            v[k] = pack_v4{0, 0, 0, 0};
-            if (ga[k]) v[k] = __builtin_nontemporal_load((const pack_v4 *)ga[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < VEC; ++k)
-            if (ga[k]) pack_lds_store16(stage + lo[k], v[k]);
-    } else {
-        // slab -> LDS: the whole tile, aligned on both sides
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
-            if (x + 16 <= t1) *(pack_v4 *)(stage + (x - t0)) = __builtin_nontemporal_load((const pack_v4 *)(slab + x));
-            else for (uint64_t y = x; y < t1; ++y) stage[y - t0] = slab[y];
-        }
-    }
-    // bytes before and after each piece's body (tensor side): 32 byte-tasks per piece
-    if (!unpack) {
-        for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
-            const uint32_t q = task >> 5, idx = task & 31;
-            const uint8_t *g0 = tg[q] + tb[q];
-            const uint32_t len = (uint32_t)(te[q] - tb[q]);
-            uint32_t h = (uint32_t)((16 - ((uintptr_t)g0 & 15)) & 15);
-            h = h < len ? h : len;
-            const uint32_t nb = (len - h) >> 4, tail = len - h - nb * 16;
-            const uint32_t base = (uint32_t)(tb[q] - t0);
-            if (idx < 16) { if (idx < h) stage[base + idx] = g0[idx]; }
-            else if (idx - 16 < tail) { const uint32_t o = h + nb * 16 + idx - 16; stage[base + o] = g0[o]; }
-        }
-    }
-    __syncthreads();
-    if (!unpack) {
-        // LDS -> slab: whole vectors inside a piece, then the bytes at piece edges
-        uint32_t q = 0;
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
-            while (q < n_p && te[q] <= x) ++q;
-            if (q < n_p && tb[q] <= x && x + 16 <= te[q])
-                __builtin_nontemporal_store(*(const pack_v4 *)(stage + (x - t0)), (pack_v4 *)(slab + x));
-        }
-        for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
-            const uint32_t r = task >> 5, idx = task & 31;
-            const uint64_t b = tb[r], e = te[r];
-            const uint64_t up = (b + 15) & ~15ull, dn = e & ~15ull;
-            if (idx < 16) {
-                const uint64_t y = b + idx;
-                if (y < (e < up ? e : up)) slab[y] = stage[y - t0];
-            } else {
-                const uint64_t y = (up > dn ? up : dn) + (idx - 16);
-                if (y < e) slab[y] = stage[y - t0];
-            }
-        }
-    } else {
-        // LDS -> tensors: shifted LDS loads, aligned 128-bit stores, then the edge bytes
-#pragma unroll
-        for (int k = 0; k < VEC; ++k)
-            if (ga[k]) __builtin_nontemporal_store(pack_lds_load16(stage + lo[k]), (pack_v4 *)ga[k]);
-        for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
-            const uint32_t r = task >> 5, idx = task & 31;
-            uint8_t *g0 = tg[r] + tb[r];
-            const uint32_t len = (uint32_t)(te[r] - tb[r]);
-            uint32_t h = (uint32_t)((16 - ((uintptr_t)g0 & 15)) & 15);
-            h = h < len ? h : len;
-            const uint32_t nb = (len - h) >> 4, tail = len - h - nb * 16;
-            const uint32_t base = (uint32_t)(tb[r] - t0);
-            if (idx < 16) { if (idx < h) g0[idx] = stage[base + idx]; }
-            else if (idx - 16 < tail) { const uint32_t o = h + nb * 16 + idx - 16; g0[o] = stage[base + o]; }
-        }
-    }
-}
-
-// 64 registers per lane keep eight waves per SIMD resident: measured 5.5 -> 6.1 TB/s together
-// with the streaming (non-temporal) accesses of the fast path
 __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void tc_pack_kernel(
     uint8_t *slab, uint8_t *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
     uint32_t n, uint64_t total, int unpack, const uint32_t *tile_first)
@@ -1057,7 +917,6 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
     __shared__ __attribute__((aligned(16))) uint8_t stage[PACK_TILE];
     __shared__ uint64_t tab_b[PACK_THREADS / WAVE][PACK_CAND], tab_e[PACK_THREADS / WAVE][PACK_CAND];
     __shared__ uint8_t *tab_g[PACK_THREADS / WAVE][PACK_CAND];
-    __shared__ uint32_t tab_v[PACK_THREADS / WAVE][PACK_CAND + 1];
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const uint64_t t0 = (uint64_t)blockIdx.x * TILE;
     const uint64_t t1 = t0 + TILE < total ? t0 + TILE : total;
@@ -1088,7 +947,7 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
         pack_tile_general(stage, slab, ptrs, bytes, slab_off, n, seg, t0, t1, unpack, tid);
         return;
     }
-    const bool staged = __ballot(valid && !ok) != 0;
+    const bool ragged = __ballot(valid && !ok) != 0;       // some piece is not whole 16-byte vectors on both sides
     const uint32_t n_p = (uint32_t)__popcll(vmask);
     if (valid) {
         const uint32_t p = (uint32_t)__popcll(vmask & ((1ull << lane) - 1));
@@ -1098,51 +957,58 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
     }
     // each wave reads only what its own lanes wrote: no workgroup barrier, a wave-level one
     pack_wave_lds_sync();
-    if (staged) {
-        // body vectors per piece and their running sum over the pieces before (lane order = piece order)
-        uint32_t nb = 0;
-        if (valid) {
-            const uint32_t len = (uint32_t)(e - b);
-            uint32_t h = (uint32_t)((16 - ((uintptr_t)g & 15)) & 15);
-            h = h < len ? h : len;
-            nb = (len - h) >> 4;
-        }
-        uint32_t incl = nb;
-#pragma unroll
-        for (int d = 1; d < WAVE; d <<= 1) {
-            const uint32_t up = __shfl_up(incl, d, WAVE);
-            if (lane >= (uint32_t)d) incl += up;
-        }
-        if (valid) tab_v[wave][(uint32_t)__popcll(vmask & ((1ull << lane) - 1))] = incl - nb;
-        if (lane == WAVE - 1) tab_v[wave][n_p] = incl;
-        pack_wave_lds_sync();
-        pack_tile_staged(stage, tab_b[wave], tab_e[wave], tab_g[wave], tab_v[wave], n_p, slab, t0, t1, unpack, tid);
-        return;
-    }
-    // address pairs first (table look-ups), then every load, then every store
-    const uint8_t *src[VEC];
-    uint8_t *dst[VEC];
+    // Every 128-bit vector of the tile that lies inside one piece moves through registers:
+    // address pairs first (table look-ups), then every load, then every store.  The slab
+    // side is always 16-byte aligned; the tensor side is wherever the tensor is (the
+    // hardware takes 128-bit global accesses at any byte address, at 91-97 % of the
+    // aligned rate, which beats realigning through LDS).
+    uint8_t *ga[VEC];
     uint32_t p = 0;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
         while (p < n_p && tab_e[wave][p] <= x) ++p;
-        const bool in = p < n_p && tab_b[wave][p] <= x;
-        uint8_t *ga = in ? tab_g[wave][p] + x : nullptr;
-        uint8_t *sa = in ? slab + x : nullptr;
-        src[k] = unpack ? sa : ga;
-        dst[k] = unpack ? ga : sa;
+        const bool in = p < n_p && tab_b[wave][p] <= x && x + 16 <= tab_e[wave][p];
+        ga[k] = in ? tab_g[wave][p] + x : nullptr;
     }
     // streaming accesses: nothing moved here is read again by this kernel
     pack_v4 v[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
+        const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
         v[k] = pack_v4{0, 0, 0, 0};
-        if (src[k]) v[k] = __builtin_nontemporal_load((const pack_v4 *)src[k]);
+        if (ga[k]) v[k] = unpack ? __builtin_nontemporal_load((const pack_v4 *)(slab + x))
+                                 : __builtin_nontemporal_load(&((const pack_u16 *)ga[k])->v);
     }
 #pragma unroll
-    for (int k = 0; k < VEC; ++k)
-        if (dst[k]) __builtin_nontemporal_store(v[k], (pack_v4 *)dst[k]);
+    for (int k = 0; k < VEC; ++k) {
+        const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+        if (ga[k]) {
+            if (unpack) __builtin_nontemporal_store(v[k], &((pack_u16 *)ga[k])->v);
+            else __builtin_nontemporal_store(v[k], (pack_v4 *)(slab + x));
+        }
+    }
+    if (!ragged) return;
+    // the bytes of each piece before its first and behind its last whole vector (slab side):
+    // 32 byte-tasks per piece
+    for (uint32_t task = tid; task < n_p * 32; task += PACK_THREADS) {
+        const uint32_t r = task >> 5, idx = task & 31;
+        const uint64_t pb = tab_b[wave][r], pe = tab_e[wave][r];
+        const uint64_t up = (pb + 15) & ~15ull, dn = pe & ~15ull;
+        uint64_t y;
+        bool mine;
+        if (idx < 16) {
+            y = pb + idx;
+            mine = y < (pe < up ? pe : up);
+        } else {
+            y = (up > dn ? up : dn) + (idx - 16);
+            mine = y < pe;
+        }
+        if (mine) {
+            uint8_t *gq = tab_g[wave][r] + y;
+            if (unpack) *gq = slab[y]; else slab[y] = *gq;
+        }
+    }
 }
 
 uint64_t tc_pack_tile_count(uint64_t total) { return (total + PACK_TILE - 1) / PACK_TILE; }

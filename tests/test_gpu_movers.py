@@ -1,6 +1,7 @@
 """The stand-alone movers of the library on a real MI355X, byte for byte
-against the plain definitions in oracle/pack_oracle.py: LDS-staged pack and
-unpack, the batched copy and the batched exchange of the migration kernel."""
+against the plain definitions in oracle/pack_oracle.py: pack and unpack (the
+register path at any alignment, the LDS-staged path for tiles of many tiny
+pieces), the batched copy and the batched exchange of the migration kernel."""
 
 import numpy as np
 import pytest
@@ -84,8 +85,9 @@ def test_pack_and_unpack_match_the_definition(name, sizes, src_gaps, slab_gaps, 
 @pytest.mark.parametrize("seed", range(8))
 def test_pack_and_unpack_on_random_layouts(seed):
     # random sizes (1 B .. 40 KiB, skewed to small ones), random gaps and phases on both
-    # sides, several hundred segments over dozens of tiles: register path, LDS-staged path
-    # and the piece-by-piece path (more than 32 pieces in a tile) all occur, tile by tile
+    # sides, several hundred segments over dozens of tiles: the register path with aligned and
+    # with misaligned tensor-side accesses, ragged piece edges, and the LDS-staged many-piece
+    # path (more than 32 pieces in a tile) all occur, tile by tile
     rng = np.random.default_rng(1000 + seed)
     n = int(rng.integers(150, 700))
     kinds = rng.integers(0, 4, size=n)
