@@ -1,6 +1,6 @@
 // HIP kernels for gfx950 (MI355X): the scheduler's decision kernel, the batched
 // migration kernel, the stamp/spin stand-in for module compute, the payload
-// fill kernel and the LDS-staged pack/unpack kernel.
+// fill kernel and the pack/unpack kernel.
 #include "tc_internal.h"
 
 #include <mutex>
