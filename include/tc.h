@@ -431,7 +431,7 @@ int tc_exchange_batch(const tc_segment *out, const tc_segment *in, uint32_t n, v
  * reverse.  Segments must be sorted by slab_off and must not overlap; bytes of
  * the slab (pack) or of a tensor (unpack) that no segment covers are not
  * written.  The slab is processed in 16 KiB tiles, one workgroup each.  A tile
- * that at most 32 segments reach into moves register to register, 128 bits
+ * that at most 256 segments reach into moves register to register, 128 bits
  * per request with all its loads in flight at once: aligned on the slab side,
  * at whatever address the tensor has on the other (bytes at segment edges that
  * fill no whole 16-byte vector of the slab move bytewise).  A tile of more,

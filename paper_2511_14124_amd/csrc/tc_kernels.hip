@@ -748,11 +748,14 @@ hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t s
 // partly (a piece that does not begin or end on a 16-byte boundary of the slab)
 // move bytewise afterwards, 32 byte-tasks per piece.
 //
-// Many-piece path (more than 32 pieces in one 16 KiB tile, i.e. pieces of a few
-// hundred bytes): pieces are taken one after the other and the tile is staged in
-// LDS as the slab sees it, so that however small the pieces, the slab side moves
-// as 128-bit requests; a piece whose two addresses agree modulo 16 goes register
-// to register.
+// Wide-table path (33 to 256 pieces in one 16 KiB tile, i.e. pieces of 64 to 500
+// bytes): the register path again, with one table entry per lane of the workgroup
+// and a bisection per vector instead of a scan.
+//
+// Many-piece path (more pieces than that): pieces are taken one after the other
+// and the tile is staged in LDS as the slab sees it, so that however small the
+// pieces, the slab side moves as 128-bit requests; a piece whose two addresses
+// agree modulo 16 goes register to register.
 //
 // Bytes of the slab (pack) or of a tensor (unpack) that no piece covers are
 // never written.  Segments must be sorted by slab offset and must not overlap.
@@ -896,6 +899,96 @@ __device__ void pack_tile_general(uint8_t *tile, uint8_t *slab, uint8_t *const *
     }
 }
 
+// One tile that up to PACK_WIDE pieces reach into: the register path with one table
+// entry per lane of the workgroup (the table lives where the many-piece path stages
+// its tile) and a bisection per vector instead of a scan.  Returns false, having moved
+// nothing, if the tile has more pieces than that.
+#define PACK_WIDE PACK_THREADS
+__device__ __noinline__ bool pack_tile_wide(uint8_t *stage, uint8_t *slab, uint8_t *const *ptrs, const uint64_t *bytes,
+                                            const uint64_t *slab_off, uint32_t n, uint32_t seg, uint64_t t0,
+                                            uint64_t t1, int unpack, uint32_t tid)
+{
+    constexpr int VEC = PACK_TILE / (PACK_THREADS * 16);
+    uint64_t *wb = (uint64_t *)stage, *we = wb + PACK_WIDE;
+    uint8_t **wg = (uint8_t **)(we + PACK_WIDE);
+    uint32_t *flag = (uint32_t *)(wg + PACK_WIDE);          // [0]: too many pieces, [1]: some piece has ragged edges
+    // entry seg + tid; a segment that does not reach into the tile becomes the empty piece [t1, t1),
+    // which keeps the begins sorted and is never the answer of a bisection for x < t1
+    uint64_t b = t1, e = t1;
+    uint8_t *g = nullptr;
+    if (seg + tid < n) {
+        const uint64_t so = slab_off[seg + tid], se = so + bytes[seg + tid];
+        if (so < t1 && se > t0) {
+            b = so > t0 ? so : t0;
+            e = se < t1 ? se : t1;
+            g = ptrs[seg + tid] - so;                       // tensor address of slab offset x is g + x
+        }
+    }
+    if (tid == 0) {
+        flag[0] = (seg + PACK_WIDE < n && slab_off[seg + PACK_WIDE] < t1) ? 1u : 0u;
+        flag[1] = 0;
+    }
+    wb[tid] = b;
+    we[tid] = e;
+    wg[tid] = g;
+    __syncthreads();
+    if (flag[0]) {
+        __syncthreads();                                    // the caller reuses the table's memory
+        return false;
+    }
+    if (((b | e) & 15) != 0) flag[1] = 1;                   // (every writer writes the same value)
+    uint8_t *ga[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+        // the last piece that begins at or before x
+        uint32_t lo = 0, hi = PACK_WIDE;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (wb[mid] <= x) lo = mid + 1; else hi = mid;
+        }
+        ga[k] = (lo > 0 && x + 16 <= we[lo - 1]) ? wg[lo - 1] + x : nullptr;
+    }
+    pack_v4 v[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+        v[k] = pack_v4{0, 0, 0, 0};
+        if (ga[k]) v[k] = unpack ? __builtin_nontemporal_load((const pack_v4 *)(slab + x))
+                                 : __builtin_nontemporal_load(&((const pack_u16 *)ga[k])->v);
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+        if (ga[k]) {
+            if (unpack) __builtin_nontemporal_store(v[k], &((pack_u16 *)ga[k])->v);
+            else __builtin_nontemporal_store(v[k], (pack_v4 *)(slab + x));
+        }
+    }
+    __syncthreads();
+    if (!flag[1]) return true;
+    // the bytes of each piece before its first and behind its last whole vector of the slab
+    for (uint32_t task = tid; task < PACK_WIDE * 32; task += PACK_THREADS) {
+        const uint32_t r = task >> 5, idx = task & 31;
+        const uint64_t pb = wb[r], pe = we[r];
+        const uint64_t up = (pb + 15) & ~15ull, dn = pe & ~15ull;
+        uint64_t y;
+        bool mine;
+        if (idx < 16) {
+            y = pb + idx;
+            mine = y < (pe < up ? pe : up);
+        } else {
+            y = (up > dn ? up : dn) + (idx - 16);
+            mine = y < pe;
+        }
+        if (mine) {
+            uint8_t *gq = wg[r] + y;
+            if (unpack) *gq = slab[y]; else slab[y] = *gq;
+        }
+    }
+    return true;
+}
+
 // Lanes of one wave exchange data through LDS without a workgroup barrier: the
 // hardware executes a wave's LDS instructions in order, but to the compiler every
 // lane is a thread of its own, and without this it may place one lane's load ahead
@@ -944,7 +1037,8 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
     const uint64_t vmask = __ballot(valid);
     // the same in every wave (all read the same entries): which way this tile goes
     if (__ballot(beyond) != 0) {
-        pack_tile_general(stage, slab, ptrs, bytes, slab_off, n, seg, t0, t1, unpack, tid);
+        if (!pack_tile_wide(stage, slab, ptrs, bytes, slab_off, n, seg, t0, t1, unpack, tid))
+            pack_tile_general(stage, slab, ptrs, bytes, slab_off, n, seg, t0, t1, unpack, tid);
         return;
     }
     const bool ragged = __ballot(valid && !ok) != 0;       // some piece is not whole 16-byte vectors on both sides

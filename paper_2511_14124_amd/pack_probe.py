@@ -4,8 +4,7 @@ Run as `python -m paper_2511_14124_amd.pack_probe`.  For every segment size from
 64 B to 1 MiB one launch packs (then unpacks) 1 GiB of equal segments, with the
 tensors at the slab's 16-byte phase and 4 bytes off it, and prints GB/s of read
 plus written bytes.  Segments of under 512 B put more than 32 pieces into a
-16 KiB tile and take the LDS-staged many-piece path; everything else moves
-through registers.
+16 KiB tile and take the path with the workgroup-wide piece table.
 """
 
 from __future__ import annotations

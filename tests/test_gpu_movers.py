@@ -37,8 +37,13 @@ PACK_CASES = [
     ("one_big", [5 << 20], [4], [0]),
     # 256-byte aligned buffers with padding between them (pool strides): the register path, gaps kept
     ("pool_strides", [1536, 4096, 12288, 3072, 24576, 512, 16384 * 2, 768] * 6, [0, 256, 1024], [0, 256]),
-    # more than 32 pieces in a tile: falls back to the piece-by-piece path
+    # 33 to 256 pieces in a tile: the register path with the workgroup-wide piece table
     ("many_small_aligned", [256] * 200 + [4096] * 5, [0], [0]),
+    ("wide_64B", [64] * 700 + [8192, 64, 64], [0, 192], [0]),
+    ("wide_ragged", [100] * 500 + [33, 7, 4096] + [52] * 300, [0, 1, 3, 28], [0, 0, 5]),
+    ("wide_exactly_256_pieces", [64] * 256 + [16384] + [64] * 257, [0], [0]),
+    # more pieces than that: staged in LDS, piece after piece
+    ("beyond_wide", [20] * 2000 + [16384] + [3] * 700, [0, 2], [0, 1]),
     # aligned and misaligned pieces mixed, tile by tile
     ("mixed", [4096] * 9 + [100] + [4096] * 7 + [8192, 33, 16384, 16384], [0], [0]),
 ]
