@@ -344,6 +344,21 @@ def test_deciding_ahead_of_the_hooks_changes_nothing(ahead, tmp_path):
     tc.close()
 
 
+@pytest.mark.parametrize("window", [None, 8])
+def test_long_replay_wraps_the_operation_ring(window, tmp_path):
+    # thirty iterations with one launch per hook call: well over a thousand copy operations, so the
+    # ring of 1024 operation events is reused, the ticket counters alternate over a
+    # thousand times and the file tier queues hundreds of requests; everything still equals the
+    # oracle, byte for byte
+    wl = W.random_workload(8, n_tensors=120, n_steps=80, max_per_step=3, hbm_frac=0.08, perturb_one_in=9,
+                           host_frac=0.3, n_iterations=30)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=1 << 20, merge_bytes=0, window=window)
+    r = check_against_oracle(wl, tc)
+    st = tc.cache_stats()
+    assert st["mover_launches"] > 1024 and r.bytes_file_write > 0          # more operations than the ring has events
+    tc.close()
+
+
 def _direct_ok(tmp_path):
     try:
         fd = os.open(os.path.join(str(tmp_path), "probe.bin"), os.O_RDWR | os.O_CREAT | os.O_DIRECT, 0o600)
