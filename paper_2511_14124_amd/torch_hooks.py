@@ -14,6 +14,10 @@ the C-ABI library:
         pc.sgd_step(lr)                                   # parameters pass through the cache once more
         pc.end_iteration()
 
+With `ParamCache(..., fused_sgd_lr=lr)` the update of a module's parameters is
+applied in its backward post-hook instead, while they are still in their cache
+buffers: no third pass, a third less traffic; `sgd_step` is then not called.
+
 Between its pre-hook and its post-hook a module's parameters are views into
 the HBM cache buffers the library returned; outside that window they point
 nowhere useful and must not be touched.  Gradients stay ordinary PyTorch
@@ -37,13 +41,15 @@ R, W, RW = 1, 2, 3
 
 
 class ParamCache:
-    def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256):
+    def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
+                 fused_sgd_lr: Optional[float] = None):
         import torch
         self.torch = torch
         self.model = model
         self.hbm_bytes = int(hbm_bytes)
         self.host_bytes = host_bytes
         self.align = align
+        self.fused_sgd_lr = fused_sgd_lr                  # plain SGD applied in the backward post-hook
         # leaf modules: those that own parameters directly
         self.mods = [m for m in model.modules() if any(True for _ in m.parameters(recurse=False))]
         self.params: List = []
@@ -123,7 +129,7 @@ class ParamCache:
     def _make_bwd_start(self, m):
         def hook(grad):
             if id(m) not in self._bwd_step:               # several outputs: the first gradient opens the step
-                self._bwd_step[id(m)] = self._begin(m, R)
+                self._bwd_step[id(m)] = self._begin(m, R if self.fused_sgd_lr is None else RW)
                 self._pending_bwd[id(m)] = len(self.mod_ids[id(m)])
             return grad
         return hook
@@ -134,6 +140,10 @@ class ParamCache:
                 return
             self._pending_bwd[id(m)] -= 1
             if self._pending_bwd[id(m)] == 0:
+                if self.fused_sgd_lr is not None and not self._recording:
+                    with self.torch.no_grad():            # the parameters are still in their cache buffers
+                        for p in m.parameters(recurse=False):
+                            p.data.add_(p.grad, alpha=-self.fused_sgd_lr)
                 self._end(m, self._bwd_step.pop(id(m)), R)
         return hook
 
@@ -153,8 +163,9 @@ class ParamCache:
             raise RuntimeError("a module's backward did not finish during the dry run")
         self._n_model_steps = len(self.steps)
         # the optimizer sweep: every parameter once, read and written
-        for t in range(len(self.params)):
-            self.steps.append([(t, RW)])
+        if self.fused_sgd_lr is None:
+            for t in range(len(self.params)):
+                self.steps.append([(t, RW)])
         for p in self.params:
             p.grad = None
 
@@ -190,6 +201,8 @@ class ParamCache:
         """Plain SGD through the cache: each parameter is fetched (read + write),
         updated in its cache buffer and left to the scheduler."""
         torch = self.torch
+        if self.fused_sgd_lr is not None:
+            raise RuntimeError("the update is applied in the backward hooks (fused_sgd_lr): there is no sweep")
         stream = torch.cuda.current_stream().cuda_stream
         k = self._n_model_steps
         with torch.no_grad():

@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--cache", type=float, default=0.3, help="HBM cache as a fraction of the parameter bytes")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--lr", type=float, default=1e-3)
+    ap.add_argument("--fused-sgd", action="store_true",
+                    help="apply the update in the backward hooks, while the parameters are still in the cache")
     args = ap.parse_args()
 
     import torch
@@ -112,14 +114,15 @@ def main():
     # ---- parameters in the tensor cache
     torch.manual_seed(0)
     model = build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
-    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache))
+    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None)
     pc.profile(lambda: iteration(model))
     pc.install()
     pc.tc.set_oplog(False, True)
 
     def cached_step():
         iteration(model)
-        pc.sgd_step(args.lr)
+        if not args.fused_sgd:
+            pc.sgd_step(args.lr)
         pc.end_iteration()
 
     s0 = None
@@ -148,7 +151,8 @@ def main():
                           "h2d_GiB_per_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n_counted / 2**30,
                           "d2h_GiB_per_step": (s1["bytes_d2h"] - s0["bytes_d2h"]) / n_counted / 2**30,
                           "h2d_GBps_over_the_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n_counted / t_off / 1e9,
-                          "hook_calls_per_step": 4 * len(pc.mods) + 2 * len(pc.params)},
+                          "hook_calls_per_step": 4 * len(pc.mods) + (0 if args.fused_sgd else 2 * len(pc.params)),
+                          "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters"},
         "note": "parameters only are managed (gradients and activations stay resident); plain SGD; hooks drive "
                 "tc_migrate_step one call at a time",
     }

@@ -23,7 +23,8 @@ def _model(seed):
     return torch.nn.Sequential(*layers).to("cuda:0")
 
 
-def test_training_through_the_cache_equals_resident_training():
+@pytest.mark.parametrize("fused", [False, True], ids=["sweep", "fused"])
+def test_training_through_the_cache_equals_resident_training(fused):
     lr, iters = 0.05, 4
     torch.manual_seed(0)
     xs = [torch.randn(32, 64, device="cuda:0") for _ in range(iters + 1)]
@@ -44,10 +45,10 @@ def test_training_through_the_cache_equals_resident_training():
 
     model = _model(7)
     total = sum(p.numel() * p.element_size() for p in model.parameters())
-    pc = ParamCache(model, hbm_bytes=int(total * 0.4))
+    pc = ParamCache(model, hbm_bytes=int(total * 0.4), fused_sgd_lr=lr if fused else None)
     pc.profile(lambda: loss_fn(model(xs[-1]), ys[-1]).backward())
     n_mod = len(pc.mods)
-    assert len(pc.steps) == 2 * n_mod + len(pc.params)           # forward, backward, one sweep
+    assert len(pc.steps) == 2 * n_mod + (0 if fused else len(pc.params))   # forward, backward, one sweep
     # backward order recorded by the hooks is the reverse of the forward order
     fwd = [tuple(t for t, _ in s) for s in pc.steps[:n_mod]]
     bwd = [tuple(t for t, _ in s) for s in pc.steps[n_mod:2 * n_mod]]
@@ -58,7 +59,8 @@ def test_training_through_the_cache_equals_resident_training():
         loss = loss_fn(model(xs[i]), ys[i])
         loss.backward()
         losses.append(float(loss.detach()))
-        pc.sgd_step(lr)
+        if not fused:
+            pc.sgd_step(lr)
         pc.end_iteration()
     got = pc.gather()
     st = pc.tc.cache_stats()
