@@ -62,6 +62,11 @@ class ParamCache:
         if any(len(list(m.parameters(recurse=False))) > T.MAX_STEP_TENSORS for m in self.mods):
             raise ValueError("a module owns more parameters than one hook call may name")
         self.mod_ids = {id(m): [self.pid[id(p)] for p in m.parameters(recurse=False)] for m in self.mods}
+        self._ids_np = {k: np.asarray(v, dtype=np.uint32) for k, v in self.mod_ids.items()}
+        self._flag_arrays: Dict[Tuple[int, int], np.ndarray] = {}
+        self._views: Dict[Tuple[int, int], object] = {}   # (parameter, buffer address) -> view into the HBM region
+        self._hbm_base = 0
+        self._one_id = [np.asarray([t], dtype=np.uint32) for t in range(len(self.params))]
         self.steps: List[List[Tuple[int, int]]] = []      # the profiled iteration
         self.tc: Optional[T.TensorCache] = None
         self._handles: list = []
@@ -86,6 +91,13 @@ class ParamCache:
             h.remove()
         self._handles = []
 
+    def _flags(self, n: int, rw: int):
+        """n copies of one R/W flag as the array the binding passes on (made once)."""
+        a = self._flag_arrays.get((n, rw))
+        if a is None:
+            a = self._flag_arrays[(n, rw)] = np.full(n, rw, dtype=np.uint8)
+        return a
+
     def _begin(self, m, rw: int) -> int:
         """Opens the next step for module m (steps are numbered in the order they open)."""
         ids = self.mod_ids[id(m)]
@@ -94,25 +106,27 @@ class ParamCache:
         if self._recording:
             self.steps.append([(t, rw) for t in ids])
         else:
-            self._fetch(k, ids, [rw] * len(ids))
+            self._fetch(k, ids, self._ids_np[id(m)], self._flags(len(ids), rw))
         return k
 
     def _end(self, m, k: int, rw: int):
-        ids = self.mod_ids[id(m)]
         if not self._recording:
+            ids = self._ids_np[id(m)]
             stream = self.torch.cuda.current_stream().cuda_stream
-            self.tc.migrate_step(k, T.POST, ids, [rw] * len(ids), stream)
+            self.tc.migrate_step(k, T.POST, ids, self._flags(len(ids), rw), stream)
 
-    def _fetch(self, k: int, ids, rw):
+    def _fetch(self, k: int, ids, ids_np, rw_np):
         stream = self.torch.cuda.current_stream().cuda_stream
-        ptrs = self.tc.migrate_step(k, T.PRE, ids, rw, stream, want_ptrs=True)
-        base = self.tc.hbm.data_ptr()
+        ptrs = self.tc.migrate_step(k, T.PRE, ids_np, rw_np, stream, want_ptrs=True)
         for t, ptr in zip(ids, ptrs):
             if not ptr:
                 raise RuntimeError(f"parameter {t} could not be given a GPU buffer (cache too small for this module)")
-            p = self.params[t]
-            n = self._nbytes[t]
-            p.data = self.tc.hbm[ptr - base: ptr - base + n].view(self._dtype[t]).view(self._shape[t])
+            # a parameter comes back to the same few buffers iteration after iteration: keep the views
+            view = self._views.get((t, ptr))
+            if view is None:
+                off, n = ptr - self._hbm_base, self._nbytes[t]
+                view = self._views[(t, ptr)] = self.tc.hbm[off: off + n].view(self._dtype[t]).view(self._shape[t])
+            self.params[t].data = view
 
     def _fwd_pre(self, m, args):
         self._fwd_step[id(m)] = self._begin(m, R)
@@ -193,6 +207,8 @@ class ParamCache:
             tc.load_tensor(t, p.detach().cpu().contiguous().view(torch.uint8).numpy().reshape(-1))
             p.data = torch.empty(0, dtype=self._dtype[t], device=p.device)
         self.tc = tc
+        self._hbm_base = tc.hbm.data_ptr()
+        self._views = {}
         self._k = 0
         self._register()
 
@@ -206,11 +222,13 @@ class ParamCache:
         stream = torch.cuda.current_stream().cuda_stream
         k = self._n_model_steps
         with torch.no_grad():
+            rw = self._flags(1, RW)
             for t, p in enumerate(self.params):
-                self._fetch(k, [t], [RW])
+                one = self._one_id[t]
+                self._fetch(k, (t,), one, rw)
                 if p.grad is not None:
                     p.data.add_(p.grad, alpha=-lr)
-                self.tc.migrate_step(k, T.POST, [t], [RW], stream)
+                self.tc.migrate_step(k, T.POST, one, rw, stream)
                 k += 1
 
     def end_iteration(self):
@@ -227,6 +245,7 @@ class ParamCache:
 
     def close(self):
         self._remove()
+        self._views = {}
         if self.tc is not None:
             self.tc.close()
             self.tc = None
