@@ -278,7 +278,7 @@ def main():
     if not args.no_pack:
         pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)
         unpack_gbs, unpack_ms, _, _ = bench_pack(torch, T, unpack=True)
-        staged_gbs, staged_ms, _, _ = bench_pack(torch, T, shift=4)
+        off4_gbs, off4_ms, _, _ = bench_pack(torch, T, shift=4)
         odd_gbs, odd_ms, _, _ = bench_pack(torch, T, shift=1)
         odd_un_gbs, odd_un_ms, _, _ = bench_pack(torch, T, shift=1, unpack=True)
         out["roofline_pack"] = {
@@ -286,7 +286,7 @@ def main():
             "frac": pack_gbs / 8000.0, "traffic": TRAFFIC_RATIO["tc_pack_kernel"] * 2.0 * pack_bytes,
             "kernel": "tc_pack_kernel", "payload_bytes": pack_bytes, "segments": pack_n, "ms": pack_ms,
             "unpack": {"achieved": unpack_gbs, "frac": unpack_gbs / 8000.0, "ms": unpack_ms},
-            "misaligned_variant": {"achieved": staged_gbs, "frac": staged_gbs / 8000.0, "ms": staged_ms,
+            "misaligned_variant": {"achieved": off4_gbs, "frac": off4_gbs / 8000.0, "ms": off4_ms,
                                    "note": "pack, every tensor 4 bytes off the slab's 16-byte phase"},
             "odd_shift_variant": {"achieved": odd_gbs, "frac": odd_gbs / 8000.0, "ms": odd_ms,
                                   "unpack": {"achieved": odd_un_gbs, "frac": odd_un_gbs / 8000.0, "ms": odd_un_ms},

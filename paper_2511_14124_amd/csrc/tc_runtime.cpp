@@ -479,7 +479,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         }
         if (dma) large.push_back(L); else small.push_back(i);
     }
-    // ---- stream K: small units and the staging copies of large ones, <= 24 units per launch
+    // ---- stream K: small units and the staging copies of large ones, at most TC_MOVER_MAX_UNITS per launch
     std::vector<std::pair<TcUnit, int64_t>> kunits;                // unit, index into `large` or -1-small
     for (size_t i : small) kunits.push_back({units[i].u, -1 - (int64_t)i});
     for (size_t j = 0; j < large.size(); ++j)
