@@ -148,6 +148,7 @@ hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, 
 // workgroups: how many should work (the launch has n_xcd times as many, those on other XCDs exit)
 // where the dispatcher puts workgroups on the current device (probed once): XCD of workgroup 0, number of XCDs
 hipError_t tc_mover_topology(uint32_t *xcc, uint32_t *n_xcd);
+hipError_t tc_launch_zero_tickets(uint32_t *tickets, hipStream_t s);   // both counters to zero, by a kernel
 // launches: how many launches have used a.tickets so far (all on one stream, in order); counted up here
 hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, uint64_t *launches);
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s);

@@ -565,6 +565,19 @@ __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
     }
 }
 
+// clears the two ticket counters of a stand-alone launch (a kernel, not a memset node: a caller
+// may be capturing the stream into a graph)
+__global__ void tc_zero_tickets_kernel(uint32_t *p)
+{
+    if (threadIdx.x < 2) p[threadIdx.x] = 0;
+}
+
+hipError_t tc_launch_zero_tickets(uint32_t *tickets, hipStream_t s)
+{
+    hipLaunchKernelGGL(tc_zero_tickets_kernel, dim3(1), dim3(64), 0, s, tickets);
+    return hipGetLastError();
+}
+
 // Which XCDs does the dispatcher deal workgroups to?  A probe launch of 64
 // workgroups writes down where each one ran: the number of distinct XCDs is the
 // factor between the grid and the workgroups that work, and the XCD of workgroup

@@ -5,7 +5,8 @@
 #include <stdint.h>
 
 // Ticket counters for the stand-alone movers: two words from the stream-ordered
-// allocator, cleared on the stream, freed on the stream behind the launches.
+// allocator, cleared on the stream by a small kernel, freed on the stream behind
+// the launches.
 namespace {
 struct StreamTickets {
     uint32_t *p = nullptr;
@@ -16,7 +17,7 @@ struct StreamTickets {
     {
         if (tc_mover_topology(&xcc, &n_xcd) != hipSuccess) return;
         if (hipMallocAsync((void **)&p, 256, s) != hipSuccess) { p = nullptr; return; }
-        if (hipMemsetAsync(p, 0, 256, s) != hipSuccess) { (void)hipFreeAsync(p, s); p = nullptr; }
+        if (tc_launch_zero_tickets(p, s) != hipSuccess) { (void)hipFreeAsync(p, s); p = nullptr; }
     }
     ~StreamTickets() { if (p) (void)hipFreeAsync(p, s); }
 };
