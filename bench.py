@@ -128,6 +128,7 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--merge-mib", type=int, default=1024, help="bytes merged into one migration launch")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-tune", action="store_true", help="keep the default number of working workgroups")
     ap.add_argument("--no-stall", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -157,6 +158,9 @@ def main():
         tc.bind_torch()
     if args.workgroups or args.chunk:
         tc.set_mover(args.workgroups, args.chunk)
+    tuned_wgs = None
+    if not args.workgroups and not args.no_tune:
+        tuned_wgs = tc.tune_mover()        # the regions hold nothing yet: measure the workgroup count
     if args.merge_mib is not None:
         tc.set_merge_bytes(args.merge_mib << 20)
     tc.fill_payload(0)
@@ -255,7 +259,7 @@ def main():
         "roofline": {"bound": "pcie", "achieved": achieved, "peak": peak, "unit": "GB/s",
                      "frac": achieved / peak if peak else None,
                      "traffic": TRAFFIC_RATIO["tc_mover_kernel"] * tm["kernel_bytes"] / max(1, n_launch),
-                     "kernel": "tc_mover_kernel", "launches": n_launch,
+                     "kernel": "tc_mover_kernel", "launches": n_launch, "working_workgroups": tuned_wgs or args.workgroups or 12,
                      "avg_launch_us": tm["kernel_ns"] / 1e3 / max(1, n_launch),
                      "algorithmic_bytes_per_launch": tm["kernel_bytes"] / max(1, n_launch),
                      "peak_published": 128.0,

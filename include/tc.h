@@ -323,6 +323,17 @@ int tc_dump_state(tc_ctx *ctx, uint8_t *tier, uint32_t *gpu_slot, uint32_t *cpu_
  * counter at a time (0 = default 16 KiB; a multiple of 4096). */
 int tc_set_mover(tc_ctx *ctx, uint32_t workgroups, uint32_t chunk_bytes);
 
+/* Measures the number of working workgroups instead of assuming it: a few
+ * exchange launches of up to 64 MiB between the bound HBM and pinned regions
+ * for each of 8..24 workgroups (about 30 ms in all), the fastest becomes the
+ * setting and is returned in *workgroups_out (may be NULL).  The optimum sits
+ * at a knee that depends on the host (too few workgroups leave the link idle,
+ * too many crowd each other out).  Only between tc_bind_memory and the first
+ * tensor loaded or hook call made, while the regions hold nothing: their
+ * contents are overwritten (TC_E_STATE afterwards).  Regions under 4 MiB are
+ * left alone and the current setting is returned. */
+int tc_tune_mover(tc_ctx *ctx, uint32_t *workgroups_out);
+
 /* File-tier I/O runs behind the calling thread.  Writes (Sec. 3.4.2: dirty
  * tensors leaving for NVMe; Alg. 4: a host buffer spilled to make room) go to
  * `writers` threads, reads into staging (a fetch from the file tier) to

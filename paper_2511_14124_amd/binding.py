@@ -120,6 +120,7 @@ def load_library(path: str = LIB_PATH):
         "tc_mover_timing": (i32, [vp, i32, C.POINTER(Timing)]),
         "tc_set_dma_threshold": (i32, [vp, u64]),
         "tc_set_merge_bytes": (i32, [vp, u64]),
+        "tc_tune_mover": (i32, [vp, C.POINTER(u32)]),
         "tc_set_io_threads": (i32, [vp, u32, u32]),
         "tc_add_stripe": (i32, [vp, i32]),
         "tc_set_io_chunk": (i32, [vp, u64]),
@@ -394,6 +395,12 @@ class TensorCache:
         t = Timing()
         self._check(lib().tc_mover_timing(self._h, int(enable), C.byref(t)))
         return {f[0]: getattr(t, f[0]) for f in Timing._fields_}
+
+    def tune_mover(self) -> int:
+        """Times exchanges between the (still empty) regions and keeps the best workgroup count."""
+        wg = C.c_uint32(0)
+        self._check(lib().tc_tune_mover(self._h, C.byref(wg)))
+        return int(wg.value)
 
     def set_merge_bytes(self, nbytes: int):
         self._check(lib().tc_set_merge_bytes(self._h, int(nbytes)))

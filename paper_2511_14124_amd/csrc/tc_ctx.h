@@ -122,6 +122,7 @@ struct tc_ctx {
     hipStream_t streams[N_STREAMS]{};   // [S_K] is the caller's migration stream
     hipStream_t dstream = nullptr;      // decision stream (ours)
     bool null_mover = false;
+    bool in_use = false;                // a tensor has been loaded or a hook call made: the regions hold data
 
     // device tables
     uint32_t *dev_block = nullptr;      // one allocation holding every table

@@ -271,6 +271,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     }
     c->streams[S_K] = (hipStream_t)mstream;
     c->null_mover = null_mover;
+    c->in_use = false;
     c->stats.hbm_budget = c->budget.hbm_bytes;
     c->stats.hbm_pool_bytes = pl.hbm_total;
     c->stats.host_budget = c->budget.host_bytes[0] + c->budget.host_bytes[1];
@@ -1027,6 +1028,7 @@ extern "C" int tc_migrate_step(tc_ctx *c, uint32_t step, int phase, const uint32
         a.rw[i] = rw ? rw[i] : (uint8_t)TC_R;
     }
     a.n = n; a.step = step; a.phase = (uint32_t)phase; a.cap = c->dout_cap;
+    c->in_use = true;
     hipStream_t compute = (hipStream_t)compute_stream;
     const TcDecideOut *o = nullptr;
     const TcOpRec *ops = nullptr;
@@ -1050,6 +1052,7 @@ extern "C" int tc_end_iteration(tc_ctx *c, void *compute_stream)
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     TcStepArgs a{};
     a.n = 0; a.step = c->prof.n_steps; a.phase = TC_END; a.cap = c->dout_cap;
+    c->in_use = true;
     int rc = settle_ahead(c);
     if (rc != TC_OK) return rc;
     rc = run_decide(c, a);
@@ -1099,6 +1102,7 @@ extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const ui
     }
     const bool saved = c->measure_stall;
     c->measure_stall = saved || measure_stall != 0;
+    c->in_use = true;
     int rc = settle_ahead(c);
     if (rc == TC_OK) rc = replay_windows(c, step_ptr, ids, rw, n_steps, compute_stream, busy_ns);
     c->measure_stall = saved;
@@ -1252,6 +1256,7 @@ extern "C" int tc_load_tensor(tc_ctx *c, uint32_t t, const void *src)
     if (!c || !src) return TC_E_ARG;
     if (c->stage != 4 || c->null_mover) return fail(c, TC_E_STATE, "needs bound memory");
     if (t >= c->prof.n_tensors) return fail(c, TC_E_ARG, "unknown tensor id");
+    c->in_use = true;
     int rc = tc_synchronize(c);
     if (rc != TC_OK) return rc;
     uint32_t tier, gs, cs;
@@ -1288,6 +1293,7 @@ extern "C" int tc_fill_payload(tc_ctx *c, uint32_t seed)
 {
     if (!c) return TC_E_ARG;
     if (c->stage != 4 || c->null_mover) return fail(c, TC_E_STATE, "needs bound memory");
+    c->in_use = true;
     int rc = tc_synchronize(c);
     if (rc != TC_OK) return rc;
     const uint32_t n_t = c->prof.n_tensors;
@@ -1319,6 +1325,64 @@ extern "C" int tc_set_mover(tc_ctx *c, uint32_t workgroups, uint32_t chunk_bytes
     if (workgroups > 8192) return fail(c, TC_E_ARG, "too many workgroups");
     c->mover_wgs = workgroups ? workgroups : 12;
     c->chunk_bytes = chunk_bytes ? chunk_bytes : 16384;
+    return TC_OK;
+}
+
+// The best number of working workgroups sits at a knee (too few leave the link idle, too
+// many crowd each other) whose place depends on the host: measure it.  The regions hold
+// nothing yet when this may be called, so exchanges between them can be timed freely.
+extern "C" int tc_tune_mover(tc_ctx *c, uint32_t *workgroups_out)
+{
+    if (!c) return TC_E_ARG;
+    if (c->stage != 4 || c->null_mover) return fail(c, TC_E_STATE, "needs bound memory");
+    if (c->in_use) return fail(c, TC_E_STATE, "the regions already hold tensors");
+    uint64_t bytes = std::min<uint64_t>(64ull << 20, std::min(c->hbm_bytes, c->pinned_bytes / 2));
+    bytes &= ~(uint64_t)65535;
+    if (workgroups_out) *workgroups_out = c->mover_wgs;
+    if (bytes < (4ull << 20)) return TC_OK;                // too small to tell anything: keep the setting
+    hipEvent_t e0, e1;
+    HIP_TRY(c, hipEventCreate(&e0));
+    HIP_TRY(c, hipEventCreate(&e1));
+    const uint32_t candidates[] = {8, 10, 12, 14, 16, 20, 24};
+    float best_ms = 1e30f;
+    uint32_t best = c->mover_wgs;
+    int rc = TC_OK;
+    for (uint32_t wg : candidates) {
+        float ms_min = 1e30f;
+        for (int rep = 0; rep < 3 && rc == TC_OK; ++rep) {   // the first is a warm-up
+            TcMoverArgs a{};
+            a.chunk_bytes = c->chunk_bytes;
+            a.tickets = c->tickets;
+            a.xcc = c->mover_xcc;
+            a.n_xcd = c->mover_xcds;
+            const uint64_t per = (bytes / 4) & ~(uint64_t)4095;
+            for (uint32_t u = 0; u < 4; ++u) {              // out: HBM -> pinned; in: the pinned half behind it -> HBM
+                TcUnit &U = a.u[a.n_units++];
+                U.out_src = c->hbm + u * per;
+                U.out_dst = c->pinned + u * per;
+                U.in_src = c->pinned + bytes + u * per;
+                U.in_dst = c->hbm + u * per;
+                U.bytes = per;
+                U.chunk0 = a.n_chunks;
+                a.n_chunks += (per + a.chunk_bytes - 1) / a.chunk_bytes;
+            }
+            hipError_t e = hipEventRecord(e0, c->streams[S_K]);
+            if (e == hipSuccess) e = tc_launch_mover(a, wg, c->streams[S_K], &c->k_launches);
+            if (e == hipSuccess) e = hipEventRecord(e1, c->streams[S_K]);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+            float ms = 0;
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+            if (e != hipSuccess) { rc = fail(c, TC_E_HIP, hipGetErrorString(e)); break; }
+            if (rep > 0) ms_min = std::min(ms_min, ms);
+        }
+        if (rc != TC_OK) break;
+        if (ms_min < best_ms) { best_ms = ms_min; best = wg; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != TC_OK) return rc;
+    c->mover_wgs = best;
+    if (workgroups_out) *workgroups_out = best;
     return TC_OK;
 }
 

@@ -203,6 +203,7 @@ class ParamCache:
         tc.plan_pools(self.hbm_bytes, (host, 0), self.align)
         tc.plan_schedule()
         tc.bind_torch()
+        tc.tune_mover()                                   # the regions are still empty: measure the workgroup count
         for t, p in enumerate(self.params):
             tc.load_tensor(t, p.detach().cpu().contiguous().view(torch.uint8).numpy().reshape(-1))
             p.data = torch.empty(0, dtype=self._dtype[t], device=p.device)

@@ -176,11 +176,11 @@ def test_dma_engine_path_keeps_every_byte(threshold, tmp_path):
 def test_gpt_1p3b_config_full_size_sampled_bytes():
     # configuration 2 at full size in the launch configuration bench.py times: 1544
     # tensors, 19.95 GiB (17 GiB pinned, 3 GiB HBM), windows of 64 steps, launches merged up
-    # to 1 GiB, twelve workgroups on one XCD taking 16 KiB chunks (the defaults).
+    # to 1 GiB, the measured number of workgroups on one XCD taking 16 KiB chunks.
     # Schedule, counters and final maps are compared in full; bytes on a sample of
     # tensors the oracle rebuilds one by one (smallest, largest, every kind, stamped ones).
     wl = W.config(1)
-    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30)
+    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30, tune=True)
     kinds = wl.tensor_kind
     order = np.argsort(wl.tensor_bytes, kind="stable")
     sample = set(order[:6].tolist()) | set(order[-6:].tolist())
@@ -211,7 +211,7 @@ def test_llama_7b_config_full_size_sampled_bytes():
     # configuration 3 at full size: 1525 tensors, 100.4 GiB (40 GiB HBM cache, 60.6 GiB pinned),
     # three iterations replayed from the profile of the first, 363 GiB moved each way
     wl = W.config(2)
-    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30)
+    tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30, tune=True)
     from oracle import tc_oracle as o
     r0 = o.replay_workload(wl)
     r = check_against_oracle(wl, tc, tensors=_sample(wl, r0, per_kind=3, extremes=3))
@@ -231,7 +231,7 @@ def test_file_tier_configs_at_two_layers_full_bytes(index, tmp_path):
     wl = W.config(index, layers=2)
     big = int(wl.tensor_bytes.max())
     tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30, file_path=_tmpfile(tmp_path),
-                     staging_bytes=16 * ((big + 4095) // 4096 * 4096), stripes=4)
+                     staging_bytes=16 * ((big + 4095) // 4096 * 4096), stripes=4, tune=True)
     from oracle import tc_oracle as o
     r0 = o.replay_workload(wl)
     small = [t for t in range(wl.n_tensors) if wl.tensor_bytes[t] < (1 << 20)]
@@ -341,6 +341,33 @@ def test_deciding_ahead_of_the_hooks_changes_nothing(ahead, tmp_path):
     assert r.misses > 0
     for t in range(wl.n_tensors):
         assert np.array_equal(tc.read_tensor(t), r.read_tensor(t)), t
+    tc.close()
+
+
+def test_tuning_the_mover_measures_on_empty_regions_only():
+    # tc_tune_mover times exchanges between the bound regions: allowed while they hold nothing,
+    # refused afterwards; whatever it picks, the replay that follows equals the oracle
+    wl = W.config(0, layers=8)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch()
+    wg = tc.tune_mover()
+    assert wg in (8, 10, 12, 14, 16, 20, 24)
+    for t in range(wl.n_tensors):
+        tc.load_tensor(t, W.workload_payload(wl, t))
+    with pytest.raises(T.TcError) as e:
+        tc.tune_mover()
+    assert e.value.code == -2                       # TC_E_STATE
+    cs = torch.cuda.Stream()
+    for steps in wl.iterations:
+        tc.replay_iteration_c(steps, cs.cuda_stream)
+    tc.synchronize()
+    check_against_oracle(wl, tc)
+    tc.close()
+    # regions too small to tell anything: the setting stays
+    small = W.example_cpu_gpu()
+    tc = T.TensorCache.from_workload(small)
+    tc.bind_torch()
+    assert tc.tune_mover() == 12
     tc.close()
 
 
