@@ -119,12 +119,27 @@ def main():
         dt = timed(lambda: T.copy_batch(off + np.uint64(src), off + np.uint64(dst), nb, st.cuda_stream, wg, chunk))
         return float(nb.sum()) / dt / 1e9
 
-    print("\nbatched kernel, one launch of up to 48 units (GB/s per direction):")
-    print(f"{'unit':>10} {'units':>6} {'H2D only':>10} {'D2H only':>10} {'exchange':>10}")
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipMemcpyAsync.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+
+    def dma(size, h2d):
+        """The same units as one hipMemcpyAsync each, back to back on one stream."""
+        off, nb = units(size)
+        src, dst, kind = (P, H, 1) if h2d else (H, P, 2)
+
+        def fn():
+            for o, n in zip(off.tolist(), nb.tolist()):
+                assert hip.hipMemcpyAsync(dst + o, src + o, n, kind, st.cuda_stream) == 0
+        return float(nb.sum()) / timed(fn) / 1e9
+
+    print("\nup to 48 units of one size: one launch of the batched kernel against one hipMemcpyAsync per unit"
+          "\n(GB/s per direction):")
+    print(f"{'unit':>10} {'units':>6} {'H2D only':>10} {'D2H only':>10} {'exchange':>10} {'DMA H2D':>10} {'DMA D2H':>10}")
     for size in (64 << 10, 1 * M, 4 * M, 16 * M, 64 * M, 256 * M, G):
         n = max(1, min(48, G // size))
-        print(f"{size >> 10:>8}Ki {n:>6} {oneway(size, True):>10.2f} {oneway(size, False):>10.2f} {exchange(size):>10.2f}",
-              flush=True)
+        print(f"{size >> 10:>8}Ki {n:>6} {oneway(size, True):>10.2f} {oneway(size, False):>10.2f} {exchange(size):>10.2f}"
+              f" {dma(size, True):>10.2f} {dma(size, False):>10.2f}", flush=True)
 
     print("\nexchange, one launch of 4 units, by bytes per direction (GB/s per direction; the call's own"
           "\nstream-ordered allocation of the ticket counters is inside the time):")
