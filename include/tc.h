@@ -77,6 +77,7 @@ extern "C" {
 /* tc_bind_memory flags */
 #define TC_BIND_NULL_MOVER 1u        /* decide and log only; no region needed, no byte moves */
 #define TC_BIND_FILE_DIRECT 2u       /* file_fd was opened with O_DIRECT: all file I/O is 4 KiB aligned */
+#define TC_BIND_HOST_TIER 4u         /* two tiers, host memory over the file: see tc_bind_memory */
 
 typedef struct tc_ctx tc_ctx;        /* opaque, library-owned */
 
@@ -225,7 +226,23 @@ int tc_plan_schedule(tc_ctx *ctx, tc_placement *out);
  *                  (TC_E_IO) by the next call that queues or waits for one.
  *   migrate_stream hipStream_t the copies are issued on (default priority)
  * With TC_BIND_NULL_MOVER no bytes move and the regions may be NULL: the
- * decision kernel still runs and the op log, stats and state are exact. */
+ * decision kernel still runs and the op log, stats and state are exact.
+ *
+ * With TC_BIND_HOST_TIER the cache is the one the paper keeps for optimizer
+ * states (Sec. 3.4.2, optimizer states scheduling policy): the fast tier is
+ * host memory, the slow tier the file, and the same scheduler evicts an
+ * updated state and prefetches the next one behind the CPU's update.  The plan
+ * must have been made with both host budgets 0 (the budget called hbm_bytes is
+ * then the host cache's); hbm_region must be pinned HOST memory of
+ * plan.hbm_total bytes; pinned_region and staging are not used (staging only
+ * by tc_fill_payload).  Tensors move between the region and the file directly,
+ * by the I/O worker threads: no copy kernel runs.  A write-back waits for what
+ * the compute stream holds at the POST call, a fetch for what it holds when
+ * the fetch is decided; a PRE call returns host pointers once the tensors'
+ * bytes have arrived, and the time it had to block is the stall that
+ * tc_cache_stats reports (bytes_h2d counts the bytes fetched into the host
+ * cache).  Decisions, op log and state are those of the three-tier mode with
+ * no host buffers. */
 int tc_bind_memory(tc_ctx *ctx, void *hbm_region, uint64_t hbm_bytes,
                    void *pinned_region, uint64_t pinned_bytes,
                    void *staging, uint64_t staging_bytes,

@@ -18,6 +18,7 @@ LITERAL_ALG2 = 1
 NO_PREFETCH = 2
 BIND_NULL_MOVER = 1
 BIND_FILE_DIRECT = 2
+BIND_HOST_TIER = 4
 NONE = 0xFFFFFFFF
 MAX_STEP_TENSORS = 16
 
@@ -266,17 +267,23 @@ class TensorCache:
                                          staging_ptr or None, staging_bytes, file_fd, migrate_stream or None, flags))
 
     def bind_torch(self, *, staging_bytes: int = 0, file_path: Optional[str] = None, null_mover: bool = False,
-                   stream=None, direct: bool = False, file_fd: Optional[int] = None, stripes: int = 1):
+                   stream=None, direct: bool = False, file_fd: Optional[int] = None, stripes: int = 1,
+                   host_tier: bool = False):
         """Allocates the regions and binds them: device memory and the streams
         come from PyTorch, the pinned regions straight from hipHostMalloc
         (PyTorch's pinned allocator rounds every request up to a power of two,
-        which for a 60 GiB pool locks 64 GiB)."""
+        which for a 60 GiB pool locks 64 GiB).  host_tier: the two-tier mode, the
+        fast tier a pinned host region (self.hbm then is that region)."""
         import torch
+        mode = BIND_HOST_TIER if host_tier else 0
         if null_mover:
-            self.bind_memory(0, 0, 0, 0, 0, 0, -1, 0, BIND_NULL_MOVER)
+            self.bind_memory(0, 0, 0, 0, 0, 0, -1, 0, BIND_NULL_MOVER | mode)
             return
         dev = torch.device("cuda:0")
-        hbm = torch.empty(max(256, int(self.plan.hbm_total)), dtype=torch.uint8, device=dev)
+        if host_tier:
+            hbm = _PinnedRegion(max(4096, int(self.plan.hbm_total)))
+        else:
+            hbm = torch.empty(max(256, int(self.plan.hbm_total)), dtype=torch.uint8, device=dev)
         pinned = _PinnedRegion(max(4096, int(self.plan.host_total)))
         if direct:
             staging_bytes = (int(staging_bytes) + 4095) // 4096 * 4096
@@ -291,9 +298,9 @@ class TensorCache:
         self._fd = fd
         self._keep = [hbm, pinned, staging, self.mstream]
         self.hbm, self.pinned, self.staging = hbm, pinned, staging
-        self.bind_memory(hbm.data_ptr(), hbm.numel(), pinned.data_ptr(), pinned.nbytes,
+        self.bind_memory(hbm.data_ptr(), hbm.nbytes if host_tier else hbm.numel(), pinned.data_ptr(), pinned.nbytes,
                          staging.data_ptr(), int(staging_bytes), fd, self.mstream.cuda_stream,
-                         BIND_FILE_DIRECT if (direct and fd >= 0) else 0)
+                         (BIND_FILE_DIRECT if (direct and fd >= 0) else 0) | mode)
         # further files the tier is striped over: file_path.1, file_path.2, ...
         self._stripe_fds = []
         for k in range(1, int(stripes) if file_path is not None and file_fd is None else 1):

@@ -29,9 +29,18 @@ const uint32_t OP_RING = 1024;          // events kept for the most recent copy 
 // writer and the reader.  One request therefore spreads over the workers, while
 // every chunk always goes to the same writer, and a worker works in order: two
 // writes of one extent land in the order they were issued.  A read of an extent
-// is queued only once the write queued for it has finished.  A write job may
-// carry an event to wait for (bytes a copy is still producing).
+// names the write queued for it and starts once that has finished (the reader
+// waits, not the hook thread).  A write job may carry an event to wait for
+// (bytes a copy is still producing).
 const uint32_t IO_MAX_THREADS = 8, IO_MAX_FILES = 8;
+
+enum { IO_WRITERS = 0, IO_READERS = 1 };
+
+struct JobSet {             // the jobs of one request: per worker the newest of them (0: none)
+    uint8_t pool = IO_WRITERS;
+    bool any = false;
+    uint64_t seq[IO_MAX_THREADS] = {};
+};
 
 struct IoJob {
     uint64_t seq;
@@ -40,6 +49,7 @@ struct IoJob {
     uint64_t bytes, off;
     int fd;
     bool read;
+    JobSet after;           // writes (writer pool) that must have finished before this job starts
 };
 
 struct IoWorker {
@@ -51,14 +61,6 @@ struct IoWorker {
     std::atomic<uint64_t> done{0};      // stored under mu, polled without
     bool quit = false;                  // under mu
     uint8_t *bounce = nullptr;          // O_DIRECT: page-aligned block of its own
-};
-
-enum { IO_WRITERS = 0, IO_READERS = 1 };
-
-struct JobSet {             // the jobs of one request: per worker the newest of them (0: none)
-    uint8_t pool = IO_WRITERS;
-    bool any = false;
-    uint64_t seq[IO_MAX_THREADS] = {};
 };
 
 struct StBlock {            // live piece of the staging ring
@@ -173,6 +175,9 @@ struct tc_ctx {
     std::deque<std::pair<hipEvent_t, JobSet>> ev_busy;  // events the queued jobs of a request wait for
     std::vector<JobSet> tensor_job;     // per tensor: newest queued write of its extent
     std::vector<JobSet> cpu_job;        // per host buffer: queued write that reads it
+    bool host_tier = false;             // two-tier mode: the fast tier is host memory, filled and drained by file I/O
+    std::vector<JobSet> fast_read;      // two-tier mode, per fast-tier buffer: the read that fills it
+    std::vector<JobSet> fast_write;     // ... and the write that drains it
     std::atomic<uint64_t> wr_ns{0}, rd_ns{0};   // time the workers spent in pwrite / pread
     std::mutex io_mu;
     std::string io_err;                 // first failure of a writer (under io_mu)
@@ -223,5 +228,9 @@ int io_check(tc_ctx *c);                       // a worker's failure, as TC_E_IO
 bool io_done(tc_ctx *c, const JobSet &r);
 int io_wait(tc_ctx *c, JobSet &r);             // wait for the jobs of one request, then forget them
 int io_wait_all(tc_ctx *c);
-int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set);
+// after: writes that must have finished before the request starts (may be nullptr)
+int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set,
+              const JobSet *after = nullptr);
+int io_submit_behind(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, bool behind, hipStream_t stream, JobSet *set,
+                     const JobSet *after = nullptr);
 int io_transfer(tc_ctx *c, uint32_t t, uint8_t *mem, bool read);

@@ -38,6 +38,20 @@ static bool pread_all(int fd, uint8_t *dst, uint64_t bytes, uint64_t want, uint6
     return true;
 }
 
+// block until the writes of `after` have finished (called by workers: a dependency was always
+// queued before the job that names it, and workers take their jobs in order, so this ends)
+static void io_wait_writes(tc_ctx *c, const JobSet &after)
+{
+    if (!after.any) return;
+    const auto &pool = c->io[IO_WRITERS];
+    for (size_t wi = 0; wi < pool.size(); ++wi) {
+        if (!after.seq[wi] || pool[wi]->done.load() >= after.seq[wi]) continue;
+        IoWorker &w = *pool[wi];
+        std::unique_lock<std::mutex> lk(w.mu);
+        w.cv_done.wait(lk, [&] { return w.done.load() >= after.seq[wi]; });
+    }
+}
+
 // one job, by a worker thread (w) or by the calling thread (w == nullptr).
 // O_DIRECT cannot target memory the GPU driver has mapped (pread into a pinned
 // region fails with EFAULT on this kernel), so in that mode every request goes
@@ -45,9 +59,10 @@ static bool pread_all(int fd, uint8_t *dst, uint64_t bytes, uint64_t want, uint6
 static void io_run_job(tc_ctx *c, IoWorker *w, const IoJob &j)
 {
     std::string err;
+    io_wait_writes(c, j.after);
     if (j.ev) {
         hipError_t e = hipEventSynchronize(j.ev);
-        if (e != hipSuccess) err = std::string("hipEventSynchronize (file write): ") + hipGetErrorString(e);
+        if (e != hipSuccess) err = std::string("hipEventSynchronize (file tier): ") + hipGetErrorString(e);
     }
     if (err.empty()) {
         const auto t0 = std::chrono::steady_clock::now();
@@ -160,6 +175,8 @@ void io_stop(tc_ctx *c)
     }
     for (JobSet &r : c->tensor_job) r = JobSet{};
     for (JobSet &r : c->cpu_job) r = JobSet{};
+    for (JobSet &r : c->fast_read) r = JobSet{};
+    for (JobSet &r : c->fast_write) r = JobSet{};
     for (StBlock &b : c->st_q) b.job = JobSet{};
     for (PUnit &p : c->deferred) p.read_job = JobSet{};
 }
@@ -191,20 +208,44 @@ int io_start(tc_ctx *c)
 // tensor t's extent: a write from `mem` or a read into it.  op != 0: the bytes
 // to write are being produced by copy operation `op`, issued on stream S a
 // moment ago.  `set` names the queued jobs.
-int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set)
+int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set, const JobSet *after)
+{
+    if (op && c->io[read ? IO_READERS : IO_WRITERS].empty()) {
+        int rc = tc_wait_op(c, op);
+        if (rc != TC_OK) return rc;
+        op = 0;
+    }
+    return io_submit_behind(c, t, mem, read, op != 0, c->streams[S], set, after);
+}
+
+// The same with the stream named: behind != 0 makes the jobs wait for everything
+// queued on `stream` so far (work that still produces the bytes to write, or
+// still uses the memory to read into).
+int io_submit_behind(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, bool behind, hipStream_t stream, JobSet *set,
+                     const JobSet *after)
 {
     *set = JobSet{};
     set->pool = read ? IO_READERS : IO_WRITERS;
     if (c->n_files == 0) return fail(c, TC_E_IO, "an op needs the file tier but no file is bound");
     int rc = io_check(c);
-    if (rc == TC_OK && read) rc = io_wait(c, c->tensor_job[t]);    // a queued write of this very extent goes first
     if (rc != TC_OK) return rc;
+    // what has to be in the file or out of the buffer first: a queued write of this very
+    // extent (for a read), and whatever the caller names
+    JobSet dep;
+    if (read && c->tensor_job[t].any && !io_done(c, c->tensor_job[t])) dep = c->tensor_job[t];
+    if (after && after->any && after->pool == IO_WRITERS && !io_done(c, *after)) {
+        dep.any = true;
+        for (uint32_t w = 0; w < IO_MAX_THREADS; ++w) dep.seq[w] = std::max(dep.seq[w], after->seq[w]);
+    }
     c->io_begun = true;
     auto &pool = c->io[set->pool];
-    if (pool.empty() && (rc = tc_wait_op(c, op)) != TC_OK) return rc;
+    if (behind && pool.empty()) {
+        HIP_TRY(c, hipStreamSynchronize(stream));
+        behind = false;
+    }
     const uint64_t n = c->prof.bytes[t], base = c->place.file_off[t];
     hipEvent_t ev = nullptr;
-    if (op && !pool.empty()) {
+    if (behind) {
         // one event for the whole request, recorded right behind the copy
         while (!c->ev_busy.empty() && io_done(c, c->ev_busy.front().second)) {
             c->ev_free.push_back(c->ev_busy.front().first);
@@ -216,15 +257,15 @@ int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S
             ev = c->ev_free.back();
             c->ev_free.pop_back();
         }
-        hipError_t e = hipEventRecord(ev, c->streams[S]);
+        hipError_t e = hipEventRecord(ev, stream);
         if (e != hipSuccess) {
             c->ev_free.push_back(ev);
-            return fail(c, TC_E_HIP, std::string("hipEventRecord (file write): ") + hipGetErrorString(e));
+            return fail(c, TC_E_HIP, std::string("hipEventRecord (file tier): ") + hipGetErrorString(e));
         }
     }
     uint64_t lane = t;
     for (uint64_t o = 0; o < n; o += c->io_chunk, ++lane) {
-        IoJob j{0, ev, mem + o, std::min(c->io_chunk, n - o), base + o, c->fds[lane % c->n_files], read};
+        IoJob j{0, ev, mem + o, std::min(c->io_chunk, n - o), base + o, c->fds[lane % c->n_files], read, dep};
         if (pool.empty()) {
             io_run_job(c, nullptr, j);
             continue;

@@ -158,6 +158,18 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     const bool direct = (flags & TC_BIND_FILE_DIRECT) != 0 && fd >= 0 && !null_mover;
     if (direct && ((((uintptr_t)staging) & 4095) || (staging_bytes & 4095)))
         return fail(c, TC_E_ARG, "with TC_BIND_FILE_DIRECT the staging region must be 4 KiB aligned and sized");
+    const bool host_tier = (flags & TC_BIND_HOST_TIER) != 0;
+    if (host_tier) {
+        if (c->pools.host_total || c->pools.cpu_slots)
+            return fail(c, TC_E_ARG, "TC_BIND_HOST_TIER needs a plan made with both host budgets 0");
+        if (!null_mover && hbm) {
+            hipPointerAttribute_t at{};
+            if (hipPointerGetAttributes(&at, hbm) != hipSuccess || at.type != hipMemoryTypeHost) {
+                (void)hipGetLastError();
+                return fail(c, TC_E_ARG, "TC_BIND_HOST_TIER: the fast-tier region must be pinned host memory");
+            }
+        }
+    }
     if (!null_mover) {
         if (c->pools.hbm_total && (!hbm || hbm_bytes < c->pools.hbm_total))
             return fail(c, TC_E_CAPACITY, "HBM region smaller than the plan");
@@ -282,6 +294,9 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->cpu_pending.assign(pl.cpu_slots, 0);
     c->tensor_job.assign(n_t, JobSet{});
     c->cpu_job.assign(pl.cpu_slots, JobSet{});
+    c->host_tier = host_tier;
+    c->fast_read.assign(host_tier ? pl.gpu_slots : 0, JobSet{});
+    c->fast_write.assign(host_tier ? pl.gpu_slots : 0, JobSet{});
     e = hipGetDevice(&c->device);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     if (fd >= 0 && !null_mover) {
@@ -651,6 +666,41 @@ static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, h
     }
 }
 
+// Two-tier mode (Sec. 3.4.2, optimizer states): the fast tier is host memory and a
+// tensor moves between its buffer and its file extent directly, by the I/O workers:
+// no copy kernel, no staging, nothing deferred.
+static int dispatch_host_tier(tc_ctx *c, const TcOpRec &r, uint32_t t, uint32_t s, hipStream_t compute)
+{
+    switch (r.op) {
+    case TC_OP_WRITEBACK: {
+        const uint32_t y = c->pools.gpu_base[s] + r.src_slot;
+        // a tensor is written back only after a module has used it, so the read that filled
+        // the buffer has long finished; the wait guards the order all the same
+        int rc = io_wait(c, c->fast_read[y]);
+        if (rc != TC_OK) return rc;
+        // the update may still be running on the compute stream: the writer waits for it
+        return io_submit_behind(c, t, gpu_addr(c, s, r.src_slot), false, true, compute, &c->fast_write[y]);
+    }
+    case TC_OP_DEMAND:
+    case TC_OP_PREFETCH: {
+        if (r.src_tier != TC_NVME) return fail(c, TC_E_HIP, "two-tier mode: a fetch from a host buffer");
+        const uint32_t y = c->pools.gpu_base[s] + r.dst_slot;
+        // an earlier read into the same buffer (of a tensor dropped before its use)
+        int rc = io_wait(c, c->fast_read[y]);
+        if (rc != TC_OK) return rc;
+        // the reader starts once the buffer's last tensor is in the file and the compute
+        // stream is done with whatever it held
+        return io_submit_behind(c, t, gpu_addr(c, s, r.dst_slot), true, true, compute, &c->fast_read[y],
+                                &c->fast_write[y]);
+    }
+    case TC_OP_RELEASE:
+    case TC_OP_FAIL:
+        return TC_OK;
+    default:
+        return fail(c, TC_E_HIP, "two-tier mode: an op that needs host buffers");
+    }
+}
+
 static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step, int phase,
                     hipStream_t compute)
 {
@@ -700,6 +750,11 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
         default: break;
         }
         if (c->null_mover) continue;
+        if (c->host_tier) {
+            int rc = dispatch_host_tier(c, r, t, s, compute);
+            if (rc != TC_OK) return rc;
+            continue;
+        }
         switch (r.op) {
         case TC_OP_SPILL: {
             // host buffer -> file extent, now: the buffer is about to be reused
@@ -970,7 +1025,9 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
         }
     std::chrono::steady_clock::time_point t0;
     uint64_t waited_ns = 0;
-    if (c->measure_stall && !c->null_mover) {
+    if (c->host_tier && !c->null_mover) {
+        t0 = std::chrono::steady_clock::now();             // the host blocks for every fetch: always timed
+    } else if (c->measure_stall && !c->null_mover) {
         // wait time as the paper measures it (Sec. 4.2.2): once the modules queued so
         // far have finished, how long until each tensor of this one is in its buffer
         HIP_TRY(c, hipStreamSynchronize(compute));
@@ -985,8 +1042,9 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
                 ptr = gpu_addr(c, s, o->slots[i]);
                 // the module's kernels wait only for the copies that fill ITS buffers
                 const uint64_t ticket = c->gpu_ticket[c->pools.gpu_base[s] + o->slots[i]];
-                if (c->measure_stall) {
-                    int rc = wait_op(c, ticket);
+                if (c->host_tier || c->measure_stall) {
+                    int rc = c->host_tier ? io_wait(c, c->fast_read[c->pools.gpu_base[s] + o->slots[i]])
+                                          : wait_op(c, ticket);
                     if (rc != TC_OK) return rc;
                     const uint64_t ns = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
                                             std::chrono::steady_clock::now() - t0).count();
@@ -1264,7 +1322,8 @@ extern "C" int tc_load_tensor(tc_ctx *c, uint32_t t, const void *src)
     if (rc != TC_OK) return rc;
     const uint32_t s = c->prof.class_of[t];
     const uint64_t n = c->prof.bytes[t];
-    if (tier == TC_GPU) HIP_TRY(c, hipMemcpy(gpu_addr(c, s, gs), src, n, hipMemcpyHostToDevice));
+    if (tier == TC_GPU && c->host_tier) memcpy(gpu_addr(c, s, gs), src, n);
+    else if (tier == TC_GPU) HIP_TRY(c, hipMemcpy(gpu_addr(c, s, gs), src, n, hipMemcpyHostToDevice));
     else if (tier == TC_CPU) memcpy(cpu_addr(c, s, cs), src, n);
     else return io_transfer(c, t, const_cast<uint8_t *>((const uint8_t *)src), false);
     return TC_OK;
@@ -1283,7 +1342,8 @@ extern "C" int tc_read_tensor(tc_ctx *c, uint32_t t, void *dst)
     if (rc != TC_OK) return rc;
     const uint32_t s = c->prof.class_of[t];
     const uint64_t n = c->prof.bytes[t];
-    if (tier == TC_GPU) HIP_TRY(c, hipMemcpy(dst, gpu_addr(c, s, gs), n, hipMemcpyDeviceToHost));
+    if (tier == TC_GPU && c->host_tier) memcpy(dst, gpu_addr(c, s, gs), n);
+    else if (tier == TC_GPU) HIP_TRY(c, hipMemcpy(dst, gpu_addr(c, s, gs), n, hipMemcpyDeviceToHost));
     else if (tier == TC_CPU) memcpy(dst, cpu_addr(c, s, cs), n);
     else return io_transfer(c, t, (uint8_t *)dst, true);
     return TC_OK;
@@ -1336,6 +1396,10 @@ extern "C" int tc_tune_mover(tc_ctx *c, uint32_t *workgroups_out)
     if (!c) return TC_E_ARG;
     if (c->stage != 4 || c->null_mover) return fail(c, TC_E_STATE, "needs bound memory");
     if (c->in_use) return fail(c, TC_E_STATE, "the regions already hold tensors");
+    if (c->host_tier) {                                     // no copy kernel runs in the two-tier mode
+        if (workgroups_out) *workgroups_out = c->mover_wgs;
+        return TC_OK;
+    }
     uint64_t bytes = std::min<uint64_t>(64ull << 20, std::min(c->hbm_bytes, c->pinned_bytes / 2));
     bytes &= ~(uint64_t)65535;
     if (workgroups_out) *workgroups_out = c->mover_wgs;

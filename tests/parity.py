@@ -27,17 +27,18 @@ def compare_logs(got, want):
 
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
                 busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False, direct=False,
-                io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False):
+                io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False):
     """Replays every iteration of wl through the library; returns the context.
 
     window None: one tc_migrate_step call per hook (the hook-driven interface);
     otherwise tc_replay_iteration with that many steps per decision launch.
     fill: the library's fill kernel writes the payload pattern instead of
-    tc_load_tensor (for footprints too large to generate on the host)."""
+    tc_load_tensor (for footprints too large to generate on the host).
+    host_tier: the two-tier mode (the fast tier is pinned host memory)."""
     import torch
     tc = T.TensorCache.from_workload(wl)
     tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes, direct=direct,
-                  stripes=stripes)
+                  stripes=stripes, host_tier=host_tier)
     if tune and not null_mover:
         tc.tune_mover()                            # as bench.py does: the workgroup count is measured
     if ahead is not None:

@@ -534,3 +534,65 @@ def test_random_settings_keep_the_schedule_and_every_byte(seed, tmp_path):
     r = check_against_oracle(wl, tc)
     assert len(r.log) > 100
     tc.close()
+
+
+# ----------------------------------------------------------------------------
+# two tiers: host cache over the file (optimizer states, Sec. 3.4.2)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("window", [None, 16])
+@pytest.mark.parametrize("n,k", [(8, 5), (8, 3), (40, 1), (6, 6)])
+def test_two_tier_sweep_of_equal_tensors(n, k, window, tmp_path):
+    wl = W.single_class_sweep(n, k, size=5120, n_iterations=3)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), host_tier=True, window=window)
+    r = check_against_oracle(wl, tc)
+    assert r.bytes_d2h == 0 and r.misses == 0
+    assert r.bytes_file_write == 3 * ((n - k) + min(k, n - k)) * 5120
+    tc.close()
+
+
+@pytest.mark.parametrize("threads,stripes,chunk", [((4, 4), 1, None), ((0, 0), 1, None), ((1, 3), 3, 1 << 16),
+                                                   ((3, 0), 2, 1 << 16), ((0, 2), 1, 1 << 17)])
+def test_two_tier_optimizer_sweep(threads, stripes, chunk, tmp_path):
+    # state tensors of several chunks, a fast tier of 40 % of the states: every updated
+    # tensor goes straight from its host buffer to the file and the next one straight in,
+    # whatever the worker threads; the reader of a buffer waits for the writer that drains it
+    wl = W.optimizer_sweep("opt_small", layers=3, hidden=128, ffn=344, vocab=3000, cache_frac=0.4, n_iterations=3)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), host_tier=True, io_writers=threads, stripes=stripes,
+                     io_chunk=chunk, window=(None if stripes == 1 else 8))
+    r = check_against_oracle(wl, tc)
+    assert r.misses == 0 and r.bytes_file_write > wl.total_bytes() and r.bytes_d2h == 0
+    st = tc.cache_stats()
+    assert st["waits_total"] == 3 * 3 * len(wl.profile)        # every fetch of a PRE call is waited for on the host
+    tc.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_two_tier_random_traces(seed, tmp_path):
+    # irregular traces (tensors dropped unused, re-fetched, several per step, read-only
+    # accesses that release without a write-back), with and without prefetching
+    wl = W.random_workload(seed + 40, n_tensors=60, n_steps=90, hbm_frac=0.1, host_frac=0.0, n_iterations=3,
+                           perturb_one_in=(7 if seed % 2 else 0),
+                           sizes=(512, 4096, 100, 33000, (1 << 17) + 24))
+    wl.no_prefetch = seed == 5
+    assert wl.host_bytes == (0, 0)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), host_tier=True, window=(None if seed < 3 else 4),
+                     io_chunk=1 << 16, ahead=(None if seed != 2 else 0))
+    r = check_against_oracle(wl, tc)
+    assert r.bytes_file_read > 0 and r.bytes_d2h == 0
+    tc.close()
+
+
+def test_two_tier_mode_wants_a_plan_without_host_buffers_and_host_memory(tmp_path):
+    import torch
+    wl = _random(3)                                     # has host budgets
+    tc = T.TensorCache.from_workload(wl)
+    with pytest.raises(T.TcError, match="host budgets 0"):
+        tc.bind_torch(file_path=_tmpfile(tmp_path), host_tier=True)
+    tc.close()
+    wl = W.single_class_sweep(8, 5)
+    tc = T.TensorCache.from_workload(wl)
+    dev = torch.empty(1 << 16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(T.TcError, match="pinned host memory"):
+        tc.bind_memory(dev.data_ptr(), dev.numel(), 0, 0, 0, 0, -1, 0, T.BIND_HOST_TIER)
+    tc.close()

@@ -297,6 +297,50 @@ def test_single_class_closed_form(n, k):
 
 
 # ----------------------------------------------------------------------------
+# two tiers, one sweep: the optimizer-state policy of Sec. 3.4.2
+# ----------------------------------------------------------------------------
+
+def test_optimizer_state_example_evicts_the_updated_tensor_and_prefetches_the_next():
+    # the figure of the optimizer states scheduling policy: states of T1..T5 start in the CPU
+    # cache, T6..T8 on NVMe; once T1's update is complete it is evicted and T6 is prefetched
+    wl = W.single_class_sweep(8, 5)
+    r = o.replay_workload(wl, check=check_state)
+    assert [t for t in range(8) if r.pl.final[t] == o.GPU] == [0, 1, 2, 3, 4]
+    assert [t for t in range(8) if r.pl.final[t] == o.NVME] == [5, 6, 7]
+    first = [e for e in r.log if e[1] == 0]
+    assert [(o.OP_NAMES[e[3]], e[4] + 1, e[2]) for e in first] == [("WRITEBACK", 1, o.POST), ("PREFETCH", 6, o.POST)]
+    assert first[0][7] == o.NVME and first[1][5] == o.NVME          # updated state goes to the file, T6 comes from it
+    assert first[1][8] == first[0][6]                                # into the buffer T1 left
+    # T2 -> T7, T3 -> T8, then nothing is left to prefetch and nothing more is evicted
+    sweep = [(o.OP_NAMES[e[3]], e[4] + 1) for e in r.log if e[1] < 8 and e[2] != o.END]
+    assert sweep == [("WRITEBACK", 1), ("PREFETCH", 6), ("WRITEBACK", 2), ("PREFETCH", 7),
+                     ("WRITEBACK", 3), ("PREFETCH", 8)]
+    assert r.misses == 0 and r.hits == 8
+
+
+@pytest.mark.parametrize("n,k", [(8, 5), (8, 3), (8, 4), (10, 1), (6, 6), (7, 2), (9, 8)])
+def test_optimizer_sweep_closed_form(n, k):
+    # Every access finds its tensor in the fast tier (the prefetch of the next absent tensor
+    # is issued n - k steps before its use).  During the sweep the first n - k updated tensors
+    # make room for the n - k absent ones; the end-of-iteration restore then returns the
+    # first k tensors, of which min(k, n - k) had left.  All evicted tensors are dirty.
+    size = 512
+    wl = W.single_class_sweep(n, k, size=size, n_iterations=3)
+    r = o.replay_workload(wl, check=check_state)
+    moved = (n - k) + min(k, n - k)
+    assert (r.hits, r.misses, r.fails) == (3 * n, 0, 0)
+    for it in range(3):
+        ops = [e for e in r.log if e[0] == it]
+        assert sum(1 for e in ops if e[3] == o.WRITEBACK) == moved
+        assert sum(1 for e in ops if e[3] == o.PREFETCH) == moved
+        assert all(e[3] in (o.WRITEBACK, o.PREFETCH) for e in ops)
+        in_sweep = [e for e in ops if e[2] != o.END]
+        assert len(in_sweep) == 2 * (n - k)
+    assert r.bytes_file_write == r.bytes_file_read == r.bytes_h2d == 3 * moved * size
+    assert r.bytes_d2h == 0
+
+
+# ----------------------------------------------------------------------------
 # brute force: fewest fetches over every possible eviction choice
 # ----------------------------------------------------------------------------
 

@@ -10,6 +10,6 @@ from .traces import (  # noqa: F401
     R, W, RW, GROUP_16, GROUP_32, Workload,
     config, config_names, gpt_shaped, llama_shaped, scaled_config,
     example_cpu_gpu, example_cpu_gpu_nvme, single_class_fwd_bwd,
-    random_workload, perturb_iteration, splitmix64,
+    random_workload, optimizer_sweep, single_class_sweep, perturb_iteration, splitmix64,
 )
 from .payload import payload_bytes, payload_words, gaussian_fp16_bytes, workload_payload, PAYLOAD_SEED  # noqa: F401

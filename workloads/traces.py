@@ -264,6 +264,34 @@ def llama_shaped(name: str, *, layers: int, hidden: int, ffn: int, vocab: int,
                      host_bytes=host_bytes, n_iterations=n_iterations, notes=notes)
 
 
+def optimizer_sweep(name: str, *, layers: int, hidden: int, ffn: int, vocab: int, cache_frac: float,
+                    n_iterations: int = 2, cpu_bytes_per_s: float = 20.0e9, notes="") -> Workload:
+    """The optimizer step on the CPU as a workload of its own (Sec. 3.4.2,
+    optimizer states scheduling policy): per parameter tensor of a
+    Llama-shaped model three fp32 state tensors (master copy, momentum,
+    variance; ids 3j, 3j+1, 3j+2), read and written by step j of a sweep over
+    the parameters.  Two tiers: `hbm_bytes` is the budget of the fast tier (the
+    CPU cache), cache_frac of all states; both host budgets are 0, so whatever
+    does not fit lives on the file tier.  compute_ns models the CPU's Adam
+    update as bound by memory traffic (28 bytes per element: gradient and three
+    states read, three states written) at cpu_bytes_per_s."""
+    h, f = hidden, ffn
+    elems: List[int] = [rows * h for rows in _vocab_shards(vocab)]
+    for _ in range(layers):
+        elems += [h, h * h, h * h, h * h, h * h, h, h * f, h * f, f * h]
+    elems += [h] + [rows * h for rows in _vocab_shards(vocab)]
+    n_p = len(elems)
+    tb = np.repeat(np.asarray(elems, dtype=np.uint64) * 4, 3)
+    kinds = np.tile(np.asarray([KIND_MASTER, KIND_M, KIND_V], dtype=np.uint8), n_p)
+    steps: List[Step] = [[(3 * j, RW), (3 * j + 1, RW), (3 * j + 2, RW)] for j in range(n_p)]
+    ns = np.asarray([int(28.0 * e / cpu_bytes_per_s * 1e9) for e in elems], dtype=np.uint64)
+    wl = Workload(name=name, tensor_bytes=tb, tensor_group=np.full(3 * n_p, GROUP_32, dtype=np.uint8),
+                  tensor_kind=kinds, profile=steps, compute_ns=ns,
+                  hbm_bytes=int(float(tb.sum()) * cache_frac), host_bytes=(0, 0), notes=notes)
+    wl.iterations = [steps for _ in range(n_iterations)]
+    return wl
+
+
 def _ample_host(wl: Workload):
     g = wl.tensor_group
     return (int(wl.tensor_bytes[g == 0].sum()) + (1 << 20), int(wl.tensor_bytes[g == 1].sum()) + (1 << 20))
@@ -353,6 +381,16 @@ def single_class_fwd_bwd(n: int, k_gpu: int, k_cpu: int, *, size: int = 512, n_i
     steps = [[(t, R)] for t in range(n)] + [[(t, rw_bwd)] for t in reversed(range(n))]
     return _simple(f"single{n}_{k_gpu}_{k_cpu}", [size] * n, [0] * n, steps,
                    hbm_bytes=k_gpu * size, host_bytes=(k_cpu * size, 0), n_iterations=n_iterations)
+
+
+def single_class_sweep(n: int, k_fast: int, *, size: int = 512, n_iterations: int = 1) -> Workload:
+    """n equal-size fp32 state tensors updated (read and written) one per step
+    in the order 0..n-1, a fast tier with room for exactly k_fast of them and
+    no host buffers below it: the optimizer-state example of Sec. 3.4.2 (its
+    figure has n = 8, k_fast = 5; ids here are the paper's minus 1)."""
+    steps = [[(t, RW)] for t in range(n)]
+    return _simple(f"sweep{n}_{k_fast}", [size] * n, [GROUP_32] * n, steps,
+                   hbm_bytes=k_fast * size, host_bytes=(0, 0), n_iterations=n_iterations)
 
 
 def example_cpu_gpu() -> Workload:
