@@ -122,6 +122,32 @@ def test_failed_background_write_is_reported(tmp_path):
         tc.close()
 
 
+def test_two_tier_mode_reports_failed_writes_and_short_reads(tmp_path):
+    # the host cache over the file: a write that fails in its writer thread (/dev/full) and a
+    # read beyond the end of a file that was cut short both come back as TC_E_IO, the read from
+    # the PRE call that waits for its bytes at the latest
+    wl = W.single_class_sweep(12, 4, size=1 << 16, n_iterations=1)
+    for threads in ((2, 2), (0, 0)):
+        tc = _planned(wl)
+        tc.bind_torch(file_fd=os.open("/dev/full", os.O_RDWR), host_tier=True)
+        tc.set_io_threads(*threads)
+        with pytest.raises(T.TcError) as e:
+            tc.replay_iteration(wl.iterations[0], 0)
+            tc.synchronize()
+        assert e.value.code == E_IO and "pwrite" in str(e.value)
+        tc.close()
+        path = os.path.join(str(tmp_path), f"short{threads[0]}.bin")
+        tc = _planned(wl)
+        tc.bind_torch(file_path=path, host_tier=True)
+        tc.set_io_threads(*threads)
+        os.truncate(path, 4096)                          # the extents of the absent tensors are gone
+        with pytest.raises(T.TcError) as e:
+            tc.replay_iteration(wl.iterations[0], 0)
+            tc.synchronize()
+        assert e.value.code == E_IO and "short file" in str(e.value)
+        tc.close()
+
+
 def test_null_mover_context_refuses_payload_calls():
     wl = W.example_cpu_gpu()
     tc = _planned(wl)
