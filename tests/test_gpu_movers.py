@@ -207,3 +207,63 @@ def test_movers_reject_bad_arguments():
     with pytest.raises(T.TcError):
         T.copy_batch(np.asarray([d.data_ptr()], dtype=np.uint64), np.asarray([d.data_ptr() + 32], dtype=np.uint64),
                      np.asarray([16], dtype=np.uint64), 0, 64, 1000)        # chunk not a multiple of 4096
+
+
+def _counter_bytes(n):
+    # n bytes of a 64-bit counter pattern on the device (every aligned 8 bytes differ)
+    words = torch.arange((n + 7) // 8, dtype=torch.int64, device="cuda:0") * 0x1E3779B97F4A7C15    # wraps
+    return words.view(torch.uint8)[:n]
+
+
+def test_copy_batch_segment_beyond_4_gib():
+    # one segment whose byte offsets pass 2^32 (and whose chunk count passes 2^18), next to small
+    # ones: offsets inside the kernel are 64-bit; the bytes behind each segment stay untouched
+    big = (1 << 32) + (3 << 20) + 4096 + 5
+    sizes = [4096, big, 70001]
+    off, at = [], 0
+    for n in sizes:
+        off.append(at)
+        at += (n + 255) // 256 * 256
+    src = _counter_bytes(at)
+    dst = torch.full((at,), 0xEE, dtype=torch.uint8, device="cuda:0")
+    o64 = np.asarray(off, dtype=np.uint64)
+    T.copy_batch(o64 + np.uint64(src.data_ptr()), o64 + np.uint64(dst.data_ptr()), np.asarray(sizes, dtype=np.uint64),
+                 torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for o, n in zip(off, sizes):
+        assert torch.equal(dst[o:o + n], src[o:o + n])
+        pad = (n + 255) // 256 * 256 - n
+        assert bool((dst[o + n:o + n + pad] == 0xEE).all())
+
+
+def test_pack_and_unpack_beyond_4_gib():
+    # a slab of more than 2^32 bytes: tile starts, slab offsets and piece addresses are 64-bit
+    rng = np.random.default_rng(9)
+    sizes = ((1 << 20) + 16 * rng.integers(0, 4096, size=4200)).astype(np.uint64)
+    sizes[7] += 5                                          # one ragged segment shifts the phase of all behind it
+    src_off = np.concatenate([[0], np.cumsum((sizes + 255) // 256 * 256)[:-1]]).astype(np.uint64)
+    slab_off = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.uint64)
+    total = int(sizes.sum())
+    assert total > (1 << 32)
+    src_total = int(src_off[-1] + sizes[-1])
+    src = _counter_bytes(src_total)
+    slab = torch.full((total,), 0xEE, dtype=torch.uint8, device="cuda:0")
+    ptrs = _dev((src_off + np.uint64(src.data_ptr())).astype(np.int64))
+    d_nb, d_off = _dev(sizes.astype(np.int64)), _dev(slab_off.astype(np.int64))
+    st = torch.cuda.current_stream().cuda_stream
+    d_index = torch.empty(T.pack_tiles(total), dtype=torch.int32, device="cuda:0")
+    T.pack_index(d_off.data_ptr(), len(sizes), total, d_index.data_ptr(), st)
+    T.pack(slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), total, st, d_index.data_ptr())
+    torch.cuda.synchronize()
+    for o, so, n in zip(src_off.tolist(), slab_off.tolist(), sizes.tolist()):
+        assert torch.equal(slab[so:so + n], src[o:o + n])
+    back = torch.full((src_total,), 0x55, dtype=torch.uint8, device="cuda:0")
+    ptrs2 = _dev((src_off + np.uint64(back.data_ptr())).astype(np.int64))
+    T.unpack(slab.data_ptr(), ptrs2.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), total, st, d_index.data_ptr())
+    torch.cuda.synchronize()
+    for i in list(range(0, len(sizes), 97)) + [7, 8, len(sizes) - 1]:
+        o, n = int(src_off[i]), int(sizes[i])
+        assert torch.equal(back[o:o + n], src[o:o + n])
+        pad = (n + 255) // 256 * 256 - n
+        if pad and i + 1 < len(sizes):
+            assert bool((back[o + n:o + n + pad] == 0x55).all())
