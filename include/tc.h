@@ -274,7 +274,9 @@ int tc_read_tensor(tc_ctx *ctx, uint32_t tensor, void *dst);
  *            prefetch table that is not resident.  The copies wait for the
  *            work already enqueued on compute_stream.
  * ids, rw: host arrays of n <= TC_MAX_STEP_TENSORS entries (rw may be NULL
- * for POST).  step indexes the profiled iteration.  Decisions are made by a
+ * for POST).  step indexes the profiled iteration, which ends with its last
+ * step that used a tensor (a call with n = 0 may name a later step: a module
+ * without tensors; it moves nothing).  Decisions are made by a
  * GPU kernel; the call returns once they are known and the copies are
  * enqueued, not when the copies finish. */
 int tc_migrate_step(tc_ctx *ctx, uint32_t step, int phase,

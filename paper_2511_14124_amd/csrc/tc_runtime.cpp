@@ -898,6 +898,7 @@ static bool call_follows_profile(const tc_ctx *c, uint32_t step, int phase, cons
                                  uint32_t n)
 {
     const TcProfile &p = c->prof;
+    if (step >= p.n_steps) return false;                  // a module without tensors behind the profile's last step
     const uint32_t b = p.row_begin[step];
     if (p.row_begin[step + 1] - b != n) return false;
     for (uint32_t i = 0; i < n; ++i) {
@@ -1077,7 +1078,8 @@ extern "C" int tc_migrate_step(tc_ctx *c, uint32_t step, int phase, const uint32
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     if (phase != TC_PRE && phase != TC_POST) return fail(c, TC_E_ARG, "phase must be TC_PRE or TC_POST");
     if (n > TC_MAX_STEP_TENSORS || (n && !ids)) return fail(c, TC_E_ARG, "too many tensors or null ids");
-    if (step >= c->prof.n_steps) return fail(c, TC_E_ARG, "step outside the profiled iteration");
+    // the profile ends with its last step that used a tensor: a module without tensors may follow
+    if (step >= c->prof.n_steps && n) return fail(c, TC_E_ARG, "step outside the profiled iteration");
     if (phase == TC_PRE && n && !rw) return fail(c, TC_E_ARG, "PRE needs rw flags");
     TcStepArgs a{};
     for (uint32_t i = 0; i < n; ++i) {
@@ -1147,8 +1149,10 @@ extern "C" int tc_replay_iteration(tc_ctx *c, const uint32_t *step_ptr, const ui
 {
     if (!c || !step_ptr || !ids || !rw) return fail(c, TC_E_ARG, "null argument");
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
-    if (n_steps > c->prof.n_steps) return fail(c, TC_E_ARG, "more steps than the profiled iteration");
     if (step_ptr[0] != 0) return fail(c, TC_E_ARG, "step_ptr must start at 0");
+    // modules without tensors behind the profile's last step decide nothing and move nothing
+    while (n_steps > c->prof.n_steps && step_ptr[n_steps] == step_ptr[n_steps - 1]) --n_steps;
+    if (n_steps > c->prof.n_steps) return fail(c, TC_E_ARG, "more steps than the profiled iteration");
     for (uint32_t k = 0; k < n_steps; ++k) {
         if (step_ptr[k + 1] < step_ptr[k]) return fail(c, TC_E_ARG, "step_ptr must not decrease");
         if (step_ptr[k + 1] - step_ptr[k] > TC_MAX_STEP_TENSORS) return fail(c, TC_E_ARG, "too many tensors in a step");

@@ -596,3 +596,28 @@ def test_two_tier_mode_wants_a_plan_without_host_buffers_and_host_memory(tmp_pat
     with pytest.raises(T.TcError, match="pinned host memory"):
         tc.bind_memory(dev.data_ptr(), dev.numel(), 0, 0, 0, 0, -1, 0, T.BIND_HOST_TIER)
     tc.close()
+
+
+# ----------------------------------------------------------------------------
+# degenerate traces
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("window", [None, 4])
+def test_degenerate_traces(window, tmp_path):
+    # an iteration without steps, modules without tensors, tensors no module uses (they never
+    # get a GPU buffer), tensors barely larger than a stamp, one tensor per class
+    from workloads import traces as Tr
+    cases = [
+        ("no_steps", [512, 1024], [0, 1], [], 4096, (4096, 4096)),
+        ("empty_steps", [512, 1024, 512], [0, 1, 0], [[], [(0, 1)], [], [(2, 3)], []], 1024, (4096, 4096)),
+        ("unused_tensors", [512, 512, 512, 2048, 100], [0, 0, 0, 1, 1], [[(0, 1)], [(1, 3)], [(0, 3)]], 512, (512, 0)),
+        ("tiny_tensors", [16, 16, 16, 20, 20, 20, 32, 32], [0] * 8,
+         [[(0, 3)], [(3, 3), (6, 2)], [(1, 3)], [(4, 3), (7, 3)], [(2, 3), (5, 1)], [(0, 1), (6, 3)]], 1024, (1024, 0)),
+        ("every_class_one_tensor", [256, 512, 768, 1024], [0, 0, 1, 1], [[(0, 3), (2, 3)], [(1, 3), (3, 3)]] * 2, 2560,
+         (0, 0)),
+    ]
+    for name, sizes, groups, steps, hbm, host in cases:
+        wl = Tr._simple(name, sizes, groups, steps, hbm, host, literal=False, n_iterations=3)
+        tc = run_library(wl, file_path=_tmpfile(tmp_path, name + ".bin"), staging_bytes=1 << 16, window=window)
+        check_against_oracle(wl, tc)
+        tc.close()
