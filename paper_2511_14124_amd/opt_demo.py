@@ -52,6 +52,48 @@ def adam_(torch, p, m, v, g, tmp, step, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8):
     p.addcdiv_(m, tmp, value=-lr / (1 - b1 ** step))
 
 
+def plain_io_rate(T, path, stripes, bytes_each_way, chunk=8 << 20):
+    """What this box's file system gives plain threads for the same job: one
+    reader and one writer thread per stripe file, 8 MiB preadv / pwrite calls
+    between the file and a pinned region, bytes_each_way read and as many
+    written at the same time (buffered; the extents read were written by the
+    runs before).  Returns GB/s, both directions together."""
+    import threading
+    n = max(1, stripes)
+    per_file = min(bytes_each_way // n, os.path.getsize(path) // 2) // chunk * chunk
+    if per_file == 0:
+        return None
+    region = T._PinnedRegion(2 * n * chunk)
+    mem = (C.c_uint8 * region.nbytes).from_address(region.ptr)
+    fds = [os.open(path if k == 0 else f"{path}.{k}", os.O_RDWR) for k in range(n)]
+    errors = []
+
+    def work(k, write):
+        try:
+            buf = memoryview(mem)[(2 * k + write) * chunk:(2 * k + write + 1) * chunk]
+            base = per_file if write else 0
+            for off in range(0, per_file, chunk):
+                if write:
+                    os.pwrite(fds[k], buf, base + off)
+                else:
+                    os.preadv(fds[k], [buf], base + off)
+        except OSError as e:
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(k, w)) for k in range(n) for w in (0, 1)]
+    t0 = time.perf_counter()
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    dt = time.perf_counter() - t0
+    for fd in fds:
+        os.close(fd)
+    del mem
+    region.free()
+    return None if errors else 2 * n * per_file / dt / 1e9
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=4)
@@ -175,11 +217,42 @@ def main(argv=None):
     if path is None:
         tmpdir = tempfile.TemporaryDirectory(prefix="tc_opt_")
         path = os.path.join(tmpdir.name, "states.bin")
+    def migration_only(path):
+        """The prefetch variant's schedule with nothing between the hooks: what the scheduler
+        and the I/O workers move per second when no update competes for the cores."""
+        tc = T.TensorCache()
+        tc.profile_order(tensor_bytes, group, ev_step, ev_tensor, ev_rw)
+        tc.plan_pools(int(state_bytes * args.cache), (0, 0), 256, 0)
+        tc.plan_schedule()
+        tc.bind_torch(file_path=path, host_tier=True, stripes=args.stripes, direct=args.direct, staging_bytes=int(tensor_bytes.max()))
+        tc.set_oplog(False, True)
+        tc.fill_payload(1)
+        steps = [[(3 * j, RW), (3 * j + 1, RW), (3 * j + 2, RW)] for j in range(n_p)]
+        tc.replay_iteration_c(steps, 0)             # warm-up
+        tc.synchronize()
+        s0 = tc.cache_stats()
+        t0 = time.perf_counter()
+        for _ in range(args.sweeps):
+            tc.replay_iteration_c(steps, 0)
+        tc.synchronize()
+        dt = time.perf_counter() - t0
+        s1 = tc.cache_stats()
+        moved = (s1["bytes_file_read"] - s0["bytes_file_read"]) + (s1["bytes_file_write"] - s0["bytes_file_write"])
+        tc.close()
+        return {"ms_per_sweep": 1e3 * dt / args.sweeps, "GBps_read_plus_written": moved / dt / 1e9,
+                "GiB_per_sweep": moved / args.sweeps / 2**30}
+
     res = {}
     ok = True
     for name, frac, prefetch in (("resident", 1.0, True), ("prefetch", args.cache, True), ("demand", args.cache, False)):
         res[name], got = run(frac, prefetch, path)
         ok = ok and all(np.array_equal(got[j][k], want[j][k]) for j in sampled for k in range(3))
+    res["migration_only"] = migration_only(path)
+    ceiling = None if args.direct else plain_io_rate(
+        T, path, args.stripes, int(res["migration_only"]["GiB_per_sweep"] * 2**30 / 2))
+    res["plain_threads_GBps_read_plus_written"] = ceiling
+    if ceiling:
+        res["migration_only"]["share_of_plain_threads"] = res["migration_only"]["GBps_read_plus_written"] / ceiling
     out = {
         "states": {"parameters": int(sum(elems)), "tensors": 3 * n_p, "GiB": state_bytes / 2**30,
                    "layers": args.layers, "hidden": args.hidden, "ffn": args.ffn, "vocab": args.vocab},
