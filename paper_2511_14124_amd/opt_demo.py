@@ -31,7 +31,7 @@ import time
 
 import numpy as np
 
-RW = 3          # an access that reads and writes (TC_R | TC_W)
+from .opt_states import RW, adam_
 
 
 def parameter_elems(layers: int, hidden: int, ffn: int, vocab: int, shard_rows: int = 4096):
@@ -41,15 +41,6 @@ def parameter_elems(layers: int, hidden: int, ffn: int, vocab: int, shard_rows: 
     for _ in range(layers):
         elems += [h, h * h, h * h, h * h, h * h, h, h * f, h * f, f * h]
     return elems + [h] + shards
-
-
-def adam_(torch, p, m, v, g, tmp, step, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8):
-    """Adam on fp32 views, in place; tmp is scratch of the same length."""
-    m.mul_(b1).add_(g, alpha=1 - b1)
-    v.mul_(b2).addcmul_(g, g, value=1 - b2)
-    torch.sqrt(v, out=tmp)
-    tmp.div_((1 - b2 ** step) ** 0.5).add_(eps)
-    p.addcdiv_(m, tmp, value=-lr / (1 - b1 ** step))
 
 
 def plain_io_rate(T, path, stripes, bytes_each_way, chunk=8 << 20):

@@ -20,7 +20,14 @@ buffers: no third pass, a third less traffic; `sgd_step` is then not called.
 
 Between its pre-hook and its post-hook a module's parameters are views into
 the HBM cache buffers the library returned; outside that window they point
-nowhere useful and must not be touched.  Gradients stay ordinary PyTorch
+nowhere useful and must not be touched.  A parameter may come back for the
+backward pass in another buffer than the one it had in the forward pass, and
+autograd keeps for the backward whatever tensor the forward handed it (for a
+Linear layer a transposed view of the weight, tied to the old buffer).  During
+a managed module's forward the helper therefore installs saved-tensor hooks:
+a tensor that aliases one of the module's parameters is saved as "parameter t,
+this shape, stride and offset" and rebuilt from the parameter's current buffer
+when the backward pass asks for it.  Gradients stay ordinary PyTorch
 tensors: this helper manages parameters only (the FP16-parameter policy of
 Sec. 3.4.2), it is a way to drive the library from real modules, not a
 training framework.
@@ -38,6 +45,14 @@ import numpy as np
 from . import binding as T
 
 R, W, RW = 1, 2, 3
+
+
+class _ParamRef:
+    """What autograd keeps in place of a tensor that aliases managed parameter t."""
+    __slots__ = ("t", "shape", "stride", "offset")
+
+    def __init__(self, t, shape, stride, offset):
+        self.t, self.shape, self.stride, self.offset = t, shape, stride, offset
 
 
 class ParamCache:
@@ -75,6 +90,8 @@ class ParamCache:
         self._pending_bwd: Dict[int, int] = {}            # module -> parameters whose gradient is still due
         self._bwd_step: Dict[int, int] = {}               # module -> step index of its running backward
         self._fwd_step: Dict[int, int] = {}               # module -> step index of its running forward
+        self._saving_for: Tuple[int, ...] = ()            # parameters of the module whose forward is running
+        self._saved_ctx: Dict[int, object] = {}           # module -> its saved-tensor hooks, while its forward runs
         if any(not p.requires_grad for p in self.params):
             raise ValueError("every managed parameter must require a gradient (its post-hook waits for it)")
 
@@ -128,10 +145,38 @@ class ParamCache:
                 view = self._views[(t, ptr)] = self.tc.hbm[off: off + n].view(self._dtype[t]).view(self._shape[t])
             self.params[t].data = view
 
+    def _pack_saved(self, x):
+        """A tensor the running forward saves for the backward pass: if it aliases one of
+        the module's parameters, keep a reference to the parameter instead of the buffer."""
+        if not x.is_cuda:
+            return x
+        ptr = x.data_ptr()
+        for t in self._saving_for:
+            d = self.params[t].data
+            base = d.data_ptr()
+            if base <= ptr < base + self._nbytes[t] and x.dtype == d.dtype:
+                return _ParamRef(t, tuple(x.shape), tuple(x.stride()), (ptr - base) // x.element_size())
+        return x
+
+    def _unpack_saved(self, r):
+        if isinstance(r, _ParamRef):
+            d = self.params[r.t].data                     # the buffer the backward pre-hook fetched it into
+            return self.torch.as_strided(d, r.shape, r.stride, d.storage_offset() + r.offset)
+        return r
+
     def _fwd_pre(self, m, args):
         self._fwd_step[id(m)] = self._begin(m, R)
+        if not self._recording and self.torch.is_grad_enabled():
+            ctx = self.torch.autograd.graph.saved_tensors_hooks(self._pack_saved, self._unpack_saved)
+            ctx.__enter__()
+            self._saved_ctx[id(m)] = ctx
+            self._saving_for = tuple(self.mod_ids[id(m)])
 
     def _fwd_post(self, m, args, out):
+        ctx = self._saved_ctx.pop(id(m), None)
+        if ctx is not None:
+            ctx.__exit__(None, None, None)
+            self._saving_for = ()
         self._end(m, self._fwd_step.pop(id(m)), R)
         # the module's backward starts when the gradient of its output arrives
         outs = out if isinstance(out, (tuple, list)) else (out,)
@@ -214,9 +259,10 @@ class ParamCache:
         self._register()
 
     # ------------------------------------------------------------- iteration
-    def sgd_step(self, lr: float):
-        """Plain SGD through the cache: each parameter is fetched (read + write),
-        updated in its cache buffer and left to the scheduler."""
+    def update_sweep(self, update: Callable[[int, object], None]):
+        """The optimizer sweep through the cache: each parameter in turn is fetched (read +
+        write), `update(t, p)` changes `p.data` in its cache buffer (p.grad holds the
+        gradient), and the parameter is left to the scheduler."""
         torch = self.torch
         if self.fused_sgd_lr is not None:
             raise RuntimeError("the update is applied in the backward hooks (fused_sgd_lr): there is no sweep")
@@ -228,9 +274,13 @@ class ParamCache:
                 one = self._one_id[t]
                 self._fetch(k, (t,), one, rw)
                 if p.grad is not None:
-                    p.data.add_(p.grad, alpha=-lr)
+                    update(t, p)
                 self.tc.migrate_step(k, T.POST, one, rw, stream)
                 k += 1
+
+    def sgd_step(self, lr: float):
+        """Plain SGD through the cache."""
+        self.update_sweep(lambda t, p: p.data.add_(p.grad, alpha=-lr))
 
     def end_iteration(self):
         self.tc.end_iteration(self.torch.cuda.current_stream().cuda_stream)

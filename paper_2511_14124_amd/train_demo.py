@@ -10,6 +10,15 @@ budget of `--cache` times the parameter bytes and then fetches and evicts the
 parameters around every module.  Gradients and activations stay ordinary
 PyTorch tensors.  Prints one JSON line: step time of both runs, tokens/s, what
 moved per step and the cache's hit rate.
+
+With `--cpu-adam` the update is the paper's whole pipeline in miniature
+(Sec. 3.4.2): the 16-bit parameters go through the HBM cache as before, and per
+parameter an fp32 master copy, momentum and variance live in a second,
+two-tier cache (pinned host memory over a file); the sweep brings each
+gradient to the host, runs Adam on the CPU over the cached states and writes
+the rounded master copy back into the parameter's HBM buffer.  The reference
+run does the same arithmetic with everything resident, and the final
+parameters of the two must be equal bit for bit.
 """
 
 from __future__ import annotations
@@ -56,7 +65,7 @@ def build_model(torch, d_model, n_layers, n_heads, vocab, dtype):
     return Model().to(device="cuda:0", dtype=dtype)
 
 
-def main():
+def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=12)
     ap.add_argument("--d-model", type=int, default=2048)
@@ -67,14 +76,20 @@ def main():
     ap.add_argument("--cache", type=float, default=0.3, help="HBM cache as a fraction of the parameter bytes")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--lr", type=float, default=1e-3)
+    ap.add_argument("--cpu-adam", action="store_true",
+                    help="Adam on the CPU, its fp32 states in a two-tier cache (host memory over a file)")
+    ap.add_argument("--state-cache", type=float, default=0.5, help="host cache as a fraction of the state bytes")
+    ap.add_argument("--threads", type=int, default=8, help="PyTorch CPU threads for the CPU update")
     ap.add_argument("--fused-sgd", action="store_true",
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
-    args = ap.parse_args()
+    args = ap.parse_args(argv)
 
     import torch
     from .torch_hooks import ParamCache
     from . import binding as T
     T.load_library()
+    if args.cpu_adam:
+        return cpu_adam_demo(args, torch, T)
     dtype = torch.bfloat16
     torch.manual_seed(0)
     tokens = torch.randint(0, args.vocab, (args.batch, args.seq), device="cuda:0")
@@ -108,6 +123,7 @@ def main():
                 p.add_(p.grad, alpha=-args.lr)
 
     t_res = timed(resident_step)
+    want = [p.detach().cpu().clone() for p in model.parameters()]
     del model
     torch.cuda.empty_cache()
 
@@ -133,11 +149,10 @@ def main():
             s0 = pc.tc.cache_stats()
         cached_step()
 
-    cached_step()                                          # first pass through the hooks
-    torch.cuda.synchronize()
-    t_off = timed(cached_step_counted)
+    t_off = timed(cached_step_counted)                     # as many steps as the resident run: one warm-up, then timed
     pc.tc.synchronize()
     s1 = pc.tc.cache_stats()
+    same = all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(pc.gather(), want))
     n_counted = args.steps + 1                             # timed() runs one warm-up step after s0 is taken
     plan = pc.tc.plan
     out = {
@@ -153,11 +168,152 @@ def main():
                           "h2d_GBps_over_the_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n_counted / t_off / 1e9,
                           "hook_calls_per_step": 4 * len(pc.mods) + (0 if args.fused_sgd else 2 * len(pc.params)),
                           "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters"},
+        "final_parameters_equal_resident_training": bool(same),
         "note": "parameters only are managed (gradients and activations stay resident); plain SGD; hooks drive "
                 "tc_migrate_step one call at a time",
     }
     pc.close()
     print(json.dumps(out))
+    return out
+
+
+def cpu_adam_demo(args, torch, T):
+    import os
+    import tempfile
+
+    import numpy as np
+
+    from .opt_states import OptStateCache, adam_
+    from .torch_hooks import ParamCache
+    if args.threads:
+        torch.set_num_threads(args.threads)
+    dtype = torch.bfloat16
+    tokens = torch.randint(0, args.vocab, (args.batch, args.seq), device="cuda:0",
+                           generator=torch.Generator(device="cuda:0").manual_seed(1))
+    target = torch.randint(0, args.vocab, (args.batch, args.seq), device="cuda:0",
+                           generator=torch.Generator(device="cuda:0").manual_seed(2))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(model):
+        loss_fn(model(tokens).float().view(-1, args.vocab), target.view(-1)).backward()
+
+    def make_model():
+        torch.manual_seed(0)
+        return build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
+
+    model = make_model()
+    params = list(model.parameters())
+    elems = [p.numel() for p in params]
+    g_host = torch.empty(max(elems), dtype=torch.float32).pin_memory()    # a gradient on its way to the CPU
+    tmp = torch.empty(max(elems), dtype=torch.float32)
+    n_steps = args.steps + 1                                              # one warm-up step, also checked
+
+    def cpu_update(p, states, step):
+        """Gradient to the host, Adam on the CPU, rounded master copy back into the parameter."""
+        n = p.numel()
+        master, m, v = states
+        g_host[:n].copy_(p.grad.reshape(-1))                              # bf16 on the GPU -> fp32 pinned, synchronous
+        adam_(torch, master, m, v, g_host[:n], tmp[:n], step, lr=args.lr)
+        p.data.copy_(master.view(p.shape))
+
+    # ---- everything resident: parameters in HBM, states in ordinary host memory
+    states = [[p.detach().float().cpu().reshape(-1), torch.zeros(p.numel()), torch.zeros(p.numel())] for p in params]
+    step_no = 0
+
+    def resident_step():
+        nonlocal step_no
+        step_no += 1
+        for p in params:
+            p.grad = None
+        iteration(model)
+        with torch.no_grad():
+            for p, st in zip(params, states):
+                cpu_update(p, st, step_no)
+
+    resident_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        resident_step()
+    torch.cuda.synchronize()
+    t_res = (time.perf_counter() - t0) / args.steps
+    want = [p.detach().cpu().clone() for p in params]
+    want_master = {j: states[j][0].clone() for j in (0, len(params) // 2, len(params) - 1)}
+    param_bytes = sum(p.numel() * p.element_size() for p in params)
+    del model, params, states
+    torch.cuda.empty_cache()
+
+    # ---- parameters through the HBM cache, states through the two-tier cache
+    model = make_model()
+    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache))
+    assert [p.numel() for p in pc.params] == elems         # the same parameter order in both runs
+    tmpdir = tempfile.TemporaryDirectory(prefix="tc_states_")
+    state_bytes = 12 * sum(elems)
+    sc = OptStateCache(elems, int(state_bytes * args.state_cache), os.path.join(tmpdir.name, "states.bin"))
+    for j, p in enumerate(pc.params):
+        sc.load(j, p.detach().float().cpu().numpy())
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    pc.tc.set_oplog(False, True)
+    step_no = 0
+
+    def update(j, p):
+        st = sc.begin(j)
+        cpu_update(p, st, step_no)
+        sc.end(j)
+
+    def cached_step():
+        nonlocal step_no
+        step_no += 1
+        iteration(model)
+        pc.update_sweep(update)
+        sc.end_iteration()
+        pc.end_iteration()
+
+    cached_step()
+    torch.cuda.synchronize()
+    s0, o0 = pc.tc.cache_stats(), sc.stats()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        cached_step()
+    torch.cuda.synchronize()
+    t_off = (time.perf_counter() - t0) / args.steps
+    pc.tc.synchronize()
+    sc.tc.synchronize()
+    s1, o1 = pc.tc.cache_stats(), sc.stats()
+    got = pc.gather()
+    differing = [j for j, (a, b) in enumerate(zip(got, want)) if not torch.equal(a.view(torch.int16), b.view(torch.int16))]
+    same = not differing
+    max_diff = max((float((got[j].float() - want[j].float()).abs().max()) for j in differing), default=0.0)
+    same_master = all(np.array_equal(sc.read(j), w.numpy()) for j, w in want_master.items())
+    n = args.steps
+    out = {
+        "model": {"layers": args.layers, "d_model": args.d_model, "params": int(sum(elems)),
+                  "param_GiB": param_bytes / 2**30, "state_GiB": state_bytes / 2**30, "dtype": "bf16 + fp32 states",
+                  "tokens_per_step": args.batch * args.seq},
+        "hbm_cache_fraction": float(pc.tc.plan.hbm_total) / param_bytes,
+        "state_cache_fraction": float(sc.tc.plan.hbm_total) / state_bytes,
+        "cpu_threads": torch.get_num_threads(),
+        "resident": {"ms_per_step": t_res * 1e3},
+        "through_both_caches": {
+            "ms_per_step": t_off * 1e3, "slowdown": t_off / t_res,
+            "param_hit_rate": (s1["hits"] - s0["hits"]) / max(1, s1["hits"] - s0["hits"] + s1["misses"] - s0["misses"]),
+            "state_miss_rate": (o1["misses"] - o0["misses"]) / max(1, o1["hits"] - o0["hits"] + o1["misses"] - o0["misses"]),
+            "h2d_GiB_per_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n / 2**30,
+            "state_file_read_GiB_per_step": (o1["bytes_file_read"] - o0["bytes_file_read"]) / n / 2**30,
+            "state_file_write_GiB_per_step": (o1["bytes_file_write"] - o0["bytes_file_write"]) / n / 2**30,
+            "ms_blocked_for_states_per_step": (o1["stall_ns"] - o0["stall_ns"]) / n / 1e6,
+        },
+        "final_parameters_equal_resident_training": bool(same),
+        "parameters_differing": len(differing), "first_differing": differing[:6], "max_abs_difference": max_diff,
+        "sampled_master_copies_equal": bool(same_master),
+        "steps_checked": n_steps,
+    }
+    sc.close()
+    pc.close()
+    tmpdir.cleanup()
+    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":

@@ -97,6 +97,62 @@ def test_training_demo_runs_a_gpt_shaped_model_through_the_cache(capsys, monkeyp
                                       "--batch", "2", "--seq", "64", "--steps", "2", "--cache", "0.4"])
     train_demo.main()
     out = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
-    assert out["through_cache"]["hit_rate"] == 1.0
+    assert out["through_cache"]["hit_rate"] == 1.0 and out["final_parameters_equal_resident_training"]
     assert out["through_cache"]["h2d_GiB_per_step"] > 0 and out["cache_fraction"] < 0.8
     assert out["model"]["modules_with_hooks"] == 2 * 6 + 3
+
+
+def test_train_demo_with_cpu_adam_over_the_two_tier_cache():
+    # the whole pipeline on a small model: 16-bit parameters through the HBM cache, fp32 Adam
+    # states through the host cache over a file, the update on the CPU; three steps give the
+    # parameters and master copies of the same training with everything resident, bit for bit
+    from paper_2511_14124_amd import train_demo
+    out = train_demo.main(["--layers", "2", "--d-model", "128", "--heads", "4", "--vocab", "512", "--batch", "2",
+                           "--seq", "64", "--steps", "2", "--cache", "0.4", "--cpu-adam", "--state-cache", "0.4",
+                           "--threads", "4"])
+    assert out["final_parameters_equal_resident_training"] and out["sampled_master_copies_equal"]
+    assert out["steps_checked"] == 3
+    both = out["through_both_caches"]
+    assert both["param_hit_rate"] == 1.0 and both["state_miss_rate"] == 0.0
+    assert both["state_file_read_GiB_per_step"] > 0 and out["state_cache_fraction"] < 0.8
+
+
+def test_a_parameter_that_returns_in_another_buffer_is_read_from_there_in_the_backward_pass():
+    # A transformer block's Linear layers keep a transposed view of their weight for the backward
+    # pass.  With several size classes and a small cache a weight evicted after its forward comes
+    # back for its backward in another buffer: the saved view must follow it there, or the
+    # gradients of everything below that layer are computed from bytes of some other tensor.
+    from paper_2511_14124_amd.train_demo import build_model
+    vocab = 512
+
+    def make():
+        torch.manual_seed(3)
+        return build_model(torch, 128, 6, 4, vocab, torch.bfloat16)
+
+    gen = torch.Generator(device="cuda:0").manual_seed(5)
+    tokens = torch.randint(0, vocab, (2, 64), device="cuda:0", generator=gen)
+    target = torch.randint(0, vocab, (2, 64), device="cuda:0", generator=gen)
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        loss_fn(m(tokens).float().view(-1, vocab), target.view(-1)).backward()
+
+    ref = make()
+    iteration(ref)
+    want = [p.grad.clone() for p in ref.parameters()]
+    model = make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(total * 0.26))
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    for _ in range(2):                                     # the second iteration starts from restored buffers
+        iteration(model)
+        torch.cuda.synchronize()
+        got = [p.grad.clone() for p in pc.params]
+        pc.end_iteration()
+        assert all(torch.equal(a, b) for a, b in zip(got, want))
+    buffers = {}
+    for (t, ptr) in pc._views:
+        buffers.setdefault(t, set()).add(ptr)
+    assert any(len(v) > 1 for v in buffers.values())       # some parameter did change buffers
+    pc.close()
