@@ -35,12 +35,12 @@ TRAFFIC_RATIO = {"tc_mover_kernel": (1.0000 + 1.0000) / 2.0,          # (fetch +
                  "tc_pack_kernel": (1.0234 + 1.0000) / 2.0}           # (fetch + write) / (2 x payload)
 
 
-def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
-    """Pack kernel on a stress shape: the workloads' small-tensor size histogram
-    repeated until ~4 GiB, one launch.  shift = 0: tensor and slab addresses agree
+def pack_stress_layout(torch, total_bytes=4 << 30, shift=0):
+    """The pack stress shape: the workloads' small-tensor size histogram repeated
+    until ~total_bytes.  Source buffers hold the same sizes in reverse order, so
+    source and slab offsets differ; shift = 0: tensor and slab addresses agree
     modulo 16 (pool buffers are 256-byte aligned); shift != 0: every tensor sits
-    `shift` bytes off, so every tensor-side 128-bit access is misaligned.  Returns
-    (GB/s algorithmic = 2 x payload / time, ms, payload bytes, segments)."""
+    `shift` bytes off, so every tensor-side 128-bit access is misaligned."""
     dev = torch.device("cuda:0")
     sizes = np.asarray([4096, 4096, 8192, 12288, 16384, 4096, 4096, 32768, 8192, 4096], dtype=np.uint64)
     n = int(total_bytes // int(sizes.sum())) * len(sizes)
@@ -51,11 +51,19 @@ def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
     src = torch.empty(total + 4096, dtype=torch.uint8, device=dev)
     slab = torch.empty(total, dtype=torch.uint8, device=dev)
     src.random_(0, 255)
-    # source buffers: the same sizes, in reverse order, so source and slab offsets differ
     src_off = (total - off - nb).astype(np.uint64) + np.uint64(shift)
-    ptrs = torch.from_numpy((src_off + np.uint64(src.data_ptr())).astype(np.int64)).to(dev)
-    nbt = torch.from_numpy(nb.astype(np.int64)).to(dev)
-    offt = torch.from_numpy(off.astype(np.int64)).to(dev)
+    return {"n": n, "total": total, "bytes": nb, "slab_off": off, "src_off": src_off, "src": src, "slab": slab,
+            "ptrs": torch.from_numpy((src_off + np.uint64(src.data_ptr())).astype(np.int64)).to(dev),
+            "d_bytes": torch.from_numpy(nb.astype(np.int64)).to(dev),
+            "d_off": torch.from_numpy(off.astype(np.int64)).to(dev)}
+
+
+def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
+    """Pack kernel on the stress shape, one launch.  Returns (GB/s algorithmic =
+    2 x payload / time, ms, payload bytes, segments)."""
+    dev = torch.device("cuda:0")
+    L = pack_stress_layout(torch, total_bytes, shift)
+    n, total, src, slab, ptrs, nbt, offt = L["n"], L["total"], L["src"], L["slab"], L["ptrs"], L["d_bytes"], L["d_off"]
     st = torch.cuda.current_stream().cuda_stream
     if shift == 0 and not unpack:
         # reference for hardware-counter runs: a plain device-to-device copy of exactly 1 GiB by

@@ -267,3 +267,39 @@ def test_pack_and_unpack_beyond_4_gib():
         pad = (n + 255) // 256 * 256 - n
         if pad and i + 1 < len(sizes):
             assert bool((back[o + n:o + n + pad] == 0x55).all())
+
+
+@pytest.mark.parametrize("shift", [0, 4, 1])
+def test_pack_stress_shape_at_the_size_and_launch_the_bench_times(shift):
+    # 4 GiB in 436 900 segments, tile index built once, one launch each way, as bench.py does it
+    # (aligned, 4 bytes off, 1 byte off); sampled segments against the definition, one by one
+    import bench
+    L = bench.pack_stress_layout(torch, 4 << 30, shift)
+    n, total = L["n"], L["total"]
+    st = torch.cuda.current_stream().cuda_stream
+    index = torch.empty(T.pack_tiles(total), dtype=torch.int32, device="cuda:0")
+    T.pack_index(L["d_off"].data_ptr(), n, total, index.data_ptr(), st)
+    L["slab"].fill_(0xEE)
+    T.pack(L["slab"].data_ptr(), L["ptrs"].data_ptr(), L["d_bytes"].data_ptr(), L["d_off"].data_ptr(), n, total, st,
+           index.data_ptr())
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(shift)
+    sample = sorted(set(rng.integers(0, n, size=300).tolist()) | {0, 1, n - 2, n - 1})
+    for i in sample:
+        o, so, k = int(L["slab_off"][i]), int(L["src_off"][i]), int(L["bytes"][i])
+        piece = L["src"][so:so + k].cpu().numpy()
+        want = po.pack([piece], np.asarray([0], dtype=np.uint64), np.zeros(k, dtype=np.uint8))
+        assert np.array_equal(L["slab"][o:o + k].cpu().numpy(), want), (shift, i)
+    # the way back, into a fresh image: sampled segments equal their slab pieces, the gaps stay
+    back = torch.full_like(L["src"], 0x55)
+    ptrs2 = _dev((L["src_off"] + np.uint64(back.data_ptr())).astype(np.int64))
+    T.unpack(L["slab"].data_ptr(), ptrs2.data_ptr(), L["d_bytes"].data_ptr(), L["d_off"].data_ptr(), n, total, st,
+             index.data_ptr())
+    torch.cuda.synchronize()
+    for i in sample:
+        o, so, k = int(L["slab_off"][i]), int(L["src_off"][i]), int(L["bytes"][i])
+        want = po.unpack(L["slab"][o:o + k].cpu().numpy(), np.asarray([k], dtype=np.uint64), np.asarray([0], dtype=np.uint64))[0]
+        assert np.array_equal(back[so:so + k].cpu().numpy(), want), (shift, i)
+    assert bool((back[:shift] == 0x55).all()) and bool((back[total + shift:] == 0x55).all())
+    # and as a whole, on the device: every byte of the image came back
+    assert torch.equal(back[shift:total + shift], L["src"][shift:total + shift])
