@@ -360,7 +360,8 @@ int tc_tune_mover(tc_ctx *ctx, uint32_t *workgroups_out);
  * chunks (tc_set_io_chunk); chunk i of tensor t belongs to lane t + i, and the lane picks the
  * worker, so one large request spreads over the threads while a given chunk
  * always goes to the same writer: writes of one extent keep their order.  A
- * read of an extent is queued only after the write queued for it has finished.
+ * read of an extent names the write queued for it, and its reader starts only
+ * once that write has finished (the calling thread does not wait for it).
  * A copy whose bytes are still on their way from the file is launched by the
  * first later call that finds the read finished, at the latest by the call
  * that needs one of its buffers (which then waits).  0 = that kind of I/O runs
