@@ -50,18 +50,20 @@ def build_probe(verbose: bool = True) -> str:
 
 
 def build_c_example(verbose: bool = True) -> str:
-    """The plain-C99 user of the ABI under tests/c (run by the GPU tests): built with gcc
-    against include/tc.h and the HIP runtime API, found at run time next to libtc.so."""
-    src = os.path.join(ROOT, "tests", "c", "tc_example.c")
-    out = os.path.join(ROOT, "tests", "c", "tc_example.bin")
+    """The plain-C99 users of the ABI under tests/c (run by the GPU tests): built with gcc
+    against include/tc.h and the HIP runtime API, libtc.so found at run time next to them."""
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
-    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
-           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), src, "-o", out,
-           "-L", HERE, "-l:libtc.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
-           "-Wl,-rpath,$ORIGIN/../../paper_2511_14124_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    out = ""
+    for name in ("tc_opt_example", "tc_example"):
+        src = os.path.join(ROOT, "tests", "c", name + ".c")
+        out = os.path.join(ROOT, "tests", "c", name + ".bin")
+        cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+               "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), src, "-o", out,
+               "-L", HERE, "-l:libtc.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+               "-Wl,-rpath,$ORIGIN/../../paper_2511_14124_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     return out
 
 

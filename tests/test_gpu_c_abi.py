@@ -25,3 +25,12 @@ def test_worked_example_from_plain_c():
     assert os.path.exists(BIN), "tests/c/tc_example.bin is missing: run `python -m paper_2511_14124_amd.build` first"
     p = subprocess.run([BIN], capture_output=True, text=True, timeout=120)
     assert p.returncode == 0 and "tc_example: ok" in p.stdout, p.stdout + p.stderr
+
+
+@pytest.mark.gpu
+def test_optimizer_state_example_from_plain_c():
+    # the two-tier mode (host cache over a file) through the same header, the update done by the C program itself
+    exe = os.path.join(ROOT, "tests", "c", "tc_opt_example.bin")
+    assert os.path.exists(exe), "tests/c/tc_opt_example.bin is missing: run `python -m paper_2511_14124_amd.build` first"
+    p = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert p.returncode == 0 and "tc_opt_example: ok" in p.stdout, p.stdout + p.stderr
