@@ -192,6 +192,27 @@ def test_gpt_1p3b_config_full_size_sampled_bytes():
     tc.close()
 
 
+@pytest.mark.parametrize("window", [None, 64], ids=["hook_by_hook", "windows"])
+def test_gpt_1p3b_config_full_size_with_compute_beside_the_copies(window):
+    # the same configuration with the modelled compute stretched to about the migration time
+    # (both streams busy throughout, launches merged up to 64 MiB as in the bench's stall run):
+    # the copies overlap the stand-in kernels that stamp the buffers, so a copy that started
+    # before its buffer was done with, or a module that started before its copy had landed,
+    # shows in the sampled bytes
+    wl = W.config(1)
+    wl.compute_ns = (wl.compute_ns.astype(np.float64) * (0.6e9 / float(wl.compute_ns.sum()))).astype(np.uint64)
+    tc = run_library(wl, fill=True, window=window, merge_bytes=64 << 20, tune=True, busy=True)
+    kinds = wl.tensor_kind
+    order = np.argsort(wl.tensor_bytes, kind="stable")
+    sample = set(order[:6].tolist()) | set(order[-6:].tolist())
+    for k in range(6):
+        ids = np.nonzero(kinds == k)[0]
+        sample |= set(ids[:: max(1, len(ids) // 8)].tolist())
+    r = check_against_oracle(wl, tc, tensors=sorted(sample))
+    assert r.misses == 0 and any(r.stamps[t] for t in sample)
+    tc.close()
+
+
 def _sample(wl, r, per_kind=4, extremes=4):
     kinds = wl.tensor_kind
     order = np.argsort(wl.tensor_bytes, kind="stable")
