@@ -107,6 +107,29 @@ def host_description():
     return {"cpu": model, "logical_cpus": os.cpu_count(), "cpu_quota": quota}
 
 
+def plain_memcpy_rate(threads=None, mib_each=256, reps=4):
+    """Beside the oracle, so that its single core is not mistaken for the host's limit: what
+    plain copies between host buffers reach with one thread per core (bytes copied / time)."""
+    import threading
+    threads = threads or min(16, os.cpu_count() or 1)
+    n = mib_each << 20
+    bufs = [(np.ones(n, dtype=np.uint8), np.zeros(n, dtype=np.uint8)) for _ in range(threads)]
+    for a, b in bufs:
+        np.copyto(b, a)                     # pages touched before the clock starts
+
+    def work(a, b):
+        for _ in range(reps):
+            np.copyto(b, a)
+
+    ts = [threading.Thread(target=work, args=ab) for ab in bufs]
+    t0 = time.perf_counter()
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    return threads * reps * n / (time.perf_counter() - t0) / 1e9
+
+
 def cpu_baseline(W, seconds_target=15.0):
     """The oracle, as it stands, in full-bytes mode on a bounded sample of the
     same workload (fewer layers, same shapes); GB/s of bytes copied into its
@@ -137,6 +160,7 @@ def cpu_baseline(W, seconds_target=15.0):
             break
     dt = time.perf_counter() - t0
     return {"value": r.bytes_h2d / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "plain_memcpy_all_cores_GBps": plain_memcpy_rate(),
             "sample": f"config 2 shapes at {layers} layers ({wl.total_bytes() / 2**30:.2f} GiB of tensors), "
                       f"{its} iterations, full-bytes mode, {dt:.1f} s",
             "us_per_hook_step": dt / (its * wl.n_steps) * 1e6, "profile_plan_place_load_ms": t_build * 1e3}
