@@ -779,6 +779,20 @@ hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t s
 typedef uint32_t pack_v4 __attribute__((ext_vector_type(4)));
 struct __attribute__((packed, aligned(1))) pack_u16 { pack_v4 v; };   // 16 bytes at any address
 
+// A tensor at an odd address (pack).  A 128-bit load at an address that is a multiple of 4
+// runs at nearly the aligned rate, one at an odd address does not.  So an interior vector of
+// such a piece (the 16 bytes before it and the 16 behind it belong to the same tensor) is read
+// as the 16 bytes at g - r, r = g mod 4, and the four bytes behind those come from the lane
+// that holds the next vector of the same piece (a cross-lane move once the loads are back);
+// only where there is no such lane (the last lane of a wave, the vector before an edge one)
+// they are loaded.  pack_join shifts the five dwords into place.
+__device__ __forceinline__ pack_v4 pack_join(pack_v4 lo, uint32_t hi, uint32_t r)
+{
+    // v_alignbyte_b32: the low dword of {first, second} >> 8 r; r = 0 returns lo unchanged
+    return pack_v4{__builtin_amdgcn_alignbyte(lo.y, lo.x, r), __builtin_amdgcn_alignbyte(lo.z, lo.y, r),
+                   __builtin_amdgcn_alignbyte(lo.w, lo.z, r), __builtin_amdgcn_alignbyte(hi, lo.w, r)};
+}
+
 // dst and src agree modulo 16; any address space mix (global/LDS); len <= PACK_TILE,
 // so a lane has at most four vectors and all of them are loaded before the first store
 __device__ __forceinline__ void pack_copy_aligned(uint8_t *dst, const uint8_t *src, uint32_t len, uint32_t tid)
@@ -1070,6 +1084,7 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
     // hardware takes 128-bit global accesses at any byte address, at 91-97 % of the
     // aligned rate, which beats realigning through LDS).
     uint8_t *ga[VEC];
+    uint32_t shift = 0;                                     // two bits per vector: its r (0: read where it is)
     uint32_t p = 0;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
@@ -1077,16 +1092,52 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
         while (p < n_p && tab_e[wave][p] <= x) ++p;
         const bool in = p < n_p && tab_b[wave][p] <= x && x + 16 <= tab_e[wave][p];
         ga[k] = in ? tab_g[wave][p] + x : nullptr;
+        if (in && !unpack && tab_b[wave][p] + 16 <= x && x + 32 <= tab_e[wave][p])
+            shift |= (uint32_t)((uintptr_t)ga[k] & 3) << (2 * k);
+    }
+    // does the next lane hold the next vector of the same piece, read the same way?  (its first
+    // dword is then the one behind this lane's sixteen bytes)
+    uint32_t from_next = 0;
+    if (__ballot(shift != 0) != 0) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const uintptr_t mine = (uintptr_t)ga[k];
+            const uint32_t nlo = (uint32_t)__shfl_down((int)(uint32_t)mine, 1, WAVE);
+            const uint32_t nhi = (uint32_t)__shfl_down((int)(uint32_t)(mine >> 32), 1, WAVE);
+            const uint32_t nsh = (uint32_t)__shfl_down((int)shift, 1, WAVE);
+            const uint32_t r = (shift >> (2 * k)) & 3;
+            const bool ok_next = lane + 1 < WAVE && r != 0 && (((uintptr_t)nhi << 32) | nlo) == mine + 16 &&
+                                 ((nsh >> (2 * k)) & 3) == r;
+            from_next |= (ok_next ? 1u : 0u) << k;
+        }
     }
     // streaming accesses: nothing moved here is read again by this kernel
     pack_v4 v[VEC];
+    uint32_t hi[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
+        const uint32_t r = (shift >> (2 * k)) & 3;
         v[k] = pack_v4{0, 0, 0, 0};
-        if (ga[k]) v[k] = unpack ? __builtin_nontemporal_load((const pack_v4 *)(slab + x))
-                                 : __builtin_nontemporal_load(&((const pack_u16 *)ga[k])->v);
+        hi[k] = 0;
+        if (ga[k]) {
+            if (unpack) {
+                v[k] = __builtin_nontemporal_load((const pack_v4 *)(slab + x));
+            } else {
+                v[k] = __builtin_nontemporal_load(&((const pack_u16 *)(ga[k] - r))->v);
+                if (r && !((from_next >> k) & 1)) hi[k] = __builtin_nontemporal_load((const uint32_t *)(ga[k] - r + 16));
+            }
+        }
     }
+    if (__ballot(from_next != 0) != 0) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const uint32_t nx = (uint32_t)__shfl_down((int)v[k].x, 1, WAVE);
+            if ((from_next >> k) & 1) hi[k] = nx;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) v[k] = pack_join(v[k], hi[k], (shift >> (2 * k)) & 3);
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
