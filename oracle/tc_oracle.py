@@ -621,7 +621,7 @@ class Replay:
         bound = p.row_end[step] if step < p.n_steps else n_rows
         self.cursor = max(self.cursor, bound)
         for t in finished:
-            if self.cursor >= n_rows:                     # Alg. 3 line 2
+            if self.cursor >= n_rows:                     # Alg. 3: the table has no row left
                 break
             while self.cursor < n_rows and (
                     self.cur[p.rows_tensor[self.cursor]] == GPU
