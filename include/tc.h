@@ -71,7 +71,7 @@ extern "C" {
 
 /* tc_budget.flags */
 #define TC_LITERAL_ALG2 1u           /* Alg. 2 exactly as printed: no per-step working-set floor */
-#define TC_NO_PREFETCH  2u           /* the paper's base variant (Sec. 4.1.4, "without prefetching"): post-hook
+#define TC_NO_PREFETCH  2u           /* the paper's base variant (Sec. 4.1.4, the one that does not prefetch): post-hook
                                         calls move nothing, tensors arrive by the pre-hook's demand fetch alone */
 
 /* tc_bind_memory flags */
@@ -283,7 +283,7 @@ int tc_migrate_step(tc_ctx *ctx, uint32_t step, int phase,
                     const uint32_t *ids, const uint8_t *rw, uint32_t n,
                     void *compute_stream, void **dev_ptrs_out);
 
-/* End of an iteration (Sec. 3.2.1): tensors return to their final locations,
+/* End of an iteration (Sec. 3.2.1): every tensor goes back to its final location,
  * the cursor returns to row 0. */
 int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
 

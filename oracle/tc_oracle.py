@@ -439,7 +439,7 @@ class Replay:
 
         Reading (dirty): an NVMe-final tensor is written back only if a write
         access touched it since it was last on the file tier; the paper's
-        "only the GPU buffer is released" covers read-only parameters.
+        releasing the GPU buffer without a copy, as the text does, covers read-only parameters.
         """
         p, s, n = self.p, self.p.class_of[v], self.bytes_of[v]
         y = self.gslot[v]
@@ -587,9 +587,9 @@ class Replay:
         """PrefetchTensor(finished tensors), Alg. 3.
 
         Reading (halt rule): Alg. 3 as printed evicts a finished tensor and
-        may immediately prefetch it back, against the text of Sec. 3.4.1 ("the
-        scheduler halts any eviction or prefetching" while the window holds
-        what the backward pass needs next).  So the next non-resident row is
+        may immediately prefetch it back, against the text of Sec. 3.4.1 (nothing
+        is evicted or prefetched while the window holds what the backward pass
+        needs next).  So the next non-resident row is
         found first, and a resident tensor gives up its buffer only if its
         own next use lies after that row.
 
@@ -597,8 +597,8 @@ class Replay:
         own size.  The finished tensor t is evicted for it when t has u's size
         (and passes the halt rule); otherwise u takes the lowest free buffer of
         its class; otherwise the resident tensor of u's class used farthest in
-        the future, provided that is later than u's own use (Sec. 3.4.2: "evicts
-        a tensor not needed soon").  If none qualifies nothing moves and the row
+        the future, provided that is later than u's own use (Sec. 3.4.2: the
+        tensor evicted is one not needed for a while).  If none qualifies nothing moves and the row
         is tried again at the next call.  A finished tensor of another size
         keeps its buffer until a tensor of its own size needs it: evicting it
         would free nothing u can use, and with Alg. 2's c_s - G_s host buffers
@@ -613,8 +613,8 @@ class Replay:
         p = self.p
         self.call += 1
         if not self.prefetch:
-            # the variant the paper calls the base version (Sec. 4.1.4: "without
-            # prefetching"): the post-hook moves nothing, tensors arrive by the
+            # the variant the paper calls the base version (Sec. 4.1.4: it does not
+            # prefetch): the post-hook moves nothing, tensors arrive by the
             # pre-hook's demand fetch alone
             return
         n_rows = p.n_rows
@@ -654,7 +654,7 @@ class Replay:
 
     # -- end of iteration ------------------------------------------------------
     def end_iteration(self) -> None:
-        """Tensors return to their final locations (Sec. 3.2.1).
+        """Every tensor goes back to its final location (Sec. 3.2.1).
 
         Reading: two hook calls.  In the first, class by class (ascending),
         every GPU-final tensor that is elsewhere comes back, in placement

@@ -305,7 +305,7 @@ __device__ void decide_post(DecideCtx &c, const TcStepArgs &a)
     T.scalars[0] = cursor;
 }
 
-// end of iteration: tensors return to their final locations (Sec. 3.2.1)
+// end of iteration: every tensor goes back to its final location (Sec. 3.2.1)
 __device__ void decide_end(DecideCtx &c)
 {
     const TcDevTables &T = c.T;

@@ -258,7 +258,7 @@ def test_example_cpu_gpu_nvme_matches_what_the_text_fixes():
             continue
         x = got_n - {7}
         assert len(x) == 1 and x <= {1, 2, 3}
-        # the text spills a tensor "inactive for a longer period": whichever of 1 and 2 it is,
+        # the text spills a tensor because it stays unused longer: whichever of 1 and 2 it is,
         # it is not tensor 3, the one the backward pass needs soonest
         assert x != {3}
         spilled = spilled or x
