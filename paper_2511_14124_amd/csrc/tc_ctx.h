@@ -174,6 +174,7 @@ struct tc_ctx {
     std::vector<hipEvent_t> ev_free;
     std::deque<std::pair<hipEvent_t, JobSet>> ev_busy;  // events the queued jobs of a request wait for
     std::vector<JobSet> tensor_job;     // per tensor: newest queued write of its extent
+    std::vector<uint8_t> wb_pending;    // per tensor: a prepared unit, not issued yet, will write it back to its extent
     std::vector<JobSet> cpu_job;        // per host buffer: queued write that reads it
     bool host_tier = false;             // two-tier mode: the fast tier is host memory, filled and drained by file I/O
     std::vector<JobSet> fast_read;      // two-tier mode, per fast-tier buffer: the read that fills it

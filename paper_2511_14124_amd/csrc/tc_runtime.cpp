@@ -293,6 +293,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->gpu_pending.assign(pl.gpu_slots, 0);
     c->cpu_pending.assign(pl.cpu_slots, 0);
     c->tensor_job.assign(n_t, JobSet{});
+    c->wb_pending.assign(n_t, 0);
     c->cpu_job.assign(pl.cpu_slots, JobSet{});
     c->host_tier = host_tier;
     c->fast_read.assign(host_tier ? pl.gpu_slots : 0, JobSet{});
@@ -600,6 +601,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         c->gpu_pending[(size_t)p.gpu_y] = 0;
         if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 0;
         if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 0;
+        if (p.out_staging) c->wb_pending[p.out_tensor] = 0;
     }
     units.clear();
     c->deferred_bytes = 0;
@@ -809,6 +811,10 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             } else {
                 uint8_t *st = nullptr;
                 int rc = TC_OK;
+                // the tensor's write-back may still sit in a prepared unit (it left the GPU a call
+                // or two ago and its unit waits for a read): that write has to be queued before
+                // this read of the same extent, which then names it
+                if (c->wb_pending[t] && (rc = issue_units(c, units, compute)) != TC_OK) return rc;
                 if (have_out && p.out_staging) st = reserved_in;
                 else rc = staging_alloc(c, units, n, compute, &st, &p.st_id);
                 if (rc != TC_OK) return rc;
@@ -827,6 +833,7 @@ static int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_
             if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 1;
             if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 1;
             c->deferred_bytes += n * ((p.u.out_src ? 1 : 0) + 1);
+            if (p.out_staging) c->wb_pending[p.out_tensor] = 1;
             units.push_back(p);
             have_out = false;
             break;

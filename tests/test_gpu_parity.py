@@ -642,3 +642,43 @@ def test_degenerate_traces(window, tmp_path):
         tc = run_library(wl, file_path=_tmpfile(tmp_path, name + ".bin"), staging_bytes=1 << 16, window=window)
         check_against_oracle(wl, tc)
         tc.close()
+
+
+# ----------------------------------------------------------------------------
+# no host buffers under the GPU cache: every eviction is a write-back to the file
+# ----------------------------------------------------------------------------
+
+def test_a_tensor_written_back_a_moment_ago_is_read_back_whole(tmp_path):
+    # four tensors, three GPU buffers, no host buffer: tensor 1 leaves for its file extent after
+    # step 4 and is prefetched again after step 5, while the unit that writes it back still
+    # waits for the read of its partner; the read of the extent has to come behind that write
+    from workloads import traces as Tr
+    R_, W_, RW_ = 1, 2, 3
+    steps = [[(1, RW_)], [(1, R_), (3, W_), (0, RW_)], [(0, RW_), (3, RW_)], [(3, W_), (1, R_)], [(1, R_), (3, RW_)],
+             [(2, R_), (3, RW_)], [(0, R_)], [(1, W_), (3, R_), (0, W_)], [(2, R_), (0, RW_)]]
+    wl = Tr._simple("wb_then_fetch", [33000] * 4, [0] * 4, steps, hbm_bytes=112272, host_bytes=(13209, 0),
+                    literal=False, n_iterations=2)
+    for window in (None, 4):
+        tc = run_library(wl, file_path=_tmpfile(tmp_path, f"w{window}.bin"), staging_bytes=8 * 36864, window=window)
+        r = check_against_oracle(wl, tc)
+        assert r.plan.cpu_count == [0] and sum(1 for e in r.log if e[3] == 4) >= 4      # write-backs
+        tc.close()
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5, 7, 8, 9, 11])
+def test_single_group_traces_with_few_or_no_host_buffers(seed, tmp_path):
+    # one group only and a host budget between nothing and a third: most evictions go to the
+    # file and come back from it a few steps later, whatever the launch settings
+    rng = np.random.default_rng(900 + seed)
+    wl = W.random_workload(700 + seed, n_tensors=int(rng.integers(6, 90)), n_steps=int(rng.integers(10, 120)),
+                           max_per_step=int(rng.integers(1, 5)),
+                           sizes=[(33000,), (512, 1024), (16, 17, 31, 4096), (70001, 262144 + 48, 1024)][seed % 4],
+                           hbm_frac=float(rng.choice([0.0, 0.1, 0.3])), host_frac=float(rng.choice([0.0, 0.1, 0.3])),
+                           two_groups=False, n_iterations=int(rng.integers(1, 4)), perturb_one_in=int(rng.choice([0, 6])))
+    big = (int(wl.tensor_bytes.max()) + 4095) // 4096 * 4096
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=int(rng.choice([2, 8])) * big,
+                     window=[None, 5, 64][seed % 3], io_writers=(int(rng.integers(0, 4)), int(rng.integers(0, 4))),
+                     busy=bool(seed % 2))
+    r = check_against_oracle(wl, tc)
+    assert r.bytes_file_write > 0 and r.bytes_file_read > 0
+    tc.close()
