@@ -450,6 +450,25 @@ def test_bytes_conserved_and_invariants_on_random_traces(seed):
     assert wl.no_prefetch == (not any(e[2] == o.POST for e in r.log))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_invariants_with_one_group_and_few_or_no_host_buffers(seed):
+    # no host buffer under the cache for some or all classes: evictions go straight to the file
+    # tier whatever the tensor's final location, and come back from it
+    wl = W.random_workload(300 + seed, n_tensors=40 + 7 * seed, n_steps=70, max_per_step=1 + seed % 4,
+                           sizes=((33000,), (512, 1024), (16, 17, 31, 4096), (512, 4096, 100, 33000))[seed % 4],
+                           hbm_frac=(0.0, 0.1, 0.3)[seed % 3], host_frac=(0.0, 0.1)[seed % 2], two_groups=False,
+                           n_iterations=2, perturb_one_in=(0 if seed % 2 else 6))
+    pay = lambda t: W.workload_payload(wl, t)
+    r = o.replay_workload(wl, payload=pay, check=check_state)
+    assert r.bytes_file_write > 0 and r.bytes_file_read > 0
+    if seed % 2 == 0:          # no host buffer at all: GPU-final tensors too leave for the file tier
+        assert any(e[3] == o.WRITEBACK and r.pl.final[e[4]] != o.NVME for e in r.log)
+    for t in range(wl.n_tensors):
+        assert np.array_equal(r.read_tensor(t), r.expected_bytes(t, pay)), t
+    meta = o.replay_workload(wl)
+    assert meta.log == r.log and meta.cur == r.cur
+
+
 def test_metadata_and_full_bytes_agree_on_a_small_transformer_trace():
     wl = W.config(0, layers=8)
     pay = lambda t: W.workload_payload(wl, t)
