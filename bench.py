@@ -181,6 +181,11 @@ def main():
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--merge-mib", type=int, default=1024, help="bytes merged into one migration launch")
+    ap.add_argument("--io-threads", type=int, nargs=2, default=[8, 8], metavar=("WRITERS", "READERS"),
+                    help="file-tier worker threads (the library's default is 4 and 4)")
+    ap.add_argument("--io-chunk-mib", type=int, default=0, help="file-tier chunk (default 8 MiB)")
+    ap.add_argument("--stripes", type=int, default=8, help="files the tier is striped over")
+    ap.add_argument("--staging-depth", type=int, default=16, help="staging ring, in largest tensors")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="keep the default number of working workgroups")
     ap.add_argument("--no-stall", action="store_true")
@@ -208,9 +213,14 @@ def main():
         import tempfile
         tmpdir = tempfile.TemporaryDirectory(dir="/tmp")
         big = (int(wl.tensor_bytes.max()) + 4095) // 4096 * 4096
-        # the file tier striped over four files (buffered writes are serialised per file),
-        # staging ring sixteen largest tensors deep
-        tc.bind_torch(file_path=os.path.join(tmpdir.name, "tier.bin"), staging_bytes=16 * big, stripes=4)
+        # the file tier striped over eight files (buffered writes are serialised per file), eight
+        # writer and eight reader threads, staging ring sixteen largest tensors deep
+        tc.bind_torch(file_path=os.path.join(tmpdir.name, "tier.bin"), staging_bytes=args.staging_depth * big,
+                      stripes=args.stripes)
+        if args.io_chunk_mib:
+            tc.set_io_chunk(args.io_chunk_mib << 20)
+        if args.io_threads:
+            tc.set_io_threads(*args.io_threads)
     else:
         tc.bind_torch()
     t_bind = time.perf_counter() - t_bind
@@ -341,8 +351,9 @@ def main():
             "write_GBps": file_stats["bytes_file_write"] / max(1, file_stats["file_write_ns"]),
             "read_GiB_per_step": file_stats["bytes_file_read"] / args.steps / 2**30,
             "write_GiB_per_step": file_stats["bytes_file_write"] / args.steps / 2**30,
-            "note": "buffered pread / pwrite by 4 reader and 4 writer threads behind the hook thread, file tier "
-                    "striped over 4 files on the box's disk; GB/s = bytes / time inside the calls summed over "
+            "io_threads": list(args.io_threads), "stripes": args.stripes,
+            "note": "buffered pread / pwrite by reader and writer threads behind the hook thread, file tier "
+                    "striped over several files on the box's disk; GB/s = bytes / time inside the calls summed over "
                     "the threads (per-thread rate); not part of the PCIe figure"}
     if not args.no_pack:
         pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)

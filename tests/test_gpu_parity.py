@@ -247,12 +247,12 @@ def test_file_tier_configs_at_two_layers_full_bytes(index, tmp_path):
     # optimizer states on the file tier (4), scarce host pools with spills and 1 % of the
     # accesses perturbed (5).  Schedule, counters and maps in full; bytes of every tensor
     # under 1 MiB and of a sample of the large ones over all kinds and final tiers.  Launch
-    # configuration as bench.py times it: file tier striped over four files, staging ring
-    # sixteen largest tensors deep, 4 + 4 I/O threads, launches merged up to 1 GiB.
+    # configuration as bench.py times it: file tier striped over eight files, staging ring
+    # sixteen largest tensors deep, 8 + 8 I/O threads, launches merged up to 1 GiB.
     wl = W.config(index, layers=2)
     big = int(wl.tensor_bytes.max())
     tc = run_library(wl, fill=True, window=64, merge_bytes=1 << 30, file_path=_tmpfile(tmp_path),
-                     staging_bytes=16 * ((big + 4095) // 4096 * 4096), stripes=4, tune=True)
+                     staging_bytes=16 * ((big + 4095) // 4096 * 4096), stripes=8, io_writers=(8, 8), tune=True)
     from oracle import tc_oracle as o
     r0 = o.replay_workload(wl)
     small = [t for t in range(wl.n_tensors) if wl.tensor_bytes[t] < (1 << 20)]
