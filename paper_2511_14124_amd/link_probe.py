@@ -178,6 +178,63 @@ def main():
     print(f"  400 small kernels, host waits for each   {with_side(400, True):8.2f}")
     print(f"  1600 small kernels, host waits for each  {with_side(1600, True):8.2f}", flush=True)
 
+    # the other way round: what the copies cost compute that runs beside them.  A fixed burst
+    # of bf16 GEMMs (8192 x 8192 x 8192, forty of them) on the current stream, alone and with
+    # 2 GiB crossing the link per direction meanwhile, by the zero-copy kernel or by DMA copies
+    a = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+    c = torch.empty(8192, 8192, device=dev, dtype=torch.bfloat16)
+    gb = 128 * M
+    hbm2 = torch.empty(gb, dtype=torch.uint8, device=dev)
+    pin_in = torch.empty(gb, dtype=torch.uint8).pin_memory()
+    pin_out = torch.empty(gb, dtype=torch.uint8).pin_memory()
+    side2 = torch.cuda.Stream()
+    one = np.asarray([gb], dtype=np.uint64)
+    p_h, p_i, p_o = (np.asarray([t.data_ptr()], dtype=np.uint64) for t in (hbm2, pin_in, pin_out))
+
+    def gemms(copies):
+        # time on the GEMMs' own stream (events), so that copies outlasting them do not count
+        best = 1e9
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            torch.cuda.synchronize()
+            copies()
+            e0.record()
+            for _ in range(40):
+                torch.matmul(a, b, out=c)
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e-3)
+        return best
+
+    def by_kernel(n, both):
+        def go():
+            for _ in range(n):
+                if both:
+                    T.exchange_batch(p_h, p_o, p_i, p_h, one, side.cuda_stream)
+                else:
+                    T.copy_batch(p_i, p_h, one, side.cuda_stream)
+        return go
+
+    def by_dma(n, both):
+        def go():
+            for _ in range(n):
+                with torch.cuda.stream(side):
+                    hbm2.copy_(pin_in, non_blocking=True)
+                if both:
+                    with torch.cuda.stream(side2):
+                        pin_out.copy_(hbm2, non_blocking=True)
+        return go
+
+    alone = gemms(lambda: None)
+    print(f"\nforty bf16 GEMMs of 8192^3 ({40 * 2 * 8192**3 / alone / 1e12:.0f} TFLOP/s alone, {alone * 1e3:.1f} ms), and beside them:")
+    for name, go in (("16 x 128 MiB host to HBM by the kernel", by_kernel(16, False)),
+                     ("16 x 128 MiB each way by the kernel (exchange)", by_kernel(16, True)),
+                     ("16 x 128 MiB host to HBM by DMA copies", by_dma(16, False)),
+                     ("16 x 128 MiB each way by DMA copies", by_dma(16, True))):
+        t = gemms(go)
+        print(f"  {name:50s} {t * 1e3:7.1f} ms  (+{(t - alone) * 1e3:4.1f} ms, +{100.0 * (t - alone) / alone:4.1f} %)", flush=True)
+
 
 if __name__ == "__main__":
     main()
