@@ -303,3 +303,45 @@ def test_pack_stress_shape_at_the_size_and_launch_the_bench_times(shift):
     assert bool((back[:shift] == 0x55).all()) and bool((back[total + shift:] == 0x55).all())
     # and as a whole, on the device: every byte of the image came back
     assert torch.equal(back[shift:total + shift], L["src"][shift:total + shift])
+
+
+def test_pack_and_copy_inside_a_captured_graph():
+    # the stand-alone movers only launch kernels on the caller's stream (the copy's ticket counters
+    # come from the stream-ordered allocator and are cleared by a kernel), so a caller may capture
+    # them; every replay, with eager work and synchronisation between the replays, must give
+    # what the eager call gives
+    rng = np.random.default_rng(3)
+    sizes = [4096, 100, 33000, 16384 * 2 + 48, 7, 12288]
+    nb = np.asarray(sizes, dtype=np.uint64)
+    src_off, src_total = _layout(rng, sizes, [0, 3, 16])
+    slab_off, slab_total = _layout(rng, sizes, [0, 5])
+    src = _dev(rng.integers(0, 256, size=src_total + 16, dtype=np.uint8))
+    ptrs = _dev((src_off + np.uint64(src.data_ptr())).astype(np.int64))
+    d_nb, d_off = _dev(nb.astype(np.int64)), _dev(slab_off.astype(np.int64))
+    slab = torch.zeros(slab_total, dtype=torch.uint8, device="cuda:0")
+    copy_dst = torch.zeros(src_total + 16, dtype=torch.uint8, device="cuda:0")
+    seg = (np.asarray([src.data_ptr()], dtype=np.uint64), np.asarray([copy_dst.data_ptr()], dtype=np.uint64),
+           np.asarray([(src_total + 16) // 16 * 16], dtype=np.uint64))
+    st = torch.cuda.Stream()
+    T.copy_batch(*seg, st.cuda_stream)                      # first use on the device: outside any capture
+    st.synchronize()
+
+    def want_now():
+        tensors = [src[int(o):int(o) + int(k)].cpu().numpy() for o, k in zip(src_off, nb)]
+        return po.pack(tensors, slab_off, np.zeros(slab_total, dtype=np.uint8)), src.cpu().numpy()[: int(seg[2][0])]
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            T.pack(slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), len(sizes), slab_total, st.cuda_stream)
+            T.copy_batch(*seg, st.cuda_stream)
+    for replay in range(3):
+        src.random_(0, 255)                                 # eager work between the replays
+        slab.zero_()
+        copy_dst.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want_slab, want_copy = want_now()
+        assert np.array_equal(slab.cpu().numpy(), want_slab), replay
+        assert np.array_equal(copy_dst.cpu().numpy()[: len(want_copy)], want_copy), replay
