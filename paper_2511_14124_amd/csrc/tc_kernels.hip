@@ -493,8 +493,17 @@ hipError_t tc_launch_decide_window(const TcDevTables &T, const TcWindowArgs &w, 
 #define MOVER_THREADS 256
 #define MOVER_UNROLL 4
 
-__device__ __forceinline__ uint4 ld16(const uint8_t *p) { return *(const uint4 *)p; }
-__device__ __forceinline__ void st16(uint8_t *p, uint4 v) { *(uint4 *)p = v; }
+// streaming accesses: nothing the mover touches is used again by it (worth 1 % on the duplex rate)
+typedef uint32_t mover_v4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld16(const uint8_t *p)
+{
+    mover_v4 v = __builtin_nontemporal_load((const mover_v4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st16(uint8_t *p, uint4 v)
+{
+    __builtin_nontemporal_store(mover_v4{v.x, v.y, v.z, v.w}, (mover_v4 *)p);
+}
 
 __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
 {
