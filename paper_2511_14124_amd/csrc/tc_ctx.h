@@ -154,6 +154,9 @@ struct tc_ctx {
     uint64_t k_launches = 0;                // migration-kernel launches so far (their parity picks the counter)
     uint32_t mover_xcc = 0, mover_xcds = 1; // where the migration kernel's workgroups work (tc_mover_topology)
     uint64_t sdma_threshold = 0;            // tensors at least this large go through the DMA engines (0: none)
+    bool dma_when_behind = false;           // ... but only while the compute stream has a backlog to hide them behind
+    hipEvent_t ev_backlog = nullptr;        // recorded on the compute stream each time units are issued
+    bool backlog_recorded = false;
     uint64_t op_id = 0;                 // copy operations issued (kernel launches and DMA copies)
     uint64_t op_done[N_STREAMS]{};      // per stream: operations known complete
     hipEvent_t op_ev[OP_RING]{};

@@ -44,6 +44,8 @@ static void release_device(tc_ctx *c)
     for (uint32_t i = 0; i < OP_RING; ++i)
         if (c->op_ev[i]) { (void)hipEventDestroy(c->op_ev[i]); c->op_ev[i] = nullptr; }
     if (c->ev_compute) { (void)hipEventDestroy(c->ev_compute); c->ev_compute = nullptr; }
+    if (c->ev_backlog) { (void)hipEventDestroy(c->ev_backlog); c->ev_backlog = nullptr; }
+    c->backlog_recorded = false;
     if (c->dstream) { (void)hipStreamDestroy(c->dstream); c->dstream = nullptr; }
     for (int i = S_H; i < N_STREAMS; ++i)
         if (c->streams[i]) { (void)hipStreamDestroy(c->streams[i]); c->streams[i] = nullptr; }
@@ -482,12 +484,25 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         if (rc == TC_OK) rc = io_wait(c, p.read_job);
         if (rc != TC_OK) return rc;
     }
+    // DMA copies are slower on the link than the kernel but hardly slow compute that runs beside
+    // them; the kernel's host reads do.  With the policy "when behind" the large units take the
+    // DMA engines only while the compute stream still has not reached the point it was at when
+    // units were last issued (a backlog to hide the copies behind), and the kernel otherwise
+    // (nothing to hide behind: the step is the link's).
+    bool dma_now = c->sdma_threshold != 0;
+    if (dma_now && c->dma_when_behind) {
+        if (!c->ev_backlog) HIP_TRY(c, hipEventCreateWithFlags(&c->ev_backlog, hipEventDisableTiming));
+        dma_now = c->backlog_recorded && hipEventQuery(c->ev_backlog) == hipErrorNotReady;
+        (void)hipGetLastError();                            // "not ready" is an answer, not an error
+        HIP_TRY(c, hipEventRecord(c->ev_backlog, compute));
+        c->backlog_recorded = true;
+    }
     struct Large { size_t unit; uint8_t *bounce; uint64_t kop; };
     std::vector<Large> large;
     std::vector<size_t> small;
     for (size_t i = 0; i < units.size(); ++i) {
         PUnit &p = units[i];
-        bool dma = c->sdma_threshold && p.u.bytes >= c->sdma_threshold && p.u.in_src;
+        bool dma = dma_now && p.u.bytes >= c->sdma_threshold && p.u.in_src;
         Large L{i, nullptr, 0};
         if (dma && p.u.out_src) {
             int rc = bounce_alloc(c, p.u.bytes, &L.bounce);
@@ -499,14 +514,30 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
     // ---- stream K: small units and the staging copies of large ones, at most TC_MOVER_MAX_UNITS per launch
     std::vector<std::pair<TcUnit, int64_t>> kunits;                // unit, index into `large` or -1-small
     for (size_t i : small) kunits.push_back({units[i].u, -1 - (int64_t)i});
-    for (size_t j = 0; j < large.size(); ++j)
-        if (large[j].bounce) {
-            TcUnit t{};
-            t.in_src = units[large[j].unit].u.out_src;
-            t.in_dst = large[j].bounce;
-            t.bytes = units[large[j].unit].u.bytes;
-            kunits.push_back({t, (int64_t)j});
+    // the outgoing halves of the large units go to their bounce blocks as device-to-device
+    // copies of the runtime, one operation for all of them: beside running compute these cost a
+    // tenth of what the same copies cost as units of the migration kernel, whose dozen
+    // workgroups stream HBM for milliseconds
+    {
+        bool any = false;
+        for (const Large &L : large) any = any || L.bounce;
+        if (any) {
+            uint64_t id;
+            int rc = begin_op(c, S_K, compute, &id);
+            if (rc != TC_OK) return rc;
+            for (Large &L : large) {
+                if (!L.bounce) continue;
+                const PUnit &p = units[L.unit];
+                if ((rc = dep(c, S_K, c->gpu_ticket[(size_t)p.gpu_y])) != TC_OK) return rc;
+                HIP_TRY(c, hipMemcpyAsync(L.bounce, p.u.out_src, p.u.bytes, hipMemcpyDeviceToDevice, c->streams[S_K]));
+                L.kop = id;
+            }
+            if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
+            for (Large &L : large)
+                if (L.bounce) c->gpu_ticket[(size_t)units[L.unit].gpu_y] = id;
+            c->last_k_op = id;
         }
+    }
     for (size_t at = 0; at < kunits.size(); at += TC_MOVER_MAX_UNITS) {
         const size_t end = std::min(kunits.size(), at + (size_t)TC_MOVER_MAX_UNITS);
         TcMoverArgs args{};
@@ -1506,6 +1537,13 @@ extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)
 {
     if (!c) return TC_E_ARG;
     c->merge_bytes = bytes;
+    return TC_OK;
+}
+
+extern "C" int tc_set_dma_policy(tc_ctx *c, int when_behind)
+{
+    if (!c) return TC_E_ARG;
+    c->dma_when_behind = when_behind != 0;
     return TC_OK;
 }
 

@@ -57,7 +57,7 @@ class _ParamRef:
 
 class ParamCache:
     def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
-                 fused_sgd_lr: Optional[float] = None):
+                 fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None):
         import torch
         self.torch = torch
         self.model = model
@@ -65,6 +65,9 @@ class ParamCache:
         self.host_bytes = host_bytes
         self.align = align
         self.fused_sgd_lr = fused_sgd_lr                  # plain SGD applied in the backward post-hook
+        # parameters of at least this many bytes travel as DMA-engine copies instead of through the
+        # zero-copy kernel: slower on the link, but compute running beside them is hardly slowed
+        self.dma_threshold = dma_threshold
         # leaf modules: those that own parameters directly
         self.mods = [m for m in model.modules() if any(True for _ in m.parameters(recurse=False))]
         self.params: List = []
@@ -249,6 +252,9 @@ class ParamCache:
         tc.plan_schedule()
         tc.bind_torch()
         tc.tune_mover()                                   # the regions are still empty: measure the workgroup count
+        if self.dma_threshold:
+            tc.set_dma_threshold(int(self.dma_threshold))
+            tc.set_dma_policy(True)                       # only while there is compute to hide the copies behind
         for t, p in enumerate(self.params):
             tc.load_tensor(t, p.detach().cpu().contiguous().view(torch.uint8).numpy().reshape(-1))
             p.data = torch.empty(0, dtype=self._dtype[t], device=p.device)

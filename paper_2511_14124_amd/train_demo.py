@@ -80,6 +80,8 @@ def main(argv=None):
                     help="Adam on the CPU, its fp32 states in a two-tier cache (host memory over a file)")
     ap.add_argument("--state-cache", type=float, default=0.5, help="host cache as a fraction of the state bytes")
     ap.add_argument("--threads", type=int, default=8, help="PyTorch CPU threads for the CPU update")
+    ap.add_argument("--dma-kib", type=int, default=0,
+                    help="parameters of at least this many KiB travel as DMA-engine copies (0: all through the kernel)")
     ap.add_argument("--fused-sgd", action="store_true",
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
     args = ap.parse_args(argv)
@@ -130,7 +132,8 @@ def main(argv=None):
     # ---- parameters in the tensor cache
     torch.manual_seed(0)
     model = build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
-    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None)
+    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None,
+                    dma_threshold=(args.dma_kib << 10) or None)
     pc.profile(lambda: iteration(model))
     pc.install()
     pc.tc.set_oplog(False, True)
@@ -167,7 +170,8 @@ def main(argv=None):
                           "d2h_GiB_per_step": (s1["bytes_d2h"] - s0["bytes_d2h"]) / n_counted / 2**30,
                           "h2d_GBps_over_the_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n_counted / t_off / 1e9,
                           "hook_calls_per_step": 4 * len(pc.mods) + (0 if args.fused_sgd else 2 * len(pc.params)),
-                          "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters"},
+                          "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters",
+                          "dma_copies_from_KiB": args.dma_kib or None},
         "final_parameters_equal_resident_training": bool(same),
         "note": "parameters only are managed (gradients and activations stay resident); plain SGD; hooks drive "
                 "tc_migrate_step one call at a time",
@@ -245,7 +249,7 @@ def cpu_adam_demo(args, torch, T):
 
     # ---- parameters through the HBM cache, states through the two-tier cache
     model = make_model()
-    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache))
+    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache), dma_threshold=(args.dma_kib << 10) or None)
     assert [p.numel() for p in pc.params] == elems         # the same parameter order in both runs
     tmpdir = tempfile.TemporaryDirectory(prefix="tc_states_")
     state_bytes = 12 * sum(elems)

@@ -27,7 +27,7 @@ def compare_logs(got, want):
 
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
                 busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False, direct=False,
-                io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False):
+                io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False, dma_when_behind=False):
     """Replays every iteration of wl through the library; returns the context.
 
     window None: one tc_migrate_step call per hook (the hook-driven interface);
@@ -53,6 +53,7 @@ def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_b
         tc.set_merge_bytes(merge_bytes)
     if dma_threshold is not None:
         tc.set_dma_threshold(dma_threshold)
+        tc.set_dma_policy(dma_when_behind)
     if window is not None:
         tc.set_replay_window(window)
     if fill and not null_mover:

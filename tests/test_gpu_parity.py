@@ -157,6 +157,22 @@ def test_merging_hook_calls_into_launches_keeps_every_byte(merge_bytes, tmp_path
     tc.close()
 
 
+@pytest.mark.parametrize("busy", [False, True], ids=["idle_compute", "busy_compute"])
+def test_dma_copies_only_behind_a_compute_backlog_keep_every_byte(busy, tmp_path):
+    # with the policy "when behind" the path a large tensor takes (DMA engines or the kernel)
+    # changes from launch to launch with the state of the compute stream; schedule and bytes do not
+    wl = _random(4)
+    if busy:
+        wl.compute_ns = np.full_like(wl.compute_ns, 200000)
+    for window in (None, 16):
+        tc = run_library(wl, file_path=_tmpfile(tmp_path, f"p{window}.bin"), staging_bytes=2 << 20, window=window,
+                         dma_threshold=1 << 10, dma_when_behind=True, busy=busy)
+        check_against_oracle(wl, tc)
+        st = tc.cache_stats()
+        assert busy or st["dma_copies"] == 0 or st["mover_launches"] > 0
+        tc.close()
+
+
 @pytest.mark.parametrize("threshold", [1 << 16, 1 << 20])
 def test_dma_engine_path_keeps_every_byte(threshold, tmp_path):
     # tensors at or above the threshold leave through an HBM bounce block and two

@@ -42,7 +42,8 @@ def test_random_workloads_under_random_settings(block, tmp_path):
                         mover=(int(rng.choice([1, 8, 12, 64, 300])), int(rng.choice([4096, 16384, 65536, 1 << 20]))),
                         busy=bool(rng.integers(0, 2)), io_writers=(int(rng.integers(0, 5)), int(rng.integers(0, 5))),
                         stripes=int(rng.choice([1, 1, 2, 4])), io_chunk=int(rng.choice([1 << 16, 1 << 17, 8 << 20])),
-                        ahead=[None, 0, 1, 3, 16, 256][int(rng.integers(0, 6))], host_tier=host_tier)
+                        ahead=[None, 0, 1, 3, 16, 256][int(rng.integers(0, 6))], host_tier=host_tier,
+                        dma_when_behind=bool(seed % 2))
         try:
             o.replay_workload(wl)
         except o.CapacityError:                           # literal Alg. 2 below a step's working set
