@@ -409,7 +409,9 @@ int tc_set_replay_window(tc_ctx *ctx, uint32_t steps);
 
 /* Tensors of at least `bytes` bytes move as DMA-engine copies (hipMemcpyAsync
  * on two side streams, one per direction), smaller ones in the migration
- * kernel's batched launch.  0 (default) = everything in the kernel. */
+ * kernel's batched launch.  0 (default) = everything in the kernel; setting 0
+ * after another value waits for the copies in flight and gives the side
+ * streams and the bounce block back. */
 int tc_set_dma_threshold(tc_ctx *ctx, uint64_t bytes);
 
 /* When the tensors above the DMA threshold take the DMA engines: always

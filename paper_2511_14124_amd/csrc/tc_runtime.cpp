@@ -1585,6 +1585,19 @@ extern "C" int tc_set_dma_threshold(tc_ctx *c, uint64_t bytes)
         c->bounce_bytes = std::min<uint64_t>(std::max<uint64_t>(4 * largest, 64ull << 20), 2048ull << 20);
         HIP_TRY(c, hipMalloc((void **)&c->bounce, c->bounce_bytes));
     }
+    if (!bytes && c->bounce) {
+        // back to the kernel alone: the side streams and the bounce ring go again (an idle
+        // stream of ours is not harmless, see above)
+        int rc = tc_synchronize(c);
+        if (rc != TC_OK) return rc;
+        for (int i = S_H; i < N_STREAMS; ++i)
+            if (c->streams[i]) { HIP_TRY(c, hipStreamDestroy(c->streams[i])); c->streams[i] = nullptr; }
+        HIP_TRY(c, hipFree(c->bounce));
+        c->bounce = nullptr;
+        c->bounce_bytes = 0;
+        c->bounce_q.clear();
+        c->bounce_head = 0;
+    }
     c->sdma_threshold = bytes;
     return TC_OK;
 }

@@ -38,6 +38,7 @@ copies are the library's kernels.
 
 from __future__ import annotations
 
+import time
 from typing import Callable, Dict, List, Optional, Tuple
 
 import numpy as np
@@ -283,6 +284,30 @@ class ParamCache:
                     update(t, p)
                 self.tc.migrate_step(k, T.POST, one, rw, stream)
                 k += 1
+
+    def autotune_dma(self, step: Callable[[], None], threshold: int = 64 << 10, steps: int = 2) -> Optional[int]:
+        """Which path suits this training loop: `step()` (one whole training step, end_iteration
+        included) is timed `steps` times after a first one with every large parameter through the
+        zero-copy kernel, then with those of at least `threshold` bytes as DMA copies while the
+        compute stream has a backlog; the faster setting stays.  The steps are ordinary training
+        steps.  Returns the threshold kept (None: the kernel alone)."""
+        torch = self.torch
+        best = None
+        for thr in (0, int(threshold)):
+            self.tc.set_dma_threshold(thr)
+            self.tc.set_dma_policy(True)
+            step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            if best is None or dt < best[0]:
+                best = (dt, thr)
+        self.tc.set_dma_threshold(best[1])
+        self.dma_threshold = best[1] or None
+        return self.dma_threshold
 
     def sgd_step(self, lr: float):
         """Plain SGD through the cache."""

@@ -82,6 +82,8 @@ def main(argv=None):
     ap.add_argument("--threads", type=int, default=8, help="PyTorch CPU threads for the CPU update")
     ap.add_argument("--dma-kib", type=int, default=0,
                     help="parameters of at least this many KiB travel as DMA-engine copies (0: all through the kernel)")
+    ap.add_argument("--dma-auto", action="store_true",
+                    help="let the first six steps decide between the kernel alone and DMA copies from 64 KiB")
     ap.add_argument("--fused-sgd", action="store_true",
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
     args = ap.parse_args(argv)
@@ -124,6 +126,8 @@ def main(argv=None):
             for p in model.parameters():
                 p.add_(p.grad, alpha=-args.lr)
 
+    for _ in range(6 if args.dma_auto else 0):             # as many steps as the tuning of the cached run takes
+        resident_step()
     t_res = timed(resident_step)
     want = [p.detach().cpu().clone() for p in model.parameters()]
     del model
@@ -152,6 +156,7 @@ def main(argv=None):
             s0 = pc.tc.cache_stats()
         cached_step()
 
+    kept = pc.autotune_dma(cached_step) if args.dma_auto else ((args.dma_kib << 10) or None)
     t_off = timed(cached_step_counted)                     # as many steps as the resident run: one warm-up, then timed
     pc.tc.synchronize()
     s1 = pc.tc.cache_stats()
@@ -171,7 +176,7 @@ def main(argv=None):
                           "h2d_GBps_over_the_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n_counted / t_off / 1e9,
                           "hook_calls_per_step": 4 * len(pc.mods) + (0 if args.fused_sgd else 2 * len(pc.params)),
                           "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters",
-                          "dma_copies_from_KiB": args.dma_kib or None},
+                          "dma_copies_from_KiB": (kept >> 10) if kept else None, "chosen_by_timing": bool(args.dma_auto)},
         "final_parameters_equal_resident_training": bool(same),
         "note": "parameters only are managed (gradients and activations stay resident); plain SGD; hooks drive "
                 "tc_migrate_step one call at a time",

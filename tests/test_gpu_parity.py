@@ -698,3 +698,26 @@ def test_single_group_traces_with_few_or_no_host_buffers(seed, tmp_path):
     r = check_against_oracle(wl, tc)
     assert r.bytes_file_write > 0 and r.bytes_file_read > 0
     tc.close()
+
+
+def test_dma_path_switched_on_and_off_between_iterations(tmp_path):
+    # the side streams and the bounce ring come and go with tc_set_dma_threshold; whatever path
+    # an iteration's copies took, schedule and bytes are the oracle's
+    wl = _random(6)
+    wl.iterations = [wl.iterations[0]] * 5
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch(file_path=_tmpfile(tmp_path), staging_bytes=2 << 20)
+    for t in range(wl.n_tensors):
+        tc.load_tensor(t, W.workload_payload(wl, t))
+    cs = torch.cuda.Stream()
+    for i, steps in enumerate(wl.iterations):
+        tc.set_dma_threshold((0, 1 << 10, 0, 1 << 16, 1 << 10)[i])
+        tc.set_dma_policy(i == 4)
+        if i % 2:
+            tc.replay_iteration_c(steps, cs.cuda_stream)
+        else:
+            tc.replay_iteration(steps, cs.cuda_stream)
+    tc.synchronize()
+    check_against_oracle(wl, tc)
+    assert tc.cache_stats()["dma_copies"] > 0
+    tc.close()

@@ -156,3 +156,13 @@ def test_a_parameter_that_returns_in_another_buffer_is_read_from_there_in_the_ba
         buffers.setdefault(t, set()).add(ptr)
     assert any(len(v) > 1 for v in buffers.values())       # some parameter did change buffers
     pc.close()
+
+
+def test_train_demo_chooses_its_copy_path_by_timing():
+    # six steps time the kernel alone against DMA copies behind a compute backlog and the faster
+    # setting stays; whichever it is, training equals resident training bit for bit
+    from paper_2511_14124_amd import train_demo
+    out = train_demo.main(["--layers", "2", "--d-model", "128", "--heads", "4", "--vocab", "512", "--batch", "2",
+                           "--seq", "64", "--steps", "2", "--cache", "0.4", "--dma-auto", "--fused-sgd"])
+    assert out["final_parameters_equal_resident_training"]
+    assert out["through_cache"]["chosen_by_timing"] and out["through_cache"]["dma_copies_from_KiB"] in (None, 64)
