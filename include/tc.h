@@ -415,13 +415,13 @@ int tc_set_replay_window(tc_ctx *ctx, uint32_t steps);
 int tc_set_dma_threshold(tc_ctx *ctx, uint64_t bytes);
 
 /* When the tensors above the DMA threshold take the DMA engines: always
- * (when_behind = 0, the default), or only while the compute stream has a
- * backlog, that is, has not yet reached the point it was at when copies were
- * last issued (when_behind = 1).  The kernel is faster on the link, but its
- * reads of host memory slow compute that runs beside it, which DMA copies
- * hardly do: with this policy copies hide behind compute where there is some
- * and use the faster path where the step is the link's.  Decisions and bytes
- * never depend on the path taken. */
+ * (when_behind = 0, the default), or only while there is compute to hide them
+ * behind (when_behind = 1): the compute stream has not yet reached one of the
+ * last few points at which copies were issued, and no copies issued at a point
+ * it has passed are still unfinished (that would mean the step waits for the
+ * link).  The kernel is faster on the link, but its reads of host memory slow
+ * compute that runs beside it, which DMA copies hardly do.  Decisions and
+ * bytes never depend on the path taken. */
 int tc_set_dma_policy(tc_ctx *ctx, int when_behind);
 
 /* Time spent inside migration work since the last call, measured with HIP

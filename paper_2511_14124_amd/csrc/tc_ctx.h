@@ -155,8 +155,11 @@ struct tc_ctx {
     uint32_t mover_xcc = 0, mover_xcds = 1; // where the migration kernel's workgroups work (tc_mover_topology)
     uint64_t sdma_threshold = 0;            // tensors at least this large go through the DMA engines (0: none)
     bool dma_when_behind = false;           // ... but only while the compute stream has a backlog to hide them behind
-    hipEvent_t ev_backlog = nullptr;        // recorded on the compute stream each time units are issued
-    bool backlog_recorded = false;
+    // the last few times units were issued: where the compute stream was (an event) and the
+    // newest copy operation issued then
+    struct IssuePoint { hipEvent_t ev = nullptr; uint64_t op = 0; bool used = false; };
+    IssuePoint issue_ring[8];
+    uint32_t issue_next = 0;
     uint64_t op_id = 0;                 // copy operations issued (kernel launches and DMA copies)
     uint64_t op_done[N_STREAMS]{};      // per stream: operations known complete
     hipEvent_t op_ev[OP_RING]{};

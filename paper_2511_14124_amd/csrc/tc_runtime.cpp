@@ -44,8 +44,11 @@ static void release_device(tc_ctx *c)
     for (uint32_t i = 0; i < OP_RING; ++i)
         if (c->op_ev[i]) { (void)hipEventDestroy(c->op_ev[i]); c->op_ev[i] = nullptr; }
     if (c->ev_compute) { (void)hipEventDestroy(c->ev_compute); c->ev_compute = nullptr; }
-    if (c->ev_backlog) { (void)hipEventDestroy(c->ev_backlog); c->ev_backlog = nullptr; }
-    c->backlog_recorded = false;
+    for (auto &pt : c->issue_ring) {
+        if (pt.ev) (void)hipEventDestroy(pt.ev);
+        pt = tc_ctx::IssuePoint{};
+    }
+    c->issue_next = 0;
     if (c->dstream) { (void)hipStreamDestroy(c->dstream); c->dstream = nullptr; }
     for (int i = S_H; i < N_STREAMS; ++i)
         if (c->streams[i]) { (void)hipStreamDestroy(c->streams[i]); c->streams[i] = nullptr; }
@@ -490,12 +493,25 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
     // units were last issued (a backlog to hide the copies behind), and the kernel otherwise
     // (nothing to hide behind: the step is the link's).
     bool dma_now = c->sdma_threshold != 0;
+    tc_ctx::IssuePoint *point = nullptr;
     if (dma_now && c->dma_when_behind) {
-        if (!c->ev_backlog) HIP_TRY(c, hipEventCreateWithFlags(&c->ev_backlog, hipEventDisableTiming));
-        dma_now = c->backlog_recorded && hipEventQuery(c->ev_backlog) == hipErrorNotReady;
-        (void)hipGetLastError();                            // "not ready" is an answer, not an error
-        HIP_TRY(c, hipEventRecord(c->ev_backlog, compute));
-        c->backlog_recorded = true;
+        // Of the last few issue points: one the compute stream has passed while its copies are
+        // still not done means the copies lag (the step is the link's: take the kernel); one the
+        // compute stream has not reached yet means there is a backlog to hide DMA copies behind.
+        bool copies_lag = false, compute_behind = false;
+        for (auto &pt : c->issue_ring) {
+            if (!pt.used) continue;
+            const bool reached = hipEventQuery(pt.ev) == hipSuccess;
+            (void)hipGetLastError();                        // "not ready" is an answer, not an error
+            if (!reached) { compute_behind = true; continue; }
+            if (poll_op(c, pt.op)) pt.used = false;         // both sides are past it
+            else copies_lag = true;
+        }
+        dma_now = compute_behind && !copies_lag;
+        point = &c->issue_ring[c->issue_next++ % 8];
+        if (!point->ev) HIP_TRY(c, hipEventCreateWithFlags(&point->ev, hipEventDisableTiming));
+        HIP_TRY(c, hipEventRecord(point->ev, compute));
+        point->used = false;                                // until its newest copy is known (below)
     }
     struct Large { size_t unit; uint8_t *bounce; uint64_t kop; };
     std::vector<Large> large;
@@ -633,6 +649,10 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 0;
         if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 0;
         if (p.out_staging) c->wb_pending[p.out_tensor] = 0;
+    }
+    if (point) {
+        point->op = c->op_id;
+        point->used = true;
     }
     units.clear();
     c->deferred_bytes = 0;
