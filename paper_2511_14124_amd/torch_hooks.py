@@ -14,6 +14,10 @@ the C-ABI library:
         pc.sgd_step(lr)                                   # parameters pass through the cache once more
         pc.end_iteration()
 
+`ParamCache(..., dma_threshold=65536)` sends the larger parameters through the DMA engines
+while there is compute to hide the copies behind (the zero-copy kernel is faster on the link but
+slows the compute that runs beside it); `autotune_dma(step)` lets a few training steps choose.
+
 With `ParamCache(..., fused_sgd_lr=lr)` the update of a module's parameters is
 applied in its backward post-hook instead, while they are still in their cache
 buffers: no third pass, a third less traffic; `sgd_step` is then not called.
