@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtc.so")
-SOURCES = ["tc_planner.cpp", "tc_runtime.cpp", "tc_io.cpp", "tc_movers.cpp", "tc_kernels.hip"]
+SOURCES = ["tc_planner.cpp", "tc_runtime.cpp", "tc_dispatch.cpp", "tc_io.cpp", "tc_movers.cpp", "tc_kernels.hip"]
 
 
 def build(verbose: bool = True) -> str:

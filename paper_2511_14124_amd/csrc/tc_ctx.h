@@ -223,7 +223,7 @@ static inline int fail(tc_ctx *c, int code, const std::string &msg)
             return fail((c), TC_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));        \
     } while (0)
 
-// ---- copy operations (tc_runtime.cpp) ----
+// ---- copy operations (tc_dispatch.cpp) ----
 int tc_wait_op(tc_ctx *c, uint64_t id);        // block the host until copy operation `id` has completed
 
 // ---- file tier (tc_io.cpp) ----
@@ -235,6 +235,31 @@ int io_check(tc_ctx *c);                       // a worker's failure, as TC_E_IO
 bool io_done(tc_ctx *c, const JobSet &r);
 int io_wait(tc_ctx *c, JobSet &r);             // wait for the jobs of one request, then forget them
 int io_wait_all(tc_ctx *c);
+// ---- addresses of pool buffers ------------------------------------------------
+static inline uint8_t *gpu_addr(const tc_ctx *c, uint32_t s, uint32_t k)
+{
+    return c->hbm + c->pools.hbm_off[s] + (uint64_t)k * c->pools.stride[s];
+}
+static inline uint8_t *cpu_addr(const tc_ctx *c, uint32_t s, uint32_t k)
+{
+    return c->pinned + c->pools.host_off[s] + (uint64_t)k * c->pools.stride[s];
+}
+
+// Every kernel launch and every DMA copy is one operation with an id and an event in
+// a ring.  An id older than the ring has completed by construction.
+static inline bool op_complete(const tc_ctx *c, uint64_t id)
+{
+    if (id == 0 || c->op_id - id >= OP_RING) return true;
+    return id <= c->op_done[c->op_stream[id % OP_RING]];
+}
+
+// tc_dispatch.cpp
+int wait_op(tc_ctx *c, uint64_t id);                 // block the host until operation `id` has completed
+int timed_begin(tc_ctx *c, int kind, hipEvent_t *t0);
+int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes);
+int flush_deferred(tc_ctx *c, hipStream_t compute);  // issue whatever units are prepared
+int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step, int phase, hipStream_t compute);
+
 // after: writes that must have finished before the request starts (may be nullptr)
 int io_submit(tc_ctx *c, uint32_t t, uint8_t *mem, bool read, uint64_t op, int S, JobSet *set,
               const JobSet *after = nullptr);
