@@ -787,6 +787,7 @@ hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t s
 #define PACK_CAND 32
 typedef uint32_t pack_v4 __attribute__((ext_vector_type(4)));
 struct __attribute__((packed, aligned(1))) pack_u16 { pack_v4 v; };   // 16 bytes at any address
+struct __attribute__((packed, aligned(1))) pack_u4 { uint32_t v; };   // 4 bytes at any address
 
 // A tensor at an odd address (pack).  A 128-bit load at an address that is a multiple of 4
 // runs at nearly the aligned rate, one at an odd address does not.  So an interior vector of
@@ -800,6 +801,20 @@ __device__ __forceinline__ pack_v4 pack_join(pack_v4 lo, uint32_t hi, uint32_t r
     // v_alignbyte_b32: the low dword of {first, second} >> 8 r; r = 0 returns lo unchanged
     return pack_v4{__builtin_amdgcn_alignbyte(lo.y, lo.x, r), __builtin_amdgcn_alignbyte(lo.z, lo.y, r),
                    __builtin_amdgcn_alignbyte(lo.w, lo.z, r), __builtin_amdgcn_alignbyte(hi, lo.w, r)};
+}
+
+// The same for stores (unpack).  An interior vector of a piece whose tensor lies at an odd
+// address is written as the 16 bytes at g - r: the last r bytes of the slab vector before it
+// (held by the lane before this one; loaded by the first lane of a wave) and the first 16 - r
+// of its own.  Its last r bytes are the first of the next interior vector's store; behind the
+// last interior vector comes the piece's last whole vector, written where it lies, and that
+// lane also writes the dword before it.  Bytes written twice get the same value both times.
+// pack_join_before returns bytes 4 - r .. 20 - r of {before, v}; r = 1 .. 3.
+__device__ __forceinline__ pack_v4 pack_join_before(uint32_t before, pack_v4 v, uint32_t r)
+{
+    const uint32_t q = 4 - r;
+    return pack_v4{__builtin_amdgcn_alignbyte(v.x, before, q), __builtin_amdgcn_alignbyte(v.y, v.x, q),
+                   __builtin_amdgcn_alignbyte(v.z, v.y, q), __builtin_amdgcn_alignbyte(v.w, v.z, q)};
 }
 
 // dst and src agree modulo 16; any address space mix (global/LDS); len <= PACK_TILE,
@@ -1091,9 +1106,11 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
     // address pairs first (table look-ups), then every load, then every store.  The slab
     // side is always 16-byte aligned; the tensor side is wherever the tensor is (the
     // hardware takes 128-bit global accesses at any byte address, at 91-97 % of the
-    // aligned rate, which beats realigning through LDS).
+    // aligned rate when the address is a multiple of 4, which beats realigning through
+    // LDS; interior vectors at odd addresses are moved as the dwords around them).
     uint8_t *ga[VEC];
-    uint32_t shift = 0;                                     // two bits per vector: its r (0: read where it is)
+    uint32_t shift = 0;                                     // two bits per vector: its r (0: moved where it is)
+    uint32_t extra = 0;                                     // unpack: this lane also writes the dword before vector k
     uint32_t p = 0;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
@@ -1101,13 +1118,17 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
         while (p < n_p && tab_e[wave][p] <= x) ++p;
         const bool in = p < n_p && tab_b[wave][p] <= x && x + 16 <= tab_e[wave][p];
         ga[k] = in ? tab_g[wave][p] + x : nullptr;
-        if (in && !unpack && tab_b[wave][p] + 16 <= x && x + 32 <= tab_e[wave][p])
-            shift |= (uint32_t)((uintptr_t)ga[k] & 3) << (2 * k);
+        if (in) {
+            const uint32_t r = (uint32_t)((uintptr_t)ga[k] & 3);
+            const bool behind = x + 32 <= tab_e[wave][p];
+            if (tab_b[wave][p] + 16 <= x && behind) shift |= r << (2 * k);
+            else if (unpack && r && !behind && tab_b[wave][p] + 32 <= x) extra |= 1u << k;   // the vector before is interior
+        }
     }
     // does the next lane hold the next vector of the same piece, read the same way?  (its first
     // dword is then the one behind this lane's sixteen bytes)
     uint32_t from_next = 0;
-    if (__ballot(shift != 0) != 0) {
+    if (!unpack && __ballot(shift != 0) != 0) {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             const uintptr_t mine = (uintptr_t)ga[k];
@@ -1132,27 +1153,50 @@ __global__ __launch_bounds__(PACK_THREADS) __attribute__((amdgpu_waves_per_eu(8,
         if (ga[k]) {
             if (unpack) {
                 v[k] = __builtin_nontemporal_load((const pack_v4 *)(slab + x));
+                // x - 16 is a whole vector of the same piece, so x - 4 lies inside this tile
+                if (lane == 0 && (r || ((extra >> k) & 1))) hi[k] = __builtin_nontemporal_load((const uint32_t *)(slab + x - 4));
             } else {
                 v[k] = __builtin_nontemporal_load(&((const pack_u16 *)(ga[k] - r))->v);
                 if (r && !((from_next >> k) & 1)) hi[k] = __builtin_nontemporal_load((const uint32_t *)(ga[k] - r + 16));
             }
         }
     }
-    if (__ballot(from_next != 0) != 0) {
+    if (unpack) {
+        if (__ballot((shift | extra) != 0) != 0) {
+            // the lane before this one holds the slab vector before this one (every lane that asks
+            // has a whole vector of its piece there); lanes that do not ask never look at hi
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            const uint32_t nx = (uint32_t)__shfl_down((int)v[k].x, 1, WAVE);
-            if ((from_next >> k) & 1) hi[k] = nx;
+            for (int k = 0; k < VEC; ++k) {
+                const uint32_t pv = (uint32_t)__shfl_up((int)v[k].w, 1, WAVE);
+                if (lane != 0) hi[k] = pv;
+            }
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                const uint32_t r = (shift >> (2 * k)) & 3;
+                if (r) v[k] = pack_join_before(hi[k], v[k], r);
+            }
         }
-    }
+    } else {
+        if (__ballot(from_next != 0) != 0) {
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) v[k] = pack_join(v[k], hi[k], (shift >> (2 * k)) & 3);
+            for (int k = 0; k < VEC; ++k) {
+                const uint32_t nx = (uint32_t)__shfl_down((int)v[k].x, 1, WAVE);
+                if ((from_next >> k) & 1) hi[k] = nx;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) v[k] = pack_join(v[k], hi[k], (shift >> (2 * k)) & 3);
+    }
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         const uint64_t x = t0 + ((uint64_t)tid + (uint64_t)k * PACK_THREADS) * 16;
         if (ga[k]) {
-            if (unpack) __builtin_nontemporal_store(v[k], &((pack_u16 *)ga[k])->v);
-            else __builtin_nontemporal_store(v[k], (pack_v4 *)(slab + x));
+            if (unpack) {
+                __builtin_nontemporal_store(v[k], &((pack_u16 *)(ga[k] - ((shift >> (2 * k)) & 3)))->v);
+                if ((extra >> k) & 1) __builtin_nontemporal_store(hi[k], &((pack_u4 *)(ga[k] - 4))->v);
+            } else {
+                __builtin_nontemporal_store(v[k], (pack_v4 *)(slab + x));
+            }
         }
     }
     if (!ragged) return;
