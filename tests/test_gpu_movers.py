@@ -44,7 +44,10 @@ PACK_CASES = [
     ("wide_exactly_256_pieces", [64] * 256 + [16384] + [64] * 257, [0], [0]),
     # more pieces than that: staged in LDS, piece after piece
     ("beyond_wide", [20] * 2000 + [16384] + [3] * 700, [0, 2], [0, 1]),
-    # aligned and misaligned pieces mixed, tile by tile
+    # tensors at odd addresses holding two to a few whole vectors of the slab: where a piece's interior
+    # vectors (moved as the aligned dwords around them) begin and end, for every address modulo 4
+    ("odd_addresses_few_vectors", [1024, 48, 2048, 64, 4096, 80, 96, 3072, 112, 128, 1500, 33, 144, 160] * 5,
+     [1, 2, 3, 5, 6, 7], [0, 0, 16]),
     ("mixed", [4096] * 9 + [100] + [4096] * 7 + [8192, 33, 16384, 16384], [0], [0]),
 ]
 
