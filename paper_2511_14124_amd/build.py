@@ -31,22 +31,7 @@ def build(verbose: bool = True) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     build_c_example(verbose)
-    build_probe(verbose)
     return LIB
-
-
-def build_probe(verbose: bool = True) -> str:
-    """The stand-alone probe of the host link by XCD (csrc/link_xcd_probe.hip): a program of
-    its own, on the HIP runtime only."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = os.path.join(HERE, "link_xcd_probe.bin")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
-           os.path.join(CSRC, "link_xcd_probe.hip"), "-o", out]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return out
 
 
 def build_c_example(verbose: bool = True) -> str:
