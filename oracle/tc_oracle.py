@@ -28,9 +28,19 @@ this file against the paper's two worked examples (Sec. 3.4.1 and 3.4.2),
 Alg. 1/2 closed forms, a single-class closed form, exhaustive search on tiny
 traces and step-by-step invariants.
 
+What the paper and the mathematics do not fix, and what stands in for them:
+the prefetch table, the dictionary and the per-step maxima are pinned by a
+hand-written trace; the end-of-iteration moves by "every displaced tensor
+moves exactly once, nothing else moves" (any order satisfying it is a correct
+restore; the order itself is a reading); keeping a finished tensor of another
+size by Sec. 3.4.1 (nothing goes to NVMe while GPU and CPU hold the model; the
+literal alternative spills); the "by this call" rules are shown to decide
+nothing on the worked examples and the unperturbed configurations.
+
 Parity unpinned (fixed only by the readings stated here, plus invariants):
-victim tie-breaks, the demand-miss path, the order of end-of-iteration moves,
-the dirty rule for file-tier tensors, and Alg. 2 with the working-set floor.
+victim tie-breaks, the demand-miss path, which of several valid
+end-of-iteration orders is taken, the dirty rule for file-tier tensors, and
+Alg. 2 with the working-set floor beyond its invariants and one hand example.
 """
 
 from __future__ import annotations
@@ -46,7 +56,7 @@ INF = 0xFFFFFFFF                     # "never used again"
 NONE = 0xFFFFFFFF                    # no tensor / no slot
 
 GPU, CPU, NVME = 0, 1, 2             # tiers
-PRE, POST, END, END_CPU = 0, 1, 2, 3 # phases of the op log (END: two hook calls)
+PRE, POST, END, END_CPU = 0, 1, 2, 3 # phases of the op log (END: two hook calls, END_CPU: a third)
 R_FLAG, W_FLAG = 1, 2
 
 # op codes of the op log
@@ -656,35 +666,50 @@ class Replay:
     def end_iteration(self) -> None:
         """Every tensor goes back to its final location (Sec. 3.2.1).
 
-        Reading: two hook calls.  In the first, class by class (ascending),
-        every GPU-final tensor that is elsewhere comes back, in placement
-        order, into the lowest free GPU buffer or else in place of the
-        lowest-id resident tensor whose final location is not the GPU (the two
-        swap).  In the second, CPU-final tensors sitting on the file tier
-        return to the lowest free host buffer, again class by class in
-        placement order.  GPU-designated marks are cleared and the cursor
-        returns to row 0.
+        Reading: the text gives no order.  The order taken moves every
+        displaced tensor exactly once and no other tensor at all, so that
+        restoring never writes a tensor to NVMe that GPU and CPU have room
+        for (Sec. 3.4.1).  Three hook calls:
+
+        1. class by class (ascending), GPU-final tensors sitting in host
+           buffers come back, in placement order, into the lowest free GPU
+           buffer or else in place of the lowest-id resident tensor whose
+           final location is not the GPU.  That guest takes the host buffer
+           the incoming tensor leaves (the two swap) or, if NVMe-final, goes
+           to its file extent.
+        2. GPU-final tensors on the file tier come back the same way; a
+           CPU-final guest now finds a free host buffer, because every
+           GPU-final tensor has left the host pool.
+        3. CPU-final tensors on the file tier return to the lowest free host
+           buffer, class by class in placement order.
+
+        (Taking the tensors of calls 1 and 2 in one pass would make a CPU-final
+        guest displaced by a tensor from the file tier spill a host tensor
+        while GPU-final tensors still hold host buffers: that tensor would move
+        twice.)  GPU-designated marks are cleared and the cursor returns to
+        row 0.
         """
         p = self.p
         step = p.n_steps
         bound = p.n_rows
         n_c = len(p.count)
         members = [[t for t in self.pl.order if p.class_of[t] == s] for s in range(n_c)]
-        self.call += 1
-        for s in range(n_c):
-            for u in members[s]:
-                if self.pl.final[u] != GPU or self.cur[u] == GPU:
-                    continue
-                y = self._lowest_free(self.gpu_owner[s], self.gpu_freed[s])
-                v = NONE
-                if y == NONE:
-                    guests = [x for x in self.gpu_owner[s]
-                              if x != NONE and self.pl.final[x] != GPU and self.moved[x] != self.call]
-                    if not guests:
+        for source in (CPU, NVME):
+            self.call += 1
+            for s in range(n_c):
+                for u in members[s]:
+                    if self.pl.final[u] != GPU or self.cur[u] != source:
                         continue
-                    v = min(guests)
-                    y = self.gslot[v]
-                self._exchange(v, u, y, step, END, PREFETCH, bound)
+                    y = self._lowest_free(self.gpu_owner[s], self.gpu_freed[s])
+                    v = NONE
+                    if y == NONE:
+                        guests = [x for x in self.gpu_owner[s]
+                                  if x != NONE and self.pl.final[x] != GPU and self.moved[x] != self.call]
+                        if not guests:
+                            continue
+                        v = min(guests)
+                        y = self.gslot[v]
+                    self._exchange(v, u, y, step, END, PREFETCH, bound)
         self.call += 1
         for s in range(n_c):
             for u in members[s]:
