@@ -51,8 +51,8 @@ extern "C" {
 
 #define TC_PRE      0   /* pre-hook: residency check + demand fetch */
 #define TC_POST     1   /* post-hook: Alg. 3 over the tensors that finished */
-#define TC_END      2   /* end of iteration, first call: GPU-final tensors return */
-#define TC_END_CPU  3   /* end of iteration, second call: CPU-final tensors return from the file tier */
+#define TC_END      2   /* end of iteration, first two calls: GPU-final tensors return, from host buffers and then from the file tier */
+#define TC_END_CPU  3   /* end of iteration, third call: CPU-final tensors return from the file tier */
 
 #define TC_OP_DEMAND    0   /* miss: tensor fetched into a GPU buffer by the pre-hook */
 #define TC_OP_PREFETCH  1   /* tensor fetched ahead of use (Alg. 3), or returned home at iteration end */
@@ -284,7 +284,11 @@ int tc_migrate_step(tc_ctx *ctx, uint32_t step, int phase,
                     void *compute_stream, void **dev_ptrs_out);
 
 /* End of an iteration (Sec. 3.2.1): every tensor goes back to its final location,
- * the cursor returns to row 0. */
+ * the cursor returns to row 0.  Every displaced tensor moves exactly once and no
+ * other tensor moves: GPU-final tensors return from host buffers first (swapping
+ * places with the guests in their class), then GPU-final tensors return from the
+ * file tier, then CPU-final tensors return from the file tier; nothing is
+ * spilled on the way. */
 int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
 
 /* Stand-in for the module's kernels in a replay: on compute_stream, XORs the

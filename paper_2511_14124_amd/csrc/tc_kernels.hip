@@ -204,10 +204,11 @@ __device__ void decide_pre(DecideCtx &c, const TcStepArgs &a)
         const bool res = mine && T.cur[t] == TC_GPU;
         const uint64_t mk = __ballot(res);
         if ((uint32_t)__popcll(mk) == a.n) {
-            if (mine) {
-                if (a.rw[c.lane] & TC_W) T.dirty[t] = 1;
-                c.out->slots[c.lane] = T.gslot[t];
-            }
+            // the dirty marks are scheduler state a later call of the same launch reads on every
+            // lane: like every other state store, each lane makes all of them itself
+            for (uint32_t i = 0; i < a.n; ++i)
+                if (a.rw[i] & TC_W) T.dirty[a.ids[i]] = 1;
+            if (mine) c.out->slots[c.lane] = T.gslot[t];
             if (c.lane == 0) { c.out->hits = a.n; c.out->misses = 0; c.out->fails = 0; }
             return;
         }
@@ -305,48 +306,55 @@ __device__ void decide_post(DecideCtx &c, const TcStepArgs &a)
     T.scalars[0] = cursor;
 }
 
-// end of iteration: every tensor goes back to its final location (Sec. 3.2.1)
+// End of iteration: every tensor goes back to its final location (Sec. 3.2.1), each displaced
+// tensor in one move and no other tensor at all.  Three hook calls: GPU-final tensors come home
+// from host buffers, then GPU-final tensors come home from the file tier (a CPU-final guest they
+// displace then finds a free host buffer, since no GPU-final tensor holds one any more), then
+// CPU-final tensors return from the file tier.
 __device__ void decide_end(DecideCtx &c)
 {
     const TcDevTables &T = c.T;
     c.bound = T.n_rows;
-    // first call: GPU-final tensors come home, class by class, placement order
-    for (uint32_t s = 0; s < T.n_classes; ++s) {
-        const uint32_t gb = T.gpu_base[s], gc = T.gpu_count[s];
-        const uint32_t mb = T.member_ptr[s], me = T.member_ptr[s + 1];
-        uint32_t i = mb;
-        while (i < me) {
-            // next member that is GPU-final and elsewhere, 64 members per ballot
-            uint32_t j = i + c.lane;
-            bool want = false;
-            if (j < me) {
-                uint32_t u = T.members[j];
-                want = T.final_tier[u] == TC_GPU && T.cur[u] != TC_GPU;
-            }
-            uint64_t mk = __ballot(want);
-            if (!mk) { i += WAVE; continue; }
-            i += (uint32_t)__ffsll((long long)mk) - 1;
-            const uint32_t u = T.members[i];
-            i++;
-            uint32_t y = lowest_free(c, T.gpu_owner + gb, T.gpu_freed + gb, gc);
-            uint32_t v = NONE;
-            if (y == NONE) {
-                uint32_t best = NONE;                      // lowest-id guest
-                for (uint32_t k = c.lane; k < gc; k += WAVE) {
-                    uint32_t x = T.gpu_owner[gb + k];
-                    if (x == NONE || T.final_tier[x] == TC_GPU || T.moved[x] == c.call) continue;
-                    best = x < best ? x : best;
+    // first and second call: GPU-final tensors come home, class by class, placement order
+    for (uint32_t source = TC_CPU; source <= TC_NVME; ++source) {
+        if (source == TC_NVME) c.call++;
+        for (uint32_t s = 0; s < T.n_classes; ++s) {
+            const uint32_t gb = T.gpu_base[s], gc = T.gpu_count[s];
+            const uint32_t mb = T.member_ptr[s], me = T.member_ptr[s + 1];
+            uint32_t i = mb;
+            while (i < me) {
+                // next member that is GPU-final and on the tier this call serves, 64 members per ballot
+                uint32_t j = i + c.lane;
+                bool want = false;
+                if (j < me) {
+                    uint32_t u = T.members[j];
+                    want = T.final_tier[u] == TC_GPU && T.cur[u] == source;
                 }
-                uint64_t r = wave_max_u64((uint64_t)(NONE - best));
-                best = NONE - (uint32_t)r;
-                if (best == NONE) continue;
-                v = best;
-                y = T.gslot[v];
+                uint64_t mk = __ballot(want);
+                if (!mk) { i += WAVE; continue; }
+                i += (uint32_t)__ffsll((long long)mk) - 1;
+                const uint32_t u = T.members[i];
+                i++;
+                uint32_t y = lowest_free(c, T.gpu_owner + gb, T.gpu_freed + gb, gc);
+                uint32_t v = NONE;
+                if (y == NONE) {
+                    uint32_t best = NONE;                      // lowest-id guest
+                    for (uint32_t k = c.lane; k < gc; k += WAVE) {
+                        uint32_t x = T.gpu_owner[gb + k];
+                        if (x == NONE || T.final_tier[x] == TC_GPU || T.moved[x] == c.call) continue;
+                        best = x < best ? x : best;
+                    }
+                    uint64_t r = wave_max_u64((uint64_t)(NONE - best));
+                    best = NONE - (uint32_t)r;
+                    if (best == NONE) continue;
+                    v = best;
+                    y = T.gslot[v];
+                }
+                exchange(c, v, u, y, TC_OP_PREFETCH);
             }
-            exchange(c, v, u, y, TC_OP_PREFETCH);
         }
     }
-    // second call: CPU-final tensors on the file tier return to host buffers
+    // third call: CPU-final tensors on the file tier return to host buffers
     c.call++;
     c.phase = TC_END_CPU;
     for (uint32_t s = 0; s < T.n_classes; ++s) {
