@@ -498,6 +498,21 @@ int tc_pack(void *slab, const void *const *ptrs, const uint64_t *bytes,
 int tc_unpack(const void *slab, void *const *ptrs, const uint64_t *bytes,
               const uint64_t *slab_off, uint32_t n, uint64_t total_bytes, const uint32_t *tile_first, void *stream);
 
+/* Pack (unpack = 0) or unpack (unpack != 0) for callers that cannot allocate
+ * and have no workspace to bring: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same kernels as tc_pack /
+ * tc_unpack with an index, but the tile index is rebuilt by every call in a
+ * device array of the library's own (1 MiB per GPU, held until the process
+ * ends), so the call takes no tile_first and calls no allocator of any kind.
+ * The array bounds the slab: total_bytes above TC_PACK_STATIC_MAX_BYTES is
+ * refused with TC_E_CAPACITY and nothing is launched.  All arguments as for
+ * tc_pack.  Asynchronous on stream.  Every call on a GPU uses that GPU's one
+ * array: calls that may overlap on one GPU (different streams or threads)
+ * race on it and must be ordered by the caller. */
+#define TC_PACK_STATIC_MAX_BYTES (4ull << 30)
+int tc_pack_static(void *slab, const void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
+                   uint32_t n, uint64_t total_bytes, int unpack, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

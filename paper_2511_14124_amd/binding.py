@@ -134,6 +134,7 @@ def load_library(path: str = LIB_PATH):
         "tc_pack_index": (i32, [vp, u32, u64, vp, vp]),
         "tc_pack": (i32, [vp, vp, vp, vp, u32, u64, vp, vp]),
         "tc_unpack": (i32, [vp, vp, vp, vp, u32, u64, vp, vp]),
+        "tc_pack_static": (i32, [vp, vp, vp, vp, u32, u64, i32, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -491,5 +492,16 @@ def unpack(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, t
            tile_first_dev: int = 0):
     rc = lib().tc_unpack(slab_ptr or None, ptrs_dev or None, bytes_dev or None, off_dev or None, n, total,
                          tile_first_dev or None, stream or None)
+    if rc:
+        raise TcError(rc)
+
+
+PACK_STATIC_MAX_BYTES = 4 << 30
+
+
+def pack_static(slab_ptr: int, ptrs_dev: int, bytes_dev: int, off_dev: int, n: int, total: int, unpack_: bool = False,
+                stream: int = 0):
+    rc = lib().tc_pack_static(slab_ptr or None, ptrs_dev or None, bytes_dev or None, off_dev or None, n, total,
+                              1 if unpack_ else 0, stream or None)
     if rc:
         raise TcError(rc)

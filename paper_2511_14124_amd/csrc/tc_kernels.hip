@@ -1252,3 +1252,56 @@ hipError_t tc_launch_pack(void *slab, const void *const *ptrs, const uint64_t *b
                        (uint8_t *const *)ptrs, bytes, slab_off, n, total, unpack, tile_first);
     return hipGetLastError();
 }
+
+// ===========================================================================
+// Pack / unpack for callers that cannot allocate (code under HIP graph capture,
+// serving loops, harnesses that forbid hipMalloc): the tile index, which tc_pack
+// takes as a workspace argument, lives in a file-scope device array instead.
+//
+// In host code the array's name is only a stand-in for the symbol; the address a
+// kernel can use is asked for once per device (hipGetSymbolAddress with that
+// device current; every GPU holds its own copy at its own address) and kept.
+// Every call on a GPU shares that GPU's array.  Nothing in it has to start at
+// zero: the index kernel writes every entry the pack kernel of the same call
+// reads, in stream order.  Calls that overlap on one GPU (two streams, two
+// threads) race on it.
+// ===========================================================================
+#define PACK_STATIC_TILES (TC_PACK_STATIC_MAX_BYTES / PACK_TILE)
+static __device__ __align__(256) uint32_t scratch[PACK_STATIC_TILES];     // 1 MiB per GPU, held until the process ends
+
+static hipError_t pack_static_scratch(uint32_t **out)
+{
+    static std::mutex mu;
+    static uint32_t *ptr[64];                               // per device, nullptr until asked for
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = (uint32_t *)p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
+extern "C" int tc_pack_static(void *slab, const void *const *ptrs, const uint64_t *bytes, const uint64_t *slab_off,
+                              uint32_t n, uint64_t total, int unpack, void *stream)
+{
+    if (total > TC_PACK_STATIC_MAX_BYTES) return TC_E_CAPACITY;          // the index would not fit the array
+    if (n == 0 || total == 0) return TC_OK;
+    if (!slab || !ptrs || !bytes || !slab_off) return TC_E_ARG;
+    if ((uintptr_t)slab & 15) return TC_E_ARG;
+    uint32_t *index = nullptr;
+    if (pack_static_scratch(&index) != hipSuccess) return TC_E_HIP;
+    const uint64_t tiles = tc_pack_tile_count(total);
+    if (tiles > PACK_STATIC_TILES) return TC_E_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    if (tc_launch_pack_index(slab_off, n, total, index, s) != hipSuccess) return TC_E_HIP;
+    if (tc_launch_pack(slab, ptrs, bytes, slab_off, n, total, unpack ? 1 : 0, index, s) != hipSuccess) return TC_E_HIP;
+    return TC_OK;
+}

@@ -24,6 +24,31 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), n
 
 
+def test_the_device_array_of_the_allocation_free_entry_point_is_visible_to_the_loader():
+    # tc_pack_static asks the runtime for the address of a file-scope device array by the
+    # name the host code registered.  The runtime finds it only if the GPU code object
+    # exports that name; an array the compiler left with local binding (it does, for one
+    # marked `used`) makes the runtime abort the process at the first call.
+    import subprocess
+    import tempfile
+    tools = "/opt/rocm/llvm/bin"
+    if not all(os.path.exists(os.path.join(tools, t)) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf")):
+        pytest.skip("LLVM binary tools not installed")
+    obj = os.path.join(ROOT, "paper_2511_14124_amd", "csrc", "tc_kernels.o")
+    if not os.path.exists(obj):
+        pytest.skip("object file of the kernels not kept by this build")
+    with tempfile.TemporaryDirectory() as d:
+        fat, co = os.path.join(d, "fat.bin"), os.path.join(d, "k.co")
+        subprocess.check_call([os.path.join(tools, "llvm-objcopy"), "--dump-section", ".hip_fatbin=" + fat, obj,
+                               os.path.join(d, "copy.o")])
+        subprocess.check_call([os.path.join(tools, "clang-offload-bundler"), "--type=o", "--unbundle",
+                               "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", "--input=" + fat, "--output=" + co])
+        table = subprocess.check_output([os.path.join(tools, "llvm-readelf"), "--dyn-syms", "-W", co], text=True)
+    rows = [ln.split() for ln in table.splitlines() if ln.strip().endswith("scratch")]
+    assert rows, "the code object exports no symbol for the array"
+    assert all(r[3] == "OBJECT" and r[4] == "GLOBAL" and int(r[2]) == (4 << 30) // 16384 * 4 for r in rows), rows
+
+
 def _oracle_plan(wl):
     st, te, rw, _ = wl.events()
     p = o.profile(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw)
