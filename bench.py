@@ -3,23 +3,27 @@
 
 A "step" is one replayed training iteration of the workload: every module's
 pre-hook (residency + demand fetch), stand-in compute (stamps of written
-tensors), post-hook (Alg. 3/4 decisions + one migration launch) and the
-end-of-iteration restore.  The workload is configuration 2 of the five
-(1.3B GPT-shaped trace with activation checkpoints, 19.95 GiB of tensors,
-2.99 GiB HBM cache), resident in its tiers (HBM region + pinned host region)
-before the timed region starts.
+tensors), post-hook (Alg. 3/4 decisions + migration launches) and the
+end-of-iteration restore.  The workload of the headline line is configuration
+3 of the five at full size (7B Llama-shaped trace: 1525 tensors, 100.4 GiB,
+40 GiB HBM cache, 60.6 GiB of pinned host pools), the largest configuration one
+GPU machine holds whole; its tensors are resident in their tiers before the timed
+region starts.
 
 Prints ONE JSON line: host->HBM migration GB/s (whole replay, zero modelled
-compute), with hit rate, stall per step (second, modelled-compute replay),
-the migration kernel's roofline against the measured host-link peak, the
-pack/unpack kernel's roofline against HBM peak, and the CPU oracle timed on
-this machine's host cores.
+compute) with hit rate and stall per step (a second, modelled-compute replay,
+split into forward / backward / optimizer steps), the migration kernel's
+roofline against the measured host-link peak, the same figures for all five
+configurations (`per_config`; 4 and 5 at the depth the box holds, the
+arithmetic in the line), the pack/unpack kernel's roofline against HBM peak,
+and the CPU oracle timed on this machine's host cores.
 """
 
 import argparse
 import json
 import os
 import sys
+import tempfile
 import time
 
 import numpy as np
@@ -27,13 +31,24 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+GiB = 1 << 30
 
 # HBM-side traffic per algorithmic byte, from the hardware-counter runs summarised under
 # profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy).
 # bench.py cannot collect counters itself; it applies the measured ratio to this run's bytes.
 TRAFFIC_RATIO = {"tc_mover_kernel": (1.0000 + 1.0000) / 2.0,          # (fetch + write) / (2 x link bytes)
                  "tc_pack_kernel": (1.0234 + 1.0000) / 2.0}           # (fetch + write) / (2 x payload)
+TRAFFIC_SOURCE = "counter ratios of profiles/ (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE) applied to this run's bytes"
 
+
+
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+# --------------------------------------------------------------------------------------
+# pack / unpack
+# --------------------------------------------------------------------------------------
 
 def pack_stress_layout(torch, total_bytes=4 << 30, shift=0):
     """The pack stress shape: the workloads' small-tensor size histogram repeated
@@ -58,9 +73,11 @@ def pack_stress_layout(torch, total_bytes=4 << 30, shift=0):
             "d_off": torch.from_numpy(off.astype(np.int64)).to(dev)}
 
 
-def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
-    """Pack kernel on the stress shape, one launch.  Returns (GB/s algorithmic =
-    2 x payload / time, ms, payload bytes, segments)."""
+def bench_pack(torch, T, total_bytes=4 << 30, reps=6, shift=0, unpack=False):
+    """Pack kernel on the stress shape, one launch per measurement.  The first launch is a
+    warm-up and is not counted; the figure is the median of the `reps` launches after it
+    (sustained), the best of them is given beside it.  Returns (GB/s algorithmic =
+    2 x payload / median time, median ms, best ms, payload bytes, segments)."""
     dev = torch.device("cuda:0")
     L = pack_stress_layout(torch, total_bytes, shift)
     n, total, src, slab, ptrs, nbt, offt = L["n"], L["total"], L["src"], L["slab"], L["ptrs"], L["d_bytes"], L["d_off"]
@@ -76,16 +93,21 @@ def bench_pack(torch, T, total_bytes=4 << 30, reps=5, shift=0, unpack=False):
     index = torch.empty(T.pack_tiles(total), dtype=torch.int32, device=dev)
     T.pack_index(offt.data_ptr(), n, total, index.data_ptr(), st)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    best = 1e30
+    times = []
     for _ in range(reps + 1):
         e0.record()
         (T.unpack if unpack else T.pack)(slab.data_ptr(), ptrs.data_ptr(), nbt.data_ptr(), offt.data_ptr(), n, total,
                                          st, index.data_ptr())
         e1.record()
         torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1))
-    return 2.0 * total / (best * 1e-3) / 1e9, best, total, n
+        times.append(e0.elapsed_time(e1))
+    sustained = float(np.median(times[1:]))
+    return 2.0 * total / (sustained * 1e-3) / 1e9, sustained, float(min(times[1:])), total, n
 
+
+# --------------------------------------------------------------------------------------
+# the box
+# --------------------------------------------------------------------------------------
 
 def host_description():
     """The machine's host side: CPU model, logical CPUs, and the CPU share the container may use."""
@@ -107,11 +129,182 @@ def host_description():
     return {"cpu": model, "logical_cpus": os.cpu_count(), "cpu_quota": quota}
 
 
-def plain_memcpy_rate(threads=None, mib_each=256, reps=4):
+def usable_cores():
+    q = host_description()["cpu_quota"]
+    n = os.cpu_count() or 1
+    return max(1, min(n, int(q))) if q else n
+
+
+# --------------------------------------------------------------------------------------
+# one configuration
+# --------------------------------------------------------------------------------------
+
+def phase_split(wl, per_step_ns):
+    names = ("forward", "backward", "optimizer")
+    if wl.step_phase is None:
+        return None
+    out = {}
+    for ph, name in enumerate(names):
+        sel = wl.step_phase == ph
+        if sel.any():
+            out[name] = {"steps": int(sel.sum()), "stall_ms": float(per_step_ns[sel].sum()) / 1e6,
+                         "stall_ms_per_step": float(per_step_ns[sel].sum()) / 1e6 / int(sel.sum())}
+    return out
+
+
+def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, tier_dirs=None, direct=False):
+    """Replays one configuration and returns its figures.  steps / warmup count iterations."""
+    from paper_2511_14124_amd.box import FULL_LAYERS, is_tmpfs
+    wl = W.config(index, layers=layers)
+    wl.no_prefetch = args.no_prefetch
+    t_plan = time.perf_counter()
+    tc = T.TensorCache.from_workload(wl)   # tc_profile_order, tc_plan_pools, tc_plan_schedule
+    t_plan = time.perf_counter() - t_plan
+    t_bind = time.perf_counter()
+    tmpdirs = []
+    file_mode = None
+    if int((tc.placement["final_tier"] == T.NVME).sum()) or index >= 3:
+        big = (int(wl.tensor_bytes.max()) + 4095) // 4096 * 4096
+        # the file tier striped over `stripes` files (buffered writes are serialised per file), dealt
+        # in turn to the tier directories; staging ring sixteen largest tensors deep
+        tier_dirs = tier_dirs or ["/tmp"]
+        paths = []
+        for d in tier_dirs:
+            tmpdirs.append(tempfile.TemporaryDirectory(dir=d))
+        for k in range(args.stripes):
+            paths.append(os.path.join(tmpdirs[k % len(tmpdirs)].name, f"tier.{k}.bin"))
+        tc.bind_torch(stripe_paths=paths, staging_bytes=args.staging_depth * big, direct=direct)
+        if args.io_chunk_mib:
+            tc.set_io_chunk(args.io_chunk_mib << 20)
+        if direct and not args.io_chunk_mib:
+            # a device that is read and written directly wants few large sequential requests on this
+            # box's virtual disk: one request per tensor, one thread per direction
+            tc.set_io_chunk(((big + (1 << 20) - 1) >> 20) << 20)
+            tc.set_io_threads(1, 1)
+        elif args.io_threads:
+            tc.set_io_threads(*args.io_threads)
+        file_mode = {"io": "O_DIRECT (page cache bypassed)" if direct else "buffered (through the page cache)",
+                     "directories": [{"dir": d, "in_memory": is_tmpfs(d)} for d in tier_dirs],
+                     "stripes": args.stripes}
+    else:
+        tc.bind_torch()
+    t_bind = time.perf_counter() - t_bind
+    if args.workgroups or args.chunk:
+        tc.set_mover(args.workgroups, args.chunk)
+    tuned_wgs = None
+    if not args.workgroups and not args.no_tune:
+        tuned_wgs = tc.tune_mover()        # the regions hold nothing yet: measure the workgroup count
+    if args.merge_mib is not None:
+        tc.set_merge_bytes(args.merge_mib << 20)
+    t_fill = time.perf_counter()
+    tc.fill_payload(0)
+    t_fill = time.perf_counter() - t_fill
+    tc.set_oplog(False, True)              # a long run does not keep 32 bytes per decision
+    cs = torch.cuda.Stream()
+    its = wl.iterations
+    log(f"config {index + 1} {wl.name}: {wl.total_bytes() / GiB:.1f} GiB in {wl.n_tensors} tensors, bound in "
+        f"{t_bind:.1f} s, filled in {t_fill:.1f} s")
+
+    for k in range(warmup):
+        tc.replay_iteration_c(its[k % len(its)], cs.cuda_stream)
+    tc.synchronize()
+    torch.cuda.synchronize()
+    s0 = tc.cache_stats()
+    tc.mover_timing(True)
+    t0 = time.perf_counter()
+    for k in range(steps):
+        tc.replay_iteration_c(its[k % len(its)], cs.cuda_stream)
+    tc.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tm = tc.mover_timing(False)
+    s1 = tc.cache_stats()
+    d = {k: s1[k] - s0[k] for k in ("bytes_h2d", "bytes_d2h", "hits", "misses", "bytes_file_read", "bytes_file_write",
+                                    "file_read_ns", "file_write_ns", "mover_launches")}
+    value = d["bytes_h2d"] / dt / 1e9
+    log(f"config {index + 1}: {value:.2f} GB/s host->HBM, {dt / steps * 1e3:.1f} ms per iteration")
+
+    res = {
+        "config": index + 1, "workload": wl.name, "layers": FULL_LAYERS[index] if layers is None else layers,
+        "full_layers": FULL_LAYERS[index], "tensors": wl.n_tensors, "total_GiB": wl.total_bytes() / GiB,
+        "hbm_cache_GiB": wl.hbm_bytes / GiB, "hook_steps_per_iteration": wl.n_steps, "iterations_timed": steps,
+        "value": value, "unit": "GB/s", "pct_of_pcie_peak_h2d": 100.0 * value / link["h2d"],
+        "d2h_GBps": d["bytes_d2h"] / dt / 1e9, "hit_rate": d["hits"] / max(1, d["hits"] + d["misses"]),
+        "ms_per_iteration": dt / steps * 1e3, "migration_launches_per_iteration": d["mover_launches"] / steps,
+        "working_workgroups": tuned_wgs or args.workgroups or 12,
+    }
+    if file_mode is not None:
+        res["file_tier"] = dict(file_mode,
+            read_GiB_per_iteration=d["bytes_file_read"] / steps / GiB,
+            write_GiB_per_iteration=d["bytes_file_write"] / steps / GiB,
+            # what the tier delivered over the replay's wall time, and the rate inside the calls
+            # (bytes / time summed over the worker threads: a per-thread figure)
+            read_GBps_over_wall=d["bytes_file_read"] / dt / 1e9, write_GBps_over_wall=d["bytes_file_write"] / dt / 1e9,
+            read_GBps_in_call=d["bytes_file_read"] / max(1, d["file_read_ns"]),
+            write_GBps_in_call=d["bytes_file_write"] / max(1, d["file_write_ns"]),
+            io_threads="1 + 1" if direct and not args.io_chunk_mib else list(args.io_threads),
+            link_time_share=(d["bytes_h2d"] / 1e9 / link["h2d"]) / dt,
+            note="link_time_share = time the host->HBM bytes alone would need at the measured one-way peak / wall "
+                 "time: what is left is file I/O (and its page-cache copies by the CPU) the schedule could not hide")
+    extra = {"tm": tm, "t_plan": t_plan, "t_bind": t_bind, "t_fill": t_fill, "dt": dt, "s1": s1, "wl": wl,
+             "tuned_wgs": tuned_wgs}
+
+    if stall:
+        steps_list = its[-1]
+
+        def stall_replay(busy_ns):
+            b0 = tc.cache_stats()
+            tc.stall_by_step(clear=True)
+            t_a = time.perf_counter()
+            tc.replay_iteration_c(steps_list, cs.cuda_stream, busy_ns=busy_ns, measure_stall=True)
+            tc.synchronize()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t_a
+            b1 = tc.cache_stats()
+            per_step = tc.stall_by_step(clear=True)
+            n_waits = max(1, b1["waits_total"] - b0["waits_total"])
+            hist = {"under_0.01ms": (b1["waits_under_10us"] - b0["waits_under_10us"]) / n_waits,
+                    "under_0.03ms": (b1["waits_under_30us"] - b0["waits_under_30us"]) / n_waits,
+                    "under_0.1ms": (b1["waits_under_100us"] - b0["waits_under_100us"]) / n_waits}
+            return (b1["stall_ns"] - b0["stall_ns"]) / 1e6 / len(steps_list), hist, wall, per_step
+
+        stall_ms, hist, _wall, per_step = stall_replay(wl.compute_ns)
+        extra["stall"] = {"stall_ms_per_step": stall_ms, "hist": hist, "by_phase": phase_split(wl, per_step)}
+        # the same with every module's modelled time stretched until an iteration computes
+        # for 1.5 x the time its migration takes: can the schedule hide the copies when
+        # there is compute to hide them behind?  Merged launches of at most 64 MiB here:
+        # a module waits for the whole launch its tensors arrive in.
+        scale = 1.5 * (dt / steps) / max(1e-9, float(wl.compute_ns.sum()) * 1e-9)
+        busy = (wl.compute_ns.astype(np.float64) * scale).astype(np.uint64)
+        tc.set_merge_bytes(64 << 20)
+        b_ms, b_hist, b_wall, b_per_step = stall_replay(busy)
+        by_phase = phase_split(wl, b_per_step)
+        if by_phase:
+            for ph, name in enumerate(("forward", "backward", "optimizer")):
+                if name in by_phase:
+                    by_phase[name]["compute_ms"] = float(busy[wl.step_phase == ph].sum()) / 1e6
+        extra["stall_balanced"] = {
+            "compute_ms_per_iteration": float(busy.sum()) / 1e6, "iteration_ms": b_wall * 1e3,
+            "stall_ms_per_step": b_ms, "share_of_tensors_waiting": b_hist, "by_phase": by_phase,
+            "note": "modelled compute stretched to 1.5 x the zero-compute iteration time, launches merged up to "
+                    "64 MiB; by_phase: the stall of the forward, backward and optimizer steps apart "
+                    "(tc_stall_by_step) beside the compute each phase has to hide copies behind"}
+    tc.close()
+    del tc
+    torch.cuda.empty_cache()
+    for td in tmpdirs:
+        td.cleanup()
+    return res, extra
+
+
+# --------------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands
+# --------------------------------------------------------------------------------------
+
+def plain_memcpy_rate(threads, mib_each=256, reps=4):
     """Beside the oracle, so that its single core is not mistaken for the host's limit: what
     plain copies between host buffers reach with one thread per core (bytes copied / time)."""
     import threading
-    threads = threads or min(16, os.cpu_count() or 1)
     n = mib_each << 20
     bufs = [(np.ones(n, dtype=np.uint8), np.zeros(n, dtype=np.uint8)) for _ in range(threads)]
     for a, b in bufs:
@@ -130,12 +323,13 @@ def plain_memcpy_rate(threads=None, mib_each=256, reps=4):
     return threads * reps * n / (time.perf_counter() - t0) / 1e9
 
 
-def cpu_baseline(W, seconds_target=15.0):
-    """The oracle, as it stands, in full-bytes mode on a bounded sample of the
-    same workload (fewer layers, same shapes); GB/s of bytes copied into its
-    HBM array over the replay's wall time."""
+def cpu_baseline(W, layers=None, iterations=2):
+    """The oracle, as it stands, in full-bytes mode on configuration 2 at full size (19.95 GiB of
+    tensors in numpy arrays; the largest configuration whose bytes the oracle moves in seconds):
+    GB/s of bytes copied into its HBM array over the replay's wall time, one core.  Beside it the
+    same copies (the oracle's own op log) carried out by one thread per core."""
     from oracle import tc_oracle as o
-    layers = 6
+    from oracle import parallel_copies as pc
     wl = W.config(1, layers=layers)
     st, te, rw, _ = wl.events()
     zeros = {}
@@ -151,30 +345,48 @@ def cpu_baseline(W, seconds_target=15.0):
                 wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload)
     t_build = time.perf_counter() - t_build            # profile, pools, placement and the initial payload copies
     t0 = time.perf_counter()
-    its = 0
-    while True:
+    for _ in range(iterations):
         for steps in wl.iterations:
             r.run_iteration(steps)
-        its += 1
-        if time.perf_counter() - t0 > seconds_target or its >= 20:
-            break
     dt = time.perf_counter() - t0
-    return {"value": r.bytes_h2d / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "plain_memcpy_all_cores_GBps": plain_memcpy_rate(),
-            "sample": f"config 2 shapes at {layers} layers ({wl.total_bytes() / 2**30:.2f} GiB of tensors), "
-                      f"{its} iterations, full-bytes mode, {dt:.1f} s",
-            "us_per_hook_step": dt / (its * wl.n_steps) * 1e6, "profile_plan_place_load_ms": t_build * 1e3}
+    one_core = r.bytes_h2d / dt / 1e9
+    n_log = len(r.log) // iterations
+    log_one = r.log[:n_log]
+    us_per_step = dt / (iterations * wl.n_steps) * 1e6
+    del r
+    # the same copies by all cores: tiers laid out alike, one iteration's op log
+    cores = usable_cores()
+    meta = o.build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
+                   wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, None)
+    tiers = pc.Tiers(meta, payload)
+    t1 = time.perf_counter()
+    moved = pc.replay_copies(tiers, log_one, cores)
+    dt_par = time.perf_counter() - t1
+    del tiers
+    return {"value": one_core, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"configuration 2 ({wl.name}) at {'full size' if layers is None else str(layers) + ' layers'}: "
+                      f"{wl.total_bytes() / GiB:.2f} GiB of tensors, {iterations} iterations in full-bytes mode, {dt:.1f} s",
+            "us_per_hook_step": us_per_step, "profile_plan_place_load_ms": t_build * 1e3,
+            "all_cores": {"value": moved / dt_par / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+                          "sample": f"the copies of one iteration of the same op log, every copy cut into {cores} "
+                                    f"slices moved by {cores} threads, {dt_par:.1f} s"},
+            "plain_memcpy_all_cores_GBps": plain_memcpy_rate(cores)}
 
+
+# --------------------------------------------------------------------------------------
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=3, help="timed iterations of the headline workload")
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=1,
-                    help="workload: index 0..4 of the five configurations (default 1 = the 1.3B GPT-shaped trace, "
-                         "the one the metric is quoted on); 3 and 4 need the file tier and --layers")
-    ap.add_argument("--layers", type=int, default=None, help="shallower model of the same shapes")
+    ap.add_argument("--config", type=int, default=2,
+                    help="headline workload: index 0..4 of the five configurations (default 2 = the 7B Llama-shaped "
+                         "trace at full size, the largest one GPU box holds whole)")
+    ap.add_argument("--layers", type=int, default=None, help="shallower model of the same shapes (configurations 4 "
+                    "and 5 default to the depth the box holds)")
+    ap.add_argument("--per-config", choices=("all", "none"), default="all",
+                    help="also replay the other four configurations and report all five (default)")
     ap.add_argument("--no-pack", action="store_true")
     ap.add_argument("--no-prefetch", action="store_true",
                     help="the paper's base variant: demand fetch only (an ablation, not the benchmark)")
@@ -185,148 +397,105 @@ def main():
                     help="file-tier worker threads (the library's default is 4 and 4)")
     ap.add_argument("--io-chunk-mib", type=int, default=0, help="file-tier chunk (default 8 MiB)")
     ap.add_argument("--stripes", type=int, default=8, help="files the tier is striped over")
+    ap.add_argument("--tier-dirs", default="/tmp", help="comma-separated directories the stripe files are dealt to")
+    ap.add_argument("--direct", action="store_true", help="open the file tier O_DIRECT (bypass the page cache)")
     ap.add_argument("--staging-depth", type=int, default=16, help="staging ring, in largest tensors")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="keep the default number of working workgroups")
     ap.add_argument("--no-stall", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: the migration path has no multi-GPU exchange step; run with --gpus 1",
-              file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (one context per GPU, no exchange step); "
+              "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
     import paper_2511_14124_amd as T
     import workloads as W
+    from paper_2511_14124_amd.box import FULL_LAYERS, box_limits, depth_the_box_holds, is_tmpfs
 
     T.load_library()                       # fails loudly if the HIP library is not built
+    from paper_2511_14124_amd.box import pinned_limit
     from paper_2511_14124_amd.link_probe import measure_link_peak
+    torch.cuda.init()
+    log(f"one process may pin {pinned_limit() / GiB:.0f} GiB of host memory here")
     link = measure_link_peak(torch)        # first: before this process holds any other stream
-    wl = W.config(args.config, layers=args.layers)
-    wl.no_prefetch = args.no_prefetch
-    t_plan = time.perf_counter()
-    tc = T.TensorCache.from_workload(wl)   # tc_profile_order, tc_plan_pools, tc_plan_schedule
-    t_plan = time.perf_counter() - t_plan
-    t_bind = time.perf_counter()
-    tmpdir = None
-    if int((tc.placement["final_tier"] == T.NVME).sum()) or args.config >= 3:
-        import tempfile
-        tmpdir = tempfile.TemporaryDirectory(dir="/tmp")
-        big = (int(wl.tensor_bytes.max()) + 4095) // 4096 * 4096
-        # the file tier striped over eight files (buffered writes are serialised per file), eight
-        # writer and eight reader threads, staging ring sixteen largest tensors deep
-        tc.bind_torch(file_path=os.path.join(tmpdir.name, "tier.bin"), staging_bytes=args.staging_depth * big,
-                      stripes=args.stripes)
-        if args.io_chunk_mib:
-            tc.set_io_chunk(args.io_chunk_mib << 20)
-        if args.io_threads:
-            tc.set_io_threads(*args.io_threads)
-    else:
-        tc.bind_torch()
-    t_bind = time.perf_counter() - t_bind
-    if args.workgroups or args.chunk:
-        tc.set_mover(args.workgroups, args.chunk)
-    tuned_wgs = None
-    if not args.workgroups and not args.no_tune:
-        tuned_wgs = tc.tune_mover()        # the regions hold nothing yet: measure the workgroup count
-    if args.merge_mib is not None:
-        tc.set_merge_bytes(args.merge_mib << 20)
-    tc.fill_payload(0)
-    cs = torch.cuda.Stream()
-    steps = wl.iterations[-1]              # (the perturbed access list for configuration 5)
+    log(f"host link: H2D {link['h2d']:.1f} D2H {link['d2h']:.1f} GB/s")
+    tier_dirs = [d for d in args.tier_dirs.split(",") if d]
 
-    for _ in range(args.warmup):
-        tc.replay_iteration_c(steps, cs.cuda_stream)
-    tc.synchronize()
-    torch.cuda.synchronize()
-    s0 = tc.cache_stats()
-    tc.mover_timing(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        tc.replay_iteration_c(steps, cs.cuda_stream)
-    tc.synchronize()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    tm = tc.mover_timing(False)
-    s1 = tc.cache_stats()
-    h2d = s1["bytes_h2d"] - s0["bytes_h2d"]
-    d2h = s1["bytes_d2h"] - s0["bytes_d2h"]
-    hits = s1["hits"] - s0["hits"]
-    misses = s1["misses"] - s0["misses"]
+    def depth_for(index, dirs):
+        if index < 3:
+            return None, None
+        limits = box_limits(torch, dirs)
+        L, rows = depth_the_box_holds(T, W, index, limits, args.staging_depth)
+        rows["box"] = {"hbm_free_GiB": limits["hbm_free"] / GiB, "host_memory_GiB": limits["host_memory"] / GiB,
+                       "pinned_limit_GiB": limits["pinned"] / GiB,
+                       "tier_dirs": [{"dir": d["dir"], "free_GiB": d["free"] / GiB, "in_memory": d["in_memory"]}
+                                     for d in limits["tier_dirs"]]}
+        return (None if L == FULL_LAYERS[index] else L), rows
 
-    # stall per step with modelled compute (not part of the timed throughput run)
-    stall_ms = None
-    wait_share = None
-    wait_hist = None
-    stall_balanced = None
+    layers, depth_rows = (args.layers, None) if args.layers is not None else depth_for(args.config, tier_dirs)
+    head, ex = run_config(torch, T, W, link, args.config, layers, args, steps=args.steps, warmup=args.warmup,
+                          stall=not args.no_stall, tier_dirs=tier_dirs, direct=args.direct)
+    if depth_rows:
+        head["depth_the_box_holds"] = depth_rows
+    wl, tm, dt = ex["wl"], ex["tm"], ex["dt"]
 
-    def stall_replay(busy_ns):
-        b0 = tc.cache_stats()
-        t_a = time.perf_counter()
-        tc.replay_iteration_c(steps, cs.cuda_stream, busy_ns=busy_ns, measure_stall=True)
-        tc.synchronize()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t_a
-        b1 = tc.cache_stats()
-        n_waits = max(1, b1["waits_total"] - b0["waits_total"])
-        hist = {"under_0.01ms": (b1["waits_under_10us"] - b0["waits_under_10us"]) / n_waits,
-                "under_0.03ms": (b1["waits_under_30us"] - b0["waits_under_30us"]) / n_waits,
-                "under_0.1ms": (b1["waits_under_100us"] - b0["waits_under_100us"]) / n_waits}
-        return (b1["stall_ns"] - b0["stall_ns"]) / 1e6 / len(steps), hist, wall
+    per_config = []
+    if args.per_config == "all":
+        # configurations 4 and 5 twice: the file tier on the box's disk (which then bounds them), and the
+        # file tier in memory (tmpfs), which shows what the schedule does when the tier keeps up
+        memory_dir = "/dev/shm" if os.path.isdir("/dev/shm") and is_tmpfs("/dev/shm") else None
+        for index in range(5):
+            if index == args.config:
+                per_config.append(head)
+                continue
+            variants = [tier_dirs]
+            if index >= 3 and memory_dir and [memory_dir] != tier_dirs and not args.direct:
+                variants.append([memory_dir])
+            for dirs in variants:
+                L, rows = depth_for(index, dirs)
+                n_it = {0: 10, 1: 3}.get(index, 1)
+                res, _ = run_config(torch, T, W, link, index, L, args, steps=n_it, warmup=1, stall=False,
+                                    tier_dirs=dirs, direct=args.direct)
+                if rows:
+                    res["depth_the_box_holds"] = rows
+                per_config.append(res)
 
-    if not args.no_stall:
-        stall_ms, wait_hist, _ = stall_replay(wl.compute_ns)
-        wait_share = wait_hist["under_0.03ms"]
-        # the same with every module's modelled time stretched until an iteration computes
-        # for 1.5 x the time its migration takes: can the schedule hide the copies when
-        # there is compute to hide them behind?  Merged launches of at most 64 MiB here:
-        # a module waits for the whole launch its tensors arrive in.
-        scale = 1.5 * (dt / args.steps) / max(1e-9, float(wl.compute_ns.sum()) * 1e-9)
-        busy = (wl.compute_ns.astype(np.float64) * scale).astype(np.uint64)
-        tc.set_merge_bytes(64 << 20)
-        b_ms, b_hist, b_wall = stall_replay(busy)
-        stall_balanced = {"compute_ms_per_iteration": float(busy.sum()) / 1e6, "iteration_ms": b_wall * 1e3,
-                          "stall_ms_per_step": b_ms, "share_of_tensors_waiting": b_hist,
-                          "note": "modelled compute stretched to 1.5 x the zero-compute iteration time, "
-                                  "launches merged up to 64 MiB"}
-    tc.close()
-    del tc
-    torch.cuda.empty_cache()
-
-    if tmpdir is not None:
-        tmpdir.cleanup()
-    file_stats = {k: s1[k] - s0[k] for k in ("bytes_file_read", "bytes_file_write", "file_read_ns", "file_write_ns")}
-
-    value = h2d / dt / 1e9
     n_launch = tm["kernel_launches"]
     launch_s = tm["kernel_ns"] * 1e-9                     # time inside migration launches (HIP events)
     achieved = tm["kernel_bytes"] / launch_s / 1e9 if launch_s else 0.0
     peak = link["h2d"] + link["d2h"]                      # both directions in use: sum of the one-way peaks
+    st = ex.get("stall")
     out = {
         "metric": "host->HBM migration GB/s (% of PCIe peak); GPU cache hit rate; stall ms/step",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": wl.name + ("" if args.layers is None else f"@{args.layers}layers"),
-                   "tensors": wl.n_tensors, "total_GiB": wl.total_bytes() / 2**30,
-                   "hbm_cache_GiB": wl.hbm_bytes / 2**30, "hook_steps_per_iteration": wl.n_steps,
+        "config": {"workload": wl.name + ("" if layers is None else f"@{layers}layers"),
+                   "tensors": wl.n_tensors, "total_GiB": wl.total_bytes() / GiB,
+                   "hbm_cache_GiB": wl.hbm_bytes / GiB, "hook_steps_per_iteration": wl.n_steps,
                    "variant": "base (no prefetching)" if args.no_prefetch else "prefetching (Alg. 3)",
-                   "mode": "zero modelled compute; every prefetch is paired with an eviction, so H2D and D2H run concurrently"},
+                   "mode": "a step = one replayed training iteration; zero modelled compute; every prefetch is paired "
+                           "with an eviction, so H2D and D2H run concurrently"},
         "paper_context": "context only, no figure for this metric: the paper reports up to 2x shorter training time and "
                          "up to 86.6x the GPU cache hit rate of offloading baselines, on NVIDIA L40S / A40 48 GB and "
                          "A100 40 GB behind PCIe 4.0 x16",
-        "one_off_costs": {"profile_order_plus_plans_ms": t_plan * 1e3, "allocate_and_bind_regions_ms": t_bind * 1e3,
+        "one_off_costs": {"profile_order_plus_plans_ms": ex["t_plan"] * 1e3,
+                          "allocate_and_bind_regions_ms": ex["t_bind"] * 1e3, "fill_payload_ms": ex["t_fill"] * 1e3,
                           "note": "the trace is given, not recorded by a dry run; the paper reports 19-119 s for "
                                   "profiling and 67-89 s for pre-allocation (its Table 7), once per training job"},
         "host": host_description(),
-        "pct_of_pcie_peak_h2d": 100.0 * value / link["h2d"],
+        "pct_of_pcie_peak_h2d": head["pct_of_pcie_peak_h2d"],
         "pcie_peak_measured_GBps": link,
-        "d2h_GBps": d2h / dt / 1e9,
-        "hit_rate": hits / max(1, hits + misses),
-        "hbm_utilisation": s1["hbm_pool_bytes"] / max(1, s1["hbm_budget"]),
-        "stall_ms_per_step": stall_ms, "share_of_tensors_waiting_under_0.03ms": wait_share,
-        "share_of_tensors_waiting": wait_hist,
-        "stall_with_compute_to_hide_behind": stall_balanced,
+        "d2h_GBps": head["d2h_GBps"],
+        "hit_rate": head["hit_rate"],
+        "hbm_utilisation": ex["s1"]["hbm_pool_bytes"] / max(1, ex["s1"]["hbm_budget"]),
+        "stall_ms_per_step": st["stall_ms_per_step"] if st else None,
+        "share_of_tensors_waiting_under_0.03ms": st["hist"]["under_0.03ms"] if st else None,
+        "share_of_tensors_waiting": st["hist"] if st else None,
+        "stall_by_phase": st["by_phase"] if st else None,
+        "stall_with_compute_to_hide_behind": ex.get("stall_balanced"),
         "modelled_compute_ms_per_iteration": float(wl.compute_ns.sum()) / 1e6,
         "decision_kernel": {"us_per_hook_call": tm["decide_ns"] / 1e3 / max(1, tm["decide_calls"]),
                             "launches": tm["decide_launches"], "hook_calls": tm["decide_calls"],
@@ -334,7 +503,9 @@ def main():
         "roofline": {"bound": "pcie", "achieved": achieved, "peak": peak, "unit": "GB/s",
                      "frac": achieved / peak if peak else None,
                      "traffic": TRAFFIC_RATIO["tc_mover_kernel"] * tm["kernel_bytes"] / max(1, n_launch),
-                     "kernel": "tc_mover_kernel", "launches": n_launch, "working_workgroups": tuned_wgs or args.workgroups or 12,
+                     "traffic_source": TRAFFIC_SOURCE,
+                     "kernel": "tc_mover_kernel", "launches": n_launch,
+                     "working_workgroups": ex["tuned_wgs"] or args.workgroups or 12,
                      "avg_launch_us": tm["kernel_ns"] / 1e3 / max(1, n_launch),
                      "algorithmic_bytes_per_launch": tm["kernel_bytes"] / max(1, n_launch),
                      "peak_published": 128.0,
@@ -345,33 +516,32 @@ def main():
                              "duplex_each = what concurrent hipMemcpyAsync H2D + D2H reach per direction in this "
                              "process; peak_published = PCIe 5.0 x16 raw, both directions"},
     }
-    if file_stats["bytes_file_read"] or file_stats["bytes_file_write"]:
-        out["file_tier"] = {
-            "read_GBps": file_stats["bytes_file_read"] / max(1, file_stats["file_read_ns"]),
-            "write_GBps": file_stats["bytes_file_write"] / max(1, file_stats["file_write_ns"]),
-            "read_GiB_per_step": file_stats["bytes_file_read"] / args.steps / 2**30,
-            "write_GiB_per_step": file_stats["bytes_file_write"] / args.steps / 2**30,
-            "io_threads": list(args.io_threads), "stripes": args.stripes,
-            "note": "buffered pread / pwrite by reader and writer threads behind the hook thread, file tier "
-                    "striped over several files on the box's disk; GB/s = bytes / time inside the calls summed over "
-                    "the threads (per-thread rate); not part of the PCIe figure"}
+    if "file_tier" in head:
+        out["file_tier"] = head["file_tier"]
+    if per_config:
+        out["per_config"] = per_config
     if not args.no_pack:
-        pack_gbs, pack_ms, pack_bytes, pack_n = bench_pack(torch, T)
-        unpack_gbs, unpack_ms, _, _ = bench_pack(torch, T, unpack=True)
-        off4_gbs, off4_ms, _, _ = bench_pack(torch, T, shift=4)
-        odd_gbs, odd_ms, _, _ = bench_pack(torch, T, shift=1)
-        odd_un_gbs, odd_un_ms, _, _ = bench_pack(torch, T, shift=1, unpack=True)
+        log("pack / unpack on the 4 GiB stress shape")
+        pack_gbs, pack_ms, pack_best, pack_bytes, pack_n = bench_pack(torch, T)
+        unpack_gbs, unpack_ms, unpack_best, _, _ = bench_pack(torch, T, unpack=True)
+        off4_gbs, off4_ms, _, _, _ = bench_pack(torch, T, shift=4)
+        odd_gbs, odd_ms, _, _, _ = bench_pack(torch, T, shift=1)
+        odd_un_gbs, odd_un_ms, _, _, _ = bench_pack(torch, T, shift=1, unpack=True)
         out["roofline_pack"] = {
             "bound": "hbm", "achieved": pack_gbs, "peak": 8000.0, "unit": "GB/s",
             "frac": pack_gbs / 8000.0, "traffic": TRAFFIC_RATIO["tc_pack_kernel"] * 2.0 * pack_bytes,
+            "traffic_source": TRAFFIC_SOURCE,
             "kernel": "tc_pack_kernel", "payload_bytes": pack_bytes, "segments": pack_n, "ms": pack_ms,
-            "unpack": {"achieved": unpack_gbs, "frac": unpack_gbs / 8000.0, "ms": unpack_ms},
+            "best_ms": pack_best,
+            "timing": "median of six launches after a first, uncounted one (sustained); best_ms = the fastest of the six",
+            "unpack": {"achieved": unpack_gbs, "frac": unpack_gbs / 8000.0, "ms": unpack_ms, "best_ms": unpack_best},
             "misaligned_variant": {"achieved": off4_gbs, "frac": off4_gbs / 8000.0, "ms": off4_ms,
                                    "note": "pack, every tensor 4 bytes off the slab's 16-byte phase"},
             "odd_shift_variant": {"achieved": odd_gbs, "frac": odd_gbs / 8000.0, "ms": odd_ms,
                                   "unpack": {"achieved": odd_un_gbs, "frac": odd_un_gbs / 8000.0, "ms": odd_un_ms},
                                   "note": "every tensor 1 byte off"}}
     if not args.no_cpu:
+        log("CPU baseline: the oracle in full-bytes mode on configuration 2")
         out["cpu_baseline"] = cpu_baseline(W)
     print(json.dumps(out))
 

@@ -305,6 +305,14 @@ int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns);
  * the calls no longer overlap with the compute stream. */
 int tc_set_stall_measurement(tc_ctx *ctx, int enable);
 
+/* Where the wait time of Sec. 4.2.2 falls within the iteration: the stall each
+ * profiled step's PRE calls have added to stall_ns since the context was bound
+ * or the counts were last cleared, so that forward, backward and optimizer
+ * steps can be told apart.  ns_out: host array of at least n_steps entries
+ * (cap says how many it holds; TC_E_CAPACITY if fewer), may be NULL; clear:
+ * reset the counts after copying them. */
+int tc_stall_by_step(tc_ctx *ctx, uint64_t *ns_out, uint32_t cap, int clear);
+
 /* Replays one whole iteration whose accesses are known up front: for every
  * step the pre-hook call, tc_emulate_compute, the post-hook call, then
  * tc_end_iteration.  step_ptr: n_steps+1 offsets into ids/rw, starting at 0

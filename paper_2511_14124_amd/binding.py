@@ -111,6 +111,7 @@ def load_library(path: str = LIB_PATH):
         "tc_end_iteration": (i32, [vp, vp]),
         "tc_emulate_compute": (i32, [vp, vp, u64]),
         "tc_set_stall_measurement": (i32, [vp, i32]),
+        "tc_stall_by_step": (i32, [vp, vp, u32, i32]),
         "tc_replay_iteration": (i32, [vp, vp, vp, vp, u32, vp, vp, i32]),
         "tc_synchronize": (i32, [vp]),
         "tc_cache_stats": (i32, [vp, C.POINTER(Stats)]),
@@ -270,13 +271,18 @@ class TensorCache:
 
     def bind_torch(self, *, staging_bytes: int = 0, file_path: Optional[str] = None, null_mover: bool = False,
                    stream=None, direct: bool = False, file_fd: Optional[int] = None, stripes: int = 1,
-                   host_tier: bool = False):
+                   host_tier: bool = False, stripe_paths: Optional[Sequence[str]] = None):
         """Allocates the regions and binds them: device memory and the streams
         come from PyTorch, the pinned regions straight from hipHostMalloc
         (PyTorch's pinned allocator rounds every request up to a power of two,
         which for a 60 GiB pool locks 64 GiB).  host_tier: the two-tier mode, the
-        fast tier a pinned host region (self.hbm then is that region)."""
+        fast tier a pinned host region (self.hbm then is that region).
+        stripe_paths: the files of the file tier named one by one (they may lie in
+        different directories or on different devices) instead of file_path and
+        file_path.1 .. file_path.(stripes-1)."""
         import torch
+        if stripe_paths:
+            file_path, stripes = stripe_paths[0], len(stripe_paths)
         mode = BIND_HOST_TIER if host_tier else 0
         if null_mover:
             self.bind_memory(0, 0, 0, 0, 0, 0, -1, 0, BIND_NULL_MOVER | mode)
@@ -306,7 +312,8 @@ class TensorCache:
         # further files the tier is striped over: file_path.1, file_path.2, ...
         self._stripe_fds = []
         for k in range(1, int(stripes) if file_path is not None and file_fd is None else 1):
-            sfd = os.open(f"{file_path}.{k}", os.O_RDWR | os.O_CREAT | (os.O_DIRECT if direct else 0), 0o600)
+            name = stripe_paths[k] if stripe_paths else f"{file_path}.{k}"
+            sfd = os.open(name, os.O_RDWR | os.O_CREAT | (os.O_DIRECT if direct else 0), 0o600)
             self._stripe_fds.append(sfd)
             os.ftruncate(sfd, int(self.plan.file_total))
             self.add_stripe(sfd)
@@ -343,6 +350,11 @@ class TensorCache:
 
     def set_stall_measurement(self, enable: bool):
         self._check(lib().tc_set_stall_measurement(self._h, int(enable)))
+
+    def stall_by_step(self, clear: bool = False) -> np.ndarray:
+        out = np.zeros(int(self.plan.n_steps), dtype=np.uint64)
+        self._check(lib().tc_stall_by_step(self._h, _ptr(out), out.size, 1 if clear else 0))
+        return out
 
     def synchronize(self):
         self._check(lib().tc_synchronize(self._h))

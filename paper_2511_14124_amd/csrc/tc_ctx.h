@@ -197,6 +197,7 @@ struct tc_ctx {
     hipStream_t last_compute = nullptr;
     uint64_t last_k_op = 0;             // newest operation issued on the migration stream
     bool measure_stall = false;         // pre-hook calls time the wait for their copies on the host
+    std::vector<uint64_t> stall_by_step; // ... and add the time each call waited to its step's entry
     // last PRE call, for tc_emulate_compute
     TcStampArgs last_pre{};
     uint32_t iteration = 0;

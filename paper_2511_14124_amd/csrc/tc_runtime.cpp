@@ -297,6 +297,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     c->cpu_ticket.assign(pl.cpu_slots, 0);
     c->gpu_pending.assign(pl.gpu_slots, 0);
     c->cpu_pending.assign(pl.cpu_slots, 0);
+    c->stall_by_step.assign(p.n_steps, 0);
     c->tensor_job.assign(n_t, JobSet{});
     c->wb_pending.assign(n_t, 0);
     c->cpu_job.assign(pl.cpu_slots, JobSet{});
@@ -509,6 +510,7 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
         }
     }
     c->stats.stall_ns += waited_ns;
+    if (waited_ns && step < c->stall_by_step.size()) c->stall_by_step[step] += waited_ns;
     return TC_OK;
 }
 
@@ -579,6 +581,18 @@ extern "C" int tc_set_stall_measurement(tc_ctx *c, int enable)
 {
     if (!c) return TC_E_ARG;
     c->measure_stall = enable != 0;
+    return TC_OK;
+}
+
+extern "C" int tc_stall_by_step(tc_ctx *c, uint64_t *ns_out, uint32_t cap, int clear)
+{
+    if (!c) return TC_E_ARG;
+    if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
+    if (ns_out) {
+        if (cap < c->stall_by_step.size()) return fail(c, TC_E_CAPACITY, "ns_out holds fewer entries than the profile has steps");
+        for (size_t k = 0; k < c->stall_by_step.size(); ++k) ns_out[k] = c->stall_by_step[k];
+    }
+    if (clear) std::fill(c->stall_by_step.begin(), c->stall_by_step.end(), 0);
     return TC_OK;
 }
 

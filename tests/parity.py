@@ -27,7 +27,8 @@ def compare_logs(got, want):
 
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
                 busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False, direct=False,
-                io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False, dma_when_behind=False):
+                io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False, dma_when_behind=False,
+                stripe_paths=None):
     """Replays every iteration of wl through the library; returns the context.
 
     window None: one tc_migrate_step call per hook (the hook-driven interface);
@@ -38,7 +39,7 @@ def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_b
     import torch
     tc = T.TensorCache.from_workload(wl)
     tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes, direct=direct,
-                  stripes=stripes, host_tier=host_tier)
+                  stripes=stripes, host_tier=host_tier, stripe_paths=stripe_paths)
     if tune and not null_mover:
         tc.tune_mover()                            # as bench.py does: the workgroup count is measured
     if ahead is not None:

@@ -906,3 +906,27 @@ def test_on_one_tensor_size_the_literal_eviction_and_the_reading_taken_agree():
     # (the worked examples have one size: there the two are the same algorithm)
     for wl in (W.example_cpu_gpu(), W.example_cpu_gpu_nvme(), W.single_class_fwd_bwd(9, 4, 5), W.single_class_sweep(8, 5)):
         assert _replay_as(_EvictWhateverTheSize, wl).log == _replay_as(o.Replay, wl).log
+
+
+# ----------------------------------------------------------------------------
+# the many-threaded copy replay the benchmark times beside the oracle moves the same bytes
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("threads", [1, 3, 8])
+def test_the_threaded_copy_replay_ends_with_the_oracles_bytes(threads):
+    from oracle import parallel_copies as pc
+    # read-only traces (no stamps): after the same ops the three tiers must hold the same bytes
+    for wl in (W.random_workload(3, n_tensors=40, n_steps=80, sizes=(512, 70001, 262144), hbm_frac=0.2, host_frac=0.3),
+               W.single_class_fwd_bwd(7, 3, 3, size=100000)):
+        wl.profile = [[(t, W.R) for (t, _a) in st] for st in wl.profile]
+        wl.iterations = [wl.profile for _ in wl.iterations]
+        pay = lambda t: W.workload_payload(wl, t)
+        full = o.replay_workload(wl, payload=pay)
+        meta = o.replay_workload(wl)
+        assert meta.log == full.log and len(full.log) > 10
+        tiers = pc.Tiers(_build(wl), pay)
+        moved = pc.replay_copies(tiers, meta.log, threads)
+        assert moved == full.bytes_h2d
+        for t in range(wl.n_tensors):
+            where = tiers.view(t, full.cur[t], full.gslot[t] if full.cur[t] == o.GPU else full.cslot[t])
+            assert np.array_equal(where, full.read_tensor(t)), t

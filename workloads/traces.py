@@ -27,6 +27,7 @@ import numpy as np
 R, W, RW = 1, 2, 3
 GROUP_16, GROUP_32 = 0, 1
 KIND_P16, KIND_G16, KIND_MASTER, KIND_M, KIND_V, KIND_CKPT = range(6)
+PHASE_FORWARD, PHASE_BACKWARD, PHASE_OPTIMIZER = range(3)
 
 GiB = 1 << 30
 VOCAB_SHARD_ROWS = 4096
@@ -52,6 +53,7 @@ class Workload:
     no_prefetch: bool = False                 # replay the paper's base variant: demand fetch only
     gaussian_p16: bool = False                # 16-bit params are fp16(N(0, 0.02))
     notes: str = ""
+    step_phase: np.ndarray | None = None      # uint8 [n_steps]: 0 forward, 1 backward, 2 optimizer sweep (None: not known)
 
     @property
     def n_tensors(self) -> int:
@@ -194,13 +196,16 @@ def _assemble(name, b: _Builder, head_modules: List[List[int]], *, ckpt_bytes: i
             bwd_ns.append(2 * ns)
     steps = fwd + bwd
     ns_all = fwd_ns + bwd_ns
+    phase = [PHASE_FORWARD] * len(fwd) + [PHASE_BACKWARD] * len(bwd)
     if with_optimizer:
         for j in range(n_p):
             steps.append([(5 * j + 1, R), (5 * j + 2, RW), (5 * j + 3, RW), (5 * j + 4, RW), (5 * j, W)])
             ns_all.append(int(16.0 * b.param_elems[j] * 2 / HBM_RATE * 1e9))
+            phase.append(PHASE_OPTIMIZER)
     wl = Workload(name=name, tensor_bytes=tb, tensor_group=tg, tensor_kind=tk, profile=steps,
                   compute_ns=np.asarray(ns_all, dtype=np.uint64),
-                  hbm_bytes=0, host_bytes=(0, 0), gaussian_p16=gaussian_p16, notes=notes)
+                  hbm_bytes=0, host_bytes=(0, 0), gaussian_p16=gaussian_p16, notes=notes,
+                  step_phase=np.asarray(phase, dtype=np.uint8))
     wl.hbm_bytes = int(hbm_bytes(wl) if callable(hbm_bytes) else hbm_bytes)
     hb = host_bytes(wl) if callable(host_bytes) else host_bytes
     wl.host_bytes = (int(hb[0]), int(hb[1]))
