@@ -208,7 +208,7 @@ class CapacityError(Exception):
 
 
 def plan_pools(p: Profile, hbm_bytes: int, host_bytes: Sequence[int], align: int = 256,
-               literal: bool = False) -> PoolPlan:
+               literal: bool = False, smallest_first: bool = False) -> PoolPlan:
     """Alg. 2 plus Step 3 of Sec. 3.3.1.
 
     The size s_i of Alg. 1/2 is the buffer size actually cut from the region
@@ -226,6 +226,15 @@ def plan_pools(p: Profile, hbm_bytes: int, host_bytes: Sequence[int], align: int
     (c_s - m_s) and memory avail - sum(m_s * s).  With every m_s = 0 the two
     agree.
 
+    `smallest_first` is not the paper's allocator but the placement it argues
+    against (Sec. 3.1 and the illustrative example of Sec. 3.3.2: the baseline
+    keeps large tensors in CPU or NVMe memory whatever their place in the
+    execution order): GPU memory beyond the floor goes to the classes in
+    ascending size, each taking as many buffers as it has tensors and the
+    memory left allows, so the smallest tensors stay on the GPU and the
+    largest live below it.  An ablation, used to state a hit-rate ratio of the
+    kind the paper reports against that baseline.
+
     Host counts are Alg. 2's second line, run once per group with that group's
     budget and its own distribution (16-bit tensors first, fp32 states after).
 
@@ -235,7 +244,16 @@ def plan_pools(p: Profile, hbm_bytes: int, host_bytes: Sequence[int], align: int
     """
     n_c = len(p.count)
     stride = [align_up(b, align) for b in p.class_bytes]
-    if literal:
+    if smallest_first:
+        gpu = [0 if literal else min(p.step_max[s], p.used[s]) for s in range(n_c)]
+        left = hbm_bytes - sum(gpu[s] * stride[s] for s in range(n_c))
+        if left < 0:
+            raise CapacityError("HBM budget below the per-step working set")
+        for s in range(n_c):                              # classes are ascending by (bytes, group)
+            more = min(p.used[s] - gpu[s], left // stride[s])
+            gpu[s] += more
+            left -= more * stride[s]
+    elif literal:
         gpu = buffer_count([(stride[s], p.used[s]) for s in range(n_c)], hbm_bytes, p.used)
     else:
         floor_ = [min(p.step_max[s], p.used[s]) for s in range(n_c)]
@@ -746,10 +764,10 @@ class Replay:
 
 
 def build(tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw, hbm_bytes, host_bytes,
-          align=256, literal=False, payload=None, prefetch=True):
+          align=256, literal=False, payload=None, prefetch=True, smallest_first=False):
     """Profile, plan, place and return a Replay ready at iteration 0."""
     p = profile(tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw)
-    plan = plan_pools(p, hbm_bytes, host_bytes, align, literal)
+    plan = plan_pools(p, hbm_bytes, host_bytes, align, literal, smallest_first)
     pl = place(p, plan)
     return Replay(p, plan, pl, payload, prefetch)
 
@@ -759,7 +777,8 @@ def replay_workload(wl, payload=None, check=None) -> Replay:
     st, te, rw, _ns = wl.events()
     r = build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
               wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload,
-              prefetch=not getattr(wl, "no_prefetch", False))
+              prefetch=not getattr(wl, "no_prefetch", False),
+              smallest_first=getattr(wl, "smallest_first", False))
     for steps in wl.iterations:
         r.run_iteration(steps, check)
     return r

@@ -930,3 +930,62 @@ def test_the_threaded_copy_replay_ends_with_the_oracles_bytes(threads):
         for t in range(wl.n_tensors):
             where = tiers.view(t, full.cur[t], full.gslot[t] if full.cur[t] == o.GPU else full.cslot[t])
             assert np.array_equal(where, full.read_tensor(t)), t
+
+
+# ----------------------------------------------------------------------------
+# the placement the paper argues against (Sec. 3.1, Sec. 3.3.2: large tensors live in CPU or NVMe
+# memory whatever their place in the execution order), by hand on nine tensors
+# ----------------------------------------------------------------------------
+
+def _nine_with_two_large(smallest_first, prefetch):
+    # tensors 1 and 2 (the first layer, needed first) are large, 3..9 small; one tensor per step,
+    # forward 1..9 then backward 9..1; GPU memory for two large and two small tensors
+    sizes = [4096, 4096] + [1024] * 7
+    steps = [[(t, W.R)] for t in range(9)] + [[(t, W.R)] for t in reversed(range(9))]
+    wl = W.traces._simple("nine_two_large", sizes, [0] * 9, steps, hbm_bytes=2 * 4096 + 2 * 1024,
+                          host_bytes=(1 << 20, 0), literal=False)
+    wl.smallest_first, wl.no_prefetch = smallest_first, not prefetch
+    return wl
+
+
+def test_smallest_first_placement_by_hand_on_nine_tensors():
+    wl = _nine_with_two_large(smallest_first=True, prefetch=False)
+    p = _profile_of(wl)
+    assert p.class_bytes == [1024, 4096] and p.step_max == [1, 1]
+    plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, smallest_first=True)
+    # one buffer per class first (5120 bytes); the other 5120 bytes go to the small class: five more
+    assert plan.gpu_count == [6, 1] and plan.cpu_count == [1, 1]
+    r = o.replay_workload(wl, check=check_state)
+    assert _tiers(r) == ({1, 3, 4, 5, 6, 7, 8}, {2, 9}, set())      # after the restore: the final locations
+    # by hand: tensor 2 misses (the large class has one buffer, held by tensor 1) and pushes tensor 1
+    # out; tensors 3-8 hit; 9 misses and replaces the small tensor used farthest ahead (3); backward:
+    # 9-4 hit, 3 misses, 2 hits, 1 misses
+    assert [(e[1], o.OP_NAMES[e[3]], e[4] + 1) for e in r.log if e[2] == o.PRE] == [
+        (1, "EVICT", 1), (1, "DEMAND", 2), (8, "EVICT", 3), (8, "DEMAND", 9),
+        (15, "EVICT", 4), (15, "DEMAND", 3), (17, "EVICT", 2), (17, "DEMAND", 1)]
+    assert (r.hits, r.misses) == (14, 4)
+    # the paper's allocator on the same memory, with its scheduler: every access a hit
+    ours = o.replay_workload(_nine_with_two_large(smallest_first=False, prefetch=True), check=check_state)
+    assert ours.plan.gpu_count == [4, 1]
+    assert (ours.hits, ours.misses) == (18, 0)
+
+
+def test_smallest_first_respects_the_budget_and_the_floor():
+    for seed in range(20):
+        wl = W.random_workload(seed, n_tensors=40, sizes=(512, 1024, 4096, 33000), hbm_frac=0.2)
+        p = _profile_of(wl)
+        a = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, smallest_first=True)
+        b = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align)
+        n_c = len(p.count)
+        assert sum(a.gpu_count[s] * a.stride[s] for s in range(n_c)) <= wl.hbm_bytes
+        for s in range(n_c):
+            assert min(p.step_max[s], p.used[s]) <= a.gpu_count[s] <= p.used[s]
+            assert a.gpu_count[s] + a.cpu_count[s] <= p.count[s]
+        # a class is short of buffers only if every smaller class is full
+        short = [s for s in range(n_c) if a.gpu_count[s] < p.used[s]]
+        if short:
+            first = short[0]
+            for s in range(n_c):
+                if a.stride[s] < a.stride[first]:
+                    assert a.gpu_count[s] == p.used[s]
+        assert sum(a.gpu_count) >= sum(b.gpu_count)          # small tensors first: at least as many buffers

@@ -51,6 +51,7 @@ class Workload:
     align: int = 256
     literal_alg2: bool = False                # Alg. 2 without the working-set floor
     no_prefetch: bool = False                 # replay the paper's base variant: demand fetch only
+    smallest_first: bool = False              # GPU buffers to the smallest tensors first (the baseline placement)
     gaussian_p16: bool = False                # 16-bit params are fp16(N(0, 0.02))
     notes: str = ""
     step_phase: np.ndarray | None = None      # uint8 [n_steps]: 0 forward, 1 backward, 2 optimizer sweep (None: not known)
