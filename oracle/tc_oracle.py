@@ -60,8 +60,8 @@ PRE, POST, END, END_CPU = 0, 1, 2, 3 # phases of the op log (END: two hook calls
 R_FLAG, W_FLAG = 1, 2
 
 # op codes of the op log
-DEMAND, PREFETCH, EVICT, RELEASE, WRITEBACK, SPILL, RESTORE, FAIL = range(8)
-OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL"]
+DEMAND, PREFETCH, EVICT, RELEASE, WRITEBACK, SPILL, RESTORE, FAIL, ALLOC = range(9)
+OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL", "ALLOC"]
 
 FILE_ALIGN = 4096
 STAMP_MAGIC = 0x10CAC4E5
@@ -336,6 +336,12 @@ def stamp16(iteration: int, step: int, tensor: int) -> np.ndarray:
     return np.asarray([STAMP_MAGIC, iteration, step, tensor], dtype="<u4").view(np.uint8).copy()
 
 
+def write_seed(iteration: int, step: int) -> int:
+    """Seed of the counter pattern a write-only access fills its tensor with when such accesses
+    are declared whole-tensor writes (see Replay): one per (iteration, step)."""
+    return 0x10000000 + iteration * 4096 + step
+
+
 def apply_stamp(buf: np.ndarray, stamp: np.ndarray) -> None:
     n = buf.shape[0]
     assert n >= 16
@@ -352,9 +358,28 @@ class Replay:
     its initial payload and the stamps it received ("metadata mode").
     """
 
-    def __init__(self, p: Profile, plan: PoolPlan, pl: Placement, payload=None, prefetch: bool = True):
+    def __init__(self, p: Profile, plan: PoolPlan, pl: Placement, payload=None, prefetch: bool = True,
+                 alloc_write_only: bool = False, pattern=None):
+        """alloc_write_only: a refinement the paper does not have.  An access that only writes
+        (a gradient in the backward pass, a checkpoint in the forward pass, the 16-bit
+        parameter in the optimizer sweep) is declared a whole-tensor write, so what the tensor
+        held before is dead and bringing it in is wasted traffic: where Alg. 3 would prefetch
+        such a tensor, or the pre-hook would fetch it on demand, it is given its GPU buffer
+        without any bytes being copied (op ALLOC).  Every decision is what it is without the
+        flag; only the copy is left out.  The stand-in for the module's kernel then fills the
+        whole tensor with the counter pattern of seed write_seed(iteration, step) instead of
+        stamping it.  `pattern(tensor, n_bytes, seed)` supplies that pattern (an input
+        generator, like `payload`).  A tensor allocated this way is undefined until its
+        write-only access really comes; on a replay that leaves the profile it may never
+        come, and then the tensor's bytes are unspecified (`undefined[t]`; reads of such
+        tensors are counted in `undefined_reads`)."""
         self.p, self.plan, self.pl = p, plan, pl
         self.prefetch = prefetch          # False: the "base" variant of Sec. 4.1.4, demand fetch only
+        self.alloc_write_only = alloc_write_only
+        self._pattern = pattern
+        self.undefined = [False] * p.n_tensors
+        self.undefined_reads = 0
+        self.whole_write: List[Optional[Tuple[int, int]]] = [None] * p.n_tensors   # (iteration, step) of the last one
         n_t, n_c = p.n_tensors, len(p.count)
         self.bytes_of = [p.class_bytes[p.class_of[t]] for t in range(n_t)]
         self.cur = list(pl.final)
@@ -417,9 +442,16 @@ class Replay:
     def read_tensor(self, t: int) -> np.ndarray:
         return self._view(t).copy()
 
-    def expected_bytes(self, t: int, payload) -> np.ndarray:
-        """Initial payload of t with every stamp it received applied."""
-        buf = np.array(payload(t), dtype=np.uint8, copy=True)
+    def expected_bytes(self, t: int, payload) -> Optional[np.ndarray]:
+        """Initial payload of t (or what its last whole-tensor write put there) with every
+        stamp it received since applied; None while the tensor's bytes are unspecified."""
+        if self.undefined[t]:
+            return None
+        if self.whole_write[t] is not None:
+            it, step = self.whole_write[t]
+            buf = np.array(self._pattern(t, self.bytes_of[t], write_seed(it, step)), dtype=np.uint8, copy=True)
+        else:
+            buf = np.array(payload(t), dtype=np.uint8, copy=True)
         for (it, step) in self.stamps[t]:
             apply_stamp(buf, stamp16(it, step, t))
         return buf
@@ -529,7 +561,7 @@ class Replay:
         s, n = self.p.class_of[u], self.bytes_of[u]
         src_tier, src_slot = self.cur[u], self.cslot[u]
         incoming = None
-        if self.full:
+        if self.full and op_in != ALLOC:
             incoming = self._view(u).copy()
         if v != NONE:
             swap = src_slot if (src_tier == CPU and self.pl.final[v] != NVME) else NONE
@@ -541,14 +573,19 @@ class Replay:
             self.cpu_owner[s][src_slot] = NONE    # "release" u's host buffer
             self.designated[s][src_slot] = False
             self.cpu_freed[s][src_slot] = self.call
-        if self.full:
-            self._gpu_view(s, y, n)[:] = incoming
-        self._emit(step, phase, op_in, u, src_tier, src_slot if src_tier == CPU else NONE, GPU, y, n)
-        if src_tier == CPU:
-            self.bytes_h2d += n
+        if op_in == ALLOC:
+            # the buffer is handed over as it is: nothing is copied, what the tensor held is dropped
+            self._emit(step, phase, ALLOC, u, src_tier, src_slot if src_tier == CPU else NONE, GPU, y, 0)
+            self.undefined[u] = True
         else:
-            self.bytes_file_read += n
-            self.bytes_h2d += n                   # file -> staging -> GPU crosses the link too
+            if self.full:
+                self._gpu_view(s, y, n)[:] = incoming
+            self._emit(step, phase, op_in, u, src_tier, src_slot if src_tier == CPU else NONE, GPU, y, n)
+            if src_tier == CPU:
+                self.bytes_h2d += n
+            else:
+                self.bytes_file_read += n
+                self.bytes_h2d += n               # file -> staging -> GPU crosses the link too
         self.cur[u], self.gslot[u], self.cslot[u] = GPU, y, NONE
         self.gpu_owner[s][y] = u
         self.moved[u] = self.call
@@ -595,8 +632,20 @@ class Replay:
                     self._emit(step, PRE, FAIL, t, self.cur[t], NONE, GPU, NONE, 0)
                     out.append(None)
                     continue
-                self._exchange(v, t, y, step, PRE, DEMAND, bound)
-            if rw & W_FLAG:
+                whole = self.alloc_write_only and rw == W_FLAG
+                self._exchange(v, t, y, step, PRE, ALLOC if whole else DEMAND, bound)
+            if (rw & R_FLAG) and self.undefined[t]:
+                self.undefined_reads += 1
+            if self.alloc_write_only and rw == W_FLAG:
+                # the module's kernel writes the whole tensor: whatever it held is replaced
+                self.dirty[t] = True
+                self.undefined[t] = False
+                self.whole_write[t] = (self.iteration, step)
+                self.stamps[t] = []
+                if self.full:
+                    self._gpu_view(s, self.gslot[t], self.bytes_of[t])[:] = \
+                        self._pattern(t, self.bytes_of[t], write_seed(self.iteration, step))
+            elif rw & W_FLAG:
                 # the module's kernel writes the tensor: stamp it, mark it dirty
                 self.dirty[t] = True
                 self.stamps[t].append((self.iteration, step))
@@ -677,7 +726,8 @@ class Replay:
                         y = self.gslot[v]
             if y == NONE:
                 continue                                  # nothing may leave: halt for this tensor
-            self._exchange(v, u, y, step, POST, PREFETCH, bound)
+            whole = self.alloc_write_only and p.rows_rw[self.cursor] == W_FLAG
+            self._exchange(v, u, y, step, POST, ALLOC if whole else PREFETCH, bound)
             self.cursor += 1
 
     # -- end of iteration ------------------------------------------------------
@@ -764,21 +814,23 @@ class Replay:
 
 
 def build(tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw, hbm_bytes, host_bytes,
-          align=256, literal=False, payload=None, prefetch=True, smallest_first=False):
+          align=256, literal=False, payload=None, prefetch=True, smallest_first=False,
+          alloc_write_only=False, pattern=None):
     """Profile, plan, place and return a Replay ready at iteration 0."""
     p = profile(tensor_bytes, tensor_group, ev_step, ev_tensor, ev_rw)
     plan = plan_pools(p, hbm_bytes, host_bytes, align, literal, smallest_first)
     pl = place(p, plan)
-    return Replay(p, plan, pl, payload, prefetch)
+    return Replay(p, plan, pl, payload, prefetch, alloc_write_only, pattern)
 
 
-def replay_workload(wl, payload=None, check=None) -> Replay:
+def replay_workload(wl, payload=None, check=None, pattern=None) -> Replay:
     """Run every iteration of a workload object (see the workloads package)."""
     st, te, rw, _ns = wl.events()
     r = build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
               wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, payload,
               prefetch=not getattr(wl, "no_prefetch", False),
-              smallest_first=getattr(wl, "smallest_first", False))
+              smallest_first=getattr(wl, "smallest_first", False),
+              alloc_write_only=getattr(wl, "alloc_write_only", False), pattern=pattern)
     for steps in wl.iterations:
         r.run_iteration(steps, check)
     return r

@@ -52,6 +52,7 @@ class Workload:
     literal_alg2: bool = False                # Alg. 2 without the working-set floor
     no_prefetch: bool = False                 # replay the paper's base variant: demand fetch only
     smallest_first: bool = False              # GPU buffers to the smallest tensors first (the baseline placement)
+    alloc_write_only: bool = False            # write-only accesses are whole-tensor writes: no fetch for them
     gaussian_p16: bool = False                # 16-bit params are fp16(N(0, 0.02))
     notes: str = ""
     step_phase: np.ndarray | None = None      # uint8 [n_steps]: 0 forward, 1 backward, 2 optimizer sweep (None: not known)
