@@ -62,6 +62,7 @@ extern "C" {
 #define TC_OP_SPILL     5   /* CPU buffer -> file extent, to make room (Alg. 4) */
 #define TC_OP_RESTORE   6   /* file extent -> CPU buffer at iteration end */
 #define TC_OP_FAIL      7   /* access that could not be given a GPU buffer */
+#define TC_OP_ALLOC     8   /* TC_ALLOC_WRITE_ONLY: a tensor about to be written whole is given its GPU buffer, no bytes move */
 
 #define TC_R 1
 #define TC_W 2
@@ -73,6 +74,24 @@ extern "C" {
 #define TC_LITERAL_ALG2 1u           /* Alg. 2 exactly as printed: no per-step working-set floor */
 #define TC_NO_PREFETCH  2u           /* the paper's base variant (Sec. 4.1.4, the one that does not prefetch): post-hook
                                         calls move nothing, tensors arrive by the pre-hook's demand fetch alone */
+
+#define TC_SMALLEST_FIRST 4u         /* not the paper's allocator but the placement it argues against (Sec. 3.1, Sec. 3.3.2:
+                                        large tensors kept in CPU or NVMe memory whatever their place in the execution
+                                        order), as an ablation of tc_plan_pools: beyond the working-set floor, GPU
+                                        memory goes to the size classes in ascending size, each taking as many buffers
+                                        as it has tensors and the memory left allows */
+
+#define TC_ALLOC_WRITE_ONLY 8u       /* a refinement the paper does not have: an access that only writes (TC_W without
+                                        TC_R: a gradient in the backward pass, a checkpoint in the forward pass, the
+                                        16-bit parameter in the optimizer sweep) is declared a whole-tensor write, so
+                                        what the tensor held is dead.  Where Alg. 3 would prefetch such a tensor (its
+                                        profiled row only writes) or the pre-hook would fetch it on demand, it is given
+                                        its GPU buffer and no bytes are copied (TC_OP_ALLOC); every decision is what it
+                                        is without the flag.  The caller's kernels must then really write the whole
+                                        tensor: until they do its bytes are unspecified, and on a replay that leaves
+                                        the profile the write may never come (tc_stats.undefined_reads counts reads of
+                                        such tensors).  tc_emulate_compute fills a tensor written this way with the
+                                        counter pattern of seed 0x10000000 + 4096 * iteration + step. */
 
 /* tc_bind_memory flags */
 #define TC_BIND_NULL_MOVER 1u        /* decide and log only; no region needed, no byte moves */
@@ -174,6 +193,9 @@ typedef struct {
     uint64_t waits_under_10us, waits_under_100us;   /* the other two thresholds of Sec. 4.2.2 (0.01 ms, 0.1 ms) */
     uint32_t cursor;                 /* prefetch-table cursor */
     uint32_t iteration;
+    uint64_t n_alloc;                /* TC_OP_ALLOC records: fetches left out because the tensor was about to be overwritten */
+    uint64_t bytes_not_fetched;      /* ... and the bytes they would have copied into HBM */
+    uint64_t undefined_reads;        /* accesses with TC_R to a tensor allocated without fetch and not yet written */
 } tc_stats;
 
 const char *tc_strerror(int code);
@@ -294,7 +316,10 @@ int tc_end_iteration(tc_ctx *ctx, void *compute_stream);
 /* Stand-in for the module's kernels in a replay: on compute_stream, XORs the
  * 16-byte stamp (words 0x10CAC4E5, iteration, step, tensor; little endian)
  * into the first and the last 16 bytes of every tensor the last PRE call
- * listed with TC_W, then spins for busy_ns nanoseconds. */
+ * listed with TC_W, then spins for busy_ns nanoseconds.  With
+ * TC_ALLOC_WRITE_ONLY a tensor listed with TC_W alone is instead overwritten
+ * whole with the counter pattern of tc_fill_payload, seed
+ * 0x10000000 + 4096 * iteration + step. */
 int tc_emulate_compute(tc_ctx *ctx, void *compute_stream, uint64_t busy_ns);
 
 /* Wait-time measurement (Sec. 4.2.2).  While enabled, a PRE call drains

@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     TENSOR_DESC, EVENT, POOL_CLASS, PLACEMENT, OP, STATS_FIELDS,
     copy_batch, exchange_batch, pack, unpack, pack_index, pack_tiles, pack_static, PACK_STATIC_MAX_BYTES,
     GPU, CPU, NVME, PRE, POST, END, END_CPU,
-    OP_NAMES, LITERAL_ALG2, NO_PREFETCH, BIND_NULL_MOVER, BIND_FILE_DIRECT, BIND_HOST_TIER,
+    OP_NAMES, LITERAL_ALG2, NO_PREFETCH, SMALLEST_FIRST, ALLOC_WRITE_ONLY, BIND_NULL_MOVER, BIND_FILE_DIRECT, BIND_HOST_TIER,
 )

@@ -13,9 +13,11 @@ LIB_PATH = os.path.join(HERE, "libtc.so")
 
 GPU, CPU, NVME = 0, 1, 2
 PRE, POST, END, END_CPU = 0, 1, 2, 3
-OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL"]
+OP_NAMES = ["DEMAND", "PREFETCH", "EVICT", "RELEASE", "WRITEBACK", "SPILL", "RESTORE", "FAIL", "ALLOC"]
 LITERAL_ALG2 = 1
 NO_PREFETCH = 2
+SMALLEST_FIRST = 4
+ALLOC_WRITE_ONLY = 8
 BIND_NULL_MOVER = 1
 BIND_FILE_DIRECT = 2
 BIND_HOST_TIER = 4
@@ -58,7 +60,8 @@ class Stats(C.Structure):
                 ("host_budget", C.c_uint64), ("host_pool_bytes", C.c_uint64),
                 ("stall_ns", C.c_uint64), ("waits_under_30us", C.c_uint64), ("waits_total", C.c_uint64),
                 ("waits_under_10us", C.c_uint64), ("waits_under_100us", C.c_uint64),
-                ("cursor", C.c_uint32), ("iteration", C.c_uint32)]
+                ("cursor", C.c_uint32), ("iteration", C.c_uint32),
+                ("n_alloc", C.c_uint64), ("bytes_not_fetched", C.c_uint64), ("undefined_reads", C.c_uint64)]
 
 
 class Timing(C.Structure):
@@ -454,7 +457,9 @@ class TensorCache:
         st, te, rw, ns = wl.events()
         tc.profile_order(wl.tensor_bytes, wl.tensor_group, st, te, rw, ns, wl.tensor_kind)
         tc.plan_pools(wl.hbm_bytes, wl.host_bytes, wl.align,
-                      (LITERAL_ALG2 if wl.literal_alg2 else 0) | (NO_PREFETCH if getattr(wl, "no_prefetch", False) else 0))
+                      (LITERAL_ALG2 if wl.literal_alg2 else 0) | (NO_PREFETCH if getattr(wl, "no_prefetch", False) else 0)
+                      | (SMALLEST_FIRST if getattr(wl, "smallest_first", False) else 0)
+                      | (ALLOC_WRITE_ONLY if getattr(wl, "alloc_write_only", False) else 0))
         tc.plan_schedule()
         return tc
 

@@ -426,6 +426,15 @@ static int dispatch_host_tier(tc_ctx *c, const TcOpRec &r, uint32_t t, uint32_t 
         return io_submit_behind(c, t, gpu_addr(c, s, r.dst_slot), true, true, compute, &c->fast_read[y],
                                 &c->fast_write[y]);
     }
+    case TC_OP_ALLOC: {
+        // nothing to read: the update may write the buffer once its last tensor has reached the
+        // file, so the PRE call's wait for "the read that fills the buffer" becomes a wait for that write
+        const uint32_t y = c->pools.gpu_base[s] + r.dst_slot;
+        int rc = io_wait(c, c->fast_read[y]);
+        if (rc != TC_OK) return rc;
+        c->fast_read[y] = c->fast_write[y];
+        return TC_OK;
+    }
     case TC_OP_RELEASE:
     case TC_OP_FAIL:
         return TC_OK;
@@ -453,7 +462,7 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
         const TcOpRec &r = ops[i];
         const uint32_t t = r.tensor;
         // never turn a record into an address before it is known to be in range
-        if (t >= c->prof.n_tensors || r.op > TC_OP_FAIL)
+        if (t >= c->prof.n_tensors || r.op > TC_OP_ALLOC)
             return fail(c, TC_E_HIP, "decision record out of range (tensor/op)");
         const uint32_t s = c->prof.class_of[t];
         {
@@ -469,9 +478,10 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
         rec.iteration = c->iteration; rec.step = step; rec.tensor = t;
         rec.src_slot = r.src_slot; rec.dst_slot = r.dst_slot;
         rec.phase = r.phase; rec.op = r.op; rec.src_tier = r.src_tier; rec.dst_tier = r.dst_tier;
-        rec.bytes = (r.op == TC_OP_RELEASE || r.op == TC_OP_FAIL) ? 0 : n;
+        rec.bytes = (r.op == TC_OP_RELEASE || r.op == TC_OP_FAIL || r.op == TC_OP_ALLOC) ? 0 : n;
         if (c->logging) c->log.push_back(rec);
-        c->stats.n_ops[r.op]++;
+        if (r.op == TC_OP_ALLOC) { c->stats.n_alloc++; c->stats.bytes_not_fetched += n; }
+        else c->stats.n_ops[r.op]++;
         switch (r.op) {
         case TC_OP_EVICT: c->stats.bytes_d2h += n; break;
         case TC_OP_WRITEBACK: case TC_OP_SPILL: c->stats.bytes_file_write += n; break;
@@ -564,6 +574,27 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
             if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 1;
             if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 1;
             c->deferred_bytes += n * ((p.u.out_src ? 1 : 0) + 1);
+            if (p.out_staging) c->wb_pending[p.out_tensor] = 1;
+            units.push_back(p);
+            have_out = false;
+            break;
+        }
+        case TC_OP_ALLOC: {
+            // the tensor is about to be written whole: its GPU buffer changes hands and nothing is
+            // copied in.  If a tensor leaves that buffer (the eviction recorded just before), its
+            // copy is a unit without an incoming half; the module's kernels wait for it through the
+            // buffer's ticket, like for any copy.
+            if (!have_out) break;
+            PUnit p = pend;
+            if (p.gpu_y != (int64_t)(c->pools.gpu_base[s] + r.dst_slot))
+                return fail(c, TC_E_HIP, "decision records: an allocation that does not follow its eviction");
+            if (c->gpu_pending[(size_t)p.gpu_y] || (p.cpu_out >= 0 && c->cpu_pending[(size_t)p.cpu_out])) {
+                int rc = issue_units(c, units, compute);
+                if (rc != TC_OK) return rc;
+            }
+            c->gpu_pending[(size_t)p.gpu_y] = 1;
+            if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 1;
+            c->deferred_bytes += n;
             if (p.out_staging) c->wb_pending[p.out_tensor] = 1;
             units.push_back(p);
             have_out = false;

@@ -68,8 +68,10 @@ struct TcDevTables {
     const uint32_t *member_ptr, *members;
     uint32_t n_rows, n_steps, n_tensors, n_classes;
     uint32_t flags;                             // tc_budget.flags
+    const uint8_t *rows_rw;                     // R/W flags of the profiled rows
     // mutable scheduler state
     uint32_t *cur, *gslot, *cslot, *dirty, *moved;
+    uint32_t *undefined;                        // allocated without fetch, not written yet
     uint32_t *gpu_owner, *gpu_freed, *cpu_owner, *cpu_freed, *designated;
     uint32_t *scalars;                          // [0] cursor, [1] call id, [2] iteration
 };
@@ -84,7 +86,7 @@ struct TcOpRec {
 // the call's op records are written to a separate array
 struct TcDecideOut {
     uint32_t n_ops, hits, misses, fails;
-    uint32_t cursor, iteration, overflow, pad_;
+    uint32_t cursor, iteration, overflow, undefined_reads;
     uint32_t slots[TC_MAX_STEP_TENSORS];
 };
 
@@ -137,6 +139,7 @@ struct TcStampArgs {
     uint8_t *ptr[TC_MAX_STEP_TENSORS];
     uint64_t bytes[TC_MAX_STEP_TENSORS];
     uint32_t tensor[TC_MAX_STEP_TENSORS];
+    uint8_t whole[TC_MAX_STEP_TENSORS];         // written whole (filled), not stamped
     uint32_t n, iteration, step;
     uint64_t busy_ns;
 };

@@ -177,6 +177,7 @@ __device__ void exchange(DecideCtx &c, uint32_t v, uint32_t u, uint32_t y, uint3
         T.cpu_freed[cb + src_slot] = c.call;
     }
     emit(c, op_in, u, src_tier, src_tier == TC_CPU ? src_slot : NONE, TC_GPU, y);
+    if (op_in == TC_OP_ALLOC) T.undefined[u] = 1;         // handed over as it is: no copy fills the buffer
     T.cur[u] = TC_GPU;
     T.gslot[u] = y;
     T.cslot[u] = NONE;
@@ -206,18 +207,23 @@ __device__ void decide_pre(DecideCtx &c, const TcStepArgs &a)
         if ((uint32_t)__popcll(mk) == a.n) {
             // the dirty marks are scheduler state a later call of the same launch reads on every
             // lane: like every other state store, each lane makes all of them itself
-            for (uint32_t i = 0; i < a.n; ++i)
+            uint32_t ur = 0;
+            for (uint32_t i = 0; i < a.n; ++i) {
+                if ((a.rw[i] & TC_R) && T.undefined[a.ids[i]]) ur++;
                 if (a.rw[i] & TC_W) T.dirty[a.ids[i]] = 1;
+                if (a.rw[i] == TC_W && (T.flags & TC_ALLOC_WRITE_ONLY)) T.undefined[a.ids[i]] = 0;
+            }
             if (mine) c.out->slots[c.lane] = T.gslot[t];
-            if (c.lane == 0) { c.out->hits = a.n; c.out->misses = 0; c.out->fails = 0; }
+            if (c.lane == 0) { c.out->hits = a.n; c.out->misses = 0; c.out->fails = 0; c.out->undefined_reads = ur; }
             return;
         }
     }
-    uint32_t h = 0, m = 0, f = 0;
+    uint32_t h = 0, m = 0, f = 0, ur = 0;
     for (uint32_t i = 0; i < a.n; ++i) {
         const uint32_t t = a.ids[i];
         const uint32_t s = T.class_of[t];
         const uint32_t gb = T.gpu_base[s], gc = T.gpu_count[s];
+        const bool whole = a.rw[i] == TC_W && (T.flags & TC_ALLOC_WRITE_ONLY);   // the module overwrites all of it
         if (T.cur[t] == TC_GPU) {
             h++;
         } else {
@@ -241,12 +247,14 @@ __device__ void decide_pre(DecideCtx &c, const TcStepArgs &a)
                 if (c.lane == 0) c.out->slots[i] = NONE;
                 continue;
             }
-            exchange(c, v, t, y, TC_OP_DEMAND);
+            exchange(c, v, t, y, whole ? TC_OP_ALLOC : TC_OP_DEMAND);
         }
+        if ((a.rw[i] & TC_R) && T.undefined[t]) ur++;
         if (a.rw[i] & TC_W) T.dirty[t] = 1;
+        if (whole) T.undefined[t] = 0;
         if (c.lane == 0) c.out->slots[i] = T.gslot[t];
     }
-    if (c.lane == 0) { c.out->hits = h; c.out->misses = m; c.out->fails = f; }
+    if (c.lane == 0) { c.out->hits = h; c.out->misses = m; c.out->fails = f; c.out->undefined_reads = ur; }
 }
 
 // post-hook: PrefetchTensor (Alg. 3) over the tensors that finished
@@ -300,7 +308,9 @@ __device__ void decide_post(DecideCtx &c, const TcStepArgs &a)
             }
         }
         if (y == NONE) continue;                          // halt for this tensor
-        exchange(c, v, u, y, TC_OP_PREFETCH);
+        // a row that only writes: the tensor's bytes are dead, the buffer alone is handed over
+        const bool whole = (T.flags & TC_ALLOC_WRITE_ONLY) && T.rows_rw[cursor] == TC_W;
+        exchange(c, v, u, y, whole ? TC_OP_ALLOC : TC_OP_PREFETCH);
         cursor++;
     }
     T.scalars[0] = cursor;
@@ -399,7 +409,7 @@ __device__ void decide_call(DecideCtx &c, const TcStepArgs &a, TcDecideOut *out,
     c.phase = a.phase;
     c.call = T.scalars[1] + 1;
     c.bound = 0;
-    if (c.lane == 0) { out->hits = 0; out->misses = 0; out->fails = 0; }
+    if (c.lane == 0) { out->hits = 0; out->misses = 0; out->fails = 0; out->undefined_reads = 0; }
     if (a.phase == TC_PRE) decide_pre(c, a);
     else if (a.phase == TC_POST) decide_post(c, a);
     else decide_end(c);

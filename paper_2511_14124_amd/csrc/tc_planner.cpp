@@ -123,7 +123,24 @@ int tc_build_pools(const TcProfile &p, const tc_budget &b, TcPools &out, std::st
     out.stride.resize(n_c);
     for (uint32_t s = 0; s < n_c; ++s) out.stride[s] = (p.class_bytes[s] + align - 1) / align * align;
 
-    if (b.flags & TC_LITERAL_ALG2) {
+    if (b.flags & TC_SMALLEST_FIRST) {
+        // The placement the paper argues against (Sec. 3.1, Sec. 3.3.2: large tensors live below the
+        // GPU whatever their place in the execution order), as an ablation: beyond the working-set
+        // floor, GPU memory goes to the classes in ascending size, each taking what it can use.
+        out.gpu_count.resize(n_c);
+        u128 reserved = 0;
+        for (uint32_t s = 0; s < n_c; ++s) {
+            out.gpu_count[s] = (b.flags & TC_LITERAL_ALG2) ? 0 : std::min(p.step_max[s], p.used[s]);
+            reserved += (u128)out.gpu_count[s] * out.stride[s];
+        }
+        if (reserved > b.hbm_bytes) { err = "HBM budget below the per-step working set"; return TC_E_CAPACITY; }
+        uint64_t left = b.hbm_bytes - (uint64_t)reserved;
+        for (uint32_t s = 0; s < n_c; ++s) {               // classes are ascending by (bytes, group)
+            const uint64_t more = std::min<uint64_t>(p.used[s] - out.gpu_count[s], left / out.stride[s]);
+            out.gpu_count[s] += (uint32_t)more;
+            left -= more * out.stride[s];
+        }
+    } else if (b.flags & TC_LITERAL_ALG2) {
         buffer_count(out.stride, p.used, b.hbm_bytes, p.used, out.gpu_count);
     } else {
         // working-set floor: step_max buffers per class first, Alg. 2 on the rest

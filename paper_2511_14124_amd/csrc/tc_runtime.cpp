@@ -209,6 +209,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     size_t o_gc = put(pl.gpu_count), o_cc = put(pl.cpu_count), o_gb = put(pl.gpu_base), o_cb = put(pl.cpu_base);
     size_t o_mp = put(c->place.member_ptr), o_mem = put(c->place.members);
     size_t o_cur = put(cur), o_gs = put(gslot), o_cs = put(cslot), o_dirty = put(zeros_t), o_moved = put(zeros_t);
+    size_t o_undef = put(zeros_t);
     size_t o_go = put(gpu_owner), o_gf = put(std::vector<uint32_t>(pl.gpu_slots, 0));
     size_t o_co = put(cpu_owner), o_cf = put(std::vector<uint32_t>(pl.cpu_slots, 0));
     size_t o_des = put(std::vector<uint32_t>(pl.cpu_slots, 0));
@@ -226,6 +227,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     T.n_rows = n_rows; T.n_steps = p.n_steps; T.n_tensors = n_t; T.n_classes = n_c;
     T.flags = c->budget.flags;
     T.cur = d + o_cur; T.gslot = d + o_gs; T.cslot = d + o_cs; T.dirty = d + o_dirty; T.moved = d + o_moved;
+    T.undefined = d + o_undef;
     T.gpu_owner = d + o_go; T.gpu_freed = d + o_gf; T.cpu_owner = d + o_co; T.cpu_freed = d + o_cf;
     T.designated = d + o_des; T.scalars = d + o_sc;
 
@@ -258,6 +260,7 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (e == hipSuccess && !p.rows_rw.empty())
         e = hipMemcpy(c->d_prof_rw, p.rows_rw.data(), p.rows_rw.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    c->T.rows_rw = c->d_prof_rw;
     c->ahead_pause = 0;
     e = hipMalloc((void **)&c->tickets, 256);
     if (e == hipSuccess) e = hipMemset(c->tickets, 0, 256);
@@ -456,6 +459,7 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
     c->stats.hits += o->hits;
     c->stats.misses += o->misses;
     c->stats.fails += o->fails;
+    c->stats.undefined_reads += o->undefined_reads;
     TcStampArgs &sa = c->last_pre;
     sa = TcStampArgs{};
     sa.iteration = c->iteration;
@@ -506,6 +510,7 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
             sa.ptr[sa.n] = ptr;
             sa.bytes[sa.n] = c->prof.bytes[t];
             sa.tensor[sa.n] = t;
+            sa.whole[sa.n] = (rw[i] == TC_W && (c->budget.flags & TC_ALLOC_WRITE_ONLY)) ? 1 : 0;
             sa.n++;
         }
     }
@@ -571,8 +576,29 @@ extern "C" int tc_emulate_compute(tc_ctx *c, void *compute_stream, uint64_t busy
 {
     if (!c) return TC_E_ARG;
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
-    TcStampArgs sa = c->last_pre;
+    // Tensors written whole are filled, the others listed with TC_W are stamped.  A list may name a
+    // tensor more than once: the writes apply in list order, so only the last whole write of a tensor
+    // counts and only the stamps listed behind it survive.  The fills are launched ahead of the stamp
+    // kernel on the same stream.
+    const TcStampArgs &lp = c->last_pre;
+    TcStampArgs sa{};
+    sa.iteration = lp.iteration;
+    sa.step = lp.step;
     sa.busy_ns = busy_ns;
+    for (uint32_t i = 0; i < lp.n; ++i) {
+        bool whole_later = false;                           // a whole write of the same tensor further down the list
+        for (uint32_t k = i + 1; k < lp.n; ++k) whole_later = whole_later || (lp.whole[k] && lp.ptr[k] == lp.ptr[i]);
+        if (whole_later) continue;
+        if (lp.whole[i]) {
+            const uint32_t seed = 0x10000000u + 4096u * lp.iteration + lp.step;
+            HIP_TRY(c, tc_launch_fill(lp.ptr[i], lp.bytes[i], lp.tensor[i], seed, (hipStream_t)compute_stream));
+        } else {
+            sa.ptr[sa.n] = lp.ptr[i];
+            sa.bytes[sa.n] = lp.bytes[i];
+            sa.tensor[sa.n] = lp.tensor[i];
+            sa.n++;
+        }
+    }
     if (sa.n || busy_ns) HIP_TRY(c, tc_launch_stamp(sa, (hipStream_t)compute_stream));
     return TC_OK;
 }

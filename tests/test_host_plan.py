@@ -52,7 +52,8 @@ def test_the_device_array_of_the_allocation_free_entry_point_is_visible_to_the_l
 def _oracle_plan(wl):
     st, te, rw, _ = wl.events()
     p = o.profile(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw)
-    plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2)
+    plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2,
+                        getattr(wl, "smallest_first", False))
     return p, plan, o.place(p, plan)
 
 
@@ -126,3 +127,18 @@ def test_error_codes_and_call_order():
         tc.migrate_step(0, T.PRE, [0], [1])                      # not bound yet
     assert e.value.code == -2
     tc.close()
+
+
+@pytest.mark.parametrize("index", range(5))
+def test_smallest_first_plan_matches_the_oracle_on_the_five_configs(index):
+    wl = W.config(index)
+    wl.smallest_first = True
+    _check_plan(wl)
+
+
+def test_smallest_first_plan_matches_the_oracle_on_random_traces():
+    for seed in range(30):
+        wl = W.random_workload(300 + seed, n_tensors=40, sizes=(512, 1024, 4096, 33000), hbm_frac=0.2,
+                               literal=(seed % 5 == 0))
+        wl.smallest_first = True
+        _check_plan(wl)
