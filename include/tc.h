@@ -76,8 +76,8 @@ extern "C" {
                                         calls move nothing, tensors arrive by the pre-hook's demand fetch alone */
 
 #define TC_SMALLEST_FIRST 4u         /* not the paper's allocator but the placement it argues against (Sec. 3.1, Sec. 3.3.2:
-                                        large tensors kept in CPU or NVMe memory whatever their place in the execution
-                                        order), as an ablation of tc_plan_pools: beyond the working-set floor, GPU
+                                        tensors placed by size, the large ones below the GPU wherever they stand in the
+                                        execution order), as an ablation of tc_plan_pools: beyond the working-set floor, GPU
                                         memory goes to the size classes in ascending size, each taking as many buffers
                                         as it has tensors and the memory left allows */
 

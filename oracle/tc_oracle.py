@@ -228,8 +228,8 @@ def plan_pools(p: Profile, hbm_bytes: int, host_bytes: Sequence[int], align: int
 
     `smallest_first` is not the paper's allocator but the placement it argues
     against (Sec. 3.1 and the illustrative example of Sec. 3.3.2: the baseline
-    keeps large tensors in CPU or NVMe memory whatever their place in the
-    execution order): GPU memory beyond the floor goes to the classes in
+    places tensors by size, the large ones below the GPU wherever they stand in
+    the execution order): GPU memory beyond the floor goes to the classes in
     ascending size, each taking as many buffers as it has tensors and the
     memory left allows, so the smallest tensors stay on the GPU and the
     largest live below it.  An ablation, used to state a hit-rate ratio of the

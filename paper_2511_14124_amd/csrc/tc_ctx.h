@@ -196,6 +196,10 @@ struct tc_ctx {
     std::vector<uint8_t> gpu_pending, cpu_pending;  // buffer is touched by a deferred unit
     hipStream_t last_compute = nullptr;
     uint64_t last_k_op = 0;             // newest operation issued on the migration stream
+    // per compute stream: the newest operation of each copy stream it has been made to wait for
+    // (a stream is in order, so an older operation of the same copy stream needs no wait of its own)
+    hipStream_t waited_stream = nullptr;
+    uint64_t waited_op[N_STREAMS] = {};
     bool measure_stall = false;         // pre-hook calls time the wait for their copies on the host
     std::vector<uint64_t> stall_by_step; // ... and add the time each call waited to its step's entry
     // last PRE call, for tc_emulate_compute

@@ -106,17 +106,22 @@ int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes)
 // dispatch: op records -> migration-kernel launches, DMA copies and file I/O
 //
 // A hook call's records are grouped into exchange units (an optional outgoing
-// copy that leaves a GPU buffer and the incoming copy that fills it).  Small
-// units all go into one migration-kernel launch on stream K: per-copy overhead
-// would dominate them, and the kernel's load-load-store-store order lets a
-// unit swap two buffers in place.  Large units go through the DMA engines,
-// which sustain the link in both directions better than a kernel does when a
-// replay is a stream of modest launches: the outgoing tensor is first copied
-// inside HBM to a bounce block (by the same kernel launch, at HBM speed), then
-// the incoming tensor is copied into the GPU buffer on stream H and the
-// outgoing one leaves the bounce block on stream D.  Ordering between streams
-// comes from per-buffer tickets: each buffer remembers the last operation that
-// touched it, and an operation waits for the tickets of the buffers it touches.
+// copy that leaves a GPU buffer and the incoming copy that fills it).  By
+// default every unit, whatever its size, goes into a migration-kernel launch on
+// stream K: per-copy overhead would dominate the small ones, the kernel's
+// load-load-store-store order lets a unit swap two buffers in place, and with
+// both directions loaded the kernel also carries the large ones faster than the
+// DMA engines do in this runtime (49 against 29 GB/s per direction).  What the
+// DMA engines are good for is compute running beside the copies, which the
+// kernel's host reads slow down and DMA copies hardly do: with a DMA threshold
+// set (tc_set_dma_threshold, tc_set_dma_policy) units at least that large take
+// them, always or only while the compute stream has a backlog to hide them
+// behind.  Such a unit's outgoing tensor is first copied inside HBM to a bounce
+// block (a device-to-device copy on stream K), then the incoming tensor is
+// copied into the GPU buffer on stream H and the outgoing one leaves the bounce
+// block on stream D.  Ordering between streams comes from per-buffer tickets:
+// each buffer remembers the last operation that touched it, and an operation
+// waits for the tickets of the buffers it touches.
 // ---------------------------------------------------------------------------
 // a block of the HBM bounce ring, or nullptr if none can be had without
 // waiting for a copy of the batch being prepared
@@ -633,7 +638,9 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
             staged = staged || p.st_id != 0;
         }
         // the link is busy: keep them for a larger launch (file-tier units go at once,
-        // their staging blocks and their writes should not wait)
+        // their staging blocks and their writes should not wait).  Keeping a second launch queued
+        // behind the running one instead was measured and changes nothing: with the host ahead of
+        // the GPU it is the module that needs a prepared buffer that decides when units are issued.
         if (!staged && c->deferred_bytes < c->merge_bytes && units.size() < 4 * TC_MOVER_MAX_UNITS &&
             !poll_op(c, c->last_k_op))
             return TC_OK;

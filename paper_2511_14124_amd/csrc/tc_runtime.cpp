@@ -501,7 +501,17 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
                     if (ns < 30000) c->stats.waits_under_30us++;
                     if (ns < 100000) c->stats.waits_under_100us++;
                 } else if (!op_complete(c, ticket)) {
-                    HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
+                    // one wait per copy operation and compute stream: what the stream already waits
+                    // for covers every older operation of the same copy stream
+                    const uint32_t st = c->op_stream[ticket % OP_RING];
+                    if (c->waited_stream != compute) {
+                        c->waited_stream = compute;
+                        for (int k = 0; k < N_STREAMS; ++k) c->waited_op[k] = 0;
+                    }
+                    if (ticket > c->waited_op[st]) {
+                        HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
+                        c->waited_op[st] = ticket;
+                    }
                 }
             }
         }

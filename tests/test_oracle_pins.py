@@ -933,8 +933,8 @@ def test_the_threaded_copy_replay_ends_with_the_oracles_bytes(threads):
 
 
 # ----------------------------------------------------------------------------
-# the placement the paper argues against (Sec. 3.1, Sec. 3.3.2: large tensors live in CPU or NVMe
-# memory whatever their place in the execution order), by hand on nine tensors
+# the placement the paper argues against (Sec. 3.1, Sec. 3.3.2: tensors placed by size, the large ones below
+# the GPU wherever they stand in the execution order), by hand on nine tensors
 # ----------------------------------------------------------------------------
 
 def _nine_with_two_large(smallest_first, prefetch):
