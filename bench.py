@@ -250,6 +250,11 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
             write_GBps_in_call=d["bytes_file_write"] / max(1, d["file_write_ns"]),
             io_threads="1 + 1" if direct and not args.io_chunk_mib else list(args.io_threads),
             link_time_share=(d["bytes_h2d"] / 1e9 / link["h2d"]) / dt,
+            inside_launches_GBps_both_directions=tm["kernel_bytes"] / max(1.0, tm["kernel_ns"]),
+            hook_thread_blocked_ms_per_iteration={
+                name: (s1["host_blocked_ns"][k] - s0["host_blocked_ns"][k]) / steps / 1e6
+                for k, name in enumerate(("file_read_not_finished", "file_write_still_reading_a_buffer",
+                                          "staging_ring_full", "copy_operation"))},
             note="link_time_share = time the host->HBM bytes alone would need at the measured one-way peak / wall "
                  "time: what is left is file I/O (and its page-cache copies by the CPU) the schedule could not hide")
     extra = {"tm": tm, "t_plan": t_plan, "t_bind": t_bind, "t_fill": t_fill, "dt": dt, "s1": s1, "wl": wl,

@@ -196,6 +196,11 @@ typedef struct {
     uint64_t n_alloc;                /* TC_OP_ALLOC records: fetches left out because the tensor was about to be overwritten */
     uint64_t bytes_not_fetched;      /* ... and the bytes they would have copied into HBM */
     uint64_t undefined_reads;        /* accesses with TC_R to a tensor allocated without fetch and not yet written */
+    /* time the calling thread spent blocked inside hook calls, by what it waited for: [0] a file read that
+     * had not finished when the copy of its bytes was due, [1] a queued file write that still read the host
+     * buffer a copy was about to overwrite, [2] room in the staging ring (its oldest block's copies and
+     * write), [3] a copy operation (a buffer a spill or a restore needs, a bounce block, an event to reuse) */
+    uint64_t host_blocked_ns[4];
 } tc_stats;
 
 const char *tc_strerror(int code);

@@ -61,7 +61,8 @@ class Stats(C.Structure):
                 ("stall_ns", C.c_uint64), ("waits_under_30us", C.c_uint64), ("waits_total", C.c_uint64),
                 ("waits_under_10us", C.c_uint64), ("waits_under_100us", C.c_uint64),
                 ("cursor", C.c_uint32), ("iteration", C.c_uint32),
-                ("n_alloc", C.c_uint64), ("bytes_not_fetched", C.c_uint64), ("undefined_reads", C.c_uint64)]
+                ("n_alloc", C.c_uint64), ("bytes_not_fetched", C.c_uint64), ("undefined_reads", C.c_uint64),
+                ("host_blocked_ns", C.c_uint64 * 4)]
 
 
 class Timing(C.Structure):
@@ -391,7 +392,7 @@ class TensorCache:
         out = {}
         for name in STATS_FIELDS:
             v = getattr(s, name)
-            out[name] = list(v) if name == "n_ops" else int(v)
+            out[name] = list(v) if name in ("n_ops", "host_blocked_ns") else int(v)
         return out
 
     def dump_oplog(self) -> np.ndarray:

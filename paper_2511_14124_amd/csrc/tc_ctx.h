@@ -6,6 +6,7 @@
 #include "tc_internal.h"
 
 #include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <deque>
 #include <memory>
@@ -220,6 +221,20 @@ static inline int fail(tc_ctx *c, int code, const std::string &msg)
     if (c) c->err = msg;
     return code;
 }
+
+// adds the time until it goes out of scope to one of tc_stats.host_blocked_ns
+struct Blocked {
+    tc_ctx *c;
+    int k;
+    std::chrono::steady_clock::time_point t0;
+    Blocked(tc_ctx *c_, int k_) : c(c_), k(k_), t0(std::chrono::steady_clock::now()) {}
+    ~Blocked()
+    {
+        c->stats.host_blocked_ns[k] += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                                           std::chrono::steady_clock::now() - t0).count();
+    }
+};
+enum { BLK_FILE_READ = 0, BLK_FILE_WRITE = 1, BLK_STAGING = 2, BLK_COPY = 3 };
 
 #define HIP_TRY(c, expr)                                                                          \
     do {                                                                                          \

@@ -52,6 +52,7 @@ static int begin_op(tc_ctx *c, int S, hipStream_t compute, uint64_t *id)
 {
     const uint64_t n = c->op_id + 1;
     if (n > OP_RING) {
+        Blocked b(c, BLK_COPY);
         int rc = wait_op(c, n - OP_RING);              // the event about to be reused
         if (rc != TC_OK) return rc;
     }
@@ -149,6 +150,7 @@ static int bounce_alloc(tc_ctx *c, uint64_t bytes, uint8_t **out)
             return TC_OK;
         }
         if (c->bounce_q.front().op == 0) return TC_OK;             // held by this very batch: give up
+        Blocked b(c, BLK_COPY);
         int rc = wait_op(c, c->bounce_q.front().op);               // oldest reader must finish first
         if (rc != TC_OK) return rc;
     }
@@ -168,8 +170,15 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
     // a host buffer some unit is about to overwrite may still be the source of a queued
     // spill, and bytes coming from the file tier may still be on their way into staging
     for (PUnit &p : units) {
-        int rc = p.cpu_out >= 0 ? io_wait(c, c->cpu_job[(size_t)p.cpu_out]) : TC_OK;
-        if (rc == TC_OK) rc = io_wait(c, p.read_job);
+        int rc = TC_OK;
+        if (p.cpu_out >= 0 && !io_done(c, c->cpu_job[(size_t)p.cpu_out])) {
+            Blocked b(c, BLK_FILE_WRITE);
+            rc = io_wait(c, c->cpu_job[(size_t)p.cpu_out]);
+        }
+        if (rc == TC_OK && !io_done(c, p.read_job)) {
+            Blocked b(c, BLK_FILE_READ);
+            rc = io_wait(c, p.read_job);
+        }
         if (rc != TC_OK) return rc;
     }
     // DMA copies are slower on the link than the kernel but hardly slow compute that runs beside
@@ -353,6 +362,25 @@ int flush_deferred(tc_ctx *c, hipStream_t compute)
     return issue_units(c, c->deferred, compute);
 }
 
+// Issue the leading prepared units whose file reads have arrived and whose host buffers no queued
+// write still reads; the rest stay prepared.  (Prepared units touch disjoint buffers, so a prefix may
+// go ahead of the others; a prefix, not any subset, because staging blocks free in the order taken.)
+static int issue_ready(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute)
+{
+    size_t n = 0;
+    while (n < units.size() && io_done(c, units[n].read_job) &&
+           (units[n].cpu_out < 0 || io_done(c, c->cpu_job[(size_t)units[n].cpu_out])))
+        ++n;
+    if (n == 0) return TC_OK;
+    if (n == units.size()) return issue_units(c, units, compute);
+    std::vector<PUnit> head(units.begin(), units.begin() + (ptrdiff_t)n);
+    units.erase(units.begin(), units.begin() + (ptrdiff_t)n);
+    const int rc = issue_units(c, head, compute);
+    c->deferred_bytes = 0;
+    for (const PUnit &p : units) c->deferred_bytes += p.u.bytes * ((p.u.out_src ? 1 : 0) + (p.u.in_src ? 1 : 0));
+    return rc;
+}
+
 // The staging region is a ring: a block is taken when a record needs bounce
 // space for the file tier and is free again once the copies that touch it have
 // completed and, for an outgoing tensor, its write has reached the file.  Blocks
@@ -389,13 +417,20 @@ static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, h
             *id = b.id;
             return TC_OK;
         }
-        // no room: the oldest block has to go first
+        // no room: the oldest block has to go first.  While this thread waits for it, the units
+        // whose bytes have arrived should be moving: issue them now (a unit prepared but not issued
+        // keeps the link idle and its staging block taken).
+        {
+            int rc = issue_ready(c, units, compute);
+            if (rc != TC_OK) return rc;
+        }
         if (!c->st_q.front().issued) {
             int rc = issue_units(c, units, compute);
             if (rc != TC_OK) return rc;
             if (!c->st_q.front().issued) return fail(c, TC_E_STATE, "staging ring holds a block no prepared unit owns");
         }
         StBlock &f = c->st_q.front();
+        Blocked b(c, BLK_STAGING);
         int rc = wait_op(c, f.ops[0]);
         if (rc == TC_OK) rc = wait_op(c, f.ops[1]);
         if (rc == TC_OK) rc = io_wait(c, f.job);
@@ -509,9 +544,11 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
             const uint32_t flat = c->pools.cpu_base[s] + r.src_slot;
             int rc = c->cpu_pending[flat] ? issue_units(c, units, compute) : TC_OK;
             if (rc != TC_OK) return rc;
-            rc = wait_op(c, c->cpu_ticket[flat]);
-            if (rc != TC_OK) return rc;
-            rc = io_submit(c, t, cpu_addr(c, s, r.src_slot), false, 0, 0, &c->cpu_job[flat]);
+            // the copy that last touched the buffer may still run: the writers wait for it, not this thread
+            const uint64_t tk = c->cpu_ticket[flat];
+            const bool running = !poll_op(c, tk);
+            rc = io_submit(c, t, cpu_addr(c, s, r.src_slot), false, running ? tk : 0,
+                           running ? c->op_stream[tk % OP_RING] : 0, &c->cpu_job[flat]);
             if (rc != TC_OK) return rc;
             break;
         }
@@ -612,12 +649,19 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
             if (rc != TC_OK) return rc;
             // the same end-of-iteration call may have written this very tensor back to
             // its extent a moment ago: that write has to reach the file first
-            rc = io_wait(c, c->tensor_job[t]);
-            if (rc != TC_OK) return rc;
             const uint32_t flat = c->pools.cpu_base[s] + r.dst_slot;
-            rc = wait_op(c, c->cpu_ticket[flat]);
+            {
+                Blocked b(c, BLK_FILE_WRITE);
+                rc = io_wait(c, c->tensor_job[t]);
+                if (rc == TC_OK) rc = io_wait(c, c->cpu_job[flat]);
+            }
             if (rc != TC_OK) return rc;
-            if ((rc = io_wait(c, c->cpu_job[flat])) != TC_OK) return rc;
+            {
+                Blocked b(c, BLK_COPY);
+                rc = wait_op(c, c->cpu_ticket[flat]);
+            }
+            if (rc != TC_OK) return rc;
+            Blocked b(c, BLK_FILE_READ);
             rc = io_transfer(c, t, cpu_addr(c, s, r.dst_slot), true);
             if (rc != TC_OK) return rc;
             break;
@@ -631,12 +675,12 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
         // Units whose bytes are still being read from the file, or whose host buffer a
         // queued spill still reads, stay prepared: a later hook call issues them, at the
         // latest the one that needs a buffer they touch.
-        bool staged = false;
+        bool staged = false, waiting = false;
         for (const PUnit &p : units) {
-            if (!io_done(c, p.read_job) || (p.cpu_out >= 0 && !io_done(c, c->cpu_job[(size_t)p.cpu_out])))
-                return TC_OK;
+            waiting = waiting || !io_done(c, p.read_job) || (p.cpu_out >= 0 && !io_done(c, c->cpu_job[(size_t)p.cpu_out]));
             staged = staged || p.st_id != 0;
         }
+        if (waiting) return issue_ready(c, units, compute);     // those in front that can go, go
         // the link is busy: keep them for a larger launch (file-tier units go at once,
         // their staging blocks and their writes should not wait).  Keeping a second launch queued
         // behind the running one instead was measured and changes nothing: with the host ahead of
