@@ -68,7 +68,7 @@ extern "C" {
 #define TC_W 2
 
 #define TC_NONE 0xFFFFFFFFu          /* "no slot" / "never" */
-#define TC_MAX_STEP_TENSORS 16       /* most tensors one hook call may name */
+#define TC_MAX_STEP_TENSORS 64       /* most tensors one hook call may name (the lanes of the wavefront that decides it) */
 
 /* tc_budget.flags */
 #define TC_LITERAL_ALG2 1u           /* Alg. 2 exactly as printed: no per-step working-set floor */

@@ -22,7 +22,7 @@ BIND_NULL_MOVER = 1
 BIND_FILE_DIRECT = 2
 BIND_HOST_TIER = 4
 NONE = 0xFFFFFFFF
-MAX_STEP_TENSORS = 16
+MAX_STEP_TENSORS = 64
 
 TENSOR_DESC = np.dtype([("bytes", "<u8"), ("group", "u1"), ("kind", "u1"), ("pad_", "u1", (6,))])
 EVENT = np.dtype([("step", "<u4"), ("tensor", "<u4"), ("compute_ns", "<u8"), ("rw", "u1"), ("pad_", "u1", (7,))])

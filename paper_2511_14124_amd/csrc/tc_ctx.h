@@ -278,6 +278,7 @@ int wait_op(tc_ctx *c, uint64_t id);                 // block the host until ope
 int timed_begin(tc_ctx *c, int kind, hipEvent_t *t0);
 int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes);
 int flush_deferred(tc_ctx *c, hipStream_t compute);  // issue whatever units are prepared
+int flush_for_buffers(tc_ctx *c, const int64_t *ys, uint32_t n, hipStream_t compute);   // ... that fill these GPU buffers, and the ready ones
 int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step, int phase, hipStream_t compute);
 
 // after: writes that must have finished before the request starts (may be nullptr)

@@ -362,23 +362,46 @@ int flush_deferred(tc_ctx *c, hipStream_t compute)
     return issue_units(c, c->deferred, compute);
 }
 
-// Issue the leading prepared units whose file reads have arrived and whose host buffers no queued
-// write still reads; the rest stay prepared.  (Prepared units touch disjoint buffers, so a prefix may
-// go ahead of the others; a prefix, not any subset, because staging blocks free in the order taken.)
-static int issue_ready(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute)
+// Issue those prepared units that are ready (their file reads have arrived and no queued write still
+// reads the host buffer they overwrite) and those `must` names, ready or not (issue_units waits for their
+// file I/O); the rest stay prepared.  Prepared units touch disjoint buffers and disjoint extents (a unit
+// that touches a buffer of a prepared one, or reads an extent a prepared one writes, issues those first),
+// so any of them may go ahead of the others.  Staging blocks free in the order taken: a block issued ahead
+// of an older one is simply held until that one is done.
+template <class Must>
+static int issue_some(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute, Must must)
 {
-    size_t n = 0;
-    while (n < units.size() && io_done(c, units[n].read_job) &&
-           (units[n].cpu_out < 0 || io_done(c, c->cpu_job[(size_t)units[n].cpu_out])))
-        ++n;
-    if (n == 0) return TC_OK;
-    if (n == units.size()) return issue_units(c, units, compute);
-    std::vector<PUnit> head(units.begin(), units.begin() + (ptrdiff_t)n);
-    units.erase(units.begin(), units.begin() + (ptrdiff_t)n);
-    const int rc = issue_units(c, head, compute);
+    std::vector<PUnit> go, stay;
+    for (const PUnit &p : units) {
+        const bool ready = io_done(c, p.read_job) && (p.cpu_out < 0 || io_done(c, c->cpu_job[(size_t)p.cpu_out]));
+        (ready || must(p) ? go : stay).push_back(p);
+    }
+    if (go.empty()) return TC_OK;
+    if (stay.empty()) return issue_units(c, units, compute);
+    units.swap(stay);
+    const int rc = issue_units(c, go, compute);
     c->deferred_bytes = 0;
     for (const PUnit &p : units) c->deferred_bytes += p.u.bytes * ((p.u.out_src ? 1 : 0) + (p.u.in_src ? 1 : 0));
     return rc;
+}
+
+static int issue_ready(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute)
+{
+    return issue_some(c, units, compute, [](const PUnit &) { return false; });
+}
+
+// what a module is about to use: the prepared units that fill these GPU buffers have to be on their way,
+// and whatever else is ready goes with them
+int flush_for_buffers(tc_ctx *c, const int64_t *ys, uint32_t n, hipStream_t compute)
+{
+    if (c->deferred.empty()) return TC_OK;
+    c->compute_recorded = false;
+    for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
+    return issue_some(c, c->deferred, compute, [&](const PUnit &p) {
+        for (uint32_t i = 0; i < n; ++i)
+            if (p.gpu_y == ys[i]) return true;
+        return false;
+    });
 }
 
 // The staging region is a ring: a block is taken when a record needs bounce
@@ -425,7 +448,8 @@ static int staging_alloc(tc_ctx *c, std::vector<PUnit> &units, uint64_t bytes, h
             if (rc != TC_OK) return rc;
         }
         if (!c->st_q.front().issued) {
-            int rc = issue_units(c, units, compute);
+            const uint64_t front = c->st_q.front().id;             // its unit goes now, ready or not
+            int rc = issue_some(c, units, compute, [front](const PUnit &p) { return p.st_id == front; });
             if (rc != TC_OK) return rc;
             if (!c->st_q.front().issued) return fail(c, TC_E_STATE, "staging ring holds a block no prepared unit owns");
         }

@@ -675,17 +675,19 @@ hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, u
 
 // ===========================================================================
 // Stand-in for a module's kernels in a replay: stamp written tensors, then spin.
-// One 32-lane group per list entry: lanes 0-15 XOR the head bytes, lanes 16-31
-// the tail bytes.  When head and tail overlap (tensors under 32 bytes) lane 0
-// applies both in order.
+// A 32-lane group per list entry (sixteen groups take the entries in turn): lanes
+// 0-15 XOR the head bytes, lanes 16-31 the tail bytes.  When head and tail overlap
+// (tensors under 32 bytes) lane 0 applies both in order.
 // ===========================================================================
-__global__ __launch_bounds__(32 * TC_MAX_STEP_TENSORS) void tc_stamp_kernel(TcStampArgs a)
+#define STAMP_THREADS 512
+__global__ __launch_bounds__(STAMP_THREADS) void tc_stamp_kernel(TcStampArgs a)
 {
-    const uint32_t i = threadIdx.x >> 5, j = threadIdx.x & 31;
+    const uint32_t j = threadIdx.x & 31;
+    for (uint32_t i = threadIdx.x >> 5; i < a.n; i += STAMP_THREADS / 32) {
     // a list may name a tensor more than once; its stamps are identical and XOR
     // cancels in pairs, so the first occurrence applies it iff the count is odd
     bool apply = false;
-    if (i < a.n && a.ptr[i]) {
+    if (a.ptr[i]) {
         uint32_t same = 0, earlier = 0;
         for (uint32_t k = 0; k < a.n; ++k) {
             same += (a.ptr[k] == a.ptr[i]);
@@ -706,6 +708,7 @@ __global__ __launch_bounds__(32 * TC_MAX_STEP_TENSORS) void tc_stamp_kernel(TcSt
             for (uint32_t b = 0; b < 16; ++b) p[n - 16 + b] ^= (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
         }
     }
+    }
     if (a.busy_ns && threadIdx.x == 0) {
         // wall_clock64 counts at 100 MHz; the loop ends once busy_ns have passed
         const uint64_t t0 = wall_clock64();
@@ -716,7 +719,8 @@ __global__ __launch_bounds__(32 * TC_MAX_STEP_TENSORS) void tc_stamp_kernel(TcSt
 
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(tc_stamp_kernel, dim3(1), dim3(32 * TC_MAX_STEP_TENSORS), 0, s, a);
+    if (a.n > TC_MAX_STEP_TENSORS) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tc_stamp_kernel, dim3(1), dim3(STAMP_THREADS), 0, s, a);
     return hipGetLastError();
 }
 

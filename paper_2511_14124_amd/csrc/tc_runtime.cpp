@@ -464,12 +464,20 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
     sa = TcStampArgs{};
     sa.iteration = c->iteration;
     sa.step = step;
-    for (uint32_t i = 0; i < n && !c->null_mover; ++i)
-        if (o->slots[i] != TC_NONE && c->gpu_pending[c->pools.gpu_base[c->prof.class_of[ids[i]]] + o->slots[i]]) {
-            int rc = flush_deferred(c, compute);          // its copy has to be on its way before the module runs
-            if (rc != TC_OK) return rc;
-            break;
+    {
+        // copies that fill the module's buffers have to be on their way before the module runs
+        int64_t ys[TC_MAX_STEP_TENSORS];
+        uint32_t n_y = 0;
+        for (uint32_t i = 0; i < n && !c->null_mover; ++i) {
+            if (o->slots[i] == TC_NONE) continue;
+            const int64_t y = (int64_t)c->pools.gpu_base[c->prof.class_of[ids[i]]] + o->slots[i];
+            if ((size_t)y < c->gpu_pending.size() && c->gpu_pending[(size_t)y]) ys[n_y++] = y;
         }
+        if (n_y) {
+            int rc = flush_for_buffers(c, ys, n_y, compute);
+            if (rc != TC_OK) return rc;
+        }
+    }
     std::chrono::steady_clock::time_point t0;
     uint64_t waited_ns = 0;
     if (c->host_tier && !c->null_mover) {

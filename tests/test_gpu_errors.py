@@ -52,7 +52,7 @@ def test_hook_arguments_are_checked_before_any_kernel_runs():
     for args in ((99, T.PRE, [0], [1]),                 # step outside the profiled iteration
                  (0, T.PRE, [77], [1]),                 # unknown tensor
                  (0, 5, [0], [1]),                      # no such phase
-                 (0, T.PRE, list(range(6)) * 3, [1] * 18)):   # more than TC_MAX_STEP_TENSORS
+                 (0, T.PRE, list(range(6)) * 11, [1] * 66)):  # more than TC_MAX_STEP_TENSORS
         with pytest.raises(T.TcError) as e:
             tc.migrate_step(*args)
         assert e.value.code == E_ARG

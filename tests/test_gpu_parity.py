@@ -73,6 +73,19 @@ def test_many_tensors_per_step_and_tiny_staging(tmp_path):
     tc.close()
 
 
+@pytest.mark.parametrize("window", [None, 8])
+def test_a_step_may_name_as_many_tensors_as_a_wavefront_has_lanes(window, tmp_path):
+    # up to 64 tensors per hook call (an optimizer step over a whole layer's tensors at once),
+    # hook by hook and in windows, with misses and the file tier; 65 are refused
+    wl = W.random_workload(211, n_tensors=1200, n_steps=30, max_per_step=64, sizes=(4096, 8192, 100, 20000),
+                           hbm_frac=0.0, host_frac=0.3, perturb_one_in=7)
+    assert max(len(st) for it in wl.iterations for st in it) > 48
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=1 << 20, window=window)
+    r = check_against_oracle(wl, tc)
+    assert r.misses > 0
+    tc.close()
+
+
 def test_gpt2_small_config_full_bytes():
     # configuration 1 at full size: 800 tensors, 1.85 GiB, fp16 N(0, 0.02) parameters
     wl = W.config(0)
