@@ -22,6 +22,15 @@ With `ParamCache(..., fused_sgd_lr=lr)` the update of a module's parameters is
 applied in its backward post-hook instead, while they are still in their cache
 buffers: no third pass, a third less traffic; `sgd_step` is then not called.
 
+With `ParamCache(..., manage_grads=True)` the gradients are tensors of the cache
+too (Sec. 3.2.1's hooks cover every tensor a layer touches; Sec. 2.1 counts the
+16-bit gradients beside the parameters): a module's backward step names its
+parameters (read) and their gradients (written), each gradient autograd hands
+over is copied into its cache buffer and dropped, and the optimizer sweep's
+step for a parameter names the gradient (read) and the parameter (read and
+written).  Outside those steps a gradient lives wherever the scheduler put it,
+and `p.grad` is None.
+
 Between its pre-hook and its post-hook a module's parameters are views into
 the HBM cache buffers the library returned; outside that window they point
 nowhere useful and must not be touched.  A parameter may come back for the
@@ -31,10 +40,9 @@ Linear layer a transposed view of the weight, tied to the old buffer).  During
 a managed module's forward the helper therefore installs saved-tensor hooks:
 a tensor that aliases one of the module's parameters is saved as "parameter t,
 this shape, stride and offset" and rebuilt from the parameter's current buffer
-when the backward pass asks for it.  Gradients stay ordinary PyTorch
-tensors: this helper manages parameters only (the FP16-parameter policy of
-Sec. 3.4.2), it is a way to drive the library from real modules, not a
-training framework.
+when the backward pass asks for it.  Without `manage_grads` gradients stay
+ordinary PyTorch tensors (the FP16-parameter policy of Sec. 3.4.2).  This is a
+way to drive the library from real modules, not a training framework.
 
 Only argument marshalling and hook bookkeeping happen here; decisions and
 copies are the library's kernels.
@@ -62,7 +70,8 @@ class _ParamRef:
 
 class ParamCache:
     def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
-                 fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None):
+                 fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None,
+                 manage_grads: bool = False):
         import torch
         self.torch = torch
         self.model = model
@@ -70,6 +79,9 @@ class ParamCache:
         self.host_bytes = host_bytes
         self.align = align
         self.fused_sgd_lr = fused_sgd_lr                  # plain SGD applied in the backward post-hook
+        if manage_grads and fused_sgd_lr is not None:
+            raise ValueError("with the update in the backward hooks no gradient outlives its module: nothing to manage")
+        self.manage_grads = manage_grads                  # gradients are tensors of the cache too (ids n_params + t)
         # parameters of at least this many bytes travel as DMA-engine copies instead of through the
         # zero-copy kernel: slower on the link, but compute running beside them is hardly slowed
         self.dma_threshold = dma_threshold
@@ -82,14 +94,28 @@ class ParamCache:
                 if id(p) not in self.pid:
                     self.pid[id(p)] = len(self.params)
                     self.params.append(p)
-        if any(len(list(m.parameters(recurse=False))) > T.MAX_STEP_TENSORS for m in self.mods):
+        per_step = 2 if manage_grads else 1
+        if any(per_step * len(list(m.parameters(recurse=False))) > T.MAX_STEP_TENSORS for m in self.mods):
             raise ValueError("a module owns more parameters than one hook call may name")
         self.mod_ids = {id(m): [self.pid[id(p)] for p in m.parameters(recurse=False)] for m in self.mods}
-        self._ids_np = {k: np.asarray(v, dtype=np.uint32) for k, v in self.mod_ids.items()}
+        n_p = len(self.params)
+        # what a module's steps name: forward its parameters (read); backward the same, or, with managed
+        # gradients, the parameters (read) and behind them their gradients (written)
+        self._step_lists: Dict[Tuple[int, str], Tuple[list, np.ndarray, np.ndarray]] = {}
+        for k, ids in self.mod_ids.items():
+            self._step_lists[(k, "fwd")] = (ids, np.asarray(ids, dtype=np.uint32), np.full(len(ids), R, dtype=np.uint8))
+            if manage_grads:
+                both = ids + [n_p + t for t in ids]
+                flags = [R] * len(ids) + [W] * len(ids)
+            else:
+                both, flags = ids, [R if fused_sgd_lr is None else RW] * len(ids)
+            self._step_lists[(k, "bwd")] = (both, np.asarray(both, dtype=np.uint32), np.asarray(flags, dtype=np.uint8))
+        self._grad_view: Dict[int, object] = {}           # parameter -> its gradient's cache buffer, during a step that names it
         self._flag_arrays: Dict[Tuple[int, int], np.ndarray] = {}
         self._views: Dict[Tuple[int, int], object] = {}   # (parameter, buffer address) -> view into the HBM region
         self._hbm_base = 0
         self._one_id = [np.asarray([t], dtype=np.uint32) for t in range(len(self.params))]
+        self._pair_id = [np.asarray([len(self.params) + t, t], dtype=np.uint32) for t in range(len(self.params))]
         self.steps: List[List[Tuple[int, int]]] = []      # the profiled iteration
         self.tc: Optional[T.TensorCache] = None
         self._handles: list = []
@@ -109,7 +135,7 @@ class ParamCache:
             self._handles.append(m.register_forward_pre_hook(self._fwd_pre))
             self._handles.append(m.register_forward_hook(self._fwd_post))
             for p in m.parameters(recurse=False):
-                self._handles.append(p.register_post_accumulate_grad_hook(self._make_grad_done(m)))
+                self._handles.append(p.register_post_accumulate_grad_hook(self._make_grad_done(m, self.pid[id(p)])))
 
     def _remove(self):
         for h in self._handles:
@@ -123,35 +149,38 @@ class ParamCache:
             a = self._flag_arrays[(n, rw)] = np.full(n, rw, dtype=np.uint8)
         return a
 
-    def _begin(self, m, rw: int) -> int:
+    def _begin(self, m, kind: str) -> int:
         """Opens the next step for module m (steps are numbered in the order they open)."""
-        ids = self.mod_ids[id(m)]
+        ids, ids_np, rw_np = self._step_lists[(id(m), kind)]
         k = self._k
         self._k += 1
         if self._recording:
-            self.steps.append([(t, rw) for t in ids])
+            self.steps.append([(t, int(a)) for t, a in zip(ids, rw_np)])
         else:
-            self._fetch(k, ids, self._ids_np[id(m)], self._flags(len(ids), rw))
+            self._fetch(k, ids, ids_np, rw_np)
         return k
 
-    def _end(self, m, k: int, rw: int):
+    def _end(self, m, k: int, kind: str):
         if not self._recording:
-            ids = self._ids_np[id(m)]
+            _ids, ids_np, rw_np = self._step_lists[(id(m), kind)]
             stream = self.torch.cuda.current_stream().cuda_stream
-            self.tc.migrate_step(k, T.POST, ids, self._flags(len(ids), rw), stream)
+            self.tc.migrate_step(k, T.POST, ids_np, rw_np, stream)
 
     def _fetch(self, k: int, ids, ids_np, rw_np):
         stream = self.torch.cuda.current_stream().cuda_stream
         ptrs = self.tc.migrate_step(k, T.PRE, ids_np, rw_np, stream, want_ptrs=True)
         for t, ptr in zip(ids, ptrs):
             if not ptr:
-                raise RuntimeError(f"parameter {t} could not be given a GPU buffer (cache too small for this module)")
-            # a parameter comes back to the same few buffers iteration after iteration: keep the views
+                raise RuntimeError(f"tensor {t} could not be given a GPU buffer (cache too small for this module)")
+            # a tensor comes back to the same few buffers iteration after iteration: keep the views
             view = self._views.get((t, ptr))
             if view is None:
                 off, n = ptr - self._hbm_base, self._nbytes[t]
                 view = self._views[(t, ptr)] = self.tc.hbm[off: off + n].view(self._dtype[t]).view(self._shape[t])
-            self.params[t].data = view
+            if t < len(self.params):
+                self.params[t].data = view
+            else:
+                self._grad_view[t - len(self.params)] = view
 
     def _pack_saved(self, x):
         """A tensor the running forward saves for the backward pass: if it aliases one of
@@ -173,7 +202,7 @@ class ParamCache:
         return r
 
     def _fwd_pre(self, m, args):
-        self._fwd_step[id(m)] = self._begin(m, R)
+        self._fwd_step[id(m)] = self._begin(m, "fwd")
         if not self._recording and self.torch.is_grad_enabled():
             ctx = self.torch.autograd.graph.saved_tensors_hooks(self._pack_saved, self._unpack_saved)
             ctx.__enter__()
@@ -185,7 +214,7 @@ class ParamCache:
         if ctx is not None:
             ctx.__exit__(None, None, None)
             self._saving_for = ()
-        self._end(m, self._fwd_step.pop(id(m)), R)
+        self._end(m, self._fwd_step.pop(id(m)), "fwd")
         # the module's backward starts when the gradient of its output arrives
         outs = out if isinstance(out, (tuple, list)) else (out,)
         for o in outs:
@@ -196,22 +225,26 @@ class ParamCache:
     def _make_bwd_start(self, m):
         def hook(grad):
             if id(m) not in self._bwd_step:               # several outputs: the first gradient opens the step
-                self._bwd_step[id(m)] = self._begin(m, R if self.fused_sgd_lr is None else RW)
+                self._bwd_step[id(m)] = self._begin(m, "bwd")
                 self._pending_bwd[id(m)] = len(self.mod_ids[id(m)])
             return grad
         return hook
 
-    def _make_grad_done(self, m):
+    def _make_grad_done(self, m, t):
         def hook(param):
             if id(m) not in self._bwd_step:
                 return
+            if self.manage_grads and not self._recording:
+                # the gradient goes into its cache buffer; the tensor autograd made is dropped
+                self._grad_view.pop(t).copy_(param.grad)
+                param.grad = None
             self._pending_bwd[id(m)] -= 1
             if self._pending_bwd[id(m)] == 0:
                 if self.fused_sgd_lr is not None and not self._recording:
                     with self.torch.no_grad():            # the parameters are still in their cache buffers
                         for p in m.parameters(recurse=False):
                             p.data.add_(p.grad, alpha=-self.fused_sgd_lr)
-                self._end(m, self._bwd_step.pop(id(m)), R)
+                self._end(m, self._bwd_step.pop(id(m)), "bwd")
         return hook
 
     # ---------------------------------------------------------------- profile
@@ -231,17 +264,19 @@ class ParamCache:
         self._n_model_steps = len(self.steps)
         # the optimizer sweep: every parameter once, read and written
         if self.fused_sgd_lr is None:
-            for t in range(len(self.params)):
-                self.steps.append([(t, RW)])
+            n_p = len(self.params)
+            for t in range(n_p):
+                self.steps.append([(n_p + t, R), (t, RW)] if self.manage_grads else [(t, RW)])
         for p in self.params:
             p.grad = None
 
     # ---------------------------------------------------------------- install
     def install(self):
         torch = self.torch
-        self._nbytes = [p.numel() * p.element_size() for p in self.params]
-        self._dtype = [p.dtype for p in self.params]
-        self._shape = [tuple(p.shape) for p in self.params]
+        rep = 2 if self.manage_grads else 1                # gradients: the same sizes once more, ids behind the parameters
+        self._nbytes = [p.numel() * p.element_size() for p in self.params] * rep
+        self._dtype = [p.dtype for p in self.params] * rep
+        self._shape = [tuple(p.shape) for p in self.params] * rep
         if min(self._nbytes) < 16:
             raise ValueError("parameters smaller than 16 bytes are not supported")
         st, te, rw = [], [], []
@@ -251,7 +286,7 @@ class ParamCache:
                 te.append(t)
                 rw.append(a)
         tc = T.TensorCache()
-        tc.profile_order(self._nbytes, [0] * len(self.params), st, te, rw)
+        tc.profile_order(self._nbytes, [0] * len(self._nbytes), st, te, rw)
         host = self.host_bytes if self.host_bytes is not None else sum((n + 255) // 256 * 256 for n in self._nbytes) + 4096
         tc.plan_pools(self.hbm_bytes, (host, 0), self.align)
         tc.plan_schedule()
@@ -263,6 +298,8 @@ class ParamCache:
         for t, p in enumerate(self.params):
             tc.load_tensor(t, p.detach().cpu().contiguous().view(torch.uint8).numpy().reshape(-1))
             p.data = torch.empty(0, dtype=self._dtype[t], device=p.device)
+        for t in range(len(self.params), len(self._nbytes)):
+            tc.load_tensor(t, np.zeros(self._nbytes[t], dtype=np.uint8))
         self.tc = tc
         self._hbm_base = tc.hbm.data_ptr()
         self._views = {}
@@ -279,14 +316,25 @@ class ParamCache:
             raise RuntimeError("the update is applied in the backward hooks (fused_sgd_lr): there is no sweep")
         stream = torch.cuda.current_stream().cuda_stream
         k = self._n_model_steps
+        n_p = len(self.params)
         with torch.no_grad():
             rw = self._flags(1, RW)
+            g_rw = np.asarray([R, RW], dtype=np.uint8)
             for t, p in enumerate(self.params):
-                one = self._one_id[t]
-                self._fetch(k, (t,), one, rw)
-                if p.grad is not None:
+                if self.manage_grads:
+                    ids = (n_p + t, t)
+                    ids_np = self._pair_id[t]
+                    self._fetch(k, ids, ids_np, g_rw)
+                    p.grad = self._grad_view.pop(t)        # the gradient, in its cache buffer, for this step only
                     update(t, p)
-                self.tc.migrate_step(k, T.POST, one, rw, stream)
+                    p.grad = None
+                    self.tc.migrate_step(k, T.POST, ids_np, g_rw, stream)
+                else:
+                    one = self._one_id[t]
+                    self._fetch(k, (t,), one, rw)
+                    if p.grad is not None:
+                        update(t, p)
+                    self.tc.migrate_step(k, T.POST, one, rw, stream)
                 k += 1
 
     def autotune_dma(self, step: Callable[[], None], threshold: int = 64 << 10, steps: int = 2) -> Optional[int]:
@@ -328,6 +376,14 @@ class ParamCache:
         torch = self.torch
         return [torch.from_numpy(self.tc.read_tensor(t)).view(self._dtype[t]).view(self._shape[t])
                 for t in range(len(self.params))]
+
+    def gather_grads(self) -> list:
+        """With managed gradients: every gradient as the cache holds it now (CPU tensors)."""
+        torch, n_p = self.torch, len(self.params)
+        if not self.manage_grads:
+            raise RuntimeError("gradients are not tensors of this cache")
+        return [torch.from_numpy(self.tc.read_tensor(n_p + t)).view(self._dtype[t]).view(self._shape[t])
+                for t in range(n_p)]
 
     def close(self):
         self._remove()

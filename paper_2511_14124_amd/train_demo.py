@@ -86,6 +86,8 @@ def main(argv=None):
                     help="let the first six steps decide between the kernel alone and DMA copies from 64 KiB")
     ap.add_argument("--fused-sgd", action="store_true",
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
+    ap.add_argument("--manage-grads", action="store_true",
+                    help="the gradients are tensors of the cache too (--cache is then a fraction of parameters + gradients)")
     args = ap.parse_args(argv)
 
     import torch
@@ -136,8 +138,9 @@ def main(argv=None):
     # ---- parameters in the tensor cache
     torch.manual_seed(0)
     model = build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
-    pc = ParamCache(model, hbm_bytes=int(param_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None,
-                    dma_threshold=(args.dma_kib << 10) or None)
+    managed_bytes = param_bytes * (2 if args.manage_grads else 1)
+    pc = ParamCache(model, hbm_bytes=int(managed_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None,
+                    dma_threshold=(args.dma_kib << 10) or None, manage_grads=args.manage_grads)
     pc.profile(lambda: iteration(model))
     pc.install()
     pc.tc.set_oplog(False, True)
@@ -166,7 +169,7 @@ def main(argv=None):
     out = {
         "model": {"layers": args.layers, "d_model": args.d_model, "params": n_params, "param_GiB": param_bytes / 2**30,
                   "dtype": "bf16", "tokens_per_step": args.batch * args.seq, "modules_with_hooks": len(pc.mods)},
-        "hbm_cache_GiB": float(plan.hbm_total) / 2**30, "cache_fraction": float(plan.hbm_total) / param_bytes,
+        "hbm_cache_GiB": float(plan.hbm_total) / 2**30, "cache_fraction": float(plan.hbm_total) / managed_bytes,
         "resident": {"ms_per_step": t_res * 1e3, "tokens_per_s": args.batch * args.seq / t_res},
         "through_cache": {"ms_per_step": t_off * 1e3, "tokens_per_s": args.batch * args.seq / t_off,
                           "slowdown": t_off / t_res,
@@ -178,8 +181,10 @@ def main(argv=None):
                           "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters",
                           "dma_copies_from_KiB": (kept >> 10) if kept else None, "chosen_by_timing": bool(args.dma_auto)},
         "final_parameters_equal_resident_training": bool(same),
-        "note": "parameters only are managed (gradients and activations stay resident); plain SGD; hooks drive "
-                "tc_migrate_step one call at a time",
+        "managed": "parameters and gradients" if args.manage_grads else "parameters",
+        "note": ("parameters and their gradients are managed (activations stay resident)" if args.manage_grads else
+                 "parameters only are managed (gradients and activations stay resident)") +
+                "; plain SGD; hooks drive tc_migrate_step one call at a time",
     }
     pc.close()
     print(json.dumps(out))

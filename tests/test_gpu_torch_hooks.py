@@ -23,8 +23,11 @@ def _model(seed):
     return torch.nn.Sequential(*layers).to("cuda:0")
 
 
-@pytest.mark.parametrize("fused", [False, True], ids=["sweep", "fused"])
-def test_training_through_the_cache_equals_resident_training(fused):
+@pytest.mark.parametrize("mode", ["sweep", "fused", "grads"])
+def test_training_through_the_cache_equals_resident_training(mode):
+    # sweep: parameters through the cache, plain SGD as a third pass; fused: the update in the backward hooks;
+    # grads: the gradients are tensors of the cache as well (written in the backward step, read in the sweep)
+    fused, grads = mode == "fused", mode == "grads"
     lr, iters = 0.05, 4
     torch.manual_seed(0)
     xs = [torch.randn(32, 64, device="cuda:0") for _ in range(iters + 1)]
@@ -45,24 +48,35 @@ def test_training_through_the_cache_equals_resident_training(fused):
 
     model = _model(7)
     total = sum(p.numel() * p.element_size() for p in model.parameters())
-    pc = ParamCache(model, hbm_bytes=int(total * 0.4), fused_sgd_lr=lr if fused else None)
+    budget = int(total * (0.8 if grads else 0.4))          # 40 % of the bytes the cache manages
+    pc = ParamCache(model, hbm_bytes=budget, fused_sgd_lr=lr if fused else None, manage_grads=grads)
     pc.profile(lambda: loss_fn(model(xs[-1]), ys[-1]).backward())
     n_mod = len(pc.mods)
     assert len(pc.steps) == 2 * n_mod + (0 if fused else len(pc.params))   # forward, backward, one sweep
     # backward order recorded by the hooks is the reverse of the forward order
+    n_p = len(pc.params)
     fwd = [tuple(t for t, _ in s) for s in pc.steps[:n_mod]]
-    bwd = [tuple(t for t, _ in s) for s in pc.steps[n_mod:2 * n_mod]]
+    bwd = [tuple(t for t, _ in s if t < n_p) for s in pc.steps[n_mod:2 * n_mod]]
     assert bwd == fwd[::-1]
+    if grads:
+        # a backward step names the parameters (read) and behind them their gradients (written);
+        # a sweep step the gradient (read) and the parameter (read and written)
+        for s_f, s_b in zip(pc.steps[:n_mod][::-1], pc.steps[n_mod:2 * n_mod]):
+            assert s_b == [(t, 1) for t, _ in s_f] + [(n_p + t, 2) for t, _ in s_f]
+        assert pc.steps[2 * n_mod:] == [[(n_p + t, 1), (t, 3)] for t in range(n_p)]
     pc.install()
     losses = []
     for i in range(iters):
         loss = loss_fn(model(xs[i]), ys[i])
         loss.backward()
         losses.append(float(loss.detach()))
+        if grads:
+            assert all(p.grad is None for p in model.parameters())   # they live in the cache, not beside it
         if not fused:
             pc.sgd_step(lr)
         pc.end_iteration()
     got = pc.gather()
+    got_grads = pc.gather_grads() if grads else None
     st = pc.tc.cache_stats()
     log = pc.tc.dump_oplog()
     pc.close()
@@ -72,13 +86,16 @@ def test_training_through_the_cache_equals_resident_training(fused):
         assert torch.equal(a, b)
     # the cache really was smaller than the model: tensors moved, and the schedule is the oracle's
     assert st["n_ops"][1] > 0 and st["n_ops"][2] > 0 and st["misses"] == 0
-    nbytes = [p.numel() * p.element_size() for p in ref.parameters()]
+    if grads:                                                # the last iteration's gradients, wherever they ended up
+        for a, b in zip(got_grads, [p.grad.detach().cpu() for p in ref.parameters()]):
+            assert torch.equal(a, b)
+    nbytes = [p.numel() * p.element_size() for p in ref.parameters()] * (2 if grads else 1)
     stp, te, rw = [], [], []
     for k, step in enumerate(pc.steps):
         for (t, a) in step:
             stp.append(k), te.append(t), rw.append(a)
     host = sum((n + 255) // 256 * 256 for n in nbytes) + 4096
-    r = o.build(nbytes, [0] * len(nbytes), stp, te, rw, int(total * 0.4), (host, 0))
+    r = o.build(nbytes, [0] * len(nbytes), stp, te, rw, budget, (host, 0))
     for _ in range(iters):
         r.run_iteration(pc.steps)
     assert len(log) == len(r.log)
@@ -100,6 +117,14 @@ def test_training_demo_runs_a_gpt_shaped_model_through_the_cache(capsys, monkeyp
     assert out["through_cache"]["hit_rate"] == 1.0 and out["final_parameters_equal_resident_training"]
     assert out["through_cache"]["h2d_GiB_per_step"] > 0 and out["cache_fraction"] < 0.8
     assert out["model"]["modules_with_hooks"] == 2 * 6 + 3
+
+
+def test_training_demo_with_the_gradients_in_the_cache():
+    from paper_2511_14124_amd import train_demo
+    out = train_demo.main(["--layers", "2", "--d-model", "128", "--heads", "4", "--vocab", "512", "--batch", "2",
+                           "--seq", "64", "--steps", "2", "--cache", "0.4", "--manage-grads"])
+    assert out["managed"] == "parameters and gradients" and out["final_parameters_equal_resident_training"]
+    assert out["through_cache"]["hit_rate"] == 1.0 and out["cache_fraction"] < 0.8
 
 
 def test_train_demo_with_cpu_adam_over_the_two_tier_cache():
