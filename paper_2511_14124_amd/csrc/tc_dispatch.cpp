@@ -56,6 +56,7 @@ static int begin_op(tc_ctx *c, int S, hipStream_t compute, uint64_t *id)
         int rc = wait_op(c, n - OP_RING);              // the event about to be reused
         if (rc != TC_OK) return rc;
     }
+    if (c->streams[S] == compute) c->stream_waited[S] = true;    // one queue, in order: nothing to wait for
     if (!c->stream_waited[S]) {
         if (!c->compute_recorded) {
             HIP_TRY(c, hipEventRecord(c->ev_compute, compute));

@@ -517,7 +517,9 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
                         for (int k = 0; k < N_STREAMS; ++k) c->waited_op[k] = 0;
                     }
                     if (ticket > c->waited_op[st]) {
-                        HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
+                        // (a module queued on the very stream the copy runs on is behind it anyway)
+                        if (c->streams[st] != compute)
+                            HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
                         c->waited_op[st] = ticket;
                     }
                 }

@@ -28,14 +28,15 @@ def compare_logs(got, want):
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
                 busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False, direct=False,
                 io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False, dma_when_behind=False,
-                stripe_paths=None):
+                stripe_paths=None, one_stream=False):
     """Replays every iteration of wl through the library; returns the context.
 
     window None: one tc_migrate_step call per hook (the hook-driven interface);
     otherwise tc_replay_iteration with that many steps per decision launch.
     fill: the library's fill kernel writes the payload pattern instead of
     tc_load_tensor (for footprints too large to generate on the host).
-    host_tier: the two-tier mode (the fast tier is pinned host memory)."""
+    host_tier: the two-tier mode (the fast tier is pinned host memory).
+    one_stream: the stand-in modules run on the migration stream itself."""
     import torch
     tc = T.TensorCache.from_workload(wl)
     tc.bind_torch(null_mover=null_mover, file_path=file_path, staging_bytes=staging_bytes, direct=direct,
@@ -62,7 +63,7 @@ def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_b
     elif payload and not null_mover:
         for t in range(wl.n_tensors):
             tc.load_tensor(t, W.workload_payload(wl, t))
-    cs = torch.cuda.Stream()
+    cs = tc.mstream if one_stream else torch.cuda.Stream()
     for steps in wl.iterations:
         ns = wl.compute_ns if busy else None
         if window is None:

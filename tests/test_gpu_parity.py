@@ -170,6 +170,21 @@ def test_merging_hook_calls_into_launches_keeps_every_byte(merge_bytes, tmp_path
     tc.close()
 
 
+@pytest.mark.parametrize("window", [None, 16])
+def test_modules_on_the_migration_stream_itself_keep_every_byte(window, tmp_path):
+    # a caller may compute on the stream the copies run on (one queue, in order): no event is waited for
+    # across streams then, and schedule and bytes are what they are with two streams
+    wl = W.random_workload(23, n_tensors=120, n_steps=90, max_per_step=3, sizes=(70001, 262144 + 48, 1 << 20, 17, 4096),
+                           hbm_frac=0.1, host_frac=0.5, perturb_one_in=9)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=4 << 20, window=window, one_stream=True, busy=True)
+    check_against_oracle(wl, tc)
+    tc.close()
+    wl = W.config(0, layers=6)
+    tc = run_library(wl, window=window, one_stream=True)
+    check_against_oracle(wl, tc)
+    tc.close()
+
+
 @pytest.mark.parametrize("busy", [False, True], ids=["idle_compute", "busy_compute"])
 def test_dma_copies_only_behind_a_compute_backlog_keep_every_byte(busy, tmp_path):
     # with the policy "when behind" the path a large tensor takes (DMA engines or the kernel)
