@@ -768,6 +768,75 @@ def test_the_by_this_call_rules_do_matter_somewhere():
 
 
 # ----------------------------------------------------------------------------
+# Two more choices the paper leaves open, shown to decide nothing that the bar names.
+# (1) Which free buffer is handed out at run time (R9 fixes only "buffer0 first"): with the HIGHEST
+#     free buffer instead, the schedule of every fixed trace is the same record for record, buffer
+#     numbers included (in steady state a class never has two free buffers: every move is a swap),
+#     and on the perturbed configuration it is the same except for buffer numbers.
+# (2) Ties between victims (R11, R12, R14: lowest id): a tie needs two tensors with the same next
+#     use, and two tensors never share a row of the prefetch table, so ties arise only between
+#     tensors that are not used again in the iteration; whichever goes, no hit or miss changes on a
+#     trace that follows its profile.
+# ----------------------------------------------------------------------------
+
+def _replay_patched(wl, patch):
+    st, te, rw, _ = wl.events()
+    r = o.build(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw,
+                wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2, None,
+                prefetch=not getattr(wl, "no_prefetch", False))
+    patch(r)
+    for steps in wl.iterations:
+        r.run_iteration(steps)
+    return r
+
+
+@pytest.mark.parametrize("name", _FIXED_TRACES)
+def test_which_free_buffer_is_handed_out_decides_nothing_but_buffer_numbers(name):
+    wl = _named_workload(name)
+
+    def highest_free_first(r):
+        def pick(owner, freed):
+            for k in range(len(owner) - 1, -1, -1):
+                if owner[k] == o.NONE and freed[k] != r.call:
+                    return k
+            return o.NONE
+        r._lowest_free = pick
+
+    got, want = _replay_patched(wl, highest_free_first), o.replay_workload(wl)
+    without_buffers = lambda log: [(e[0], e[1], e[2], e[3], e[4], e[5], e[7], e[9]) for e in log]
+    assert without_buffers(got.log) == without_buffers(want.log)
+    assert (got.hits, got.misses, got.fails, got.cur) == (want.hits, want.misses, want.fails, want.cur)
+    if name != "config4":                  # the unperturbed traces: not even a buffer number changes
+        assert got.log == want.log
+
+
+@pytest.mark.parametrize("name", _FIXED_TRACES[:-1])
+def test_victim_ties_arise_only_between_tensors_not_used_again_and_change_no_hit_or_miss(name):
+    wl = _named_workload(name)
+    seen = {"ties": 0}
+
+    def highest_id_wins(r):
+        def pick(cands, bound):
+            lo = hi = o.NONE
+            for x in cands:
+                nu = r.p.next_use(x, bound)
+                if lo == o.NONE or (-nu, x) < (-r.p.next_use(lo, bound), lo):
+                    lo = x
+                if hi == o.NONE or (-nu, -x) < (-r.p.next_use(hi, bound), -hi):
+                    hi = x
+            if lo != hi:                   # a tie: both are never used again in this iteration
+                seen["ties"] += 1
+                assert r.p.next_use(lo, bound) == r.p.next_use(hi, bound) == r.p.next_use(lo, r.p.n_rows)
+            return hi
+        r._farthest = pick
+
+    got, want = _replay_patched(wl, highest_id_wins), o.replay_workload(wl)
+    assert (got.hits, got.misses, got.fails) == (want.hits, want.misses, want.fails)
+    if name.startswith("config"):
+        assert seen["ties"] > 0            # (the configurations do have such ties: the test is not vacuous)
+
+
+# ----------------------------------------------------------------------------
 # end of iteration (Sec. 3.2.1: tensors are restored to their final locations).  Whatever the
 # order, every displaced tensor must move, none needs to move twice, nothing else moves at all.
 # ----------------------------------------------------------------------------
