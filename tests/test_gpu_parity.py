@@ -33,6 +33,13 @@ def test_worked_example_cpu_gpu_nvme(tmp_path):
     tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=1 << 16)
     check_against_oracle(wl, tc)
     tc.close()
+    # the same example with the two sizes its text implies (tensor 2 is the one spilled)
+    wl = W.example_cpu_gpu_nvme_two_sizes()
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=1 << 16)
+    r = check_against_oracle(wl, tc)
+    from oracle import tc_oracle as o
+    assert [e[4] for e in r.log if e[3] == o.SPILL] == [1]
+    tc.close()
 
 
 @pytest.mark.parametrize("n,k", [(8, 3), (8, 1), (5, 5), (70, 9), (200, 130)])

@@ -92,7 +92,8 @@ def test_plan_and_placement_match_the_oracle_on_random_traces(seed):
 
 def test_worked_example_placements():
     for wl, gpu, cpu, nvme in ((W.example_cpu_gpu(), [0, 1, 2], [3, 4, 5], []),
-                               (W.example_cpu_gpu_nvme(), [0, 1, 2], [3, 4, 5], [6])):
+                               (W.example_cpu_gpu_nvme(), [0, 1, 2], [3, 4, 5], [6]),
+                               (W.example_cpu_gpu_nvme_two_sizes(), [0, 1, 2], [3, 4, 5], [6])):
         tc = T.TensorCache.from_workload(wl)
         f = tc.placement["final_tier"]
         assert [t for t in range(wl.n_tensors) if f[t] == T.GPU] == gpu

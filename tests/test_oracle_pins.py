@@ -272,6 +272,35 @@ def test_example_cpu_gpu_nvme_matches_what_the_text_fixes():
     assert ops == [("RELEASE", 7), ("PREFETCH", 4)]   # the NVMe copy exists: only the buffer is freed
 
 
+def test_example_cpu_gpu_nvme_with_the_sizes_the_text_implies_spills_tensor_2():
+    # the text's reason for spilling tensor 2 is its size (that of tensor 4): with two sizes every
+    # printed state is reproduced, the identity of the spilled tensor included
+    wl = W.example_cpu_gpu_nvme_two_sizes()
+    r, lines, states, logs, slots = _run_example(wl, "example_cpu_gpu_nvme_two_sizes.txt")
+    assert (r.plan.gpu_count, r.plan.cpu_count) == ([2, 1], [2, 1])
+    for line in lines:
+        if line.startswith("halt"):
+            assert logs[line[5:].strip()] == [], line
+            continue
+        if line.startswith("reuse"):
+            assert slots["backward_done 7"][3] == slots["forward_done 7"][6]
+            continue
+        ev, g, c, n = [x.strip() for x in line.split(";")]
+        want = tuple({int(i) for i in _ids(x).split(",") if i} for x in (g, c, n))
+        got_g, got_c, got_n = states[ev]
+        # a tensor brought in from NVMe keeps its NVMe copy: the fixture lists 7 there throughout
+        assert (got_g, got_c, got_n | {7}) == want, (ev, states[ev], want)
+    ops = [(o.OP_NAMES[e[3]], e[4] + 1) for e in logs["forward_done 5"]]
+    assert ops == [("SPILL", 2), ("EVICT", 4), ("PREFETCH", 7)]
+    assert logs["forward_done 5"][1][8] == logs["forward_done 5"][0][6]    # 4 takes the host buffer 2 left
+    assert logs["forward_done 5"][2][5] == o.NVME                          # 7 comes from the file tier
+    ops = [(o.OP_NAMES[e[3]], e[4] + 1) for e in logs["backward_done 7"]]
+    assert ops == [("RELEASE", 7), ("PREFETCH", 4)]
+    assert r.misses == 0 and r.hits == 14
+    r.end_iteration()
+    assert _tiers(r) == ({1, 2, 3}, {4, 5, 6}, {7})
+
+
 # ----------------------------------------------------------------------------
 # closed form: one class, N tensors, K GPU buffers, trace 0..N-1, N-1..0
 # ----------------------------------------------------------------------------

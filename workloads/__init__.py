@@ -9,7 +9,7 @@ the library stay independent of each other while replaying identical inputs.
 from .traces import (  # noqa: F401
     R, W, RW, GROUP_16, GROUP_32, Workload, PHASE_FORWARD, PHASE_BACKWARD, PHASE_OPTIMIZER,
     config, config_names, gpt_shaped, llama_shaped, scaled_config,
-    example_cpu_gpu, example_cpu_gpu_nvme, single_class_fwd_bwd,
+    example_cpu_gpu, example_cpu_gpu_nvme, example_cpu_gpu_nvme_two_sizes, single_class_fwd_bwd,
     random_workload, optimizer_sweep, single_class_sweep, perturb_iteration, splitmix64,
 )
 from .payload import payload_bytes, payload_words, gaussian_fp16_bytes, workload_payload, PAYLOAD_SEED  # noqa: F401

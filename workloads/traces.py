@@ -413,6 +413,22 @@ def example_cpu_gpu_nvme() -> Workload:
     return single_class_fwd_bwd(7, 3, 3)
 
 
+def example_cpu_gpu_nvme_two_sizes() -> Workload:
+    """The CPU-GPU-NVMe example of Sec. 3.4.2 with the sizes its text implies: the text
+    spills tensor 2 because it "has the same size as tensor 4", so not every tensor has
+    that size.  Tensors 2, 4 and 7 (paper ids) are 1024 bytes, tensors 1, 3, 5 and 6 are
+    512; budgets of half of all bytes on the GPU and half below it give Alg. 2 two + one
+    GPU buffers and two + one host buffers, and the allocator GPU {1,2,3}, CPU {4,5,6},
+    NVMe {7} as the figure has it.  Ids here are the paper's minus 1."""
+    small, large = 512, 1024
+    sizes = [small, large, small, large, small, small, large]
+    n = len(sizes)
+    steps = [[(t, R)] for t in range(n)] + [[(t, R)] for t in reversed(range(n))]
+    total = sum(sizes)
+    return _simple("example_cpu_gpu_nvme_two_sizes", sizes, [0] * n, steps, hbm_bytes=total // 2,
+                   host_bytes=(total // 2, 0))
+
+
 def random_workload(seed: int, *, n_tensors: int = 24, n_steps: int = 40, max_per_step: int = 3,
                     sizes: Sequence[int] = (512, 1024, 4096, 100, 33000), hbm_frac: float = 0.4,
                     host_frac: float = 0.4, two_groups: bool = True, n_iterations: int = 2,
