@@ -312,7 +312,7 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
     return res, extra
 
 
-def hit_rate_ablations(T, W, indices=(0, 1, 2)):
+def hit_rate_ablations(T, W, indices=(0, 1, 2, 3, 4)):
     """GPU cache hit rates of the variants the paper compares (its Sec. 4.1.4 and 4.3), by dry replays
     with the null mover (the decision kernel runs, no byte moves; a hit rate is a property of the
     schedule): the paper's allocator and scheduler, its base variant (no prefetching), and the
