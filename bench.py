@@ -105,6 +105,42 @@ def bench_pack(torch, T, total_bytes=4 << 30, reps=6, shift=0, unpack=False):
     return 2.0 * total / (sustained * 1e-3) / 1e9, sustained, float(min(times[1:])), total, n
 
 
+def bench_pack_natural(torch, T, launches=200):
+    """What the pack kernel costs at the volume one hook step naturally has: the small tensors
+    of one GPT-2-small block's modules (two LayerNorm vectors, the attention and the two
+    FFN biases: five segments, 15 KiB), `launches` launches back to back.  Latency, not bandwidth."""
+    dev = torch.device("cuda:0")
+    nb = np.asarray([1536, 1536, 4608, 1536, 6144], dtype=np.uint64)
+    off = np.zeros(len(nb), dtype=np.uint64)
+    off[1:] = np.cumsum(nb)[:-1]
+    total = int(nb.sum())
+    src = torch.empty(256 * len(nb) + total, dtype=torch.uint8, device=dev).random_(0, 255)
+    slab = torch.empty(total, dtype=torch.uint8, device=dev)
+    src_off = off + np.arange(len(nb), dtype=np.uint64) * np.uint64(256)       # each tensor in a buffer of its own
+    ptrs = torch.from_numpy((src_off + np.uint64(src.data_ptr())).astype(np.int64)).to(dev)
+    nbt = torch.from_numpy(nb.astype(np.int64)).to(dev)
+    offt = torch.from_numpy(off.astype(np.int64)).to(dev)
+    st = torch.cuda.current_stream().cuda_stream
+    index = torch.empty(T.pack_tiles(total), dtype=torch.int32, device=dev)
+    T.pack_index(offt.data_ptr(), len(nb), total, index.data_ptr(), st)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {}
+    for name, fn in (("pack", T.pack), ("unpack", T.unpack)):
+        for k in range(launches + 8):
+            if k == 8:
+                e0.record()
+            fn(slab.data_ptr(), ptrs.data_ptr(), nbt.data_ptr(), offt.data_ptr(), len(nb), total, st, index.data_ptr())
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_us_per_launch"] = e0.elapsed_time(e1) * 1e3 / launches
+    want = torch.cat([src[int(o): int(o) + int(n)] for o, n in zip(src_off, nb)])
+    T.pack(slab.data_ptr(), ptrs.data_ptr(), nbt.data_ptr(), offt.data_ptr(), len(nb), total, st, index.data_ptr())
+    torch.cuda.synchronize()
+    out.update(segments=len(nb), payload_bytes=total, exact=bool(torch.equal(slab, want)),
+               note="one hook step's small tensors (five segments of 1.5 - 6 KiB): back-to-back launches, latency-bound")
+    return out
+
+
 # --------------------------------------------------------------------------------------
 # the box
 # --------------------------------------------------------------------------------------
@@ -616,7 +652,8 @@ def main():
                                    "note": "pack, every tensor 4 bytes off the slab's 16-byte phase"},
             "odd_shift_variant": {"achieved": odd_gbs, "frac": odd_gbs / 8000.0, "ms": odd_ms,
                                   "unpack": {"achieved": odd_un_gbs, "frac": odd_un_gbs / 8000.0, "ms": odd_un_ms},
-                                  "note": "every tensor 1 byte off"}}
+                                  "note": "every tensor 1 byte off"},
+            "natural_step": bench_pack_natural(torch, T)}
     if not args.no_cpu:
         log("CPU baseline: the oracle in full-bytes mode on configuration 2")
         out["cpu_baseline"] = cpu_baseline(W)
