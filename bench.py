@@ -217,9 +217,10 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
             tc.set_io_chunk(args.io_chunk_mib << 20)
         if direct and not args.io_chunk_mib:
             # a device that is read and written directly wants few large sequential requests on this
-            # box's virtual disk: one request per tensor, one thread per direction
+            # box's virtual disk: one request per tensor, two threads per direction (measured: 1 + 1
+            # 6.0, 2 + 2 7.0, 4 + 4 with 64 MiB chunks 6.3, 8 + 8 with 16 MiB chunks 5.4 GB/s host->HBM)
             tc.set_io_chunk(((big + (1 << 20) - 1) >> 20) << 20)
-            tc.set_io_threads(1, 1)
+            tc.set_io_threads(2, 2)
         elif args.io_threads:
             tc.set_io_threads(*args.io_threads)
         file_mode = {"io": "O_DIRECT (page cache bypassed)" if direct else "buffered (through the page cache)",
@@ -288,7 +289,7 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
             read_GBps_over_wall=d["bytes_file_read"] / dt / 1e9, write_GBps_over_wall=d["bytes_file_write"] / dt / 1e9,
             read_GBps_in_call=d["bytes_file_read"] / max(1, d["file_read_ns"]),
             write_GBps_in_call=d["bytes_file_write"] / max(1, d["file_write_ns"]),
-            io_threads="1 + 1" if direct and not args.io_chunk_mib else list(args.io_threads),
+            io_threads=[2, 2] if direct and not args.io_chunk_mib else list(args.io_threads),
             link_time_share=(d["bytes_h2d"] / 1e9 / link["h2d"]) / dt,
             inside_launches_GBps_both_directions=tm["kernel_bytes"] / max(1.0, tm["kernel_ns"]),
             hook_thread_blocked_ms_per_iteration={
@@ -548,6 +549,15 @@ def main():
                                     tier_dirs=dirs, direct=args.direct)
                 if rows:
                     res["depth_the_box_holds"] = rows
+                per_config.append(res)
+            if index == 3 and not args.direct:
+                # the same with the page cache bypassed (O_DIRECT): what this box's disk itself gives,
+                # at a depth that keeps the row to some seconds
+                try:
+                    res, _ = run_config(torch, T, W, link, index, 4, args, steps=1, warmup=1, stall=False,
+                                        tier_dirs=tier_dirs, direct=True)
+                except Exception as e:                 # a directory that does not take O_DIRECT (tmpfs)
+                    res = {"config": index + 1, "layers": 4, "file_tier": {"io": "O_DIRECT"}, "skipped": str(e)[:200]}
                 per_config.append(res)
             if index == 0 and not args.one_stream:
                 # configuration 1's cache is so shallow that launches and modules alternate anyway: what the
