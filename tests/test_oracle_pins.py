@@ -1000,6 +1000,26 @@ def test_nothing_touches_the_file_tier_while_gpu_and_cpu_hold_the_model():
         assert literal.bytes_h2d > taken.bytes_h2d
 
 
+def test_the_literal_eviction_contradicts_the_states_the_text_prints_for_two_sizes():
+    # R11 against the paper itself: in the CPU-GPU-NVMe example with the two sizes its text implies,
+    # evicting every finished tensor whatever the size of the incoming one (Alg. 3 as printed) spills
+    # into NVMe as soon as tensor 1 finishes (its size class has no free host buffer), while the text
+    # has NVMe hold tensor 7 alone until tensor 2 is spilled for tensor 4; the reading taken reproduces
+    # the printed states (test_example_cpu_gpu_nvme_with_the_sizes_the_text_implies_spills_tensor_2)
+    wl = W.example_cpu_gpu_nvme_two_sizes()
+    st, te, rw, _ = wl.events()
+    p = o.profile(wl.tensor_bytes.tolist(), wl.tensor_group.tolist(), st, te, rw)
+    plan = o.plan_pools(p, wl.hbm_bytes, wl.host_bytes, wl.align, wl.literal_alg2)
+    lit, taken = _EvictWhateverTheSize(p, plan, o.place(p, plan)), o.Replay(p, plan, o.place(p, plan))
+    for r in (lit, taken):
+        for k in range(4):                                       # forward through tensor 4
+            r.pre(k, wl.profile[k])
+            r.post(k, [t for t, _ in wl.profile[k]])
+    assert _tiers(taken) == ({4, 5, 6}, {1, 2, 3}, {7})          # as printed
+    assert not any(e[3] == o.SPILL for e in taken.log)
+    assert any(e[3] == o.SPILL for e in lit.log) and _tiers(lit)[2] != {7}
+
+
 def test_on_one_tensor_size_the_literal_eviction_and_the_reading_taken_agree():
     # (the worked examples have one size: there the two are the same algorithm)
     for wl in (W.example_cpu_gpu(), W.example_cpu_gpu_nvme(), W.single_class_fwd_bwd(9, 4, 5), W.single_class_sweep(8, 5)):
