@@ -141,6 +141,77 @@ def bench_pack_natural(torch, T, launches=200):
     return out
 
 
+def bench_small_tensor_routes(torch, T, reps=200):
+    """The small tensors of six GPT-2-small blocks (48 tensors of 1.5 - 6 KiB, 120 KiB), swapped between
+    HBM buffers and pinned host buffers of their own, two ways: (a) as the replay moves them, one launch
+    of the migration kernel with 48 exchange units; (b) through slabs: pack the outgoing tensors into a
+    slab in HBM, one exchange unit (slab out, slab in), unpack the incoming slab into the buffers - three
+    launches, and that without the gather and scatter between the slab and the per-tensor host buffers
+    the host tier keeps, which the CPU would have to do on top.  Microseconds per swap of all 48."""
+    dev = torch.device("cuda:0")
+    nb = np.asarray([1536, 1536, 4608, 1536, 1536, 1536, 6144, 1536] * 6, dtype=np.uint64)
+    n = len(nb)
+    stride = (nb + np.uint64(255)) // np.uint64(256) * np.uint64(256)
+    boff = np.zeros(n, dtype=np.uint64)
+    boff[1:] = np.cumsum(stride)[:-1]
+    soff = np.zeros(n, dtype=np.uint64)
+    soff[1:] = np.cumsum(nb)[:-1]
+    room, total = int(stride.sum()), int(nb.sum())
+    hbm = torch.empty(room, dtype=torch.uint8, device=dev).random_(0, 255)
+    host_out = torch.empty(room, dtype=torch.uint8).pin_memory()
+    host_in = torch.empty(room, dtype=torch.uint8).random_(0, 255).pin_memory()
+    slab_out, slab_in = (torch.empty(total, dtype=torch.uint8, device=dev) for _ in range(2))
+    pin_slab_out = torch.empty(total, dtype=torch.uint8).pin_memory()
+    pin_slab_in = torch.empty(total, dtype=torch.uint8).pin_memory()
+    for i in range(n):                                   # the incoming slab holds what the host buffers hold
+        pin_slab_in[int(soff[i]): int(soff[i] + nb[i])] = host_in[int(boff[i]): int(boff[i] + nb[i])]
+    g = boff + np.uint64(hbm.data_ptr())
+    ptrs = torch.from_numpy(g.astype(np.int64)).to(dev)
+    nbt = torch.from_numpy(nb.astype(np.int64)).to(dev)
+    offt = torch.from_numpy(soff.astype(np.int64)).to(dev)
+    st = torch.cuda.current_stream().cuda_stream
+    index = torch.empty(T.pack_tiles(total), dtype=torch.int32, device=dev)
+    T.pack_index(offt.data_ptr(), n, total, index.data_ptr(), st)
+    one = lambda x: np.asarray([x], dtype=np.uint64)
+
+    def batched():
+        T.exchange_batch(g, boff + np.uint64(host_out.data_ptr()), boff + np.uint64(host_in.data_ptr()), g, nb, st)
+
+    def slabs():
+        T.pack(slab_out.data_ptr(), ptrs.data_ptr(), nbt.data_ptr(), offt.data_ptr(), n, total, st, index.data_ptr())
+        T.exchange_batch(one(slab_out.data_ptr()), one(pin_slab_out.data_ptr()), one(pin_slab_in.data_ptr()),
+                         one(slab_in.data_ptr()), one(total), st)
+        T.unpack(slab_in.data_ptr(), ptrs.data_ptr(), nbt.data_ptr(), offt.data_ptr(), n, total, st, index.data_ptr())
+
+    before = hbm.clone()
+    out = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for name, fn in (("batched_exchange_units", batched), ("through_slabs", slabs)):
+        hbm.copy_(before)
+        fn()
+        torch.cuda.synchronize()
+        # one swap: the buffers now hold the host's tensors, the host side the buffers' old content
+        ok = all(torch.equal(hbm[int(boff[i]): int(boff[i] + nb[i])].cpu(), host_in[int(boff[i]): int(boff[i] + nb[i])])
+                 for i in range(n))
+        left = pin_slab_out if name == "through_slabs" else host_out
+        loff = soff if name == "through_slabs" else boff
+        ok = ok and all(torch.equal(left[int(loff[i]): int(loff[i] + nb[i])], before[int(boff[i]): int(boff[i] + nb[i])].cpu())
+                        for i in range(n))
+        for k in range(reps + 4):
+            if k == 4:
+                e0.record()
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = {"us_per_swap": e0.elapsed_time(e1) * 1e3 / reps, "exact": bool(ok),
+                     "launches": 1 if name == "batched_exchange_units" else 3}
+    out.update(tensors=n, payload_bytes=total,
+               note="why the replay sends small tensors as units of the batched launch and not through a slab: "
+                    "the slab route costs two more launches and, on the host side (not timed here), a gather and a "
+                    "scatter between the slab and the per-tensor host buffers")
+    return out
+
+
 # --------------------------------------------------------------------------------------
 # the box
 # --------------------------------------------------------------------------------------
@@ -663,7 +734,8 @@ def main():
             "odd_shift_variant": {"achieved": odd_gbs, "frac": odd_gbs / 8000.0, "ms": odd_ms,
                                   "unpack": {"achieved": odd_un_gbs, "frac": odd_un_gbs / 8000.0, "ms": odd_un_ms},
                                   "note": "every tensor 1 byte off"},
-            "natural_step": bench_pack_natural(torch, T)}
+            "natural_step": bench_pack_natural(torch, T),
+            "small_tensor_routes": bench_small_tensor_routes(torch, T)}
     if not args.no_cpu:
         log("CPU baseline: the oracle in full-bytes mode on configuration 2")
         out["cpu_baseline"] = cpu_baseline(W)
