@@ -307,6 +307,8 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
         tuned_wgs = tc.tune_mover()        # the regions hold nothing yet: measure the workgroup count
     if args.merge_mib is not None:
         tc.set_merge_bytes(args.merge_mib << 20)
+    if args.dma_mib:
+        tc.set_dma_threshold(int(args.dma_mib * (1 << 20)))
     t_fill = time.perf_counter()
     tc.fill_payload(0)
     t_fill = time.perf_counter() - t_fill
@@ -551,6 +553,8 @@ def main():
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--merge-mib", type=int, default=1024, help="bytes merged into one migration launch")
+    ap.add_argument("--dma-mib", type=float, default=0,
+                    help="tensors of at least this many MiB travel as DMA-engine copies (0: everything in the kernel)")
     ap.add_argument("--one-stream", action="store_true",
                     help="the stand-in modules run on the migration stream itself (no second queue, nothing overlaps)")
     ap.add_argument("--io-threads", type=int, nargs=2, default=[8, 8], metavar=("WRITERS", "READERS"),
@@ -696,12 +700,15 @@ def main():
                      "avg_launch_us": tm["kernel_ns"] / 1e3 / max(1, n_launch),
                      "algorithmic_bytes_per_launch": tm["kernel_bytes"] / max(1, n_launch),
                      "peak_published": 128.0,
+                     "frac_of_dma_duplex": achieved / (2.0 * link["duplex_each"]) if link.get("duplex_each") else None,
                      "note": "bound by the host link, both directions in use; achieved = bytes crossing the link "
                              "(H2D + D2H) / time inside launches (HIP events on the migration stream); peak = measured "
                              "one-way pinned hipMemcpyAsync H2D peak + D2H peak of this run (an upper bound: with both "
                              "directions loaded each carries the other's read requests and acknowledgements); "
                              "duplex_each = what concurrent hipMemcpyAsync H2D + D2H reach per direction in this "
-                             "process; peak_published = PCIe 5.0 x16 raw, both directions"},
+                             "process (two streams whose first copies ran at once, so that they use two DMA engines); "
+                             "frac_of_dma_duplex = achieved / (2 x duplex_each): the kernel against what the DMA engines "
+                             "move with both directions loaded; peak_published = PCIe 5.0 x16 raw, both directions"},
     }
     if "file_tier" in head:
         out["file_tier"] = head["file_tier"]
