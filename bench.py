@@ -349,6 +349,12 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
         "working_workgroups": tuned_wgs or args.workgroups or 12,
         "streams": "one: modules and copies in one queue" if one_stream else "two: modules on a stream of their own",
     }
+    if args.dma_mib:
+        res["dma_path"] = {"from_MiB": args.dma_mib, "copies": tm["h2d_copies"] + tm["d2h_copies"],
+                           "h2d_GBps_inside_copies": tm["h2d_bytes"] / max(1.0, tm["h2d_ns"]),
+                           "d2h_GBps_inside_copies": tm["d2h_bytes"] / max(1.0, tm["d2h_ns"]),
+                           "h2d_busy_share": tm["h2d_ns"] * 1e-9 / dt, "d2h_busy_share": tm["d2h_ns"] * 1e-9 / dt,
+                           "kernel_bytes_share": tm["kernel_bytes"] / max(1, tm["kernel_bytes"] + tm["h2d_bytes"] + tm["d2h_bytes"])}
     if wl.alloc_write_only:
         na = s1["bytes_not_fetched"] - s0["bytes_not_fetched"]
         res["allocate_without_fetch"] = {"GiB_not_fetched_per_iteration": na / steps / GiB,
@@ -712,6 +718,8 @@ def main():
     }
     if "file_tier" in head:
         out["file_tier"] = head["file_tier"]
+    if "dma_path" in head:
+        out["dma_path"] = head["dma_path"]
     if awf:
         out["allocate_without_fetch"] = awf
     if per_config:
