@@ -307,6 +307,8 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
         tuned_wgs = tc.tune_mover()        # the regions hold nothing yet: measure the workgroup count
     if args.merge_mib is not None:
         tc.set_merge_bytes(args.merge_mib << 20)
+    if args.gpu_deps:
+        tc.set_gpu_dependencies(True)
     if args.dma_mib:
         tc.set_dma_threshold(int(args.dma_mib * (1 << 20)))
     t_fill = time.perf_counter()
@@ -561,6 +563,8 @@ def main():
     ap.add_argument("--merge-mib", type=int, default=1024, help="bytes merged into one migration launch")
     ap.add_argument("--dma-mib", type=float, default=0,
                     help="tensors of at least this many MiB travel as DMA-engine copies (0: everything in the kernel)")
+    ap.add_argument("--gpu-deps", action="store_true",
+                    help="dependencies between modules and migration launches resolved on the GPU (tc_set_gpu_dependencies)")
     ap.add_argument("--one-stream", action="store_true",
                     help="the stand-in modules run on the migration stream itself (no second queue, nothing overlaps)")
     ap.add_argument("--io-threads", type=int, nargs=2, default=[8, 8], metavar=("WRITERS", "READERS"),

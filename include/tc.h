@@ -456,6 +456,26 @@ int tc_set_replay_window(tc_ctx *ctx, uint32_t steps);
  * streams and the bounce block back. */
 int tc_set_dma_threshold(tc_ctx *ctx, uint64_t bytes);
 
+/* Dependencies between module kernels and migration launches resolved on the
+ * GPU instead of by events between the two streams (a wait across hardware
+ * queues takes about 17 us on this hardware, twice per launch where launches
+ * and modules alternate).  enable != 0: a hook call that prepares copies
+ * queues a one-lane kernel on its compute stream that raises a sequence word
+ * behind the modules queued so far; the migration launch is queued at once and
+ * its workgroups wait for that word themselves; every launch raises a second
+ * word when its last workgroup leaves, and a module that needs what a launch
+ * brings is preceded on its stream by a one-lane kernel that waits for it.
+ * Every such wait is bounded by timeout_ms (0 = 5000): a waiter that gives up
+ * moves nothing, and the next hook call or tc_synchronize returns TC_E_HIP; the
+ * bytes are then not to be trusted and the context should be destroyed.  Use
+ * it where every module's kernels finish well within the timeout and the
+ * compute stream and the migration stream run on different hardware queues
+ * (two streams of one process normally do).  With the modules on the migration
+ * stream itself nothing changes (that stream is in order).  Decisions and
+ * bytes never depend on the setting.  The call waits for the copies in flight.
+ * Default: off. */
+int tc_set_gpu_dependencies(tc_ctx *ctx, int enable, uint32_t timeout_ms);
+
 /* When the tensors above the DMA threshold take the DMA engines: always
  * (when_behind = 0, the default), or only while there is compute to hide them
  * behind (when_behind = 1): the compute stream has not yet reached one of the

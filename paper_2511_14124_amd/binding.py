@@ -127,6 +127,7 @@ def load_library(path: str = LIB_PATH):
         "tc_set_dma_threshold": (i32, [vp, u64]),
         "tc_set_merge_bytes": (i32, [vp, u64]),
         "tc_set_dma_policy": (i32, [vp, i32]),
+        "tc_set_gpu_dependencies": (i32, [vp, i32, u32]),
         "tc_tune_mover": (i32, [vp, C.POINTER(u32)]),
         "tc_set_io_threads": (i32, [vp, u32, u32]),
         "tc_add_stripe": (i32, [vp, i32]),
@@ -429,6 +430,9 @@ class TensorCache:
 
     def set_merge_bytes(self, nbytes: int):
         self._check(lib().tc_set_merge_bytes(self._h, int(nbytes)))
+
+    def set_gpu_dependencies(self, enable: bool, timeout_ms: int = 0):
+        self._check(lib().tc_set_gpu_dependencies(self._h, int(bool(enable)), int(timeout_ms)))
 
     def set_dma_policy(self, when_behind: bool):
         self._check(lib().tc_set_dma_policy(self._h, int(bool(when_behind))))

@@ -82,6 +82,7 @@ struct PUnit {              // one exchange unit being prepared
     int64_t cpu_in = -1;    // flat index of the host buffer the incoming tensor comes from
     bool out_staging = false, in_staging = false;
     uint32_t out_tensor = 0;
+    uint32_t sig = 0;       // signal the call that prepared it queued on its compute stream (0: none)
     uint64_t st_id = 0;     // its block of the staging ring (0: none)
     JobSet read_job;        // file read that fills in_src (in_staging)
 };
@@ -197,6 +198,21 @@ struct tc_ctx {
     std::vector<uint8_t> gpu_pending, cpu_pending;  // buffer is touched by a deferred unit
     hipStream_t last_compute = nullptr;
     uint64_t last_k_op = 0;             // newest operation issued on the migration stream
+    // Dependencies resolved on the GPU (tc_set_gpu_dependencies): a hook call that prepares units queues a
+    // one-lane kernel on its compute stream that raises the word `progress` to the call's number; the launch
+    // that carries the units is queued at once and its workgroups wait for that number themselves.  Every
+    // launch raises the word `done` to its own number when its last workgroup leaves, and a module that
+    // needs what a launch brings is preceded on its stream by a one-lane kernel that waits for that number.
+    // No event crosses between the two hardware queues (a wait across queues takes about 17 us here).
+    bool gpu_deps = false;
+    uint64_t spin_ticks = 500000000ull; // bound of every such wait, in ticks of the 100 MHz clock (5 s)
+    uint32_t *fault = nullptr;          // pinned: a waiter that gave up writes here
+    uint32_t sig_seq = 0;               // signals queued so far
+    bool sig_sent = false;              // this hook call has queued its signal
+    hipStream_t sig_stream = nullptr;   // the compute stream the signals were queued on
+    uint32_t launch_seq = 0;            // launches that raise `done`
+    uint32_t op_lseq[OP_RING]{};        // per copy operation: its launch number (0: not such a launch)
+    uint32_t waited_lseq = 0;           // the newest launch number waited_stream has been made to wait for
     // per compute stream: the newest operation of each copy stream it has been made to wait for
     // (a stream is in order, so an older operation of the same copy stream needs no wait of its own)
     hipStream_t waited_stream = nullptr;

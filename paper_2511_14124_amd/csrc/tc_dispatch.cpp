@@ -48,7 +48,8 @@ static int dep(tc_ctx *c, int S, uint64_t id)
 
 // start an operation on stream S: the first one of a hook call on that stream
 // makes the stream wait for the work already queued on the compute stream
-static int begin_op(tc_ctx *c, int S, hipStream_t compute, uint64_t *id)
+// (wait_compute false: the operation waits for the modules it depends on by itself)
+static int begin_op(tc_ctx *c, int S, hipStream_t compute, uint64_t *id, bool wait_compute = true)
 {
     const uint64_t n = c->op_id + 1;
     if (n > OP_RING) {
@@ -56,8 +57,9 @@ static int begin_op(tc_ctx *c, int S, hipStream_t compute, uint64_t *id)
         int rc = wait_op(c, n - OP_RING);              // the event about to be reused
         if (rc != TC_OK) return rc;
     }
+    c->op_lseq[n % OP_RING] = 0;
     if (c->streams[S] == compute) c->stream_waited[S] = true;    // one queue, in order: nothing to wait for
-    if (!c->stream_waited[S]) {
+    if (wait_compute && !c->stream_waited[S]) {
         if (!c->compute_recorded) {
             HIP_TRY(c, hipEventRecord(c->ev_compute, compute));
             c->compute_recorded = true;
@@ -257,8 +259,31 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         args.xcc = c->mover_xcc;
         args.n_xcd = c->mover_xcds;
         uint64_t id, bytes = 0;
-        int rc = begin_op(c, S_K, compute, &id);
+        // Dependencies resolved on the GPU: the launch is not made to wait for the compute stream; its
+        // workgroups wait for the newest of the signals the calls that prepared its units have queued
+        // there.  (Not with the modules on the migration stream itself, which is in order anyway, nor
+        // for a unit without a signal or with one queued on another stream than this call's.)
+        bool gate = c->gpu_deps && compute != c->streams[S_K] && c->sig_stream == compute;
+        uint32_t need_sig = 0;
+        for (size_t k = at; k < end && gate; ++k) {
+            const PUnit &p = units[(size_t)(-1 - kunits[k].second)];
+            if (p.sig == 0 || (int32_t)(c->sig_seq - p.sig) < 0) gate = false;
+            else if (need_sig == 0 || (int32_t)(p.sig - need_sig) > 0) need_sig = p.sig;
+        }
+        int rc = begin_op(c, S_K, compute, &id, !gate);
         if (rc != TC_OK) return rc;
+        if (c->gpu_deps) {
+            args.fault = c->fault;
+            args.gave_up = c->tickets + 35;
+            args.spin_ticks = c->spin_ticks;
+            args.done = c->tickets + 33;
+            args.exited = c->tickets + 34;
+            args.done_seq = ++c->launch_seq;
+            if (gate) {
+                args.progress = c->tickets + 32;
+                args.need_seq = need_sig;
+            }
+        }
         for (size_t k = at; k < end; ++k) {
             TcUnit u = kunits[k].first;
             u.chunk0 = args.n_chunks;
@@ -277,6 +302,7 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         HIP_TRY(c, tc_launch_mover(args, c->mover_wgs, c->streams[S_K], &c->k_launches));
         if ((rc = timed_end(c, S_K, t0, bytes)) != TC_OK) return rc;
         if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
+        if (c->gpu_deps) c->op_lseq[id % OP_RING] = args.done_seq;
         c->last_k_op = id;
         c->stats.mover_launches++;
         c->stats.mover_units += args.n_units;
@@ -508,6 +534,24 @@ static int dispatch_host_tier(tc_ctx *c, const TcOpRec &r, uint32_t t, uint32_t 
     }
 }
 
+// the signal of this hook call on its compute stream: queued when the call prepares its first unit,
+// behind the modules queued so far
+static int call_signal(tc_ctx *c, hipStream_t compute, uint32_t *sig)
+{
+    *sig = 0;
+    if (!c->gpu_deps || compute == c->streams[S_K]) return TC_OK;
+    if (!c->sig_sent) {
+        uint32_t n = c->sig_seq + 1;
+        if (n == 0) n = 1;                              // 0 means "none"
+        HIP_TRY(c, tc_launch_signal(c->tickets + 32, n, compute));
+        c->sig_seq = n;
+        c->sig_stream = compute;
+        c->sig_sent = true;
+    }
+    *sig = c->sig_seq;
+    return TC_OK;
+}
+
 int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step, int phase,
                     hipStream_t compute)
 {
@@ -522,6 +566,7 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
     bool have_out = false;
     uint8_t *reserved_in = nullptr; // bounce space kept for the partner of a write-back
     c->compute_recorded = false;
+    c->sig_sent = false;
     for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
     for (uint32_t i = 0; i < o->n_ops; ++i) {
         const TcOpRec &r = ops[i];
@@ -642,6 +687,10 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
             if (p.cpu_in >= 0) c->cpu_pending[(size_t)p.cpu_in] = 1;
             c->deferred_bytes += n * ((p.u.out_src ? 1 : 0) + 1);
             if (p.out_staging) c->wb_pending[p.out_tensor] = 1;
+            {
+                int rc = call_signal(c, compute, &p.sig);
+                if (rc != TC_OK) return rc;
+            }
             units.push_back(p);
             have_out = false;
             break;
@@ -663,6 +712,10 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
             if (p.cpu_out >= 0) c->cpu_pending[(size_t)p.cpu_out] = 1;
             c->deferred_bytes += n;
             if (p.out_staging) c->wb_pending[p.out_tensor] = 1;
+            {
+                int rc = call_signal(c, compute, &p.sig);
+                if (rc != TC_OK) return rc;
+            }
             units.push_back(p);
             have_out = false;
             break;

@@ -133,6 +133,18 @@ struct TcMoverArgs {
     uint32_t slot;                              // 0 or 1: set by the launcher, alternates between launches
     uint32_t xcc;                               // the XCD whose workgroups do the work
     uint32_t n_xcd;                             // XCDs the dispatcher deals workgroups to (grid = workgroups x n_xcd)
+    // Dependencies resolved on the GPU (all nullptr / 0: none).  gate: the launch may be queued before the
+    // modules it has to wait for have run; its working workgroups wait until the word at `progress` has
+    // reached need_seq (tc_signal_kernel, queued on the compute stream behind those modules, raises it).
+    // done: every workgroup counts itself out in `exited`; the last one raises the word at `done` to done_seq
+    // (tc_wait_kernel, queued on the compute stream in front of a module, waits for that).  Both waits
+    // are bounded: after spin_ticks of the 100 MHz wall clock a waiter gives up, raises *fault and the
+    // launch moves nothing (the host reports it; the data is then not to be trusted).
+    const uint32_t *progress;
+    uint32_t *done, *exited, *fault;            // fault: pinned host word the host reads
+    uint32_t *gave_up;                          // device word: set with *fault, makes every later waiter give up at once
+    uint32_t need_seq, done_seq;
+    uint64_t spin_ticks;
 };
 
 struct TcStampArgs {
@@ -154,6 +166,11 @@ hipError_t tc_mover_topology(uint32_t *xcc, uint32_t *n_xcd);
 hipError_t tc_launch_zero_tickets(uint32_t *tickets, hipStream_t s);   // both counters to zero, by a kernel
 // launches: how many launches have used a.tickets so far (all on one stream, in order); counted up here
 hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, uint64_t *launches);
+// raises the word at `word` to seq (never lowers it), one lane, on stream s
+hipError_t tc_launch_signal(uint32_t *word, uint32_t seq, hipStream_t s);
+// waits on stream s until the word at `word` has reached seq, at most spin_ticks of the 100 MHz clock (then *fault = 2)
+hipError_t tc_launch_wait(const uint32_t *word, uint32_t seq, uint64_t spin_ticks, uint32_t *fault, uint32_t *gave_up,
+                          hipStream_t s);
 hipError_t tc_launch_stamp(const TcStampArgs &a, hipStream_t s);
 hipError_t tc_launch_fill(void *dst, uint64_t bytes, uint32_t tensor, uint32_t seed, hipStream_t s);
 uint64_t tc_pack_tile_count(uint64_t total);

@@ -523,14 +523,72 @@ __device__ __forceinline__ void st16(uint8_t *p, uint4 v)
     __builtin_nontemporal_store(mover_v4{v.x, v.y, v.z, v.w}, (mover_v4 *)p);
 }
 
+// has the word reached seq?  (sequence numbers wrap: compare the difference)
+__device__ __forceinline__ bool seq_reached(const uint32_t *word, uint32_t seq)
+{
+    const uint32_t v = __hip_atomic_load(word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    return (int32_t)(v - seq) >= 0;
+}
+
+// bounded wait for a sequence word, by one lane; false: gave up, after `ticks` of the 100 MHz clock
+// or because a waiter before it did (so that a context whose streams cannot make progress against
+// each other drains in one timeout, not one per launch)
+__device__ bool seq_wait(const uint32_t *word, uint32_t seq, uint64_t ticks, uint32_t *fault, uint32_t *gave_up, uint32_t code)
+{
+    if (seq_reached(word, seq)) return true;
+    const uint64_t t0 = wall_clock64();
+    for (uint32_t n = 0;; ++n) {
+        if ((n & 255u) == 0 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+        __builtin_amdgcn_s_sleep(4);
+        if (seq_reached(word, seq)) return true;
+        if (wall_clock64() - t0 > ticks) break;
+    }
+    __hip_atomic_store(gave_up, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(fault, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return false;
+}
+
+// a workgroup leaves the launch: the last of the whole grid to do so raises the launch's done word.
+// Its own stores (and, through the counter, everyone's before it) are released first.
+__device__ __forceinline__ void mover_count_out(const TcMoverArgs &a, uint32_t tid)
+{
+    if (!a.done) return;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(a.exited, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (before + 1 == gridDim.x) {
+            __hip_atomic_store(a.exited, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the launch behind this one
+            // (launches of one stream end in order, so the word only grows)
+            __hip_atomic_store(a.done, a.done_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
 {
     uint32_t xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    if ((xcc & 15u) != a.xcc && blockIdx.x != 0) return;
-    __shared__ uint32_t ticket;
     const uint32_t tid = threadIdx.x;
+    if ((xcc & 15u) != a.xcc && blockIdx.x != 0) {
+        mover_count_out(a, tid);
+        return;
+    }
+    __shared__ uint32_t ticket;
+    __shared__ uint32_t go;
     if (blockIdx.x == 0 && tid == 0) a.tickets[a.slot ^ 1u] = 0;
+    if (a.progress) {
+        // the modules this launch has to wait for may still be running: wait for their signal
+        if (tid == 0) {
+            go = seq_wait(a.progress, a.need_seq, a.spin_ticks, a.fault, a.gave_up, 1u) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!go) {                                         // gave up: move nothing, leave in order
+            mover_count_out(a, tid);
+            return;
+        }
+        __threadfence();                                   // what those modules wrote is read from here on
+    }
     uint32_t ui = 0;                                       // tickets only grow: the unit search resumes where it stopped
     for (;;) {
         __syncthreads();                                   // everyone has read the ticket before
@@ -590,6 +648,44 @@ __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
             if (tid < tail) d[(uint64_t)n16 * 16 + tid] = s[(uint64_t)n16 * 16 + tid];
         }
     }
+    mover_count_out(a, tid);
+}
+
+// The compute stream's side of the dependencies resolved on the GPU: one lane raises a sequence word
+// behind the modules queued so far, one lane waits for a word in front of a module (bounded).
+__global__ void tc_signal_kernel(uint32_t *word, uint32_t seq)
+{
+    if (threadIdx.x == 0) {
+        __threadfence();
+        uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // never lower it: signals of two compute streams may arrive out of order
+        while ((int32_t)(seq - v) > 0 &&
+               !__hip_atomic_compare_exchange_strong(word, &v, seq, __ATOMIC_RELEASE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+        }
+    }
+}
+
+__global__ void tc_wait_kernel(const uint32_t *word, uint32_t seq, uint64_t ticks, uint32_t *fault, uint32_t *gave_up)
+{
+    if (threadIdx.x == 0) {
+        (void)seq_wait(word, seq, ticks, fault, gave_up, 2u);
+        __threadfence();
+    }
+}
+
+hipError_t tc_launch_signal(uint32_t *word, uint32_t seq, hipStream_t s)
+{
+    if (!word) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tc_signal_kernel, dim3(1), dim3(64), 0, s, word, seq);
+    return hipGetLastError();
+}
+
+hipError_t tc_launch_wait(const uint32_t *word, uint32_t seq, uint64_t spin_ticks, uint32_t *fault, uint32_t *gave_up,
+                          hipStream_t s)
+{
+    if (!word || !fault || !gave_up || !spin_ticks) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tc_wait_kernel, dim3(1), dim3(64), 0, s, word, seq, spin_ticks, fault, gave_up);
+    return hipGetLastError();
 }
 
 // clears the two ticket counters of a stand-alone launch (a kernel, not a memset node: a caller
@@ -654,6 +750,8 @@ hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, u
     if (a.n_units > TC_MOVER_MAX_UNITS || a.chunk_bytes == 0 || (a.chunk_bytes & 15)) return hipErrorInvalidValue;
     if (!a.tickets || !launches || workgroups == 0 || workgroups > 8192 || a.n_xcd == 0 || a.n_xcd > 16)
         return hipErrorInvalidValue;
+    if ((a.progress || a.done) && (!a.fault || !a.gave_up || !a.spin_ticks)) return hipErrorInvalidValue;
+    if (a.done && !a.exited) return hipErrorInvalidValue;
     uint64_t chunks = 0;
     for (uint32_t i = 0; i < a.n_units; ++i) {
         const TcUnit &u = a.u[i];

@@ -58,6 +58,7 @@ static void release_device(tc_ctx *c)
     if (c->d_rw) { (void)hipFree(c->d_rw); c->d_rw = nullptr; }
     if (c->bounce) { (void)hipFree(c->bounce); c->bounce = nullptr; }
     if (c->tickets) { (void)hipFree(c->tickets); c->tickets = nullptr; }
+    if (c->fault) { (void)hipHostFree(c->fault); c->fault = nullptr; }
     for (int b = 0; b < 2; ++b) {
         if (c->snap[b]) { (void)hipFree(c->snap[b]); c->snap[b] = nullptr; }
         if (c->win_ev[b]) { (void)hipEventDestroy(c->win_ev[b]); c->win_ev[b] = nullptr; }
@@ -266,6 +267,10 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (e == hipSuccess) e = hipMemset(c->tickets, 0, 256);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     c->k_launches = 0;
+    e = hipHostMalloc((void **)&c->fault, 64, hipHostMallocDefault);
+    if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
+    *c->fault = 0;
+    c->sig_seq = c->launch_seq = c->waited_lseq = 0;
     e = tc_mover_topology(&c->mover_xcc, &c->mover_xcds);
     if (e != hipSuccess) { release_device(c); return fail(c, TC_E_HIP, hipGetErrorString(e)); }
     for (uint32_t i = 0; i < OP_RING; ++i) {
@@ -514,12 +519,23 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
                     const uint32_t st = c->op_stream[ticket % OP_RING];
                     if (c->waited_stream != compute) {
                         c->waited_stream = compute;
+                        c->waited_lseq = 0;
                         for (int k = 0; k < N_STREAMS; ++k) c->waited_op[k] = 0;
                     }
                     if (ticket > c->waited_op[st]) {
                         // (a module queued on the very stream the copy runs on is behind it anyway)
-                        if (c->streams[st] != compute)
+                        const uint32_t lseq = c->op_lseq[ticket % OP_RING];
+                        if (c->streams[st] == compute) {
+                        } else if (c->gpu_deps && lseq) {
+                            // a launch that says on the GPU when it is done: a one-lane kernel in front of
+                            // the module waits for its number (launches of the stream end in order)
+                            if ((int32_t)(lseq - c->waited_lseq) > 0 || c->waited_lseq == 0) {
+                                HIP_TRY(c, tc_launch_wait(c->tickets + 33, lseq, c->spin_ticks, c->fault, c->tickets + 35, compute));
+                                c->waited_lseq = lseq;
+                            }
+                        } else {
                             HIP_TRY(c, hipStreamWaitEvent(compute, c->op_ev[ticket % OP_RING], 0));
+                        }
                         c->waited_op[st] = ticket;
                     }
                 }
@@ -539,12 +555,23 @@ static int finish_pre(tc_ctx *c, const TcDecideOut *o, uint32_t step, const uint
     return TC_OK;
 }
 
+// a bounded wait on the GPU ran out (tc_set_gpu_dependencies): a launch moved nothing or a module ran
+// without its tensors; the bytes are not to be trusted from here on
+static int gpu_wait_gave_up(tc_ctx *c)
+{
+    return fail(c, TC_E_HIP, *(volatile uint32_t *)c->fault == 1
+                                 ? "a migration launch gave up waiting for the modules before it (do the compute stream "
+                                   "and the migration stream share a hardware queue, or does a module run longer than the timeout?)"
+                                 : "a module's wait for its migration launch ran out");
+}
+
 extern "C" int tc_migrate_step(tc_ctx *c, uint32_t step, int phase, const uint32_t *ids, const uint8_t *rw,
                                uint32_t n, void *compute_stream, void **dev_ptrs_out)
 {
     if (!c) return TC_E_ARG;
     if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
     if (phase != TC_PRE && phase != TC_POST) return fail(c, TC_E_ARG, "phase must be TC_PRE or TC_POST");
+    if (c->fault && *(volatile uint32_t *)c->fault) return gpu_wait_gave_up(c);
     if (n > TC_MAX_STEP_TENSORS || (n && !ids)) return fail(c, TC_E_ARG, "too many tensors or null ids");
     // the profile ends with its last step that used a tensor: a module without tensors may follow
     if (step >= c->prof.n_steps && n) return fail(c, TC_E_ARG, "step outside the profiled iteration");
@@ -754,6 +781,7 @@ extern "C" int tc_synchronize(tc_ctx *c)
         rc = io_wait_all(c);                           // queued file I/O
         if (rc != TC_OK) return rc;
         c->st_q.clear();
+        if (c->fault && *(volatile uint32_t *)c->fault) return gpu_wait_gave_up(c);
     }
     return TC_OK;
 }
@@ -1000,6 +1028,21 @@ extern "C" int tc_set_merge_bytes(tc_ctx *c, uint64_t bytes)
 {
     if (!c) return TC_E_ARG;
     c->merge_bytes = bytes;
+    return TC_OK;
+}
+
+extern "C" int tc_set_gpu_dependencies(tc_ctx *c, int enable, uint32_t timeout_ms)
+{
+    if (!c) return TC_E_ARG;
+    if (c->stage != 4) return fail(c, TC_E_STATE, "tc_bind_memory must come first");
+    if (enable && timeout_ms == 0) timeout_ms = 5000;
+    if (timeout_ms > 600000) return fail(c, TC_E_ARG, "timeout above ten minutes");
+    if (c->null_mover || c->host_tier) return TC_OK;        // no copy kernel runs
+    // everything queued under the old setting finishes first: the two kinds of waiting do not mix
+    int rc = tc_synchronize(c);
+    if (rc != TC_OK) return rc;
+    c->gpu_deps = enable != 0;
+    if (enable) c->spin_ticks = (uint64_t)timeout_ms * 100000ull;      // the clock runs at 100 MHz
     return TC_OK;
 }
 

@@ -28,7 +28,7 @@ def compare_logs(got, want):
 def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_bytes=0, mover=None,
                 busy=False, window=None, merge_bytes=None, dma_threshold=None, fill=False, direct=False,
                 io_writers=None, stripes=1, io_chunk=None, ahead=None, tune=False, host_tier=False, dma_when_behind=False,
-                stripe_paths=None, one_stream=False):
+                stripe_paths=None, one_stream=False, gpu_deps=False):
     """Replays every iteration of wl through the library; returns the context.
 
     window None: one tc_migrate_step call per hook (the hook-driven interface);
@@ -51,6 +51,8 @@ def run_library(wl, *, payload=True, null_mover=False, file_path=None, staging_b
         tc.set_io_threads(*io_writers)
     if mover:
         tc.set_mover(*mover)
+    if gpu_deps and not null_mover:            # True, or the bound of the waits in ms
+        tc.set_gpu_dependencies(True, 0 if gpu_deps is True else int(gpu_deps))
     if merge_bytes is not None:
         tc.set_merge_bytes(merge_bytes)
     if dma_threshold is not None:
