@@ -260,9 +260,10 @@ def phase_split(wl, per_step_ns):
 
 
 def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, tier_dirs=None, direct=False,
-               alloc_write_only=False, one_stream=None):
+               alloc_write_only=False, one_stream=None, gpu_deps=None):
     """Replays one configuration and returns its figures.  steps / warmup count iterations."""
     one_stream = args.one_stream if one_stream is None else one_stream
+    gpu_deps = args.gpu_deps if gpu_deps is None else gpu_deps
     from paper_2511_14124_amd.box import FULL_LAYERS, is_tmpfs
     wl = W.config(index, layers=layers)
     wl.no_prefetch = args.no_prefetch
@@ -307,7 +308,7 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
         tuned_wgs = tc.tune_mover()        # the regions hold nothing yet: measure the workgroup count
     if args.merge_mib is not None:
         tc.set_merge_bytes(args.merge_mib << 20)
-    if args.gpu_deps:
+    if gpu_deps:
         tc.set_gpu_dependencies(True)
     if args.dma_mib:
         tc.set_dma_threshold(int(args.dma_mib * (1 << 20)))
@@ -350,6 +351,8 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
         "ms_per_iteration": dt / steps * 1e3, "migration_launches_per_iteration": d["mover_launches"] / steps,
         "working_workgroups": tuned_wgs or args.workgroups or 12,
         "streams": "one: modules and copies in one queue" if one_stream else "two: modules on a stream of their own",
+        "dependencies": "resolved on the GPU (tc_set_gpu_dependencies)" if gpu_deps and not one_stream else
+                        "stream order" if one_stream else "events between the streams",
     }
     if args.dma_mib:
         res["dma_path"] = {"from_MiB": args.dma_mib, "copies": tm["h2d_copies"] + tm["d2h_copies"],
@@ -650,6 +653,11 @@ def main():
                 res, _ = run_config(torch, T, W, link, index, None, args, steps=10, warmup=1, stall=False,
                                     one_stream=True)
                 per_config.append(res)
+                if not args.gpu_deps:
+                    # ... and with two queues but no event between them: the waits resolved on the GPU
+                    res, _ = run_config(torch, T, W, link, index, None, args, steps=10, warmup=1, stall=False,
+                                        gpu_deps=True)
+                    per_config.append(res)
 
     awf = None
     if args.per_config == "all" and not args.alloc_write_only:

@@ -471,9 +471,12 @@ int tc_set_dma_threshold(tc_ctx *ctx, uint64_t bytes);
  * it where every module's kernels finish well within the timeout and the
  * compute stream and the migration stream run on different hardware queues
  * (two streams of one process normally do).  With the modules on the migration
- * stream itself nothing changes (that stream is in order).  Decisions and
- * bytes never depend on the setting.  The call waits for the copies in flight.
- * Default: off. */
+ * stream itself nothing changes (that stream is in order).  A launch that
+ * waits on the GPU has at most 32 working workgroups whatever tc_set_mover
+ * says: workgroups that wait hold their places on the XCD they run on, and
+ * must leave room there for the one-workgroup kernel that ends their wait.
+ * Decisions and bytes never depend on the setting.  The call waits for the
+ * copies in flight.  Default: off. */
 int tc_set_gpu_dependencies(tc_ctx *ctx, int enable, uint32_t timeout_ms);
 
 /* When the tensors above the DMA threshold take the DMA engines: always

@@ -299,7 +299,13 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         }
         hipEvent_t t0;
         if ((rc = timed_begin(c, S_K, &t0)) != TC_OK) return rc;
-        HIP_TRY(c, tc_launch_mover(args, c->mover_wgs, c->streams[S_K], &c->k_launches));
+        // Workgroups that wait on the GPU hold their places on the XCD they run on while they wait.  If
+        // they took all of them, a one-workgroup kernel of the compute stream that the dispatcher deals
+        // to that XCD (the signal they wait for among them) would find no place: the wait would end only
+        // by its bound.  A gated launch therefore has at most one working workgroup per compute unit of
+        // an XCD (the measured optimum is a dozen).
+        const uint32_t wgs = gate ? std::min<uint32_t>(c->mover_wgs, 32) : c->mover_wgs;
+        HIP_TRY(c, tc_launch_mover(args, wgs, c->streams[S_K], &c->k_launches));
         if ((rc = timed_end(c, S_K, t0, bytes)) != TC_OK) return rc;
         if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
         if (c->gpu_deps) c->op_lseq[id % OP_RING] = args.done_seq;

@@ -739,6 +739,7 @@ static int replay_windows(tc_ctx *c, const uint32_t *step_ptr, const uint32_t *i
     for (uint32_t k0 = 0; k0 < n_steps; k0 += c->replay_window, blk ^= 1) {
         const uint32_t count = std::min(c->replay_window, n_steps - k0);
         HIP_TRY(c, hipStreamSynchronize(c->dstream));
+        if (c->fault && *(volatile uint32_t *)c->fault) return gpu_wait_gave_up(c);
         if (k0 + count < n_steps) {
             int rc = launch(k0 + count, blk ^ 1);
             if (rc != TC_OK) return rc;

@@ -192,6 +192,49 @@ def test_modules_on_the_migration_stream_itself_keep_every_byte(window, tmp_path
     tc.close()
 
 
+@pytest.mark.parametrize("window", [None, 16])
+def test_dependencies_resolved_on_the_gpu_keep_every_byte(window, tmp_path):
+    # tc_set_gpu_dependencies: launches wait for their modules' signal themselves and modules wait for a launch's
+    # done word through a small kernel, no event between the streams; schedule and bytes are the oracle's, with
+    # modelled compute running beside the copies, with the file tier and misses, hook by hook and in windows
+    wl = W.random_workload(29, n_tensors=120, n_steps=90, max_per_step=3, sizes=(70001, 262144 + 48, 1 << 20, 17, 4096),
+                           hbm_frac=0.1, host_frac=0.5, perturb_one_in=9, n_iterations=3)
+    tc = run_library(wl, file_path=_tmpfile(tmp_path), staging_bytes=4 << 20, window=window, gpu_deps=True, busy=True)
+    check_against_oracle(wl, tc)
+    tc.close()
+    wl = W.config(0, layers=8)
+    for merge in (0, 1 << 30):
+        tc = run_library(wl, window=window, gpu_deps=True, merge_bytes=merge)
+        check_against_oracle(wl, tc)
+        tc.close()
+    # with allocate-without-fetch (units that only take a tensor out of a buffer the module then fills)
+    wl = W.config(0, layers=6)
+    wl.alloc_write_only = True
+    tc = run_library(wl, window=window, gpu_deps=True, busy=True)
+    check_against_oracle(wl, tc)
+    tc.close()
+
+
+def test_a_wait_on_the_gpu_that_runs_out_is_reported_and_every_kernel_still_ends():
+    # the waits on the GPU are bounded: with a bound of 1 ms and modules that run for 20 ms a launch gives up
+    # waiting for the modules before it; it moves nothing, every later waiter gives up at once, every kernel
+    # ends, and the library reports it at the next call (the bytes are then not to be trusted)
+    wl = W.config(0, layers=6)
+    tc = T.TensorCache.from_workload(wl)
+    tc.bind_torch()
+    tc.set_gpu_dependencies(True, 1)
+    tc.fill_payload(W.PAYLOAD_SEED)
+    cs = torch.cuda.Stream()
+    busy = np.full(wl.n_steps, 20_000_000, dtype=np.uint64)
+    with pytest.raises(T.TcError) as e:
+        for _ in range(3):
+            tc.replay_iteration(wl.iterations[0], cs.cuda_stream, busy_ns=busy)
+        tc.synchronize()
+    assert e.value.code == -5 and "gave up" in str(e.value)            # TC_E_HIP
+    torch.cuda.synchronize()                                          # everything queued has ended
+    tc.close()
+
+
 @pytest.mark.parametrize("busy", [False, True], ids=["idle_compute", "busy_compute"])
 def test_dma_copies_only_behind_a_compute_backlog_keep_every_byte(busy, tmp_path):
     # with the policy "when behind" the path a large tensor takes (DMA engines or the kernel)

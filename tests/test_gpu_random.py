@@ -43,7 +43,8 @@ def test_random_workloads_under_random_settings(block, tmp_path):
                         busy=bool(rng.integers(0, 2)), io_writers=(int(rng.integers(0, 5)), int(rng.integers(0, 5))),
                         stripes=int(rng.choice([1, 1, 2, 4])), io_chunk=int(rng.choice([1 << 16, 1 << 17, 8 << 20])),
                         ahead=[None, 0, 1, 3, 16, 256][int(rng.integers(0, 6))], host_tier=host_tier,
-                        dma_when_behind=bool(seed % 2), one_stream=bool(seed % 5 == 0))
+                        dma_when_behind=bool(seed % 2), one_stream=bool(seed % 5 == 0),
+                        gpu_deps=bool(seed % 3 == 0) and not host_tier)
         wl.alloc_write_only = bool(seed % 7 == 0)
         try:
             o.replay_workload(wl)
