@@ -31,6 +31,11 @@ step for a parameter names the gradient (read) and the parameter (read and
 written).  Outside those steps a gradient lives wherever the scheduler put it,
 and `p.grad` is None.
 
+A parameter shared by two modules (tied weights) and a module that runs twice in
+a pass are handled in the parameters-only mode: such a use's backward step is
+closed when the gradients of its own inputs arrive, not when its parameters'
+gradients do (those are complete only after the last use).
+
 Between its pre-hook and its post-hook a module's parameters are views into
 the HBM cache buffers the library returned; outside that window they point
 nowhere useful and must not be touched.  A parameter may come back for the
@@ -128,6 +133,28 @@ class ParamCache:
         self._saved_ctx: Dict[int, object] = {}           # module -> its saved-tensor hooks, while its forward runs
         if any(not p.requires_grad for p in self.params):
             raise ValueError("every managed parameter must require a gradient (its post-hook waits for it)")
+        # A module's backward step is normally closed when the gradients of its parameters have arrived.
+        # That does not work where a parameter is shared by two modules (tied weights) or a module runs
+        # twice in a pass: the gradient arrives only after the last of the uses, and the steps of the
+        # earlier ones would stay open across other modules' steps.  Such a use is closed instead when
+        # the gradients of its own inputs arrive (the kernels that read its parameters are queued by
+        # then); a use without an input that needs a gradient (an embedding) falls back to the rule above.
+        owners: Dict[int, list] = {}
+        for m in self.mods:
+            for p in m.parameters(recurse=False):
+                owners.setdefault(id(p), []).append(m)
+        self._by_input = {id(m) for ms in owners.values() if len(ms) > 1 for m in ms}
+        self._uses: Dict[int, int] = {}                   # module -> forward calls in the running iteration
+        self._next_use = 0
+        self._open_use: Dict[int, int] = {}               # module -> the use whose forward is running
+        self._use_inputs: Dict[int, int] = {}             # use -> input gradients still due
+        self._use_step: Dict[int, int] = {}               # use -> step index of its running backward
+        self._check_by_input()
+
+    def _check_by_input(self):
+        if self._by_input and (self.fused_sgd_lr is not None or self.manage_grads):
+            raise ValueError("shared parameters and modules used twice in a pass are supported for parameters with a "
+                             "separate update sweep only (their gradients are complete only after the last use)")
 
     # ------------------------------------------------------------------ hooks
     def _register(self):
@@ -202,12 +229,35 @@ class ParamCache:
         return r
 
     def _fwd_pre(self, m, args):
+        self._uses[id(m)] = self._uses.get(id(m), 0) + 1
+        if self._uses[id(m)] > 1 and id(m) not in self._by_input:
+            if not self._recording:
+                raise RuntimeError("a module ran twice in a pass but only once in the profiled iteration")
+            self._by_input.add(id(m))                     # (its first use's backward comes later: it will see this)
+            self._check_by_input()
         self._fwd_step[id(m)] = self._begin(m, "fwd")
+        new_args = None
+        if id(m) in self._by_input and self.torch.is_grad_enabled():
+            # this use's own view of every input that needs a gradient: the gradient of the view is this
+            # module's contribution alone, and its arrival closes the use's backward step
+            u = self._next_use
+            self._next_use += 1
+            self._open_use[id(m)] = u
+            views = []
+            for a in args:
+                if self.torch.is_tensor(a) and a.requires_grad:
+                    a = a.view_as(a)
+                    a.register_hook(self._make_input_grad(m, u))
+                    self._use_inputs[u] = self._use_inputs.get(u, 0) + 1
+                views.append(a)
+            self._use_inputs.setdefault(u, 0)
+            new_args = tuple(views)
         if not self._recording and self.torch.is_grad_enabled():
             ctx = self.torch.autograd.graph.saved_tensors_hooks(self._pack_saved, self._unpack_saved)
             ctx.__enter__()
             self._saved_ctx[id(m)] = ctx
             self._saving_for = tuple(self.mod_ids[id(m)])
+        return new_args
 
     def _fwd_post(self, m, args, out):
         ctx = self._saved_ctx.pop(id(m), None)
@@ -217,10 +267,35 @@ class ParamCache:
         self._end(m, self._fwd_step.pop(id(m)), "fwd")
         # the module's backward starts when the gradient of its output arrives
         outs = out if isinstance(out, (tuple, list)) else (out,)
+        u = self._open_use.pop(id(m), None)
         for o in outs:
             if self.torch.is_tensor(o) and o.requires_grad:
-                o.register_hook(self._make_bwd_start(m))
+                o.register_hook(self._make_bwd_start(m) if u is None else self._make_use_bwd_start(m, u))
                 break
+
+    def _make_use_bwd_start(self, m, u):
+        def hook(grad):
+            if u in self._use_step or u not in self._use_inputs:
+                return grad
+            if self._use_inputs[u] == 0:                  # no input to wait for: the parameters' gradients close it
+                del self._use_inputs[u]
+                if id(m) not in self._bwd_step:
+                    self._bwd_step[id(m)] = self._begin(m, "bwd")
+                    self._pending_bwd[id(m)] = len(self.mod_ids[id(m)])
+                return grad
+            self._use_step[u] = self._begin(m, "bwd")
+            return grad
+        return hook
+
+    def _make_input_grad(self, m, u):
+        def hook(grad):
+            if u in self._use_step:
+                self._use_inputs[u] -= 1
+                if self._use_inputs[u] == 0:
+                    del self._use_inputs[u]
+                    self._end(m, self._use_step.pop(u), "bwd")
+            return grad
+        return hook
 
     def _make_bwd_start(self, m):
         def hook(grad):
@@ -252,6 +327,7 @@ class ParamCache:
         """Dry run (Sec. 3.2.1): one forward + backward under recording hooks."""
         self.steps = []
         self._k = 0
+        self._uses, self._next_use, self._open_use, self._use_inputs, self._use_step = {}, 0, {}, {}, {}
         self._recording = True
         self._register()
         try:
@@ -259,8 +335,9 @@ class ParamCache:
         finally:
             self._remove()
             self._recording = False
-        if self._bwd_step:
+        if self._bwd_step or self._use_step:
             raise RuntimeError("a module's backward did not finish during the dry run")
+        self._uses, self._next_use, self._use_inputs = {}, 0, {}
         self._n_model_steps = len(self.steps)
         # the optimizer sweep: every parameter once, read and written
         if self.fused_sgd_lr is None:
@@ -368,6 +445,7 @@ class ParamCache:
     def end_iteration(self):
         self.tc.end_iteration(self.torch.cuda.current_stream().cuda_stream)
         self._k = 0
+        self._uses, self._next_use, self._open_use, self._use_inputs, self._use_step = {}, 0, {}, {}, {}
         for p in self.params:
             p.grad = None
 

@@ -104,6 +104,95 @@ def test_training_through_the_cache_equals_resident_training(mode):
     assert (st["hits"], st["misses"]) == (r.hits, r.misses)
 
 
+class _Tied(torch.nn.Module):
+    """Token embedding tied to the output projection (one parameter, two modules), and one block
+    that runs twice in a pass."""
+
+    def __init__(self, vocab=96, d=64):
+        super().__init__()
+        self.emb = torch.nn.Embedding(vocab, d)
+        self.inp = torch.nn.Linear(d, d)
+        self.block = torch.nn.Sequential(torch.nn.LayerNorm(d), torch.nn.Linear(d, d), torch.nn.ReLU())
+        self.mid = torch.nn.Linear(d, d)
+        self.head = torch.nn.Linear(d, vocab, bias=False)
+        self.head.weight = self.emb.weight
+
+    def forward(self, tok):
+        x = self.inp(self.emb(tok))
+        x = x + self.block(x)
+        x = self.mid(x)
+        x = x + self.block(x)                             # the same modules a second time
+        return self.head(x)
+
+
+def test_tied_weights_and_a_block_used_twice_train_like_the_resident_model():
+    lr, iters = 0.05, 4
+    torch.manual_seed(1)
+    toks = [torch.randint(0, 96, (8, 16), device="cuda:0") for _ in range(iters + 1)]
+    tgts = [torch.randint(0, 96, (8 * 16,), device="cuda:0") for _ in range(iters + 1)]
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def make():
+        torch.manual_seed(3)
+        return _Tied().to("cuda:0")
+
+    ref = make()
+    ref_losses = []
+    for i in range(iters):
+        for p in ref.parameters():
+            p.grad = None
+        loss = loss_fn(ref(toks[i]).view(-1, 96), tgts[i])
+        loss.backward()
+        ref_losses.append(float(loss.detach()))
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+
+    model = make()
+    assert model.head.weight is model.emb.weight
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(total * 0.75))
+    assert len(pc.params) == len(list(model.parameters()))          # the shared parameter is one tensor of the cache
+    pc.profile(lambda: loss_fn(model(toks[-1]).view(-1, 96), tgts[-1]).backward())
+    n_p = len(pc.params)
+    fwd_bwd = pc.steps[:-n_p]
+    # emb, inp, (ln, lin), mid, (ln, lin), head forward = 8 module uses, as many backward
+    assert len(fwd_bwd) == 16
+    shared = pc.pid[id(model.emb.weight)]
+    assert [k for k, st in enumerate(fwd_bwd) if any(t == shared for t, _ in st)] == [0, 7, 8, 15]
+    pc.install()
+    losses = []
+    for i in range(iters):
+        loss = loss_fn(model(toks[i]).view(-1, 96), tgts[i])
+        loss.backward()
+        losses.append(float(loss.detach()))
+        pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    st = pc.tc.cache_stats()
+    log = pc.tc.dump_oplog()
+    pc.close()
+    assert losses == ref_losses
+    for a, b in zip(got, [p.detach().cpu() for p in ref.parameters()]):
+        assert torch.equal(a, b)
+    assert st["n_ops"][1] > 0 and st["misses"] == 0
+    nbytes = [p.numel() * p.element_size() for p in ref.parameters()]
+    stp, te, rw = [], [], []
+    for k, step in enumerate(pc.steps):
+        for (t, a) in step:
+            stp.append(k), te.append(t), rw.append(a)
+    host = sum((n + 255) // 256 * 256 for n in nbytes) + 4096
+    r = o.build(nbytes, [0] * len(nbytes), stp, te, rw, int(total * 0.75), (host, 0))
+    for _ in range(iters):
+        r.run_iteration(pc.steps)
+    assert [(int(x["step"]), int(x["op"]), int(x["tensor"]), int(x["dst_slot"])) for x in log] == \
+        [(e[1], e[3], e[4], e[8]) for e in r.log]
+    # the update in the hooks and managed gradients need every gradient complete at the module's own step
+    for kw in (dict(fused_sgd_lr=0.1), dict(manage_grads=True)):
+        with pytest.raises(ValueError):
+            ParamCache(make(), hbm_bytes=int(total * 0.75), **kw)
+
+
 def test_training_demo_runs_a_gpt_shaped_model_through_the_cache(capsys, monkeypatch):
     # the demonstration script, at a size that takes a second: attention blocks, embedding,
     # untied head, bf16; every parameter passes through the cache and nothing misses
