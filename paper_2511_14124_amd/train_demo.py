@@ -65,6 +65,22 @@ def build_model(torch, d_model, n_layers, n_heads, vocab, dtype):
     return Model().to(device="cuda:0", dtype=dtype)
 
 
+def build_library_model(torch, family, d_model, n_layers, n_heads, vocab, seq, dtype):
+    """A model this package did not write: the GPT-2 (head tied to the token table) or Llama class of the
+    transformers package at the given size, random weights, no dropout; nothing is downloaded."""
+    import transformers as tf
+    if family == "gpt2":
+        cfg = tf.GPT2Config(vocab_size=vocab, n_positions=seq, n_embd=d_model, n_layer=n_layers, n_head=n_heads,
+                            resid_pdrop=0.0, embd_pdrop=0.0, attn_pdrop=0.0, bos_token_id=0, eos_token_id=0)
+        model = tf.GPT2LMHeadModel(cfg)
+    else:
+        cfg = tf.LlamaConfig(vocab_size=vocab, hidden_size=d_model, intermediate_size=(8 * d_model // 3 + 255) // 256 * 256,
+                             num_hidden_layers=n_layers, num_attention_heads=n_heads, num_key_value_heads=n_heads,
+                             max_position_embeddings=seq, bos_token_id=0, eos_token_id=0)
+        model = tf.LlamaForCausalLM(cfg)
+    return model.to(device="cuda:0", dtype=dtype)
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=12)
@@ -86,6 +102,8 @@ def main(argv=None):
                     help="let the first six steps decide between the kernel alone and DMA copies from 64 KiB")
     ap.add_argument("--fused-sgd", action="store_true",
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
+    ap.add_argument("--hf", choices=["gpt2", "llama"], default=None,
+                    help="train the transformers package's GPT-2 or Llama class at this size instead of the built-in model")
     ap.add_argument("--manage-grads", action="store_true",
                     help="the gradients are tensors of the cache too (--cache is then a fraction of parameters + gradients)")
     args = ap.parse_args(argv)
@@ -103,8 +121,16 @@ def main(argv=None):
     loss_fn = torch.nn.CrossEntropyLoss()
 
     def iteration(model):
+        if args.hf:
+            model(input_ids=tokens, labels=target).loss.backward()
+            return
         logits = model(tokens)
         loss_fn(logits.float().view(-1, args.vocab), target.view(-1)).backward()
+
+    def build():
+        if args.hf:
+            return build_library_model(torch, args.hf, args.d_model, args.layers, args.heads, args.vocab, args.seq, dtype)
+        return build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
 
     def timed(step_fn):
         step_fn()                                          # warm-up (allocator, kernel selection)
@@ -116,7 +142,8 @@ def main(argv=None):
         return (time.perf_counter() - t0) / args.steps
 
     # ---- parameters resident
-    model = build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
+    torch.manual_seed(0)
+    model = build()
     n_params = sum(p.numel() for p in model.parameters())
     param_bytes = sum(p.numel() * p.element_size() for p in model.parameters())
 
@@ -137,7 +164,7 @@ def main(argv=None):
 
     # ---- parameters in the tensor cache
     torch.manual_seed(0)
-    model = build_model(torch, args.d_model, args.layers, args.heads, args.vocab, dtype)
+    model = build()
     managed_bytes = param_bytes * (2 if args.manage_grads else 1)
     pc = ParamCache(model, hbm_bytes=int(managed_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None,
                     dma_threshold=(args.dma_kib << 10) or None, manage_grads=args.manage_grads)
@@ -167,7 +194,9 @@ def main(argv=None):
     n_counted = args.steps + 1                             # timed() runs one warm-up step after s0 is taken
     plan = pc.tc.plan
     out = {
-        "model": {"layers": args.layers, "d_model": args.d_model, "params": n_params, "param_GiB": param_bytes / 2**30,
+        "model": {"class": {"gpt2": "transformers.GPT2LMHeadModel", "llama": "transformers.LlamaForCausalLM",
+                            None: "built-in GPT-shaped decoder"}[args.hf],
+                  "layers": args.layers, "d_model": args.d_model, "params": n_params, "param_GiB": param_bytes / 2**30,
                   "dtype": "bf16", "tokens_per_step": args.batch * args.seq, "modules_with_hooks": len(pc.mods)},
         "hbm_cache_GiB": float(plan.hbm_total) / 2**30, "cache_fraction": float(plan.hbm_total) / managed_bytes,
         "resident": {"ms_per_step": t_res * 1e3, "tokens_per_s": args.batch * args.seq / t_res},
@@ -302,7 +331,9 @@ def cpu_adam_demo(args, torch, T):
     same_master = all(np.array_equal(sc.read(j), w.numpy()) for j, w in want_master.items())
     n = args.steps
     out = {
-        "model": {"layers": args.layers, "d_model": args.d_model, "params": int(sum(elems)),
+        "model": {"class": {"gpt2": "transformers.GPT2LMHeadModel", "llama": "transformers.LlamaForCausalLM",
+                            None: "built-in GPT-shaped decoder"}[args.hf],
+                  "layers": args.layers, "d_model": args.d_model, "params": int(sum(elems)),
                   "param_GiB": param_bytes / 2**30, "state_GiB": state_bytes / 2**30, "dtype": "bf16 + fp32 states",
                   "tokens_per_step": args.batch * args.seq},
         "hbm_cache_fraction": float(pc.tc.plan.hbm_total) / param_bytes,

@@ -193,6 +193,59 @@ def test_tied_weights_and_a_block_used_twice_train_like_the_resident_model():
             ParamCache(make(), hbm_bytes=int(total * 0.75), **kw)
 
 
+@pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
+def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
+    # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
+    # small size with random weights (nothing is downloaded).  GPT-2 ties its head to the token table,
+    # Llama has grouped-query attention, a rotary module without parameters and RMS norms; three
+    # steps through a cache of 35 % of the parameters leave the bytes of resident training.
+    tf = pytest.importorskip("transformers")
+    if family == "gpt2":
+        cfg = tf.GPT2Config(vocab_size=512, n_positions=64, n_embd=128, n_layer=4, n_head=4, resid_pdrop=0.0,
+                            embd_pdrop=0.0, attn_pdrop=0.0, bos_token_id=0, eos_token_id=0,
+                            attn_implementation="eager")
+        cls = tf.GPT2LMHeadModel
+    else:
+        cfg = tf.LlamaConfig(vocab_size=512, hidden_size=128, intermediate_size=256, num_hidden_layers=4,
+                             num_attention_heads=4, num_key_value_heads=2, max_position_embeddings=64,
+                             tie_word_embeddings=family == "llama_tied", attn_implementation="eager",
+                             bos_token_id=0, eos_token_id=0)
+        cls = tf.LlamaForCausalLM
+
+    def make():
+        torch.manual_seed(3)
+        return cls(cfg).to(device="cuda:0", dtype=torch.bfloat16)
+
+    x = torch.randint(0, 512, (2, 32), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(5))
+
+    def iteration(m):
+        m(input_ids=x, labels=x).loss.backward()
+
+    lr = 1e-2
+    ref, model = make(), make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(total * 0.35))
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    for _ in range(3):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+        iteration(model)
+        pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    st = pc.tc.cache_stats()
+    pc.close()
+    assert len(got) == len(list(ref.parameters()))
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
+    assert st["misses"] == 0 and st["n_ops"][1] > 100 and st["bytes_h2d"] > 2 * total
+
+
 def test_training_demo_runs_a_gpt_shaped_model_through_the_cache(capsys, monkeypatch):
     # the demonstration script, at a size that takes a second: attention blocks, embedding,
     # untied head, bf16; every parameter passes through the cache and nothing misses
@@ -213,6 +266,15 @@ def test_training_demo_with_the_gradients_in_the_cache():
     out = train_demo.main(["--layers", "2", "--d-model", "128", "--heads", "4", "--vocab", "512", "--batch", "2",
                            "--seq", "64", "--steps", "2", "--cache", "0.4", "--manage-grads"])
     assert out["managed"] == "parameters and gradients" and out["final_parameters_equal_resident_training"]
+    assert out["through_cache"]["hit_rate"] == 1.0 and out["cache_fraction"] < 0.8
+
+
+def test_training_demo_with_a_model_of_the_transformers_package():
+    pytest.importorskip("transformers")
+    from paper_2511_14124_amd import train_demo
+    out = train_demo.main(["--hf", "gpt2", "--layers", "2", "--d-model", "128", "--heads", "4", "--vocab", "512",
+                           "--batch", "2", "--seq", "64", "--steps", "2", "--cache", "0.4"])
+    assert out["model"]["class"] == "transformers.GPT2LMHeadModel" and out["final_parameters_equal_resident_training"]
     assert out["through_cache"]["hit_rate"] == 1.0 and out["cache_fraction"] < 0.8
 
 
