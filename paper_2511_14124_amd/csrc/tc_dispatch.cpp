@@ -114,10 +114,11 @@ int timed_end(tc_ctx *c, int kind, hipEvent_t t0, uint64_t bytes)
 // default every unit, whatever its size, goes into a migration-kernel launch on
 // stream K: per-copy overhead would dominate the small ones, the kernel's
 // load-load-store-store order lets a unit swap two buffers in place, and with
-// both directions loaded the kernel also carries the large ones faster than the
-// DMA engines do in this runtime (49 against 29 GB/s per direction).  What the
+// both directions loaded the kernel carries the large ones as fast as two DMA
+// engines do (49.7 against 48.6 GB/s per direction) without the bounce copy and
+// the waits between three streams a swap by DMA copies needs.  What the
 // DMA engines are good for is compute running beside the copies, which the
-// kernel's host reads slow down and DMA copies hardly do: with a DMA threshold
+// kernel's host accesses slow down and DMA copies do not: with a DMA threshold
 // set (tc_set_dma_threshold, tc_set_dma_policy) units at least that large take
 // them, always or only while the compute stream has a backlog to hide them
 // behind.  Such a unit's outgoing tensor is first copied inside HBM to a bounce
