@@ -364,8 +364,8 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         if ((rc = timed_end(c, S_D, t0, p.u.bytes)) != TC_OK) return rc;
         if ((rc = end_op(c, S_D, idd)) != TC_OK) return rc;
         if (p.cpu_out >= 0) c->cpu_ticket[(size_t)p.cpu_out] = idd;
-        for (BounceBlock &blk : c->bounce_q)
-            if (c->bounce + blk.off == L.bounce) blk.op = idd;
+        for (BounceBlock &bb : c->bounce_q)
+            if (c->bounce + bb.off == L.bounce) bb.op = idd;
         c->stats.dma_copies++;
         if (p.out_staging && blk) {
             blk->ops[1] = idd;
