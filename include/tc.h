@@ -69,6 +69,7 @@ extern "C" {
 
 #define TC_NONE 0xFFFFFFFFu          /* "no slot" / "never" */
 #define TC_MAX_STEP_TENSORS 64       /* most tensors one hook call may name (the lanes of the wavefront that decides it) */
+#define TC_MAX_STEPS (1u << 28)      /* step indices of a profile are below this (tables are sized by the last one) */
 
 /* tc_budget.flags */
 #define TC_LITERAL_ALG2 1u           /* Alg. 2 exactly as printed: no per-step working-set floor */
@@ -212,7 +213,10 @@ int tc_destroy(tc_ctx *ctx);
 /* Sec. 3.2 (tensor characteristic analyzer).  Builds the prefetch table from
  * one profiled iteration: rows in execution order (a tensor named twice by one
  * step is one row), per-tensor use lists, the size->count dictionary TC and the
- * per-class per-step maximum.  t, ev: host arrays. */
+ * per-class per-step maximum.  t, ev: host arrays.  TC_E_ARG for events not
+ * ordered by step, a step index of TC_MAX_STEPS or more, an unknown tensor, a
+ * tensor under 16 bytes, a group other than 0 or 1, rw outside TC_R|TC_W;
+ * TC_E_CAPACITY if the host has no memory for the tables. */
 int tc_profile_order(tc_ctx *ctx, const tc_tensor_desc *t, uint32_t n_tensors,
                      const tc_event *ev, uint64_t n_events);
 

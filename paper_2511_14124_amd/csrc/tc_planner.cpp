@@ -26,6 +26,10 @@ int tc_build_profile(TcProfile &p, const tc_tensor_desc *t, uint32_t n_t, const 
         p.kind[i] = t[i].kind;
     }
     if (n_ev >= TC_INF) { err = "too many events"; return TC_E_ARG; }
+    // the last event names the last step only if the events are in order: look before the tables are sized by it
+    for (uint64_t i = 1; i < n_ev; ++i)
+        if (ev[i].step < ev[i - 1].step) { err = "events are not ordered by step"; return TC_E_ARG; }
+    if (n_ev && ev[n_ev - 1].step >= TC_MAX_STEPS) { err = "step index beyond TC_MAX_STEPS"; return TC_E_ARG; }
     p.n_steps = n_ev ? ev[n_ev - 1].step + 1 : 0;
     // Prefetch table (Sec. 3.2.1): rows in execution order; a tensor a step
     // names twice is one row whose flags are OR-ed.

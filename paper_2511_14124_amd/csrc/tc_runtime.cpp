@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <exception>
 
 extern "C" const char *tc_strerror(int code)
 {
@@ -84,7 +85,12 @@ extern "C" int tc_profile_order(tc_ctx *c, const tc_tensor_desc *t, uint32_t n_t
     if (c->stage >= 4) return fail(c, TC_E_STATE, "context is already bound");
     std::string err;
     TcProfile p;
-    int rc = tc_build_profile(p, t, n_t, ev, n_ev, err);
+    int rc;
+    try {
+        rc = tc_build_profile(p, t, n_t, ev, n_ev, err);
+    } catch (const std::exception &) {                  // bad_alloc, length_error: nothing may cross the C boundary
+        return fail(c, TC_E_CAPACITY, "out of host memory while building the prefetch table");
+    }
     if (rc != TC_OK) return fail(c, rc, err);
     c->prof = std::move(p);
     c->stage = 1;
@@ -100,7 +106,12 @@ extern "C" int tc_plan_pools(tc_ctx *c, const tc_budget *b, tc_pool_plan *plan_o
     if (classes_out && cap < n_c) return fail(c, TC_E_CAPACITY, "classes_out too small");
     std::string err;
     TcPools pools;
-    int rc = tc_build_pools(c->prof, *b, pools, err);
+    int rc;
+    try {
+        rc = tc_build_pools(c->prof, *b, pools, err);
+    } catch (const std::exception &) {
+        return fail(c, TC_E_CAPACITY, "out of host memory while planning the pools");
+    }
     if (rc != TC_OK) return fail(c, rc, err);
     c->pools = std::move(pools);
     c->budget = *b;
@@ -138,7 +149,11 @@ extern "C" int tc_plan_schedule(tc_ctx *c, tc_placement *out)
 {
     if (!c) return TC_E_ARG;
     if (c->stage < 2 || c->stage >= 4) return fail(c, TC_E_STATE, "tc_plan_pools must come first");
-    tc_build_placement(c->prof, c->pools, c->place);
+    try {
+        tc_build_placement(c->prof, c->pools, c->place);
+    } catch (const std::exception &) {
+        return fail(c, TC_E_CAPACITY, "out of host memory while placing the tensors");
+    }
     if (out)
         for (uint32_t t = 0; t < c->prof.n_tensors; ++t) {
             out[t].file_off = c->place.file_off[t];

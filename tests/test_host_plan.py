@@ -110,6 +110,17 @@ def test_error_codes_and_call_order():
         tc.profile_order([512, 512], [0, 0], [1, 0], [0, 1], [1, 1])      # steps out of order
     assert e.value.code == -1
     with pytest.raises(T.TcError) as e:
+        # a step index in the middle that is larger than the last one: the tables are sized by the last
+        # event's step, so this must be refused before anything is written
+        tc.profile_order([512, 512], [0, 0], [0, 900, 1], [0, 1, 0], [1, 1, 1])
+    assert e.value.code == -1 and "ordered" in str(e.value)
+    with pytest.raises(T.TcError) as e:
+        tc.profile_order([512, 512], [0, 0], [0, 1 << 28], [0, 1], [1, 1])  # step index of TC_MAX_STEPS
+    assert e.value.code == -1
+    with pytest.raises(T.TcError) as e:
+        tc.profile_order([512, 512], [0, 0], [0, 0xFFFFFFFF], [0, 1], [1, 1])
+    assert e.value.code == -1
+    with pytest.raises(T.TcError) as e:
         tc.profile_order([512, 512], [0, 0], [0, 1], [0, 7], [1, 1])      # unknown tensor
     assert e.value.code == -1
     with pytest.raises(T.TcError) as e:
