@@ -466,9 +466,10 @@ int tc_set_dma_threshold(tc_ctx *ctx, uint64_t bytes);
  * and modules alternate).  enable != 0: a hook call that prepares copies
  * queues a one-lane kernel on its compute stream that raises a sequence word
  * behind the modules queued so far; the migration launch is queued at once and
- * its workgroups wait for that word themselves; every launch raises a second
- * word when its last workgroup leaves, and a module that needs what a launch
- * brings is preceded on its stream by a one-lane kernel that waits for it.
+ * its workgroups wait for that word themselves; a one-lane kernel queued
+ * behind every launch on the migration stream raises a second word to the
+ * launch's number, and a module that needs what a launch brings is preceded
+ * on its stream by a one-lane kernel that waits for that number.
  * Every such wait is bounded by timeout_ms (0 = 5000): a waiter that gives up
  * moves nothing, and the next hook call or tc_synchronize returns TC_E_HIP; the
  * bytes are then not to be trusted and the context should be destroyed.  Use

@@ -273,14 +273,13 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         }
         int rc = begin_op(c, S_K, compute, &id, !gate);
         if (rc != TC_OK) return rc;
+        uint32_t done_seq = 0;
         if (c->gpu_deps) {
-            args.fault = c->fault;
-            args.gave_up = c->tickets + 35;
-            args.spin_ticks = c->spin_ticks;
-            args.done = c->tickets + 33;
-            args.exited = c->tickets + 34;
-            args.done_seq = ++c->launch_seq;
+            done_seq = ++c->launch_seq;
             if (gate) {
+                args.fault = c->fault;
+                args.gave_up = c->tickets + 35;
+                args.spin_ticks = c->spin_ticks;
                 args.progress = c->tickets + 32;
                 args.need_seq = need_sig;
             }
@@ -308,8 +307,10 @@ static int issue_units(tc_ctx *c, std::vector<PUnit> &units, hipStream_t compute
         const uint32_t wgs = gate ? std::min<uint32_t>(c->mover_wgs, 32) : c->mover_wgs;
         HIP_TRY(c, tc_launch_mover(args, wgs, c->streams[S_K], &c->k_launches));
         if ((rc = timed_end(c, S_K, t0, bytes)) != TC_OK) return rc;
+        // the launch's number goes into the done word by a one-lane kernel right behind it on this stream
+        if (c->gpu_deps) HIP_TRY(c, tc_launch_signal(c->tickets + 33, done_seq, c->streams[S_K]));
         if ((rc = end_op(c, S_K, id)) != TC_OK) return rc;
-        if (c->gpu_deps) c->op_lseq[id % OP_RING] = args.done_seq;
+        if (c->gpu_deps) c->op_lseq[id % OP_RING] = done_seq;
         c->last_k_op = id;
         c->stats.mover_launches++;
         c->stats.mover_units += args.n_units;
@@ -541,8 +542,8 @@ static int dispatch_host_tier(tc_ctx *c, const TcOpRec &r, uint32_t t, uint32_t 
     }
 }
 
-// the signal of this hook call on its compute stream: queued when the call prepares its first unit,
-// behind the modules queued so far
+// the signal the units of this hook call wait for, on its compute stream: queued when a call prepares a unit
+// and no signal queued behind the last module is at hand
 static int call_signal(tc_ctx *c, hipStream_t compute, uint32_t *sig)
 {
     *sig = 0;
@@ -573,7 +574,11 @@ int dispatch(tc_ctx *c, const TcDecideOut *o, const TcOpRec *ops, uint32_t step,
     bool have_out = false;
     uint8_t *reserved_in = nullptr; // bounce space kept for the partner of a write-back
     c->compute_recorded = false;
-    c->sig_sent = false;
+    // A signal stands for "the modules queued so far": it stays good for the units of later calls until a
+    // module may have been queued behind it, i.e. until a PRE call has returned (cache buffers are used only
+    // between a step's PRE and POST).  So a POST or end-of-iteration call starts without one, a PRE call
+    // keeps the one the call before it queued.
+    if (phase != TC_PRE || c->sig_stream != compute) c->sig_sent = false;
     for (int i = 0; i < N_STREAMS; ++i) c->stream_waited[i] = false;
     for (uint32_t i = 0; i < o->n_ops; ++i) {
         const TcOpRec &r = ops[i];

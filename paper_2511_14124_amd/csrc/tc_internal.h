@@ -133,17 +133,17 @@ struct TcMoverArgs {
     uint32_t slot;                              // 0 or 1: set by the launcher, alternates between launches
     uint32_t xcc;                               // the XCD whose workgroups do the work
     uint32_t n_xcd;                             // XCDs the dispatcher deals workgroups to (grid = workgroups x n_xcd)
-    // Dependencies resolved on the GPU (all nullptr / 0: none).  gate: the launch may be queued before the
-    // modules it has to wait for have run; its working workgroups wait until the word at `progress` has
-    // reached need_seq (tc_signal_kernel, queued on the compute stream behind those modules, raises it).
-    // done: every workgroup counts itself out in `exited`; the last one raises the word at `done` to done_seq
-    // (tc_wait_kernel, queued on the compute stream in front of a module, waits for that).  Both waits
-    // are bounded: after spin_ticks of the 100 MHz wall clock a waiter gives up, raises *fault and the
-    // launch moves nothing (the host reports it; the data is then not to be trusted).
+    // Dependencies resolved on the GPU (progress nullptr: none).  The launch may be queued before the modules
+    // it has to wait for have run; its working workgroups wait until the word at `progress` has reached
+    // need_seq (tc_signal_kernel, queued on the compute stream behind those modules, raises it).  The wait
+    // is bounded: after spin_ticks of the 100 MHz wall clock a waiter gives up, raises *fault and the launch
+    // moves nothing (the host reports it; the data is then not to be trusted).  (That a launch is done is
+    // signalled the same way, by a tc_signal_kernel queued behind it on its own stream, and waited for by a
+    // tc_wait_kernel in front of the module that needs it.)
     const uint32_t *progress;
-    uint32_t *done, *exited, *fault;            // fault: pinned host word the host reads
+    uint32_t *fault;                            // pinned host word the host reads
     uint32_t *gave_up;                          // device word: set with *fault, makes every later waiter give up at once
-    uint32_t need_seq, done_seq;
+    uint32_t need_seq;
     uint64_t spin_ticks;
 };
 

@@ -548,32 +548,12 @@ __device__ bool seq_wait(const uint32_t *word, uint32_t seq, uint64_t ticks, uin
     return false;
 }
 
-// a workgroup leaves the launch: the last of the whole grid to do so raises the launch's done word.
-// Its own stores (and, through the counter, everyone's before it) are released first.
-__device__ __forceinline__ void mover_count_out(const TcMoverArgs &a, uint32_t tid)
-{
-    if (!a.done) return;
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t before = __hip_atomic_fetch_add(a.exited, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        if (before + 1 == gridDim.x) {
-            __hip_atomic_store(a.exited, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the launch behind this one
-            // (launches of one stream end in order, so the word only grows)
-            __hip_atomic_store(a.done, a.done_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
-
 __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
 {
     uint32_t xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
     const uint32_t tid = threadIdx.x;
-    if ((xcc & 15u) != a.xcc && blockIdx.x != 0) {
-        mover_count_out(a, tid);
-        return;
-    }
+    if ((xcc & 15u) != a.xcc && blockIdx.x != 0) return;
     __shared__ uint32_t ticket;
     __shared__ uint32_t go;
     if (blockIdx.x == 0 && tid == 0) a.tickets[a.slot ^ 1u] = 0;
@@ -583,10 +563,7 @@ __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
             go = seq_wait(a.progress, a.need_seq, a.spin_ticks, a.fault, a.gave_up, 1u) ? 1u : 0u;
         }
         __syncthreads();
-        if (!go) {                                         // gave up: move nothing, leave in order
-            mover_count_out(a, tid);
-            return;
-        }
+        if (!go) return;                                   // gave up: move nothing
         __threadfence();                                   // what those modules wrote is read from here on
     }
     uint32_t ui = 0;                                       // tickets only grow: the unit search resumes where it stopped
@@ -648,17 +625,19 @@ __global__ __launch_bounds__(MOVER_THREADS) void tc_mover_kernel(TcMoverArgs a)
             if (tid < tail) d[(uint64_t)n16 * 16 + tid] = s[(uint64_t)n16 * 16 + tid];
         }
     }
-    mover_count_out(a, tid);
 }
 
-// The compute stream's side of the dependencies resolved on the GPU: one lane raises a sequence word
-// behind the modules queued so far, one lane waits for a word in front of a module (bounded).
+// The other side of the dependencies resolved on the GPU: one lane raises a sequence word behind what is
+// queued so far on its stream (the modules on the compute stream; a launch on the migration stream), one
+// lane waits for a word in front of a module (bounded).
 __global__ void tc_signal_kernel(uint32_t *word, uint32_t seq)
 {
     if (threadIdx.x == 0) {
-        __threadfence();
-        uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // never lower it: signals of two compute streams may arrive out of order
+        // (what the kernels before this one on the stream wrote was released when they ended; the
+        // exchange is a release all the same)
+        // never lower the word: signals of two compute streams may arrive out of order.  The usual
+        // case is the number before this one, so that is the first guess: one trip to memory.
+        uint32_t v = seq - 1;
         while ((int32_t)(seq - v) > 0 &&
                !__hip_atomic_compare_exchange_strong(word, &v, seq, __ATOMIC_RELEASE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
         }
@@ -750,8 +729,7 @@ hipError_t tc_launch_mover(TcMoverArgs &a, uint32_t workgroups, hipStream_t s, u
     if (a.n_units > TC_MOVER_MAX_UNITS || a.chunk_bytes == 0 || (a.chunk_bytes & 15)) return hipErrorInvalidValue;
     if (!a.tickets || !launches || workgroups == 0 || workgroups > 8192 || a.n_xcd == 0 || a.n_xcd > 16)
         return hipErrorInvalidValue;
-    if ((a.progress || a.done) && (!a.fault || !a.gave_up || !a.spin_ticks)) return hipErrorInvalidValue;
-    if (a.done && !a.exited) return hipErrorInvalidValue;
+    if (a.progress && (!a.fault || !a.gave_up || !a.spin_ticks)) return hipErrorInvalidValue;
     uint64_t chunks = 0;
     for (uint32_t i = 0; i < a.n_units; ++i) {
         const TcUnit &u = a.u[i];

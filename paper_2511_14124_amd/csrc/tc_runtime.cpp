@@ -1058,6 +1058,7 @@ extern "C" int tc_set_gpu_dependencies(tc_ctx *c, int enable, uint32_t timeout_m
     int rc = tc_synchronize(c);
     if (rc != TC_OK) return rc;
     c->gpu_deps = enable != 0;
+    c->sig_sent = false;
     if (enable) c->spin_ticks = (uint64_t)timeout_ms * 100000ull;      // the clock runs at 100 MHz
     return TC_OK;
 }
