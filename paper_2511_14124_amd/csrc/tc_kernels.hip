@@ -539,7 +539,10 @@ __device__ bool seq_wait(const uint32_t *word, uint32_t seq, uint64_t ticks, uin
     const uint64_t t0 = wall_clock64();
     for (uint32_t n = 0;; ++n) {
         if ((n & 255u) == 0 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
-        __builtin_amdgcn_s_sleep(4);
+        // a short wait is polled closely (0.1 us), a long one every microsecond or so: polls go to memory, and a
+        // dozen waiters polling one word closely for milliseconds slow the kernels that run meanwhile
+        if (n < 64) __builtin_amdgcn_s_sleep(4);
+        else __builtin_amdgcn_s_sleep(32);
         if (seq_reached(word, seq)) return true;
         if (wall_clock64() - t0 > ticks) break;
     }

@@ -104,6 +104,8 @@ def main(argv=None):
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
     ap.add_argument("--hf", choices=["gpt2", "llama"], default=None,
                     help="train the transformers package's GPT-2 or Llama class at this size instead of the built-in model")
+    ap.add_argument("--gpu-deps", action="store_true",
+                    help="modules and migration launches wait for each other on the GPU (tc_set_gpu_dependencies)")
     ap.add_argument("--manage-grads", action="store_true",
                     help="the gradients are tensors of the cache too (--cache is then a fraction of parameters + gradients)")
     args = ap.parse_args(argv)
@@ -171,6 +173,8 @@ def main(argv=None):
     pc.profile(lambda: iteration(model))
     pc.install()
     pc.tc.set_oplog(False, True)
+    if args.gpu_deps:
+        pc.tc.set_gpu_dependencies(True)
 
     def cached_step():
         iteration(model)
