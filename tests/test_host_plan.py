@@ -154,3 +154,48 @@ def test_smallest_first_plan_matches_the_oracle_on_random_traces():
                                literal=(seed % 5 == 0))
         wl.smallest_first = True
         _check_plan(wl)
+
+
+def test_random_malformed_profiles_are_refused_or_planned_and_never_take_the_process_down():
+    # what the planner is handed comes from a caller: whatever is wrong with it (steps out of order, a
+    # step index far beyond the others, unknown tensors, sizes under 16 bytes, bad groups and flags, a
+    # budget of nothing) must come back as an error code, and what is right must be planned
+    rng = np.random.default_rng(20261128)
+    outcomes = {"planned": 0, -1: 0, -3: 0}
+    for case in range(400):
+        n_t, n_s = int(rng.integers(1, 60)), int(rng.integers(1, 40))
+        sizes = rng.choice([16, 17, 100, 512, 4096, 33000], size=n_t).astype(np.uint64)
+        group = rng.integers(0, 2, size=n_t)
+        step, tensor, rw = [], [], []
+        for k in range(n_s):
+            for _ in range(int(rng.integers(0, 5))):
+                step.append(k), tensor.append(int(rng.integers(0, n_t))), rw.append(int(rng.integers(1, 4)))
+        broken = int(rng.integers(0, 10))
+        if step:
+            i = int(rng.integers(0, len(step)))
+            if broken == 0:
+                step[i] = n_s + int(rng.integers(1, 1 << 20))       # larger than the last event's, in the middle
+            elif broken == 1:
+                tensor[i] = n_t + int(rng.integers(0, 3))
+            elif broken == 2:
+                rw[i] = int(rng.choice([0, 4, 255]))
+            elif broken == 3:
+                step[i] = 0xFFFFFFFF
+        if broken == 4:
+            sizes[int(rng.integers(0, n_t))] = int(rng.integers(0, 16))
+        elif broken == 5:
+            group[int(rng.integers(0, n_t))] = 2
+        tc = T.TensorCache()
+        try:
+            tc.profile_order(sizes, group, step, tensor, rw)
+            total = int(sizes.sum())
+            tc.plan_pools(int(total * rng.choice([0.0, 0.1, 0.5, 2.0])), (int(total * rng.choice([0.0, 0.3, 2.0])),) * 2,
+                          align=int(rng.choice([256, 16, 4096, 3, 8])), flags=int(rng.integers(0, 16)))
+            tc.plan_schedule()
+            outcomes["planned"] += 1
+        except T.TcError as e:
+            assert e.code in (-1, -3), (case, e)
+            outcomes[e.code] += 1
+        finally:
+            tc.close()
+    assert outcomes["planned"] > 50 and outcomes[-1] > 50 and outcomes[-3] > 10, outcomes
