@@ -36,6 +36,15 @@ a pass are handled in the parameters-only mode: such a use's backward step is
 closed when the gradients of its own inputs arrive, not when its parameters'
 gradients do (those are complete only after the last use).
 
+What is managed are the parameters of the modules that own parameters and call no other module that
+does (the leaves of the model as far as parameters go: Linear, LayerNorm, Embedding ...).  A module
+that owns parameters AND calls such modules (a root module with a position table of its own, say)
+uses its parameters across its children's steps, where nothing protects them from eviction: its own
+parameters stay ordinary resident tensors (`ParamCache.resident`), and so do those of the modules
+named in `resident_modules` (for a module whose parameters are used without its forward being called,
+as the output projection inside `nn.MultiheadAttention` is; the dry run refuses such a module
+otherwise).  `sgd_step` and `gather` cover the resident parameters too.
+
 Between its pre-hook and its post-hook a module's parameters are views into
 the HBM cache buffers the library returned; outside that window they point
 nowhere useful and must not be touched.  A parameter may come back for the
@@ -76,7 +85,7 @@ class _ParamRef:
 class ParamCache:
     def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
                  fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None,
-                 manage_grads: bool = False):
+                 manage_grads: bool = False, resident_modules=()):
         import torch
         self.torch = torch
         self.model = model
@@ -90,8 +99,15 @@ class ParamCache:
         # parameters of at least this many bytes travel as DMA-engine copies instead of through the
         # zero-copy kernel: slower on the link, but compute running beside them is hardly slowed
         self.dma_threshold = dma_threshold
-        # leaf modules: those that own parameters directly
-        self.mods = [m for m in model.modules() if any(True for _ in m.parameters(recurse=False))]
+        # managed: the modules that own parameters and call no other module that does.  A module above such
+        # a module uses its own parameters across its children's steps (nothing would keep them in their
+        # buffers there): those stay resident, like the parameters of the modules the caller names.
+        def owns(m):
+            return any(True for _ in m.parameters(recurse=False))
+        keep_out = {id(m) for r in resident_modules for m in r.modules()}
+        owners = [m for m in model.modules() if owns(m)]
+        self.mods = [m for m in owners
+                     if id(m) not in keep_out and not any(c is not m and owns(c) for c in m.modules())]
         self.params: List = []
         self.pid: Dict[int, int] = {}
         for m in self.mods:
@@ -99,6 +115,14 @@ class ParamCache:
                 if id(p) not in self.pid:
                     self.pid[id(p)] = len(self.params)
                     self.params.append(p)
+        if not self.params:
+            raise ValueError("no module of this model owns parameters the cache could manage")
+        self.resident: List = []                          # parameters left where they are
+        for p in model.parameters():
+            if id(p) not in self.pid:
+                self.resident.append(p)
+        # model.parameters() order -> managed index or resident tensor (for gather)
+        self._order = [self.pid.get(id(p), p) for p in model.parameters()]
         per_step = 2 if manage_grads else 1
         if any(per_step * len(list(m.parameters(recurse=False))) > T.MAX_STEP_TENSORS for m in self.mods):
             raise ValueError("a module owns more parameters than one hook call may name")
@@ -149,6 +173,7 @@ class ParamCache:
         self._open_use: Dict[int, int] = {}               # module -> the use whose forward is running
         self._use_inputs: Dict[int, int] = {}             # use -> input gradients still due
         self._use_step: Dict[int, int] = {}               # use -> step index of its running backward
+        self._ran: Dict[int, bool] = {}                   # module -> its forward ran in the dry run
         self._check_by_input()
 
     def _check_by_input(self):
@@ -229,6 +254,8 @@ class ParamCache:
         return r
 
     def _fwd_pre(self, m, args):
+        if self._recording:
+            self._ran[id(m)] = True
         self._uses[id(m)] = self._uses.get(id(m), 0) + 1
         if self._uses[id(m)] > 1 and id(m) not in self._by_input:
             if not self._recording:
@@ -329,6 +356,7 @@ class ParamCache:
         self._k = 0
         self._uses, self._next_use, self._open_use, self._use_inputs, self._use_step = {}, 0, {}, {}, {}
         self._recording = True
+        self._ran: Dict[int, bool] = {}
         self._register()
         try:
             run_iteration()
@@ -337,6 +365,11 @@ class ParamCache:
             self._recording = False
         if self._bwd_step or self._use_step:
             raise RuntimeError("a module's backward did not finish during the dry run")
+        ran = {id(m) for m in self.mods if self._ran.get(id(m))}
+        idle = [type(m).__name__ for m in self.mods if id(m) not in ran]
+        if idle:
+            raise ValueError("modules whose forward never ran in the dry run own parameters: " + ", ".join(sorted(set(idle))) +
+                             " (if their parameters are used by another module's forward, name them in resident_modules)")
         self._uses, self._next_use, self._use_inputs = {}, 0, {}
         self._n_model_steps = len(self.steps)
         # the optimizer sweep: every parameter once, read and written
@@ -344,7 +377,7 @@ class ParamCache:
             n_p = len(self.params)
             for t in range(n_p):
                 self.steps.append([(n_p + t, R), (t, RW)] if self.manage_grads else [(t, RW)])
-        for p in self.params:
+        for p in self.params + self.resident:             # what the dry run left behind is no gradient of a step
             p.grad = None
 
     # ---------------------------------------------------------------- install
@@ -439,21 +472,33 @@ class ParamCache:
         return self.dma_threshold
 
     def sgd_step(self, lr: float):
-        """Plain SGD through the cache."""
+        """Plain SGD: the managed parameters through the cache, the resident ones where they are."""
         self.update_sweep(lambda t, p: p.data.add_(p.grad, alpha=-lr))
+        with self.torch.no_grad():
+            for p in self.resident:
+                if p.grad is not None:
+                    p.add_(p.grad, alpha=-lr)
 
     def end_iteration(self):
         self.tc.end_iteration(self.torch.cuda.current_stream().cuda_stream)
         self._k = 0
         self._uses, self._next_use, self._open_use, self._use_inputs, self._use_step = {}, 0, {}, {}, {}
+        if self.fused_sgd_lr is not None:                 # the resident parameters have no hook to be updated in
+            with self.torch.no_grad():
+                for p in self.resident:
+                    if p.grad is not None:
+                        p.add_(p.grad, alpha=-self.fused_sgd_lr)
         for p in self.params:
+            p.grad = None
+        for p in self.resident:
             p.grad = None
 
     def gather(self) -> list:
-        """Current value of every parameter, wherever it lives (CPU tensors)."""
+        """Current value of every parameter of the model, in the order of `model.parameters()`, wherever
+        it lives (CPU tensors)."""
         torch = self.torch
         return [torch.from_numpy(self.tc.read_tensor(t)).view(self._dtype[t]).view(self._shape[t])
-                for t in range(len(self.params))]
+                if isinstance(t, int) else t.detach().cpu() for t in self._order]
 
     def gather_grads(self) -> list:
         """With managed gradients: every gradient as the cache holds it now (CPU tensors)."""

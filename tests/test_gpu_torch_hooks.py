@@ -193,6 +193,83 @@ def test_tied_weights_and_a_block_used_twice_train_like_the_resident_model():
             ParamCache(make(), hbm_bytes=int(total * 0.75), **kw)
 
 
+class _Rooted(torch.nn.Module):
+    """A root module with parameters of its own (a position table, a scale) that calls modules with
+    parameters, and optionally nn.MultiheadAttention, which uses its output projection's parameters
+    without calling that module."""
+
+    def __init__(self, mha):
+        super().__init__()
+        self.pos = torch.nn.Parameter(torch.randn(16, 64) * 0.02)
+        self.scale = torch.nn.Parameter(torch.ones(64))
+        self.emb = torch.nn.Embedding(96, 64)
+        self.blocks = torch.nn.ModuleList([torch.nn.Sequential(torch.nn.LayerNorm(64), torch.nn.Linear(64, 64),
+                                                               torch.nn.GELU()) for _ in range(4)])
+        self.mha = torch.nn.MultiheadAttention(64, 4, batch_first=True) if mha else None
+        self.out = torch.nn.Linear(64, 96)
+
+    def forward(self, x):
+        h = self.emb(x) + self.pos
+        for b in self.blocks:
+            h = h + b(h)
+        if self.mha is not None:
+            h = h + self.mha(h, h, h, need_weights=False)[0]
+        return self.out(h * self.scale)
+
+
+@pytest.mark.parametrize("mha", [False, True])
+@pytest.mark.parametrize("mode", ["sweep", "fused", "grads"])
+def test_parameters_of_a_module_that_calls_managed_modules_stay_resident(mha, mode):
+    # the root's own parameters are in use across its children's steps, where nothing would keep them in
+    # their buffers: they stay ordinary tensors (managed naively the model trained to other bytes, without
+    # an error); a module whose parameters are used without its forward being called is refused by the dry
+    # run until the caller names it
+    lr = 0.05
+    x = torch.randint(0, 96, (4, 16), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    y = torch.randint(0, 96, (64,), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(2))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        loss_fn(m(x).view(-1, 96), y).backward()
+
+    def make():
+        torch.manual_seed(3)
+        return _Rooted(mha).to("cuda:0")
+
+    kw = {"fused": dict(fused_sgd_lr=lr), "grads": dict(manage_grads=True), "sweep": {}}[mode]
+    ref, model = make(), make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    budget = int(total * (1.2 if mode == "grads" else 0.6))
+    pc = ParamCache(model, hbm_bytes=budget, **kw)
+    if mha:
+        with pytest.raises(ValueError, match="resident_modules"):
+            pc.profile(lambda: iteration(model))
+        pc.close()
+        pc = ParamCache(model, hbm_bytes=budget, resident_modules=[model.mha], **kw)
+    pc.profile(lambda: iteration(model))
+    assert [id(p) for p in pc.resident[:2]] == [id(model.pos), id(model.scale)]
+    assert len(pc.resident) == (6 if mha else 2) and len(pc.params) + len(pc.resident) == len(list(model.parameters()))
+    pc.install()
+    for _ in range(3):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+        iteration(model)
+        if mode != "fused":
+            pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    st = pc.tc.cache_stats()
+    pc.close()
+    assert len(got) == len(list(ref.parameters()))
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a, b.detach().cpu())
+    assert st["misses"] == 0 and st["n_ops"][1] > 0
+
+
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
