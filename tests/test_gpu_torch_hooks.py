@@ -270,6 +270,51 @@ def test_parameters_of_a_module_that_calls_managed_modules_stay_resident(mha, mo
     assert st["misses"] == 0 and st["n_ops"][1] > 0
 
 
+def test_gradients_accumulated_over_two_micro_batches_train_like_the_resident_model():
+    # two forward + backward passes before the update: every module runs twice in the iteration, which the
+    # hooks treat like a module used twice in a pass; with the update in the hooks or managed gradients
+    # (a gradient complete only after the last pass) the dry run refuses instead of training to other bytes
+    from paper_2511_14124_amd.train_demo import build_model
+    vocab, lr = 256, 0.05
+    xs = [torch.randint(0, vocab, (2, 32), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(s))
+          for s in (1, 2)]
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        for x in xs:
+            loss_fn(m(x).float().view(-1, vocab), x.view(-1)).backward()
+
+    def make():
+        torch.manual_seed(3)
+        return build_model(torch, 64, 3, 4, vocab, torch.float32)
+
+    ref, model = make(), make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(total * 0.5))
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    for _ in range(3):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+        iteration(model)
+        pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    pc.close()
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a, b.detach().cpu())
+    for kw in (dict(manage_grads=True), dict(fused_sgd_lr=lr)):
+        other = make()
+        pc = ParamCache(other, hbm_bytes=int(total * 1.0), **kw)
+        with pytest.raises(ValueError, match="separate update sweep"):
+            pc.profile(lambda: iteration(other))
+        pc.close()
+
+
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
