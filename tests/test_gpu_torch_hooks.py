@@ -315,6 +315,77 @@ def test_gradients_accumulated_over_two_micro_batches_train_like_the_resident_mo
         pc.close()
 
 
+class _Plain(torch.nn.Module):
+    def __init__(self, ckpt=False, unused=False):
+        super().__init__()
+        self.emb = torch.nn.Embedding(96, 64)
+        self.blocks = torch.nn.ModuleList([torch.nn.Sequential(torch.nn.LayerNorm(64), torch.nn.Linear(64, 64),
+                                                               torch.nn.GELU()) for _ in range(4)])
+        self.side = torch.nn.Linear(64, 64) if unused else None
+        self.out = torch.nn.Linear(64, 96)
+        self.ckpt, self.skip = ckpt, False
+
+    def forward(self, x):
+        from torch.utils.checkpoint import checkpoint
+        h = self.emb(x)
+        for i, b in enumerate(self.blocks):
+            if self.skip and i == 2:
+                continue
+            h = h + (checkpoint(b, h, use_reentrant=False) if self.ckpt else b(h))
+        if self.side is not None:
+            self.side(h.detach())                          # computed, not part of the loss
+        return self.out(h)
+
+
+@pytest.mark.parametrize("case", ["eval_between", "block_skipped", "module_outside_the_loss", "activation_checkpointing"])
+def test_passes_that_are_not_the_profiled_one_still_train_like_the_resident_model(case):
+    # a forward-only pass between training iterations, an iteration that skips a block (demand misses),
+    # a module whose output the loss does not use, blocks recomputed in the backward pass
+    lr = 0.05
+    x = torch.randint(0, 96, (4, 16), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    y = torch.randint(0, 96, (64,), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(2))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        loss_fn(m(x).view(-1, 96), y).backward()
+
+    def make():
+        torch.manual_seed(3)
+        return _Plain(ckpt=case == "activation_checkpointing", unused=case == "module_outside_the_loss").to("cuda:0")
+
+    script = {"eval_between": ["train", "eval", "train", "eval", "train"],
+              "block_skipped": ["train", "skip", "train"]}.get(case, ["train"] * 3)
+    ref, model = make(), make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(total * 0.5))
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    for what in script:
+        if what == "eval":
+            with torch.no_grad():
+                want, got = ref(x), model(x)
+            pc.end_iteration()
+            assert torch.equal(want, got)
+            continue
+        ref.skip = model.skip = what == "skip"
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                if p.grad is not None:
+                    p.add_(p.grad, alpha=-lr)
+        iteration(model)
+        pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    st = pc.tc.cache_stats()
+    pc.close()
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a, b.detach().cpu())
+    assert (st["misses"] > 0) == (case == "block_skipped")
+
+
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
