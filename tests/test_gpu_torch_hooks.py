@@ -386,6 +386,55 @@ def test_passes_that_are_not_the_profiled_one_still_train_like_the_resident_mode
     assert (st["misses"] > 0) == (case == "block_skipped")
 
 
+@pytest.mark.parametrize("mode", ["sweep", "fused", "grads"])
+@pytest.mark.parametrize("weights", ["fp32_under_autocast", "bf16_linears_fp32_norms"])
+def test_mixed_precision_trains_like_the_resident_model(mode, weights):
+    # autocast makes 16-bit copies of fp32 weights inside the forward (nothing autograd saves aliases the
+    # parameter then); with 16-bit Linear layers beside fp32 norms the cache has size classes of both widths
+    from paper_2511_14124_amd.train_demo import build_model
+    vocab, lr = 256, 0.05
+    x = torch.randint(0, vocab, (2, 32), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        with torch.autocast("cuda", dtype=torch.bfloat16):
+            out = m(x)
+        loss_fn(out.float().view(-1, vocab), x.view(-1)).backward()
+
+    def make():
+        torch.manual_seed(3)
+        m = build_model(torch, 64, 3, 4, vocab, torch.float32)
+        if weights == "bf16_linears_fp32_norms":
+            for mod in m.modules():
+                if isinstance(mod, torch.nn.Linear):
+                    mod.to(torch.bfloat16)
+        return m
+
+    kw = {"fused": dict(fused_sgd_lr=lr), "grads": dict(manage_grads=True), "sweep": {}}[mode]
+    ref, model = make(), make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(total * (1.0 if mode == "grads" else 0.5)), **kw)
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    for _ in range(3):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+        iteration(model)
+        if mode != "fused":
+            pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    st = pc.tc.cache_stats()
+    pc.close()
+    for a, b in zip(got, ref.parameters()):
+        assert a.dtype == b.dtype and torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
+    assert st["misses"] == 0 and st["n_ops"][1] > 0
+
+
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
