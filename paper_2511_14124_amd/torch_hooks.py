@@ -500,6 +500,17 @@ class ParamCache:
         return [torch.from_numpy(self.tc.read_tensor(t)).view(self._dtype[t]).view(self._shape[t])
                 if isinstance(t, int) else t.detach().cpu() for t in self._order]
 
+    def state_dict(self) -> dict:
+        """`model.state_dict()` with the managed parameters' current values in place of the empty tensors
+        the module holds outside its steps (every name of a shared parameter included); CPU tensors for
+        the parameters, the model's own tensors for its buffers."""
+        value = {id(p): v for p, v in zip(self.model.parameters(), self.gather())}
+        sd = self.model.state_dict()
+        for name, p in self.model.named_parameters(remove_duplicate=False):
+            if name in sd:
+                sd[name] = value[id(p)]
+        return sd
+
     def gather_grads(self) -> list:
         """With managed gradients: every gradient as the cache holds it now (CPU tensors)."""
         torch, n_p = self.torch, len(self.params)

@@ -480,12 +480,18 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
         pc.sgd_step(lr)
         pc.end_iteration()
     got = pc.gather()
+    sd = pc.state_dict()
     st = pc.tc.cache_stats()
     pc.close()
     assert len(got) == len(list(ref.parameters()))
     for a, b in zip(got, ref.parameters()):
         assert torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
     assert st["misses"] == 0 and st["n_ops"][1] > 100 and st["bytes_h2d"] > 2 * total
+    # a checkpoint written from the cache: every name of the model's own state_dict, tied names included
+    want = ref.state_dict()
+    assert list(sd) == list(want)
+    for name in want:
+        assert torch.equal(sd[name].cpu().view(torch.uint8), want[name].cpu().view(torch.uint8)), name
 
 
 def test_training_demo_runs_a_gpt_shaped_model_through_the_cache(capsys, monkeypatch):
