@@ -519,8 +519,16 @@ class ParamCache:
         return [torch.from_numpy(self.tc.read_tensor(n_p + t)).view(self._dtype[t]).view(self._shape[t])
                 for t in range(n_p)]
 
-    def close(self):
+    def close(self, restore: bool = False):
+        """Hooks off, the cache's memory released.  restore: first give every managed parameter its
+        current value back as an ordinary tensor on its device, so that the model works without the
+        cache again (otherwise its managed parameters stay the empty tensors they are outside a step)."""
         self._remove()
+        if restore and self.tc is not None:
+            for t, p in enumerate(self.params):
+                value = self.torch.from_numpy(self.tc.read_tensor(t)).view(self._dtype[t]).view(self._shape[t])
+                p.data = value.to(p.device)
+                p.grad = None
         self._views = {}
         if self.tc is not None:
             self.tc.close()

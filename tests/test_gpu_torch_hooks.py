@@ -482,7 +482,9 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
     got = pc.gather()
     sd = pc.state_dict()
     st = pc.tc.cache_stats()
-    pc.close()
+    pc.close(restore=True)
+    with torch.no_grad():                                  # the model works without the cache again
+        assert torch.equal(model(input_ids=x).logits, ref(input_ids=x).logits)
     assert len(got) == len(list(ref.parameters()))
     for a, b in zip(got, ref.parameters()):
         assert torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
