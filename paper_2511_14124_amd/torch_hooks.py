@@ -351,18 +351,32 @@ class ParamCache:
 
     # ---------------------------------------------------------------- profile
     def profile(self, run_iteration: Callable[[], None]):
-        """Dry run (Sec. 3.2.1): one forward + backward under recording hooks."""
+        """Dry run (Sec. 3.2.1): one forward + backward under recording hooks.  Parameters are not
+        updated, gradients are dropped, the model's buffers and the random number generators are put
+        back as they were: training after it starts from the state before it."""
         self.steps = []
         self._k = 0
         self._uses, self._next_use, self._open_use, self._use_inputs, self._use_step = {}, 0, {}, {}, {}
         self._recording = True
         self._ran: Dict[int, bool] = {}
         self._register()
+        # the dry run leaves nothing behind: what its forward changes besides gradients (running statistics
+        # of normalisation layers, the random number generators a dropout draws from) is put back
+        torch = self.torch
+        buffers = [(b, b.detach().clone()) for b in self.model.buffers()]
+        rng_cpu = torch.get_rng_state()
+        rng_gpu = torch.cuda.get_rng_state_all() if torch.cuda.is_available() else None
         try:
             run_iteration()
         finally:
             self._remove()
             self._recording = False
+            with torch.no_grad():
+                for b, saved in buffers:
+                    b.copy_(saved)
+            torch.set_rng_state(rng_cpu)
+            if rng_gpu is not None:
+                torch.cuda.set_rng_state_all(rng_gpu)
         if self._bwd_step or self._use_step:
             raise RuntimeError("a module's backward did not finish during the dry run")
         ran = {id(m) for m in self.mods if self._ran.get(id(m))}

@@ -435,6 +435,69 @@ def test_mixed_precision_trains_like_the_resident_model(mode, weights):
     assert st["misses"] == 0 and st["n_ops"][1] > 0
 
 
+class _Stateful(torch.nn.Module):
+    """Modules whose forward changes more than activations: batch-norm statistics (buffers), dropout
+    (the random number generator); and a recurrent layer, which owns eight parameters in one step."""
+
+    def __init__(self, kind):
+        super().__init__()
+        self.emb = torch.nn.Embedding(96, 64)
+        self.rnn = {"lstm": torch.nn.LSTM, "gru": torch.nn.GRU}[kind](64, 64, num_layers=2, batch_first=True)
+        self.drop = torch.nn.Dropout(0.1)
+        self.conv = torch.nn.Conv1d(64, 64, 3, padding=1)
+        self.bn = torch.nn.BatchNorm1d(64)
+        self.out = torch.nn.Linear(64, 96)
+
+    def forward(self, x):
+        h, _ = self.rnn(self.emb(x))
+        h = self.bn(self.conv(self.drop(h).transpose(1, 2))).transpose(1, 2)
+        return self.out(h)
+
+
+@pytest.mark.parametrize("kind", ["lstm", "gru"])
+def test_the_dry_run_leaves_buffers_and_random_number_generators_as_they_were(kind):
+    # the resident model trains first, from a seeded generator; then the generator is seeded again, the
+    # other model is profiled (a whole forward and backward: batch-norm statistics move, dropout draws)
+    # and trained through the cache: same parameters, same running statistics, same dropout masks
+    lr = 0.05
+    x = torch.randint(0, 96, (4, 16), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    y = torch.randint(0, 96, (64,), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(2))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        loss_fn(m(x).reshape(-1, 96), y).backward()
+
+    def make():
+        torch.manual_seed(3)
+        return _Stateful(kind).to("cuda:0")
+
+    ref = make()
+    torch.manual_seed(11)
+    for _ in range(3):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+    model = make()
+    total = sum(p.numel() * p.element_size() for p in model.parameters())
+    torch.manual_seed(11)
+    pc = ParamCache(model, hbm_bytes=int(total * 0.95))
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    for _ in range(3):
+        iteration(model)
+        pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    pc.close()
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a, b.detach().cpu())
+    for (name, a), (_, b) in zip(model.named_buffers(), ref.named_buffers()):
+        assert torch.equal(a, b), name
+
+
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
