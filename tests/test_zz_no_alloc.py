@@ -95,3 +95,41 @@ def test_pack_static_refuses_a_slab_beyond_its_array_and_launches_nothing():
     # only the argument check is exercised here): an empty batch of that size is a no-op
     T.pack_static(d.data_ptr(), one.data_ptr(), nb.data_ptr(), off.data_ptr(), 0, T.PACK_STATIC_MAX_BYTES, False, st)
     torch.cuda.synchronize()
+
+
+def test_pack_static_inside_a_captured_graph_replays_like_the_eager_call():
+    # the callers it is for: after one eager call (the library asks for its array's address once per
+    # device) a pack and an unpack are captured into a graph; three replays, with eager work and
+    # synchronisation between them and new bytes in the tensors each time, against the plain definition
+    nb, src_off, slab_off, slab_total, src = _case(seed=19, n=300, aligned=False)
+    n = len(nb)
+    st = torch.cuda.Stream()
+    d_src = _dev(src)
+    d_nb, d_off = _dev(nb.astype(np.int64)), _dev(slab_off.astype(np.int64))
+    ptrs = _dev((src_off + np.uint64(d_src.data_ptr())).astype(np.int64))
+    slab = torch.zeros(slab_total, dtype=torch.uint8, device="cuda:0")
+    back = torch.zeros(src.size, dtype=torch.uint8, device="cuda:0")
+    ptrs_back = _dev((src_off + np.uint64(back.data_ptr())).astype(np.int64))
+    torch.cuda.synchronize()
+    T.pack_static(slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), n, slab_total, False, st.cuda_stream)
+    st.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            T.pack_static(slab.data_ptr(), ptrs.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), n, slab_total, False,
+                          st.cuda_stream)
+            T.pack_static(slab.data_ptr(), ptrs_back.data_ptr(), d_nb.data_ptr(), d_off.data_ptr(), n, slab_total, True,
+                          st.cuda_stream)
+    for replay in range(3):
+        d_src.random_(0, 255)                               # eager work between the replays
+        slab.zero_()
+        back.fill_(0x55)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        now = d_src.cpu().numpy()
+        tensors = [now[int(o):int(o) + int(k)] for o, k in zip(src_off, nb)]
+        assert np.array_equal(slab.cpu().numpy(), po.pack(tensors, slab_off, np.zeros(slab_total, dtype=np.uint8))), replay
+        got = back.cpu().numpy()
+        for o, k in zip(src_off, nb):
+            assert np.array_equal(got[int(o):int(o) + int(k)], now[int(o):int(o) + int(k)]), replay
