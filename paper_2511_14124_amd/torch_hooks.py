@@ -380,7 +380,11 @@ class ParamCache:
         if self._bwd_step or self._use_step:
             raise RuntimeError("a module's backward did not finish during the dry run")
         ran = {id(m) for m in self.mods if self._ran.get(id(m))}
-        idle = [type(m).__name__ for m in self.mods if id(m) not in ran]
+        # (a module that never runs but shares every parameter with modules that do, like a container's
+        # handle on a tied embedding, needs no step of its own)
+        covered = {id(p) for m in self.mods if id(m) in ran for p in m.parameters(recurse=False)}
+        idle = [type(m).__name__ for m in self.mods
+                if id(m) not in ran and any(id(p) not in covered for p in m.parameters(recurse=False))]
         if idle:
             raise ValueError("modules whose forward never ran in the dry run own parameters: " + ", ".join(sorted(set(idle))) +
                              " (if their parameters are used by another module's forward, name them in resident_modules)")

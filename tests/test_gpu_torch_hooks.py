@@ -498,10 +498,10 @@ def test_the_dry_run_leaves_buffers_and_random_number_generators_as_they_were(ki
         assert torch.equal(a, b), name
 
 
-@pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied"])
+@pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied", "bert", "t5"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
-    # Not a model written for this cache: the GPT-2 and Llama classes of the transformers package at a
-    # small size with random weights (nothing is downloaded).  GPT-2 ties its head to the token table,
+    # Not models written for this cache: the GPT-2, Llama, BERT and T5 classes of the transformers package at
+    # a small size with random weights (nothing is downloaded).  GPT-2 ties its head to the token table,
     # Llama has grouped-query attention, a rotary module without parameters and RMS norms; three
     # steps through a cache of 35 % of the parameters leave the bytes of resident training.
     tf = pytest.importorskip("transformers")
@@ -510,6 +510,15 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
                             embd_pdrop=0.0, attn_pdrop=0.0, bos_token_id=0, eos_token_id=0,
                             attn_implementation="eager")
         cls = tf.GPT2LMHeadModel
+    elif family == "bert":                                 # an encoder; decoder weight tied to the token table, a bias of its own
+        cfg = tf.BertConfig(vocab_size=512, hidden_size=128, num_hidden_layers=2, num_attention_heads=4,
+                            intermediate_size=256, max_position_embeddings=64, hidden_dropout_prob=0.0,
+                            attention_probs_dropout_prob=0.0, attn_implementation="eager")
+        cls = tf.BertForMaskedLM
+    elif family == "t5":                                   # encoder and decoder with cross-attention; one table used by both and by the head
+        cfg = tf.T5Config(vocab_size=512, d_model=128, d_kv=32, d_ff=256, num_layers=2, num_heads=4, dropout_rate=0.0,
+                          decoder_start_token_id=0)
+        cls = tf.T5ForConditionalGeneration
     else:
         cfg = tf.LlamaConfig(vocab_size=512, hidden_size=128, intermediate_size=256, num_hidden_layers=4,
                              num_attention_heads=4, num_key_value_heads=2, max_position_embeddings=64,
@@ -521,7 +530,7 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
         torch.manual_seed(3)
         return cls(cfg).to(device="cuda:0", dtype=torch.bfloat16)
 
-    x = torch.randint(0, 512, (2, 32), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(5))
+    x = torch.randint(1, 512, (2, 32), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(5))
 
     def iteration(m):
         m(input_ids=x, labels=x).loss.backward()
@@ -547,7 +556,7 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
     st = pc.tc.cache_stats()
     pc.close(restore=True)
     with torch.no_grad():                                  # the model works without the cache again
-        assert torch.equal(model(input_ids=x).logits, ref(input_ids=x).logits)
+        assert torch.equal(model(input_ids=x, labels=x).logits, ref(input_ids=x, labels=x).logits)
     assert len(got) == len(list(ref.parameters()))
     for a, b in zip(got, ref.parameters()):
         assert torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
