@@ -22,6 +22,10 @@ With `ParamCache(..., fused_sgd_lr=lr)` the update of a module's parameters is
 applied in its backward post-hook instead, while they are still in their cache
 buffers: no third pass, a third less traffic; `sgd_step` is then not called.
 
+With `ParamCache(..., host_bytes=..., file_path=...)` what neither the HBM cache nor that much pinned
+host memory hold lives in a file (the paper's CPU-GPU-NVMe set-up, Sec. 3.4.2): fetched through a
+pinned staging ring by the library's reader threads, spilled and written back by its writer threads.
+
 With `ParamCache(..., manage_grads=True)` the gradients are tensors of the cache
 too (Sec. 3.2.1's hooks cover every tensor a layer touches; Sec. 2.1 counts the
 16-bit gradients beside the parameters): a module's backward step names its
@@ -85,7 +89,8 @@ class _ParamRef:
 class ParamCache:
     def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
                  fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None,
-                 manage_grads: bool = False, resident_modules=()):
+                 manage_grads: bool = False, resident_modules=(), file_path: Optional[str] = None,
+                 stripes: int = 1):
         import torch
         self.torch = torch
         self.model = model
@@ -96,6 +101,9 @@ class ParamCache:
         if manage_grads and fused_sgd_lr is not None:
             raise ValueError("with the update in the backward hooks no gradient outlives its module: nothing to manage")
         self.manage_grads = manage_grads                  # gradients are tensors of the cache too (ids n_params + t)
+        # a file for what neither the HBM cache nor `host_bytes` of pinned memory hold (the paper's
+        # CPU-GPU-NVMe set-up, Sec. 3.4.2), optionally striped over file_path, file_path.1, ...
+        self.file_path, self.stripes = file_path, int(stripes)
         # parameters of at least this many bytes travel as DMA-engine copies instead of through the
         # zero-copy kernel: slower on the link, but compute running beside them is hardly slowed
         self.dma_threshold = dma_threshold
@@ -418,7 +426,11 @@ class ParamCache:
         host = self.host_bytes if self.host_bytes is not None else sum((n + 255) // 256 * 256 for n in self._nbytes) + 4096
         tc.plan_pools(self.hbm_bytes, (host, 0), self.align)
         tc.plan_schedule()
-        tc.bind_torch()
+        if self.file_path is not None:
+            largest = (max(self._nbytes) + 4095) // 4096 * 4096
+            tc.bind_torch(file_path=self.file_path, staging_bytes=8 * largest, stripes=self.stripes)
+        else:
+            tc.bind_torch()
         tc.tune_mover()                                   # the regions are still empty: measure the workgroup count
         if self.dma_threshold:
             tc.set_dma_threshold(int(self.dma_threshold))

@@ -104,6 +104,9 @@ def main(argv=None):
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
     ap.add_argument("--hf", choices=["gpt2", "llama"], default=None,
                     help="train the transformers package's GPT-2 or Llama class at this size instead of the built-in model")
+    ap.add_argument("--file", default=None,
+                    help="a file for what neither the HBM cache nor --host of pinned memory hold (three tiers)")
+    ap.add_argument("--host", type=float, default=0.3, help="with --file: pinned host memory as a fraction of the managed bytes")
     ap.add_argument("--gpu-deps", action="store_true",
                     help="modules and migration launches wait for each other on the GPU (tc_set_gpu_dependencies)")
     ap.add_argument("--manage-grads", action="store_true",
@@ -169,7 +172,8 @@ def main(argv=None):
     model = build()
     managed_bytes = param_bytes * (2 if args.manage_grads else 1)
     pc = ParamCache(model, hbm_bytes=int(managed_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None,
-                    dma_threshold=(args.dma_kib << 10) or None, manage_grads=args.manage_grads)
+                    dma_threshold=(args.dma_kib << 10) or None, manage_grads=args.manage_grads,
+                    host_bytes=int(managed_bytes * args.host) if args.file else None, file_path=args.file)
     pc.profile(lambda: iteration(model))
     pc.install()
     pc.tc.set_oplog(False, True)
@@ -212,7 +216,9 @@ def main(argv=None):
                           "h2d_GBps_over_the_step": (s1["bytes_h2d"] - s0["bytes_h2d"]) / n_counted / t_off / 1e9,
                           "hook_calls_per_step": 4 * len(pc.mods) + (0 if args.fused_sgd else 2 * len(pc.params)),
                           "update": "in the backward hooks" if args.fused_sgd else "a sweep over the parameters",
-                          "dma_copies_from_KiB": (kept >> 10) if kept else None, "chosen_by_timing": bool(args.dma_auto)},
+                          "dma_copies_from_KiB": (kept >> 10) if kept else None, "chosen_by_timing": bool(args.dma_auto),
+                          "file_read_GiB_per_step": (s1["bytes_file_read"] - s0["bytes_file_read"]) / n_counted / 2**30,
+                          "file_write_GiB_per_step": (s1["bytes_file_write"] - s0["bytes_file_write"]) / n_counted / 2**30},
         "final_parameters_equal_resident_training": bool(same),
         "managed": "parameters and gradients" if args.manage_grads else "parameters",
         "note": ("parameters and their gradients are managed (activations stay resident)" if args.manage_grads else

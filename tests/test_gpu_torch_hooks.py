@@ -10,6 +10,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
+import paper_2511_14124_amd as T                          # noqa: E402
 from paper_2511_14124_amd.torch_hooks import ParamCache   # noqa: E402
 from oracle import tc_oracle as o                         # noqa: E402
 
@@ -496,6 +497,49 @@ def test_the_dry_run_leaves_buffers_and_random_number_generators_as_they_were(ki
         assert torch.equal(a, b.detach().cpu())
     for (name, a), (_, b) in zip(model.named_buffers(), ref.named_buffers()):
         assert torch.equal(a, b), name
+
+
+@pytest.mark.parametrize("mode", ["sweep", "fused", "grads"])
+def test_training_with_parameters_in_hbm_host_memory_and_a_file(mode, tmp_path):
+    # the paper's CPU-GPU-NVMe set-up driven by the hooks: 30 % of the managed bytes in the HBM cache,
+    # 30 % in pinned host memory, the rest in a file striped over three files
+    from paper_2511_14124_amd.train_demo import build_model
+    vocab, lr = 512, 0.05
+    x = torch.randint(0, vocab, (2, 64), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        loss_fn(m(x).float().view(-1, vocab), x.view(-1)).backward()
+
+    def make():
+        torch.manual_seed(3)
+        return build_model(torch, 128, 4, 4, vocab, torch.bfloat16)
+
+    kw = {"fused": dict(fused_sgd_lr=lr), "grads": dict(manage_grads=True), "sweep": {}}[mode]
+    ref, model = make(), make()
+    managed = sum(p.numel() * p.element_size() for p in model.parameters()) * (2 if mode == "grads" else 1)
+    pc = ParamCache(model, hbm_bytes=int(managed * 0.3), host_bytes=int(managed * 0.3),
+                    file_path=str(tmp_path / "tier.bin"), stripes=3, **kw)
+    pc.profile(lambda: iteration(model))
+    pc.install()
+    assert (pc.tc.placement["final_tier"] == T.NVME).sum() > 0
+    for _ in range(3):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p in ref.parameters():
+                p.add_(p.grad, alpha=-lr)
+        iteration(model)
+        if mode != "fused":
+            pc.sgd_step(lr)
+        pc.end_iteration()
+    got = pc.gather()
+    st = pc.tc.cache_stats()
+    pc.close()
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a.view(torch.int16), b.detach().cpu().view(torch.int16))
+    assert st["misses"] == 0 and st["bytes_file_read"] > 0 and st["bytes_file_write"] > 0
 
 
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied", "bert", "t5", "mixtral", "vit"])
