@@ -35,6 +35,11 @@ step for a parameter names the gradient (read) and the parameter (read and
 written).  Outside those steps a gradient lives wherever the scheduler put it,
 and `p.grad` is None.
 
+With `ParamCache(..., state_tensors=2)` every managed parameter has that many fp32 optimizer-state
+tensors of its shape in the cache as well (the north star's "parameter, gradient and optimizer
+tensors"): the parameter's step of the update sweep names them read and written, `update_sweep`
+hands them to the update, and `adam_step` is Adam over them (first and second moment).
+
 A parameter shared by two modules (tied weights) and a module that runs twice in
 a pass are handled in the parameters-only mode: such a use's backward step is
 closed when the gradients of its own inputs arrive, not when its parameters'
@@ -90,7 +95,7 @@ class ParamCache:
     def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
                  fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None,
                  manage_grads: bool = False, resident_modules=(), file_path: Optional[str] = None,
-                 stripes: int = 1):
+                 stripes: int = 1, state_tensors: int = 0):
         import torch
         self.torch = torch
         self.model = model
@@ -104,6 +109,11 @@ class ParamCache:
         # a file for what neither the HBM cache nor `host_bytes` of pinned memory hold (the paper's
         # CPU-GPU-NVMe set-up, Sec. 3.4.2), optionally striped over file_path, file_path.1, ...
         self.file_path, self.stripes = file_path, int(stripes)
+        # optimizer states through the same cache: per managed parameter this many fp32 tensors of its
+        # shape, zero at first, named (read and written) by the parameter's step of the update sweep
+        self.state_tensors = int(state_tensors)
+        if self.state_tensors and fused_sgd_lr is not None:
+            raise ValueError("optimizer states are tensors of the update sweep; with the update in the backward hooks there is none")
         # parameters of at least this many bytes travel as DMA-engine copies instead of through the
         # zero-copy kernel: slower on the link, but compute running beside them is hardly slowed
         self.dma_threshold = dma_threshold
@@ -151,8 +161,6 @@ class ParamCache:
         self._flag_arrays: Dict[Tuple[int, int], np.ndarray] = {}
         self._views: Dict[Tuple[int, int], object] = {}   # (parameter, buffer address) -> view into the HBM region
         self._hbm_base = 0
-        self._one_id = [np.asarray([t], dtype=np.uint32) for t in range(len(self.params))]
-        self._pair_id = [np.asarray([len(self.params) + t, t], dtype=np.uint32) for t in range(len(self.params))]
         self.steps: List[List[Tuple[int, int]]] = []      # the profiled iteration
         self.tc: Optional[T.TensorCache] = None
         self._handles: list = []
@@ -239,8 +247,10 @@ class ParamCache:
                 view = self._views[(t, ptr)] = self.tc.hbm[off: off + n].view(self._dtype[t]).view(self._shape[t])
             if t < len(self.params):
                 self.params[t].data = view
-            else:
+            elif t < self._state_base:
                 self._grad_view[t - len(self.params)] = view
+            else:
+                self._state_view[t] = view
 
     def _pack_saved(self, x):
         """A tensor the running forward saves for the backward pass: if it aliases one of
@@ -401,8 +411,10 @@ class ParamCache:
         # the optimizer sweep: every parameter once, read and written
         if self.fused_sgd_lr is None:
             n_p = len(self.params)
+            base = n_p * (2 if self.manage_grads else 1)
             for t in range(n_p):
-                self.steps.append([(n_p + t, R), (t, RW)] if self.manage_grads else [(t, RW)])
+                step = [(n_p + t, R), (t, RW)] if self.manage_grads else [(t, RW)]
+                self.steps.append(step + [(base + j * n_p + t, RW) for j in range(self.state_tensors)])
         for p in self.params + self.resident:             # what the dry run left behind is no gradient of a step
             p.grad = None
 
@@ -413,6 +425,19 @@ class ParamCache:
         self._nbytes = [p.numel() * p.element_size() for p in self.params] * rep
         self._dtype = [p.dtype for p in self.params] * rep
         self._shape = [tuple(p.shape) for p in self.params] * rep
+        self._state_base = len(self._nbytes)              # optimizer states: fp32, ids behind those
+        for _ in range(self.state_tensors):
+            self._nbytes += [p.numel() * 4 for p in self.params]
+            self._dtype += [torch.float32] * len(self.params)
+            self._shape += [tuple(p.shape) for p in self.params]
+        n_p = len(self.params)
+        self._sweep = []                                  # per parameter: the ids and flags of its sweep step
+        for t in range(n_p):
+            ids = ([n_p + t] if self.manage_grads else []) + [t] + \
+                  [self._state_base + j * n_p + t for j in range(self.state_tensors)]
+            flags = ([R] if self.manage_grads else []) + [RW] * (1 + self.state_tensors)
+            self._sweep.append((tuple(ids), np.asarray(ids, dtype=np.uint32), np.asarray(flags, dtype=np.uint8)))
+        self._state_view: Dict[int, object] = {}          # state tensor id -> its cache buffer, during a step that names it
         if min(self._nbytes) < 16:
             raise ValueError("parameters smaller than 16 bytes are not supported")
         st, te, rw = [], [], []
@@ -450,7 +475,8 @@ class ParamCache:
     def update_sweep(self, update: Callable[[int, object], None]):
         """The optimizer sweep through the cache: each parameter in turn is fetched (read +
         write), `update(t, p)` changes `p.data` in its cache buffer (p.grad holds the
-        gradient), and the parameter is left to the scheduler."""
+        gradient), and the parameter is left to the scheduler.  With state_tensors the call is
+        `update(t, p, states)`, states being the parameter's fp32 state tensors in their cache buffers."""
         torch = self.torch
         if self.fused_sgd_lr is not None:
             raise RuntimeError("the update is applied in the backward hooks (fused_sgd_lr): there is no sweep")
@@ -458,23 +484,20 @@ class ParamCache:
         k = self._n_model_steps
         n_p = len(self.params)
         with torch.no_grad():
-            rw = self._flags(1, RW)
-            g_rw = np.asarray([R, RW], dtype=np.uint8)
             for t, p in enumerate(self.params):
+                ids, ids_np, rw = self._sweep[t]
+                self._fetch(k, ids, ids_np, rw)
+                states = [self._state_view.pop(self._state_base + j * n_p + t) for j in range(self.state_tensors)]
                 if self.manage_grads:
-                    ids = (n_p + t, t)
-                    ids_np = self._pair_id[t]
-                    self._fetch(k, ids, ids_np, g_rw)
                     p.grad = self._grad_view.pop(t)        # the gradient, in its cache buffer, for this step only
-                    update(t, p)
-                    p.grad = None
-                    self.tc.migrate_step(k, T.POST, ids_np, g_rw, stream)
-                else:
-                    one = self._one_id[t]
-                    self._fetch(k, (t,), one, rw)
-                    if p.grad is not None:
+                if p.grad is not None:
+                    if self.state_tensors:
+                        update(t, p, states)
+                    else:
                         update(t, p)
-                    self.tc.migrate_step(k, T.POST, one, rw, stream)
+                if self.manage_grads:
+                    p.grad = None
+                self.tc.migrate_step(k, T.POST, ids_np, rw, stream)
                 k += 1
 
     def autotune_dma(self, step: Callable[[], None], threshold: int = 64 << 10, steps: int = 2) -> Optional[int]:
@@ -503,11 +526,36 @@ class ParamCache:
 
     def sgd_step(self, lr: float):
         """Plain SGD: the managed parameters through the cache, the resident ones where they are."""
-        self.update_sweep(lambda t, p: p.data.add_(p.grad, alpha=-lr))
+        self.update_sweep(lambda t, p, *_: p.data.add_(p.grad, alpha=-lr))
         with self.torch.no_grad():
             for p in self.resident:
                 if p.grad is not None:
                     p.add_(p.grad, alpha=-lr)
+
+    @staticmethod
+    def adam_update(p, grad, m, v, step: int, lr: float, beta1: float, beta2: float, eps: float):
+        """One Adam update of p (any float dtype) from grad, over fp32 moments m and v, in place."""
+        g = grad.float()
+        m.mul_(beta1).add_(g, alpha=1.0 - beta1)
+        v.mul_(beta2).addcmul_(g, g, value=1.0 - beta2)
+        denom = (v / (1.0 - beta2 ** step)).sqrt_().add_(eps)
+        p.add_((m / (1.0 - beta1 ** step)).div_(denom).mul_(-lr).to(p.dtype))
+
+    def adam_step(self, lr: float, betas=(0.9, 0.999), eps: float = 1e-8):
+        """Adam with its two moments as tensors of the cache (needs state_tensors >= 2); the resident
+        parameters keep theirs as ordinary tensors."""
+        if self.state_tensors < 2:
+            raise RuntimeError("adam_step needs ParamCache(state_tensors=2)")
+        self._adam_step = getattr(self, "_adam_step", 0) + 1
+        k = self._adam_step
+        self.update_sweep(lambda t, p, st: self.adam_update(p.data, p.grad, st[0], st[1], k, lr, betas[0], betas[1], eps))
+        with self.torch.no_grad():
+            if not hasattr(self, "_resident_moments"):
+                self._resident_moments = [(self.torch.zeros_like(p, dtype=self.torch.float32),
+                                           self.torch.zeros_like(p, dtype=self.torch.float32)) for p in self.resident]
+            for p, (m, v) in zip(self.resident, self._resident_moments):
+                if p.grad is not None:
+                    self.adam_update(p, p.grad, m, v, k, lr, betas[0], betas[1], eps)
 
     def end_iteration(self):
         self.tc.end_iteration(self.torch.cuda.current_stream().cuda_stream)
@@ -548,6 +596,13 @@ class ParamCache:
             raise RuntimeError("gradients are not tensors of this cache")
         return [torch.from_numpy(self.tc.read_tensor(n_p + t)).view(self._dtype[t]).view(self._shape[t])
                 for t in range(n_p)]
+
+    def gather_states(self) -> list:
+        """Every optimizer-state tensor as the cache holds it now: one list per state, in the order of
+        the managed parameters (CPU tensors)."""
+        torch, n_p = self.torch, len(self.params)
+        return [[torch.from_numpy(self.tc.read_tensor(self._state_base + j * n_p + t)).view(torch.float32).view(self._shape[t])
+                 for t in range(n_p)] for j in range(self.state_tensors)]
 
     def close(self, restore: bool = False):
         """Hooks off, the cache's memory released.  restore: first give every managed parameter its

@@ -104,6 +104,9 @@ def main(argv=None):
                     help="apply the update in the backward hooks, while the parameters are still in the cache")
     ap.add_argument("--hf", choices=["gpt2", "llama"], default=None,
                     help="train the transformers package's GPT-2 or Llama class at this size instead of the built-in model")
+    ap.add_argument("--adam", action="store_true",
+                    help="Adam on the GPU with its two fp32 moments as tensors of the cache too "
+                         "(--cache is then a fraction of parameters + moments)")
     ap.add_argument("--file", default=None,
                     help="a file for what neither the HBM cache nor --host of pinned memory hold (three tiers)")
     ap.add_argument("--host", type=float, default=0.3, help="with --file: pinned host memory as a fraction of the managed bytes")
@@ -152,11 +155,23 @@ def main(argv=None):
     n_params = sum(p.numel() for p in model.parameters())
     param_bytes = sum(p.numel() * p.element_size() for p in model.parameters())
 
+    moments = None
+    res_k = 0
+
     def resident_step():
+        nonlocal moments, res_k
         for p in model.parameters():
             p.grad = None
         iteration(model)
         with torch.no_grad():
+            if args.adam:
+                if moments is None:
+                    moments = [(torch.zeros_like(p, dtype=torch.float32), torch.zeros_like(p, dtype=torch.float32))
+                               for p in model.parameters()]
+                res_k += 1
+                for p, (m, v) in zip(model.parameters(), moments):
+                    ParamCache.adam_update(p, p.grad, m, v, res_k, args.lr, 0.9, 0.999, 1e-8)
+                return
             for p in model.parameters():
                 p.add_(p.grad, alpha=-args.lr)
 
@@ -165,15 +180,17 @@ def main(argv=None):
     t_res = timed(resident_step)
     want = [p.detach().cpu().clone() for p in model.parameters()]
     del model
+    moments = None
     torch.cuda.empty_cache()
 
     # ---- parameters in the tensor cache
     torch.manual_seed(0)
     model = build()
-    managed_bytes = param_bytes * (2 if args.manage_grads else 1)
+    managed_bytes = param_bytes * (2 if args.manage_grads else 1) + (8 * n_params if args.adam else 0)
     pc = ParamCache(model, hbm_bytes=int(managed_bytes * args.cache), fused_sgd_lr=args.lr if args.fused_sgd else None,
                     dma_threshold=(args.dma_kib << 10) or None, manage_grads=args.manage_grads,
-                    host_bytes=int(managed_bytes * args.host) if args.file else None, file_path=args.file)
+                    host_bytes=int(managed_bytes * args.host) if args.file else None, file_path=args.file,
+                    state_tensors=2 if args.adam else 0)
     pc.profile(lambda: iteration(model))
     pc.install()
     pc.tc.set_oplog(False, True)
@@ -182,7 +199,9 @@ def main(argv=None):
 
     def cached_step():
         iteration(model)
-        if not args.fused_sgd:
+        if args.adam:
+            pc.adam_step(args.lr)
+        elif not args.fused_sgd:
             pc.sgd_step(args.lr)
         pc.end_iteration()
 
@@ -220,10 +239,10 @@ def main(argv=None):
                           "file_read_GiB_per_step": (s1["bytes_file_read"] - s0["bytes_file_read"]) / n_counted / 2**30,
                           "file_write_GiB_per_step": (s1["bytes_file_write"] - s0["bytes_file_write"]) / n_counted / 2**30},
         "final_parameters_equal_resident_training": bool(same),
-        "managed": "parameters and gradients" if args.manage_grads else "parameters",
+        "managed": ("parameters and gradients" if args.manage_grads else "parameters") + (" and Adam's moments" if args.adam else ""),
         "note": ("parameters and their gradients are managed (activations stay resident)" if args.manage_grads else
-                 "parameters only are managed (gradients and activations stay resident)") +
-                "; plain SGD; hooks drive tc_migrate_step one call at a time",
+                 "of parameters and gradients only the parameters are managed (activations stay resident)") +
+                ("; Adam" if args.adam else "; plain SGD") + "; hooks drive tc_migrate_step one call at a time",
     }
     pc.close()
     print(json.dumps(out))

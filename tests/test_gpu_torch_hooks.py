@@ -542,6 +542,61 @@ def test_training_with_parameters_in_hbm_host_memory_and_a_file(mode, tmp_path):
     assert st["misses"] == 0 and st["bytes_file_read"] > 0 and st["bytes_file_write"] > 0
 
 
+@pytest.mark.parametrize("grads", [False, True], ids=["parameters_and_moments", "parameters_gradients_and_moments"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_adam_with_its_moments_in_the_cache_equals_resident_adam(dtype, grads):
+    # parameter, gradient and optimizer tensors all through one HBM cache of 30 % of their bytes: the fp32
+    # first and second moments are tensors of the cache, named by each parameter's step of the update
+    # sweep; parameters and moments after three steps are those of Adam with everything resident (the
+    # reference spells the update out op by op)
+    from paper_2511_14124_amd.train_demo import build_model
+    vocab, lr, b1, b2, eps = 512, 1e-3, 0.9, 0.999, 1e-8
+    dt = {"bf16": torch.bfloat16, "fp32": torch.float32}[dtype]
+    x = torch.randint(0, vocab, (2, 64), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    loss_fn = torch.nn.CrossEntropyLoss()
+
+    def iteration(m):
+        loss_fn(m(x).float().view(-1, vocab), x.view(-1)).backward()
+
+    def make():
+        torch.manual_seed(3)
+        return build_model(torch, 128, 4, 4, vocab, dt)
+
+    ref, model = make(), make()
+    ms = [torch.zeros_like(p, dtype=torch.float32) for p in ref.parameters()]
+    vs = [torch.zeros_like(p, dtype=torch.float32) for p in ref.parameters()]
+    managed = sum(p.numel() * (p.element_size() * (2 if grads else 1) + 8) for p in model.parameters())
+    pc = ParamCache(model, hbm_bytes=int(managed * 0.3), state_tensors=2, manage_grads=grads)
+    pc.profile(lambda: iteration(model))
+    n_p = len(pc.params)
+    assert len(pc.steps[-1]) == (4 if grads else 3) and len(pc.steps) == pc._n_model_steps + n_p
+    pc.install()
+    for k in range(1, 4):
+        for p in ref.parameters():
+            p.grad = None
+        iteration(ref)
+        with torch.no_grad():
+            for p, m, v in zip(ref.parameters(), ms, vs):
+                g = p.grad.float()
+                m.mul_(b1).add_(g, alpha=1.0 - b1)
+                v.mul_(b2).addcmul_(g, g, value=1.0 - b2)
+                denom = (v / (1.0 - b2 ** k)).sqrt_().add_(eps)
+                p.add_((m / (1.0 - b1 ** k)).div_(denom).mul_(-lr).to(p.dtype))
+        iteration(model)
+        pc.adam_step(lr, (b1, b2), eps)
+        pc.end_iteration()
+    got, states, st = pc.gather(), pc.gather_states(), pc.tc.cache_stats()
+    pc.close()
+    for a, b in zip(got, ref.parameters()):
+        assert torch.equal(a.view(torch.uint8), b.detach().cpu().view(torch.uint8))
+    for have, want in ((states[0], ms), (states[1], vs)):
+        for a, b in zip(have, want):
+            assert torch.equal(a, b.cpu())
+    assert st["misses"] == 0 and st["bytes_h2d"] > managed
+    with pytest.raises(ValueError):
+        ParamCache(make(), hbm_bytes=managed, state_tensors=2, fused_sgd_lr=lr)
+
+
 @pytest.mark.parametrize("family", ["gpt2", "llama", "llama_tied", "bert", "t5", "mixtral", "vit"])
 def test_models_defined_by_a_model_library_train_like_the_resident_models(family):
     # Not models written for this cache: the GPT-2, Llama, BERT and T5 classes of the transformers package at
