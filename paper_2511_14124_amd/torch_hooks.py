@@ -95,7 +95,7 @@ class ParamCache:
     def __init__(self, model, hbm_bytes: int, host_bytes: Optional[int] = None, align: int = 256,
                  fused_sgd_lr: Optional[float] = None, dma_threshold: Optional[int] = None,
                  manage_grads: bool = False, resident_modules=(), file_path: Optional[str] = None,
-                 stripes: int = 1, state_tensors: int = 0):
+                 stripes: int = 1, state_tensors: int = 0, keep_oplog: bool = False):
         import torch
         self.torch = torch
         self.model = model
@@ -111,6 +111,7 @@ class ParamCache:
         self.file_path, self.stripes = file_path, int(stripes)
         # optimizer states through the same cache: per managed parameter this many fp32 tensors of its
         # shape, zero at first, named (read and written) by the parameter's step of the update sweep
+        self.keep_oplog = keep_oplog                      # the library's op log: 32 bytes per decision, for ever (for tests)
         self.state_tensors = int(state_tensors)
         if self.state_tensors and fused_sgd_lr is not None:
             raise ValueError("optimizer states are tensors of the update sweep; with the update in the backward hooks there is none")
@@ -465,6 +466,7 @@ class ParamCache:
             p.data = torch.empty(0, dtype=self._dtype[t], device=p.device)
         for t in range(len(self.params), len(self._nbytes)):
             tc.load_tensor(t, np.zeros(self._nbytes[t], dtype=np.uint8))
+        tc.set_oplog(self.keep_oplog, True)               # a training run of a million steps must not keep every decision
         self.tc = tc
         self._hbm_base = tc.hbm.data_ptr()
         self._views = {}

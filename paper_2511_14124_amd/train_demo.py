@@ -193,7 +193,6 @@ def main(argv=None):
                     state_tensors=2 if args.adam else 0)
     pc.profile(lambda: iteration(model))
     pc.install()
-    pc.tc.set_oplog(False, True)
     if args.gpu_deps:
         pc.tc.set_gpu_dependencies(True)
 

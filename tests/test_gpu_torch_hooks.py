@@ -50,7 +50,7 @@ def test_training_through_the_cache_equals_resident_training(mode):
     model = _model(7)
     total = sum(p.numel() * p.element_size() for p in model.parameters())
     budget = int(total * (0.8 if grads else 0.4))          # 40 % of the bytes the cache manages
-    pc = ParamCache(model, hbm_bytes=budget, fused_sgd_lr=lr if fused else None, manage_grads=grads)
+    pc = ParamCache(model, hbm_bytes=budget, fused_sgd_lr=lr if fused else None, manage_grads=grads, keep_oplog=True)
     pc.profile(lambda: loss_fn(model(xs[-1]), ys[-1]).backward())
     n_mod = len(pc.mods)
     assert len(pc.steps) == 2 * n_mod + (0 if fused else len(pc.params))   # forward, backward, one sweep
@@ -152,7 +152,7 @@ def test_tied_weights_and_a_block_used_twice_train_like_the_resident_model():
     model = make()
     assert model.head.weight is model.emb.weight
     total = sum(p.numel() * p.element_size() for p in model.parameters())
-    pc = ParamCache(model, hbm_bytes=int(total * 0.75))
+    pc = ParamCache(model, hbm_bytes=int(total * 0.75), keep_oplog=True)
     assert len(pc.params) == len(list(model.parameters()))          # the shared parameter is one tensor of the cache
     pc.profile(lambda: loss_fn(model(toks[-1]).view(-1, 96), tgts[-1]).backward())
     n_p = len(pc.params)
