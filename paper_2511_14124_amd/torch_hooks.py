@@ -109,9 +109,9 @@ class ParamCache:
         # a file for what neither the HBM cache nor `host_bytes` of pinned memory hold (the paper's
         # CPU-GPU-NVMe set-up, Sec. 3.4.2), optionally striped over file_path, file_path.1, ...
         self.file_path, self.stripes = file_path, int(stripes)
+        self.keep_oplog = keep_oplog                      # the library's op log: 32 bytes per decision, for ever (for tests)
         # optimizer states through the same cache: per managed parameter this many fp32 tensors of its
         # shape, zero at first, named (read and written) by the parameter's step of the update sweep
-        self.keep_oplog = keep_oplog                      # the library's op log: 32 bytes per decision, for ever (for tests)
         self.state_tensors = int(state_tensors)
         if self.state_tensors and fused_sgd_lr is not None:
             raise ValueError("optimizer states are tensors of the update sweep; with the update in the backward hooks there is none")
@@ -159,7 +159,6 @@ class ParamCache:
                 both, flags = ids, [R if fused_sgd_lr is None else RW] * len(ids)
             self._step_lists[(k, "bwd")] = (both, np.asarray(both, dtype=np.uint32), np.asarray(flags, dtype=np.uint8))
         self._grad_view: Dict[int, object] = {}           # parameter -> its gradient's cache buffer, during a step that names it
-        self._flag_arrays: Dict[Tuple[int, int], np.ndarray] = {}
         self._views: Dict[Tuple[int, int], object] = {}   # (parameter, buffer address) -> view into the HBM region
         self._hbm_base = 0
         self.steps: List[List[Tuple[int, int]]] = []      # the profiled iteration
@@ -180,11 +179,11 @@ class ParamCache:
         # earlier ones would stay open across other modules' steps.  Such a use is closed instead when
         # the gradients of its own inputs arrive (the kernels that read its parameters are queued by
         # then); a use without an input that needs a gradient (an embedding) falls back to the rule above.
-        owners: Dict[int, list] = {}
+        owned_by: Dict[int, list] = {}
         for m in self.mods:
             for p in m.parameters(recurse=False):
-                owners.setdefault(id(p), []).append(m)
-        self._by_input = {id(m) for ms in owners.values() if len(ms) > 1 for m in ms}
+                owned_by.setdefault(id(p), []).append(m)
+        self._by_input = {id(m) for ms in owned_by.values() if len(ms) > 1 for m in ms}
         self._uses: Dict[int, int] = {}                   # module -> forward calls in the running iteration
         self._next_use = 0
         self._open_use: Dict[int, int] = {}               # module -> the use whose forward is running
@@ -210,13 +209,6 @@ class ParamCache:
         for h in self._handles:
             h.remove()
         self._handles = []
-
-    def _flags(self, n: int, rw: int):
-        """n copies of one R/W flag as the array the binding passes on (made once)."""
-        a = self._flag_arrays.get((n, rw))
-        if a is None:
-            a = self._flag_arrays[(n, rw)] = np.full(n, rw, dtype=np.uint8)
-        return a
 
     def _begin(self, m, kind: str) -> int:
         """Opens the next step for module m (steps are numbered in the order they open)."""
