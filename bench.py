@@ -287,14 +287,8 @@ def run_config(torch, T, W, link, index, layers, args, *, steps, warmup, stall, 
         tc.bind_torch(stripe_paths=paths, staging_bytes=args.staging_depth * big, direct=direct)
         if args.io_chunk_mib:
             tc.set_io_chunk(args.io_chunk_mib << 20)
-        if direct and not args.io_chunk_mib:
-            # a device that is read and written directly wants few large sequential requests on this
-            # box's virtual disk: one request per tensor, two threads per direction (measured: 1 + 1
-            # 6.0, 2 + 2 7.0, 4 + 4 with 64 MiB chunks 6.3, 8 + 8 with 16 MiB chunks 5.4 GB/s host->HBM)
-            tc.set_io_chunk(((big + (1 << 20) - 1) >> 20) << 20)
-            tc.set_io_threads(2, 2)
-        elif args.io_threads:
-            tc.set_io_threads(*args.io_threads)
+        if args.io_threads:                # (a direct file otherwise gets the library's own defaults:
+            tc.set_io_threads(*args.io_threads)    #  one request per tensor, two threads each way)
         file_mode = {"io": "O_DIRECT (page cache bypassed)" if direct else "buffered (through the page cache)",
                      "directories": [{"dir": d, "in_memory": is_tmpfs(d)} for d in tier_dirs],
                      "stripes": args.stripes}

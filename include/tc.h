@@ -250,7 +250,11 @@ int tc_plan_schedule(tc_ctx *ctx, tc_placement *out);
  *                  memory, offset and length and goes through a page-aligned
  *                  bounce block of the library's own (direct I/O cannot
  *                  target GPU-mapped pinned memory); staging must then be
- *                  4 KiB aligned and sized.  File reads and writes are
+ *                  4 KiB aligned and sized.  Unless tc_set_io_threads /
+ *                  tc_set_io_chunk were called before, a direct file is served
+ *                  by two threads per direction with one request per tensor
+ *                  (few large sequential requests suit a device; many small
+ *                  ones suit the page cache).  File reads and writes are
  *                  queued to worker threads of the library's own
  *                  (tc_set_io_threads); writes have reached the file when
  *                  tc_synchronize returns.  A failed request is reported

@@ -178,6 +178,7 @@ struct tc_ctx {
     // file tier behind the hook thread
     int device = 0;
     uint32_t n_io[2] = {4, 4};          // writer and reader threads; 0: that kind of I/O runs in the calling thread
+    bool io_threads_set = false, io_chunk_set = false;   // the caller chose them (else a direct file gets defaults of its own)
     std::vector<std::unique_ptr<IoWorker>> io[2];
     std::vector<hipEvent_t> ev_free;
     std::deque<std::pair<hipEvent_t, JobSet>> ev_busy;  // events the queued jobs of a request wait for

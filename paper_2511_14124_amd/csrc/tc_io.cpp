@@ -302,6 +302,7 @@ extern "C" int tc_set_io_threads(tc_ctx *c, uint32_t writers, uint32_t readers)
     if (writers > IO_MAX_THREADS || readers > IO_MAX_THREADS) return fail(c, TC_E_ARG, "at most 8 writer and 8 reader threads");
     c->n_io[IO_WRITERS] = writers;
     c->n_io[IO_READERS] = readers;
+    c->io_threads_set = true;
     if (c->stage != 4 || c->n_files == 0 || c->null_mover) return TC_OK;
     int rc = tc_synchronize(c);
     if (rc != TC_OK) return rc;
@@ -315,6 +316,7 @@ extern "C" int tc_set_io_chunk(tc_ctx *c, uint64_t bytes)
     if (bytes < 65536 || bytes % 4096) return fail(c, TC_E_ARG, "chunk must be a multiple of 4096, at least 64 KiB");
     if (c->stage == 4 && c->io_begun) return fail(c, TC_E_STATE, "the file tier is already in use");
     c->io_chunk = bytes;
+    c->io_chunk_set = true;
     if (c->stage != 4 || c->n_files == 0 || c->null_mover || !c->file_direct) return TC_OK;
     // O_DIRECT bounce blocks are one chunk each: make them anew
     io_stop(c);

@@ -304,6 +304,12 @@ extern "C" int tc_bind_memory(tc_ctx *c, void *hbm, uint64_t hbm_bytes, void *pi
     if (direct) {
         uint64_t largest = 0;
         for (uint32_t t = 0; t < n_t; ++t) largest = std::max(largest, p.bytes[t]);
+        // A device read and written directly wants few, large, sequential requests (measured on a virtual
+        // disk: one request per tensor and two threads per direction 7.0 GB/s host->HBM, four threads each
+        // with 64 MiB chunks 6.3, eight each with 16 MiB chunks 5.4, four each with 8 MiB chunks 3.4): unless
+        // the caller has chosen, a direct file gets one request per tensor and two threads each way.
+        if (!c->io_chunk_set) c->io_chunk = std::max<uint64_t>(c->io_chunk, (largest + (1ull << 20) - 1) >> 20 << 20);
+        if (!c->io_threads_set) c->n_io[IO_WRITERS] = c->n_io[IO_READERS] = 2;
         c->io_bounce_bytes = std::min<uint64_t>(c->io_chunk, (largest + 4095) & ~4095ull);
         void *blk = nullptr;
         if (posix_memalign(&blk, 4096, c->io_bounce_bytes) != 0) { release_device(c); return fail(c, TC_E_CAPACITY, "no memory for the I/O bounce block"); }
