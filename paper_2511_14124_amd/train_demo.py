@@ -7,8 +7,11 @@ from leaf modules that own their parameters (LayerNorm, Linear, Embedding), so
 that the pre- and post-hooks of the paper's analyzer (Sec. 3.2.1) see every
 parameter; `ParamCache` profiles one iteration, plans the pools for an HBM
 budget of `--cache` times the parameter bytes and then fetches and evicts the
-parameters around every module.  Gradients and activations stay ordinary
-PyTorch tensors.  Prints one JSON line: step time of both runs, tokens/s, what
+parameters around every module.  Activations stay ordinary PyTorch tensors;
+gradients do too unless `--manage-grads` puts them into the cache, and `--adam`
+keeps Adam's two fp32 moments there as well (`--file PATH` adds a file tier
+below pinned host memory, `--hf gpt2|llama` trains the transformers package's
+classes).  Prints one JSON line: step time of both runs, tokens/s, what
 moved per step and the cache's hit rate.
 
 With `--cpu-adam` the update is the paper's whole pipeline in miniature
