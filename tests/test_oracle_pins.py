@@ -106,6 +106,40 @@ def test_plan_literal_vs_floor_and_budget():
         assert lit.gpu_count == [min(p.used[s], p.used[s] * wl.hbm_bytes // total) for s in range(n_c)]
 
 
+def test_the_working_set_floor_is_what_keeps_a_profiled_trace_from_failing_and_more_budget_never_takes_a_buffer():
+    # Why R5 exists, shown on the oracle alone: under a tight budget Alg. 2 as printed leaves classes with
+    # fewer GPU buffers than one step names at once, and a trace that follows its own profile then has
+    # accesses that cannot be given a buffer; with every class first given its per-step maximum no access
+    # of a profiled trace fails (or the plan is refused up front).  And for both variants a larger budget
+    # never gives any class fewer buffers.
+    kw = dict(n_tensors=40, n_steps=30, max_per_step=4, sizes=(512, 4096, 100, 33000), hbm_frac=0.1, host_frac=1.3)
+    literal_failed = 0
+    for seed in range(12):
+        r = o.replay_workload(W.random_workload(seed, literal=True, **kw))
+        literal_failed += r.fails > 0
+        try:
+            r = o.replay_workload(W.random_workload(seed, literal=False, **kw))
+            assert r.fails == 0 and not any(e[3] == o.FAIL for e in r.log)
+        except o.CapacityError:
+            pass
+        wl = W.random_workload(seed, literal=False, **kw)
+        p = _profile_of(wl)
+        total = sum((int(b) + wl.align - 1) // wl.align * wl.align for b in wl.tensor_bytes)
+        for literal in (True, False):
+            before = None
+            for budget in range(0, total + total // 8, max(1, total // 40)):
+                try:
+                    g = o.plan_pools(p, budget, wl.host_bytes, wl.align, literal=literal).gpu_count
+                except o.CapacityError:
+                    assert not literal and before is None      # only below the floor, never again above it
+                    continue
+                if before is not None:
+                    assert all(a <= b for a, b in zip(before, g)), (seed, literal, budget)
+                before = g
+            assert before == [p.used[s] for s in range(len(p.count))]   # with room for everything, everything fits
+    assert literal_failed == 12
+
+
 def test_plan_floor_equals_literal_when_no_step_uses_anything():
     # a profile with tensors but a trace that touches a class at most 0 times -> floor is 0 there
     wl = W.single_class_fwd_bwd(6, 3, 3)
