@@ -39,8 +39,10 @@ nothing on the worked examples and the unperturbed configurations.
 
 Parity unpinned (fixed only by the readings stated here, plus invariants):
 victim tie-breaks, the demand-miss path, which of several valid
-end-of-iteration orders is taken, the dirty rule for file-tier tensors, and
-Alg. 2 with the working-set floor beyond its invariants and one hand example.
+end-of-iteration orders is taken, the dirty rule for file-tier tensors (that
+the log follows the rule is checked from the log and the trace alone; the rule
+is a reading), and Alg. 2 with the working-set floor beyond its invariants, one
+hand example and the reason it exists (no access of a profiled trace fails).
 """
 
 from __future__ import annotations

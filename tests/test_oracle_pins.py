@@ -661,6 +661,53 @@ def test_forgetting_the_dirty_write_back_is_caught(monkeypatch):
 # table, the dictionary and the per-step maxima typed in by hand
 # ----------------------------------------------------------------------------
 
+def test_write_backs_and_releases_follow_the_write_accesses_of_the_trace():
+    # The dirty rule checked from the op log and the trace alone, without the oracle's own marks: a tensor
+    # whose final location is the file leaves its GPU buffer with a WRITEBACK exactly when a write access
+    # named it since it last left (the copy in the file is stale) and with a RELEASE exactly when none did;
+    # a tensor that only visits the file is written every time it goes there and never just released.
+    seen = {"writeback": 0, "release": 0, "visitor": 0}
+    for seed in range(16):
+        wl = W.random_workload(seed, n_tensors=60, n_steps=50, max_per_step=3, sizes=(512, 4096, 33000),
+                               hbm_frac=0.1, host_frac=0.2, n_iterations=3)
+        try:
+            r = o.replay_workload(wl)
+        except o.CapacityError:
+            continue
+        final = r.pl.final
+        written = [False] * wl.n_tensors
+        log, i = r.log, 0
+
+        def take(e):
+            op, t = e[3], e[4]
+            if final[t] != o.NVME:
+                assert op != o.RELEASE, (seed, e)
+                seen["visitor"] += op == o.WRITEBACK
+            elif op == o.WRITEBACK:
+                assert written[t], (seed, e)
+                written[t] = False
+                seen["writeback"] += 1
+            elif op == o.RELEASE:
+                assert not written[t], (seed, e)
+                seen["release"] += 1
+
+        for it, steps in enumerate(wl.iterations):
+            for k, step in enumerate(steps):
+                for phase in (o.PRE, o.POST):
+                    while i < len(log) and log[i][:3] == (it, k, phase):
+                        take(log[i])
+                        i += 1
+                    if phase == o.PRE:                     # the module runs between the two hook calls
+                        for t, rw in step:
+                            if rw & o.W_FLAG:
+                                written[t] = True
+            while i < len(log) and log[i][0] == it:        # end of the iteration
+                take(log[i])
+                i += 1
+        assert i == len(log)
+    assert seen["writeback"] > 500 and seen["release"] > 100 and seen["visitor"] > 10, seen
+
+
 def test_profile_of_a_hand_written_trace_with_a_tensor_named_twice_in_a_step():
     # five tensors: 0, 1 (512 B, 16-bit), 2 and 4 (1024 B, 16-bit; 4 is never used), 3 (512 B, fp32:
     # the same byte size as tensors 0 and 1 but sized in the other run of Alg. 2, so a class of its own)
