@@ -199,3 +199,45 @@ def test_random_malformed_profiles_are_refused_or_planned_and_never_take_the_pro
         finally:
             tc.close()
     assert outcomes["planned"] > 50 and outcomes[-1] > 50 and outcomes[-3] > 10, outcomes
+
+
+def test_the_bindings_records_have_the_layout_the_header_declares(tmp_path):
+    # every struct the binding mirrors, field by field: a C program compiled against include/tc.h prints
+    # sizeof and offsetof, which must be what numpy / ctypes lay out (a field added on one side only would
+    # otherwise shift every figure behind it without an error); the constants the two sides share as well
+    import ctypes
+    import subprocess
+    from paper_2511_14124_amd import binding as B
+    records = {"tc_tensor_desc": B.TENSOR_DESC, "tc_event": B.EVENT, "tc_pool_class": B.POOL_CLASS,
+               "tc_placement": B.PLACEMENT, "tc_op": B.OP, "tc_segment": B.SEGMENT,
+               "tc_budget": B.Budget, "tc_pool_plan": B.PoolPlan, "tc_stats": B.Stats, "tc_timing": B.Timing}
+    consts = {"TC_GPU": B.GPU, "TC_CPU": B.CPU, "TC_NVME": B.NVME, "TC_PRE": B.PRE, "TC_POST": B.POST,
+              "TC_END": B.END, "TC_END_CPU": B.END_CPU, "TC_NONE": B.NONE, "TC_MAX_STEP_TENSORS": B.MAX_STEP_TENSORS,
+              "TC_ALLOC_WRITE_ONLY": B.ALLOC_WRITE_ONLY, "TC_BIND_NULL_MOVER": B.BIND_NULL_MOVER,
+              "TC_BIND_FILE_DIRECT": B.BIND_FILE_DIRECT, "TC_BIND_HOST_TIER": B.BIND_HOST_TIER}
+
+    def fields(rec):
+        if isinstance(rec, np.dtype):
+            return rec.itemsize, [(n, rec.fields[n][1]) for n in rec.names]
+        return ctypes.sizeof(rec), [(n, getattr(rec, n).offset) for n, _ in rec._fields_]
+
+    lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "tc.h"', 'int main(void) {']
+    for name, rec in records.items():
+        lines.append(f'  printf("{name} %zu", sizeof({name}));')
+        for f, _ in fields(rec)[1]:
+            lines.append(f'  printf(" %zu", offsetof({name}, {f}));')
+        lines.append('  printf("\\n");')
+    for name in consts:
+        lines.append(f'  printf("{name} %llu\\n", (unsigned long long)({name}));')
+    lines.append('  return 0; }')
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout.bin"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = subprocess.check_output([str(exe)], text=True).split("\n")
+    got = {ln.split()[0]: [int(x) for x in ln.split()[1:]] for ln in out if ln}
+    for name, rec in records.items():
+        size, fs = fields(rec)
+        assert got[name] == [size] + [off for _, off in fs], name
+    for name, value in consts.items():
+        assert got[name] == [value], name
