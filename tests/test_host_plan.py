@@ -241,3 +241,24 @@ def test_the_bindings_records_have_the_layout_the_header_declares(tmp_path):
         assert got[name] == [size] + [off for _, off in fs], name
     for name, value in consts.items():
         assert got[name] == [value], name
+
+
+def test_every_bound_function_takes_as_many_arguments_as_the_header_declares():
+    # ctypes checks nothing against the header: an argument left out of a prototype in the binding would
+    # shift the ones behind it silently.  Every declaration of include/tc.h, comments stripped, against the
+    # argument list the binding registered for that symbol.
+    import ctypes
+    hdr = re.sub(r"/\*.*?\*/", " ", open(os.path.join(ROOT, "include", "tc.h")).read(), flags=re.S)
+    decls = re.findall(r"\b(int|const char \*|uint64_t)\s*(tc_[a-z_0-9]+)\s*\(([^;{]*?)\)\s*;", hdr)
+    assert len(decls) > 40
+    L = T.load_library()
+    checked = 0
+    for ret, name, params in decls:
+        fn = getattr(L, name)
+        n = 0 if params.strip() in ("", "void") else params.count(",") + 1
+        if fn.argtypes is None:
+            continue                                       # (a symbol the binding does not call)
+        assert len(fn.argtypes) == n, (name, params)
+        assert (fn.restype is ctypes.c_char_p) == ret.startswith("const char"), name
+        checked += 1
+    assert checked > 40
